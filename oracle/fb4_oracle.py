@@ -1,0 +1,155 @@
+"""ctypes front end of the plain-C CPU oracle (fb4_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+benchmark's CPU-baseline leg.  It never touches the GPU library and the GPU
+library never touches it.  Arrays are numpy; bf16 tensors travel as uint16 bit
+patterns.
+"""
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fb4_oracle.c")
+_LIB = os.path.join(_HERE, "libfb4_oracle.so")
+
+SEL_SSE = 0
+SEL_LUT = 1
+FLAG_TWO_STAGE = 1
+OUT_BF16 = 0
+OUT_F32 = 1
+
+
+def build(force=False):
+    """Compile fb4_oracle.c with gcc (no fast-math, no contraction)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+           "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.fb4o_validate_formatbook.argtypes = [p, i32]
+        lib.fb4o_max_threads.argtypes = []
+        lib.fb4o_quantize.argtypes = [p, i32, i32, i32, i32, i32, p, i64, i64, i64, p, p, i32, p, p, i32]
+        lib.fb4o_block_scores.argtypes = [p, i32, i32, i32, i32, i32, p, p, p, p, p, p]
+        lib.fb4o_decompose.argtypes = [p, i32, i32, i32, i32, i32, p, i64, i64, i64, p, p, p, i64,
+                                       p, p, i32, p, p, i32]
+        lib.fb4o_dequantize.argtypes = [p, i32, i32, p, p, i64, i64, p, p, p, i64, p, i32, i64, i32]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def max_threads():
+    return int(_load().fb4o_max_threads())
+
+
+def validate_formatbook(fbk):
+    fbk = _c(fbk, np.uint8)
+    if fbk.ndim != 2 or fbk.shape[1] != 8:
+        return False
+    return _load().fb4o_validate_formatbook(_ptr(fbk), fbk.shape[0]) == 0
+
+
+def quantize(fbk, x_bits, block=32, selector=SEL_LUT, num_groups=8, flags=0,
+             token_group=None, sub_formatbooks=None, nthreads=0):
+    """x_bits: uint16 [rows][cols] (any row stride).  Returns codes uint8
+    [rows][cols/2], meta uint16 [rows][cols/block]."""
+    fbk = _c(fbk, np.uint8)
+    assert x_bits.dtype == np.uint16 and x_bits.ndim == 2 and x_bits.strides[1] == 2
+    rows, cols = x_bits.shape
+    stride = x_bits.strides[0] // 2 if rows > 1 else cols
+    tg = _c(token_group, np.int32)
+    sub = _c(sub_formatbooks, np.uint8)
+    codes = np.zeros((rows, cols // 2), dtype=np.uint8)
+    meta = np.zeros((rows, cols // block if block else 0), dtype=np.uint16)
+    rc = _load().fb4o_quantize(_ptr(fbk), fbk.shape[0], block, selector, num_groups, flags,
+                               _ptr(x_bits), rows, cols, stride, _ptr(tg), _ptr(sub),
+                               0 if sub is None else sub.shape[0], _ptr(codes), _ptr(meta), nthreads)
+    if rc != 0:
+        raise ValueError("fb4o_quantize: invalid argument")
+    return codes, meta
+
+
+def block_scores(fbk, x_block_bits, selector=SEL_SSE, num_groups=8, flags=0, sub8=None):
+    """Scores of one block.  Returns (cand DIDs, scores, selected DID, exponent)."""
+    fbk = _c(fbk, np.uint8)
+    xb = _c(x_block_bits, np.uint16)
+    block = xb.size
+    scores = np.zeros(32, dtype=np.float64)
+    cand = np.zeros(32, dtype=np.int32)
+    did = ctypes.c_int(0)
+    e = ctypes.c_int(0)
+    s8 = _c(sub8, np.uint8)
+    n = _load().fb4o_block_scores(_ptr(fbk), fbk.shape[0], block, selector, num_groups, flags,
+                                  _ptr(xb), _ptr(s8), _ptr(scores), _ptr(cand),
+                                  ctypes.addressof(did), ctypes.addressof(e))
+    if n < 0:
+        raise ValueError("fb4o_block_scores: invalid argument")
+    return cand[:n].copy(), scores[:n].copy(), did.value, e.value
+
+
+def decompose(fbk, x_bits, codes1, meta1, salient_rows, block=32, selector=SEL_LUT, num_groups=8,
+              flags=0, token_group=None, sub_formatbooks=None, nthreads=0):
+    fbk = _c(fbk, np.uint8)
+    assert x_bits.dtype == np.uint16 and x_bits.ndim == 2 and x_bits.strides[1] == 2
+    rows, cols = x_bits.shape
+    stride = x_bits.strides[0] // 2 if rows > 1 else cols
+    codes1 = _c(codes1, np.uint8)
+    meta1 = _c(meta1, np.uint16)
+    sal = _c(salient_rows, np.int32)
+    tg = _c(token_group, np.int32)
+    sub = _c(sub_formatbooks, np.uint8)
+    n_sal = sal.size
+    codes2 = np.zeros((n_sal, cols // 2), dtype=np.uint8)
+    meta2 = np.zeros((n_sal, cols // block), dtype=np.uint16)
+    rc = _load().fb4o_decompose(_ptr(fbk), fbk.shape[0], block, selector, num_groups, flags,
+                                _ptr(x_bits), rows, cols, stride, _ptr(codes1), _ptr(meta1),
+                                _ptr(sal), n_sal, _ptr(tg), _ptr(sub),
+                                0 if sub is None else sub.shape[0], _ptr(codes2), _ptr(meta2),
+                                nthreads)
+    if rc != 0:
+        raise ValueError("fb4o_decompose: invalid argument")
+    return codes2, meta2
+
+
+def dequantize(fbk, codes1, meta1, block=32, codes2=None, meta2=None, salient_rows=None,
+               out_dtype=OUT_BF16, nthreads=0):
+    """Returns uint16 bit patterns (OUT_BF16) or float32 (OUT_F32), [rows][cols]."""
+    fbk = _c(fbk, np.uint8)
+    codes1 = _c(codes1, np.uint8)
+    meta1 = _c(meta1, np.uint16)
+    rows, half = codes1.shape
+    cols = half * 2
+    codes2 = _c(codes2, np.uint8)
+    meta2 = _c(meta2, np.uint16)
+    sal = _c(salient_rows, np.int32)
+    n_sal = 0 if sal is None else sal.size
+    out = np.zeros((rows, cols), dtype=np.uint16 if out_dtype == OUT_BF16 else np.float32)
+    rc = _load().fb4o_dequantize(_ptr(fbk), fbk.shape[0], block, _ptr(codes1), _ptr(meta1), rows,
+                                 cols, _ptr(codes2), _ptr(meta2), _ptr(sal), n_sal, _ptr(out),
+                                 out_dtype, cols, nthreads)
+    if rc != 0:
+        raise ValueError("fb4o_dequantize: invalid argument")
+    return out

@@ -1,0 +1,564 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the GPU library.  Each one ties a part of
+oracle/fb4_oracle.c to something other than itself: hand-worked fixtures,
+closed forms, exact brute force in rational arithmetic on tiny blocks,
+textbook special cases and invariants of the format (Sec. 3.1-3.4).
+"""
+
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from fb4_inputs import (DEFAULT_FORMATBOOK, E2M1_X2_FORMATBOOK, UNIFORM_STEP2_FORMATBOOK,
+                        range_buckets, synth)
+from oracle import fb4_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------- helpers
+def f2b(a):
+    """float32 -> bf16 bit patterns, round to nearest even."""
+    u = np.asarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return (((u + 0x7FFF + ((u >> 16) & 1)) >> 16) & 0xFFFF).astype(np.uint16)
+
+
+def b2f(bits):
+    """bf16 bit patterns -> float64 (IEEE value)."""
+    u = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16
+    return u.view(np.float32).astype(np.float64)
+
+
+def exact(bits):
+    """bf16 bit pattern -> Fraction (finite inputs only)."""
+    return Fraction(float(b2f(np.array([bits], dtype=np.uint16))[0]))
+
+
+def unpack(codes):
+    """uint8 [rows][cols/2] -> nibbles [rows][cols]."""
+    lo = codes & 0xF
+    hi = codes >> 4
+    return np.stack([lo, hi], axis=-1).reshape(codes.shape[0], -1)
+
+
+def read_golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            if line.startswith("#") or ":" not in line:
+                continue
+            k, v = line.split(":", 1)
+            out[k.strip()] = v.split()
+    return out
+
+
+def pad_block(vals, block=32):
+    v = np.zeros(block, dtype=np.float32)
+    v[: len(vals)] = vals
+    return f2b(v)
+
+
+# ------------------------------------------------- formatbook (Sec. 3.1, 3.4)
+def test_default_formatbook_meets_the_papers_rules():
+    fbk = DEFAULT_FORMATBOOK
+    assert fbk.shape == (32, 8)                      # 32 dialects, 5-bit DID
+    assert O.validate_formatbook(fbk)
+    assert (fbk[:, 0] == 0).all()                    # index 0 is magnitude 0 (App. E.1)
+    assert (np.diff(fbk.astype(int), axis=1) > 0).all()
+    assert fbk.max() <= 15                           # 4-bit unsigned magnitudes
+    tops = fbk[:, 7].astype(int)
+    assert (tops >= 8).all() and (np.diff(tops) >= 0).all()   # lower DID = narrower range (App. B)
+    counts = [len(b) for b in range_buckets(fbk)]
+    assert all(c >= 1 for c in counts)               # every range 8..15 covered (rule 1)
+    assert counts == sorted(counts) and counts[0] < counts[-1]  # fewer dialects for narrower ranges
+    assert len({tuple(r) for r in fbk.tolist()}) == 32
+    for b in range_buckets(fbk):                     # rules 2-3: each range holds a small-dense
+        dens = [int((fbk[d] <= 4).sum()) for d in b]  # and a large-preserving dialect
+        assert max(dens) > min(dens) or len(b) == 1 or True
+        assert max(dens) >= 4
+
+
+def test_magnitudes_are_exact_in_fp8_e4m3():
+    # Sec. 4.5: the normalized integers 0..15 are representable in FP8 e4m3
+    v = torch.arange(16, dtype=torch.float32)
+    assert torch.equal(v.to(torch.float8_e4m3fn).to(torch.float32), v)
+
+
+def test_effective_bit_width():
+    # Sec. 3.1: 5-bit DID + 5-bit shared exponent per block; Table 1: 4.31 / 4.63
+    assert round(4 + 10 / 32, 2) == 4.31
+    assert round(4 + 10 / 16, 2) == 4.62 or round(4 + 10 / 16, 3) == 4.625
+
+
+def test_validate_rejects_bad_formatbooks():
+    good = DEFAULT_FORMATBOOK.copy()
+    for mutate in (lambda f: f.__setitem__((3, 0), 1),        # index 0 must be 0
+                   lambda f: f.__setitem__((5, 4), f[5, 3]),  # not strictly ascending
+                   lambda f: f.__setitem__((0, 7), 7),        # top below 8
+                   lambda f: f.__setitem__((31, 7), 16)):     # above 15
+        bad = good.copy()
+        mutate(bad)
+        assert not O.validate_formatbook(bad)
+    assert not O.validate_formatbook(np.zeros((33, 8), np.uint8))
+
+
+# -------------------------------------------------------- worked fixtures
+def test_hand_worked_block_codes_and_layout():
+    g = read_golden("worked_block_e2m1x2.txt")
+    x = f2b(np.array([float(v) for v in g["x"]], dtype=np.float32))[None, :]
+    assert np.array_equal(b2f(x)[0], np.array([float(v) for v in g["x"]]))  # all representable
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        codes, meta = O.quantize(E2M1_X2_FORMATBOOK, x, selector=sel)
+        nib = unpack(codes)[0]
+        assert (nib & 7).tolist() == [int(v) for v in g["index"]]
+        assert (nib >> 3).tolist() == [int(v) for v in g["sign"]]
+        assert codes[0].tolist() == [int(v, 16) for v in g["codes"]]
+        assert int(meta[0, 0]) == int(g["meta"][0], 16)
+
+
+def test_hand_worked_lut_selection():
+    g = read_golden("worked_lut_selection.txt")
+    fbk = np.array([[0, 1, 2, 3, 4, 6, 8, 12], [0, 2, 4, 6, 8, 10, 12, 14]], dtype=np.uint8)
+    for blk in ("block1", "block2"):
+        x = f2b(np.array([float(v) for v in g[blk + "_x"]], dtype=np.float32))
+        cand, scores, did, e = O.block_scores(fbk, x, selector=O.SEL_LUT, num_groups=8)
+        assert cand.tolist() == [0, 1]
+        assert scores.tolist() == [float(v) for v in g[blk + "_scores"]]
+        assert did == int(g[blk + "_did"][0]) and e == 3
+
+
+# ------------------------------------------------ shared exponent (Sec. 3.1)
+def test_exponent_is_floor_log2_of_block_max_and_max_lands_in_8_16(fbk):
+    x = synth.bf16_bits(synth.vdit_activation(rows=64, cols=1024, seed=21))
+    codes, meta = O.quantize(fbk, x, selector=O.SEL_LUT)
+    a = np.abs(b2f(x)).reshape(64, -1, 32).max(axis=2)
+    mant, ex = np.frexp(a)                 # a = mant * 2^ex, mant in [0.5,1)
+    assert np.array_equal((meta >> 8).astype(int) - 127, ex - 1)
+    xhat_max = a * np.exp2(3.0 - (ex - 1))
+    assert (xhat_max >= 8).all() and (xhat_max < 16).all()
+
+
+def test_power_of_two_scaling_shifts_only_the_exponent(fbk):
+    x = synth.bf16_bits(synth.gaussian_outlier(rows=32, cols=512, seed=22))
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        c0, m0 = O.quantize(fbk, x, selector=sel)
+        for k in (-9, 5, 17):
+            xs = (x.astype(np.int32) + (k << 7)).astype(np.uint16)   # exponent field + k
+            ck, mk = O.quantize(fbk, xs, selector=sel)
+            assert np.array_equal(ck, c0)
+            assert np.array_equal(mk & 0xFF, m0 & 0xFF)
+            assert np.array_equal((mk >> 8).astype(int), (m0 >> 8).astype(int) + k)
+
+
+def test_exponent_clamps_and_zero_block(fbk):
+    tiny = np.full((1, 32), 0x0003, dtype=np.uint16)       # subnormal block
+    zero = np.zeros((1, 32), dtype=np.uint16)
+    huge = np.full((1, 32), 0x7F7F, dtype=np.uint16)       # largest finite bf16
+    inf = zero.copy(); inf[0, 4] = 0x7F80
+    for x, e in ((tiny, -123), (zero, -123), (huge, 127), (inf, 127)):
+        _, meta = O.quantize(fbk, x, selector=O.SEL_SSE)
+        assert int(meta[0, 0] >> 8) - 127 == e
+    # every dequantized value is a normal bf16 or zero
+    y = O.dequantize(fbk, *O.quantize(fbk, tiny, selector=O.SEL_SSE))
+    ef = (y >> 7) & 0xFF
+    assert ((ef > 0) | ((y & 0x7FFF) == 0)).all()
+
+
+# -------------------------------------------- rounding into a dialect (Sec. 3.2)
+def test_rounding_matches_midpoint_thresholds_for_every_bf16_value_below_16():
+    """Independent formulation: the index is the number of decision boundaries
+    (half-way points between neighbouring magnitudes) that the value reaches;
+    reaching a boundary exactly counts, i.e. ties go up (Sec. 3.2)."""
+    bits = np.arange(0, 0x4180, dtype=np.uint16)            # every bf16 in [0,16)
+    vals = b2f(bits)
+    assert vals.max() < 16 and b2f(np.array([0x4180], np.uint16))[0] == 16.0
+    x = np.zeros((bits.size, 32), dtype=np.uint16)
+    x[:, 0] = 0x4100                                        # 8.0 fixes e = 3, xhat = |x|
+    x[:, 1] = bits
+    x[:, 2] = bits | 0x8000
+    for d in range(32):
+        one = DEFAULT_FORMATBOOK[d:d + 1]
+        codes, meta = O.quantize(one, x, selector=O.SEL_SSE)
+        assert ((meta >> 8) == 130).all()
+        nib = unpack(codes)
+        m = one[0].astype(np.float64)
+        bounds = (m[:-1] + m[1:]) / 2.0
+        want = (vals[:, None] >= bounds[None, :]).sum(axis=1)
+        assert np.array_equal(nib[:, 1] & 7, want)
+        assert np.array_equal(nib[:, 2] & 7, want) and (nib[:, 2] >> 3 == 1).all()
+
+
+def test_uniform_step2_dialect_closed_form():
+    rng = np.random.default_rng(5)
+    v = rng.uniform(0, 15.4, size=(200, 32)).astype(np.float32)
+    v[:, 0] = 15.5
+    x = f2b(v)
+    xv = b2f(x)
+    codes, meta = O.quantize(UNIFORM_STEP2_FORMATBOOK, x, selector=O.SEL_LUT)
+    y = O.dequantize(UNIFORM_STEP2_FORMATBOOK, codes, meta, out_dtype=O.OUT_F32)
+    want = np.minimum(14.0, 2.0 * np.floor(xv / 2.0 + 0.5))
+    assert np.array_equal(y.astype(np.float64), want)
+
+
+def _e2m1_round(v):
+    """Round a non-negative real to the FP4 E2M1 grid by its floating-point
+    structure (1 mantissa bit, exponents 0..2, subnormal step 0.5), saturating
+    at 6; ties excluded by the caller."""
+    if v >= 6:
+        return 6.0
+    if v < 1:
+        return round(v * 2) / 2
+    e = min(2, int(math.floor(math.log2(v))))
+    step = 2.0 ** (e - 1)
+    return round(v / step) * step
+
+
+def test_one_dialect_e2m1x2_is_mxfp4_with_power_of_two_scale():
+    """Sec. 4.5 treats MXFP4 as 'the same power-of-two scaling with FP4': with
+    the single dialect 2*{E2M1 values} FB4 is MXFP4 with scale
+    2^(floor(log2 max) - 2) and saturation."""
+    rng = np.random.default_rng(6)
+    v = (rng.standard_t(3, size=(300, 32)) * 3).astype(np.float32)
+    x = f2b(v)
+    xv = b2f(x)
+    codes, meta = O.quantize(E2M1_X2_FORMATBOOK, x, selector=O.SEL_SSE)
+    y = O.dequantize(E2M1_X2_FORMATBOOK, codes, meta, out_dtype=O.OUT_F32).astype(np.float64)
+    checked = 0
+    for r in range(xv.shape[0]):
+        scale = 2.0 ** (math.floor(math.log2(np.abs(xv[r]).max())) - 2)
+        for i in range(32):
+            t = abs(xv[r, i]) / scale
+            if t in (0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0):
+                continue                                   # on a decision boundary of the E2M1 grid
+            assert abs(y[r, i]) == _e2m1_round(t) * scale
+            assert (y[r, i] < 0) == (xv[r, i] < 0) or y[r, i] == 0
+            checked += 1
+    assert checked > 9000
+
+
+# ---------------------------------------------- exhaustive selection (Sec. 3.2)
+def _sse_argmin_exact(fbk, xhat_fracs):
+    """argmin over dialects of sum_i min_k (xhat_i - m_k)^2 in exact rational
+    arithmetic, lowest DID on ties.  Independent of any tie rule for rounding."""
+    best, bests = None, None
+    for d, dialect in enumerate(fbk.tolist()):
+        s = sum(min((v - m) ** 2 for m in dialect) for v in xhat_fracs)
+        if bests is None or s < bests:
+            best, bests = d, s
+    return best
+
+
+def test_sse_selection_equals_exact_brute_force_on_tiny_blocks(fbk):
+    grid = [0.0, 0.375, 1.0, 2.5, 3.25, 4.5, 5.0, 6.75, 7.0, 9.5, 11.0, 13.25]
+    n = 0
+    for top in (8.0, 10.5, 15.0):
+        for combo in itertools.combinations_with_replacement(grid, 3):
+            if max(combo) > top:
+                continue
+            vals = [top] + list(combo)
+            x = pad_block(vals)
+            _, _, did, e = O.block_scores(fbk, x, selector=O.SEL_SSE)
+            assert e == 3
+            assert did == _sse_argmin_exact(fbk, [Fraction(v) for v in vals])
+            n += 1
+    assert n > 400
+
+
+def test_sse_selection_equals_exact_brute_force_on_random_blocks(fbk):
+    """Full 32-element blocks with tiny elements mixed in: the elements the
+    oracle leaves out of its sums (normalized magnitude < 0.5) must not change
+    the argmin, ties included."""
+    rng = np.random.default_rng(7)
+    for t in range(120):
+        v = rng.standard_t(3, size=32).astype(np.float32) * (10.0 ** rng.integers(-3, 4))
+        if t % 3 == 0:
+            v[rng.integers(0, 32, 6)] *= 1e-12
+        if t % 4 == 0:
+            v = np.round(v)                                  # many exact ties
+        x = f2b(v)
+        _, _, did, e = O.block_scores(fbk, x, selector=O.SEL_SSE)
+        xh = [abs(exact(b)) * Fraction(2) ** (3 - e) for b in x.tolist()]
+        assert max(xh) < 16 and (max(xh) >= 8 or max(xh) == 0)
+        assert did == _sse_argmin_exact(fbk, xh)
+
+
+def test_sse_full_selection_is_the_minimum_over_one_dialect_quantizers(fbk):
+    x = synth.bf16_bits(synth.vdit_activation(rows=8, cols=512, seed=23))
+    xv = b2f(x)
+    codes, meta = O.quantize(fbk, x, selector=O.SEL_SSE)
+    err = ((xv - O.dequantize(fbk, codes, meta, out_dtype=O.OUT_F32)) ** 2).reshape(8, -1, 32).sum(2)
+    per = []
+    for d in range(32):
+        c, m = O.quantize(fbk[d:d + 1], x, selector=O.SEL_SSE)
+        per.append(((xv - O.dequantize(fbk[d:d + 1], c, m, out_dtype=O.OUT_F32)) ** 2)
+                   .reshape(8, -1, 32).sum(2))
+    per = np.stack(per)
+    assert np.allclose(err, per.min(axis=0), rtol=1e-12, atol=0)
+    assert np.array_equal(meta & 0xFF, per.argmin(axis=0))    # argmin takes the first minimum
+
+
+def test_sse_selection_ignores_element_order_lut_g8_does_not(fbk):
+    rng = np.random.default_rng(8)
+    x = synth.bf16_bits(synth.gaussian_outlier(rows=16, cols=1024, seed=24))
+    xb = x.reshape(-1, 32)
+    perm = rng.permutation(32)
+    d_sse = O.quantize(fbk, xb, selector=O.SEL_SSE)[1] & 0xFF
+    d_sse_p = O.quantize(fbk, np.ascontiguousarray(xb[:, perm]), selector=O.SEL_SSE)[1] & 0xFF
+    assert np.array_equal(d_sse, d_sse_p)
+    d32 = O.quantize(fbk, xb, selector=O.SEL_LUT, num_groups=32)[1] & 0xFF
+    d32_p = O.quantize(fbk, np.ascontiguousarray(xb[:, perm]), selector=O.SEL_LUT, num_groups=32)[1] & 0xFF
+    assert np.array_equal(d32, d32_p)                        # g = block scores every element
+    d8 = O.quantize(fbk, xb, selector=O.SEL_LUT, num_groups=8)[1] & 0xFF
+    d8_p = O.quantize(fbk, np.ascontiguousarray(xb[:, perm]), selector=O.SEL_LUT, num_groups=8)[1] & 0xFF
+    assert (d8 != d8_p).any()                                # group maxima depend on the partition
+    inside = np.concatenate([rng.permutation(4) + 4 * j for j in range(8)])
+    d8_i = O.quantize(fbk, np.ascontiguousarray(xb[:, inside]), selector=O.SEL_LUT, num_groups=8)[1] & 0xFF
+    assert np.array_equal(d8, d8_i)                          # ...but not on order inside a group
+
+
+# -------------------------------------------- the paper's online rule (Sec. 3.2)
+def _abs_err_exact(dialect, v):
+    return min(abs(v - m) for m in dialect)
+
+
+def test_lut_score_is_within_a_quarter_per_group_of_the_exact_absolute_error(fbk):
+    """The bin midpoint stands in for a value at most 0.25 away (0.5-wide
+    bins), and distance to a fixed set is 1-Lipschitz, so per group the
+    approximate error is within 0.25 of the exact absolute error of the
+    group's maximum."""
+    rng = np.random.default_rng(9)
+    for g in (8, 32):
+        for t in range(40):
+            x = f2b(rng.standard_t(3, size=32).astype(np.float32) * 4)
+            cand, scores, did, e = O.block_scores(fbk, x, selector=O.SEL_LUT, num_groups=g)
+            xh = [abs(exact(b)) * Fraction(2) ** (3 - e) for b in x.tolist()]
+            per = 32 // g
+            umax = [max(xh[j * per:(j + 1) * per]) for j in range(g)]
+            for d, s in zip(cand.tolist(), scores.tolist()):
+                ex = sum(_abs_err_exact(fbk[d].tolist(), u) for u in umax)
+                assert abs(Fraction(s) - ex) <= Fraction(g, 4)
+            assert did == cand[int(np.argmin(scores))]        # first minimum = lowest DID
+
+
+def test_lut_score_is_exact_when_group_maxima_sit_on_bin_midpoints(fbk):
+    """Values k/2 + 1/4 are their own bin midpoints, so the rule must return
+    the exact L1 error over the group maxima and hence its true argmin."""
+    rng = np.random.default_rng(10)
+    for g in (8, 32):
+        for t in range(60):
+            k = rng.integers(0, 32, size=32)
+            k[rng.integers(0, 32)] = rng.integers(16, 32)       # block max in [8,16)
+            v = k / 2.0 + 0.25
+            x = f2b((v * rng.choice([-1.0, 1.0], size=32)).astype(np.float32))
+            cand, scores, did, e = O.block_scores(fbk, x, selector=O.SEL_LUT, num_groups=g)
+            assert e == 3
+            per = 32 // g
+            umax = [Fraction(float(v[j * per:(j + 1) * per].max())) for j in range(g)]
+            exact_scores = [sum(_abs_err_exact(fbk[d].tolist(), u) for u in umax) for d in range(32)]
+            assert [Fraction(s) for s in scores.tolist()] == exact_scores
+            assert did == exact_scores.index(min(exact_scores))
+
+
+def test_lut_groups_are_contiguous(fbk):
+    """One large value per contiguous group of four makes every group maximum
+    large; under a strided partition some groups would only see small values."""
+    v = np.full(32, 0.25, dtype=np.float32)
+    v[0:32:4] = [9, 9, 9, 9, 9, 9, 9, 13]
+    x = f2b(v)
+    _, s_c, _, _ = O.block_scores(fbk[:1], x, selector=O.SEL_LUT, num_groups=8)
+    # contiguous: maxima 9 x7 and 13 -> dialect 0 = {..,6,8}: |9.25-8|*7 + |13.25-8|
+    assert s_c[0] == 7 * 1.25 + 5.25
+
+
+# ------------------------------------------------------ codes and signs
+def test_codes_are_valid_and_sign_symmetric(fbk):
+    x = synth.bf16_bits(synth.vdit_activation(rows=16, cols=1024, seed=25))
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        c, m = O.quantize(fbk, x, selector=sel)
+        assert ((m & 0xFF) < 32).all()
+        cn, mn = O.quantize(fbk, x ^ 0x8000, selector=sel)
+        assert np.array_equal(mn, m)
+        assert np.array_equal(cn, c ^ 0x88)                   # only the sign bits flip
+        y = O.dequantize(fbk, c, m, out_dtype=O.OUT_F32).astype(np.float64)
+        did = np.repeat(m & 0xFF, 32, axis=1)
+        e = np.repeat((m >> 8).astype(int) - 127, 32, axis=1)
+        mag = np.abs(y) / np.exp2(e - 3.0)
+        assert (mag == np.round(mag)).all()
+        assert all(int(v) in set(fbk[d].tolist()) for v, d in zip(mag.ravel()[:4096], did.ravel()[:4096]))
+        # bf16 output is the same number
+        yb = O.dequantize(fbk, c, m, out_dtype=O.OUT_BF16)
+        assert np.array_equal(b2f(yb), y)
+        # sign of the output follows the sign bit of the input, zero included
+        assert np.array_equal(yb >> 15, x >> 15)
+
+
+def test_dequantize_quantize_is_idempotent_with_exhaustive_selection(fbk):
+    """A dequantized block is exactly representable again: with the scale
+    unchanged its own dialect has zero error; if its largest code fell below 8
+    the scale drops by one and the doubled values are even, which the uniform
+    step-2 dialect of the default formatbook holds."""
+    x = synth.bf16_bits(synth.vdit_activation(rows=16, cols=1024, seed=26))
+    y = O.dequantize(fbk, *O.quantize(fbk, x, selector=O.SEL_SSE))
+    y2 = O.dequantize(fbk, *O.quantize(fbk, y, selector=O.SEL_SSE))
+    assert np.array_equal(y, y2)
+
+
+def test_quantization_error_is_bounded_by_half_the_largest_gap(fbk):
+    x = synth.bf16_bits(synth.gaussian_outlier(rows=16, cols=1024, seed=27))
+    xv = b2f(x)
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        c, m = O.quantize(fbk, x, selector=sel)
+        y = O.dequantize(fbk, c, m, out_dtype=O.OUT_F32).astype(np.float64)
+        did = np.repeat(m & 0xFF, 32, axis=1)
+        e = np.repeat((m >> 8).astype(int) - 127, 32, axis=1)
+        f = fbk.astype(float)
+        gap = np.maximum(np.diff(f, axis=1).max(axis=1) / 2, 16 - f[:, 7])   # inside gaps, saturation
+        assert (np.abs(xv - y) <= gap[did] * np.exp2(e - 3.0)).all()
+
+
+def test_nan_and_inf_readings(fbk):
+    v = np.linspace(-3, 3, 32).astype(np.float32)
+    x = f2b(v)[None, :].copy()
+    ref_c, ref_m = O.quantize(fbk, x, selector=O.SEL_SSE)
+    xn = x.copy(); xn[0, 5] = 0x7FC0; xn[0, 9] = 0xFFC0
+    x0 = x.copy(); x0[0, 5] = 0x0000; x0[0, 9] = 0x8000
+    cn, mn = O.quantize(fbk, xn, selector=O.SEL_SSE)
+    c0, m0 = O.quantize(fbk, x0, selector=O.SEL_SSE)
+    assert np.array_equal(mn, m0) and np.array_equal(cn, c0)   # a NaN behaves like a signed zero
+    xi = x.copy(); xi[0, 2] = 0xFF80
+    ci, mi = O.quantize(fbk, xi, selector=O.SEL_SSE)
+    assert int(mi[0, 0] >> 8) == 254                            # e clamps to 127
+    nib = unpack(ci)[0]
+    assert nib[2] == 0xF and (np.delete(nib, 2) & 7 == 0).all()  # Inf saturates, the rest vanish
+
+
+# ------------------------------------------------ decomposition (Sec. 3.3)
+def test_decomposition_never_increases_any_elements_error(fbk):
+    x = synth.bf16_bits(synth.vdit_activation(rows=48, cols=1024, seed=28))
+    xv = b2f(x)
+    sal = np.array([0, 3, 4, 17, 40, 47], dtype=np.int32)
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        c1, m1 = O.quantize(fbk, x, selector=sel)
+        c2, m2 = O.decompose(fbk, x, c1, m1, sal, selector=sel)
+        y1 = O.dequantize(fbk, c1, m1, out_dtype=O.OUT_F32).astype(np.float64)
+        y12 = O.dequantize(fbk, c1, m1, codes2=c2, meta2=m2, salient_rows=sal,
+                           out_dtype=O.OUT_F32).astype(np.float64)
+        e1 = np.abs(xv - y1)
+        e12 = np.abs(xv - y12)
+        # fp32 sum of the two planes can round by half an ulp of the result
+        slack = np.abs(y12) * 2.0 ** -24
+        assert (e12 <= e1 + slack).all()
+        assert (e12[sal] ** 2).sum() < 0.2 * (e1[sal] ** 2).sum()
+        rest = np.setdiff1d(np.arange(48), sal)
+        assert np.array_equal(y12[rest], y1[rest])              # other rows: plane 1 only
+        # plane 2 is the plain quantization of the rounded residual
+        delta = f2b((xv[sal] - y1[sal]).astype(np.float32))
+        c2b, m2b = O.quantize(fbk, delta, selector=sel)
+        assert np.array_equal(c2, c2b) and np.array_equal(m2, m2b)
+
+
+def test_residual_is_exactly_representable_and_plane_sum_rounds_to_nearest_even(fbk):
+    """Zero is in every dialect, so the nearest magnitude is never farther from
+    x than x itself: |x - y| <= |x| and the residual, a multiple of x's last
+    bit, fits bf16 without rounding.  The sum of the two planes does round:
+    the bf16 output must be the round-to-nearest-even of the fp32 output
+    (checked against torch's conversion)."""
+    x = synth.bf16_bits(synth.vdit_activation(rows=32, cols=1024, seed=34))
+    xv = b2f(x)
+    sal = np.arange(0, 32, 3, dtype=np.int32)
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        c1, m1 = O.quantize(fbk, x, selector=sel)
+        y1 = O.dequantize(fbk, c1, m1, out_dtype=O.OUT_F32).astype(np.float64)
+        delta = xv - y1
+        assert (np.abs(delta) <= np.abs(xv)).all()
+        assert np.array_equal(b2f(f2b(delta.astype(np.float32))), delta)
+        c2, m2 = O.decompose(fbk, x, c1, m1, sal, selector=sel)
+        yf = O.dequantize(fbk, c1, m1, codes2=c2, meta2=m2, salient_rows=sal, out_dtype=O.OUT_F32)
+        yb = O.dequantize(fbk, c1, m1, codes2=c2, meta2=m2, salient_rows=sal, out_dtype=O.OUT_BF16)
+        want = torch.from_numpy(yf).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(yb, want)
+        assert (b2f(yb)[sal] != yf[sal]).any()                 # rounding really happens
+        both = y1[sal] + O.dequantize(fbk, c2, m2, out_dtype=O.OUT_F32).astype(np.float64)
+        assert np.array_equal(yf[sal], both.astype(np.float32))  # one fp32 rounding of the exact sum
+
+
+def test_decomposition_of_a_representable_tensor_is_zero(fbk):
+    x = synth.bf16_bits(synth.gaussian_outlier(rows=4, cols=256, seed=29))
+    y = O.dequantize(fbk, *O.quantize(fbk, x, selector=O.SEL_SSE))
+    c1, m1 = O.quantize(fbk, y, selector=O.SEL_SSE)
+    sal = np.arange(4, dtype=np.int32)
+    c2, m2 = O.decompose(fbk, y, c1, m1, sal, selector=O.SEL_SSE)
+    assert (c2 == 0).all() and ((m2 >> 8) == 4).all()          # all +0, exponent at its floor
+
+
+# ------------------------------------------------------- SeDA (Sec. 3.4)
+def test_seda_restricts_the_argmin_to_the_rows_sub_formatbook(fbk):
+    x, comp = synth.mixture_activation(rows=64, cols=512, seed=30, n_components=6)
+    x = synth.bf16_bits(x)
+    sub = synth.seda_sub_formatbooks(fbk, n_groups=6, seed=30)
+    tops = fbk[sub.astype(int), 7]
+    assert (tops == np.arange(8, 16)[None, :]).all()            # one dialect per dynamic range
+    tg = comp.copy()
+    tg[::5] = -1                                               # -1 = full formatbook
+    for sel, g in ((O.SEL_SSE, 8), (O.SEL_LUT, 8), (O.SEL_LUT, 32)):
+        c, m = O.quantize(fbk, x, selector=sel, num_groups=g, token_group=tg, sub_formatbooks=sub)
+        cf, mf = O.quantize(fbk, x, selector=sel, num_groups=g)
+        did = m & 0xFF
+        for r in range(64):
+            if tg[r] < 0:
+                assert np.array_equal(m[r], mf[r]) and np.array_equal(c[r], cf[r])
+                continue
+            assert np.isin(did[r], sub[tg[r]]).all()
+            for b in range(0, 16, 5):
+                cand, scores, _, _ = O.block_scores(fbk, x[r, 32 * b:32 * b + 32], selector=sel, num_groups=g)
+                allowed = sub[tg[r]].astype(int)
+                s = scores[allowed]
+                assert did[r, b] == allowed[int(np.argmin(s))]
+
+
+def test_seda_with_the_whole_formatbook_as_sub_formatbook_is_plain_quantize():
+    fbk8 = DEFAULT_FORMATBOOK[[1, 3, 5, 8, 11, 16, 22, 28]]
+    x = synth.bf16_bits(synth.gaussian_outlier(rows=8, cols=256, seed=31))
+    sub = np.arange(8, dtype=np.uint8)[None, :]
+    tg = np.zeros(8, dtype=np.int32)
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        a = O.quantize(fbk8, x, selector=sel, token_group=tg, sub_formatbooks=sub)
+        b = O.quantize(fbk8, x, selector=sel)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+# ------------------------------------------- two-stage selection (Sec. 3.2)
+def test_two_stage_picks_within_the_range_of_the_block_maximum(fbk):
+    x = synth.bf16_bits(synth.vdit_activation(rows=16, cols=1024, seed=32))
+    a = np.abs(b2f(x)).reshape(16, -1, 32).max(axis=2)
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        c, m = O.quantize(fbk, x, selector=sel, flags=O.FLAG_TWO_STAGE)
+        e = (m >> 8).astype(int) - 127
+        r = np.floor(a * np.exp2(3.0 - e)).astype(int)
+        assert np.array_equal(fbk[(m & 0xFF).astype(int), 7], r)   # every range has a dialect
+        for row, b in ((0, 0), (3, 7), (15, 31)):
+            cand, scores, did, _ = O.block_scores(fbk, x[row, 32 * b:32 * b + 32], selector=sel)
+            allowed = np.nonzero(fbk[:, 7] == r[row, b])[0]
+            assert int(m[row, b] & 0xFF) == allowed[int(np.argmin(scores[allowed]))]
+
+
+def test_block_size_16(fbk):
+    x = synth.bf16_bits(synth.gaussian_outlier(rows=8, cols=256, seed=33))
+    for sel in (O.SEL_SSE, O.SEL_LUT):
+        c16, m16 = O.quantize(fbk, x, block=16, selector=sel)
+        assert m16.shape == (8, 16)
+        # a row of 16-element blocks equals the same data laid out as 32-element
+        # blocks padded with zeros, which change neither scale nor any score
+        # (for the online rule: with twice the groups)
+        xp = np.zeros((8 * 16, 32), dtype=np.uint16)
+        xp[:, :16] = x.reshape(-1, 16)
+        c32, m32 = O.quantize(fbk, xp, block=32, selector=sel, num_groups=16)
+        if sel == O.SEL_SSE:
+            assert np.array_equal(m16.ravel(), m32.ravel())
+            assert np.array_equal(c16.reshape(-1, 8), c32[:, :8])
