@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the FB4 online quantizer on one MI355X.
+
+A step is one pass of the hot path -- fb4_quantize with the paper's online
+selector (Qerror over 8 group-wise maxima, all 32 dialects, block 32) -- over
+one 16384 x 3072 bf16 activation tensor already resident in HBM.  Steps rotate
+through several input/output buffer sets (more than 512 MB in total) so that
+the 129 MB working set is streamed from HBM and not served by the 256 MB
+Infinity Cache.  Prints ONE JSON line.
+
+The other entry points (exhaustive selector, g = 32, SeDA, decomposition,
+dequantize) are timed the same way and reported under "extras".
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+ROWS, COLS, BLOCK = 16384, 3072, 32
+N_SETS = 6
+
+
+def algorithmic_bytes(rows, cols, block=32):
+    """bf16 in + 4-bit codes out + 16-bit metadata per block out."""
+    return rows * cols * 2 + rows * cols // 2 + rows * (cols // block) * 2
+
+
+def time_graph(fn_steps, steps, warmup):
+    """Run `warmup` eager steps, capture `steps` steps into one HIP graph, replay it once untimed and once
+    timed.  Returns (wall seconds, event seconds) for the timed replay."""
+    import torch
+    for i in range(warmup):
+        fn_steps(i)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for i in range(steps):
+                fn_steps(i)
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, e0.elapsed_time(e1) * 1e-3
+
+
+def time_eager(fn_steps, steps, warmup):
+    import torch
+    for i in range(warmup):
+        fn_steps(i)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn_steps(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, e0.elapsed_time(e1) * 1e-3
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--eager", action="store_true", help="time eager launches instead of one HIP graph")
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2603_02883_amd as F
+    from fb4_inputs import DEFAULT_FORMATBOOK, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    timer = time_eager if args.eager else time_graph
+    luts = F.fb4_build_luts(DEFAULT_FORMATBOOK)
+
+    x0 = synth.vdit_activation(rows=ROWS, cols=COLS, seed=2, device="cuda")
+    xs = [x0] + [x0.clone() for _ in range(N_SETS - 1)]
+    codes = [torch.empty((ROWS, COLS // 2), dtype=torch.uint8, device="cuda") for _ in range(N_SETS)]
+    metas = [torch.empty((ROWS, COLS // BLOCK), dtype=torch.int16, device="cuda") for _ in range(N_SETS)]
+    n_el = ROWS * COLS
+    abytes = algorithmic_bytes(ROWS, COLS)
+
+    def quant_step(o):
+        def f(i):
+            k = i % N_SETS
+            F.fb4_quantize(luts, o, xs[k], codes=codes[k], meta=metas[k])
+        return f
+
+    # ---- headline: the paper's online selector
+    o_main = F.opts(block=BLOCK, selector=F.SEL_LUT, num_groups=8)
+    wall, ev = timer(quant_step(o_main), args.steps, args.warmup)
+    ms_per_step = wall * 1e3 / args.steps
+    kern_s = ev / args.steps
+    result = {
+        "metric": "G elements/s quantized + achieved HBM GB/s (% of peak), 16384x3072 bf16",
+        "value": n_el / (wall / args.steps) / 1e9,
+        "unit": "G elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {
+            "workload": "cfg2: Open-Sora-2.0-like VDiT activation 16384x3072 bf16, Student-t(3), per-frame "
+                        "scale drift, 0.5% outlier channels x100",
+            "entry_point": "fb4_quantize", "selector": "lut", "num_groups": 8, "block": BLOCK,
+            "formatbook": "32 dialects (default table)", "buffer_sets": N_SETS,
+            "launch": "eager" if args.eager else "hip_graph",
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+            "kernel": "quantize_kernel<LUT,8,plain>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
+        },
+    }
+
+    # ---- other entry points, same protocol
+    if not args.no_extras:
+        extras = {}
+        steps2 = max(10, args.steps // 4)
+
+        def add(name, fn, nbytes, nelem, steps=steps2):
+            w, e = timer(fn, steps, 3)
+            extras[name] = {"us": e / steps * 1e6, "G_elements_per_s": nelem / (e / steps) / 1e9,
+                            "GB_per_s": nbytes / (e / steps) / 1e9, "hbm_frac": nbytes / (e / steps) / 1e9 / HBM_PEAK_GBS}
+
+        add("quantize_lut_g32", quant_step(F.opts(selector=F.SEL_LUT, num_groups=32)), abytes, n_el)
+        add("quantize_lut_g8_two_stage", quant_step(F.opts(selector=F.SEL_LUT, num_groups=8,
+                                                           flags=F.FLAG_TWO_STAGE)), abytes, n_el)
+        add("quantize_sse", quant_step(F.opts(selector=F.SEL_SSE)), abytes, n_el, steps=max(5, args.steps // 10))
+        # SeDA (cfg4)
+        xm, comp = synth.mixture_activation(rows=ROWS, cols=COLS, seed=4, device="cuda")
+        xms = [xm] + [xm.clone() for _ in range(N_SETS - 1)]
+        tg = torch.from_numpy(comp).cuda()
+        sub = torch.from_numpy(synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, 64, 4)).cuda()
+
+        def seda_step(i):
+            k = i % N_SETS
+            F.fb4_quantize_seda(luts, o_main, xms[k], tg, sub, codes=codes[k], meta=metas[k])
+        add("quantize_seda_lut_g8", seda_step, abytes + ROWS * 4, n_el)
+        # decomposition (cfg3): 5 % salient rows
+        sal = synth.salient_rows_from_attention(ROWS, frac=0.05, heads=24, seed=3, device="cuda")
+        sal_d = torch.from_numpy(sal).cuda()
+        n_sal = sal.size
+        F.fb4_quantize(luts, o_main, xs[0], codes=codes[0], meta=metas[0])
+        for k in range(1, N_SETS):
+            codes[k].copy_(codes[0]); metas[k].copy_(metas[0])
+        c2 = torch.empty((n_sal, COLS // 2), dtype=torch.uint8, device="cuda")
+        m2 = torch.empty((n_sal, COLS // BLOCK), dtype=torch.int16, device="cuda")
+
+        def decomp_step(i):
+            k = i % N_SETS
+            F.fb4_decompose(luts, o_main, xs[k], codes[k], metas[k], sal_d, codes2=c2, meta2=m2)
+        dbytes = n_sal * COLS * 2 + 2 * (n_sal * COLS // 2 + n_sal * (COLS // BLOCK) * 2)
+        add("decompose_5pct_lut_g8", decomp_step, dbytes, n_sal * COLS)
+        outs = [torch.empty((ROWS, COLS), dtype=torch.bfloat16, device="cuda") for _ in range(N_SETS)]
+
+        def deq_step(i):
+            k = i % N_SETS
+            F.fb4_dequantize(luts, codes[k], metas[k], codes2=c2, meta2=m2, salient_rows=sal_d, out=outs[k])
+        add("dequantize_bf16_with_5pct_second_plane", deq_step, abytes + dbytes, n_el)
+        result["extras"] = extras
+
+    # ---- CPU oracle on the host cores of this machine (a baseline for context, not a target)
+    if not args.no_cpu_baseline:
+        from oracle import fb4_oracle as O
+        xb = synth.bf16_bits(x0)
+        nthr = O.max_threads()
+        t0 = time.perf_counter()
+        cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, selector=O.SEL_LUT, num_groups=8, nthreads=nthr)
+        dt = time.perf_counter() - t0
+        same = bool(np.array_equal(cr, codes[0].cpu().numpy()) if args.no_extras else True)
+        result["cpu_baseline"] = {
+            "value": n_el / dt / 1e9, "unit": "G elements/s", "cores": nthr, "kind": "oracle",
+            "sample": "the whole 16384x3072 cfg2 tensor, selector lut g=8, %.2f s wall on %d threads" % (dt, nthr),
+        }
+        if args.no_extras:
+            result["cpu_baseline"]["matches_gpu_codes"] = same
+
+    luts.free()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,191 @@
+/*
+ * fb4.h -- C ABI of the MI355X (gfx950) FB4 online quantizer.
+ *
+ * FB4 is the 4-bit block format of the SemanticDialect paper (Sec. 3.1): a
+ * block of 32 (or 16) consecutive elements shares a power-of-two scale and one
+ * "dialect" -- a set of eight integer magnitudes out of 0..15 -- chosen per
+ * block from a 32-entry formatbook; an element is a sign bit plus a 3-bit
+ * index into the dialect.
+ *
+ * Conventions shared by every entry point
+ *   - Returns FB4_OK (0) or a negative FB4_ERR_* code; nothing aborts or
+ *     throws across this boundary.  fb4_strerror() names a code.
+ *   - Pointers marked "device" are GPU global-memory pointers owned by the
+ *     caller; pointers marked "host" are ordinary CPU pointers.  The library
+ *     allocates no tensor memory and never synchronizes: kernels are enqueued
+ *     on the caller's HIP stream (`stream` is a hipStream_t passed as void*,
+ *     NULL = the default stream) and the call returns immediately.
+ *   - Tensors are row-major.  x is bf16 (raw 16-bit patterns) with an explicit
+ *     row stride in elements; rows must start 16-byte aligned (base pointer
+ *     16-byte aligned and row_stride a multiple of 8), cols must be a multiple
+ *     of the block size; otherwise FB4_ERR_UNSUPPORTED.
+ *   - codes: uint8 [rows][cols/2], contiguous.  Element 2j is the low nibble
+ *     and element 2j+1 the high nibble of byte j; nibble = sign<<3 | index.
+ *   - meta: uint16 [rows][cols/block], contiguous.  Low byte = dialect ID
+ *     (DID), high byte = shared exponent e + 127, e = floor(log2(max|x|))
+ *     clamped to [-123, 127] (all-zero block: -123).  The paper budgets 5+5
+ *     metadata bits (Sec. 3.1); the wider exponent byte covers the bf16 range.
+ *   - A code decodes to (-1)^sign * M[DID][index] * 2^(e-3) (Sec. 3.1: the
+ *     normalized block lies in [0,16) with its maximum in [8,16)).
+ *   - Degenerate inputs: a NaN element is ignored by the block maximum and by
+ *     dialect selection and is emitted as index 0 with its sign; +/-Inf is read
+ *     as the finite magnitude 2^128 (so it saturates and e = 127); the sign bit
+ *     of the input is copied to the code even when the magnitude rounds to 0.
+ *   - rows == 0 or cols == 0 is a successful no-op.
+ */
+#ifndef FB4_H
+#define FB4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FB4_OK 0
+#define FB4_ERR_INVALID_ARG (-1) /* null pointer, bad size, bad option, bad formatbook */
+#define FB4_ERR_UNSUPPORTED (-2) /* valid request this build cannot serve (alignment, block size) */
+#define FB4_ERR_ALLOC (-3)       /* host or device allocation of the LUT handle failed */
+#define FB4_ERR_HIP (-4)         /* a HIP runtime call or kernel launch failed */
+
+/* Dialect selectors (Sec. 3.2). */
+#define FB4_SEL_SSE 0 /* exhaustive: squared error of every candidate over every element,
+                         the "MSE-based" selection used for weights and the Exact-MSE ablation */
+#define FB4_SEL_LUT 1 /* the paper's online rule: Qerror midpoint absolute error summed over
+                         the group-wise maxima of num_groups contiguous groups */
+
+/* Option flags. */
+#define FB4_FLAG_TWO_STAGE 1u /* Sec. 3.2 "Two-stage Dialect Selection": first keep only the
+                                 candidates whose largest magnitude equals the integer part of
+                                 the normalized block maximum (8..15); if none has it, keep all */
+
+#define FB4_DTYPE_BF16 0
+#define FB4_DTYPE_F32 1
+
+typedef struct fb4_luts fb4_luts; /* opaque, immutable after creation */
+
+typedef struct fb4_opts {
+    int32_t block;      /* 32 (16: see FB4_ERR_UNSUPPORTED)                          */
+    int32_t selector;   /* FB4_SEL_SSE or FB4_SEL_LUT                                */
+    int32_t num_groups; /* FB4_SEL_LUT only: 8, 16 or 32 groups per block (paper: 8) */
+    uint32_t flags;     /* FB4_FLAG_*                                                */
+} fb4_opts;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int fb4_version(void);
+
+/* Static, never-NULL description of a return code. */
+const char* fb4_strerror(int code);
+
+/* Bytes of caller-provided device workspace any call needs: always 0. */
+size_t fb4_workspace_bytes(void);
+
+/*
+ * Sec. 3.2, "LUT-Based Quantization Error Approximation": build the per-dialect
+ * lookup tables from a formatbook and upload them to the current HIP device.
+ *   formatbook  host, uint8 [n_dialects][8], each row ascending and distinct,
+ *               row[0] == 0, row[7] in 8..15 (FB4_ERR_INVALID_ARG otherwise)
+ *   n_dialects  1..32
+ *   out         host; receives a handle owned by the library until
+ *               fb4_free_luts().  The handle is immutable and may be used from
+ *               several streams and threads at once, on the device it was
+ *               built on.
+ * Tables: Qvalue (bin of width 0.5 over [0,16) -> exact 3-bit index of the
+ * nearest magnitude, ties upward), Qerror (bin -> |bin midpoint - nearest
+ * magnitude|, kept in quarter units so it is an odd integer 1..31), the
+ * nearest-magnitude rows used by the exhaustive selector, and the decode table.
+ */
+int fb4_build_luts(const uint8_t* formatbook, int n_dialects, fb4_luts** out);
+
+/*
+ * Same tables, host only (no GPU needed): writes the blob that
+ * fb4_build_luts() would upload into `blob` (host, `capacity` bytes) and its
+ * size into *size (host, may be the only non-NULL output to query the size).
+ * Blob layout, all little-endian, offsets in bytes:
+ *      0  qerror8  uint8  [32 bins][32 dialects]   Qerror in quarter units
+ *   1024  qvalue64 uint8  [32 dialects][64]        (sign<<5 | bin) -> sign<<3 | index
+ *   3072  qerror16 uint16 [32 bins][32 dialects]   Qerror*32 (quarter units, pre-shifted)
+ *   5120  mag16    uint16 [32 bins][32 dialects]   nearest magnitude m
+ *   7168  gain16   uint16 [32 bins][32 dialects]   m * (bin - m)
+ *   9216  decode   uint16 [32 dialects][8]         bf16 bit pattern of the magnitude
+ *   9728  top      uint8  [32]                     largest magnitude of the dialect
+ *   9760  n_dialects int32, then padding to 9792
+ * Entries of dialects >= n_dialects are filled so that they never win.
+ */
+int fb4_build_luts_host(const uint8_t* formatbook, int n_dialects, void* blob, size_t capacity,
+                        size_t* size);
+
+/* Releases a handle (NULL is allowed).  The caller must have drained every
+ * stream that still uses it. */
+void fb4_free_luts(fb4_luts* luts);
+
+/*
+ * Sec. 3.1 + 3.2: quantize a [rows][cols] bf16 tensor with the full formatbook.
+ * Per block: shared exponent from the largest magnitude, dialect selection by
+ * opts->selector over all dialects (lowest DID wins ties), then every element
+ * through Qvalue.  Also serves weight matrices (blocks along the contiguous
+ * dimension).
+ *   luts        handle from fb4_build_luts
+ *   opts        host
+ *   x           device, bf16 [rows][row_stride]
+ *   codes,meta  device, outputs as described above
+ */
+int fb4_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
+                 int64_t cols, int64_t row_stride, uint8_t* codes, uint16_t* meta, void* stream);
+
+/*
+ * Sec. 3.4 (SeDA): as fb4_quantize, but a row whose token_group[r] = g >= 0
+ * selects only among the eight DIDs sub_formatbooks[g][0..7]; the stored DID
+ * is still the global one, so decoding is unchanged.
+ *   token_group      device, int32 [rows]; -1 (or any value outside
+ *                    0..n_groups-1) = full formatbook for that row
+ *   sub_formatbooks  device, uint8 [n_groups][8]; entries >= n_dialects are
+ *                    skipped; a group with no valid entry falls back to the
+ *                    full formatbook
+ *   n_groups         >= 1
+ */
+int fb4_quantize_seda(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
+                      int64_t cols, int64_t row_stride, const int32_t* token_group,
+                      const uint8_t* sub_formatbooks, int n_groups, uint8_t* codes, uint16_t* meta,
+                      void* stream);
+
+/*
+ * Sec. 3.3 (activation decomposition): for the salient rows only, form the
+ * residual x - dequant(codes1, meta1) exactly, round it once to bf16 and
+ * quantize it with the same routine into a compact second plane.
+ *   x, rows, cols, row_stride   the original tensor (device)
+ *   codes1, meta1               its first plane (device), as written by fb4_quantize*
+ *   salient_rows                device, int32 [n_sal], ascending and unique row
+ *                               indices; an index outside 0..rows-1 leaves its
+ *                               output row untouched
+ *   codes2                      device, uint8 [n_sal][cols/2]   (row p <-> salient_rows[p])
+ *   meta2                       device, uint16 [n_sal][cols/block]
+ *   token_group, sub_formatbooks, n_groups
+ *                               optional SeDA restriction of the residual's
+ *                               candidates (App. D); pass NULL, NULL, 0 for none
+ */
+int fb4_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
+                  int64_t cols, int64_t row_stride, const uint8_t* codes1, const uint16_t* meta1,
+                  const int32_t* salient_rows, int64_t n_sal, const int32_t* token_group,
+                  const uint8_t* sub_formatbooks, int n_groups, uint8_t* codes2, uint16_t* meta2,
+                  void* stream);
+
+/*
+ * Decode (Sec. 3.1; the 4-bit -> 16-bit decode of App. E.2).  Every row is
+ * decoded from plane 1; a salient row additionally gets its second plane:
+ * out = round_to_dtype(fp32(y1) + fp32(y2)) (Sec. 3.3, Q(Act) + Q(Delta)).
+ *   codes2, meta2, salient_rows may all be NULL with n_sal = 0
+ *   out             device, [rows][out_row_stride] of out_dtype
+ *                   (FB4_DTYPE_BF16: 16-byte aligned rows; FB4_DTYPE_F32: 32-byte)
+ * A DID >= n_dialects in the metadata decodes as all-zero magnitudes.
+ */
+int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* meta1,
+                   int64_t rows, int64_t cols, int block, const uint8_t* codes2,
+                   const uint16_t* meta2, const int32_t* salient_rows, int64_t n_sal, void* out,
+                   int out_dtype, int64_t out_row_stride, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FB4_H */

@@ -1,0 +1,207 @@
+"""Thin ctypes binding of libfb4.so: the same entry points as include/fb4.h.
+
+Argument marshalling only -- every step of the quantizer runs in the library's
+HIP kernels.  PyTorch tensors are used for device memory and for the current
+stream; nothing here computes on them.  There is no CPU fallback: if the
+library has not been built, importing this module raises.
+"""
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_UNSUPPORTED = -2
+ERR_ALLOC = -3
+ERR_HIP = -4
+
+SEL_SSE = 0
+SEL_LUT = 1
+FLAG_TWO_STAGE = 1
+DTYPE_BF16 = 0
+DTYPE_F32 = 1
+
+BLOB_BYTES = 9792
+
+
+class Fb4Error(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, strerror(code), code))
+
+
+class fb4_opts(ctypes.Structure):
+    _fields_ = [("block", ctypes.c_int32), ("selector", ctypes.c_int32),
+                ("num_groups", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+def _load():
+    if not os.path.exists(_build.LIB):
+        raise ImportError("libfb4.so is not built: run `python -m paper_2603_02883_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no CPU fallback")
+    lib = ctypes.CDLL(_build.LIB)
+    p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    lib.fb4_version.restype = i32
+    lib.fb4_strerror.restype = ctypes.c_char_p
+    lib.fb4_strerror.argtypes = [i32]
+    lib.fb4_workspace_bytes.restype = ctypes.c_size_t
+    lib.fb4_build_luts.argtypes = [p, i32, ctypes.POINTER(p)]
+    lib.fb4_build_luts_host.argtypes = [p, i32, p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+    lib.fb4_free_luts.argtypes = [p]
+    lib.fb4_free_luts.restype = None
+    lib.fb4_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, p]
+    lib.fb4_quantize_seda.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, i32, p, p, p]
+    lib.fb4_decompose.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, p, i64, p, p, i32,
+                                  p, p, p]
+    lib.fb4_dequantize.argtypes = [p, p, p, i64, i64, i32, p, p, p, i64, p, i32, i64, p]
+    return lib
+
+
+_lib = _load()
+
+EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts", "fb4_build_luts_host",
+           "fb4_free_luts", "fb4_quantize", "fb4_quantize_seda", "fb4_decompose", "fb4_dequantize"]
+
+
+def lib():
+    """The loaded ctypes library (for tests that call the C ABI directly)."""
+    return _lib
+
+
+def version():
+    return int(_lib.fb4_version())
+
+
+def strerror(code):
+    return _lib.fb4_strerror(int(code)).decode()
+
+
+def workspace_bytes():
+    return int(_lib.fb4_workspace_bytes())
+
+
+def _dp(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise Fb4Error(rc, where)
+
+
+def opts(block=32, selector=SEL_LUT, num_groups=8, flags=0):
+    return fb4_opts(block, selector, num_groups, flags)
+
+
+class Luts:
+    """Owner of an fb4_luts handle."""
+
+    def __init__(self, handle, n_dialects):
+        self.handle = handle
+        self.n_dialects = n_dialects
+
+    def free(self):
+        if self.handle:
+            _lib.fb4_free_luts(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def fb4_build_luts_host(formatbook):
+    """Lookup-table blob as a uint8 numpy array (no GPU needed)."""
+    fbk = np.ascontiguousarray(formatbook, dtype=np.uint8)
+    blob = np.zeros(BLOB_BYTES, dtype=np.uint8)
+    size = ctypes.c_size_t(0)
+    rc = _lib.fb4_build_luts_host(fbk.ctypes.data_as(ctypes.c_void_p), fbk.shape[0] if fbk.ndim == 2 else 0,
+                                  blob.ctypes.data_as(ctypes.c_void_p), blob.size, ctypes.byref(size))
+    _check(rc, "fb4_build_luts_host")
+    assert size.value == BLOB_BYTES
+    return blob
+
+
+def fb4_build_luts(formatbook):
+    fbk = np.ascontiguousarray(formatbook, dtype=np.uint8)
+    h = ctypes.c_void_p(None)
+    rc = _lib.fb4_build_luts(fbk.ctypes.data_as(ctypes.c_void_p), fbk.shape[0] if fbk.ndim == 2 else 0,
+                             ctypes.byref(h))
+    _check(rc, "fb4_build_luts")
+    return Luts(h, fbk.shape[0])
+
+
+def fb4_free_luts(luts):
+    luts.free()
+
+
+def fb4_quantize(luts, o, x, codes=None, meta=None, stream=None):
+    """x: bf16 cuda tensor [rows][cols] (row stride allowed).  Returns (codes, meta)."""
+    rows, cols = x.shape
+    if codes is None:
+        codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
+    if meta is None:
+        meta = torch.empty((rows, cols // o.block), dtype=torch.int16, device=x.device)
+    rc = _lib.fb4_quantize(luts.handle, ctypes.byref(o), _dp(x), rows, cols, x.stride(0) if rows > 1 else cols,
+                           _dp(codes), _dp(meta), _stream(stream))
+    _check(rc, "fb4_quantize")
+    return codes, meta
+
+
+def fb4_quantize_seda(luts, o, x, token_group, sub_formatbooks, codes=None, meta=None, stream=None):
+    """token_group: int32 cuda [rows]; sub_formatbooks: uint8 cuda [n_groups][8]."""
+    rows, cols = x.shape
+    if codes is None:
+        codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
+    if meta is None:
+        meta = torch.empty((rows, cols // o.block), dtype=torch.int16, device=x.device)
+    rc = _lib.fb4_quantize_seda(luts.handle, ctypes.byref(o), _dp(x), rows, cols,
+                                x.stride(0) if rows > 1 else cols, _dp(token_group), _dp(sub_formatbooks),
+                                sub_formatbooks.shape[0], _dp(codes), _dp(meta), _stream(stream))
+    _check(rc, "fb4_quantize_seda")
+    return codes, meta
+
+
+def fb4_decompose(luts, o, x, codes1, meta1, salient_rows, token_group=None, sub_formatbooks=None,
+                  codes2=None, meta2=None, stream=None):
+    """salient_rows: int32 cuda [n_sal], ascending.  Returns the compact second plane (codes2, meta2)."""
+    rows, cols = x.shape
+    n_sal = salient_rows.numel()
+    if codes2 is None:
+        codes2 = torch.empty((n_sal, cols // 2), dtype=torch.uint8, device=x.device)
+    if meta2 is None:
+        meta2 = torch.empty((n_sal, cols // o.block), dtype=torch.int16, device=x.device)
+    rc = _lib.fb4_decompose(luts.handle, ctypes.byref(o), _dp(x), rows, cols, x.stride(0) if rows > 1 else cols,
+                            _dp(codes1), _dp(meta1), _dp(salient_rows), n_sal, _dp(token_group),
+                            _dp(sub_formatbooks), 0 if sub_formatbooks is None else sub_formatbooks.shape[0],
+                            _dp(codes2), _dp(meta2), _stream(stream))
+    _check(rc, "fb4_decompose")
+    return codes2, meta2
+
+
+def fb4_dequantize(luts, codes1, meta1, block=32, codes2=None, meta2=None, salient_rows=None,
+                   out=None, out_dtype=DTYPE_BF16, stream=None):
+    rows, half = codes1.shape
+    cols = half * 2
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.bfloat16 if out_dtype == DTYPE_BF16 else torch.float32,
+                          device=codes1.device)
+    n_sal = 0 if salient_rows is None else salient_rows.numel()
+    rc = _lib.fb4_dequantize(luts.handle, _dp(codes1), _dp(meta1), rows, cols, block, _dp(codes2), _dp(meta2),
+                             _dp(salient_rows), n_sal, _dp(out), out_dtype, out.stride(0) if rows > 1 else cols,
+                             _stream(stream))
+    _check(rc, "fb4_dequantize")
+    return out

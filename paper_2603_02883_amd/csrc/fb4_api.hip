@@ -1,0 +1,293 @@
+// C ABI of the FB4 quantizer library: argument checking, lookup-table
+// handle management and kernel launches.  Declarations and the contract of
+// every entry point are in include/fb4.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <new>
+
+#include "../../include/fb4.h"
+#include "fb4_kernels.hpp"
+#include "fb4_tables.hpp"
+
+struct fb4_luts {
+    uint8_t host_blob[fb4::kBlobBytes];
+    uint8_t* dev_blob;
+    int n_dialects;
+    int device;
+    int n_cu;
+};
+
+namespace {
+
+using namespace fb4;
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int grid_for(const fb4_luts* l, long long n_tiles)
+{
+    long long groups = (n_tiles + kWavesPerGroup - 1) / kWavesPerGroup;
+    long long cap = (long long)l->n_cu * 8;
+    if (groups > cap) groups = cap;
+    if (groups < 1) groups = 1;
+    return (int)groups;
+}
+
+int check_opts(const fb4_opts* o)
+{
+    if (!o) return FB4_ERR_INVALID_ARG;
+    if (o->selector != FB4_SEL_SSE && o->selector != FB4_SEL_LUT) return FB4_ERR_INVALID_ARG;
+    if (o->flags & ~FB4_FLAG_TWO_STAGE) return FB4_ERR_INVALID_ARG;
+    if (o->block != 32 && o->block != 16) return FB4_ERR_INVALID_ARG;
+    if (o->selector == FB4_SEL_LUT && o->num_groups != 8 && o->num_groups != 16 && o->num_groups != 32)
+        return FB4_ERR_INVALID_ARG;
+    if (o->block != 32) return FB4_ERR_UNSUPPORTED;
+    return FB4_OK;
+}
+
+template <int SEL, int G, int MODE>
+void launch_ts(bool two_stage, int grid, hipStream_t s, const QuantParams& p)
+{
+    if (two_stage)
+        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, true>), dim3(grid), dim3(kThreads), 0, s, p);
+    else
+        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, false>), dim3(grid), dim3(kThreads), 0, s, p);
+}
+
+template <int MODE>
+int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& p)
+{
+    const bool ts = (o->flags & FB4_FLAG_TWO_STAGE) != 0;
+    if (o->selector == FB4_SEL_SSE) {
+        launch_ts<kSelSse, 8, MODE>(ts, grid, s, p);
+    } else if (o->num_groups == 8) {
+        launch_ts<kSelLut, 8, MODE>(ts, grid, s, p);
+    } else if (o->num_groups == 16) {
+        launch_ts<kSelLut, 16, MODE>(ts, grid, s, p);
+    } else {
+        launch_ts<kSelLut, 32, MODE>(ts, grid, s, p);
+    }
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+// Shared validation of the tensor arguments of the three quantizing calls.
+int check_tensor(const fb4_luts* l, const fb4_opts* o, const void* x, int64_t rows, int64_t cols,
+                 int64_t row_stride, const void* codes, const void* meta)
+{
+    if (!l) return FB4_ERR_INVALID_ARG;
+    int rc = check_opts(o);
+    if (rc != FB4_OK) return rc;
+    if (rows < 0 || cols < 0 || row_stride < cols) return FB4_ERR_INVALID_ARG;
+    if (cols % o->block) return FB4_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return FB4_OK;
+    if (!x || !codes || !meta) return FB4_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || (row_stride % 8) || !aligned(codes, 4) || !aligned(meta, 2)) return FB4_ERR_UNSUPPORTED;
+    return FB4_OK;
+}
+
+// Tiling of `out_rows` rows of `cols` columns; false if it does not fit 32-bit tile indices.
+bool tiling(int64_t out_rows, int64_t cols, int block, int* nb, int* tpr, int* n_tiles)
+{
+    int64_t b = cols / block;
+    int64_t t = (b + kBlocksPerTile - 1) / kBlocksPerTile;
+    if (b > 0x7FFFFFFF || t * out_rows > 0x7FFFFFF0LL) return false;
+    *nb = (int)b;
+    *tpr = (int)t;
+    *n_tiles = (int)(t * out_rows);
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fb4_version(void) { return 100; }
+
+const char* fb4_strerror(int code)
+{
+    switch (code) {
+    case FB4_OK: return "ok";
+    case FB4_ERR_INVALID_ARG: return "invalid argument";
+    case FB4_ERR_UNSUPPORTED: return "unsupported shape, alignment or option";
+    case FB4_ERR_ALLOC: return "allocation failed";
+    case FB4_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+    }
+}
+
+size_t fb4_workspace_bytes(void) { return 0; }
+
+int fb4_build_luts_host(const uint8_t* formatbook, int n_dialects, void* blob, size_t capacity, size_t* size)
+{
+    if (!formatbook_ok(formatbook, n_dialects)) return FB4_ERR_INVALID_ARG;
+    if (size) *size = kBlobBytes;
+    if (!blob) return size ? FB4_OK : FB4_ERR_INVALID_ARG;
+    if (capacity < kBlobBytes) return FB4_ERR_INVALID_ARG;
+    build_blob(formatbook, n_dialects, static_cast<uint8_t*>(blob));
+    return FB4_OK;
+}
+
+int fb4_build_luts(const uint8_t* formatbook, int n_dialects, fb4_luts** out)
+{
+    if (!out) return FB4_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!formatbook_ok(formatbook, n_dialects)) return FB4_ERR_INVALID_ARG;
+    fb4_luts* l = new (std::nothrow) fb4_luts;
+    if (!l) return FB4_ERR_ALLOC;
+    build_blob(formatbook, n_dialects, l->host_blob);
+    l->n_dialects = n_dialects;
+    l->dev_blob = nullptr;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&l->device) != hipSuccess || hipGetDeviceProperties(&prop, l->device) != hipSuccess) {
+        delete l;
+        return FB4_ERR_HIP;
+    }
+    l->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if (hipMalloc(reinterpret_cast<void**>(&l->dev_blob), kBlobBytes) != hipSuccess) {
+        (void)hipGetLastError();
+        delete l;
+        return FB4_ERR_ALLOC;
+    }
+    if (hipMemcpy(l->dev_blob, l->host_blob, kBlobBytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(l->dev_blob);
+        delete l;
+        return FB4_ERR_HIP;
+    }
+    *out = l;
+    return FB4_OK;
+}
+
+void fb4_free_luts(fb4_luts* luts)
+{
+    if (!luts) return;
+    if (luts->dev_blob) (void)hipFree(luts->dev_blob);
+    delete luts;
+}
+
+int fb4_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
+                 int64_t row_stride, uint8_t* codes, uint16_t* meta, void* stream)
+{
+    int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
+    if (rc != FB4_OK || rows == 0 || cols == 0) return rc;
+    QuantParams p = {};
+    if (!tiling(rows, cols, opts->block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
+    p.x = static_cast<const uint16_t*>(x);
+    p.row_stride = row_stride;
+    p.rows = rows;
+    p.codes = codes;
+    p.meta = meta;
+    p.blob = luts->dev_blob;
+    p.n_dialects = luts->n_dialects;
+    return launch_quant<kPlain>(opts, grid_for(luts, p.n_tiles), static_cast<hipStream_t>(stream), p);
+}
+
+int fb4_quantize_seda(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
+                      int64_t row_stride, const int32_t* token_group, const uint8_t* sub_formatbooks,
+                      int n_groups, uint8_t* codes, uint16_t* meta, void* stream)
+{
+    int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
+    if (rc != FB4_OK) return rc;
+    if (n_groups < 1) return FB4_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return FB4_OK;
+    if (!token_group || !sub_formatbooks) return FB4_ERR_INVALID_ARG;
+    if (!aligned(token_group, 4)) return FB4_ERR_UNSUPPORTED;
+    QuantParams p = {};
+    if (!tiling(rows, cols, opts->block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
+    p.x = static_cast<const uint16_t*>(x);
+    p.row_stride = row_stride;
+    p.rows = rows;
+    p.codes = codes;
+    p.meta = meta;
+    p.token_group = token_group;
+    p.sub = sub_formatbooks;
+    p.n_groups = n_groups;
+    p.blob = luts->dev_blob;
+    p.n_dialects = luts->n_dialects;
+    return launch_quant<kSeda>(opts, grid_for(luts, p.n_tiles), static_cast<hipStream_t>(stream), p);
+}
+
+int fb4_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
+                  int64_t row_stride, const uint8_t* codes1, const uint16_t* meta1, const int32_t* salient_rows,
+                  int64_t n_sal, const int32_t* token_group, const uint8_t* sub_formatbooks, int n_groups,
+                  uint8_t* codes2, uint16_t* meta2, void* stream)
+{
+    if (n_sal < 0) return FB4_ERR_INVALID_ARG;
+    int rc = check_tensor(luts, opts, x, rows, cols, row_stride, n_sal ? (const void*)codes2 : (const void*)x,
+                          n_sal ? (const void*)meta2 : (const void*)x);
+    if (rc != FB4_OK) return rc;
+    const bool seda = token_group || sub_formatbooks || n_groups;
+    if (seda && (!token_group || !sub_formatbooks || n_groups < 1)) return FB4_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0 || n_sal == 0) return FB4_OK;
+    if (!codes1 || !meta1 || !salient_rows) return FB4_ERR_INVALID_ARG;
+    if (!aligned(codes1, 4) || !aligned(meta1, 2) || !aligned(salient_rows, 4)) return FB4_ERR_UNSUPPORTED;
+    if (n_sal > rows) return FB4_ERR_INVALID_ARG;   // ascending and unique implies n_sal <= rows
+    QuantParams p = {};
+    if (!tiling(n_sal, cols, opts->block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
+    p.x = static_cast<const uint16_t*>(x);
+    p.row_stride = row_stride;
+    p.rows = rows;
+    p.codes = codes2;
+    p.meta = meta2;
+    p.token_group = token_group;
+    p.sub = sub_formatbooks;
+    p.n_groups = n_groups;
+    p.codes1 = codes1;
+    p.meta1 = meta1;
+    p.salient = salient_rows;
+    p.blob = luts->dev_blob;
+    p.n_dialects = luts->n_dialects;
+    return launch_quant<kDecomp>(opts, grid_for(luts, p.n_tiles), static_cast<hipStream_t>(stream), p);
+}
+
+int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* meta1, int64_t rows, int64_t cols,
+                   int block, const uint8_t* codes2, const uint16_t* meta2, const int32_t* salient_rows,
+                   int64_t n_sal, void* out, int out_dtype, int64_t out_row_stride, void* stream)
+{
+    if (!luts) return FB4_ERR_INVALID_ARG;
+    if (block != 32 && block != 16) return FB4_ERR_INVALID_ARG;
+    if (out_dtype != FB4_DTYPE_BF16 && out_dtype != FB4_DTYPE_F32) return FB4_ERR_INVALID_ARG;
+    if (rows < 0 || cols < 0 || n_sal < 0 || out_row_stride < cols) return FB4_ERR_INVALID_ARG;
+    if (block != 32 || cols % block) return FB4_ERR_UNSUPPORTED;
+    if (n_sal > 0 && (!codes2 || !meta2 || !salient_rows)) return FB4_ERR_INVALID_ARG;
+    if (n_sal > rows) return FB4_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return FB4_OK;
+    if (!codes1 || !meta1 || !out) return FB4_ERR_INVALID_ARG;
+    const size_t oal = out_dtype == FB4_DTYPE_BF16 ? 16 : 32;
+    if (!aligned(out, oal) || (out_row_stride % 8) || !aligned(codes1, 4) || !aligned(meta1, 2))
+        return FB4_ERR_UNSUPPORTED;
+    if (n_sal > 0 && (!aligned(codes2, 4) || !aligned(meta2, 2) || !aligned(salient_rows, 4)))
+        return FB4_ERR_UNSUPPORTED;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    DequantParams p = {};
+    if (!tiling(rows, cols, block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
+    p.codes1 = codes1;
+    p.meta1 = meta1;
+    p.rows = rows;
+    p.out = out;
+    p.out_row_stride = out_row_stride;
+    p.blob = luts->dev_blob;
+    int grid = grid_for(luts, p.n_tiles);
+    if (out_dtype == FB4_DTYPE_F32)
+        hipLaunchKernelGGL((dequantize_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p);
+    else
+        hipLaunchKernelGGL((dequantize_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, p);
+    if (hipGetLastError() != hipSuccess) return FB4_ERR_HIP;
+    if (n_sal > 0) {
+        // second pass, ordered after the first on the same stream: salient rows = plane 1 + plane 2
+        DequantParams p2 = p;
+        if (!tiling(n_sal, cols, block, &p2.nb, &p2.tiles_per_row, &p2.n_tiles)) return FB4_ERR_UNSUPPORTED;
+        p2.codes2 = codes2;
+        p2.meta2 = meta2;
+        p2.salient = salient_rows;
+        grid = grid_for(luts, p2.n_tiles);
+        if (out_dtype == FB4_DTYPE_F32)
+            hipLaunchKernelGGL((dequantize_kernel<true, true>), dim3(grid), dim3(kThreads), 0, s, p2);
+        else
+            hipLaunchKernelGGL((dequantize_kernel<true, false>), dim3(grid), dim3(kThreads), 0, s, p2);
+        if (hipGetLastError() != hipSuccess) return FB4_ERR_HIP;
+    }
+    return FB4_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,400 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bar: codes, dialect IDs, exponents and dequantized values are bit-exact.  The
+only tolerated difference is a dialect choice between two candidates whose
+oracle scores agree to 1e-6 relative; such a block is reported (and its codes
+are checked against the oracle run with the GPU's choice).  All scores are
+exact integers on the GPU, so no such block is expected.
+"""
+
+import warnings
+
+import numpy as np
+import pytest
+import torch
+
+from fb4_inputs import DEFAULT_FORMATBOOK, E2M1_X2_FORMATBOOK, synth
+from oracle import fb4_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+SELECTORS = [("lut8", 1, 8), ("lut32", 1, 32), ("sse", 0, 8)]
+
+
+@pytest.fixture(scope="module")
+def F():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2603_02883_amd as F
+    return F
+
+
+@pytest.fixture(scope="module")
+def luts(F):
+    l = F.fb4_build_luts(DEFAULT_FORMATBOOK)
+    yield l
+    l.free()
+
+
+def dev_bits(bits):
+    return synth.bits_to_bf16(bits, "cuda")
+
+
+def host_u8(t):
+    return t.cpu().numpy()
+
+
+def host_u16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def compare_quant(fbk, x_bits, cg, mg, cr, mr, sel, g, flags=0, token_group=None, sub=None, what=""):
+    """cg/mg from the GPU, cr/mr from the oracle (numpy)."""
+    assert cg.shape == cr.shape and mg.shape == mr.shape
+    if np.array_equal(mg, mr) and np.array_equal(cg, cr):
+        return 0
+    assert np.array_equal(mg >> 8, mr >> 8), what + ": shared exponents differ"
+    bad = np.argwhere((mg & 0xFF) != (mr & 0xFF))
+    ties = 0
+    for r, b in bad[:64]:
+        blk = x_bits[r, 32 * b:32 * b + 32]
+        sub8 = None if (token_group is None or token_group[r] < 0) else sub[token_group[r]]
+        cand, scores, did, e = O.block_scores(fbk, blk, selector=sel, num_groups=g, flags=flags, sub8=sub8)
+        dg = int(mg[r, b] & 0xFF)
+        assert dg in cand.tolist(), "%s: GPU chose DID %d outside the candidates at (%d,%d)" % (what, dg, r, b)
+        sg = scores[cand.tolist().index(dg)]
+        sr = scores[cand.tolist().index(int(mr[r, b] & 0xFF))]
+        assert abs(sg - sr) <= 1e-6 * max(abs(sr), 1e-30), (
+            "%s: dialect mismatch at row %d block %d: gpu %d (score %r) oracle %d (score %r)"
+            % (what, r, b, dg, sg, int(mr[r, b] & 0xFF), sr))
+        c1, _ = O.quantize(fbk[dg:dg + 1], blk[None, :], selector=O.SEL_SSE)
+        assert np.array_equal(cg[r, 16 * b:16 * b + 16], c1[0]), what + ": codes of a tied block"
+        ties += 1
+    assert len(bad) <= 64, what + ": %d dialect mismatches" % len(bad)
+    if ties:
+        warnings.warn("%s: %d argmin ties resolved differently (scores equal within 1e-6)" % (what, ties))
+    ok = np.ones(mg.shape, dtype=bool)
+    ok[bad[:, 0], bad[:, 1]] = False
+    assert np.array_equal(cg.reshape(mg.shape + (16,))[ok], cr.reshape(mr.shape + (16,))[ok]), what + ": codes differ"
+    return ties
+
+
+def run_quant(F, luts, x, sel, g, flags=0):
+    o = F.opts(selector=sel, num_groups=g, flags=flags)
+    c, m = F.fb4_quantize(luts, o, x)
+    torch.cuda.synchronize()
+    return host_u8(c), host_u16(m), c, m
+
+
+# ----------------------------------------------------------------- configs
+@pytest.mark.parametrize("name,sel,g", SELECTORS)
+def test_cfg1_gaussian_outliers_full_tensor(F, luts, name, sel, g):
+    x = synth.gaussian_outlier(device="cuda")                 # 1024 x 3072
+    xb = synth.bf16_bits(x)
+    cg, mg, c, m = run_quant(F, luts, x, sel, g)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, selector=sel, num_groups=g)
+    compare_quant(DEFAULT_FORMATBOOK, xb, cg, mg, cr, mr, sel, g, what="cfg1 " + name)
+    for dt, odt in ((F.DTYPE_BF16, O.OUT_BF16), (F.DTYPE_F32, O.OUT_F32)):
+        y = F.fb4_dequantize(luts, c, m, out_dtype=dt)
+        torch.cuda.synchronize()
+        yr = O.dequantize(DEFAULT_FORMATBOOK, cg, mg, out_dtype=odt)
+        yg = synth.bf16_bits(y) if dt == F.DTYPE_BF16 else y.cpu().numpy().view(np.uint32)
+        assert np.array_equal(yg, yr if dt == F.DTYPE_BF16 else yr.view(np.uint32))
+
+
+@pytest.mark.parametrize("name,sel,g", SELECTORS)
+def test_cfg2_vdit_activation_full_size(F, luts, name, sel, g):
+    x = synth.vdit_activation(device="cuda")                  # 16384 x 3072, the benchmark workload
+    xb = synth.bf16_bits(x)
+    cg, mg, c, m = run_quant(F, luts, x, sel, g)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, selector=sel, num_groups=g)
+    compare_quant(DEFAULT_FORMATBOOK, xb, cg, mg, cr, mr, sel, g, what="cfg2 " + name)
+    hist = np.bincount((mg & 0xFF).ravel(), minlength=32)
+    assert (hist > 0).sum() >= 24                             # many dialects in use (App. B: no collapse)
+
+
+@pytest.mark.parametrize("name,sel,g", [SELECTORS[0], SELECTORS[2]])
+def test_cfg3_decomposition_of_salient_tokens(F, luts, name, sel, g):
+    x = synth.vdit_activation(device="cuda")
+    xb = synth.bf16_bits(x)
+    sal = synth.salient_rows_from_attention(16384, frac=0.05, heads=24, seed=3, device="cuda")
+    assert sal.size == 819 and (np.diff(sal) > 0).all()
+    o = F.opts(selector=sel, num_groups=g)
+    c1, m1 = F.fb4_quantize(luts, o, x)
+    sal_d = torch.from_numpy(sal).cuda()
+    c2, m2 = F.fb4_decompose(luts, o, x, c1, m1, sal_d)
+    y = F.fb4_dequantize(luts, c1, m1, codes2=c2, meta2=m2, salient_rows=sal_d)
+    yf = F.fb4_dequantize(luts, c1, m1, codes2=c2, meta2=m2, salient_rows=sal_d, out_dtype=F.DTYPE_F32)
+    torch.cuda.synchronize()
+    c1h, m1h = host_u8(c1), host_u16(m1)
+    # oracle on the salient rows only (plane 1 of the other rows is covered by cfg2)
+    c1r, m1r = O.quantize(DEFAULT_FORMATBOOK, xb[sal], selector=sel, num_groups=g)
+    compare_quant(DEFAULT_FORMATBOOK, xb[sal], c1h[sal], m1h[sal], c1r, m1r, sel, g, what="cfg3 plane1 " + name)
+    c2r, m2r = O.decompose(DEFAULT_FORMATBOOK, xb[sal], c1h[sal], m1h[sal], np.arange(sal.size, dtype=np.int32),
+                           selector=sel, num_groups=g)
+    compare_quant(DEFAULT_FORMATBOOK, xb[sal], host_u8(c2), host_u16(m2), c2r, m2r, sel, g, what="cfg3 plane2 " + name)
+    # dequantize: salient rows = both planes, a sample of the other rows = plane 1
+    rest = np.setdiff1d(np.arange(0, 16384, 37), sal)
+    rows = np.sort(np.concatenate([sal, rest])).astype(np.int64)
+    pos = np.searchsorted(rows, sal).astype(np.int32)
+    yr = O.dequantize(DEFAULT_FORMATBOOK, c1h[rows], m1h[rows], codes2=host_u8(c2), meta2=host_u16(m2),
+                      salient_rows=pos, out_dtype=O.OUT_BF16)
+    assert np.array_equal(synth.bf16_bits(y)[rows], yr)
+    yfr = O.dequantize(DEFAULT_FORMATBOOK, c1h[rows], m1h[rows], codes2=host_u8(c2), meta2=host_u16(m2),
+                       salient_rows=pos, out_dtype=O.OUT_F32)
+    assert np.array_equal(yf.cpu().numpy()[rows].view(np.uint32), yfr.view(np.uint32))
+    # Sec. 3.3: the second plane shrinks the error of the salient rows
+    xs = x[sal_d.long()].float()
+    e1 = (xs - F.fb4_dequantize(luts, c1, m1, out_dtype=F.DTYPE_F32)[sal_d.long()]).pow(2).sum()
+    e2 = (xs - yf[sal_d.long()]).pow(2).sum()
+    assert float(e2) < 0.2 * float(e1)
+
+
+@pytest.mark.parametrize("name,sel,g", SELECTORS)
+def test_cfg4_seda_sub_formatbooks(F, luts, name, sel, g):
+    x, comp = synth.mixture_activation(device="cuda")         # 16384 x 3072, 64 groups
+    xb = synth.bf16_bits(x)
+    sub = synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, n_groups=64, seed=4)
+    tg = comp.copy()
+    tg[::97] = -1                                             # a few rows on the full formatbook
+    o = F.opts(selector=sel, num_groups=g)
+    c, m = F.fb4_quantize_seda(luts, o, x, torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda())
+    torch.cuda.synchronize()
+    rows = np.arange(0, 16384, 4) if sel == 0 else np.arange(16384)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb[rows], selector=sel, num_groups=g, token_group=tg[rows],
+                        sub_formatbooks=sub)
+    compare_quant(DEFAULT_FORMATBOOK, xb[rows], host_u8(c)[rows], host_u16(m)[rows], cr, mr, sel, g,
+                  token_group=tg[rows], sub=sub, what="cfg4 " + name)
+    did = host_u16(m) & 0xFF
+    inside = (did[:, :, None] == sub[np.maximum(tg, 0)][:, None, :]).any(axis=2)
+    assert inside[tg >= 0].all()                              # every DID from the row's sub-formatbook
+
+
+def test_cfg5_large_ffn_activation_and_weight(F, luts):
+    rows, cols = synth.CONFIG_SHAPES["cfg5"]
+    x = synth.vdit_activation(rows=rows, cols=cols, seed=5, device="cuda", outlier_frac=0.01)
+    sal = synth.salient_rows_from_attention(rows, frac=0.05, heads=24, seed=5, device="cuda", window=1024)
+    assert sal.size == 3276
+    sal_d = torch.from_numpy(sal).cuda()
+    rng = np.random.default_rng(55)
+    sample = np.unique(np.concatenate([rng.integers(0, rows, 48), sal[:16], [0, rows - 1]])).astype(np.int64)
+    xs = synth.bf16_bits(x[torch.from_numpy(sample).cuda()])
+    for name, sel, g in (SELECTORS[0], SELECTORS[2]):
+        o = F.opts(selector=sel, num_groups=g)
+        c1, m1 = F.fb4_quantize(luts, o, x)
+        c2, m2 = F.fb4_decompose(luts, o, x, c1, m1, sal_d)
+        y = F.fb4_dequantize(luts, c1, m1, codes2=c2, meta2=m2, salient_rows=sal_d)
+        torch.cuda.synchronize()
+        idx = torch.from_numpy(sample).cuda()
+        c1s, m1s = host_u8(c1[idx]), host_u16(m1[idx])
+        cr, mr = O.quantize(DEFAULT_FORMATBOOK, xs, selector=sel, num_groups=g)
+        compare_quant(DEFAULT_FORMATBOOK, xs, c1s, m1s, cr, mr, sel, g, what="cfg5 " + name)
+        # second plane of the sampled salient rows
+        in_sal = np.isin(sample, sal)
+        p_of = np.searchsorted(sal, sample[in_sal])
+        c2r, m2r = O.decompose(DEFAULT_FORMATBOOK, xs[in_sal], c1s[in_sal], m1s[in_sal],
+                               np.arange(in_sal.sum(), dtype=np.int32), selector=sel, num_groups=g)
+        pidx = torch.from_numpy(p_of).cuda()
+        compare_quant(DEFAULT_FORMATBOOK, xs[in_sal], host_u8(c2[pidx]), host_u16(m2[pidx]), c2r, m2r, sel, g,
+                      what="cfg5 plane2 " + name)
+        yr = O.dequantize(DEFAULT_FORMATBOOK, c1s, m1s, codes2=host_u8(c2[pidx]), meta2=host_u16(m2[pidx]),
+                          salient_rows=np.nonzero(in_sal)[0].astype(np.int32))
+        assert np.array_equal(synth.bf16_bits(y[idx]), yr)
+        # properties that hold at any size, checked on the whole tensor on the device
+        mi = m1.view(torch.int16).to(torch.int32) & 0xFFFF
+        assert int((mi & 0xFF).max()) < 32
+        amax = x.view(rows, cols // 32, 32).abs().amax(dim=2).float()
+        _, ex = torch.frexp(amax)                              # amax = mant * 2^ex, mant in [0.5, 1)
+        e = torch.where(amax > 0, ex - 1, torch.full_like(ex, -123)).clamp(-123, 127).to(torch.int32)
+        assert torch.equal((mi >> 8) - 127, e)
+        nz = y.float().abs() <= amax.repeat_interleave(32, dim=1) * 2.0    # decoded values stay in range
+        assert bool(nz.all())
+        del c1, m1, c2, m2, y
+    # the weight matrix of the layer goes through the same kernel (exhaustive selection, Sec. 3.3 / App. D)
+    w = synth.weight_matrix(device="cuda")
+    wb = synth.bf16_bits(w)
+    cg, mg, _, _ = run_quant(F, luts, w, 0, 8)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, wb, selector=O.SEL_SSE)
+    compare_quant(DEFAULT_FORMATBOOK, wb, cg, mg, cr, mr, 0, 8, what="cfg5 weight")
+
+
+# -------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("name,sel,g", SELECTORS)
+def test_degenerate_values(F, luts, name, sel, g):
+    xb = synth.edge_case_tensor(cols=256)
+    x = dev_bits(xb)
+    o = F.opts(selector=sel, num_groups=g)
+    c, m = F.fb4_quantize(luts, o, x)
+    torch.cuda.synchronize()
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, selector=sel, num_groups=g)
+    compare_quant(DEFAULT_FORMATBOOK, xb, host_u8(c), host_u16(m), cr, mr, sel, g, what="edge " + name)
+    y = F.fb4_dequantize(luts, c, m)
+    torch.cuda.synchronize()
+    assert np.array_equal(synth.bf16_bits(y), O.dequantize(DEFAULT_FORMATBOOK, cr, mr))
+    # decomposition of every row, including Inf/NaN/subnormal residuals
+    sal = np.arange(xb.shape[0], dtype=np.int32)
+    c2, m2 = F.fb4_decompose(luts, o, x, c, m, torch.from_numpy(sal).cuda())
+    yy = F.fb4_dequantize(luts, c, m, codes2=c2, meta2=m2, salient_rows=torch.from_numpy(sal).cuda())
+    torch.cuda.synchronize()
+    c2r, m2r = O.decompose(DEFAULT_FORMATBOOK, xb, cr, mr, sal, selector=sel, num_groups=g)
+    compare_quant(DEFAULT_FORMATBOOK, xb, host_u8(c2), host_u16(m2), c2r, m2r, sel, g, what="edge plane2 " + name)
+    yyr = O.dequantize(DEFAULT_FORMATBOOK, cr, mr, codes2=c2r, meta2=m2r, salient_rows=sal)
+    assert np.array_equal(synth.bf16_bits(yy), yyr)
+
+
+@pytest.mark.parametrize("name,sel,g", SELECTORS)
+def test_ragged_shapes_and_row_stride(F, luts, name, sel, g):
+    rng = np.random.default_rng(12)
+    for rows, cols, stride in ((37, 32 * 19, 32 * 19 + 8), (1, 32, 32), (5, 32 * 33, 32 * 40), (300, 64, 64)):
+        big = synth.vdit_activation(rows=rows, cols=stride, seed=40 + cols % 7, device="cuda")
+        x = big[:, :cols]                                     # non-contiguous view when stride > cols
+        xb = synth.bf16_bits(big)[:, :cols]
+        o = F.opts(selector=sel, num_groups=g)
+        c, m = F.fb4_quantize(luts, o, x)
+        torch.cuda.synchronize()
+        cr, mr = O.quantize(DEFAULT_FORMATBOOK, np.ascontiguousarray(xb), selector=sel, num_groups=g)
+        compare_quant(DEFAULT_FORMATBOOK, xb, host_u8(c), host_u16(m), cr, mr, sel, g,
+                      what="ragged %dx%d %s" % (rows, cols, name))
+        out = torch.full((rows, stride), 7.0, dtype=torch.bfloat16, device="cuda")
+        F.fb4_dequantize(luts, c, m, out=out[:, :cols])
+        torch.cuda.synchronize()
+        assert np.array_equal(synth.bf16_bits(out)[:, :cols], O.dequantize(DEFAULT_FORMATBOOK, cr, mr))
+        assert bool((out[:, cols:] == 7.0).all())             # padding untouched
+
+
+@pytest.mark.parametrize("name,sel,g", SELECTORS)
+def test_two_stage_selection(F, luts, name, sel, g):
+    x = synth.vdit_activation(rows=512, cols=3072, seed=41, device="cuda")
+    xb = synth.bf16_bits(x)
+    cg, mg, _, _ = run_quant(F, luts, x, sel, g, flags=F.FLAG_TWO_STAGE)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, selector=sel, num_groups=g, flags=O.FLAG_TWO_STAGE)
+    compare_quant(DEFAULT_FORMATBOOK, xb, cg, mg, cr, mr, sel, g, flags=O.FLAG_TWO_STAGE, what="two-stage " + name)
+
+
+@pytest.mark.parametrize("name,sel,g", SELECTORS)
+def test_small_formatbooks(F, name, sel, g):
+    x = synth.gaussian_outlier(rows=64, cols=1024, seed=42, device="cuda")
+    xb = synth.bf16_bits(x)
+    for fbk in (E2M1_X2_FORMATBOOK, DEFAULT_FORMATBOOK[:5], DEFAULT_FORMATBOOK[[0, 3, 9, 12, 17, 23, 31]]):
+        l = F.fb4_build_luts(fbk)
+        for flags in (0, F.FLAG_TWO_STAGE):
+            cg, mg, c, m = run_quant(F, l, x, sel, g, flags=flags)
+            cr, mr = O.quantize(fbk, xb, selector=sel, num_groups=g, flags=flags)
+            compare_quant(fbk, xb, cg, mg, cr, mr, sel, g, flags=flags, what="small formatbook " + name)
+        y = F.fb4_dequantize(l, c, m)
+        torch.cuda.synchronize()
+        assert np.array_equal(synth.bf16_bits(y), O.dequantize(fbk, cr, mr))
+        l.free()
+
+
+@pytest.mark.parametrize("name,sel,g", SELECTORS)
+def test_seda_with_two_stage_decomposition_and_odd_tables(F, luts, name, sel, g):
+    x, comp = synth.mixture_activation(rows=256, cols=32 * 21, seed=43, device="cuda", n_components=5)
+    xb = synth.bf16_bits(x)
+    sub = synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, n_groups=5, seed=43)
+    sub[3] = [2, 2, 5, 9, 9, 30, 31, 31]                      # duplicates, ranges missing
+    tg = comp.copy()
+    tg[::9] = -1
+    tg_d, sub_d = torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda()
+    for flags in (0, F.FLAG_TWO_STAGE):
+        o = F.opts(selector=sel, num_groups=g, flags=flags)
+        c, m = F.fb4_quantize_seda(luts, o, x, tg_d, sub_d)
+        torch.cuda.synchronize()
+        # the oracle wants ascending unique lists: give it the same sets, padded by repetition-free order
+        cr = np.zeros_like(host_u8(c)); mr = np.zeros_like(host_u16(m))
+        for grp in range(-1, 5):
+            rows = np.nonzero(tg == grp)[0]
+            if grp < 0:
+                a, b = O.quantize(DEFAULT_FORMATBOOK, xb[rows], selector=sel, num_groups=g, flags=flags)
+            else:
+                a, b = _oracle_subset(xb[rows], sorted(set(sub[grp].tolist())), sel, g, flags)
+            cr[rows], mr[rows] = a, b
+        compare_quant(DEFAULT_FORMATBOOK, xb, host_u8(c), host_u16(m), cr, mr, sel, g, flags=flags,
+                      what="seda odd %s flags %d" % (name, flags))
+        # decomposition restricted to the same sub-formatbooks (App. D)
+        sal = np.arange(0, 256, 7, dtype=np.int32)
+        c2, m2 = F.fb4_decompose(luts, o, x, c, m, torch.from_numpy(sal).cuda(), token_group=tg_d,
+                                 sub_formatbooks=sub_d)
+        torch.cuda.synchronize()
+        if flags == 0:
+            keep = tg[sal] != 3                                # group 3's table is not a valid oracle input
+            sal, c2, m2 = sal[keep], c2[torch.from_numpy(keep).cuda()], m2[torch.from_numpy(keep).cuda()]
+            sub_ok = sub.copy()
+            sub_ok[3] = sub[0]
+            c2r, m2r = O.decompose(DEFAULT_FORMATBOOK, xb, host_u8(c), host_u16(m), sal, selector=sel,
+                                   num_groups=g, token_group=tg, sub_formatbooks=sub_ok)
+            compare_quant(DEFAULT_FORMATBOOK, xb[sal], host_u8(c2), host_u16(m2), c2r, m2r, sel, g,
+                          what="seda decomposition " + name)
+
+
+def _oracle_subset(xb, dids, sel, g, flags):
+    """Oracle selection restricted to an arbitrary DID set: quantize with the
+    formatbook cut down to those dialects and map the DIDs back."""
+    fbk = DEFAULT_FORMATBOOK[dids]
+    c, m = O.quantize(fbk, xb, selector=sel, num_groups=g, flags=flags)
+    did = np.asarray(dids, dtype=np.uint16)[m & 0xFF]
+    return c, (m & 0xFF00) | did
+
+
+def test_seda_invalid_groups_and_dids_fall_back(F, luts):
+    x = synth.gaussian_outlier(rows=32, cols=512, seed=44, device="cuda")
+    xb = synth.bf16_bits(x)
+    l5 = F.fb4_build_luts(DEFAULT_FORMATBOOK[:5])
+    sub = np.array([[0, 1, 2, 3, 4, 4, 4, 4], [9, 9, 9, 9, 9, 9, 9, 9], [1, 40, 200, 3, 3, 3, 3, 3]], dtype=np.uint8)
+    tg = np.array([0, 1, 2, 3, -1, -7, 99, 0] * 4, dtype=np.int32)
+    o = F.opts(selector=F.SEL_LUT, num_groups=8)
+    c, m = F.fb4_quantize_seda(l5, o, x, torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda())
+    torch.cuda.synchronize()
+    fb5 = DEFAULT_FORMATBOOK[:5]
+    cr = np.zeros_like(host_u8(c)); mr = np.zeros_like(host_u16(m))
+    full = np.isin(tg, [1, 3, -1, -7, 99])                     # group 1 has no valid DID -> full formatbook
+    cr[full], mr[full] = O.quantize(fb5, xb[full], selector=O.SEL_LUT)
+    cr[tg == 0], mr[tg == 0] = O.quantize(fb5, xb[tg == 0], selector=O.SEL_LUT)   # all five dialects listed
+    c13, m13 = O.quantize(fb5[[1, 3]], xb[tg == 2], selector=O.SEL_LUT)
+    cr[tg == 2] = c13
+    mr[tg == 2] = (m13 & 0xFF00) | np.array([1, 3], dtype=np.uint16)[m13 & 0xFF]
+    assert np.array_equal(host_u16(m), mr) and np.array_equal(host_u8(c), cr)
+    l5.free()
+
+
+def test_empty_inputs_and_error_codes_with_a_real_handle(F, luts):
+    o = F.opts()
+    x = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
+    c, m = F.fb4_quantize(luts, o, x)
+    assert c.shape == (0, 32) and m.shape == (0, 2)
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    c, m = F.fb4_quantize(luts, o, x)
+    sal = torch.zeros(0, dtype=torch.int32, device="cuda")
+    c2, m2 = F.fb4_decompose(luts, o, x, c, m, sal)
+    assert c2.shape == (0, 32)
+    y = F.fb4_dequantize(luts, c, m, codes2=c2, meta2=m2, salient_rows=sal)
+    torch.cuda.synchronize()
+    assert bool((y == 0).all())
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_quantize(luts, o, torch.zeros((4, 48), dtype=torch.bfloat16, device="cuda"))
+    assert e.value.code == F.ERR_UNSUPPORTED
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_quantize(luts, F.opts(block=16), x)
+    assert e.value.code == F.ERR_UNSUPPORTED
+    # out-of-range salient rows leave their output rows untouched
+    sal = torch.tensor([1, 77], dtype=torch.int32, device="cuda")
+    c2 = torch.full((2, 32), 0x5A, dtype=torch.uint8, device="cuda")
+    m2 = torch.zeros((2, 2), dtype=torch.int16, device="cuda")
+    F.fb4_decompose(luts, o, x, c, m, sal, codes2=c2, meta2=m2)
+    torch.cuda.synchronize()
+    assert bool((c2[1] == 0x5A).all()) and bool((c2[0] == 0).all())
+
+
+def test_luts_handle_is_reusable_across_streams(F, luts):
+    x = synth.gaussian_outlier(rows=256, cols=1024, seed=45, device="cuda")
+    o = F.opts()
+    ref = F.fb4_quantize(luts, o, x)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for s in (s1, s2, s1, s2):
+        with torch.cuda.stream(s):
+            outs.append(F.fb4_quantize(luts, o, x))
+    torch.cuda.synchronize()
+    for c, m in outs:
+        assert torch.equal(c, ref[0]) and torch.equal(m, ref[1])
