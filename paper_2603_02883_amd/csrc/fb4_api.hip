@@ -7,6 +7,7 @@
 #include <new>
 
 #include "../../include/fb4.h"
+#include "fb4_fast.hpp"
 #include "fb4_kernels.hpp"
 #include "fb4_tables.hpp"
 
@@ -178,7 +179,35 @@ int fb4_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int6
     p.meta = meta;
     p.blob = luts->dev_blob;
     p.n_dialects = luts->n_dialects;
-    return launch_quant<kPlain>(opts, grid_for(luts, p.n_tiles), static_cast<hipStream_t>(stream), p);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (opts->selector == FB4_SEL_LUT && opts->num_groups == 8 && opts->flags == 0 && aligned(codes, 16)) {
+        // the paper's default online configuration: one lane per block, packed 16-bit path
+        FastParams f = {};
+        const uint64_t n_blocks = (uint64_t)rows * (uint64_t)p.nb;
+        if (n_blocks < 0x7FFFFF00ull) {
+            f.x = p.x;
+            f.row_stride = row_stride;
+            f.nb = (uint32_t)p.nb;
+            f.n_blocks = (uint32_t)n_blocks;
+            f.n_tiles = (uint32_t)((n_blocks + 63) / 64);
+            uint32_t l = 0;
+            while ((1ull << l) < (uint64_t)p.nb) ++l;
+            f.div_shift = 31 + l;
+            f.div_mul = (uint32_t)(((1ull << f.div_shift) + (uint64_t)p.nb - 1) / (uint64_t)p.nb);
+            f.codes = codes;
+            f.meta = meta;
+            f.blob = luts->dev_blob;
+            long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
+            const long long cap = (long long)luts->n_cu * 4;
+            if (groups > cap) groups = cap;
+            if (row_stride == cols)
+                hipLaunchKernelGGL((quantize_lut8_kernel<true>), dim3((unsigned)groups), dim3(kFastThreads), 0, s, f);
+            else
+                hipLaunchKernelGGL((quantize_lut8_kernel<false>), dim3((unsigned)groups), dim3(kFastThreads), 0, s, f);
+            return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+        }
+    }
+    return launch_quant<kPlain>(opts, grid_for(luts, p.n_tiles), s, p);
 }
 
 int fb4_quantize_seda(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
