@@ -111,6 +111,8 @@ int fb4_build_luts(const uint8_t* formatbook, int n_dialects, fb4_luts** out);
  *   9216  decode   uint16 [32 dialects][8]         bf16 bit pattern of the magnitude
  *   9728  top      uint8  [32]                     largest magnitude of the dialect
  *   9760  n_dialects int32, then padding to 9792
+ *   9792  qvalueT  uint8  [32 bins][32 dialects]   bin -> 3-bit index, bin-major copy of Qvalue
+ * Total 10816 bytes.
  * Entries of dialects >= n_dialects are filled so that they never win.
  */
 int fb4_build_luts_host(const uint8_t* formatbook, int n_dialects, void* blob, size_t capacity,

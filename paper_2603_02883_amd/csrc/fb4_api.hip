@@ -198,7 +198,7 @@ int fb4_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int6
             f.meta = meta;
             f.blob = luts->dev_blob;
             long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
-            const long long cap = (long long)luts->n_cu * 4;
+            const long long cap = (long long)luts->n_cu * FB4_FAST_GROUPS_PER_CU;
             if (groups > cap) groups = cap;
             if (row_stride == cols)
                 hipLaunchKernelGGL((quantize_lut8_kernel<true>), dim3((unsigned)groups), dim3(kFastThreads), 0, s, f);

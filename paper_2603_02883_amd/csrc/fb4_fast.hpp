@@ -8,6 +8,13 @@
 // covers 64 consecutive blocks (4 KiB of input) and writes 1 KiB of codes and
 // 128 bytes of metadata, all contiguous.
 //
+// LDS tables, built once per workgroup:
+//   * Qerror rows (32 bytes per bin, one byte per dialect), eight copies laid
+//     out so that lane l always reads banks 4*(l%8)..4*(l%8)+3: the 16-byte row
+//     reads of a wavefront never collide whatever bins the lanes ask for;
+//   * a pair table: (bin of element 2m, bin of element 2m+1, dialect) -> the
+//     finished code byte without sign bits, so one lookup emits two elements.
+//
 // A block whose largest magnitude is NaN/Inf-sized or below 2^-122 (and not
 // zero) leaves the packed path: the wavefront then redoes its tile with a
 // plain per-element routine that covers every input.
@@ -20,7 +27,14 @@
 
 namespace fb4 {
 
-constexpr int kFastThreads = 256;
+#ifndef FB4_FAST_THREADS
+#define FB4_FAST_THREADS 512
+#endif
+#ifndef FB4_FAST_GROUPS_PER_CU
+#define FB4_FAST_GROUPS_PER_CU 2   // resident workgroups per compute unit the grid is sized for
+#endif
+
+constexpr int kFastThreads = FB4_FAST_THREADS;
 constexpr int kFastWaves = kFastThreads / 64;
 
 struct FastParams {
@@ -58,20 +72,39 @@ __device__ __forceinline__ uint32_t pk_shr(uint32_t v, uint32_t s)   // per half
 }
 __device__ __forceinline__ uint32_t halves_max(uint32_t v) { return max(v & 0xFFFFu, v >> 16); }
 __device__ __forceinline__ uint32_t halves_min(uint32_t v) { return min(v & 0xFFFFu, v >> 16); }
+// a.lo*b.lo + a.hi*b.hi + c
+__device__ __forceinline__ uint32_t dot2_u16(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_udot2(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b), c, false);
+}
+// A constant the optimizer cannot fold back into an instruction literal: keeps
+// three-operand instructions encodable with the constant in a register.
+__device__ __forceinline__ uint32_t sgpr_const(uint32_t v)
+{
+    uint32_t r;
+    asm volatile("s_mov_b32 %0, %1" : "=s"(r) : "i"(v));
+    return r;
+}
+__device__ __forceinline__ uint32_t vgpr_const(uint32_t v)
+{
+    uint32_t r;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "i"(v));
+    return r;
+}
 
-// LDS layout of the fast kernel
-constexpr int kLdsQerr8 = 0;        // u8 [32 bins][32 dialects]
-constexpr int kLdsNibLo = 1024;     // u8 [32 dialects][32 bins]: index
-constexpr int kLdsNibHi = 2048;     // u8 [32 dialects][32 bins]: index << 4
-constexpr int kLdsFastBytes = 3072;
+// LDS layout of the fast kernel (bytes)
+constexpr int kLdsRows = 0;              // [32 bins][2 halves][8 copies][16 B]   8 KiB
+constexpr int kLdsPair = 8192;           // [32 hi bins][32 lo bins][32 dialects] 32 KiB
+constexpr int kLdsNibT = 8192 + 32768;   // [32 bins][32 dialects]                1 KiB
+constexpr int kLdsFastBytes = kLdsNibT + 1024;
 
-// Plain per-element routine for one block, any input (Sec. 3.1-3.2); reads the
-// block again from global memory.  Same arithmetic as the generic kernel.
 struct BlockCodes {
     uint32_t code[4];
     uint32_t meta;
 };
 
+// Plain per-element routine for one block, any input (Sec. 3.1-3.2); reads the
+// block again from global memory.  Same arithmetic as the generic kernel.
 __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, const uint8_t* lds)
 {
     BlockCodes out;
@@ -95,7 +128,7 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         uint32_t g = 0;
-#pragma unroll
+#pragma unroll 1
         for (int i = 0; i < 4; ++i) g = max(g, bin_of(xb[4 * j + i]));
         gbin[j] = g;
     }
@@ -104,7 +137,7 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
     for (uint32_t d = 0; d < 32; ++d) {
         uint32_t s = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) s += lds[kLdsQerr8 + gbin[j] * 32 + d];
+        for (int j = 0; j < 8; ++j) s += lds[kLdsRows + gbin[j] * 256 + (d >> 4) * 128 + (d & 15)];
         best = min(best, (s << 5) | d);
     }
     const uint32_t did = best & 31u;
@@ -114,7 +147,7 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
 #pragma unroll 1
         for (int i = 0; i < 8; ++i) {
             uint32_t h = xb[8 * c + i];
-            uint32_t nib = lds[kLdsNibLo + did * 32 + bin_of(h)] | ((h >> 15) << 3);
+            uint32_t nib = lds[kLdsNibT + bin_of(h) * 32 + did] | ((h >> 15) << 3);
             v |= nib << (4 * i);
         }
         out.code[c] = v;
@@ -123,47 +156,32 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
     return out;
 }
 
-template <bool kFlat>
-__global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams p)
-{
-    __shared__ __align__(16) uint8_t lds[kLdsFastBytes];
-    {
-        // Qerror rows as they are; Qvalue nibbles in two variants (low / high nibble position)
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(p.blob + kOffQerror8);
-        reinterpret_cast<uint32_t*>(lds + kLdsQerr8)[threadIdx.x] = src[threadIdx.x];   // 256 x 4 B
-        const int d = threadIdx.x >> 3, b4 = (threadIdx.x & 7) * 4;                      // 4 bins per thread
-        const uint32_t v = *reinterpret_cast<const uint32_t*>(p.blob + kOffQvalue64 + d * 64 + b4);
-        *reinterpret_cast<uint32_t*>(lds + kLdsNibLo + d * 32 + b4) = v;
-        *reinterpret_cast<uint32_t*>(lds + kLdsNibHi + d * 32 + b4) = v << 4;
-        __syncthreads();
-    }
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t stride = gridDim.x * kFastWaves;
+struct TileConsts {
+    uint32_t k7f, k80, kpair, row_base;
+    uint32_t kdid[16];   // DID pairs of the 16 key registers: (4i, 4i+2) and (4i+1, 4i+3)
+};
 
-    // DID constants of the 16 key registers: register 2i holds dialects (4i, 4i+2), 2i+1 holds (4i+1, 4i+3)
-    for (uint32_t t = blockIdx.x * kFastWaves + wave; t < p.n_tiles; t += stride) {
-        const uint32_t gb = t * 64u + lane;
-        const bool valid = gb < p.n_blocks;
-        long long xoff;
-        if (kFlat) {
-            xoff = (long long)gb * 32;
-        } else {
-            const uint32_t row = (uint32_t)(((unsigned long long)gb * p.div_mul) >> p.div_shift);
-            xoff = (long long)row * p.row_stride + (long long)(gb - row * p.nb) * 32;
-        }
-        uint32_t w[16];
-        {
-            uint4 q0 = make_uint4(0, 0, 0, 0), q1 = q0, q2 = q0, q3 = q0;
-            if (valid) {
-                const uint4* px = reinterpret_cast<const uint4*>(p.x + xoff);
-                q0 = px[0]; q1 = px[1]; q2 = px[2]; q3 = px[3];
-            }
-            w[0] = q0.x; w[1] = q0.y; w[2] = q0.z; w[3] = q0.w;
-            w[4] = q1.x; w[5] = q1.y; w[6] = q1.z; w[7] = q1.w;
-            w[8] = q2.x; w[9] = q2.y; w[10] = q2.z; w[11] = q2.w;
-            w[12] = q3.x; w[13] = q3.y; w[14] = q3.z; w[15] = q3.w;
-        }
+__device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane)
+{
+    TileConsts K;
+    K.row_base = kLdsRows + (lane & 7u) * 16u;
+    K.k7f = sgpr_const(0x007F007Fu);
+    K.k80 = vgpr_const(0x00800080u);
+    K.kpair = sgpr_const(32u | (1024u << 16));   // lo bin * 32 + hi bin * 1024
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        K.kdid[2 * i] = sgpr_const((4u * i) | ((4u * i + 2u) << 16));
+        K.kdid[2 * i + 1] = sgpr_const((4u * i + 1u) | ((4u * i + 3u) << 16));
+    }
+    return K;
+}
+
+// One block per lane: w = its 32 bf16 as 16 packed pairs.  Produces the four code words and the metadata
+// word.  xb / in_range are only used by the plain per-element routine of a tile with special values.
+template <bool kPair>
+__device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint8_t* lds, const TileConsts& K,
+                                             const uint16_t* xb, bool in_range, uint32_t (&code)[4], uint32_t& meta)
+{
         // ---- magnitudes and maxima (bf16 bit patterns order like the values)
         uint32_t a[16];
 #pragma unroll
@@ -175,13 +193,12 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
                                               pk_max(pk_max(gm[4], gm[5]), pk_max(gm[6], gm[7]))));
         const bool special = !(bm == 0u || (bm - 0x0280u) < (0x7F80u - 0x0280u));
 
-        uint32_t code[4], meta;
         if (__builtin_amdgcn_ballot_w64(special) != 0) {
             // rare: some block of this tile holds NaN / Inf or is tiny
             code[0] = code[1] = code[2] = code[3] = 0;
             meta = 0;
-            if (valid) {
-                const BlockCodes r = quantize_block_plain(p.x + xoff, lds);
+            if (in_range) {
+                const BlockCodes r = quantize_block_plain(xb, lds);
                 code[0] = r.code[0]; code[1] = r.code[1]; code[2] = r.code[2]; code[3] = r.code[3];
                 meta = r.meta;
             }
@@ -195,7 +212,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
             for (int k = 0; k < 16; ++k) {
                 const uint32_t ef = pk_shr(a[k], 0x00070007u);                 // exponent fields
                 const uint32_t sh = pk_min(pk_sub(ec, ef), 0x000F000Fu);       // >= 3; >= 8 means bin 0
-                const uint32_t sig = (a[k] & 0x007F007Fu) | 0x00800080u;       // 1.m as 8-bit integers
+                const uint32_t sig = (a[k] & K.k7f) | K.k80;                       // 1.m as 8-bit integers
                 b2[k] = pk_shr(sig, sh);                                       // floor(2*xhat), 0..31
             }
             // ---- group-wise maxima: group j = elements 4j..4j+3 = registers 2j, 2j+1
@@ -203,8 +220,9 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const uint32_t gbin = halves_max(pk_max(b2[2 * j], b2[2 * j + 1]));
-                const uint4* row = reinterpret_cast<const uint4*>(lds + kLdsQerr8 + (gbin << 5));
-                const uint4 r0 = row[0], r1 = row[1];
+                const uint8_t* row = lds + K.row_base + (gbin << 8);
+                const uint4 r0 = *reinterpret_cast<const uint4*>(row);
+                const uint4 r1 = *reinterpret_cast<const uint4*>(row + 128);
                 acc[0] += r0.x; acc[1] += r0.y; acc[2] += r0.z; acc[3] += r0.w;
                 acc[4] += r1.x; acc[5] += r1.y; acc[6] += r1.z; acc[7] += r1.w;
             }
@@ -212,23 +230,28 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
             uint32_t best = 0xFFFFFFFFu;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const uint32_t ev = acc[i] & 0x00FF00FFu;                         // dialects 4i, 4i+2
+                const uint32_t ev = acc[i] & 0x00FF00FFu;                             // dialects 4i, 4i+2
                 const uint32_t od = __builtin_amdgcn_perm(0u, acc[i], 0x0C030C01u);   // dialects 4i+1, 4i+3
-                const uint32_t ke = (ev << 5) | ((4u * i) | ((4u * i + 2u) << 16));
-                const uint32_t ko = (od << 5) | ((4u * i + 1u) | ((4u * i + 3u) << 16));
+                const uint32_t ke = (ev << 5) | K.kdid[2 * i];
+                const uint32_t ko = (od << 5) | K.kdid[2 * i + 1];
                 best = pk_min(best, pk_min(ke, ko));
             }
             const uint32_t did = halves_min(best) & 31u;
             meta = did | (eb << 8);
             // ---- emit: every element through Qvalue of the chosen dialect
-            const uint32_t qlo = kLdsNibLo + did * 32u, qhi = kLdsNibHi + did * 32u;
+            const uint32_t pbase = (kPair ? kLdsPair : kLdsNibT) + did;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 uint32_t byte[4];
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
-                    const uint32_t bb = b2[4 * c + m];
-                    byte[m] = (uint32_t)lds[qlo + (bb & 0xFFFFu)] | (uint32_t)lds[qhi + (bb >> 16)];
+                    if (kPair) {
+                        // two elements per lookup through the pair table
+                        byte[m] = lds[dot2_u16(b2[4 * c + m], K.kpair, pbase)];
+                    } else {
+                        const uint32_t bb = b2[4 * c + m] << 5;      // bin * 32 in both halves
+                        byte[m] = (uint32_t)lds[pbase + (bb & 0xFFFFu)] | ((uint32_t)lds[pbase + (bb >> 16)] << 4);
+                    }
                 }
                 uint32_t v = byte[0] | (byte[1] << 8) | (byte[2] << 16) | (byte[3] << 24);
                 // sign bits: element 2m -> bit 8m+3, element 2m+1 -> bit 8m+7
@@ -240,11 +263,129 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
                 code[c] = v;
             }
         }
-        if (valid) {
-            *reinterpret_cast<uint4*>(p.codes + (size_t)gb * 16) = make_uint4(code[0], code[1], code[2], code[3]);
-            p.meta[gb] = (uint16_t)meta;
-        }
+}
+
+// Address of block gb's first element, in elements from p.x.
+template <bool kFlat>
+__device__ __forceinline__ long long block_offset(const FastParams& p, uint32_t gb)
+{
+    if (kFlat) return (long long)gb * 32;
+    const uint32_t row = (uint32_t)(((unsigned long long)gb * p.div_mul) >> p.div_shift);
+    return (long long)row * p.row_stride + (long long)(gb - row * p.nb) * 32;
+}
+
+struct Block64 {   // one block: 32 bf16 = four 16-byte loads
+    uint4 q0, q1, q2, q3;
+};
+
+template <bool kFlat>
+__device__ __forceinline__ Block64 load_block(const FastParams& p, uint32_t gb)
+{
+    Block64 b;
+    b.q0 = b.q1 = b.q2 = b.q3 = make_uint4(0, 0, 0, 0);
+    if (gb < p.n_blocks) {
+        const uint4* px = reinterpret_cast<const uint4*>(p.x + block_offset<kFlat>(p, gb));
+        b.q0 = px[0]; b.q1 = px[1]; b.q2 = px[2]; b.q3 = px[3];
     }
+    return b;
+}
+
+// Writes one tile's results: 16 bytes of codes per lane and the 16-bit metadata words.  When the whole
+// tile is in range and the metadata array is 16-byte aligned, eight neighbouring lanes gather their
+// metadata into one 16-byte store (sub-dword stores are slow to coalesce).
+__device__ __forceinline__ void store_tile(const FastParams& p, uint32_t gb, uint32_t lane, const uint4& code,
+                                           uint32_t meta, bool meta_aligned)
+{
+    const uint32_t tile_first = gb - lane;   // wave-uniform
+    if (meta_aligned && tile_first + 64u <= p.n_blocks) {
+        *reinterpret_cast<uint4*>(p.codes + (size_t)gb * 16) = code;
+        const uint32_t m = meta & 0xFFFFu;
+        const uint32_t m1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x101, 0xF, 0xF, true);    // lane i <- i+1
+        const uint32_t p2 = m | (m1 << 16);
+        const uint32_t q2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)p2, 0x102, 0xF, 0xF, true);   // lane i <- i+2
+        const uint32_t r0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)p2, 0x104, 0xF, 0xF, true);   // lane i <- i+4
+        const uint32_t r1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)q2, 0x104, 0xF, 0xF, true);
+        if ((lane & 7u) == 0u) *reinterpret_cast<uint4*>(p.meta + gb) = make_uint4(p2, q2, r0, r1);
+    } else if (gb < p.n_blocks) {
+        *reinterpret_cast<uint4*>(p.codes + (size_t)gb * 16) = code;
+        p.meta[gb] = (uint16_t)meta;
+    }
+}
+
+template <bool kFlat>
+__global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams p)
+{
+    __shared__ __align__(16) uint8_t lds[kLdsFastBytes];
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // Tiles of workgroup b are b, b + G, b + 2G, ... (G = number of workgroups).  The waves of a workgroup
+    // take them from a shared counter as they become free, so a wave that runs ahead of its neighbours
+    // keeps working instead of idling at the end.
+    __shared__ uint32_t wg_next;
+    const uint32_t G = gridDim.x;
+    Block64 cur;
+    uint32_t t = blockIdx.x + wave * G;                      // first tile: static
+    uint32_t t_next = blockIdx.x + (kFastWaves + wave) * G;   // second tile: static
+    if (threadIdx.x == 0) wg_next = 2 * kFastWaves;
+    // the first tile is requested before anything else: it streams in while the tables are built
+    cur = load_block<kFlat>(p, t * 64u + lane);
+    {
+        static_assert(kFastThreads >= 512, "one 16-byte Qerror piece and at most one Qvalue word per thread");
+        const int bin = threadIdx.x >> 4, half = (threadIdx.x >> 3) & 1;
+        uint4 rq = make_uint4(0, 0, 0, 0);
+        uint32_t nq = 0;
+        if (threadIdx.x < 512) rq = *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
+        if (threadIdx.x < 256) nq = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[threadIdx.x];
+        if (threadIdx.x < 512) reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x] = rq;   // eight bank-disjoint copies
+        if (threadIdx.x < 256) reinterpret_cast<uint32_t*>(lds + kLdsNibT)[threadIdx.x] = nq;
+        __syncthreads();
+        // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
+        for (int i = threadIdx.x; i < 1024; i += kFastThreads) {
+            const int hi = i >> 5, lo = i & 31;
+            const uint4* rl = reinterpret_cast<const uint4*>(lds + kLdsNibT + lo * 32);
+            const uint4* rh = reinterpret_cast<const uint4*>(lds + kLdsNibT + hi * 32);
+            uint4* dst = reinterpret_cast<uint4*>(lds + kLdsPair + i * 32);
+            const uint4 l0 = rl[0], l1 = rl[1], h0 = rh[0], h1 = rh[1];
+            dst[0] = make_uint4(l0.x | (h0.x << 4), l0.y | (h0.y << 4), l0.z | (h0.z << 4), l0.w | (h0.w << 4));
+            dst[1] = make_uint4(l1.x | (h1.x << 4), l1.y | (h1.y << 4), l1.z | (h1.z << 4), l1.w | (h1.w << 4));
+        }
+        __syncthreads();
+    }
+    const TileConsts K = make_tile_consts(lane);
+
+    // Results of a tile are held in registers and written at the top of the next iteration, right after
+    // that iteration's input has arrived: memory operations retire in issue order, so a store issued just
+    // before the wait for the next input would stall the wavefront for the whole write latency.
+    uint4 held_code = make_uint4(0, 0, 0, 0);
+    uint32_t held_meta = 0, held_gb = 0;
+    bool have_held = false;   // wave-uniform
+    const bool meta_aligned = (reinterpret_cast<uintptr_t>(p.meta) & 15u) == 0;
+
+    while (t < p.n_tiles) {
+        const uint32_t gb = t * 64u + lane;
+        uint32_t w[16];
+        w[0] = cur.q0.x; w[1] = cur.q0.y; w[2] = cur.q0.z; w[3] = cur.q0.w;
+        w[4] = cur.q1.x; w[5] = cur.q1.y; w[6] = cur.q1.z; w[7] = cur.q1.w;
+        w[8] = cur.q2.x; w[9] = cur.q2.y; w[10] = cur.q2.z; w[11] = cur.q2.w;
+        w[12] = cur.q3.x; w[13] = cur.q3.y; w[14] = cur.q3.z; w[15] = cur.q3.w;
+        // the previous tile's stores must not be scheduled above the arrival of this tile's input
+        asm volatile("" : "+v"(held_meta) : "v"(w[0]), "v"(w[15]));
+        if (have_held) store_tile(p, held_gb, lane, held_code, held_meta, meta_aligned);
+        have_held = true;
+        // the next tile's loads go out before this tile's arithmetic
+        cur = load_block<kFlat>(p, (t_next < p.n_tiles) ? t_next * 64u + lane : 0xFFFFFFFFu);
+        uint32_t claim = 0;
+        if (lane == 0) claim = atomicAdd(&wg_next, 1u);
+        const uint32_t t_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * G;
+        uint32_t code[4], meta;
+        compute_tile<true>(w, lds, K, p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u), gb < p.n_blocks, code, meta);
+        held_code = make_uint4(code[0], code[1], code[2], code[3]);
+        held_meta = meta;
+        held_gb = gb;
+        t = t_next;
+        t_next = t_after;
+    }
+    if (have_held) store_tile(p, held_gb, lane, held_code, held_meta, meta_aligned);
 }
 
 }  // namespace fb4

@@ -20,7 +20,8 @@ constexpr size_t kOffGain16 = 7168;    // u16 [32 bins][32 dialects]
 constexpr size_t kOffDecode = 9216;    // u16 [32 dialects][8]
 constexpr size_t kOffTop = 9728;       // u8  [32]
 constexpr size_t kOffCount = 9760;     // i32
-constexpr size_t kBlobBytes = 9792;
+constexpr size_t kOffQvalueT = 9792;   // u8  [32 bins][32 dialects]: 3-bit index, bin-major
+constexpr size_t kBlobBytes = 10816;
 
 // A formatbook row is valid when its magnitudes ascend strictly from 0 and its
 // largest one lies in 8..15: one dynamic range per integer block maximum
@@ -57,6 +58,7 @@ inline void build_blob(const uint8_t* fbk, int n, uint8_t* blob)
     uint16_t* gain16 = reinterpret_cast<uint16_t*>(blob + kOffGain16);
     uint16_t* decode = reinterpret_cast<uint16_t*>(blob + kOffDecode);
     uint8_t* top = blob + kOffTop;
+    uint8_t* qvalT = blob + kOffQvalueT;
     for (int d = 0; d < kMaxDialects; ++d) {
         if (d >= n) {
             // A dialect that does not exist must never be selected: worst
@@ -91,6 +93,7 @@ inline void build_blob(const uint8_t* fbk, int n, uint8_t* blob)
             // because 0 is a magnitude of every dialect.
             gain16[b * 32 + d] = (uint16_t)(mag * (b - mag));
             qval[d * 64 + b] = (uint8_t)idx;
+            qvalT[b * 32 + d] = (uint8_t)idx;
             qval[d * 64 + 32 + b] = (uint8_t)(8 | idx);
         }
     }

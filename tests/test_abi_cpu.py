@@ -56,6 +56,7 @@ def _blob_views(blob):
     v["decode"] = blob[9216:9728].view(np.uint16).reshape(32, 8)
     v["top"] = blob[9728:9760]
     v["n"] = int(blob[9760:9764].view(np.int32)[0])
+    v["qvalT"] = blob[9792:10816].reshape(32, 32)
     return v
 
 
@@ -98,6 +99,7 @@ def test_qvalue_table_equals_oracle_rounding_on_bin_edges_and_midpoints():
         assert np.array_equal(v["qerr16"][:, d], 32 * v["qerr8"][:, d].astype(int))
         assert np.array_equal(v["gain16"][:, d], mag * (np.arange(32) - mag))
         assert v["top"][d] == DEFAULT_FORMATBOOK[d, 7]
+        assert np.array_equal(v["qvalT"][:, d], v["qval"][d, :32])
         dec = (v["decode"][d].astype(np.uint32) << 16).view(np.float32)
         assert np.array_equal(dec, DEFAULT_FORMATBOOK[d].astype(np.float32))
 
