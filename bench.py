@@ -23,6 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the headline kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the
+# same counter reads for a plain copy of known size (profiles/quantize_lut8_cfg2_traffic.md): 98,399 KiB read
+# (counter x 1.9995) + 27,648 KiB written (counter x 1.0).
+MEASURED_TRAFFIC_BYTES = 129072230
 ROWS, COLS, BLOCK = 16384, 3072, 32
 N_SETS = 6
 
@@ -84,6 +88,9 @@ def main():
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of one HIP graph")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: a few plain device copies of known size, "
+                         "then a few quantize launches; prints nothing but a marker line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -107,6 +114,20 @@ def main():
     metas = [torch.empty((ROWS, COLS // BLOCK), dtype=torch.int16, device="cuda") for _ in range(N_SETS)]
     n_el = ROWS * COLS
     abytes = algorithmic_bytes(ROWS, COLS)
+
+    if args.traffic_probe:
+        # plain copy kernel of known size: reads 100,663,296 B and writes 100,663,296 B per launch
+        dst = torch.empty_like(x0)
+        o = F.opts(block=BLOCK, selector=F.SEL_LUT, num_groups=8)
+        for i in range(10):
+            dst.copy_(xs[i % N_SETS])
+        for i in range(10):
+            F.fb4_quantize(luts, o, xs[i % N_SETS], codes=codes[i % N_SETS], meta=metas[i % N_SETS])
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "copy_bytes_read": x0.numel() * 2, "copy_bytes_written": x0.numel() * 2,
+                          "quantize_algorithmic_bytes": abytes}))
+        luts.free()
+        return
 
     def quant_step(o):
         def f(i):
@@ -141,8 +162,8 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
-            "kernel": "quantize_kernel<LUT,8,plain>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
+            "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+            "kernel": "fb4::quantize_lut8_kernel<true>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
         },
     }
 
