@@ -298,14 +298,18 @@ __device__ __forceinline__ void store_tile(const FastParams& p, uint32_t gb, uin
 {
     const uint32_t tile_first = gb - lane;   // wave-uniform
     if (meta_aligned && tile_first + 64u <= p.n_blocks) {
-        *reinterpret_cast<uint4*>(p.codes + (size_t)gb * 16) = code;
+        // results are written once and not read again by this kernel: streaming (non-temporal) stores
+        typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+        const u32x4s cv = {code.x, code.y, code.z, code.w};
+        __builtin_nontemporal_store(cv, reinterpret_cast<u32x4s*>(p.codes + (size_t)gb * 16));
         const uint32_t m = meta & 0xFFFFu;
         const uint32_t m1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x101, 0xF, 0xF, true);    // lane i <- i+1
         const uint32_t p2 = m | (m1 << 16);
         const uint32_t q2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)p2, 0x102, 0xF, 0xF, true);   // lane i <- i+2
         const uint32_t r0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)p2, 0x104, 0xF, 0xF, true);   // lane i <- i+4
         const uint32_t r1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)q2, 0x104, 0xF, 0xF, true);
-        if ((lane & 7u) == 0u) *reinterpret_cast<uint4*>(p.meta + gb) = make_uint4(p2, q2, r0, r1);
+        const u32x4s mv = {p2, q2, r0, r1};
+        if ((lane & 7u) == 0u) __builtin_nontemporal_store(mv, reinterpret_cast<u32x4s*>(p.meta + gb));
     } else if (gb < p.n_blocks) {
         *reinterpret_cast<uint4*>(p.codes + (size_t)gb * 16) = code;
         p.meta[gb] = (uint16_t)meta;
