@@ -112,7 +112,8 @@ int fb4_build_luts(const uint8_t* formatbook, int n_dialects, fb4_luts** out);
  *   9728  top      uint8  [32]                     largest magnitude of the dialect
  *   9760  n_dialects int32, then padding to 9792
  *   9792  qvalueT  uint8  [32 bins][32 dialects]   bin -> 3-bit index, bin-major copy of Qvalue
- * Total 10816 bytes.
+ *  10816  range_excl uint8 [8 ranges][32 dialects]  two-stage filter: 0xFF = largest magnitude != 8 + range
+ * Total 11072 bytes.
  * Entries of dialects >= n_dialects are filled so that they never win.
  */
 int fb4_build_luts_host(const uint8_t* formatbook, int n_dialects, void* blob, size_t capacity,

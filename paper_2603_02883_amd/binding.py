@@ -26,7 +26,7 @@ FLAG_TWO_STAGE = 1
 DTYPE_BF16 = 0
 DTYPE_F32 = 1
 
-BLOB_BYTES = 10816
+BLOB_BYTES = 11072
 
 
 class Fb4Error(RuntimeError):

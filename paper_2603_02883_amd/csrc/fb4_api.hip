@@ -7,6 +7,7 @@
 #include <new>
 
 #include "../../include/fb4.h"
+#include "fb4_dequant_fast.hpp"
 #include "fb4_fast.hpp"
 #include "fb4_kernels.hpp"
 #include "fb4_tables.hpp"
@@ -69,6 +70,57 @@ int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& 
         launch_ts<kSelLut, 32, MODE>(ts, grid, s, p);
     }
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+template <bool kTwoStage, bool kSeda>
+void launch_fast_variant(bool flat, unsigned groups, hipStream_t s, const FastParams& f)
+{
+    if (flat)
+        hipLaunchKernelGGL((quantize_lut8_kernel<true, kTwoStage, kSeda>), dim3(groups), dim3(kFastThreads), 0, s, f);
+    else
+        hipLaunchKernelGGL((quantize_lut8_kernel<false, kTwoStage, kSeda>), dim3(groups), dim3(kFastThreads), 0, s, f);
+}
+
+// The streaming kernel serves the paper's default online configuration (LUT selector, 8 groups, block 32),
+// with or without the two-stage filter and SeDA lists.  Returns false if the request is not one it serves.
+bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& p, int64_t cols,
+                 const int32_t* token_group, const uint8_t* sub, int n_groups, hipStream_t s, int* rc)
+{
+    if (opts->selector != FB4_SEL_LUT || opts->num_groups != 8 || !aligned(p.codes, 16)) return false;
+    const uint64_t n_blocks = (uint64_t)p.rows * (uint64_t)p.nb;
+    if (n_blocks >= 0x7FFFFF00ull) return false;
+    if (token_group && (uint32_t)n_groups > kMaxFastGroups) return false;
+    FastParams f = {};
+    f.x = p.x;
+    f.row_stride = p.row_stride;
+    f.nb = (uint32_t)p.nb;
+    f.n_blocks = (uint32_t)n_blocks;
+    f.n_tiles = (uint32_t)((n_blocks + 63) / 64);
+    uint32_t l = 0;
+    while ((1ull << l) < (uint64_t)p.nb) ++l;
+    f.div_shift = 31 + l;
+    f.div_mul = (uint32_t)(((1ull << f.div_shift) + (uint64_t)p.nb - 1) / (uint64_t)p.nb);
+    f.codes = p.codes;
+    f.meta = p.meta;
+    f.blob = luts->dev_blob;
+    f.token_group = token_group;
+    f.sub = sub;
+    f.n_groups = (uint32_t)n_groups;
+    f.n_dialects = (uint32_t)luts->n_dialects;
+    long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
+    const long long cap = (long long)luts->n_cu * FB4_FAST_GROUPS_PER_CU;
+    if (groups > cap) groups = cap;
+    const bool flat = p.row_stride == cols;
+    const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
+    if (token_group) {
+        if (ts) launch_fast_variant<true, true>(flat, (unsigned)groups, s, f);
+        else launch_fast_variant<false, true>(flat, (unsigned)groups, s, f);
+    } else {
+        if (ts) launch_fast_variant<true, false>(flat, (unsigned)groups, s, f);
+        else launch_fast_variant<false, false>(flat, (unsigned)groups, s, f);
+    }
+    *rc = hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+    return true;
 }
 
 // Shared validation of the tensor arguments of the three quantizing calls.
@@ -180,33 +232,7 @@ int fb4_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int6
     p.blob = luts->dev_blob;
     p.n_dialects = luts->n_dialects;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (opts->selector == FB4_SEL_LUT && opts->num_groups == 8 && opts->flags == 0 && aligned(codes, 16)) {
-        // the paper's default online configuration: one lane per block, packed 16-bit path
-        FastParams f = {};
-        const uint64_t n_blocks = (uint64_t)rows * (uint64_t)p.nb;
-        if (n_blocks < 0x7FFFFF00ull) {
-            f.x = p.x;
-            f.row_stride = row_stride;
-            f.nb = (uint32_t)p.nb;
-            f.n_blocks = (uint32_t)n_blocks;
-            f.n_tiles = (uint32_t)((n_blocks + 63) / 64);
-            uint32_t l = 0;
-            while ((1ull << l) < (uint64_t)p.nb) ++l;
-            f.div_shift = 31 + l;
-            f.div_mul = (uint32_t)(((1ull << f.div_shift) + (uint64_t)p.nb - 1) / (uint64_t)p.nb);
-            f.codes = codes;
-            f.meta = meta;
-            f.blob = luts->dev_blob;
-            long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
-            const long long cap = (long long)luts->n_cu * FB4_FAST_GROUPS_PER_CU;
-            if (groups > cap) groups = cap;
-            if (row_stride == cols)
-                hipLaunchKernelGGL((quantize_lut8_kernel<true>), dim3((unsigned)groups), dim3(kFastThreads), 0, s, f);
-            else
-                hipLaunchKernelGGL((quantize_lut8_kernel<false>), dim3((unsigned)groups), dim3(kFastThreads), 0, s, f);
-            return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
-        }
-    }
+    if (launch_fast(luts, opts, p, cols, nullptr, nullptr, 0, s, &rc)) return rc;
     return launch_quant<kPlain>(opts, grid_for(luts, p.n_tiles), s, p);
 }
 
@@ -232,6 +258,8 @@ int fb4_quantize_seda(const fb4_luts* luts, const fb4_opts* opts, const void* x,
     p.n_groups = n_groups;
     p.blob = luts->dev_blob;
     p.n_dialects = luts->n_dialects;
+    if (launch_fast(luts, opts, p, cols, token_group, sub_formatbooks, n_groups, static_cast<hipStream_t>(stream), &rc))
+        return rc;
     return launch_quant<kSeda>(opts, grid_for(luts, p.n_tiles), static_cast<hipStream_t>(stream), p);
 }
 
@@ -297,10 +325,38 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
     p.out_row_stride = out_row_stride;
     p.blob = luts->dev_blob;
     int grid = grid_for(luts, p.n_tiles);
-    if (out_dtype == FB4_DTYPE_F32)
+    const uint64_t n_blocks = (uint64_t)rows * (uint64_t)p.nb;
+    if (aligned(codes1, 16) && aligned(out, 16) && n_blocks < 0x3FFFFF00ull) {
+        // plane 1 of every row: one lane per block, pair table in LDS
+        DeqFastParams f = {};
+        f.codes = codes1;
+        f.meta = meta1;
+        f.out = out;
+        f.out_row_stride = out_row_stride;
+        f.nb = (uint32_t)p.nb;
+        f.n_blocks = (uint32_t)n_blocks;
+        f.n_tiles = (uint32_t)((n_blocks + 63) / 64);
+        uint32_t l = 0;
+        while ((1ull << l) < (uint64_t)p.nb) ++l;
+        f.div_shift = 31 + l;
+        f.div_mul = (uint32_t)(((1ull << f.div_shift) + (uint64_t)p.nb - 1) / (uint64_t)p.nb);
+        f.blob = luts->dev_blob;
+        long long groups = ((long long)f.n_tiles + kDeqWaves - 1) / kDeqWaves;
+        const long long cap = (long long)luts->n_cu * 2;
+        if (groups > cap) groups = cap;
+        const bool flat = out_row_stride == cols;
+        if (out_dtype == FB4_DTYPE_F32) {
+            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, true>), dim3((unsigned)groups), dim3(kDeqThreads), 0, s, f);
+            else hipLaunchKernelGGL((dequantize_fast_kernel<false, true>), dim3((unsigned)groups), dim3(kDeqThreads), 0, s, f);
+        } else {
+            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, false>), dim3((unsigned)groups), dim3(kDeqThreads), 0, s, f);
+            else hipLaunchKernelGGL((dequantize_fast_kernel<false, false>), dim3((unsigned)groups), dim3(kDeqThreads), 0, s, f);
+        }
+    } else if (out_dtype == FB4_DTYPE_F32) {
         hipLaunchKernelGGL((dequantize_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p);
-    else
+    } else {
         hipLaunchKernelGGL((dequantize_kernel<false, false>), dim3(grid), dim3(kThreads), 0, s, p);
+    }
     if (hipGetLastError() != hipSuccess) return FB4_ERR_HIP;
     if (n_sal > 0) {
         // second pass, ordered after the first on the same stream: salient rows = plane 1 + plane 2

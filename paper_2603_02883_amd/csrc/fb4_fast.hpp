@@ -48,7 +48,13 @@ struct FastParams {
     uint8_t* codes;
     uint16_t* meta;
     const uint8_t* blob;
+    const int32_t* token_group;   // SeDA: [rows] or null
+    const uint8_t* sub;           // SeDA: [n_groups][8] DIDs
+    uint32_t n_groups;            // SeDA: <= kMaxFastGroups
+    uint32_t n_dialects;
 };
+
+constexpr uint32_t kMaxFastGroups = 1023;   // SeDA groups whose exclusion rows fit the workgroup's LDS
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
@@ -96,7 +102,10 @@ __device__ __forceinline__ uint32_t vgpr_const(uint32_t v)
 constexpr int kLdsRows = 0;              // [32 bins][2 halves][8 copies][16 B]   8 KiB
 constexpr int kLdsPair = 8192;           // [32 hi bins][32 lo bins][32 dialects] 32 KiB
 constexpr int kLdsNibT = 8192 + 32768;   // [32 bins][32 dialects]                1 KiB
-constexpr int kLdsFastBytes = kLdsNibT + 1024;
+constexpr int kLdsRange = kLdsNibT + 1024;   // two-stage: [8 ranges][32 B] 0xFF = dialect excluded
+constexpr int kLdsSeda = kLdsRange + 256;    // SeDA: [n_groups + 1][32 B] 0xFF = dialect excluded; last row: none
+constexpr int kLdsFastBytes = kLdsSeda;      // without SeDA
+constexpr int kLdsFastBytesSeda = kLdsSeda + (kMaxFastGroups + 1) * 32;
 
 struct BlockCodes {
     uint32_t code[4];
@@ -105,7 +114,10 @@ struct BlockCodes {
 
 // Plain per-element routine for one block, any input (Sec. 3.1-3.2); reads the
 // block again from global memory.  Same arithmetic as the generic kernel.
-__device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, const uint8_t* lds)
+// excl_a / excl_b: LDS offsets of 32-byte exclusion rows (0xFF = excluded), or 0xFFFFFFFF for none.  A dialect
+// excluded by excl_a never wins; excl_b (the two-stage range filter) applies only if it leaves a candidate.
+__device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, const uint8_t* lds, uint32_t excl_a,
+                                                        bool two_stage)
 {
     BlockCodes out;
     uint32_t amax = 0;
@@ -132,14 +144,21 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
         for (int i = 0; i < 4; ++i) g = max(g, bin_of(xb[4 * j + i]));
         gbin[j] = g;
     }
-    uint32_t best = 0xFFFFFFFFu;
+    uint32_t bmax = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) bmax = max(bmax, gbin[j]);
+    const uint32_t excl_b = kLdsRange + (min(max(bmax >> 1, 8u), 15u) - 8u) * 32u;
+    uint32_t best = 0xFFFFFFFFu, best_b = 0xFFFFFFFFu;
 #pragma unroll 1
     for (uint32_t d = 0; d < 32; ++d) {
+        if (excl_a != 0xFFFFFFFFu && lds[excl_a + d]) continue;
         uint32_t s = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) s += lds[kLdsRows + gbin[j] * 256 + (d >> 4) * 128 + (d & 15)];
         best = min(best, (s << 5) | d);
+        if (two_stage && !lds[excl_b + d]) best_b = min(best_b, (s << 5) | d);
     }
+    if (best_b != 0xFFFFFFFFu) best = best_b;
     const uint32_t did = best & 31u;
 #pragma unroll 1
     for (int c = 0; c < 4; ++c) {
@@ -178,9 +197,11 @@ __device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane)
 
 // One block per lane: w = its 32 bf16 as 16 packed pairs.  Produces the four code words and the metadata
 // word.  xb / in_range are only used by the plain per-element routine of a tile with special values.
-template <bool kPair>
+// excl_a: LDS offset of this block's SeDA exclusion row (kSeda only).
+template <bool kPair, bool kTwoStage, bool kSeda>
 __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint8_t* lds, const TileConsts& K,
-                                             const uint16_t* xb, bool in_range, uint32_t (&code)[4], uint32_t& meta)
+                                             const uint16_t* xb, bool in_range, uint32_t excl_a,
+                                             uint32_t (&code)[4], uint32_t& meta)
 {
         // ---- magnitudes and maxima (bf16 bit patterns order like the values)
         uint32_t a[16];
@@ -198,7 +219,7 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
             code[0] = code[1] = code[2] = code[3] = 0;
             meta = 0;
             if (in_range) {
-                const BlockCodes r = quantize_block_plain(xb, lds);
+                const BlockCodes r = quantize_block_plain(xb, lds, kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage);
                 code[0] = r.code[0]; code[1] = r.code[1]; code[2] = r.code[2]; code[3] = r.code[3];
                 meta = r.meta;
             }
@@ -217,14 +238,41 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
             }
             // ---- group-wise maxima: group j = elements 4j..4j+3 = registers 2j, 2j+1
             uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            uint32_t binmax = 0;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const uint32_t gbin = halves_max(pk_max(b2[2 * j], b2[2 * j + 1]));
+                if (kTwoStage) binmax = max(binmax, gbin);
                 const uint8_t* row = lds + K.row_base + (gbin << 8);
                 const uint4 r0 = *reinterpret_cast<const uint4*>(row);
                 const uint4 r1 = *reinterpret_cast<const uint4*>(row + 128);
                 acc[0] += r0.x; acc[1] += r0.y; acc[2] += r0.z; acc[3] += r0.w;
                 acc[4] += r1.x; acc[5] += r1.y; acc[6] += r1.z; acc[7] += r1.w;
+            }
+            // ---- candidate restrictions (Sec. 3.4 SeDA, Sec. 3.2 two-stage): an excluded dialect gets the byte
+            // 0xFF OR-ed into its 8-bit sum, which no real sum (<= 248) reaches
+            if (kSeda || kTwoStage) {
+                uint32_t ea[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (kSeda) {
+                    const uint4 a0 = *reinterpret_cast<const uint4*>(lds + excl_a);
+                    const uint4 a1 = *reinterpret_cast<const uint4*>(lds + excl_a + 16);
+                    ea[0] = a0.x; ea[1] = a0.y; ea[2] = a0.z; ea[3] = a0.w;
+                    ea[4] = a1.x; ea[5] = a1.y; ea[6] = a1.z; ea[7] = a1.w;
+                }
+                if (kTwoStage) {
+                    // first stage: keep the dialects whose top magnitude is the integer part of the block maximum
+                    const uint32_t roff = kLdsRange + (min(max(binmax >> 1, 8u), 15u) - 8u) * 32u;
+                    const uint4 r0 = *reinterpret_cast<const uint4*>(lds + roff);
+                    const uint4 r1 = *reinterpret_cast<const uint4*>(lds + roff + 16);
+                    const uint32_t eb2[8] = {ea[0] | r0.x, ea[1] | r0.y, ea[2] | r0.z, ea[3] | r0.w,
+                                             ea[4] | r1.x, ea[5] | r1.y, ea[6] | r1.z, ea[7] | r1.w};
+                    // ... unless that leaves nothing (possible only together with a SeDA list)
+                    const bool none = kSeda && ((eb2[0] & eb2[1] & eb2[2] & eb2[3] & eb2[4] & eb2[5] & eb2[6] & eb2[7]) == 0xFFFFFFFFu);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) ea[i] = none ? ea[i] : eb2[i];
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] |= ea[i];
             }
             // ---- argmin with lowest DID on ties: 16-bit keys (sum << 5 | DID), 32 of them in 16 registers
             uint32_t best = 0xFFFFFFFFu;
@@ -274,18 +322,21 @@ __device__ __forceinline__ long long block_offset(const FastParams& p, uint32_t 
     return (long long)row * p.row_stride + (long long)(gb - row * p.nb) * 32;
 }
 
-struct Block64 {   // one block: 32 bf16 = four 16-byte loads
+struct Block64 {   // one block: 32 bf16 = four 16-byte loads, plus its row's SeDA group
     uint4 q0, q1, q2, q3;
+    int32_t grp;
 };
 
-template <bool kFlat>
+template <bool kFlat, bool kSeda>
 __device__ __forceinline__ Block64 load_block(const FastParams& p, uint32_t gb)
 {
     Block64 b;
     b.q0 = b.q1 = b.q2 = b.q3 = make_uint4(0, 0, 0, 0);
+    b.grp = -1;
     if (gb < p.n_blocks) {
         const uint4* px = reinterpret_cast<const uint4*>(p.x + block_offset<kFlat>(p, gb));
         b.q0 = px[0]; b.q1 = px[1]; b.q2 = px[2]; b.q3 = px[3];
+        if (kSeda) b.grp = p.token_group[(uint32_t)(((unsigned long long)gb * p.div_mul) >> p.div_shift)];
     }
     return b;
 }
@@ -316,10 +367,10 @@ __device__ __forceinline__ void store_tile(const FastParams& p, uint32_t gb, uin
     }
 }
 
-template <bool kFlat>
+template <bool kFlat, bool kTwoStage, bool kSeda>
 __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams p)
 {
-    __shared__ __align__(16) uint8_t lds[kLdsFastBytes];
+    __shared__ __align__(16) uint8_t lds[kSeda ? kLdsFastBytesSeda : kLdsFastBytes];
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // Tiles of workgroup b are b, b + G, b + 2G, ... (G = number of workgroups).  The waves of a workgroup
@@ -332,7 +383,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
     uint32_t t_next = blockIdx.x + (kFastWaves + wave) * G;   // second tile: static
     if (threadIdx.x == 0) wg_next = 2 * kFastWaves;
     // the first tile is requested before anything else: it streams in while the tables are built
-    cur = load_block<kFlat>(p, t * 64u + lane);
+    cur = load_block<kFlat, kSeda>(p, t * 64u + lane);
     {
         static_assert(kFastThreads >= 512, "one 16-byte Qerror piece and at most one Qvalue word per thread");
         const int bin = threadIdx.x >> 4, half = (threadIdx.x >> 3) & 1;
@@ -342,6 +393,33 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
         if (threadIdx.x < 256) nq = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[threadIdx.x];
         if (threadIdx.x < 512) reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x] = rq;   // eight bank-disjoint copies
         if (threadIdx.x < 256) reinterpret_cast<uint32_t*>(lds + kLdsNibT)[threadIdx.x] = nq;
+        if (kTwoStage && threadIdx.x < 64)
+            reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] =
+                reinterpret_cast<const uint32_t*>(p.blob + kOffRangeExcl)[threadIdx.x];
+        if (kSeda) {
+            // one exclusion row per group: everything excluded except the group's valid DIDs; a group without
+            // a valid DID, and the extra last row (rows outside any group), exclude nothing
+            for (uint32_t g = threadIdx.x; g <= p.n_groups; g += kFastThreads) {
+                uint32_t keep = 0;
+                if (g < p.n_groups) {
+                    const uint2 s8 = *reinterpret_cast<const uint2*>(p.sub + (size_t)g * 8);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const uint32_t d = ((k < 4 ? s8.x : s8.y) >> (8 * (k & 3))) & 0xFFu;
+                        if (d < p.n_dialects) keep |= 1u << d;
+                    }
+                }
+                uint32_t* row = reinterpret_cast<uint32_t*>(lds + kLdsSeda + g * 32);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t k4 = (keep >> (4 * i)) & 0xFu;
+                    // bit j of k4 set -> byte j 0x00, else 0xFF
+                    const uint32_t ex = ((k4 & 1u) ? 0u : 0x000000FFu) | ((k4 & 2u) ? 0u : 0x0000FF00u) |
+                                        ((k4 & 4u) ? 0u : 0x00FF0000u) | ((k4 & 8u) ? 0u : 0xFF000000u);
+                    row[i] = keep ? ex : 0u;
+                }
+            }
+        }
         __syncthreads();
         // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
         for (int i = threadIdx.x; i < 1024; i += kFastThreads) {
@@ -372,17 +450,20 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
         w[4] = cur.q1.x; w[5] = cur.q1.y; w[6] = cur.q1.z; w[7] = cur.q1.w;
         w[8] = cur.q2.x; w[9] = cur.q2.y; w[10] = cur.q2.z; w[11] = cur.q2.w;
         w[12] = cur.q3.x; w[13] = cur.q3.y; w[14] = cur.q3.z; w[15] = cur.q3.w;
+        const uint32_t excl_a =
+            kLdsSeda + 32u * ((cur.grp >= 0 && (uint32_t)cur.grp < p.n_groups) ? (uint32_t)cur.grp : p.n_groups);
         // the previous tile's stores must not be scheduled above the arrival of this tile's input
         asm volatile("" : "+v"(held_meta) : "v"(w[0]), "v"(w[15]));
         if (have_held) store_tile(p, held_gb, lane, held_code, held_meta, meta_aligned);
         have_held = true;
         // the next tile's loads go out before this tile's arithmetic
-        cur = load_block<kFlat>(p, (t_next < p.n_tiles) ? t_next * 64u + lane : 0xFFFFFFFFu);
+        cur = load_block<kFlat, kSeda>(p, (t_next < p.n_tiles) ? t_next * 64u + lane : 0xFFFFFFFFu);
         uint32_t claim = 0;
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
         const uint32_t t_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * G;
         uint32_t code[4], meta;
-        compute_tile<true>(w, lds, K, p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u), gb < p.n_blocks, code, meta);
+        compute_tile<true, kTwoStage, kSeda>(w, lds, K, p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u),
+                                             gb < p.n_blocks, excl_a, code, meta);
         held_code = make_uint4(code[0], code[1], code[2], code[3]);
         held_meta = meta;
         held_gb = gb;

@@ -21,7 +21,8 @@ constexpr size_t kOffDecode = 9216;    // u16 [32 dialects][8]
 constexpr size_t kOffTop = 9728;       // u8  [32]
 constexpr size_t kOffCount = 9760;     // i32
 constexpr size_t kOffQvalueT = 9792;   // u8  [32 bins][32 dialects]: 3-bit index, bin-major
-constexpr size_t kBlobBytes = 10816;
+constexpr size_t kOffRangeExcl = 10816;  // u8 [8 ranges][32 dialects]: 0xFF = not in that dynamic range
+constexpr size_t kBlobBytes = 11072;
 
 // A formatbook row is valid when its magnitudes ascend strictly from 0 and its
 // largest one lies in 8..15: one dynamic range per integer block maximum
@@ -96,6 +97,15 @@ inline void build_blob(const uint8_t* fbk, int n, uint8_t* blob)
             qvalT[b * 32 + d] = (uint8_t)idx;
             qval[d * 64 + 32 + b] = (uint8_t)(8 | idx);
         }
+    }
+    // Two-stage selection (Sec. 3.2): range r = 8..15 keeps the dialects whose largest magnitude is r.  A range
+    // that no dialect has keeps everything (the first stage is skipped).
+    uint8_t* rex = blob + kOffRangeExcl;
+    for (int r = 0; r < 8; ++r) {
+        bool any = false;
+        for (int d = 0; d < n; ++d) any = any || (fbk[8 * d + 7] == 8 + r);
+        for (int d = 0; d < kMaxDialects; ++d)
+            rex[r * 32 + d] = !any ? 0x00 : ((d < n && fbk[8 * d + 7] == 8 + r) ? 0x00 : 0xFF);
     }
     int32_t cnt = n;
     std::memcpy(blob + kOffCount, &cnt, 4);

@@ -57,6 +57,7 @@ def _blob_views(blob):
     v["top"] = blob[9728:9760]
     v["n"] = int(blob[9760:9764].view(np.int32)[0])
     v["qvalT"] = blob[9792:10816].reshape(32, 32)
+    v["range_excl"] = blob[10816:11072].reshape(8, 32)
     return v
 
 
@@ -120,6 +121,17 @@ def test_qerror_sum_equals_oracle_score(fbk=DEFAULT_FORMATBOOK):
             bins = np.minimum(31, np.floor(2 * gmax)).astype(int)
             table = v["qerr8"][bins, :].astype(int).sum(axis=0)
             assert np.array_equal(table, (scores * 4).astype(int))
+
+
+def test_range_exclusion_rows():
+    v = _blob_views(F.fb4_build_luts_host(DEFAULT_FORMATBOOK))
+    tops = DEFAULT_FORMATBOOK[:, 7].astype(int)
+    for r in range(8):
+        assert np.array_equal(v["range_excl"][r] == 0, tops == 8 + r)
+    v = _blob_views(F.fb4_build_luts_host(DEFAULT_FORMATBOOK[[0, 3, 9]]))      # ranges 8, 9, 11 only
+    assert (v["range_excl"][[2, 4, 5, 6, 7]] == 0).all()                        # absent range: no filter
+    assert v["range_excl"][0].tolist() == [0] + [255] * 31
+    assert v["range_excl"][3].tolist() == [255, 255, 0] + [255] * 29
 
 
 def test_unused_dialects_can_never_win():
