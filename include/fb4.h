@@ -45,7 +45,7 @@ extern "C" {
 
 #define FB4_OK 0
 #define FB4_ERR_INVALID_ARG (-1) /* null pointer, bad size, bad option, bad formatbook */
-#define FB4_ERR_UNSUPPORTED (-2) /* valid request this build cannot serve (alignment, block size) */
+#define FB4_ERR_UNSUPPORTED (-2) /* valid request this build cannot serve (alignment, ragged cols) */
 #define FB4_ERR_ALLOC (-3)       /* host or device allocation of the LUT handle failed */
 #define FB4_ERR_HIP (-4)         /* a HIP runtime call or kernel launch failed */
 
@@ -66,9 +66,10 @@ extern "C" {
 typedef struct fb4_luts fb4_luts; /* opaque, immutable after creation */
 
 typedef struct fb4_opts {
-    int32_t block;      /* 32 (16: see FB4_ERR_UNSUPPORTED)                          */
-    int32_t selector;   /* FB4_SEL_SSE or FB4_SEL_LUT                                */
-    int32_t num_groups; /* FB4_SEL_LUT only: 8, 16 or 32 groups per block (paper: 8) */
+    int32_t block;      /* 32 or 16 elements per block (Sec. 4.1 evaluates both)       */
+    int32_t selector;   /* FB4_SEL_SSE or FB4_SEL_LUT                                  */
+    int32_t num_groups; /* FB4_SEL_LUT only: 8, 16 or 32 groups per block, at most
+                           `block` (paper: 8)                                           */
     uint32_t flags;     /* FB4_FLAG_*                                                */
 } fb4_opts;
 

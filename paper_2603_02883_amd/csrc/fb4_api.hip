@@ -41,33 +41,43 @@ int check_opts(const fb4_opts* o)
     if (o->selector != FB4_SEL_SSE && o->selector != FB4_SEL_LUT) return FB4_ERR_INVALID_ARG;
     if (o->flags & ~FB4_FLAG_TWO_STAGE) return FB4_ERR_INVALID_ARG;
     if (o->block != 32 && o->block != 16) return FB4_ERR_INVALID_ARG;
-    if (o->selector == FB4_SEL_LUT && o->num_groups != 8 && o->num_groups != 16 && o->num_groups != 32)
+    if (o->selector == FB4_SEL_LUT &&
+        ((o->num_groups != 8 && o->num_groups != 16 && o->num_groups != 32) || o->num_groups > o->block))
         return FB4_ERR_INVALID_ARG;
-    if (o->block != 32) return FB4_ERR_UNSUPPORTED;
     return FB4_OK;
 }
 
-template <int SEL, int G, int MODE>
+template <int SEL, int G, int MODE, int LPB>
 void launch_ts(bool two_stage, int grid, hipStream_t s, const QuantParams& p)
 {
     if (two_stage)
-        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, true>), dim3(grid), dim3(kThreads), 0, s, p);
+        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, true, LPB>), dim3(grid), dim3(kThreads), 0, s, p);
     else
-        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, false>), dim3(grid), dim3(kThreads), 0, s, p);
+        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, false, LPB>), dim3(grid), dim3(kThreads), 0, s, p);
 }
 
 template <int MODE>
 int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& p)
 {
     const bool ts = (o->flags & FB4_FLAG_TWO_STAGE) != 0;
-    if (o->selector == FB4_SEL_SSE) {
-        launch_ts<kSelSse, 8, MODE>(ts, grid, s, p);
-    } else if (o->num_groups == 8) {
-        launch_ts<kSelLut, 8, MODE>(ts, grid, s, p);
-    } else if (o->num_groups == 16) {
-        launch_ts<kSelLut, 16, MODE>(ts, grid, s, p);
-    } else {
-        launch_ts<kSelLut, 32, MODE>(ts, grid, s, p);
+    if (o->block == 32) {
+        if (o->selector == FB4_SEL_SSE) {
+            launch_ts<kSelSse, 8, MODE, 4>(ts, grid, s, p);
+        } else if (o->num_groups == 8) {
+            launch_ts<kSelLut, 8, MODE, 4>(ts, grid, s, p);
+        } else if (o->num_groups == 16) {
+            launch_ts<kSelLut, 16, MODE, 4>(ts, grid, s, p);
+        } else {
+            launch_ts<kSelLut, 32, MODE, 4>(ts, grid, s, p);
+        }
+    } else {   // block 16: two lanes per block
+        if (o->selector == FB4_SEL_SSE) {
+            launch_ts<kSelSse, 8, MODE, 2>(ts, grid, s, p);
+        } else if (o->num_groups == 8) {
+            launch_ts<kSelLut, 8, MODE, 2>(ts, grid, s, p);
+        } else {
+            launch_ts<kSelLut, 16, MODE, 2>(ts, grid, s, p);
+        }
     }
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
@@ -86,7 +96,8 @@ void launch_fast_variant(bool flat, unsigned groups, hipStream_t s, const FastPa
 bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& p, int64_t cols,
                  const int32_t* token_group, const uint8_t* sub, int n_groups, hipStream_t s, int* rc)
 {
-    if (opts->selector != FB4_SEL_LUT || opts->num_groups != 8 || !aligned(p.codes, 16)) return false;
+    if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8 || !aligned(p.codes, 16))
+        return false;
     const uint64_t n_blocks = (uint64_t)p.rows * (uint64_t)p.nb;
     if (n_blocks >= 0x7FFFFF00ull) return false;
     if (token_group && (uint32_t)n_groups > kMaxFastGroups) return false;
@@ -142,7 +153,7 @@ int check_tensor(const fb4_luts* l, const fb4_opts* o, const void* x, int64_t ro
 bool tiling(int64_t out_rows, int64_t cols, int block, int* nb, int* tpr, int* n_tiles)
 {
     int64_t b = cols / block;
-    int64_t t = (b + kBlocksPerTile - 1) / kBlocksPerTile;
+    int64_t t = (cols + kTileElems - 1) / kTileElems;
     if (b > 0x7FFFFFFF || t * out_rows > 0x7FFFFFF0LL) return false;
     *nb = (int)b;
     *tpr = (int)t;
@@ -227,6 +238,7 @@ int fb4_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int6
     p.x = static_cast<const uint16_t*>(x);
     p.row_stride = row_stride;
     p.rows = rows;
+    p.cols = cols;
     p.codes = codes;
     p.meta = meta;
     p.blob = luts->dev_blob;
@@ -251,6 +263,7 @@ int fb4_quantize_seda(const fb4_luts* luts, const fb4_opts* opts, const void* x,
     p.x = static_cast<const uint16_t*>(x);
     p.row_stride = row_stride;
     p.rows = rows;
+    p.cols = cols;
     p.codes = codes;
     p.meta = meta;
     p.token_group = token_group;
@@ -283,6 +296,7 @@ int fb4_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int
     p.x = static_cast<const uint16_t*>(x);
     p.row_stride = row_stride;
     p.rows = rows;
+    p.cols = cols;
     p.codes = codes2;
     p.meta = meta2;
     p.token_group = token_group;
@@ -304,7 +318,7 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
     if (block != 32 && block != 16) return FB4_ERR_INVALID_ARG;
     if (out_dtype != FB4_DTYPE_BF16 && out_dtype != FB4_DTYPE_F32) return FB4_ERR_INVALID_ARG;
     if (rows < 0 || cols < 0 || n_sal < 0 || out_row_stride < cols) return FB4_ERR_INVALID_ARG;
-    if (block != 32 || cols % block) return FB4_ERR_UNSUPPORTED;
+    if (cols % block) return FB4_ERR_UNSUPPORTED;
     if (n_sal > 0 && (!codes2 || !meta2 || !salient_rows)) return FB4_ERR_INVALID_ARG;
     if (n_sal > rows) return FB4_ERR_INVALID_ARG;
     if (rows == 0 || cols == 0) return FB4_OK;
@@ -321,12 +335,14 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
     p.codes1 = codes1;
     p.meta1 = meta1;
     p.rows = rows;
+    p.cols = cols;
     p.out = out;
     p.out_row_stride = out_row_stride;
+    p.block_shift = block == 32 ? 5 : 4;
     p.blob = luts->dev_blob;
     int grid = grid_for(luts, p.n_tiles);
     const uint64_t n_blocks = (uint64_t)rows * (uint64_t)p.nb;
-    if (aligned(codes1, 16) && aligned(out, 16) && n_blocks < 0x3FFFFF00ull) {
+    if (block == 32 && aligned(codes1, 16) && aligned(out, 16) && n_blocks < 0x3FFFFF00ull) {
         // plane 1 of every row: one lane per block, pair table in LDS
         DeqFastParams f = {};
         f.codes = codes1;

@@ -1,10 +1,10 @@
 // gfx950 kernels of the FB4 online quantizer (Sec. 3.1-3.4 of the paper).
 //
-// Work mapping.  A wavefront (64 lanes) handles one "tile": 16 consecutive
-// blocks of 32 elements of ONE tensor row.  Four neighbouring lanes (a quad)
-// own one block; every lane loads 16 bytes = 8 bf16 elements, so a wavefront
-// load is 1 KiB of contiguous memory.  Reductions over a block are quad-wide
-// DPP operations.  The lookup tables live in LDS.  All arithmetic is integer
+// Work mapping.  A wavefront (64 lanes) handles one "tile": 512 consecutive
+// elements of ONE tensor row.  Every lane loads 16 bytes = 8 bf16 elements, so a
+// wavefront load is 1 KiB of contiguous memory.  LPB neighbouring lanes own one
+// block: the four lanes of a quad for block size 32, a pair of lanes for block
+// size 16.  Reductions over a block are DPP operations inside the quad.  The lookup tables live in LDS.  All arithmetic is integer
 // arithmetic on the bf16 bit pattern, so results do not depend on floating
 // point modes.
 #pragma once
@@ -18,7 +18,7 @@ namespace fb4 {
 
 constexpr int kThreads = 256;          // 4 wavefronts per workgroup
 constexpr int kWavesPerGroup = kThreads / 64;
-constexpr int kBlocksPerTile = 16;
+constexpr int kTileElems = 512;         // elements of one row a wavefront handles at a time
 
 enum Mode : int { kPlain = 0, kSeda = 1, kDecomp = 2 };
 enum Selector : int { kSelSse = 0, kSelLut = 1 };
@@ -27,8 +27,9 @@ struct QuantParams {
     const uint16_t* x;       // [rows][row_stride] bf16 bits
     long long row_stride;    // elements
     long long rows;          // rows of x
+    long long cols;          // elements per row (a multiple of the block size)
     int nb;                  // blocks per row
-    int tiles_per_row;       // ceil(nb / 16)
+    int tiles_per_row;       // ceil(cols / 512)
     int n_tiles;             // tiles over the OUTPUT rows
     uint8_t* codes;          // [out_rows][nb*16]
     uint16_t* meta;          // [out_rows][nb]
@@ -49,7 +50,9 @@ struct DequantParams {
     const uint16_t* meta2;
     const int32_t* salient;  // null for the plane-1 pass
     long long rows;          // rows of the output tensor
-    int nb;
+    long long cols;
+    int nb;                  // blocks per row
+    int block_shift;         // log2(block size): 4 or 5
     int tiles_per_row;
     int n_tiles;
     void* out;
@@ -91,6 +94,44 @@ __device__ __forceinline__ uint32_t quad_or(uint32_t v)
     return v | quad_xor2(v);
 }
 
+// Reductions and broadcasts over the LPB lanes of one block.
+template <int LPB>
+__device__ __forceinline__ uint32_t blk_max(uint32_t v)
+{
+    v = max(v, quad_xor1(v));
+    return LPB == 4 ? max(v, quad_xor2(v)) : v;
+}
+template <int LPB>
+__device__ __forceinline__ uint32_t blk_min(uint32_t v)
+{
+    v = min(v, quad_xor1(v));
+    return LPB == 4 ? min(v, quad_xor2(v)) : v;
+}
+// value held by lane l of this lane's block
+template <int LPB>
+__device__ __forceinline__ uint32_t blk_bcast(uint32_t v, int l)
+{
+    if (LPB == 4) return quad_bcast(v, l);
+    if (l == 0) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xA0, 0xF, 0xF, true);   // lanes 0,0,2,2
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xF5, 0xF, 0xF, true);                // lanes 1,1,3,3
+}
+// N consecutive dwords from LDS with the widest loads
+template <int N>
+__device__ __forceinline__ void lds_dwords(const uint8_t* p, uint32_t (&o)[N])
+{
+    static_assert(N == 2 || N == 4 || N == 8, "2, 4 or 8 dwords");
+    if (N == 2) {
+        const uint2 r = *reinterpret_cast<const uint2*>(p);
+        o[0] = r.x; o[1] = r.y;
+    } else {
+#pragma unroll
+        for (int k = 0; k < N / 4; ++k) {
+            const uint4 r = reinterpret_cast<const uint4*>(p)[k];
+            o[4 * k] = r.x; o[4 * k + 1] = r.y; o[4 * k + 2] = r.z; o[4 * k + 3] = r.w;
+        }
+    }
+}
+
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b)
 {
@@ -116,9 +157,9 @@ struct Lane8 {
     uint32_t binmax;   // bin of the block maximum
 };
 
-// Shared exponent and bins from the raw bf16 patterns of a quad.
+// Shared exponent and bins from the raw bf16 patterns of a block.
 //   h[i]: the 16-bit patterns of this lane's elements.
-template <bool kNeedFrac>
+template <bool kNeedFrac, int LPB>
 __device__ __forceinline__ void normalize_block(const uint32_t (&h)[8], Lane8& o)
 {
     uint32_t a[8];
@@ -130,7 +171,7 @@ __device__ __forceinline__ void normalize_block(const uint32_t (&h)[8], Lane8& o
         a[i] = (m > 0x7F80u) ? 0u : m;  // NaN: ignored (treated as a signed zero)
         amax = max(amax, a[i]);
     }
-    amax = quad_max(amax);                            // block maximum (bit patterns are monotonic)
+    amax = blk_max<LPB>(amax);                        // block maximum (bit patterns are monotonic)
     uint32_t eb = min(max(amax >> 7, 4u), 254u);      // floor(log2 max) + 127, clamped
     o.ebyte = eb;
     uint32_t bmax = 0;
@@ -146,7 +187,7 @@ __device__ __forceinline__ void normalize_block(const uint32_t (&h)[8], Lane8& o
         if (kNeedFrac) o.frac[i] = X - (b << 7);
         bmax = max(bmax, b);
     }
-    o.binmax = quad_max(bmax);
+    o.binmax = blk_max<LPB>(bmax);
 }
 
 // LDS table views
@@ -173,11 +214,10 @@ __device__ __forceinline__ Tables table_views(const uint8_t* lds)
 }
 
 // Group-wise maxima (Sec. 3.2): the bin of a group's maximum is the maximum of
-// its bins.  G groups per 32-element block, contiguous; this lane owns 8*G/32.
-template <int G>
-__device__ __forceinline__ void group_bins(const Lane8& e, uint32_t (&gb)[8 * G / 32])
+// its bins.  Groups are contiguous runs of PER elements; this lane owns 8 / PER.
+template <int PER>
+__device__ __forceinline__ void group_bins(const Lane8& e, uint32_t (&gb)[8 / PER])
 {
-    constexpr int PER = 32 / G;
 #pragma unroll
     for (int g = 0; g < 8 / PER; ++g) {
         uint32_t m = e.bin[g * PER];
@@ -188,116 +228,116 @@ __device__ __forceinline__ void group_bins(const Lane8& e, uint32_t (&gb)[8 * G 
 }
 
 // ---------------------------------------------------------------- selection
-// Every select_* returns the winning DID, identical in the four lanes of a quad.
+// Every select_* returns the winning DID, identical in all lanes of a block.
+// Lane jb of a block (0..LPB-1) scores a share of the candidates.
 
-// Keys of the lane's eight dialects are (score << 5 | DID); smaller is better.
+// Keys of the lane's N candidates are (score << 5 | DID); smaller is better,
+// 0xFFFFFFFF = no candidate.
 // range = 0: no first stage; otherwise keep only dialects whose top magnitude
 // equals `range`, unless no candidate of the block has it.
-template <bool kTwoStage>
-__device__ __forceinline__ uint32_t finish_min_keys(const uint32_t (&key)[8], const uint32_t (&did)[8],
-                                                    const Tables& T, uint32_t range)
+template <bool kTwoStage, int N, int LPB>
+__device__ __forceinline__ uint32_t finish_min_keys(const uint32_t (&key)[N], const Tables& T, uint32_t range)
 {
     uint32_t best = 0xFFFFFFFFu, bestf = 0xFFFFFFFFu;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < N; ++i) {
         best = min(best, key[i]);
         if (kTwoStage) {
-            bool ok = key[i] != 0xFFFFFFFFu && T.top[did[i] & 31u] == range;
+            bool ok = key[i] != 0xFFFFFFFFu && T.top[key[i] & 31u] == range;
             bestf = min(bestf, ok ? key[i] : 0xFFFFFFFFu);
         }
     }
-    best = quad_min(best);
+    best = blk_min<LPB>(best);
     if (kTwoStage) {
-        bestf = quad_min(bestf);
+        bestf = blk_min<LPB>(bestf);
         if (bestf != 0xFFFFFFFFu) best = bestf;
     }
     return best & 31u;
 }
 
-// The paper's online rule over the full formatbook: lane j of the quad scores
-// dialects 8j..8j+7 for all G group maxima of the block.
-template <int G, bool kTwoStage>
-__device__ __forceinline__ uint32_t select_lut_full(const Lane8& e, const Tables& T, int j, uint32_t range)
+// The paper's online rule over the full formatbook: lane jb of the block scores
+// dialects jb*DPL .. jb*DPL + DPL-1 for all G group maxima of the block.
+template <int G, bool kTwoStage, int LPB>
+__device__ __forceinline__ uint32_t select_lut_full(const Lane8& e, const Tables& T, int jb, uint32_t range)
 {
-    constexpr int GL = 8 * G / 32;
+    constexpr int PER = 8 * LPB / G;     // elements per group
+    constexpr int GL = 8 / PER;          // groups owned by this lane
+    constexpr int DPL = 32 / LPB;        // dialects scored by this lane
+    static_assert(PER >= 1 && PER <= 8, "a group lies inside one lane");
     uint32_t gb[GL];
-    group_bins<G>(e, gb);
-    uint32_t key[8], did[8];
+    group_bins<PER>(e, gb);
+    uint32_t key[DPL];
     if (G == 8) {
         // 8-bit fields: 8 groups x Qerror <= 31 stays below 256
-        uint32_t a0 = 0, a1 = 0;
+        uint32_t acc[DPL / 4];
 #pragma unroll
-        for (int l = 0; l < 4; ++l)
+        for (int k = 0; k < DPL / 4; ++k) acc[k] = 0;
+#pragma unroll
+        for (int l = 0; l < LPB; ++l)
 #pragma unroll
             for (int g = 0; g < GL; ++g) {
-                uint32_t b = quad_bcast(gb[g], l);
-                const uint2 r = *reinterpret_cast<const uint2*>(T.qerr8 + b * 32 + j * 8);
-                a0 += r.x;
-                a1 += r.y;
+                const uint32_t b = blk_bcast<LPB>(gb[g], l);
+                uint32_t r[DPL / 4];
+                lds_dwords<DPL / 4>(T.qerr8 + b * 32 + jb * DPL, r);
+#pragma unroll
+                for (int k = 0; k < DPL / 4; ++k) acc[k] += r[k];
             }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            did[i] = 8 * j + i;
-            did[4 + i] = 8 * j + 4 + i;
-            key[i] = (((a0 >> (8 * i)) & 0xFFu) << 5) | did[i];
-            key[4 + i] = (((a1 >> (8 * i)) & 0xFFu) << 5) | did[4 + i];
-        }
+        for (int k = 0; k < DPL / 4; ++k)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                key[4 * k + i] = (((acc[k] >> (8 * i)) & 0xFFu) << 5) | (uint32_t)(jb * DPL + 4 * k + i);
     } else {
         // 16-bit fields holding Qerror*32: 32 groups x 31*32 stays below 65536
-        uint32_t a[4] = {0, 0, 0, 0};
+        uint32_t acc[DPL / 2];
 #pragma unroll
-        for (int l = 0; l < 4; ++l)
+        for (int k = 0; k < DPL / 2; ++k) acc[k] = 0;
+#pragma unroll
+        for (int l = 0; l < LPB; ++l)
 #pragma unroll
             for (int g = 0; g < GL; ++g) {
-                uint32_t b = quad_bcast(gb[g], l);
-                const uint4 r = *reinterpret_cast<const uint4*>(T.qerr16 + b * 64 + j * 16);
-                a[0] += r.x;
-                a[1] += r.y;
-                a[2] += r.z;
-                a[3] += r.w;
+                const uint32_t b = blk_bcast<LPB>(gb[g], l);
+                uint32_t r[DPL / 2];
+                lds_dwords<DPL / 2>(T.qerr16 + b * 64 + jb * DPL * 2, r);
+#pragma unroll
+                for (int k = 0; k < DPL / 2; ++k) acc[k] += r[k];
             }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            did[2 * i] = 8 * j + 2 * i;
-            did[2 * i + 1] = 8 * j + 2 * i + 1;
-            key[2 * i] = (a[i] & 0xFFFFu) | did[2 * i];
-            key[2 * i + 1] = (a[i] >> 16) | did[2 * i + 1];
+        for (int k = 0; k < DPL / 2; ++k) {
+            key[2 * k] = (acc[k] & 0xFFFFu) | (uint32_t)(jb * DPL + 2 * k);
+            key[2 * k + 1] = (acc[k] >> 16) | (uint32_t)(jb * DPL + 2 * k + 1);
         }
     }
-    return finish_min_keys<kTwoStage>(key, did, T, range);
+    return finish_min_keys<kTwoStage, DPL, LPB>(key, T, range);
 }
 
-// The online rule over a SeDA sub-formatbook (Sec. 3.4): lane j scores the
-// candidates c0, c1 (bytes 2j, 2j+1 of the row's eight DIDs).
-template <int G, bool kTwoStage>
-__device__ __forceinline__ uint32_t select_lut_seda(const Lane8& e, const Tables& T, uint32_t c0, uint32_t c1,
+// The online rule over a SeDA sub-formatbook (Sec. 3.4): lane jb scores NC = 8 / LPB
+// of the row's eight DIDs (bytes jb*NC .. of the list).
+template <int G, bool kTwoStage, int LPB>
+__device__ __forceinline__ uint32_t select_lut_seda(const Lane8& e, const Tables& T, const uint32_t (&c)[8 / LPB],
                                                     int n_dialects, uint32_t range)
 {
-    constexpr int GL = 8 * G / 32;
+    constexpr int PER = 8 * LPB / G, GL = 8 / PER, NC = 8 / LPB;
     uint32_t gb[GL];
-    group_bins<G>(e, gb);
-    const bool v0 = c0 < (uint32_t)n_dialects, v1 = c1 < (uint32_t)n_dialects;
-    const uint32_t d0 = v0 ? c0 : 0u, d1 = v1 ? c1 : 0u;
-    uint32_t s0 = 0, s1 = 0;
+    group_bins<PER>(e, gb);
+    uint32_t d[NC], s[NC];
 #pragma unroll
-    for (int l = 0; l < 4; ++l)
+    for (int k = 0; k < NC; ++k) {
+        d[k] = c[k] < (uint32_t)n_dialects ? c[k] : 0u;
+        s[k] = 0;
+    }
+#pragma unroll
+    for (int l = 0; l < LPB; ++l)
 #pragma unroll
         for (int g = 0; g < GL; ++g) {
-            uint32_t b = quad_bcast(gb[g], l);
-            s0 += T.qerr8[b * 32 + d0];
-            s1 += T.qerr8[b * 32 + d1];
-        }
-    uint32_t key[8], did[8];
+            const uint32_t b = blk_bcast<LPB>(gb[g], l);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        key[i] = 0xFFFFFFFFu;
-        did[i] = 0;
-    }
-    key[0] = v0 ? ((s0 << 5) | d0) : 0xFFFFFFFFu;
-    key[1] = v1 ? ((s1 << 5) | d1) : 0xFFFFFFFFu;
-    did[0] = d0;
-    did[1] = d1;
-    return finish_min_keys<kTwoStage>(key, did, T, range);
+            for (int k = 0; k < NC; ++k) s[k] += T.qerr8[b * 32 + d[k]];
+        }
+    uint32_t key[NC];
+#pragma unroll
+    for (int k = 0; k < NC; ++k) key[k] = c[k] < (uint32_t)n_dialects ? ((s[k] << 5) | d[k]) : 0xFFFFFFFFu;
+    return finish_min_keys<kTwoStage, NC, LPB>(key, T, range);
 }
 
 // Exhaustive squared error (Sec. 3.2, first paragraph).  With X = 256*xhat =
@@ -306,69 +346,74 @@ __device__ __forceinline__ uint32_t select_lut_seda(const Lane8& e, const Tables
 // so the dialect with the smallest error is the one with the largest
 // Z_d = 128 * sum gain[bin][d] + sum frac * mag[bin][d].  Both sums fit 16-bit
 // fields over a whole block (<= 7680 and <= 61440), so two dialects share a
-// 32-bit register.  Lane j accumulates dialects 8j..8j+7 over all 32 elements.
-template <bool kTwoStage>
-__device__ __forceinline__ uint32_t select_sse_full(const Lane8& e, const Tables& T, int j, uint32_t range)
+// 32-bit register.  Lane jb accumulates its DPL dialects over all elements.
+template <bool kTwoStage, int LPB>
+__device__ __forceinline__ uint32_t select_sse_full(const Lane8& e, const Tables& T, int jb, uint32_t range)
 {
-    uint32_t U[4] = {0, 0, 0, 0}, V[4] = {0, 0, 0, 0};
+    constexpr int DPL = 32 / LPB;
+    uint32_t U[DPL / 2], V[DPL / 2];
 #pragma unroll
-    for (int l = 0; l < 4; ++l)
+    for (int k = 0; k < DPL / 2; ++k) U[k] = V[k] = 0;
+#pragma unroll
+    for (int l = 0; l < LPB; ++l)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            uint32_t b = quad_bcast(e.bin[i], l);
-            uint32_t f = quad_bcast(e.frac[i], l);
-            const uint4 m = *reinterpret_cast<const uint4*>(T.mag16 + b * 64 + j * 16);
-            const uint4 g = *reinterpret_cast<const uint4*>(T.gain16 + b * 64 + j * 16);
-            U[0] += g.x; U[1] += g.y; U[2] += g.z; U[3] += g.w;
-            V[0] += m.x * f; V[1] += m.y * f; V[2] += m.z * f; V[3] += m.w * f;
+            const uint32_t b = blk_bcast<LPB>(e.bin[i], l);
+            const uint32_t f = blk_bcast<LPB>(e.frac[i], l);
+            uint32_t m[DPL / 2], g[DPL / 2];
+            lds_dwords<DPL / 2>(T.mag16 + b * 64 + jb * DPL * 2, m);
+            lds_dwords<DPL / 2>(T.gain16 + b * 64 + jb * DPL * 2, g);
+#pragma unroll
+            for (int k = 0; k < DPL / 2; ++k) {
+                U[k] += g[k];
+                V[k] += m[k] * f;
+            }
         }
     // key: smaller is better -> invert Z (Z < 2^20)
-    uint32_t key[8], did[8];
+    uint32_t key[DPL];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t zlo = ((U[i] & 0xFFFFu) << 7) + (V[i] & 0xFFFFu);
-        uint32_t zhi = ((U[i] >> 16) << 7) + (V[i] >> 16);
-        did[2 * i] = 8 * j + 2 * i;
-        did[2 * i + 1] = 8 * j + 2 * i + 1;
-        key[2 * i] = ((0xFFFFFu - zlo) << 5) | did[2 * i];
-        key[2 * i + 1] = ((0xFFFFFu - zhi) << 5) | did[2 * i + 1];
+    for (int k = 0; k < DPL / 2; ++k) {
+        const uint32_t zlo = ((U[k] & 0xFFFFu) << 7) + (V[k] & 0xFFFFu);
+        const uint32_t zhi = ((U[k] >> 16) << 7) + (V[k] >> 16);
+        key[2 * k] = ((0xFFFFFu - zlo) << 5) | (uint32_t)(jb * DPL + 2 * k);
+        key[2 * k + 1] = ((0xFFFFFu - zhi) << 5) | (uint32_t)(jb * DPL + 2 * k + 1);
     }
-    return finish_min_keys<kTwoStage>(key, did, T, range);
+    return finish_min_keys<kTwoStage, DPL, LPB>(key, T, range);
 }
 
-template <bool kTwoStage>
-__device__ __forceinline__ uint32_t select_sse_seda(const Lane8& e, const Tables& T, uint32_t c0, uint32_t c1,
+template <bool kTwoStage, int LPB>
+__device__ __forceinline__ uint32_t select_sse_seda(const Lane8& e, const Tables& T, const uint32_t (&c)[8 / LPB],
                                                     int n_dialects, uint32_t range)
 {
-    const bool v0 = c0 < (uint32_t)n_dialects, v1 = c1 < (uint32_t)n_dialects;
-    const uint32_t d0 = v0 ? c0 : 0u, d1 = v1 ? c1 : 0u;
+    constexpr int NC = 8 / LPB;
     const uint16_t* mag = reinterpret_cast<const uint16_t*>(T.mag16);
     const uint16_t* gain = reinterpret_cast<const uint16_t*>(T.gain16);
-    uint32_t z0 = 0, z1 = 0;
+    uint32_t d[NC], z[NC];
 #pragma unroll
-    for (int l = 0; l < 4; ++l)
+    for (int k = 0; k < NC; ++k) {
+        d[k] = c[k] < (uint32_t)n_dialects ? c[k] : 0u;
+        z[k] = 0;
+    }
+#pragma unroll
+    for (int l = 0; l < LPB; ++l)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            uint32_t b = quad_bcast(e.bin[i], l);
-            uint32_t f = quad_bcast(e.frac[i], l);
-            z0 += ((uint32_t)gain[b * 32 + d0] << 7) + (uint32_t)mag[b * 32 + d0] * f;
-            z1 += ((uint32_t)gain[b * 32 + d1] << 7) + (uint32_t)mag[b * 32 + d1] * f;
-        }
-    uint32_t key[8], did[8];
+            const uint32_t b = blk_bcast<LPB>(e.bin[i], l);
+            const uint32_t f = blk_bcast<LPB>(e.frac[i], l);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        key[i] = 0xFFFFFFFFu;
-        did[i] = 0;
-    }
-    key[0] = v0 ? (((0xFFFFFu - z0) << 5) | d0) : 0xFFFFFFFFu;
-    key[1] = v1 ? (((0xFFFFFu - z1) << 5) | d1) : 0xFFFFFFFFu;
-    did[0] = d0;
-    did[1] = d1;
-    return finish_min_keys<kTwoStage>(key, did, T, range);
+            for (int k = 0; k < NC; ++k)
+                z[k] += ((uint32_t)gain[b * 32 + d[k]] << 7) + (uint32_t)mag[b * 32 + d[k]] * f;
+        }
+    uint32_t key[NC];
+#pragma unroll
+    for (int k = 0; k < NC; ++k)
+        key[k] = c[k] < (uint32_t)n_dialects ? (((0xFFFFFu - z[k]) << 5) | d[k]) : 0xFFFFFFFFu;
+    return finish_min_keys<kTwoStage, NC, LPB>(key, T, range);
 }
 
 // ------------------------------------------------------------ quantize kernel
-template <int SEL, int G, int MODE, bool kTwoStage>
+// LPB = lanes per block: 4 for block size 32, 2 for block size 16.
+template <int SEL, int G, int MODE, bool kTwoStage, int LPB>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p)
 {
     __shared__ __align__(16) uint8_t lds[kBlobBytes];
@@ -377,8 +422,9 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int q = lane >> 2, j = lane & 3;
+    const int jb = lane & (LPB - 1);      // lane within its block
     const int stride = gridDim.x * kWavesPerGroup;
+    const long long code_pitch = p.cols / 2;
 
     for (int t = blockIdx.x * kWavesPerGroup + wave; t < p.n_tiles; t += stride) {
         const int orow = t / p.tiles_per_row;               // output row (wave-uniform)
@@ -388,12 +434,13 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p)
             srow = p.salient[orow];
             if (srow < 0 || srow >= p.rows) continue;       // wave-uniform
         }
-        const int bc = chunk * kBlocksPerTile + q;          // block within the row
-        const bool valid = bc < p.nb;
+        const long long col = (long long)chunk * kTileElems + lane * 8;   // first of this lane's 8 elements
+        const bool valid = col < p.cols;                    // the same for all lanes of a block
+        const long long blk = col / (8 * LPB);              // block within the row
 
         // ---- load this lane's eight elements
         uint4 w = make_uint4(0, 0, 0, 0);
-        if (valid) w = *reinterpret_cast<const uint4*>(p.x + srow * p.row_stride + (long long)bc * 32 + j * 8);
+        if (valid) w = *reinterpret_cast<const uint4*>(p.x + srow * p.row_stride + col);
         uint32_t h[8] = {w.x & 0xFFFFu, w.x >> 16, w.y & 0xFFFFu, w.y >> 16,
                          w.z & 0xFFFFu, w.z >> 16, w.w & 0xFFFFu, w.w >> 16};
 
@@ -401,8 +448,8 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p)
             // Sec. 3.3: residual of the first plane, exact, rounded once to bf16
             uint32_t c1 = 0, m1 = 0;
             if (valid) {
-                c1 = *reinterpret_cast<const uint32_t*>(p.codes1 + (srow * p.nb + bc) * 16 + j * 4);
-                m1 = p.meta1[srow * p.nb + bc];
+                c1 = *reinterpret_cast<const uint32_t*>(p.codes1 + srow * code_pitch + col / 2);
+                m1 = p.meta1[srow * p.nb + blk];
             }
             const uint32_t did1 = m1 & 0xFFu, e1 = m1 >> 8;
 #pragma unroll
@@ -420,20 +467,26 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p)
         }
 
         Lane8 e;
-        normalize_block<SEL == kSelSse>(h, e);
+        normalize_block<SEL == kSelSse, LPB>(h, e);
         const uint32_t range = kTwoStage ? min(max(e.binmax >> 1, 8u), 15u) : 0u;
 
         // ---- candidates
+        constexpr int NC = 8 / LPB;
         bool seda = false;
-        uint32_t c0 = 0, c1 = 0;
+        uint32_t c[NC];
+#pragma unroll
+        for (int k = 0; k < NC; ++k) c[k] = 0;
         if (MODE == kSeda || MODE == kDecomp) {
             if (p.token_group != nullptr) {
                 const int grp = p.token_group[srow];           // wave-uniform
                 if (grp >= 0 && grp < p.n_groups) {
                     const uint8_t* s = p.sub + (long long)grp * 8;
-                    c0 = s[2 * j];
-                    c1 = s[2 * j + 1];
-                    const bool any = (c0 < (uint32_t)p.n_dialects) || (c1 < (uint32_t)p.n_dialects);
+                    bool any = false;
+#pragma unroll
+                    for (int k = 0; k < NC; ++k) {
+                        c[k] = s[NC * jb + k];
+                        any = any || (c[k] < (uint32_t)p.n_dialects);
+                    }
                     seda = __builtin_amdgcn_ballot_w64(any) != 0;   // wave-uniform
                 }
             }
@@ -441,11 +494,11 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p)
 
         uint32_t did;
         if (seda) {
-            did = (SEL == kSelSse) ? select_sse_seda<kTwoStage>(e, T, c0, c1, p.n_dialects, range)
-                                   : select_lut_seda<G, kTwoStage>(e, T, c0, c1, p.n_dialects, range);
+            did = (SEL == kSelSse) ? select_sse_seda<kTwoStage, LPB>(e, T, c, p.n_dialects, range)
+                                   : select_lut_seda<G, kTwoStage, LPB>(e, T, c, p.n_dialects, range);
         } else {
-            did = (SEL == kSelSse) ? select_sse_full<kTwoStage>(e, T, j, range)
-                                   : select_lut_full<G, kTwoStage>(e, T, j, range);
+            did = (SEL == kSelSse) ? select_sse_full<kTwoStage, LPB>(e, T, jb, range)
+                                   : select_lut_full<G, kTwoStage, LPB>(e, T, jb, range);
         }
 
         // ---- emit (Sec. 3.2: every element through Qvalue of the chosen dialect)
@@ -454,9 +507,8 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p)
 #pragma unroll
         for (int i = 0; i < 8; ++i) code |= (uint32_t)qv[(e.sign[i] << 5) | e.bin[i]] << (4 * i);
         if (valid) {
-            const long long ob = (long long)orow * p.nb + bc;
-            *reinterpret_cast<uint32_t*>(p.codes + ob * 16 + j * 4) = code;
-            if (j == 0) p.meta[ob] = (uint16_t)(did | (e.ebyte << 8));
+            *reinterpret_cast<uint32_t*>(p.codes + (long long)orow * code_pitch + col / 2) = code;
+            if (jb == 0) p.meta[(long long)orow * p.nb + blk] = (uint16_t)(did | (e.ebyte << 8));
         }
     }
 }
@@ -474,8 +526,8 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(DequantParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int q = lane >> 2, j = lane & 3;
     const int stride = gridDim.x * kWavesPerGroup;
+    const long long code_pitch = p.cols / 2;
 
     for (int t = blockIdx.x * kWavesPerGroup + wave; t < p.n_tiles; t += stride) {
         const int prow = t / p.tiles_per_row;
@@ -485,17 +537,16 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(DequantParams p)
             orow = p.salient[prow];
             if (orow < 0 || orow >= p.rows) continue;
         }
-        const int bc = chunk * kBlocksPerTile + q;
-        if (bc >= p.nb) continue;   // no cross-lane operation below
+        const long long col = (long long)chunk * kTileElems + lane * 8;
+        if (col >= p.cols) continue;   // no cross-lane operation below
+        const long long blk = col >> p.block_shift;
 
-        const long long b1 = orow * p.nb + bc;
-        const uint32_t c1 = *reinterpret_cast<const uint32_t*>(p.codes1 + b1 * 16 + j * 4);
-        const uint32_t m1 = p.meta1[b1];
+        const uint32_t c1 = *reinterpret_cast<const uint32_t*>(p.codes1 + orow * code_pitch + col / 2);
+        const uint32_t m1 = p.meta1[orow * p.nb + blk];
         uint32_t c2 = 0, m2 = 0;
         if (kSum) {
-            const long long b2 = (long long)prow * p.nb + bc;
-            c2 = *reinterpret_cast<const uint32_t*>(p.codes2 + b2 * 16 + j * 4);
-            m2 = p.meta2[b2];
+            c2 = *reinterpret_cast<const uint32_t*>(p.codes2 + (long long)prow * code_pitch + col / 2);
+            m2 = p.meta2[(long long)prow * p.nb + blk];
         }
         uint32_t outb[8];
 #pragma unroll
@@ -515,7 +566,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(DequantParams p)
             outb[i] = f;
         }
         if (kF32) {
-            float* o = reinterpret_cast<float*>(p.out) + orow * p.out_row_stride + (long long)bc * 32 + j * 8;
+            float* o = reinterpret_cast<float*>(p.out) + orow * p.out_row_stride + col;
             reinterpret_cast<uint4*>(o)[0] = make_uint4(outb[0], outb[1], outb[2], outb[3]);
             reinterpret_cast<uint4*>(o)[1] = make_uint4(outb[4], outb[5], outb[6], outb[7]);
         } else {
@@ -526,7 +577,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(DequantParams p)
                 if (kSum) u += 0x7FFFu + ((u >> 16) & 1u);   // round to nearest even
                 hb[i] = u >> 16;
             }
-            uint16_t* o = reinterpret_cast<uint16_t*>(p.out) + orow * p.out_row_stride + (long long)bc * 32 + j * 8;
+            uint16_t* o = reinterpret_cast<uint16_t*>(p.out) + orow * p.out_row_stride + col;
             *reinterpret_cast<uint4*>(o) = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16),
                                                       hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
         }

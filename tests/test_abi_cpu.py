@@ -164,7 +164,8 @@ def test_argument_validation_happens_before_any_gpu_work():
     assert _call_quantize(h, F.opts(num_groups=5), P(al), 1, 32, 32, P(al), P(al)) == F.ERR_INVALID_ARG
     assert _call_quantize(h, F.opts(block=24), P(al), 1, 32, 32, P(al), P(al)) == F.ERR_INVALID_ARG
     assert _call_quantize(h, F.opts(flags=8), P(al), 1, 32, 32, P(al), P(al)) == F.ERR_INVALID_ARG
-    assert _call_quantize(h, F.opts(block=16), P(al), 1, 32, 32, P(al), P(al)) == F.ERR_UNSUPPORTED
+    assert _call_quantize(h, F.opts(block=16, num_groups=32), P(al), 1, 32, 32, P(al), P(al)) == F.ERR_INVALID_ARG
+    assert _call_quantize(h, F.opts(block=16), P(al), 1, 40, 40, P(al), P(al)) == F.ERR_UNSUPPORTED  # cols % 16
     # shapes
     assert _call_quantize(h, good, P(al), -1, 32, 32, P(al), P(al)) == F.ERR_INVALID_ARG
     assert _call_quantize(h, good, P(al), 1, 64, 32, P(al), P(al)) == F.ERR_INVALID_ARG      # stride < cols
@@ -198,7 +199,7 @@ def test_argument_validation_happens_before_any_gpu_work():
     assert dq(None, P(al), P(al), 1, 32, 32, None, None, None, 0, P(al), 0, 32, None) == F.ERR_INVALID_ARG
     assert dq(h, P(al), P(al), 1, 32, 32, None, None, None, 0, P(al), 5, 32, None) == F.ERR_INVALID_ARG
     assert dq(h, P(al), P(al), 1, 32, 32, None, None, None, 2, P(al), 0, 32, None) == F.ERR_INVALID_ARG
-    assert dq(h, P(al), P(al), 1, 32, 16, None, None, None, 0, P(al), 0, 32, None) == F.ERR_UNSUPPORTED
+    assert dq(h, P(al), P(al), 1, 40, 16, None, None, None, 0, P(al), 0, 40, None) == F.ERR_UNSUPPORTED
     assert dq(h, P(al), P(al), 1, 32, 32, None, None, None, 0, P(al + 16), 1, 32, None) == F.ERR_UNSUPPORTED
     assert dq(h, P(al), P(al), 0, 32, 32, None, None, None, 0, None, 0, 32, None) == F.OK
 

@@ -48,7 +48,7 @@ def host_u16(t):
     return t.cpu().numpy().view(np.uint16)
 
 
-def compare_quant(fbk, x_bits, cg, mg, cr, mr, sel, g, flags=0, token_group=None, sub=None, what=""):
+def compare_quant(fbk, x_bits, cg, mg, cr, mr, sel, g, flags=0, token_group=None, sub=None, what="", block=32):
     """cg/mg from the GPU, cr/mr from the oracle (numpy)."""
     assert cg.shape == cr.shape and mg.shape == mr.shape
     if np.array_equal(mg, mr) and np.array_equal(cg, cr):
@@ -57,7 +57,7 @@ def compare_quant(fbk, x_bits, cg, mg, cr, mr, sel, g, flags=0, token_group=None
     bad = np.argwhere((mg & 0xFF) != (mr & 0xFF))
     ties = 0
     for r, b in bad[:64]:
-        blk = x_bits[r, 32 * b:32 * b + 32]
+        blk = x_bits[r, block * b:block * b + block]
         sub8 = None if (token_group is None or token_group[r] < 0) else sub[token_group[r]]
         cand, scores, did, e = O.block_scores(fbk, blk, selector=sel, num_groups=g, flags=flags, sub8=sub8)
         dg = int(mg[r, b] & 0xFF)
@@ -67,15 +67,16 @@ def compare_quant(fbk, x_bits, cg, mg, cr, mr, sel, g, flags=0, token_group=None
         assert abs(sg - sr) <= 1e-6 * max(abs(sr), 1e-30), (
             "%s: dialect mismatch at row %d block %d: gpu %d (score %r) oracle %d (score %r)"
             % (what, r, b, dg, sg, int(mr[r, b] & 0xFF), sr))
-        c1, _ = O.quantize(fbk[dg:dg + 1], blk[None, :], selector=O.SEL_SSE)
-        assert np.array_equal(cg[r, 16 * b:16 * b + 16], c1[0]), what + ": codes of a tied block"
+        c1, _ = O.quantize(fbk[dg:dg + 1], blk[None, :], block=block, selector=O.SEL_SSE)
+        assert np.array_equal(cg[r, block // 2 * b:block // 2 * (b + 1)], c1[0]), what + ": codes of a tied block"
         ties += 1
     assert len(bad) <= 64, what + ": %d dialect mismatches" % len(bad)
     if ties:
         warnings.warn("%s: %d argmin ties resolved differently (scores equal within 1e-6)" % (what, ties))
     ok = np.ones(mg.shape, dtype=bool)
     ok[bad[:, 0], bad[:, 1]] = False
-    assert np.array_equal(cg.reshape(mg.shape + (16,))[ok], cr.reshape(mr.shape + (16,))[ok]), what + ": codes differ"
+    assert np.array_equal(cg.reshape(mg.shape + (block // 2,))[ok], cr.reshape(mr.shape + (block // 2,))[ok]), \
+        what + ": codes differ"
     return ties
 
 
@@ -374,8 +375,8 @@ def test_empty_inputs_and_error_codes_with_a_real_handle(F, luts):
         F.fb4_quantize(luts, o, torch.zeros((4, 48), dtype=torch.bfloat16, device="cuda"))
     assert e.value.code == F.ERR_UNSUPPORTED
     with pytest.raises(F.Fb4Error) as e:
-        F.fb4_quantize(luts, F.opts(block=16), x)
-    assert e.value.code == F.ERR_UNSUPPORTED
+        F.fb4_quantize(luts, F.opts(block=16, num_groups=32), x)        # more groups than elements
+    assert e.value.code == F.ERR_INVALID_ARG
     # out-of-range salient rows leave their output rows untouched
     sal = torch.tensor([1, 77], dtype=torch.int32, device="cuda")
     c2 = torch.full((2, 32), 0x5A, dtype=torch.uint8, device="cuda")
@@ -383,6 +384,68 @@ def test_empty_inputs_and_error_codes_with_a_real_handle(F, luts):
     F.fb4_decompose(luts, o, x, c, m, sal, codes2=c2, meta2=m2)
     torch.cuda.synchronize()
     assert bool((c2[1] == 0x5A).all()) and bool((c2[0] == 0).all())
+
+
+# ------------------------------------------------------------ block size 16
+SELECTORS_B16 = [("lut8", 1, 8), ("lut16", 1, 16), ("sse", 0, 8)]
+
+
+@pytest.mark.parametrize("name,sel,g", SELECTORS_B16)
+def test_block16_all_entry_points(F, luts, name, sel, g):
+    """Sec. 4.1 evaluates block sizes 16 and 32: the same pipeline with a scale and a dialect per 16 elements."""
+    fbk = DEFAULT_FORMATBOOK
+    for rows, cols, stride, seed in ((512, 3072, 3072, 46), (37, 16 * 21, 16 * 21 + 8, 47), (3, 16, 16, 48)):
+        big = synth.vdit_activation(rows=rows, cols=stride, seed=seed, device="cuda")
+        x = big[:, :cols]
+        xb = np.ascontiguousarray(synth.bf16_bits(big)[:, :cols])
+        for flags in (0, F.FLAG_TWO_STAGE):
+            o = F.opts(block=16, selector=sel, num_groups=g, flags=flags)
+            c, m = F.fb4_quantize(luts, o, x)
+            torch.cuda.synchronize()
+            assert m.shape == (rows, cols // 16)
+            cr, mr = O.quantize(fbk, xb, block=16, selector=sel, num_groups=g, flags=flags)
+            compare_quant(fbk, xb, host_u8(c), host_u16(m), cr, mr, sel, g, flags=flags, block=16,
+                          what="block16 %dx%d %s flags %d" % (rows, cols, name, flags))
+        # second plane of some rows, then both decodes
+        sal = np.arange(0, rows, 3, dtype=np.int32)
+        sal_d = torch.from_numpy(sal).cuda()
+        c2, m2 = F.fb4_decompose(luts, o, x, c, m, sal_d)
+        torch.cuda.synchronize()
+        c2r, m2r = O.decompose(fbk, xb, host_u8(c), host_u16(m), sal, block=16, selector=sel, num_groups=g,
+                               flags=flags)
+        compare_quant(fbk, xb[sal], host_u8(c2), host_u16(m2), c2r, m2r, sel, g, flags=flags, block=16,
+                      what="block16 plane2 " + name)
+        for dt, odt in ((F.DTYPE_BF16, O.OUT_BF16), (F.DTYPE_F32, O.OUT_F32)):
+            y = F.fb4_dequantize(luts, c, m, block=16, codes2=c2, meta2=m2, salient_rows=sal_d, out_dtype=dt)
+            torch.cuda.synchronize()
+            yr = O.dequantize(fbk, host_u8(c), host_u16(m), block=16, codes2=host_u8(c2), meta2=host_u16(m2),
+                              salient_rows=sal, out_dtype=odt)
+            yg = synth.bf16_bits(y) if dt == F.DTYPE_BF16 else y.cpu().numpy().view(np.uint32)
+            assert np.array_equal(yg, yr if dt == F.DTYPE_BF16 else yr.view(np.uint32))
+
+
+@pytest.mark.parametrize("name,sel,g", SELECTORS_B16)
+def test_block16_seda_and_degenerate_values(F, luts, name, sel, g):
+    x, comp = synth.mixture_activation(rows=256, cols=16 * 41, seed=49, device="cuda", n_components=5)
+    xb = synth.bf16_bits(x)
+    sub = synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, n_groups=5, seed=49)
+    tg = comp.copy()
+    tg[::9] = -1
+    o = F.opts(block=16, selector=sel, num_groups=g)
+    c, m = F.fb4_quantize_seda(luts, o, x, torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda())
+    torch.cuda.synchronize()
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, block=16, selector=sel, num_groups=g, token_group=tg,
+                        sub_formatbooks=sub)
+    compare_quant(DEFAULT_FORMATBOOK, xb, host_u8(c), host_u16(m), cr, mr, sel, g, token_group=tg, sub=sub,
+                  block=16, what="block16 seda " + name)
+    xe = synth.edge_case_tensor(cols=256)
+    c, m = F.fb4_quantize(luts, o, dev_bits(xe))
+    y = F.fb4_dequantize(luts, c, m, block=16)
+    torch.cuda.synchronize()
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xe, block=16, selector=sel, num_groups=g)
+    compare_quant(DEFAULT_FORMATBOOK, xe, host_u8(c), host_u16(m), cr, mr, sel, g, block=16,
+                  what="block16 edge " + name)
+    assert np.array_equal(synth.bf16_bits(y), O.dequantize(DEFAULT_FORMATBOOK, cr, mr, block=16))
 
 
 def test_luts_handle_is_reusable_across_streams(F, luts):
