@@ -163,7 +163,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-            "kernel": "fb4::quantize_lut8_kernel<true>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
+            "kernel": "fb4::quantize_lut_kernel<32, 8, true, false, false>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
         },
     }
 
@@ -177,7 +177,15 @@ def main():
             extras[name] = {"us": e / steps * 1e6, "G_elements_per_s": nelem / (e / steps) / 1e9,
                             "GB_per_s": nbytes / (e / steps) / 1e9, "hbm_frac": nbytes / (e / steps) / 1e9 / HBM_PEAK_GBS}
 
+        add("quantize_lut_g16", quant_step(F.opts(selector=F.SEL_LUT, num_groups=16)), abytes, n_el)
         add("quantize_lut_g32", quant_step(F.opts(selector=F.SEL_LUT, num_groups=32)), abytes, n_el)
+        metas16 = [torch.empty((ROWS, COLS // 16), dtype=torch.int16, device="cuda") for _ in range(N_SETS)]
+        o16 = F.opts(block=16, selector=F.SEL_LUT, num_groups=8)
+
+        def b16_step(i):
+            k = i % N_SETS
+            F.fb4_quantize(luts, o16, xs[k], codes=codes[k], meta=metas16[k])
+        add("quantize_block16_lut_g8", b16_step, algorithmic_bytes(ROWS, COLS, 16), n_el)
         add("quantize_lut_g8_two_stage", quant_step(F.opts(selector=F.SEL_LUT, num_groups=8,
                                                            flags=F.FLAG_TWO_STAGE)), abytes, n_el)
         add("quantize_sse", quant_step(F.opts(selector=F.SEL_SSE)), abytes, n_el, steps=max(5, args.steps // 10))

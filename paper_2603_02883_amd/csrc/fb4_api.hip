@@ -82,35 +82,40 @@ int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& 
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
-template <bool kTwoStage, bool kSeda>
-void launch_fast_variant(bool flat, unsigned groups, hipStream_t s, const FastParams& f)
+template <int kBlock, int G, bool kFlat>
+void launch_fast_variant(bool ts, bool seda, unsigned groups, hipStream_t s, const FastParams& f)
 {
-    if (flat)
-        hipLaunchKernelGGL((quantize_lut8_kernel<true, kTwoStage, kSeda>), dim3(groups), dim3(kFastThreads), 0, s, f);
-    else
-        hipLaunchKernelGGL((quantize_lut8_kernel<false, kTwoStage, kSeda>), dim3(groups), dim3(kFastThreads), 0, s, f);
+    if (seda) {
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true>), dim3(groups), dim3(kFastThreads), 0, s, f);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true>), dim3(groups), dim3(kFastThreads), 0, s, f);
+    } else {
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false>), dim3(groups), dim3(kFastThreads), 0, s, f);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false>), dim3(groups), dim3(kFastThreads), 0, s, f);
+    }
 }
 
-// The streaming kernel serves the paper's default online configuration (LUT selector, 8 groups, block 32),
-// with or without the two-stage filter and SeDA lists.  Returns false if the request is not one it serves.
+// The streaming kernel serves the paper's online selector (LUT, any supported block size and group count),
+// with or without the two-stage filter and SeDA lists, when rows are whole 32-element chunks and the outputs
+// are aligned for its wide stores.  Returns false if the request is not one it serves.
 bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& p, int64_t cols,
                  const int32_t* token_group, const uint8_t* sub, int n_groups, hipStream_t s, int* rc)
 {
-    if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8 || !aligned(p.codes, 16))
-        return false;
-    const uint64_t n_blocks = (uint64_t)p.rows * (uint64_t)p.nb;
+    if (opts->selector != FB4_SEL_LUT || (cols % 32) || !aligned(p.codes, 16)) return false;
+    if (opts->block == 16 && !aligned(p.meta, 4)) return false;
+    const uint64_t nb = (uint64_t)cols / 32;
+    const uint64_t n_blocks = (uint64_t)p.rows * nb;
     if (n_blocks >= 0x7FFFFF00ull) return false;
     if (token_group && (uint32_t)n_groups > kMaxFastGroups) return false;
     FastParams f = {};
     f.x = p.x;
     f.row_stride = p.row_stride;
-    f.nb = (uint32_t)p.nb;
+    f.nb = (uint32_t)nb;
     f.n_blocks = (uint32_t)n_blocks;
     f.n_tiles = (uint32_t)((n_blocks + 63) / 64);
     uint32_t l = 0;
-    while ((1ull << l) < (uint64_t)p.nb) ++l;
+    while ((1ull << l) < nb) ++l;
     f.div_shift = 31 + l;
-    f.div_mul = (uint32_t)(((1ull << f.div_shift) + (uint64_t)p.nb - 1) / (uint64_t)p.nb);
+    f.div_mul = (uint32_t)(((1ull << f.div_shift) + nb - 1) / nb);
     f.codes = p.codes;
     f.meta = p.meta;
     f.blob = luts->dev_blob;
@@ -121,14 +126,22 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
     long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
     const long long cap = (long long)luts->n_cu * FB4_FAST_GROUPS_PER_CU;
     if (groups > cap) groups = cap;
+    const unsigned ng = (unsigned)groups;
     const bool flat = p.row_stride == cols;
     const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
-    if (token_group) {
-        if (ts) launch_fast_variant<true, true>(flat, (unsigned)groups, s, f);
-        else launch_fast_variant<false, true>(flat, (unsigned)groups, s, f);
+    const bool seda = token_group != nullptr;
+    if (opts->block == 32) {
+        if (opts->num_groups == 8) {
+            if (flat) launch_fast_variant<32, 8, true>(ts, seda, ng, s, f);
+            else launch_fast_variant<32, 8, false>(ts, seda, ng, s, f);
+        } else if (opts->num_groups == 16) {
+            launch_fast_variant<32, 16, false>(ts, seda, ng, s, f);
+        } else {
+            launch_fast_variant<32, 32, false>(ts, seda, ng, s, f);
+        }
     } else {
-        if (ts) launch_fast_variant<true, false>(flat, (unsigned)groups, s, f);
-        else launch_fast_variant<false, false>(flat, (unsigned)groups, s, f);
+        if (opts->num_groups == 8) launch_fast_variant<16, 8, false>(ts, seda, ng, s, f);
+        else launch_fast_variant<16, 16, false>(ts, seda, ng, s, f);
     }
     *rc = hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
     return true;

@@ -1,12 +1,14 @@
-// Streaming kernel for the paper's default online configuration (Sec. 3.2:
-// Qerror over 8 group-wise maxima, all dialects, block 32).
+// Streaming kernel for the paper's online selector (Sec. 3.2: Qerror summed
+// over group-wise maxima; default 8 groups, all dialects, block 32).
 //
-// One lane owns one whole block: it loads the block's 64 bytes with four
-// 16-byte loads, keeps the 32 elements as 16 packed bf16 pairs and runs every
-// per-element step on both halves of a register at once (packed 16-bit
-// integer instructions).  Nothing crosses lanes.  A wavefront therefore
-// covers 64 consecutive blocks (4 KiB of input) and writes 1 KiB of codes and
-// 128 bytes of metadata, all contiguous.
+// One lane owns 32 consecutive elements of a row -- one block of 32 or two
+// blocks of 16: it loads the 64 bytes with four 16-byte loads, keeps the
+// elements as 16 packed bf16 pairs and runs every per-element step on both
+// halves of a register at once (packed 16-bit integer instructions).  Nothing
+// crosses lanes.  A wavefront therefore covers 64 consecutive 32-element
+// chunks (4 KiB of input) and writes 1 KiB of codes and 128 (block 16: 256)
+// bytes of metadata, all contiguous.  In the code below "chunk" indices (gb)
+// count these 32-element pieces.
 //
 // LDS tables, built once per workgroup:
 //   * Qerror rows (32 bytes per bin, one byte per dialect), eight copies laid
@@ -40,7 +42,7 @@ constexpr int kFastWaves = kFastThreads / 64;
 struct FastParams {
     const uint16_t* x;
     long long row_stride;   // elements
-    uint32_t nb;            // blocks per row
+    uint32_t nb;            // 32-element chunks per row
     uint32_t n_blocks;      // rows * nb
     uint32_t n_tiles;       // ceil(n_blocks / 64)
     uint32_t div_mul;       // row = (gb * div_mul) >> div_shift   (gb < 2^31)
@@ -112,17 +114,19 @@ struct BlockCodes {
     uint32_t meta;
 };
 
-// Plain per-element routine for one block, any input (Sec. 3.1-3.2); reads the
-// block again from global memory.  Same arithmetic as the generic kernel.
+// Plain per-element routine for one block of kBlock elements with G groups, any input (Sec. 3.1-3.2); reads
+// the block again from global memory.  Same arithmetic as the generic kernel.
 // excl_a / excl_b: LDS offsets of 32-byte exclusion rows (0xFF = excluded), or 0xFFFFFFFF for none.  A dialect
 // excluded by excl_a never wins; excl_b (the two-stage range filter) applies only if it leaves a candidate.
+template <int kBlock, int G>
 __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, const uint8_t* lds, uint32_t excl_a,
                                                         bool two_stage)
 {
+    constexpr int PER = kBlock / G;
     BlockCodes out;
     uint32_t amax = 0;
 #pragma unroll 1
-    for (int i = 0; i < 32; ++i) {
+    for (int i = 0; i < kBlock; ++i) {
         uint32_t m = xb[i] & 0x7FFFu;
         amax = max(amax, (m > 0x7F80u) ? 0u : m);
     }
@@ -136,17 +140,17 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
         uint32_t X = (sh <= 7u) ? (sig << (7u - sh)) : (sig >> min(sh - 7u, 31u));
         return min(X >> 7, 31u);
     };
-    uint32_t gbin[8];
+    uint32_t gbin[G];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < G; ++j) {
         uint32_t g = 0;
 #pragma unroll 1
-        for (int i = 0; i < 4; ++i) g = max(g, bin_of(xb[4 * j + i]));
+        for (int i = 0; i < PER; ++i) g = max(g, bin_of(xb[PER * j + i]));
         gbin[j] = g;
     }
     uint32_t bmax = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) bmax = max(bmax, gbin[j]);
+    for (int j = 0; j < G; ++j) bmax = max(bmax, gbin[j]);
     const uint32_t excl_b = kLdsRange + (min(max(bmax >> 1, 8u), 15u) - 8u) * 32u;
     uint32_t best = 0xFFFFFFFFu, best_b = 0xFFFFFFFFu;
 #pragma unroll 1
@@ -154,14 +158,15 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
         if (excl_a != 0xFFFFFFFFu && lds[excl_a + d]) continue;
         uint32_t s = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) s += lds[kLdsRows + gbin[j] * 256 + (d >> 4) * 128 + (d & 15)];
+        for (int j = 0; j < G; ++j) s += lds[kLdsRows + gbin[j] * 256 + (d >> 4) * 128 + (d & 15)];
         best = min(best, (s << 5) | d);
         if (two_stage && !lds[excl_b + d]) best_b = min(best_b, (s << 5) | d);
     }
     if (best_b != 0xFFFFFFFFu) best = best_b;
     const uint32_t did = best & 31u;
+    out.code[0] = out.code[1] = out.code[2] = out.code[3] = 0;
 #pragma unroll 1
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < kBlock / 8; ++c) {
         uint32_t v = 0;
 #pragma unroll 1
         for (int i = 0; i < 8; ++i) {
@@ -195,122 +200,182 @@ __device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane)
     return K;
 }
 
-// One block per lane: w = its 32 bf16 as 16 packed pairs.  Produces the four code words and the metadata
-// word.  xb / in_range are only used by the plain per-element routine of a tile with special values.
+// Sec. 3.2 online selection for one block from the bins of its R group maxima: sum the Qerror rows, drop the
+// excluded candidates, argmin with the lowest DID on ties.  Rows hold one byte per dialect; eight of them
+// (8 x 31 = 248) still fit the byte, so rows are summed eight at a time and widened to 16 bits in between.
 // excl_a: LDS offset of this block's SeDA exclusion row (kSeda only).
-template <bool kPair, bool kTwoStage, bool kSeda>
+template <int R, bool kTwoStage, bool kSeda>
+__device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], const uint8_t* lds,
+                                                    const TileConsts& K, uint32_t excl_a)
+{
+    static_assert(R % 8 == 0, "rows are summed eight at a time");
+    uint32_t ev[8], od[8];   // 16-bit sums of dialects (4i, 4i+2) and (4i+1, 4i+3); R == 8 keeps bytes in ev
+    uint32_t binmax = 0;
+#pragma unroll
+    for (int c = 0; c < R / 8; ++c) {
+        uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t gb = gbin[8 * c + j];
+            if (kTwoStage) binmax = max(binmax, gb);
+            const uint8_t* row = lds + K.row_base + (gb << 8);
+            const uint4 r0 = *reinterpret_cast<const uint4*>(row);
+            const uint4 r1 = *reinterpret_cast<const uint4*>(row + 128);
+            acc[0] += r0.x; acc[1] += r0.y; acc[2] += r0.z; acc[3] += r0.w;
+            acc[4] += r1.x; acc[5] += r1.y; acc[6] += r1.z; acc[7] += r1.w;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (R == 8) {
+                ev[i] = acc[i];
+            } else {
+                const uint32_t e = acc[i] & 0x00FF00FFu;
+                const uint32_t o = __builtin_amdgcn_perm(0u, acc[i], 0x0C030C01u);
+                ev[i] = c ? ev[i] + e : e;
+                od[i] = c ? od[i] + o : o;
+            }
+        }
+    }
+    // ---- candidate restrictions (Sec. 3.4 SeDA, Sec. 3.2 two-stage): bytes, 0xFF = excluded
+    uint32_t ea[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (kSeda || kTwoStage) {
+        if (kSeda) {
+            const uint4 a0 = *reinterpret_cast<const uint4*>(lds + excl_a);
+            const uint4 a1 = *reinterpret_cast<const uint4*>(lds + excl_a + 16);
+            ea[0] = a0.x; ea[1] = a0.y; ea[2] = a0.z; ea[3] = a0.w;
+            ea[4] = a1.x; ea[5] = a1.y; ea[6] = a1.z; ea[7] = a1.w;
+        }
+        if (kTwoStage) {
+            // first stage: keep the dialects whose top magnitude is the integer part of the block maximum
+            const uint32_t roff = kLdsRange + (min(max(binmax >> 1, 8u), 15u) - 8u) * 32u;
+            const uint4 r0 = *reinterpret_cast<const uint4*>(lds + roff);
+            const uint4 r1 = *reinterpret_cast<const uint4*>(lds + roff + 16);
+            const uint32_t eb2[8] = {ea[0] | r0.x, ea[1] | r0.y, ea[2] | r0.z, ea[3] | r0.w,
+                                     ea[4] | r1.x, ea[5] | r1.y, ea[6] | r1.z, ea[7] | r1.w};
+            // ... unless that leaves nothing (possible only together with a SeDA list)
+            const bool none = kSeda && ((eb2[0] & eb2[1] & eb2[2] & eb2[3] & eb2[4] & eb2[5] & eb2[6] & eb2[7]) == 0xFFFFFFFFu);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ea[i] = none ? ea[i] : eb2[i];
+        }
+    }
+    // ---- argmin with lowest DID on ties: 16-bit keys (sum << 5 | DID), 32 of them in 16 registers.  An
+    // excluded dialect gets a key no real sum reaches.
+    uint32_t best = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t e, o;
+        if (R == 8) {
+            const uint32_t a = (kSeda || kTwoStage) ? (ev[i] | ea[i]) : ev[i];   // 0xFF > 248 >= any real sum
+            e = a & 0x00FF00FFu;                                  // dialects 4i, 4i+2
+            o = __builtin_amdgcn_perm(0u, a, 0x0C030C01u);        // dialects 4i+1, 4i+3
+        } else {
+            e = ev[i];
+            o = od[i];
+        }
+        uint32_t ke = (e << 5) | K.kdid[2 * i];
+        uint32_t ko = (o << 5) | K.kdid[2 * i + 1];
+        if (R != 8 && (kSeda || kTwoStage)) {
+            const uint32_t xe = ea[i] & 0x00FF00FFu;
+            const uint32_t xo = __builtin_amdgcn_perm(0u, ea[i], 0x0C030C01u);
+            ke |= xe | (xe << 8);                                 // 0xFFFF > (992 << 5 | 31)
+            ko |= xo | (xo << 8);
+        }
+        best = pk_min(best, pk_min(ke, ko));
+    }
+    return halves_min(best) & 31u;
+}
+
+// One lane owns 32 consecutive elements of a row: w = its 32 bf16 as 16 packed pairs, holding one block of
+// 32 or two blocks of 16.  Produces the four code words and the metadata (one 16-bit word, or two for block
+// size 16 with the first block in the low half).  xb / in_range are only used by the plain per-element
+// routine of a tile with special values.
+template <int kBlock, int G, bool kTwoStage, bool kSeda>
 __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint8_t* lds, const TileConsts& K,
                                              const uint16_t* xb, bool in_range, uint32_t excl_a,
                                              uint32_t (&code)[4], uint32_t& meta)
 {
-        // ---- magnitudes and maxima (bf16 bit patterns order like the values)
-        uint32_t a[16];
+    constexpr int NB = 32 / kBlock;     // blocks per lane
+    constexpr int RB = 16 / NB;         // packed registers per block
+    constexpr int PER = kBlock / G;     // elements per group
+    static_assert((kBlock == 32 || kBlock == 16) && (PER == 4 || PER == 2 || PER == 1), "supported shapes");
+    // ---- magnitudes and maxima (bf16 bit patterns order like the values)
+    uint32_t a[16];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) a[k] = w[k] & 0x7FFF7FFFu;
-        uint32_t gm[8];
+    for (int k = 0; k < 16; ++k) a[k] = w[k] & 0x7FFF7FFFu;
+    uint32_t gm[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) gm[j] = pk_max(a[2 * j], a[2 * j + 1]);
-        const uint32_t bm = halves_max(pk_max(pk_max(pk_max(gm[0], gm[1]), pk_max(gm[2], gm[3])),
-                                              pk_max(pk_max(gm[4], gm[5]), pk_max(gm[6], gm[7]))));
-        const bool special = !(bm == 0u || (bm - 0x0280u) < (0x7F80u - 0x0280u));
+    for (int j = 0; j < 8; ++j) gm[j] = pk_max(a[2 * j], a[2 * j + 1]);
+    uint32_t bm[NB];
+    if (NB == 1) {
+        bm[0] = halves_max(pk_max(pk_max(pk_max(gm[0], gm[1]), pk_max(gm[2], gm[3])),
+                                  pk_max(pk_max(gm[4], gm[5]), pk_max(gm[6], gm[7]))));
+    } else {
+        bm[0] = halves_max(pk_max(pk_max(gm[0], gm[1]), pk_max(gm[2], gm[3])));
+        bm[NB - 1] = halves_max(pk_max(pk_max(gm[4], gm[5]), pk_max(gm[6], gm[7])));
+    }
+    bool special = false;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) special = special || !(bm[b] == 0u || (bm[b] - 0x0280u) < (0x7F80u - 0x0280u));
 
-        if (__builtin_amdgcn_ballot_w64(special) != 0) {
-            // rare: some block of this tile holds NaN / Inf or is tiny
-            code[0] = code[1] = code[2] = code[3] = 0;
-            meta = 0;
-            if (in_range) {
-                const BlockCodes r = quantize_block_plain(xb, lds, kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage);
-                code[0] = r.code[0]; code[1] = r.code[1]; code[2] = r.code[2]; code[3] = r.code[3];
-                meta = r.meta;
-            }
-        } else {
-            // ---- shared exponent (Sec. 3.1) and bins (Sec. 3.2), two elements per instruction
-            const uint32_t ebm = bm >> 7;
-            const uint32_t eb = max(ebm, 4u);                       // stored exponent byte
-            const uint32_t ec = (max(ebm, 5u) + 3u) * 0x00010001u;  // shift base in both halves
-            uint32_t b2[16];
+    if (__builtin_amdgcn_ballot_w64(special) != 0) {
+        // rare: some block of this tile holds NaN / Inf or is tiny
+        code[0] = code[1] = code[2] = code[3] = 0;
+        meta = 0;
+        if (in_range) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const uint32_t ef = pk_shr(a[k], 0x00070007u);                 // exponent fields
-                const uint32_t sh = pk_min(pk_sub(ec, ef), 0x000F000Fu);       // >= 3; >= 8 means bin 0
-                const uint32_t sig = (a[k] & K.k7f) | K.k80;                       // 1.m as 8-bit integers
-                b2[k] = pk_shr(sig, sh);                                       // floor(2*xhat), 0..31
-            }
-            // ---- group-wise maxima: group j = elements 4j..4j+3 = registers 2j, 2j+1
-            uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            uint32_t binmax = 0;
+            for (int b = 0; b < NB; ++b) {
+                const BlockCodes r = quantize_block_plain<kBlock, G>(xb + b * kBlock, lds,
+                                                                     kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t gbin = halves_max(pk_max(b2[2 * j], b2[2 * j + 1]));
-                if (kTwoStage) binmax = max(binmax, gbin);
-                const uint8_t* row = lds + K.row_base + (gbin << 8);
-                const uint4 r0 = *reinterpret_cast<const uint4*>(row);
-                const uint4 r1 = *reinterpret_cast<const uint4*>(row + 128);
-                acc[0] += r0.x; acc[1] += r0.y; acc[2] += r0.z; acc[3] += r0.w;
-                acc[4] += r1.x; acc[5] += r1.y; acc[6] += r1.z; acc[7] += r1.w;
-            }
-            // ---- candidate restrictions (Sec. 3.4 SeDA, Sec. 3.2 two-stage): an excluded dialect gets the byte
-            // 0xFF OR-ed into its 8-bit sum, which no real sum (<= 248) reaches
-            if (kSeda || kTwoStage) {
-                uint32_t ea[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (kSeda) {
-                    const uint4 a0 = *reinterpret_cast<const uint4*>(lds + excl_a);
-                    const uint4 a1 = *reinterpret_cast<const uint4*>(lds + excl_a + 16);
-                    ea[0] = a0.x; ea[1] = a0.y; ea[2] = a0.z; ea[3] = a0.w;
-                    ea[4] = a1.x; ea[5] = a1.y; ea[6] = a1.z; ea[7] = a1.w;
-                }
-                if (kTwoStage) {
-                    // first stage: keep the dialects whose top magnitude is the integer part of the block maximum
-                    const uint32_t roff = kLdsRange + (min(max(binmax >> 1, 8u), 15u) - 8u) * 32u;
-                    const uint4 r0 = *reinterpret_cast<const uint4*>(lds + roff);
-                    const uint4 r1 = *reinterpret_cast<const uint4*>(lds + roff + 16);
-                    const uint32_t eb2[8] = {ea[0] | r0.x, ea[1] | r0.y, ea[2] | r0.z, ea[3] | r0.w,
-                                             ea[4] | r1.x, ea[5] | r1.y, ea[6] | r1.z, ea[7] | r1.w};
-                    // ... unless that leaves nothing (possible only together with a SeDA list)
-                    const bool none = kSeda && ((eb2[0] & eb2[1] & eb2[2] & eb2[3] & eb2[4] & eb2[5] & eb2[6] & eb2[7]) == 0xFFFFFFFFu);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) ea[i] = none ? ea[i] : eb2[i];
-                }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] |= ea[i];
-            }
-            // ---- argmin with lowest DID on ties: 16-bit keys (sum << 5 | DID), 32 of them in 16 registers
-            uint32_t best = 0xFFFFFFFFu;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t ev = acc[i] & 0x00FF00FFu;                             // dialects 4i, 4i+2
-                const uint32_t od = __builtin_amdgcn_perm(0u, acc[i], 0x0C030C01u);   // dialects 4i+1, 4i+3
-                const uint32_t ke = (ev << 5) | K.kdid[2 * i];
-                const uint32_t ko = (od << 5) | K.kdid[2 * i + 1];
-                best = pk_min(best, pk_min(ke, ko));
-            }
-            const uint32_t did = halves_min(best) & 31u;
-            meta = did | (eb << 8);
-            // ---- emit: every element through Qvalue of the chosen dialect
-            const uint32_t pbase = (kPair ? kLdsPair : kLdsNibT) + did;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                uint32_t byte[4];
-#pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    if (kPair) {
-                        // two elements per lookup through the pair table
-                        byte[m] = lds[dot2_u16(b2[4 * c + m], K.kpair, pbase)];
-                    } else {
-                        const uint32_t bb = b2[4 * c + m] << 5;      // bin * 32 in both halves
-                        byte[m] = (uint32_t)lds[pbase + (bb & 0xFFFFu)] | ((uint32_t)lds[pbase + (bb >> 16)] << 4);
-                    }
-                }
-                uint32_t v = byte[0] | (byte[1] << 8) | (byte[2] << 16) | (byte[3] << 24);
-                // sign bits: element 2m -> bit 8m+3, element 2m+1 -> bit 8m+7
-                const uint32_t x01 = __builtin_amdgcn_perm(w[4 * c + 1], w[4 * c + 0], 0x07030501u);  // b1(w0) b1(w1) b3(w0) b3(w1)
-                const uint32_t x23 = __builtin_amdgcn_perm(w[4 * c + 3], w[4 * c + 2], 0x07030501u);
-                const uint32_t lo = __builtin_amdgcn_perm(x23, x01, 0x05040100u);   // b1 of w0..w3
-                const uint32_t hi = __builtin_amdgcn_perm(x23, x01, 0x07060302u);   // b3 of w0..w3
-                v |= ((lo >> 4) & 0x08080808u) | (hi & 0x80808080u);
-                code[c] = v;
+                for (int c = 0; c < 4 / NB; ++c) code[b * (4 / NB) + c] = r.code[c];
+                meta |= r.meta << (16 * b);
             }
         }
+    } else {
+        uint32_t b2[16];
+        uint32_t did[NB];
+        meta = 0;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            // ---- shared exponent (Sec. 3.1) and bins (Sec. 3.2), two elements per instruction
+            const uint32_t ebm = bm[b] >> 7;
+            const uint32_t eb = max(ebm, 4u);                       // stored exponent byte
+            const uint32_t ec = (max(ebm, 5u) + 3u) * 0x00010001u;  // shift base in both halves
+#pragma unroll
+            for (int k = b * RB; k < (b + 1) * RB; ++k) {
+                const uint32_t ef = pk_shr(a[k], 0x00070007u);                 // exponent fields
+                const uint32_t sh = pk_min(pk_sub(ec, ef), 0x000F000Fu);       // >= 3; >= 8 means bin 0
+                const uint32_t sig = (a[k] & K.k7f) | K.k80;                   // 1.m as 8-bit integers
+                b2[k] = pk_shr(sig, sh);                                       // floor(2*xhat), 0..31
+            }
+            // ---- group-wise maxima: groups are runs of PER elements
+            uint32_t gbin[G];
+#pragma unroll
+            for (int r = 0; r < G; ++r) {
+                if (PER == 4) gbin[r] = halves_max(pk_max(b2[b * RB + 2 * r], b2[b * RB + 2 * r + 1]));
+                else if (PER == 2) gbin[r] = halves_max(b2[b * RB + r]);
+                else gbin[r] = (r & 1) ? (b2[b * RB + r / 2] >> 16) : (b2[b * RB + r / 2] & 0xFFFFu);
+            }
+            did[b] = select_lut_rows<G, kTwoStage, kSeda>(gbin, lds, K, excl_a);
+            meta |= (did[b] | (eb << 8)) << (16 * b);
+        }
+        // ---- emit: every element through Qvalue of the chosen dialect, two elements per pair-table lookup
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t pbase = kLdsPair + did[c / (4 / NB)];
+            uint32_t byte[4];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) byte[m] = lds[dot2_u16(b2[4 * c + m], K.kpair, pbase)];
+            uint32_t v = byte[0] | (byte[1] << 8) | (byte[2] << 16) | (byte[3] << 24);
+            // sign bits: element 2m -> bit 8m+3, element 2m+1 -> bit 8m+7
+            const uint32_t x01 = __builtin_amdgcn_perm(w[4 * c + 1], w[4 * c + 0], 0x07030501u);  // b1(w0) b1(w1) b3(w0) b3(w1)
+            const uint32_t x23 = __builtin_amdgcn_perm(w[4 * c + 3], w[4 * c + 2], 0x07030501u);
+            const uint32_t lo = __builtin_amdgcn_perm(x23, x01, 0x05040100u);   // b1 of w0..w3
+            const uint32_t hi = __builtin_amdgcn_perm(x23, x01, 0x07060302u);   // b3 of w0..w3
+            v |= ((lo >> 4) & 0x08080808u) | (hi & 0x80808080u);
+            code[c] = v;
+        }
+    }
 }
 
 // Address of block gb's first element, in elements from p.x.
@@ -341,9 +406,10 @@ __device__ __forceinline__ Block64 load_block(const FastParams& p, uint32_t gb)
     return b;
 }
 
-// Writes one tile's results: 16 bytes of codes per lane and the 16-bit metadata words.  When the whole
-// tile is in range and the metadata array is 16-byte aligned, eight neighbouring lanes gather their
-// metadata into one 16-byte store (sub-dword stores are slow to coalesce).
+// Writes one tile's results: 16 bytes of codes per lane and the metadata words.  When the whole tile is in
+// range and the metadata array is 16-byte aligned, eight neighbouring lanes gather their 16-bit metadata
+// into one 16-byte store (sub-dword stores are slow to coalesce); block size 16 has one dword per lane.
+template <int kBlock>
 __device__ __forceinline__ void store_tile(const FastParams& p, uint32_t gb, uint32_t lane, const uint4& code,
                                            uint32_t meta, bool meta_aligned)
 {
@@ -353,34 +419,39 @@ __device__ __forceinline__ void store_tile(const FastParams& p, uint32_t gb, uin
         typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
         const u32x4s cv = {code.x, code.y, code.z, code.w};
         __builtin_nontemporal_store(cv, reinterpret_cast<u32x4s*>(p.codes + (size_t)gb * 16));
-        const uint32_t m = meta & 0xFFFFu;
-        const uint32_t m1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x101, 0xF, 0xF, true);    // lane i <- i+1
-        const uint32_t p2 = m | (m1 << 16);
-        const uint32_t q2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)p2, 0x102, 0xF, 0xF, true);   // lane i <- i+2
-        const uint32_t r0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)p2, 0x104, 0xF, 0xF, true);   // lane i <- i+4
-        const uint32_t r1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)q2, 0x104, 0xF, 0xF, true);
-        const u32x4s mv = {p2, q2, r0, r1};
-        if ((lane & 7u) == 0u) __builtin_nontemporal_store(mv, reinterpret_cast<u32x4s*>(p.meta + gb));
+        if (kBlock == 16) {
+            __builtin_nontemporal_store(meta, reinterpret_cast<uint32_t*>(p.meta) + gb);
+        } else {
+            const uint32_t m = meta & 0xFFFFu;
+            const uint32_t m1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x101, 0xF, 0xF, true);    // lane i <- i+1
+            const uint32_t p2 = m | (m1 << 16);
+            const uint32_t q2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)p2, 0x102, 0xF, 0xF, true);   // lane i <- i+2
+            const uint32_t r0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)p2, 0x104, 0xF, 0xF, true);   // lane i <- i+4
+            const uint32_t r1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)q2, 0x104, 0xF, 0xF, true);
+            const u32x4s mv = {p2, q2, r0, r1};
+            if ((lane & 7u) == 0u) __builtin_nontemporal_store(mv, reinterpret_cast<u32x4s*>(p.meta + gb));
+        }
     } else if (gb < p.n_blocks) {
         *reinterpret_cast<uint4*>(p.codes + (size_t)gb * 16) = code;
-        p.meta[gb] = (uint16_t)meta;
+        if (kBlock == 16) reinterpret_cast<uint32_t*>(p.meta)[gb] = meta;   // the launcher checks 4-byte alignment
+        else p.meta[gb] = (uint16_t)meta;
     }
 }
 
-template <bool kFlat, bool kTwoStage, bool kSeda>
-__global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams p)
+template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda>
+__global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p)
 {
     __shared__ __align__(16) uint8_t lds[kSeda ? kLdsFastBytesSeda : kLdsFastBytes];
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // Tiles of workgroup b are b, b + G, b + 2G, ... (G = number of workgroups).  The waves of a workgroup
+    // Tiles of workgroup b are b, b + W, b + 2W, ... (W = number of workgroups).  The waves of a workgroup
     // take them from a shared counter as they become free, so a wave that runs ahead of its neighbours
     // keeps working instead of idling at the end.
     __shared__ uint32_t wg_next;
-    const uint32_t G = gridDim.x;
+    const uint32_t W = gridDim.x;
     Block64 cur;
-    uint32_t t = blockIdx.x + wave * G;                      // first tile: static
-    uint32_t t_next = blockIdx.x + (kFastWaves + wave) * G;   // second tile: static
+    uint32_t t = blockIdx.x + wave * W;                      // first tile: static
+    uint32_t t_next = blockIdx.x + (kFastWaves + wave) * W;   // second tile: static
     if (threadIdx.x == 0) wg_next = 2 * kFastWaves;
     // the first tile is requested before anything else: it streams in while the tables are built
     cur = load_block<kFlat, kSeda>(p, t * 64u + lane);
@@ -454,15 +525,15 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
             kLdsSeda + 32u * ((cur.grp >= 0 && (uint32_t)cur.grp < p.n_groups) ? (uint32_t)cur.grp : p.n_groups);
         // the previous tile's stores must not be scheduled above the arrival of this tile's input
         asm volatile("" : "+v"(held_meta) : "v"(w[0]), "v"(w[15]));
-        if (have_held) store_tile(p, held_gb, lane, held_code, held_meta, meta_aligned);
+        if (have_held) store_tile<kBlock>(p, held_gb, lane, held_code, held_meta, meta_aligned);
         have_held = true;
         // the next tile's loads go out before this tile's arithmetic
         cur = load_block<kFlat, kSeda>(p, (t_next < p.n_tiles) ? t_next * 64u + lane : 0xFFFFFFFFu);
         uint32_t claim = 0;
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
-        const uint32_t t_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * G;
+        const uint32_t t_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
         uint32_t code[4], meta;
-        compute_tile<true, kTwoStage, kSeda>(w, lds, K, p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u),
+        compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u),
                                              gb < p.n_blocks, excl_a, code, meta);
         held_code = make_uint4(code[0], code[1], code[2], code[3]);
         held_meta = meta;
@@ -470,7 +541,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut8_kernel(FastParams 
         t = t_next;
         t_next = t_after;
     }
-    if (have_held) store_tile(p, held_gb, lane, held_code, held_meta, meta_aligned);
+    if (have_held) store_tile<kBlock>(p, held_gb, lane, held_code, held_meta, meta_aligned);
 }
 
 }  // namespace fb4

@@ -18,7 +18,7 @@ from oracle import fb4_oracle as O
 
 pytestmark = pytest.mark.gpu
 
-SELECTORS = [("lut8", 1, 8), ("lut32", 1, 32), ("sse", 0, 8)]
+SELECTORS = [("lut8", 1, 8), ("lut32", 1, 32), ("sse", 0, 8), ("lut16", 1, 16)]
 
 
 @pytest.fixture(scope="module")
@@ -446,6 +446,35 @@ def test_block16_seda_and_degenerate_values(F, luts, name, sel, g):
     compare_quant(DEFAULT_FORMATBOOK, xe, host_u8(c), host_u16(m), cr, mr, sel, g, block=16,
                   what="block16 edge " + name)
     assert np.array_equal(synth.bf16_bits(y), O.dequantize(DEFAULT_FORMATBOOK, cr, mr, block=16))
+
+
+@pytest.mark.parametrize("block", [32, 16])
+def test_outputs_without_wide_alignment_and_many_seda_groups(F, luts, block):
+    """Requests the streaming kernels do not serve (4-byte aligned codes, 2-byte aligned metadata, more SeDA
+    groups than fit their LDS) take the generic kernels and give the same results."""
+    rows, cols = 96, 1024
+    x = synth.vdit_activation(rows=rows, cols=cols, seed=50, device="cuda")
+    xb = synth.bf16_bits(x)
+    o = F.opts(block=block)
+    cbuf = torch.zeros(rows * cols // 2 + 16, dtype=torch.uint8, device="cuda")
+    mbuf = torch.zeros(rows * (cols // block) + 8, dtype=torch.int16, device="cuda")
+    codes = cbuf[4:4 + rows * cols // 2].view(rows, cols // 2)
+    meta = mbuf[1:1 + rows * (cols // block)].view(rows, cols // block)
+    assert codes.data_ptr() % 16 == 4 and meta.data_ptr() % 4 == 2
+    F.fb4_quantize(luts, o, x, codes=codes, meta=meta)
+    y = F.fb4_dequantize(luts, codes, meta, block=block)
+    torch.cuda.synchronize()
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, block=block)
+    assert np.array_equal(host_u8(codes), cr) and np.array_equal(host_u16(meta), mr)
+    assert np.array_equal(synth.bf16_bits(y), O.dequantize(DEFAULT_FORMATBOOK, cr, mr, block=block))
+    assert int(cbuf[:4].sum()) == 0 and int(cbuf[4 + rows * cols // 2:].sum()) == 0 and int(mbuf[0]) == 0
+    # 2000 SeDA groups
+    sub = synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, n_groups=2000, seed=51)
+    tg = ((np.arange(rows) * 37) % 2000).astype(np.int32)
+    c, m = F.fb4_quantize_seda(luts, o, x, torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda())
+    torch.cuda.synchronize()
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, block=block, token_group=tg, sub_formatbooks=sub)
+    assert np.array_equal(host_u8(c), cr) and np.array_equal(host_u16(m), mr)
 
 
 def test_luts_handle_is_reusable_across_streams(F, luts):
