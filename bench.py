@@ -220,6 +220,13 @@ def main():
             k = i % N_SETS
             F.fb4_dequantize(luts, codes[k], metas[k], codes2=c2, meta2=m2, salient_rows=sal_d, out=outs[k])
         add("dequantize_bf16_with_5pct_second_plane", deq_step, abytes + dbytes, n_el)
+        els = [torch.empty((ROWS, COLS), dtype=torch.uint8, device="cuda") for _ in range(N_SETS)]
+        scs = [torch.empty((ROWS, COLS // 32), dtype=torch.uint8, device="cuda") for _ in range(N_SETS)]
+
+        def repack_step(i):
+            k = i % N_SETS
+            F.fb4_repack_mxfp8(luts, codes[k], metas[k], elems=els[k], scales=scs[k])
+        add("repack_mxfp8", repack_step, n_el // 2 + n_el // 16 + n_el + n_el // 32, n_el)
         result["extras"] = extras
 
     # ---- CPU oracle on the host cores of this machine (a baseline for context, not a target)

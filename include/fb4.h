@@ -189,6 +189,29 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
                    const uint16_t* meta2, const int32_t* salient_rows, int64_t n_sal, void* out,
                    int out_dtype, int64_t out_row_stride, void* stream);
 
+/*
+ * Sec. 4.5 and App. E.2 (MXFP8 compatibility: the magnitudes 0..15 are exact
+ * in FP8 E4M3 and the block scale is a power of two): re-encode one code plane
+ * as MXFP8 operands for a block-scaled FP8 matrix unit, without going through
+ * 16-bit values.  A salient row's second plane is repacked by a second call on
+ * (codes2, meta2).
+ *   codes, meta   device, one plane as written by fb4_quantize* / fb4_decompose
+ *   cols          a multiple of 32 (FB4_ERR_UNSUPPORTED otherwise)
+ *   elems         device, uint8 [rows][elem_row_stride]: OCP FP8 E4M3 (bias 7,
+ *                 no infinities), sign bit copied from the code; rows 8-byte
+ *                 aligned
+ *   scales        device, uint8 [rows][cols/32], contiguous: E8M0, value 2^(s-127)
+ * Block size 32: s = exponent byte - 3 and every element is its integer
+ * magnitude, so elems * scale equals fb4_dequantize exactly.  Block size 16:
+ * the two blocks of an MX block share the larger exponent; the elements of the
+ * other block are magnitude * 2^-k (k = exponent difference) rounded to
+ * nearest even in E4M3, which is exact for k <= 9 and zero for k >= 14.
+ * A DID >= n_dialects gives zero magnitudes.
+ */
+int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t* meta, int64_t rows,
+                     int64_t cols, int block, uint8_t* elems, int64_t elem_row_stride,
+                     uint8_t* scales, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -505,3 +505,64 @@ int fb4o_dequantize(const uint8_t* fbk, int n_dialects, int block, const uint8_t
     (void)nthreads;
     return 0;
 }
+
+/* ------------------------------------------------------------------ */
+/* MXFP8 operands                                                      */
+/* ------------------------------------------------------------------ */
+
+/* OCP FP8 E4M3 encoding (bias 7, 3 mantissa bits, subnormals down to 2^-9,
+ * no infinities) of a finite 0 <= v < 448, round to nearest, ties to even. */
+static uint8_t e4m3_of(double v)
+{
+    if (v == 0.0) return 0;
+    int ex;
+    (void)frexp(v, &ex); /* v = f * 2^ex, f in [0.5, 1) */
+    int e = ex - 1;      /* floor(log2 v) */
+    if (e < -6) e = -6;  /* subnormals share the spacing of the smallest normal binade */
+    double n = nearbyint(ldexp(v, 3 - e)); /* v in units of the spacing 2^(e-3); default rounding = ties to even */
+    if (n < 8.0) return (uint8_t)n;        /* subnormal (only reachable with e == -6) */
+    if (n == 16.0) {
+        e += 1;
+        n = 8.0;
+    }
+    return (uint8_t)(((e + 7) << 3) | ((int)n - 8));
+}
+
+/* Sec. 4.5 / App. E.2: the integer magnitudes 0..15 are exact in FP8 E4M3 and
+ * the block scale is a power of two, so a code plane is an MXFP8 operand: per
+ * 32 elements one E8M0 scale byte s (scale 2^(s-127)) and 32 E4M3 bytes.
+ * Block size 32: s = (e+127) - 3 and element = +/- magnitude, exact.  Block
+ * size 16: the two blocks of an MX block share the larger exponent; the
+ * elements of the other one are magnitude * 2^(e_small - e_large), rounded to
+ * E4M3 (exact while the exponents differ by at most 9).
+ * elems [rows][cols] bytes, scales [rows][cols/32]; cols % 32 == 0. */
+int fb4o_repack_mxfp8(const uint8_t* fbk, int n_dialects, int block, const uint8_t* codes,
+                      const uint16_t* meta, int64_t rows, int64_t cols, uint8_t* elems, uint8_t* scales)
+{
+    if (fb4o_validate_formatbook(fbk, n_dialects)) return -1;
+    if ((block != 16 && block != 32) || rows < 0 || cols < 0 || cols % 32) return -1;
+    int64_t nb = cols / block;
+    for (int64_t i = 0; i < rows * nb; ++i)
+        if ((meta[i] & 0xFF) >= n_dialects) return -1;
+    int per = 32 / block; /* FB4 blocks per MX block */
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t q = 0; q < cols / 32; ++q) {
+            int emax = 0;
+            for (int k = 0; k < per; ++k) {
+                int eb = meta[r * nb + q * per + k] >> 8;
+                if (eb > emax) emax = eb;
+            }
+            scales[r * (cols / 32) + q] = (uint8_t)(emax - 3);
+            for (int i = 0; i < 32; ++i) {
+                int64_t c = q * 32 + i;
+                uint16_t m = meta[r * nb + c / block];
+                int nib = nibble_at(codes + r * (cols / 2), c);
+                double mag = (double)fbk[(m & 0xFF) * 8 + (nib & 7)];
+                double v = ldexp(mag, (int)(m >> 8) - emax);
+                elems[r * cols + c] = (uint8_t)(e4m3_of(v) | ((nib & 8) << 4));
+            }
+        }
+    }
+    return 0;
+}
+

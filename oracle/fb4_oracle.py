@@ -49,6 +49,7 @@ def _load():
         lib.fb4o_decompose.argtypes = [p, i32, i32, i32, i32, i32, p, i64, i64, i64, p, p, p, i64,
                                        p, p, i32, p, p, i32]
         lib.fb4o_dequantize.argtypes = [p, i32, i32, p, p, i64, i64, p, p, p, i64, p, i32, i64, i32]
+        lib.fb4o_repack_mxfp8.argtypes = [p, i32, i32, p, p, i64, i64, p, p]
         _lib = lib
     return _lib
 
@@ -153,3 +154,19 @@ def dequantize(fbk, codes1, meta1, block=32, codes2=None, meta2=None, salient_ro
     if rc != 0:
         raise ValueError("fb4o_dequantize: invalid argument")
     return out
+
+
+def repack_mxfp8(fbk, codes, meta, block=32):
+    """One code plane as MXFP8 operands: (E4M3 bytes [rows][cols], E8M0 scale bytes [rows][cols/32])."""
+    fbk = _c(fbk, np.uint8)
+    codes = _c(codes, np.uint8)
+    meta = _c(meta, np.uint16)
+    rows, half = codes.shape
+    cols = half * 2
+    elems = np.zeros((rows, cols), dtype=np.uint8)
+    scales = np.zeros((rows, cols // 32), dtype=np.uint8)
+    rc = _load().fb4o_repack_mxfp8(_ptr(fbk), fbk.shape[0], block, _ptr(codes), _ptr(meta), rows, cols,
+                                   _ptr(elems), _ptr(scales))
+    if rc != 0:
+        raise ValueError("fb4o_repack_mxfp8: invalid argument")
+    return elems, scales

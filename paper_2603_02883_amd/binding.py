@@ -59,13 +59,15 @@ def _load():
     lib.fb4_decompose.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, p, i64, p, p, i32,
                                   p, p, p]
     lib.fb4_dequantize.argtypes = [p, p, p, i64, i64, i32, p, p, p, i64, p, i32, i64, p]
+    lib.fb4_repack_mxfp8.argtypes = [p, p, p, i64, i64, i32, p, i64, p, p]
     return lib
 
 
 _lib = _load()
 
 EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts", "fb4_build_luts_host",
-           "fb4_free_luts", "fb4_quantize", "fb4_quantize_seda", "fb4_decompose", "fb4_dequantize"]
+           "fb4_free_luts", "fb4_quantize", "fb4_quantize_seda", "fb4_decompose", "fb4_dequantize",
+           "fb4_repack_mxfp8"]
 
 
 def lib():
@@ -205,3 +207,17 @@ def fb4_dequantize(luts, codes1, meta1, block=32, codes2=None, meta2=None, salie
                              _stream(stream))
     _check(rc, "fb4_dequantize")
     return out
+
+
+def fb4_repack_mxfp8(luts, codes, meta, block=32, elems=None, scales=None, stream=None):
+    """One code plane as MXFP8 operands: (E4M3 bytes uint8 [rows][cols], E8M0 scale bytes uint8 [rows][cols/32])."""
+    rows, half = codes.shape
+    cols = half * 2
+    if elems is None:
+        elems = torch.empty((rows, cols), dtype=torch.uint8, device=codes.device)
+    if scales is None:
+        scales = torch.empty((rows, cols // 32), dtype=torch.uint8, device=codes.device)
+    rc = _lib.fb4_repack_mxfp8(luts.handle, _dp(codes), _dp(meta), rows, cols, block, _dp(elems),
+                               elems.stride(0) if rows > 1 else cols, _dp(scales), _stream(stream))
+    _check(rc, "fb4_repack_mxfp8")
+    return elems, scales

@@ -10,6 +10,7 @@
 #include "fb4_dequant_fast.hpp"
 #include "fb4_fast.hpp"
 #include "fb4_kernels.hpp"
+#include "fb4_repack.hpp"
 #include "fb4_tables.hpp"
 
 struct fb4_luts {
@@ -354,21 +355,23 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
     p.block_shift = block == 32 ? 5 : 4;
     p.blob = luts->dev_blob;
     int grid = grid_for(luts, p.n_tiles);
-    const uint64_t n_blocks = (uint64_t)rows * (uint64_t)p.nb;
-    if (block == 32 && aligned(codes1, 16) && aligned(out, 16) && n_blocks < 0x3FFFFF00ull) {
-        // plane 1 of every row: one lane per block, pair table in LDS
+    const uint64_t nb32 = (uint64_t)cols / 32;          // 32-element chunks per row
+    const uint64_t n_blocks = (uint64_t)rows * nb32;
+    if ((cols % 32) == 0 && aligned(codes1, 16) && aligned(out, 16) && n_blocks < 0x3FFFFF00ull) {
+        // plane 1 of every row: one lane per code word, pair table in LDS
         DeqFastParams f = {};
         f.codes = codes1;
         f.meta = meta1;
+        f.meta_shift = block == 32 ? 2 : 1;
         f.out = out;
         f.out_row_stride = out_row_stride;
-        f.nb = (uint32_t)p.nb;
+        f.nb = (uint32_t)nb32;
         f.n_blocks = (uint32_t)n_blocks;
         f.n_tiles = (uint32_t)((n_blocks + 63) / 64);
         uint32_t l = 0;
-        while ((1ull << l) < (uint64_t)p.nb) ++l;
+        while ((1ull << l) < nb32) ++l;
         f.div_shift = 31 + l;
-        f.div_mul = (uint32_t)(((1ull << f.div_shift) + (uint64_t)p.nb - 1) / (uint64_t)p.nb);
+        f.div_mul = (uint32_t)(((1ull << f.div_shift) + nb32 - 1) / nb32);
         f.blob = luts->dev_blob;
         long long groups = ((long long)f.n_tiles + kDeqWaves - 1) / kDeqWaves;
         const long long cap = (long long)luts->n_cu * 2;
@@ -402,6 +405,48 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
         if (hipGetLastError() != hipSuccess) return FB4_ERR_HIP;
     }
     return FB4_OK;
+}
+
+int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t* meta, int64_t rows, int64_t cols,
+                     int block, uint8_t* elems, int64_t elem_row_stride, uint8_t* scales, void* stream)
+{
+    if (!luts) return FB4_ERR_INVALID_ARG;
+    if (block != 32 && block != 16) return FB4_ERR_INVALID_ARG;
+    if (rows < 0 || cols < 0 || elem_row_stride < cols) return FB4_ERR_INVALID_ARG;
+    if (cols % 32) return FB4_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return FB4_OK;
+    if (!codes || !meta || !elems || !scales) return FB4_ERR_INVALID_ARG;
+    if (!aligned(codes, 4) || !aligned(meta, 2) || !aligned(elems, 8) || (elem_row_stride % 8))
+        return FB4_ERR_UNSUPPORTED;
+    const uint64_t nb32 = (uint64_t)cols / 32;
+    const uint64_t n_chunks = (uint64_t)rows * nb32;
+    if (n_chunks >= 0x3FFFFF00ull) return FB4_ERR_UNSUPPORTED;
+    RepackParams f = {};
+    f.codes = codes;
+    f.meta = meta;
+    f.elems = elems;
+    f.elem_row_stride = elem_row_stride;
+    f.scales = scales;
+    f.nb32 = (uint32_t)nb32;
+    f.n_chunks = (uint32_t)n_chunks;
+    uint32_t l = 0;
+    while ((1ull << l) < nb32) ++l;
+    f.div_shift = 31 + l;
+    f.div_mul = (uint32_t)(((1ull << f.div_shift) + nb32 - 1) / nb32);
+    f.blob = luts->dev_blob;
+    long long groups = ((long long)n_chunks * 4 + kRepackThreads - 1) / kRepackThreads;
+    const long long cap = (long long)luts->n_cu * 4;
+    if (groups > cap) groups = cap;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool flat = elem_row_stride == cols;
+    if (block == 16) {
+        if (flat) hipLaunchKernelGGL((repack_mxfp8_kernel<true, true>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
+        else hipLaunchKernelGGL((repack_mxfp8_kernel<false, true>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
+    } else {
+        if (flat) hipLaunchKernelGGL((repack_mxfp8_kernel<true, false>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
+        else hipLaunchKernelGGL((repack_mxfp8_kernel<false, false>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
+    }
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
 }  // extern "C"

@@ -21,8 +21,9 @@ constexpr int kDeqThreads = 512;
 constexpr int kDeqWaves = kDeqThreads / 64;
 
 struct DeqFastParams {
-    const uint8_t* codes;     // [n_blocks][16]
-    const uint16_t* meta;     // [n_blocks]
+    const uint8_t* codes;     // [n_blocks][16]; a "block" here is a 32-element chunk of a row
+    const uint16_t* meta;     // one word per 4 code words (block size 32) or per 2 (block size 16)
+    uint32_t meta_shift;      // 2 or 1
     void* out;                // bf16 or fp32, [rows][out_row_stride]
     long long out_row_stride; // elements
     uint32_t nb, n_blocks, n_tiles, div_mul, div_shift;
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(DeqFastPar
             mw[u] = 0;
             if (i < n_words) {
                 cw[u] = reinterpret_cast<const uint32_t*>(p.codes)[i];
-                mw[u] = p.meta[i >> 2];
+                mw[u] = p.meta[i >> p.meta_shift];
             }
         }
 #pragma unroll

@@ -477,6 +477,41 @@ def test_outputs_without_wide_alignment_and_many_seda_groups(F, luts, block):
     assert np.array_equal(host_u8(c), cr) and np.array_equal(host_u16(m), mr)
 
 
+# ------------------------------------------------------------ MXFP8 operands
+@pytest.mark.parametrize("block", [32, 16])
+def test_mxfp8_repack(F, luts, block):
+    fbk = DEFAULT_FORMATBOOK
+    for rows, cols, stride, seed in ((1024, 3072, 3072, 52), (2, 32, 32, 54), (37, 32 * 19, 32 * 19 + 8, 53)):
+        x = synth.vdit_activation(rows=rows, cols=cols, seed=seed, device="cuda")
+        if block == 16:
+            # neighbouring blocks far apart in magnitude: exercises the shifted, rounded elements
+            gen = torch.Generator(device="cpu").manual_seed(seed)
+            gap = torch.randint(0, 16, (rows, cols // 16), generator=gen).cuda()
+            x = (x.float() * torch.exp2(-gap.float()).repeat_interleave(16, dim=1)).to(torch.bfloat16)
+        o = F.opts(block=block)
+        c, m = F.fb4_quantize(luts, o, x)
+        out = torch.full((rows, stride), 0x55, dtype=torch.uint8, device="cuda")
+        el, sc = F.fb4_repack_mxfp8(luts, c, m, block=block, elems=out[:, :cols])
+        torch.cuda.synchronize()
+        elr, scr = O.repack_mxfp8(fbk, host_u8(c), host_u16(m), block=block)
+        assert np.array_equal(host_u8(sc), scr)
+        assert np.array_equal(host_u8(out)[:, :cols], elr)
+        assert bool((out[:, cols:] == 0x55).all())
+        if block == 32:
+            # exact: E4M3 value times the E8M0 scale is the decoded tensor
+            v = out[:, :cols].contiguous().view(torch.float8_e4m3fn).float()
+            y = F.fb4_dequantize(luts, c, m, out_dtype=F.DTYPE_F32)
+            scale = torch.exp2(sc.float() - 127).repeat_interleave(32, dim=1)
+            assert torch.equal(v * scale, y)
+    # the second plane of salient rows is repacked the same way
+    sal = torch.arange(0, rows, 1, dtype=torch.int32, device="cuda")
+    c2, m2 = F.fb4_decompose(luts, o, x, c, m, sal)
+    el2, sc2 = F.fb4_repack_mxfp8(luts, c2, m2, block=block)
+    torch.cuda.synchronize()
+    elr, scr = O.repack_mxfp8(fbk, host_u8(c2), host_u16(m2), block=block)
+    assert np.array_equal(host_u8(el2), elr) and np.array_equal(host_u8(sc2), scr)
+
+
 def test_luts_handle_is_reusable_across_streams(F, luts):
     x = synth.gaussian_outlier(rows=256, cols=1024, seed=45, device="cuda")
     o = F.opts()

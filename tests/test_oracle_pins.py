@@ -562,3 +562,75 @@ def test_block_size_16(fbk):
         if sel == O.SEL_SSE:
             assert np.array_equal(m16.ravel(), m32.ravel())
             assert np.array_equal(c16.reshape(-1, 8), c32[:, :8])
+
+
+# ------------------------------------------------------------ MXFP8 operands
+def _mx_value(elems, scales):
+    """Decode MXFP8 operands with torch's own FP8 type: E4M3 value * 2^(scale byte - 127)."""
+    v = torch.from_numpy(elems.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    s = np.ldexp(1.0, scales.astype(np.int64) - 127)
+    return v * np.repeat(s, 32, axis=1)
+
+
+def test_mxfp8_repack_of_block32_decodes_to_the_same_values(fbk):
+    # Sec. 4.5 / App. E.2: magnitudes 0..15 are exact in E4M3 and the scale is a power of two
+    x = synth.bf16_bits(synth.vdit_activation(rows=24, cols=512, seed=34))
+    c, m = O.quantize(fbk, x)
+    el, sc = O.repack_mxfp8(fbk, c, m)
+    assert el.shape == (24, 512) and sc.shape == (24, 16)
+    y = O.dequantize(fbk, c, m, out_dtype=O.OUT_F32).astype(np.float64)
+    assert np.array_equal(_mx_value(el, sc), y)
+    # the sign bit travels even when the magnitude is zero (same convention as the codes)
+    nib = np.stack([c & 15, c >> 4], axis=2).reshape(24, 512)
+    assert np.array_equal(el >> 7, nib >> 3)
+    # every element is one of the sixteen integers, so the low mantissa pattern is that of torch's conversion
+    mags = torch.arange(16, dtype=torch.float32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert set(np.unique(el & 0x7F).tolist()) <= set(mags.tolist())
+
+
+def test_mxfp8_repack_of_block16_shares_the_larger_exponent(fbk):
+    rng = np.random.default_rng(35)
+    rows, cols = 16, 256
+    # neighbouring 16-element blocks with very different magnitudes: exponent gaps 0..14
+    base = rng.standard_normal((rows, cols)).astype(np.float32)
+    gap = rng.integers(0, 15, size=(rows, cols // 16))
+    x = f2b(base * np.repeat(np.ldexp(1.0, -gap), 16, axis=1).astype(np.float32))
+    c, m = O.quantize(fbk, x, block=16)
+    el, sc = O.repack_mxfp8(fbk, c, m, block=16)
+    eb = (m >> 8).astype(np.int64).reshape(rows, cols // 32, 2)
+    assert np.array_equal(sc, (eb.max(axis=2) - 3).astype(np.uint8))
+    # each element is torch's round-to-nearest-even E4M3 of (decoded value / MX scale)
+    y = O.dequantize(fbk, c, m, block=16, out_dtype=O.OUT_F32).astype(np.float64)
+    scale = np.repeat(np.ldexp(1.0, sc.astype(np.int64) - 127), 32, axis=1)
+    want = torch.from_numpy((y / scale).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    nz = (el & 0x7F) != 0
+    assert np.array_equal(el[nz], want[nz])
+    assert np.array_equal(el & 0x7F, want & 0x7F)
+    # exact whenever the two exponents of an MX block differ by at most 9
+    close = np.repeat((eb.max(axis=2) - eb.min(axis=2)) <= 9, 32, axis=1)
+    assert close.any() and (~close).any()
+    assert np.array_equal(_mx_value(el, sc)[close], y[close])
+
+
+def test_e4m3_rounding_of_the_oracle_on_every_shifted_magnitude():
+    # two dialects that together hold every magnitude 0..15; an MX block made of a 16-element block with
+    # exponent byte 130 - k and one with 130, k = 0..20: the first block's elements are m * 2^-k in units of
+    # the shared scale, compared one by one with torch's conversion (normals, subnormals, ties, underflow)
+    fb = np.array([[0, 1, 2, 3, 4, 5, 6, 8], [0, 7, 10, 11, 12, 13, 14, 15]], dtype=np.uint8)
+    idx = np.arange(8)
+    top = torch.tensor([15.0]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()[0]
+    seen = set()
+    for k in range(0, 21):
+        for did in (0, 1):
+            codes = np.zeros((1, 16), dtype=np.uint8)
+            codes[0, :8] = (idx | (idx << 4)).astype(np.uint8)           # elements 0..15: every index twice
+            codes[0, 8:] = 0x77                                           # elements 16..31: the top magnitude
+            meta = np.array([[did | ((130 - k) << 8), 1 | (130 << 8)]], dtype=np.uint16)
+            el, sc = O.repack_mxfp8(fb, codes, meta, block=16)
+            assert sc[0, 0] == 127
+            vals = fb[did][np.repeat(idx, 2)].astype(np.float64) * 2.0 ** (-k)
+            want = torch.from_numpy(vals.astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+            assert np.array_equal(el[0, :16], want), (k, did)
+            assert (el[0, 16:] == top).all()
+            seen.update(want.tolist())
+    assert 0 in seen and 1 in seen and any(2 <= v < 8 for v in seen)     # zero, the smallest subnormal, others
