@@ -37,8 +37,9 @@ def algorithmic_bytes(rows, cols, block=32):
 
 
 def time_graph(fn_steps, steps, warmup):
-    """Run `warmup` eager steps, capture `steps` steps into one HIP graph, replay it once untimed and once
-    timed.  Returns (wall seconds, event seconds) for the timed replay."""
+    """Run `warmup` eager steps, capture `steps` steps into one HIP graph, replay it untimed (once, and
+    again until `warmup` steps have been replayed: clocks need tens of milliseconds of load to settle), then
+    once timed.  Returns (wall seconds, event seconds) for the timed replay."""
     import torch
     for i in range(warmup):
         fn_steps(i)
@@ -50,7 +51,8 @@ def time_graph(fn_steps, steps, warmup):
             for i in range(steps):
                 fn_steps(i)
     torch.cuda.synchronize()
-    g.replay()
+    for _ in range(max(1, -(-warmup // steps))):
+        g.replay()
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
@@ -84,7 +86,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of one HIP graph")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -173,7 +175,7 @@ def main():
         steps2 = max(10, args.steps // 4)
 
         def add(name, fn, nbytes, nelem, steps=steps2):
-            w, e = timer(fn, steps, 3)
+            w, e = timer(fn, steps, 2 * steps)
             extras[name] = {"us": e / steps * 1e6, "G_elements_per_s": nelem / (e / steps) / 1e9,
                             "GB_per_s": nbytes / (e / steps) / 1e9, "hbm_frac": nbytes / (e / steps) / 1e9 / HBM_PEAK_GBS}
 
@@ -214,6 +216,12 @@ def main():
             F.fb4_decompose(luts, o_main, xs[k], codes[k], metas[k], sal_d, codes2=c2, meta2=m2)
         dbytes = n_sal * COLS * 2 + 2 * (n_sal * COLS // 2 + n_sal * (COLS // BLOCK) * 2)
         add("decompose_5pct_lut_g8", decomp_step, dbytes, n_sal * COLS)
+
+        def fused_step(i):
+            k = i % N_SETS
+            F.fb4_quantize_decompose(luts, o_main, xs[k], sal_d, codes1=codes[k], meta1=metas[k], codes2=c2, meta2=m2)
+        add("quantize_decompose_5pct_one_pass", fused_step,
+            abytes + n_sal * COLS // 2 + n_sal * (COLS // BLOCK) * 2 + n_sal * 4, n_el)
         outs = [torch.empty((ROWS, COLS), dtype=torch.bfloat16, device="cuda") for _ in range(N_SETS)]
 
         def deq_step(i):

@@ -176,6 +176,25 @@ int fb4_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int
                   void* stream);
 
 /*
+ * Sec. 3.1-3.4 in one pass: fb4_quantize (or fb4_quantize_seda when
+ * token_group is given) followed by fb4_decompose of the salient rows with the
+ * same options and SeDA lists, with identical results.  When the request fits
+ * the streaming kernel (FB4_SEL_LUT with 8 groups, rows <= 65536, cols a
+ * multiple of 32, 16-byte aligned code planes) x is read once and
+ * the residual is formed from registers; otherwise the two kernels run one after
+ * the other on `stream`.
+ *   token_group, sub_formatbooks, n_groups   NULL, NULL, 0 for the full formatbook
+ *   salient_rows, n_sal                      as in fb4_decompose; n_sal may be 0
+ *   codes1, meta1                            first plane, every row
+ *   codes2, meta2                            compact second plane, [n_sal] rows
+ */
+int fb4_quantize_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
+                           int64_t cols, int64_t row_stride, const int32_t* token_group,
+                           const uint8_t* sub_formatbooks, int n_groups, const int32_t* salient_rows,
+                           int64_t n_sal, uint8_t* codes1, uint16_t* meta1, uint8_t* codes2,
+                           uint16_t* meta2, void* stream);
+
+/*
  * Decode (Sec. 3.1; the 4-bit -> 16-bit decode of App. E.2).  Every row is
  * decoded from plane 1; a salient row additionally gets its second plane:
  * out = round_to_dtype(fp32(y1) + fp32(y2)) (Sec. 3.3, Q(Act) + Q(Delta)).

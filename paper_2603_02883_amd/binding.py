@@ -59,6 +59,7 @@ def _load():
     lib.fb4_decompose.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, p, i64, p, p, i32,
                                   p, p, p]
     lib.fb4_dequantize.argtypes = [p, p, p, i64, i64, i32, p, p, p, i64, p, i32, i64, p]
+    lib.fb4_quantize_decompose.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, i32, p, i64, p, p, p, p, p]
     lib.fb4_repack_mxfp8.argtypes = [p, p, p, i64, i64, i32, p, i64, p, p]
     return lib
 
@@ -67,7 +68,7 @@ _lib = _load()
 
 EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts", "fb4_build_luts_host",
            "fb4_free_luts", "fb4_quantize", "fb4_quantize_seda", "fb4_decompose", "fb4_dequantize",
-           "fb4_repack_mxfp8"]
+           "fb4_quantize_decompose", "fb4_repack_mxfp8"]
 
 
 def lib():
@@ -192,6 +193,28 @@ def fb4_decompose(luts, o, x, codes1, meta1, salient_rows, token_group=None, sub
                             _dp(codes2), _dp(meta2), _stream(stream))
     _check(rc, "fb4_decompose")
     return codes2, meta2
+
+
+def fb4_quantize_decompose(luts, o, x, salient_rows, token_group=None, sub_formatbooks=None,
+                           codes1=None, meta1=None, codes2=None, meta2=None, stream=None):
+    """Both planes in one call.  Returns (codes1, meta1, codes2, meta2)."""
+    rows, cols = x.shape
+    n_sal = salient_rows.numel()
+    if codes1 is None:
+        codes1 = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
+    if meta1 is None:
+        meta1 = torch.empty((rows, cols // o.block), dtype=torch.int16, device=x.device)
+    if codes2 is None:
+        codes2 = torch.empty((n_sal, cols // 2), dtype=torch.uint8, device=x.device)
+    if meta2 is None:
+        meta2 = torch.empty((n_sal, cols // o.block), dtype=torch.int16, device=x.device)
+    rc = _lib.fb4_quantize_decompose(luts.handle, ctypes.byref(o), _dp(x), rows, cols,
+                                     x.stride(0) if rows > 1 else cols, _dp(token_group), _dp(sub_formatbooks),
+                                     0 if sub_formatbooks is None else sub_formatbooks.shape[0],
+                                     _dp(salient_rows), n_sal, _dp(codes1), _dp(meta1), _dp(codes2), _dp(meta2),
+                                     _stream(stream))
+    _check(rc, "fb4_quantize_decompose")
+    return codes1, meta1, codes2, meta2
 
 
 def fb4_dequantize(luts, codes1, meta1, block=32, codes2=None, meta2=None, salient_rows=None,

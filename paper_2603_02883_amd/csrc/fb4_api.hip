@@ -83,23 +83,33 @@ int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& 
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
-template <int kBlock, int G, bool kFlat>
+template <int kBlock, int G, bool kFlat, bool kDecomp>
 void launch_fast_variant(bool ts, bool seda, unsigned groups, hipStream_t s, const FastParams& f)
 {
     if (seda) {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true>), dim3(groups), dim3(kFastThreads), 0, s, f);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true>), dim3(groups), dim3(kFastThreads), 0, s, f);
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, f);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, f);
     } else {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false>), dim3(groups), dim3(kFastThreads), 0, s, f);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false>), dim3(groups), dim3(kFastThreads), 0, s, f);
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, f);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, f);
     }
 }
 
+// Second-plane outputs of the fused quantize + decompose call.
+struct FusedPlane {
+    const int32_t* salient;
+    int64_t n_sal;
+    uint8_t* codes2;
+    uint16_t* meta2;
+};
+
 // The streaming kernel serves the paper's online selector (LUT, any supported block size and group count),
 // with or without the two-stage filter and SeDA lists, when rows are whole 32-element chunks and the outputs
-// are aligned for its wide stores.  Returns false if the request is not one it serves.
+// are aligned for its wide stores; with `fused` it also writes the second plane of the salient rows (8 groups,
+// row and list counts that fit its LDS).  Returns false if the request is not one it serves.
 bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& p, int64_t cols,
-                 const int32_t* token_group, const uint8_t* sub, int n_groups, hipStream_t s, int* rc)
+                 const int32_t* token_group, const uint8_t* sub, int n_groups, const FusedPlane* fused,
+                 hipStream_t s, int* rc)
 {
     if (opts->selector != FB4_SEL_LUT || (cols % 32) || !aligned(p.codes, 16)) return false;
     if (opts->block == 16 && !aligned(p.meta, 4)) return false;
@@ -107,6 +117,8 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
     const uint64_t n_blocks = (uint64_t)p.rows * nb;
     if (n_blocks >= 0x7FFFFF00ull) return false;
     if (token_group && (uint32_t)n_groups > kMaxFastGroups) return false;
+    if (fused && (opts->num_groups != 8 || p.rows > (long long)kMaxFusedRows || !aligned(fused->codes2, 16)))
+        return false;
     FastParams f = {};
     f.x = p.x;
     f.row_stride = p.row_stride;
@@ -124,6 +136,13 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
     f.sub = sub;
     f.n_groups = (uint32_t)n_groups;
     f.n_dialects = (uint32_t)luts->n_dialects;
+    if (fused) {
+        f.salient = fused->salient;
+        f.n_sal = (uint32_t)fused->n_sal;
+        f.rows = (uint32_t)p.rows;
+        f.codes2 = fused->codes2;
+        f.meta2 = fused->meta2;
+    }
     long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
     const long long cap = (long long)luts->n_cu * FB4_FAST_GROUPS_PER_CU;
     if (groups > cap) groups = cap;
@@ -131,18 +150,25 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
     const bool flat = p.row_stride == cols;
     const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
     const bool seda = token_group != nullptr;
-    if (opts->block == 32) {
-        if (opts->num_groups == 8) {
-            if (flat) launch_fast_variant<32, 8, true>(ts, seda, ng, s, f);
-            else launch_fast_variant<32, 8, false>(ts, seda, ng, s, f);
-        } else if (opts->num_groups == 16) {
-            launch_fast_variant<32, 16, false>(ts, seda, ng, s, f);
+    if (fused) {
+        if (opts->block == 32) {
+            if (flat) launch_fast_variant<32, 8, true, true>(ts, seda, ng, s, f);
+            else launch_fast_variant<32, 8, false, true>(ts, seda, ng, s, f);
         } else {
-            launch_fast_variant<32, 32, false>(ts, seda, ng, s, f);
+            launch_fast_variant<16, 8, false, true>(ts, seda, ng, s, f);
+        }
+    } else if (opts->block == 32) {
+        if (opts->num_groups == 8) {
+            if (flat) launch_fast_variant<32, 8, true, false>(ts, seda, ng, s, f);
+            else launch_fast_variant<32, 8, false, false>(ts, seda, ng, s, f);
+        } else if (opts->num_groups == 16) {
+            launch_fast_variant<32, 16, false, false>(ts, seda, ng, s, f);
+        } else {
+            launch_fast_variant<32, 32, false, false>(ts, seda, ng, s, f);
         }
     } else {
-        if (opts->num_groups == 8) launch_fast_variant<16, 8, false>(ts, seda, ng, s, f);
-        else launch_fast_variant<16, 16, false>(ts, seda, ng, s, f);
+        if (opts->num_groups == 8) launch_fast_variant<16, 8, false, false>(ts, seda, ng, s, f);
+        else launch_fast_variant<16, 16, false, false>(ts, seda, ng, s, f);
     }
     *rc = hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
     return true;
@@ -258,7 +284,7 @@ int fb4_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int6
     p.blob = luts->dev_blob;
     p.n_dialects = luts->n_dialects;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (launch_fast(luts, opts, p, cols, nullptr, nullptr, 0, s, &rc)) return rc;
+    if (launch_fast(luts, opts, p, cols, nullptr, nullptr, 0, nullptr, s, &rc)) return rc;
     return launch_quant<kPlain>(opts, grid_for(luts, p.n_tiles), s, p);
 }
 
@@ -285,7 +311,8 @@ int fb4_quantize_seda(const fb4_luts* luts, const fb4_opts* opts, const void* x,
     p.n_groups = n_groups;
     p.blob = luts->dev_blob;
     p.n_dialects = luts->n_dialects;
-    if (launch_fast(luts, opts, p, cols, token_group, sub_formatbooks, n_groups, static_cast<hipStream_t>(stream), &rc))
+    if (launch_fast(luts, opts, p, cols, token_group, sub_formatbooks, n_groups, nullptr,
+                    static_cast<hipStream_t>(stream), &rc))
         return rc;
     return launch_quant<kSeda>(opts, grid_for(luts, p.n_tiles), static_cast<hipStream_t>(stream), p);
 }
@@ -322,6 +349,45 @@ int fb4_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int
     p.blob = luts->dev_blob;
     p.n_dialects = luts->n_dialects;
     return launch_quant<kDecomp>(opts, grid_for(luts, p.n_tiles), static_cast<hipStream_t>(stream), p);
+}
+
+int fb4_quantize_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
+                           int64_t row_stride, const int32_t* token_group, const uint8_t* sub_formatbooks,
+                           int n_groups, const int32_t* salient_rows, int64_t n_sal, uint8_t* codes1,
+                           uint16_t* meta1, uint8_t* codes2, uint16_t* meta2, void* stream)
+{
+    if (n_sal < 0) return FB4_ERR_INVALID_ARG;
+    int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes1, meta1);
+    if (rc != FB4_OK) return rc;
+    const bool seda = token_group || sub_formatbooks || n_groups;
+    if (seda && (!token_group || !sub_formatbooks || n_groups < 1)) return FB4_ERR_INVALID_ARG;
+    if (n_sal > rows) return FB4_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return FB4_OK;
+    if (n_sal > 0 && (!salient_rows || !codes2 || !meta2)) return FB4_ERR_INVALID_ARG;
+    if (seda && !aligned(token_group, 4)) return FB4_ERR_UNSUPPORTED;
+    if (n_sal > 0 && (!aligned(salient_rows, 4) || !aligned(codes2, 4) || !aligned(meta2, 2))) return FB4_ERR_UNSUPPORTED;
+    if (n_sal > 0) {
+        // one pass: the second plane is formed from the registers that hold the tile
+        QuantParams p = {};
+        if (!tiling(rows, cols, opts->block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
+        p.x = static_cast<const uint16_t*>(x);
+        p.row_stride = row_stride;
+        p.rows = rows;
+        p.cols = cols;
+        p.codes = codes1;
+        p.meta = meta1;
+        const FusedPlane fp = {salient_rows, n_sal, codes2, meta2};
+        if (launch_fast(luts, opts, p, cols, token_group, sub_formatbooks, n_groups, &fp,
+                        static_cast<hipStream_t>(stream), &rc))
+            return rc;
+    }
+    // otherwise the two steps one after the other on the same stream
+    rc = seda ? fb4_quantize_seda(luts, opts, x, rows, cols, row_stride, token_group, sub_formatbooks, n_groups,
+                                  codes1, meta1, stream)
+              : fb4_quantize(luts, opts, x, rows, cols, row_stride, codes1, meta1, stream);
+    if (rc != FB4_OK || n_sal == 0) return rc;
+    return fb4_decompose(luts, opts, x, rows, cols, row_stride, codes1, meta1, salient_rows, n_sal, token_group,
+                         sub_formatbooks, n_groups, codes2, meta2, stream);
 }
 
 int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* meta1, int64_t rows, int64_t cols,

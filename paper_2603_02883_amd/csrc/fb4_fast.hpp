@@ -54,6 +54,12 @@ struct FastParams {
     const uint8_t* sub;           // SeDA: [n_groups][8] DIDs
     uint32_t n_groups;            // SeDA: <= kMaxFastGroups
     uint32_t n_dialects;
+    // fused second plane of the salient rows (Sec. 3.3)
+    const int32_t* salient;       // [n_sal] ascending, unique
+    uint32_t n_sal;
+    uint32_t rows;                // <= kMaxFusedRows
+    uint8_t* codes2;              // [n_sal][nb * 16]
+    uint16_t* meta2;              // [n_sal][nb * 32 / block]
 };
 
 constexpr uint32_t kMaxFastGroups = 1023;   // SeDA groups whose exclusion rows fit the workgroup's LDS
@@ -105,29 +111,64 @@ constexpr int kLdsRows = 0;              // [32 bins][2 halves][8 copies][16 B] 
 constexpr int kLdsPair = 8192;           // [32 hi bins][32 lo bins][32 dialects] 32 KiB
 constexpr int kLdsNibT = 8192 + 32768;   // [32 bins][32 dialects]                1 KiB
 constexpr int kLdsRange = kLdsNibT + 1024;   // two-stage: [8 ranges][32 B] 0xFF = dialect excluded
-constexpr int kLdsSeda = kLdsRange + 256;    // SeDA: [n_groups + 1][32 B] 0xFF = dialect excluded; last row: none
-constexpr int kLdsFastBytes = kLdsSeda;      // without SeDA
-constexpr int kLdsFastBytesSeda = kLdsSeda + (kMaxFastGroups + 1) * 32;
+// fused decomposition only: decode table, bitmap of salient rows, salient rows before each bitmap word
+constexpr uint32_t kMaxFusedRows = 65536;
+constexpr int kLdsDecode = kLdsRange + 256;              // [32 dialects][8] bf16 patterns      512 B
+constexpr int kLdsMagNib = kLdsDecode + 512;             // [32 dialects] eight 4-bit magnitudes 128 B
+constexpr int kLdsSalBits = kLdsMagNib + 128;            // one bit per row                     8 KiB
+constexpr int kLdsSalRank = kLdsSalBits + kMaxFusedRows / 8;   // uint16 per bitmap word         4 KiB
+constexpr int kLdsDecompBytes = 512 + 128 + kMaxFusedRows / 8 + kMaxFusedRows / 32 * 2;
+// SeDA: [n_groups + 1][32 B] 0xFF = dialect excluded; last row: none.  Placed after everything else.
+constexpr int lds_seda_offset(bool decomp) { return kLdsRange + 256 + (decomp ? kLdsDecompBytes : 0); }
+constexpr int lds_fast_bytes(bool seda, bool decomp)
+{
+    return lds_seda_offset(decomp) + (seda ? (int)(kMaxFastGroups + 1) * 32 : 0);
+}
 
 struct BlockCodes {
     uint32_t code[4];
     uint32_t meta;
 };
 
+// Sec. 3.3 residual of one element: x - y, exact in fp32, rounded once to bf16 (nearest even), where y is
+// the decoded first-plane value of the element.  An Inf / NaN element is its own residual.
+//   xh: bf16 pattern of x; nib: its first-plane code; did, eoff: dialect and (exponent byte - 130) << 7 of
+//   its block; dec: decode table [dialect][index] of bf16 magnitude patterns.
+__device__ __forceinline__ uint32_t residual_elem(uint32_t xh, uint32_t nib, uint32_t did, uint32_t eoff,
+                                                  const uint16_t* dec)
+{
+    const uint32_t mb = did < 32u ? (uint32_t)dec[did * 8 + (nib & 7u)] : 0u;
+    uint32_t yb = mb ? ((mb + eoff) & 0x7FFFu) : 0u;
+    yb |= (nib & 8u) << 12;
+    const float d = __uint_as_float(xh << 16) - __uint_as_float(yb << 16);
+    uint32_t u = __float_as_uint(d);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (((xh >> 7) & 0xFFu) == 0xFFu) ? xh : (u >> 16);
+}
+
 // Plain per-element routine for one block of kBlock elements with G groups, any input (Sec. 3.1-3.2); reads
 // the block again from global memory.  Same arithmetic as the generic kernel.
 // excl_a / excl_b: LDS offsets of 32-byte exclusion rows (0xFF = excluded), or 0xFFFFFFFF for none.  A dialect
 // excluded by excl_a never wins; excl_b (the two-stage range filter) applies only if it leaves a candidate.
-template <int kBlock, int G>
+// kResidual: quantize the residual of the first plane (c1 = the block's first-plane code words, m1 = its
+// metadata word) instead of x itself.
+template <int kBlock, int G, bool kResidual>
 __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, const uint8_t* lds, uint32_t excl_a,
-                                                        bool two_stage)
+                                                        bool two_stage, uint4 c1, uint32_t m1)
 {
     constexpr int PER = kBlock / G;
     BlockCodes out;
+    auto elem = [&](int i) -> uint32_t {
+        const uint32_t h = xb[i];
+        if (!kResidual) return h;
+        const uint32_t cw = i < 8 ? c1.x : i < 16 ? c1.y : i < 24 ? c1.z : c1.w;
+        return residual_elem(h, (cw >> (4 * (i & 7))) & 0xFu, m1 & 0xFFu, ((m1 >> 8) - 130u) << 7,
+                             reinterpret_cast<const uint16_t*>(lds + kLdsDecode));
+    };
     uint32_t amax = 0;
 #pragma unroll 1
     for (int i = 0; i < kBlock; ++i) {
-        uint32_t m = xb[i] & 0x7FFFu;
+        uint32_t m = elem(i) & 0x7FFFu;
         amax = max(amax, (m > 0x7F80u) ? 0u : m);
     }
     const uint32_t eb = min(max(amax >> 7, 4u), 254u);
@@ -145,7 +186,7 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
     for (int j = 0; j < G; ++j) {
         uint32_t g = 0;
 #pragma unroll 1
-        for (int i = 0; i < PER; ++i) g = max(g, bin_of(xb[PER * j + i]));
+        for (int i = 0; i < PER; ++i) g = max(g, bin_of(elem(PER * j + i)));
         gbin[j] = g;
     }
     uint32_t bmax = 0;
@@ -170,7 +211,7 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
         uint32_t v = 0;
 #pragma unroll 1
         for (int i = 0; i < 8; ++i) {
-            uint32_t h = xb[8 * c + i];
+            uint32_t h = elem(8 * c + i);
             uint32_t nib = lds[kLdsNibT + bin_of(h) * 32 + did] | ((h >> 15) << 3);
             v |= nib << (4 * i);
         }
@@ -288,11 +329,13 @@ __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], c
 // One lane owns 32 consecutive elements of a row: w = its 32 bf16 as 16 packed pairs, holding one block of
 // 32 or two blocks of 16.  Produces the four code words and the metadata (one 16-bit word, or two for block
 // size 16 with the first block in the low half).  xb / in_range are only used by the plain per-element
-// routine of a tile with special values.
-template <int kBlock, int G, bool kTwoStage, bool kSeda>
+// routine of a tile with special values (tile_special reports that this route was taken).  kResidual: w holds the Sec. 3.3 residual of the first plane
+// (code1, meta1), which the plain routine recomputes from x.
+template <int kBlock, int G, bool kTwoStage, bool kSeda, bool kResidual = false>
 __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint8_t* lds, const TileConsts& K,
                                              const uint16_t* xb, bool in_range, uint32_t excl_a,
-                                             uint32_t (&code)[4], uint32_t& meta)
+                                             uint32_t (&code)[4], uint32_t& meta,
+                                             const uint32_t (&code1)[4], uint32_t meta1, bool& tile_special)
 {
     constexpr int NB = 32 / kBlock;     // blocks per lane
     constexpr int RB = 16 / NB;         // packed registers per block
@@ -317,15 +360,18 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
 #pragma unroll
     for (int b = 0; b < NB; ++b) special = special || !(bm[b] == 0u || (bm[b] - 0x0280u) < (0x7F80u - 0x0280u));
 
-    if (__builtin_amdgcn_ballot_w64(special) != 0) {
+    tile_special = __builtin_amdgcn_ballot_w64(special) != 0;   // wave-uniform
+    if (tile_special) {
         // rare: some block of this tile holds NaN / Inf or is tiny
         code[0] = code[1] = code[2] = code[3] = 0;
         meta = 0;
         if (in_range) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const BlockCodes r = quantize_block_plain<kBlock, G>(xb + b * kBlock, lds,
-                                                                     kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage);
+                const uint4 c1 = NB == 1 ? make_uint4(code1[0], code1[1], code1[2], code1[3])
+                                         : make_uint4(code1[2 * b], code1[2 * b + 1], 0u, 0u);
+                const BlockCodes r = quantize_block_plain<kBlock, G, kResidual>(
+                    xb + b * kBlock, lds, kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage, c1, (meta1 >> (16 * b)) & 0xFFFFu);
 #pragma unroll
                 for (int c = 0; c < 4 / NB; ++c) code[b * (4 / NB) + c] = r.code[c];
                 meta |= r.meta << (16 * b);
@@ -438,10 +484,52 @@ __device__ __forceinline__ void store_tile(const FastParams& p, uint32_t gb, uin
     }
 }
 
-template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda>
+// Sec. 3.3 residual of one lane's 32 elements against its first plane (code, meta): x - y in fp32 (exact),
+// then one rounding to bf16.  y = copysign(magnitude * 2^(e-3), x): the code carries x's sign.  The eight
+// 4-bit magnitudes of the block's dialect sit in one register; an Inf / NaN element (only possible when
+// may_have_naninf) is its own residual.
+template <int kBlock>
+__device__ __forceinline__ void residual32(const uint32_t (&w)[16], const uint32_t (&code)[4], uint32_t meta,
+                                           const uint8_t* lds, bool may_have_naninf, uint32_t (&r)[16])
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    constexpr int NB = 32 / kBlock;
+    uint32_t mags[NB];
+    float scale[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const uint32_t mw = (meta >> (16 * b)) & 0xFFFFu;
+        const uint32_t did = mw & 0xFFu;
+        mags[b] = did < 32u ? reinterpret_cast<const uint32_t*>(lds + kLdsMagNib)[did] : 0u;
+        scale[b] = __uint_as_float(((mw >> 8) - 3u) << 23);          // 2^(e-3); exponent byte >= 4
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int b = k / (16 / NB);
+        const uint32_t cw = code[k >> 2];
+        const int j = 2 * (k & 3);                                   // nibble of the low half
+        const uint32_t s0 = j ? ((cw >> (4 * j - 2)) & 0x1Cu) : ((cw << 2) & 0x1Cu);   // 4 * index
+        const uint32_t s1 = (cw >> (4 * j + 2)) & 0x1Cu;
+        const float m0 = (float)((mags[b] >> s0) & 0xFu), m1 = (float)((mags[b] >> s1) & 0xFu);
+        const float x0 = __uint_as_float(w[k] << 16), x1 = __uint_as_float(w[k] & 0xFFFF0000u);
+        const f32x2 d = {x0 - __builtin_copysignf(m0 * scale[b], x0), x1 - __builtin_copysignf(m1 * scale[b], x1)};
+        uint32_t out = __builtin_bit_cast(uint32_t, __builtin_convertvector(d, bf16x2));   // round to nearest even
+        if (may_have_naninf) {
+            if (((w[k] >> 7) & 0xFFu) == 0xFFu) out = (out & 0xFFFF0000u) | (w[k] & 0xFFFFu);
+            if (((w[k] >> 23) & 0xFFu) == 0xFFu) out = (out & 0xFFFFu) | (w[k] & 0xFFFF0000u);
+        }
+        r[k] = out;
+    }
+}
+
+template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda, bool kDecomp = false>
 __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p)
 {
-    __shared__ __align__(16) uint8_t lds[kSeda ? kLdsFastBytesSeda : kLdsFastBytes];
+    constexpr int kLdsSeda = lds_seda_offset(kDecomp);
+    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kDecomp)];
+    __shared__ uint32_t sal_before;      // fused decomposition: list entries below row 0
+    __shared__ uint32_t sal_wave[kFastWaves];
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // Tiles of workgroup b are b, b + W, b + 2W, ... (W = number of workgroups).  The waves of a workgroup
@@ -467,6 +555,38 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
         if (kTwoStage && threadIdx.x < 64)
             reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] =
                 reinterpret_cast<const uint32_t*>(p.blob + kOffRangeExcl)[threadIdx.x];
+        // fused decomposition: a short salient list is requested now, together with the tables, and used
+        // after the barrier; a long one is read in a loop later
+        constexpr int kSalEarly = 8;
+        int32_t sal_reg[kSalEarly];
+        const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kFastThreads;
+        if (kDecomp && sal_early) {
+#pragma unroll
+            for (int k = 0; k < kSalEarly; ++k) {
+                const uint32_t i = threadIdx.x + k * kFastThreads;
+                sal_reg[k] = i < p.n_sal ? p.salient[i] : 0x7FFFFFFF;   // beyond any row: ignored
+            }
+        }
+        if (kDecomp) {
+            if (threadIdx.x < 128)
+                reinterpret_cast<uint32_t*>(lds + kLdsDecode)[threadIdx.x] =
+                    reinterpret_cast<const uint32_t*>(p.blob + kOffDecode)[threadIdx.x];
+            if (threadIdx.x < 32) {
+                // the dialect's eight magnitudes (integers 0..15 stored as bf16 patterns) as nibbles
+                const uint4 dq = *reinterpret_cast<const uint4*>(p.blob + kOffDecode + threadIdx.x * 16);
+                const uint32_t dv[4] = {dq.x, dq.y, dq.z, dq.w};
+                uint32_t mw = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t bits = (dv[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
+                    mw |= ((uint32_t)(int)__uint_as_float(bits << 16) & 0xFu) << (4 * i);
+                }
+                reinterpret_cast<uint32_t*>(lds + kLdsMagNib)[threadIdx.x] = mw;
+            }
+            for (uint32_t i = threadIdx.x; i < kMaxFusedRows / 32; i += kFastThreads)
+                reinterpret_cast<uint32_t*>(lds + kLdsSalBits)[i] = 0;
+            if (threadIdx.x == 0) sal_before = 0;
+        }
         if (kSeda) {
             // one exclusion row per group: everything excluded except the group's valid DIDs; a group without
             // a valid DID, and the extra last row (rows outside any group), exclude nothing
@@ -492,6 +612,39 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
             }
         }
         __syncthreads();
+        if (kDecomp) {
+            // Salient rows as a bitmap.  The list is ascending and unique, so the position of row r in it is
+            // (entries below row 0) + (salient rows below r): kept as a running count per bitmap word.
+            static_assert(!kDecomp || kFastThreads * 4 * 32 == kMaxFusedRows, "four bitmap words per thread");
+            uint32_t* bits = reinterpret_cast<uint32_t*>(lds + kLdsSalBits);
+            auto mark = [&](int32_t r) {
+                if (r < 0) atomicAdd(&sal_before, 1u);
+                else if ((uint32_t)r < p.rows) atomicOr(bits + ((uint32_t)r >> 5), 1u << (r & 31));
+            };
+            if (sal_early) {
+#pragma unroll
+                for (int k = 0; k < kSalEarly; ++k) mark(sal_reg[k]);
+            } else {
+                for (uint32_t i = threadIdx.x; i < p.n_sal; i += kFastThreads) mark(p.salient[i]);
+            }
+            __syncthreads();
+            const uint4 wv = reinterpret_cast<const uint4*>(bits)[threadIdx.x];
+            const uint32_t c0 = __builtin_popcount(wv.x), c1 = c0 + __builtin_popcount(wv.y);
+            const uint32_t c2 = c1 + __builtin_popcount(wv.z), c3 = c2 + __builtin_popcount(wv.w);
+            uint32_t incl = c3;   // inclusive scan over the wavefront
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t v = __shfl_up(incl, off);
+                if ((int)lane >= off) incl += v;
+            }
+            if (lane == 63) sal_wave[wave] = incl;
+            __syncthreads();
+            uint32_t base = sal_before + incl - c3;
+            for (uint32_t k = 0; k < wave; ++k) base += sal_wave[k];
+            uint16_t* rank = reinterpret_cast<uint16_t*>(lds + kLdsSalRank) + threadIdx.x * 4;
+            rank[0] = (uint16_t)base; rank[1] = (uint16_t)(base + c0);
+            rank[2] = (uint16_t)(base + c1); rank[3] = (uint16_t)(base + c2);
+        }
         // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
         for (int i = threadIdx.x; i < 1024; i += kFastThreads) {
             const int hi = i >> 5, lo = i & 31;
@@ -533,8 +686,42 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
         const uint32_t t_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
         uint32_t code[4], meta;
-        compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u),
-                                             gb < p.n_blocks, excl_a, code, meta);
+        const uint16_t* xb = p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u);
+        const uint32_t no_code[4] = {0, 0, 0, 0};
+        bool tile_special;
+        compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
+                                                  tile_special);
+        if (kDecomp) {
+            // second plane of the salient rows, from the registers that still hold the tile
+            const uint32_t gbc = gb < p.n_blocks ? gb : 0u;
+            const uint32_t row = (uint32_t)(((unsigned long long)gbc * p.div_mul) >> p.div_shift);
+            const bool sal = gb < p.n_blocks &&
+                             ((reinterpret_cast<const uint32_t*>(lds + kLdsSalBits)[row >> 5] >> (row & 31)) & 1u);
+            if (__builtin_amdgcn_ballot_w64(sal) != 0) {
+                // position of the row in the salient list
+                const uint32_t wbits = reinterpret_cast<const uint32_t*>(lds + kLdsSalBits)[row >> 5];
+                const uint32_t lo = reinterpret_cast<const uint16_t*>(lds + kLdsSalRank)[row >> 5] +
+                                    __builtin_popcount(wbits & ((1u << (row & 31)) - 1u));
+                uint32_t w2[16], code2[4], meta2;
+                residual32<kBlock>(w, code, meta, lds, tile_special, w2);
+                // a lane that is not salient runs the arithmetic on zeros and stores nothing
+#pragma unroll
+                for (int k = 0; k < 16; ++k) w2[k] = sal ? w2[k] : 0u;
+                bool special2;
+                compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, sal, excl_a, code2, meta2, code, meta,
+                                                                special2);
+                if (sal) {
+                    const size_t ob = (size_t)lo * p.nb + (gb - row * p.nb);
+                    *reinterpret_cast<uint4*>(p.codes2 + ob * 16) = make_uint4(code2[0], code2[1], code2[2], code2[3]);
+                    if (kBlock == 16) {
+                        p.meta2[ob * 2] = (uint16_t)meta2;
+                        p.meta2[ob * 2 + 1] = (uint16_t)(meta2 >> 16);
+                    } else {
+                        p.meta2[ob] = (uint16_t)meta2;
+                    }
+                }
+            }
+        }
         held_code = make_uint4(code[0], code[1], code[2], code[3]);
         held_meta = meta;
         held_gb = gb;

@@ -477,6 +477,89 @@ def test_outputs_without_wide_alignment_and_many_seda_groups(F, luts, block):
     assert np.array_equal(host_u8(c), cr) and np.array_equal(host_u16(m), mr)
 
 
+# ------------------------------------------------ both planes in one call
+def _both_planes_separately(F, luts, o, x, sal_d, tg_d=None, sub_d=None):
+    if tg_d is None:
+        c1, m1 = F.fb4_quantize(luts, o, x)
+    else:
+        c1, m1 = F.fb4_quantize_seda(luts, o, x, tg_d, sub_d)
+    c2, m2 = F.fb4_decompose(luts, o, x, c1, m1, sal_d, token_group=tg_d, sub_formatbooks=sub_d)
+    return c1, m1, c2, m2
+
+
+@pytest.mark.parametrize("block", [32, 16])
+def test_quantize_decompose_in_one_pass(F, luts, block):
+    fbk = DEFAULT_FORMATBOOK
+    # the decomposition workload (cfg3 shape): the fused kernel against the oracle on the salient rows
+    x = synth.vdit_activation(device="cuda")
+    xb = synth.bf16_bits(x)
+    sal = synth.salient_rows_from_attention(16384, frac=0.05, heads=24, seed=3, device="cuda")
+    sal_d = torch.from_numpy(sal).cuda()
+    o = F.opts(block=block)
+    c1, m1, c2, m2 = F.fb4_quantize_decompose(luts, o, x, sal_d)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([sal, np.arange(0, 16384, 61)]))
+    c1r, m1r = O.quantize(fbk, xb[rows], block=block)
+    assert np.array_equal(host_u8(c1)[rows], c1r) and np.array_equal(host_u16(m1)[rows], m1r)
+    c2r, m2r = O.decompose(fbk, xb[sal], host_u8(c1)[sal], host_u16(m1)[sal], np.arange(sal.size, dtype=np.int32),
+                           block=block)
+    assert np.array_equal(host_u8(c2), c2r) and np.array_equal(host_u16(m2), m2r)
+    s1, t1, s2, t2 = _both_planes_separately(F, luts, o, x, sal_d)
+    assert torch.equal(c1, s1) and torch.equal(m1, t1) and torch.equal(c2, s2) and torch.equal(m2, t2)
+    # variants: two-stage, SeDA, row stride, list entries outside the tensor, no salient row at all
+    xm, comp = synth.mixture_activation(rows=300, cols=32 * 21 + 8, seed=55, device="cuda", n_components=5)
+    xs = xm[:, :32 * 21]
+    sub_d = torch.from_numpy(synth.seda_sub_formatbooks(fbk, n_groups=5, seed=55)).cuda()
+    tg = comp.copy()
+    tg[::9] = -1
+    tg_d = torch.from_numpy(tg).cuda()
+    for flags in (0, F.FLAG_TWO_STAGE):
+        for seda in (False, True):
+            for sal in (np.arange(0, 300, 7), np.array([-5, -1, 0, 3, 299, 300, 4000]), np.zeros(0)):
+                o = F.opts(block=block, flags=flags)
+                sal_d = torch.from_numpy(sal.astype(np.int32)).cuda()
+                a = (tg_d, sub_d) if seda else (None, None)
+                c2 = torch.full((sal.size, 32 * 21 // 2), 0x5A, dtype=torch.uint8, device="cuda")
+                c1, m1, c2, m2 = F.fb4_quantize_decompose(luts, o, xs, sal_d, token_group=a[0], sub_formatbooks=a[1],
+                                                          codes2=c2)
+                s2 = torch.full((sal.size, 32 * 21 // 2), 0x5A, dtype=torch.uint8, device="cuda")
+                if seda:
+                    s1, t1 = F.fb4_quantize_seda(luts, o, xs, tg_d, sub_d)
+                else:
+                    s1, t1 = F.fb4_quantize(luts, o, xs)
+                _, t2 = F.fb4_decompose(luts, o, xs, s1, t1, sal_d, token_group=a[0], sub_formatbooks=a[1], codes2=s2)
+                torch.cuda.synchronize()
+                ok = torch.from_numpy((sal >= 0) & (sal < 300)).cuda()
+                assert torch.equal(c1, s1) and torch.equal(m1, t1) and torch.equal(c2, s2)
+                assert torch.equal(m2[ok], t2[ok])
+    # degenerate values: every row salient, residuals with Inf / NaN / tiny magnitudes
+    xe = synth.edge_case_tensor(cols=256)
+    x = dev_bits(xe)
+    sal = np.arange(xe.shape[0], dtype=np.int32)
+    for flags in (0, F.FLAG_TWO_STAGE):
+        o = F.opts(block=block, flags=flags)
+        c1, m1, c2, m2 = F.fb4_quantize_decompose(luts, o, x, torch.from_numpy(sal).cuda())
+        torch.cuda.synchronize()
+        c1r, m1r = O.quantize(fbk, xe, block=block, flags=flags)
+        c2r, m2r = O.decompose(fbk, xe, c1r, m1r, sal, block=block, flags=flags)
+        compare_quant(fbk, xe, host_u8(c1), host_u16(m1), c1r, m1r, 1, 8, flags=flags, block=block, what="fused edge 1")
+        assert np.array_equal(host_u8(c2), c2r) and np.array_equal(host_u16(m2), m2r)
+    # requests the one-pass kernel does not serve run the two kernels: other selectors, too many rows
+    x = synth.gaussian_outlier(rows=64, cols=512, seed=56, device="cuda")
+    sal_d = torch.arange(0, 64, 5, dtype=torch.int32, device="cuda")
+    for o in (F.opts(block=block, selector=F.SEL_SSE), F.opts(block=block, num_groups=16)):
+        got = F.fb4_quantize_decompose(luts, o, x, sal_d)
+        want = _both_planes_separately(F, luts, o, x, sal_d)
+        torch.cuda.synchronize()
+        assert all(torch.equal(g, w) for g, w in zip(got, want))
+    x = synth.gaussian_outlier(rows=65600, cols=32, seed=57, device="cuda")
+    sal_d = torch.arange(0, 65600, 41, dtype=torch.int32, device="cuda")
+    got = F.fb4_quantize_decompose(luts, F.opts(block=block), x, sal_d)
+    want = _both_planes_separately(F, luts, F.opts(block=block), x, sal_d)
+    torch.cuda.synchronize()
+    assert all(torch.equal(g, w) for g, w in zip(got, want))
+
+
 # ------------------------------------------------------------ MXFP8 operands
 @pytest.mark.parametrize("block", [32, 16])
 def test_mxfp8_repack(F, luts, block):
