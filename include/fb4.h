@@ -209,6 +209,29 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
                    int out_dtype, int64_t out_row_stride, void* stream);
 
 /*
+ * Sec. 3.4, "Constructing an 8-Dialect Sub-Formatbook": bin-count profile of
+ * the dialects selected on the anchor tokens of each group, then per
+ * dynamic-range bucket k (largest magnitude 8 + k) the most frequently selected
+ * dialect of that bucket.  The result is a valid `sub_formatbooks` argument of
+ * fb4_quantize_seda / fb4_decompose.
+ *   meta             device, uint16 [rows][blocks_per_row], metadata of an
+ *                    already quantized tensor (any block size)
+ *   anchor_group     device, int32 [rows]: g in 0..n_groups-1 marks an anchor
+ *                    token of group g; any other value: not an anchor
+ *   counts           device, uint32 [n_groups][32], output (cleared by the
+ *                    call): selections per group and DID, counted in blocks
+ *   sub_formatbooks  device, uint8 [n_groups][8], output.  Ties go to the lowest
+ *                    DID; a bucket none of whose dialects was selected gets its
+ *                    lowest DID; a bucket the formatbook has no dialect for
+ *                    gets 255, which the quantizing calls skip.
+ * Which tokens are anchors is the caller's business (the paper derives them
+ * from attention maps).
+ */
+int fb4_seda_profile(const fb4_luts* luts, const uint16_t* meta, int64_t rows, int64_t blocks_per_row,
+                     const int32_t* anchor_group, int n_groups, uint32_t* counts,
+                     uint8_t* sub_formatbooks, void* stream);
+
+/*
  * Sec. 4.5 and App. E.2 (MXFP8 compatibility: the magnitudes 0..15 are exact
  * in FP8 E4M3 and the block scale is a power of two): re-encode one code plane
  * as MXFP8 operands for a block-scaled FP8 matrix unit, without going through

@@ -170,3 +170,32 @@ def repack_mxfp8(fbk, codes, meta, block=32):
     if rc != 0:
         raise ValueError("fb4o_repack_mxfp8: invalid argument")
     return elems, scales
+
+
+def seda_profile(fbk, meta, anchor_group, n_groups):
+    """Sec. 3.4, "Constructing an 8-Dialect Sub-Formatbook": bin-count profile of the dialects selected on the
+    anchor tokens of each group, then per dynamic-range bucket (largest magnitude 8..15) the most frequently
+    selected dialect of that bucket.  meta: uint16 [rows][blocks per row] of an already quantized tensor;
+    anchor_group: int32 [rows], g in 0..n_groups-1 marks an anchor token of group g (anything else: not an
+    anchor).  Ties go to the lowest DID; a bucket none of whose dialects was selected gets its lowest DID; a
+    bucket the formatbook has no dialect for gets 255.  Returns (counts uint32 [n_groups][32], sub uint8
+    [n_groups][8]).  Plain numpy loops."""
+    fbk = np.asarray(fbk, dtype=np.uint8)
+    meta = np.asarray(meta, dtype=np.uint16)
+    anchor_group = np.asarray(anchor_group, dtype=np.int32)
+    counts = np.zeros((n_groups, 32), dtype=np.uint32)
+    for r in range(meta.shape[0]):
+        g = int(anchor_group[r])
+        if 0 <= g < n_groups:
+            for did in (meta[r] & 0xFF).tolist():
+                if did < 32:
+                    counts[g, did] += 1
+    sub = np.full((n_groups, 8), 255, dtype=np.uint8)
+    for g in range(n_groups):
+        for k in range(8):
+            best, best_count = 255, -1
+            for d in range(fbk.shape[0]):
+                if int(fbk[d, 7]) == 8 + k and int(counts[g, d]) > best_count:
+                    best, best_count = d, int(counts[g, d])
+            sub[g, k] = best
+    return counts, sub

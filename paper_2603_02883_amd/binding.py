@@ -60,6 +60,7 @@ def _load():
                                   p, p, p]
     lib.fb4_dequantize.argtypes = [p, p, p, i64, i64, i32, p, p, p, i64, p, i32, i64, p]
     lib.fb4_quantize_decompose.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, i32, p, i64, p, p, p, p, p]
+    lib.fb4_seda_profile.argtypes = [p, p, i64, i64, p, i32, p, p, p]
     lib.fb4_repack_mxfp8.argtypes = [p, p, p, i64, i64, i32, p, i64, p, p]
     return lib
 
@@ -68,7 +69,8 @@ _lib = _load()
 
 EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts", "fb4_build_luts_host",
            "fb4_free_luts", "fb4_quantize", "fb4_quantize_seda", "fb4_decompose", "fb4_dequantize",
-           "fb4_quantize_decompose", "fb4_repack_mxfp8"]
+           "fb4_quantize_decompose", "fb4_seda_profile",
+           "fb4_repack_mxfp8"]
 
 
 def lib():
@@ -244,3 +246,17 @@ def fb4_repack_mxfp8(luts, codes, meta, block=32, elems=None, scales=None, strea
                                elems.stride(0) if rows > 1 else cols, _dp(scales), _stream(stream))
     _check(rc, "fb4_repack_mxfp8")
     return elems, scales
+
+
+def fb4_seda_profile(luts, meta, anchor_group, n_groups, counts=None, sub_formatbooks=None, stream=None):
+    """Sub-formatbooks from the dialects selected on anchor tokens.  Returns (counts int32 [n_groups][32],
+    sub_formatbooks uint8 [n_groups][8])."""
+    rows, nb = meta.shape
+    if counts is None:
+        counts = torch.empty((n_groups, 32), dtype=torch.int32, device=meta.device)
+    if sub_formatbooks is None:
+        sub_formatbooks = torch.empty((n_groups, 8), dtype=torch.uint8, device=meta.device)
+    rc = _lib.fb4_seda_profile(luts.handle, _dp(meta), rows, nb, _dp(anchor_group), n_groups, _dp(counts),
+                               _dp(sub_formatbooks), _stream(stream))
+    _check(rc, "fb4_seda_profile")
+    return counts, sub_formatbooks

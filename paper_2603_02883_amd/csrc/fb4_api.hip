@@ -10,6 +10,7 @@
 #include "fb4_dequant_fast.hpp"
 #include "fb4_fast.hpp"
 #include "fb4_kernels.hpp"
+#include "fb4_profile.hpp"
 #include "fb4_repack.hpp"
 #include "fb4_tables.hpp"
 
@@ -512,6 +513,32 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
         if (flat) hipLaunchKernelGGL((repack_mxfp8_kernel<true, false>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
         else hipLaunchKernelGGL((repack_mxfp8_kernel<false, false>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
     }
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+int fb4_seda_profile(const fb4_luts* luts, const uint16_t* meta, int64_t rows, int64_t blocks_per_row,
+                     const int32_t* anchor_group, int n_groups, uint32_t* counts, uint8_t* sub_formatbooks,
+                     void* stream)
+{
+    if (!luts || rows < 0 || blocks_per_row < 0 || n_groups < 1 || n_groups > (1 << 24)) return FB4_ERR_INVALID_ARG;
+    if (!counts || !sub_formatbooks) return FB4_ERR_INVALID_ARG;
+    if (rows > 0 && blocks_per_row > 0 && (!meta || !anchor_group)) return FB4_ERR_INVALID_ARG;
+    if (!aligned(counts, 4) || (meta && !aligned(meta, 2)) || (anchor_group && !aligned(anchor_group, 4)))
+        return FB4_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t n = (uint32_t)n_groups * 32u;
+    // cleared by a kernel (not a memset node), so the call can be captured into a HIP graph
+    hipLaunchKernelGGL(profile_clear_kernel, dim3((n + kProfileThreads - 1) / kProfileThreads), dim3(kProfileThreads),
+                       0, s, counts, n);
+    if (rows > 0 && blocks_per_row > 0) {
+        long long groups = (rows + kProfileThreads / 64 - 1) / (kProfileThreads / 64);
+        const long long cap = (long long)luts->n_cu * 8;
+        if (groups > cap) groups = cap;
+        hipLaunchKernelGGL(profile_count_kernel, dim3((unsigned)groups), dim3(kProfileThreads), 0, s, meta,
+                           (long long)rows, (long long)blocks_per_row, anchor_group, n_groups, counts);
+    }
+    hipLaunchKernelGGL(profile_select_kernel, dim3(((unsigned)n_groups * 8u + kProfileThreads - 1) / kProfileThreads),
+                       dim3(kProfileThreads), 0, s, counts, n_groups, luts->dev_blob, sub_formatbooks);
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 

@@ -560,6 +560,39 @@ def test_quantize_decompose_in_one_pass(F, luts, block):
     assert all(torch.equal(g, w) for g, w in zip(got, want))
 
 
+# ------------------------------------------------ sub-formatbook construction
+def test_seda_profile_builds_sub_formatbooks(F, luts):
+    fbk = DEFAULT_FORMATBOOK
+    x, comp = synth.mixture_activation(device="cuda")         # cfg4: 16384 x 3072, 64 groups
+    rng = np.random.default_rng(58)
+    anchors = np.where(rng.random(16384) < 0.02, comp, -1).astype(np.int32)   # about 2 % of the tokens
+    anchors[:5] = [64, 1000, -7, 0, 63]                       # values outside the groups are no anchors
+    for block in (32, 16):
+        c, m = F.fb4_quantize(luts, F.opts(block=block), x)
+        counts = torch.full((64, 32), 12345, dtype=torch.int32, device="cuda")      # cleared by the call
+        counts, sub = F.fb4_seda_profile(luts, m, torch.from_numpy(anchors).cuda(), 64, counts=counts)
+        torch.cuda.synchronize()
+        cr, sr = O.seda_profile(fbk, host_u16(m), anchors, 64)
+        assert np.array_equal(counts.cpu().numpy().view(np.uint32), cr)
+        assert np.array_equal(host_u8(sub), sr)
+        # and the tables drive the restricted pass
+        c2, m2 = F.fb4_quantize_seda(luts, F.opts(block=block), x, torch.from_numpy(comp).cuda(), sub)
+        torch.cuda.synchronize()
+        rows = np.arange(0, 16384, 16)
+        c2r, m2r = O.quantize(fbk, synth.bf16_bits(x)[rows], block=block, token_group=comp[rows], sub_formatbooks=sr)
+        assert np.array_equal(host_u8(c2)[rows], c2r) and np.array_equal(host_u16(m2)[rows], m2r)
+    # a small formatbook: buckets without a dialect are marked 255; no anchors at all: first dialect per bucket
+    l3 = F.fb4_build_luts(fbk[[0, 3, 31]])
+    xs = synth.gaussian_outlier(rows=8, cols=256, seed=59, device="cuda")
+    c, m = F.fb4_quantize(l3, F.opts(), xs)
+    for anc in (np.zeros(8, dtype=np.int32), np.full(8, -1, dtype=np.int32)):
+        counts, sub = F.fb4_seda_profile(l3, m, torch.from_numpy(anc).cuda(), 2)
+        torch.cuda.synchronize()
+        cr, sr = O.seda_profile(fbk[[0, 3, 31]], host_u16(m), anc, 2)
+        assert np.array_equal(counts.cpu().numpy().view(np.uint32), cr) and np.array_equal(host_u8(sub), sr)
+    l3.free()
+
+
 # ------------------------------------------------------------ MXFP8 operands
 @pytest.mark.parametrize("block", [32, 16])
 def test_mxfp8_repack(F, luts, block):

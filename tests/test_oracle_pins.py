@@ -634,3 +634,53 @@ def test_e4m3_rounding_of_the_oracle_on_every_shifted_magnitude():
             assert (el[0, 16:] == top).all()
             seen.update(want.tolist())
     assert 0 in seen and 1 in seen and any(2 <= v < 8 for v in seen)     # zero, the smallest subnormal, others
+
+
+# ------------------------------------------------- sub-formatbook construction
+def test_seda_profile_picks_the_most_frequent_dialect_of_each_range(fbk):
+    # hand-made metadata: group 0 anchors are rows 0 and 2, group 1 anchor is row 3, row 1 is no anchor
+    buckets = range_buckets(fbk)                           # range k -> list of DIDs whose largest magnitude is 8 + k
+    d8, d15 = buckets[0], buckets[7]
+    assert len(d8) >= 2 and len(d15) >= 3
+    e = 130 << 8
+    meta = np.array([[d8[1], d8[1], d15[2], d15[0]],
+                     [d8[0], d8[0], d8[0], d8[0]],
+                     [d8[0], d15[2], d15[1], d15[1]],
+                     [d15[1], d15[1], d15[1], d8[1]]], dtype=np.uint16) | e
+    counts, sub = O.seda_profile(fbk, meta, np.array([0, -1, 0, 1], dtype=np.int32), 2)
+    assert counts.sum() == 12 and counts[0, d8[1]] == 2 and counts[0, d8[0]] == 1 and counts[0, d15[2]] == 2
+    assert counts[0, d15[1]] == 2 and counts[0, d15[0]] == 1
+    assert sub[0, 0] == d8[1]                              # two selections beat one
+    assert sub[0, 7] == min(d15[1], d15[2])                # a tie goes to the lower DID
+    assert sub[1, 0] == d8[1] and sub[1, 7] == d15[1]
+    for k in range(1, 7):                                  # never selected: the first dialect of the bucket
+        assert sub[0, k] == buckets[k][0] and sub[1, k] == buckets[k][0]
+    # a formatbook without some ranges: those buckets are marked 255
+    small = fbk[[0, 3, 31]]
+    _, sub = O.seda_profile(small, np.array([[0, 1, 2, 2]], dtype=np.uint16) | e, np.array([0], dtype=np.int32), 1)
+    tops = small[:, 7].astype(int) - 8
+    want = np.full(8, 255)
+    for d, k in enumerate(tops):
+        if want[k] == 255:
+            want[k] = d
+    assert sub[0].tolist() == want.tolist()
+
+
+def test_seda_profile_on_a_quantized_tensor_restricts_to_dialects_that_were_in_use(fbk):
+    x, comp = synth.mixture_activation(rows=128, cols=1024, seed=36, n_components=4)
+    xb = synth.bf16_bits(x)
+    c, m = O.quantize(fbk, xb)
+    anchors = np.where(np.arange(128) % 4 == 0, comp, -1).astype(np.int32)     # every fourth token is an anchor
+    counts, sub = O.seda_profile(fbk, m, anchors, 4)
+    for g in range(4):
+        rows = np.nonzero(anchors == g)[0]
+        assert counts[g].sum() == rows.size * m.shape[1]
+        assert np.array_equal(counts[g], np.bincount((m[rows] & 0xFF).ravel(), minlength=32))
+        for k in range(8):
+            d = int(sub[g, k])
+            assert fbk[d, 7] == 8 + k
+            same_range = np.nonzero(fbk[:, 7] == 8 + k)[0]
+            assert counts[g, d] == counts[g, same_range].max()
+    # the constructed tables are valid SeDA inputs: every DID of the restricted pass comes from its row's table
+    c2, m2 = O.quantize(fbk, xb, token_group=comp, sub_formatbooks=sub)
+    assert ((m2 & 0xFF)[:, :, None] == sub[comp][:, None, :]).any(axis=2).all()
