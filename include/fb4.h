@@ -32,6 +32,8 @@
  *     as the finite magnitude 2^128 (so it saturates and e = 127); the sign bit
  *     of the input is copied to the code even when the magnitude rounds to 0.
  *   - rows == 0 or cols == 0 is a successful no-op.
+ *   - A call made while another device than the handle's is current returns
+ *     FB4_ERR_INVALID_ARG.
  */
 #ifndef FB4_H
 #define FB4_H

@@ -28,6 +28,18 @@ using namespace fb4;
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// The tables live on the device the handle was built on: launching from another current device would hand
+// the kernels a foreign pointer.
+int check_device(const fb4_luts* l)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return FB4_ERR_HIP;
+    }
+    return dev == l->device ? FB4_OK : FB4_ERR_INVALID_ARG;
+}
+
 int grid_for(const fb4_luts* l, long long n_tiles)
 {
     long long groups = (n_tiles + kWavesPerGroup - 1) / kWavesPerGroup;
@@ -274,6 +286,7 @@ int fb4_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int6
 {
     int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
     if (rc != FB4_OK || rows == 0 || cols == 0) return rc;
+    if ((rc = check_device(luts)) != FB4_OK) return rc;
     QuantParams p = {};
     if (!tiling(rows, cols, opts->block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
     p.x = static_cast<const uint16_t*>(x);
@@ -299,6 +312,7 @@ int fb4_quantize_seda(const fb4_luts* luts, const fb4_opts* opts, const void* x,
     if (rows == 0 || cols == 0) return FB4_OK;
     if (!token_group || !sub_formatbooks) return FB4_ERR_INVALID_ARG;
     if (!aligned(token_group, 4)) return FB4_ERR_UNSUPPORTED;
+    if ((rc = check_device(luts)) != FB4_OK) return rc;
     QuantParams p = {};
     if (!tiling(rows, cols, opts->block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
     p.x = static_cast<const uint16_t*>(x);
@@ -333,6 +347,7 @@ int fb4_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int
     if (!codes1 || !meta1 || !salient_rows) return FB4_ERR_INVALID_ARG;
     if (!aligned(codes1, 4) || !aligned(meta1, 2) || !aligned(salient_rows, 4)) return FB4_ERR_UNSUPPORTED;
     if (n_sal > rows) return FB4_ERR_INVALID_ARG;   // ascending and unique implies n_sal <= rows
+    if ((rc = check_device(luts)) != FB4_OK) return rc;
     QuantParams p = {};
     if (!tiling(n_sal, cols, opts->block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
     p.x = static_cast<const uint16_t*>(x);
@@ -367,6 +382,7 @@ int fb4_quantize_decompose(const fb4_luts* luts, const fb4_opts* opts, const voi
     if (n_sal > 0 && (!salient_rows || !codes2 || !meta2)) return FB4_ERR_INVALID_ARG;
     if (seda && !aligned(token_group, 4)) return FB4_ERR_UNSUPPORTED;
     if (n_sal > 0 && (!aligned(salient_rows, 4) || !aligned(codes2, 4) || !aligned(meta2, 2))) return FB4_ERR_UNSUPPORTED;
+    if ((rc = check_device(luts)) != FB4_OK) return rc;
     if (n_sal > 0) {
         // one pass: the second plane is formed from the registers that hold the tile
         QuantParams p = {};
@@ -410,6 +426,7 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
     if (n_sal > 0 && (!aligned(codes2, 4) || !aligned(meta2, 2) || !aligned(salient_rows, 4)))
         return FB4_ERR_UNSUPPORTED;
 
+    if (int rc = check_device(luts)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     DequantParams p = {};
     if (!tiling(rows, cols, block, &p.nb, &p.tiles_per_row, &p.n_tiles)) return FB4_ERR_UNSUPPORTED;
@@ -488,6 +505,7 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
     const uint64_t nb32 = (uint64_t)cols / 32;
     const uint64_t n_chunks = (uint64_t)rows * nb32;
     if (n_chunks >= 0x3FFFFF00ull) return FB4_ERR_UNSUPPORTED;
+    if (int rc = check_device(luts)) return rc;
     RepackParams f = {};
     f.codes = codes;
     f.meta = meta;
@@ -525,6 +543,7 @@ int fb4_seda_profile(const fb4_luts* luts, const uint16_t* meta, int64_t rows, i
     if (rows > 0 && blocks_per_row > 0 && (!meta || !anchor_group)) return FB4_ERR_INVALID_ARG;
     if (!aligned(counts, 4) || (meta && !aligned(meta, 2)) || (anchor_group && !aligned(anchor_group, 4)))
         return FB4_ERR_UNSUPPORTED;
+    if (int rc = check_device(luts)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t n = (uint32_t)n_groups * 32u;
     // cleared by a kernel (not a memset node), so the call can be captured into a HIP graph

@@ -628,6 +628,66 @@ def test_mxfp8_repack(F, luts, block):
     assert np.array_equal(host_u8(el2), elr) and np.array_equal(host_u8(sc2), scr)
 
 
+# ------------------------------------------------------------ random sweep
+def test_random_shapes_options_and_magnitudes(F, luts):
+    """Seeded sweep over shapes (ragged tiles, row strides), block sizes, selectors, group counts, flags, SeDA
+    lists and salient sets, on data whose rows span 40 binades and contain exact zeros; every entry point
+    against the oracle."""
+    fbk = DEFAULT_FORMATBOOK
+    rng = np.random.default_rng(60)
+    for case in range(48):
+        block = int(rng.choice([32, 16]))
+        rows = int(rng.integers(1, 70))
+        nblk = int(rng.integers(1, 41))
+        cols = block * nblk
+        stride = cols + 8 * int(rng.integers(0, 4))
+        sel = int(rng.choice([F.SEL_LUT, F.SEL_LUT, F.SEL_SSE]))
+        g = int(rng.choice([8, 16, 32] if block == 32 else [8, 16]))
+        flags = int(rng.choice([0, F.FLAG_TWO_STAGE]))
+        what = "case %d: block %d %dx%d stride %d sel %d g %d flags %d" % (case, block, rows, cols, stride, sel, g, flags)
+        v = rng.standard_t(3, size=(rows, stride)).astype(np.float32)
+        v *= np.exp2(rng.integers(-20, 21, size=(rows, 1))).astype(np.float32)
+        v[rng.random((rows, stride)) < 0.05] = 0.0
+        full = torch.from_numpy(v).to(torch.bfloat16).cuda()
+        x = full[:, :cols]
+        xb = np.ascontiguousarray(synth.bf16_bits(full)[:, :cols])
+        o = F.opts(block=block, selector=sel, num_groups=g, flags=flags)
+        use_seda = bool(rng.random() < 0.5)
+        tg = sub = tg_d = sub_d = None
+        if use_seda:
+            ng = int(rng.integers(1, 6))
+            sub = synth.seda_sub_formatbooks(fbk, n_groups=ng, seed=100 + case)
+            tg = rng.integers(-1, ng, size=rows).astype(np.int32)
+            tg_d, sub_d = torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda()
+        sal = np.nonzero(rng.random(rows) < 0.4)[0].astype(np.int32)
+        sal_d = torch.from_numpy(sal).cuda()
+        c1, m1, c2, m2 = F.fb4_quantize_decompose(luts, o, x, sal_d, token_group=tg_d, sub_formatbooks=sub_d)
+        s1, t1, s2, t2 = _both_planes_separately(F, luts, o, x, sal_d, tg_d, sub_d)
+        y = F.fb4_dequantize(luts, c1, m1, block=block, codes2=c2, meta2=m2, salient_rows=sal_d)
+        yf = F.fb4_dequantize(luts, c1, m1, block=block, out_dtype=F.DTYPE_F32)
+        torch.cuda.synchronize()
+        assert torch.equal(c1, s1) and torch.equal(m1, t1) and torch.equal(c2, s2) and torch.equal(m2, t2), what
+        c1r, m1r = O.quantize(fbk, xb, block=block, selector=sel, num_groups=g, flags=flags, token_group=tg,
+                              sub_formatbooks=sub)
+        compare_quant(fbk, xb, host_u8(c1), host_u16(m1), c1r, m1r, sel, g, flags=flags, token_group=tg, sub=sub,
+                      block=block, what=what)
+        c2r, m2r = O.decompose(fbk, xb, host_u8(c1), host_u16(m1), sal, block=block, selector=sel, num_groups=g,
+                               flags=flags, token_group=tg, sub_formatbooks=sub)
+        if sal.size:
+            compare_quant(fbk, xb[sal], host_u8(c2), host_u16(m2), c2r, m2r, sel, g, flags=flags,
+                          token_group=None if tg is None else tg[sal], sub=sub, block=block, what=what + " plane 2")
+        yr = O.dequantize(fbk, host_u8(c1), host_u16(m1), block=block, codes2=host_u8(c2), meta2=host_u16(m2),
+                          salient_rows=sal)
+        assert np.array_equal(synth.bf16_bits(y), yr), what
+        yfr = O.dequantize(fbk, host_u8(c1), host_u16(m1), block=block, out_dtype=O.OUT_F32)
+        assert np.array_equal(yf.cpu().numpy().view(np.uint32), yfr.view(np.uint32)), what
+        if cols % 32 == 0:
+            el, sc = F.fb4_repack_mxfp8(luts, c1, m1, block=block)
+            torch.cuda.synchronize()
+            elr, scr = O.repack_mxfp8(fbk, host_u8(c1), host_u16(m1), block=block)
+            assert np.array_equal(host_u8(el), elr) and np.array_equal(host_u8(sc), scr), what
+
+
 def test_luts_handle_is_reusable_across_streams(F, luts):
     x = synth.gaussian_outlier(rows=256, cols=1024, seed=45, device="cuda")
     o = F.opts()
