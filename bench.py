@@ -91,8 +91,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
-                    help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: a few plain device copies of known size, "
-                         "then a few quantize launches; prints nothing but a marker line")
+                    help="for `rocprofv3 --pmc ...`: a few plain device copies of known size, then a few "
+                         "launches of the headline kernel and of the exhaustive selector; prints a marker line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -125,6 +125,10 @@ def main():
             dst.copy_(xs[i % N_SETS])
         for i in range(10):
             F.fb4_quantize(luts, o, xs[i % N_SETS], codes=codes[i % N_SETS], meta=metas[i % N_SETS])
+        # the exhaustive selector, for its instruction and LDS counters
+        o_sse = F.opts(block=BLOCK, selector=F.SEL_SSE)
+        for i in range(4):
+            F.fb4_quantize(luts, o_sse, xs[i % N_SETS], codes=codes[i % N_SETS], meta=metas[i % N_SETS])
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": True, "copy_bytes_read": x0.numel() * 2, "copy_bytes_written": x0.numel() * 2,
                           "quantize_algorithmic_bytes": abytes}))

@@ -615,7 +615,8 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
         if (kDecomp) {
             // Salient rows as a bitmap.  The list is ascending and unique, so the position of row r in it is
             // (entries below row 0) + (salient rows below r): kept as a running count per bitmap word.
-            static_assert(!kDecomp || kFastThreads * 4 * 32 == kMaxFusedRows, "four bitmap words per thread");
+            constexpr uint32_t kScanners = kMaxFusedRows / 32 / 4;   // threads that own four bitmap words each
+            static_assert(!kDecomp || (uint32_t)kFastThreads >= kScanners, "four bitmap words per thread");
             uint32_t* bits = reinterpret_cast<uint32_t*>(lds + kLdsSalBits);
             auto mark = [&](int32_t r) {
                 if (r < 0) atomicAdd(&sal_before, 1u);
@@ -628,7 +629,8 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
                 for (uint32_t i = threadIdx.x; i < p.n_sal; i += kFastThreads) mark(p.salient[i]);
             }
             __syncthreads();
-            const uint4 wv = reinterpret_cast<const uint4*>(bits)[threadIdx.x];
+            const bool scanner = threadIdx.x < kScanners;
+            const uint4 wv = scanner ? reinterpret_cast<const uint4*>(bits)[threadIdx.x] : make_uint4(0, 0, 0, 0);
             const uint32_t c0 = __builtin_popcount(wv.x), c1 = c0 + __builtin_popcount(wv.y);
             const uint32_t c2 = c1 + __builtin_popcount(wv.z), c3 = c2 + __builtin_popcount(wv.w);
             uint32_t incl = c3;   // inclusive scan over the wavefront
@@ -641,9 +643,11 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
             __syncthreads();
             uint32_t base = sal_before + incl - c3;
             for (uint32_t k = 0; k < wave; ++k) base += sal_wave[k];
-            uint16_t* rank = reinterpret_cast<uint16_t*>(lds + kLdsSalRank) + threadIdx.x * 4;
-            rank[0] = (uint16_t)base; rank[1] = (uint16_t)(base + c0);
-            rank[2] = (uint16_t)(base + c1); rank[3] = (uint16_t)(base + c2);
+            if (scanner) {
+                uint16_t* rank = reinterpret_cast<uint16_t*>(lds + kLdsSalRank) + threadIdx.x * 4;
+                rank[0] = (uint16_t)base; rank[1] = (uint16_t)(base + c0);
+                rank[2] = (uint16_t)(base + c1); rank[3] = (uint16_t)(base + c2);
+            }
         }
         // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
         for (int i = threadIdx.x; i < 1024; i += kFastThreads) {
