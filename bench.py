@@ -157,7 +157,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32",
+        "dtype": "u16",
         "data": "synthetic",
         "config": {
             "workload": "cfg2: Open-Sora-2.0-like VDiT activation 16384x3072 bf16, Student-t(3), per-frame "
@@ -169,7 +169,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-            "kernel": "fb4::quantize_lut_kernel<32, 8, true, false, false>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
+            "kernel": "fb4::quantize_lut_kernel<32, 8, true, false, false, false>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
         },
     }
 
