@@ -461,12 +461,29 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
         const long long cap = (long long)luts->n_cu * 2;
         if (groups > cap) groups = cap;
         const bool flat = out_row_stride == cols;
+        const dim3 dg((unsigned)groups), db(kDeqThreads);
+        if (n_sal > 0 && rows <= (int64_t)kMaxFusedRows) {
+            // salient rows get both planes in the same pass
+            f.codes2 = codes2;
+            f.meta2 = meta2;
+            f.salient = salient_rows;
+            f.n_sal = (uint32_t)n_sal;
+            f.rows = (uint32_t)rows;
+            if (out_dtype == FB4_DTYPE_F32) {
+                if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, true, true>), dg, db, 0, s, f);
+                else hipLaunchKernelGGL((dequantize_fast_kernel<false, true, true>), dg, db, 0, s, f);
+            } else {
+                if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, false, true>), dg, db, 0, s, f);
+                else hipLaunchKernelGGL((dequantize_fast_kernel<false, false, true>), dg, db, 0, s, f);
+            }
+            return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+        }
         if (out_dtype == FB4_DTYPE_F32) {
-            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, true>), dim3((unsigned)groups), dim3(kDeqThreads), 0, s, f);
-            else hipLaunchKernelGGL((dequantize_fast_kernel<false, true>), dim3((unsigned)groups), dim3(kDeqThreads), 0, s, f);
+            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, true>), dg, db, 0, s, f);
+            else hipLaunchKernelGGL((dequantize_fast_kernel<false, true>), dg, db, 0, s, f);
         } else {
-            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, false>), dim3((unsigned)groups), dim3(kDeqThreads), 0, s, f);
-            else hipLaunchKernelGGL((dequantize_fast_kernel<false, false>), dim3((unsigned)groups), dim3(kDeqThreads), 0, s, f);
+            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, false>), dg, db, 0, s, f);
+            else hipLaunchKernelGGL((dequantize_fast_kernel<false, false>), dg, db, 0, s, f);
         }
     } else if (out_dtype == FB4_DTYPE_F32) {
         hipLaunchKernelGGL((dequantize_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p);

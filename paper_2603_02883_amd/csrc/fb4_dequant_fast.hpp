@@ -28,12 +28,64 @@ struct DeqFastParams {
     long long out_row_stride; // elements
     uint32_t nb, n_blocks, n_tiles, div_mul, div_shift;
     const uint8_t* blob;
+    // kSum: second plane of the salient rows (Sec. 3.3), added in fp32
+    const uint8_t* codes2;    // [n_sal][nb * 16]
+    const uint16_t* meta2;
+    const int32_t* salient;   // [n_sal] ascending, unique
+    uint32_t n_sal;
+    uint32_t rows;            // <= kMaxFusedRows
 };
 
-template <bool kFlat, bool kF32>
+// Decoded pair (two bf16 patterns) of one code byte: table entry for exponent byte 130 plus the block's
+// exponent offset on every non-zero half.
+__device__ __forceinline__ uint32_t decode_pair(const uint32_t* pair, uint32_t base, uint32_t byte, uint32_t live,
+                                                uint32_t eoff2)
+{
+    const uint32_t v = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(pair) + base + byte * 4) & live;
+    const uint32_t nz = pk_min(v & 0x7FFF7FFFu, 0x00010001u);          // 1 where the magnitude is not zero
+    const u16x2 r = __builtin_bit_cast(u16x2, nz) * __builtin_bit_cast(u16x2, eoff2) + __builtin_bit_cast(u16x2, v);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// kSum: rows listed in p.salient are written as round(fp32(plane 1) + fp32(plane 2)); a bitmap of those rows
+// with a running count per bitmap word (LDS) gives a row's position in the compact second plane.
+template <bool kFlat, bool kF32, bool kSum = false>
 __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(DeqFastParams p)
 {
     __shared__ __align__(16) uint32_t pair[32 * 256];   // [DID][code byte] -> two bf16 patterns
+    __shared__ __align__(16) uint32_t sal_bits[kSum ? kMaxFusedRows / 32 : 4];
+    __shared__ uint16_t sal_rank[kSum ? kMaxFusedRows / 32 : 4];
+    __shared__ uint32_t sal_before, sal_wave[kDeqWaves];
+    if (kSum) {
+        static_assert(kDeqThreads * 4 * 32 == (int)kMaxFusedRows, "four bitmap words per thread");
+        for (uint32_t i = threadIdx.x; i < kMaxFusedRows / 32; i += kDeqThreads) sal_bits[i] = 0;
+        if (threadIdx.x == 0) sal_before = 0;
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < p.n_sal; i += kDeqThreads) {
+            const int32_t r = p.salient[i];
+            if (r < 0) atomicAdd(&sal_before, 1u);
+            else if ((uint32_t)r < p.rows) atomicOr(&sal_bits[(uint32_t)r >> 5], 1u << (r & 31));
+        }
+        __syncthreads();
+        const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const uint4 wv = reinterpret_cast<const uint4*>(sal_bits)[threadIdx.x];
+        const uint32_t c0 = __builtin_popcount(wv.x), c1 = c0 + __builtin_popcount(wv.y);
+        const uint32_t c2 = c1 + __builtin_popcount(wv.z), c3 = c2 + __builtin_popcount(wv.w);
+        uint32_t incl = c3;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t v = __shfl_up(incl, off);
+            if ((int)lane >= off) incl += v;
+        }
+        if (lane == 63) sal_wave[wave] = incl;
+        __syncthreads();
+        uint32_t base = sal_before + incl - c3;
+        for (uint32_t k = 0; k < wave; ++k) base += sal_wave[k];
+        sal_rank[threadIdx.x * 4] = (uint16_t)base;
+        sal_rank[threadIdx.x * 4 + 1] = (uint16_t)(base + c0);
+        sal_rank[threadIdx.x * 4 + 2] = (uint16_t)(base + c1);
+        sal_rank[threadIdx.x * 4 + 3] = (uint16_t)(base + c2);
+    }
     {
         // thread (DID, high nibble) fills 16 entries
         const uint32_t did = threadIdx.x >> 4, hn = threadIdx.x & 15;
@@ -80,12 +132,40 @@ __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(DeqFastPar
             const uint32_t live = did < 32u ? 0xFFFFFFFFu : 0u;
             uint32_t o[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const uint32_t byte = (cw[u] >> (8 * k)) & 0xFFu;
-                const uint32_t v = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(pair) + base + byte * 4) & live;
-                const uint32_t nz = pk_min(v & 0x7FFF7FFFu, 0x00010001u);          // 1 where the magnitude is not zero
-                const u16x2 r = __builtin_bit_cast(u16x2, nz) * __builtin_bit_cast(u16x2, eoff2) + __builtin_bit_cast(u16x2, v);
-                o[k] = __builtin_bit_cast(uint32_t, r);
+            for (int k = 0; k < 4; ++k) o[k] = decode_pair(pair, base, (cw[u] >> (8 * k)) & 0xFFu, live, eoff2);
+            float fsum[8];
+            bool summed = false;
+            if (kSum) {
+                const uint32_t gb = i >> 2;
+                const uint32_t row = (uint32_t)(((unsigned long long)gb * p.div_mul) >> p.div_shift);
+                const uint32_t wbits = sal_bits[row >> 5];
+                if ((wbits >> (row & 31)) & 1u) {
+                    // second plane: same decode, then one fp32 addition per element
+                    summed = true;
+                    const size_t pos = sal_rank[row >> 5] + __builtin_popcount(wbits & ((1u << (row & 31)) - 1u));
+                    const size_t w2 = (pos * p.nb + (gb - row * p.nb)) * 4 + (i & 3u);
+                    const uint32_t c2 = reinterpret_cast<const uint32_t*>(p.codes2)[w2];
+                    const uint32_t m2 = p.meta2[w2 >> p.meta_shift];
+                    const uint32_t did2 = m2 & 0xFFu;
+                    const uint32_t e2 = (((m2 >> 8) - 130u) << 7) & 0xFFFFu;
+                    const uint32_t base2 = (did2 < 32u ? did2 : 0u) * 1024u;
+                    const uint32_t live2 = did2 < 32u ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const uint32_t q = decode_pair(pair, base2, (c2 >> (8 * k)) & 0xFFu, live2, e2 | (e2 << 16));
+                        fsum[2 * k] = __uint_as_float(o[k] << 16) + __uint_as_float(q << 16);
+                        fsum[2 * k + 1] = __uint_as_float(o[k] & 0xFFFF0000u) + __uint_as_float(q & 0xFFFF0000u);
+                    }
+                    if (!kF32) {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            uint32_t a = __float_as_uint(fsum[2 * k]), b = __float_as_uint(fsum[2 * k + 1]);
+                            a += 0x7FFFu + ((a >> 16) & 1u);           // round to nearest even
+                            b += 0x7FFFu + ((b >> 16) & 1u);
+                            o[k] = (a >> 16) | (b & 0xFFFF0000u);
+                        }
+                    }
+                }
             }
             long long off;   // elements
             if (kFlat) {
@@ -97,8 +177,12 @@ __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(DeqFastPar
             }
             if (kF32) {
                 u32x4* dst = reinterpret_cast<u32x4*>(reinterpret_cast<float*>(p.out) + off);
-                const u32x4 v0 = {o[0] << 16, o[0] & 0xFFFF0000u, o[1] << 16, o[1] & 0xFFFF0000u};
-                const u32x4 v1 = {o[2] << 16, o[2] & 0xFFFF0000u, o[3] << 16, o[3] & 0xFFFF0000u};
+                u32x4 v0 = {o[0] << 16, o[0] & 0xFFFF0000u, o[1] << 16, o[1] & 0xFFFF0000u};
+                u32x4 v1 = {o[2] << 16, o[2] & 0xFFFF0000u, o[3] << 16, o[3] & 0xFFFF0000u};
+                if (kSum && summed) {
+                    v0 = u32x4{__float_as_uint(fsum[0]), __float_as_uint(fsum[1]), __float_as_uint(fsum[2]), __float_as_uint(fsum[3])};
+                    v1 = u32x4{__float_as_uint(fsum[4]), __float_as_uint(fsum[5]), __float_as_uint(fsum[6]), __float_as_uint(fsum[7])};
+                }
                 __builtin_nontemporal_store(v0, dst);
                 __builtin_nontemporal_store(v1, dst + 1);
             } else {

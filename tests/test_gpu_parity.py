@@ -558,6 +558,13 @@ def test_quantize_decompose_in_one_pass(F, luts, block):
     want = _both_planes_separately(F, luts, F.opts(block=block), x, sal_d)
     torch.cuda.synchronize()
     assert all(torch.equal(g, w) for g, w in zip(got, want))
+    # ... and the decode of that many rows adds the second plane in a pass of its own
+    y = F.fb4_dequantize(luts, got[0], got[1], block=block, codes2=got[2], meta2=got[3], salient_rows=sal_d)
+    torch.cuda.synchronize()
+    sal = sal_d.cpu().numpy()
+    yr = O.dequantize(DEFAULT_FORMATBOOK, host_u8(got[0]), host_u16(got[1]), block=block, codes2=host_u8(got[2]),
+                      meta2=host_u16(got[3]), salient_rows=sal)
+    assert np.array_equal(synth.bf16_bits(y), yr)
 
 
 # ------------------------------------------------ sub-formatbook construction
