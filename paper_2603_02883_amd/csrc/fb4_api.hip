@@ -157,7 +157,10 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
         f.meta2 = fused->meta2;
     }
     long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
-    const long long cap = (long long)luts->n_cu * FB4_FAST_GROUPS_PER_CU;
+    // persistent workgroups: as many as are resident at once (the variant with both the SeDA rows and the
+    // salient-row tables needs more than half of a compute unit's LDS)
+    const bool one_per_cu = lds_fast_bytes(token_group != nullptr, fused != nullptr) > 80 * 1024;
+    const long long cap = (long long)luts->n_cu * (one_per_cu ? 1 : FB4_FAST_GROUPS_PER_CU);
     if (groups > cap) groups = cap;
     const unsigned ng = (unsigned)groups;
     const bool flat = p.row_stride == cols;
