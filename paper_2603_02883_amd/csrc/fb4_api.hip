@@ -157,10 +157,13 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
         f.meta2 = fused->meta2;
     }
     long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
-    // persistent workgroups: as many as are resident at once (the variant with both the SeDA rows and the
-    // salient-row tables needs more than half of a compute unit's LDS)
-    const bool one_per_cu = lds_fast_bytes(token_group != nullptr, fused != nullptr) > 80 * 1024;
-    const long long cap = (long long)luts->n_cu * (one_per_cu ? 1 : FB4_FAST_GROUPS_PER_CU);
+    // Persistent workgroups.  One per compute unit (8 wavefronts) is fastest for the plain variants: measured
+    // 24.4 us against 26.0 us with two on the 16384x3072 workload, and 4, 12 or 16 wavefronts are slower too.
+    // The variants with a per-row lookup (SeDA group, salient-row bitmap) gain from a second resident
+    // workgroup, unless both tables together need more than half of a compute unit's LDS.
+    const bool lookups = token_group != nullptr || fused != nullptr;
+    const bool fits_twice = lds_fast_bytes(token_group != nullptr, fused != nullptr) <= 80 * 1024;
+    const long long cap = (long long)luts->n_cu * ((lookups && fits_twice) ? 2 : 1);
     if (groups > cap) groups = cap;
     const unsigned ng = (unsigned)groups;
     const bool flat = p.row_stride == cols;
@@ -461,7 +464,7 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
         f.div_mul = (uint32_t)(((1ull << f.div_shift) + nb32 - 1) / nb32);
         f.blob = luts->dev_blob;
         long long groups = ((long long)f.n_tiles + kDeqWaves - 1) / kDeqWaves;
-        const long long cap = (long long)luts->n_cu * 2;
+        const long long cap = (long long)luts->n_cu * 3;   // three workgroups (and their tables) per CU
         if (groups > cap) groups = cap;
         const bool flat = out_row_stride == cols;
         const dim3 dg((unsigned)groups), db(kDeqThreads);
@@ -540,7 +543,7 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
     f.div_mul = (uint32_t)(((1ull << f.div_shift) + nb32 - 1) / nb32);
     f.blob = luts->dev_blob;
     long long groups = ((long long)n_chunks * 4 + kRepackThreads - 1) / kRepackThreads;
-    const long long cap = (long long)luts->n_cu * 4;
+    const long long cap = (long long)luts->n_cu * 3;
     if (groups > cap) groups = cap;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool flat = elem_row_stride == cols;

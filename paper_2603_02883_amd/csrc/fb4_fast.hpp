@@ -32,9 +32,6 @@ namespace fb4 {
 #ifndef FB4_FAST_THREADS
 #define FB4_FAST_THREADS 512
 #endif
-#ifndef FB4_FAST_GROUPS_PER_CU
-#define FB4_FAST_GROUPS_PER_CU 2   // resident workgroups per compute unit the grid is sized for
-#endif
 
 constexpr int kFastThreads = FB4_FAST_THREADS;
 constexpr int kFastWaves = kFastThreads / 64;
@@ -546,14 +543,14 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
     // the first tile is requested before anything else: it streams in while the tables are built
     cur = load_block<kFlat, kSeda>(p, t * 64u + lane);
     {
-        static_assert(kFastThreads >= 512, "one 16-byte Qerror piece and at most one Qvalue word per thread");
-        const int bin = threadIdx.x >> 4, half = (threadIdx.x >> 3) & 1;
-        uint4 rq = make_uint4(0, 0, 0, 0);
-        uint32_t nq = 0;
-        if (threadIdx.x < 512) rq = *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
-        if (threadIdx.x < 256) nq = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[threadIdx.x];
-        if (threadIdx.x < 512) reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x] = rq;   // eight bank-disjoint copies
-        if (threadIdx.x < 256) reinterpret_cast<uint32_t*>(lds + kLdsNibT)[threadIdx.x] = nq;
+        // Qerror rows as eight bank-disjoint copies: piece i = (bin, half, copy) is 16 bytes of row `bin`
+        for (int i = threadIdx.x; i < 512; i += kFastThreads) {
+            const int bin = i >> 4, half = (i >> 3) & 1;
+            reinterpret_cast<uint4*>(lds + kLdsRows)[i] =
+                *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
+        }
+        for (int i = threadIdx.x; i < 256; i += kFastThreads)
+            reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[i];
         if (kTwoStage && threadIdx.x < 64)
             reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] =
                 reinterpret_cast<const uint32_t*>(p.blob + kOffRangeExcl)[threadIdx.x];
@@ -617,8 +614,8 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
         if (kDecomp) {
             // Salient rows as a bitmap.  The list is ascending and unique, so the position of row r in it is
             // (entries below row 0) + (salient rows below r): kept as a running count per bitmap word.
-            constexpr uint32_t kScanners = kMaxFusedRows / 32 / 4;   // threads that own four bitmap words each
-            static_assert(!kDecomp || (uint32_t)kFastThreads >= kScanners, "four bitmap words per thread");
+            constexpr uint32_t kWords = kMaxFusedRows / 32;
+            constexpr uint32_t kWpt = (kWords + kFastThreads - 1) / kFastThreads;   // bitmap words per thread
             uint32_t* bits = reinterpret_cast<uint32_t*>(lds + kLdsSalBits);
             auto mark = [&](int32_t r) {
                 if (r < 0) atomicAdd(&sal_before, 1u);
@@ -631,11 +628,15 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
                 for (uint32_t i = threadIdx.x; i < p.n_sal; i += kFastThreads) mark(p.salient[i]);
             }
             __syncthreads();
-            const bool scanner = threadIdx.x < kScanners;
-            const uint4 wv = scanner ? reinterpret_cast<const uint4*>(bits)[threadIdx.x] : make_uint4(0, 0, 0, 0);
-            const uint32_t c0 = __builtin_popcount(wv.x), c1 = c0 + __builtin_popcount(wv.y);
-            const uint32_t c2 = c1 + __builtin_popcount(wv.z), c3 = c2 + __builtin_popcount(wv.w);
-            uint32_t incl = c3;   // inclusive scan over the wavefront
+            uint32_t run[kWpt];   // salient rows in this thread's words before word k
+            uint32_t total = 0;
+#pragma unroll
+            for (uint32_t k = 0; k < kWpt; ++k) {
+                const uint32_t wi = threadIdx.x * kWpt + k;
+                run[k] = total;
+                total += wi < kWords ? (uint32_t)__builtin_popcount(bits[wi]) : 0u;
+            }
+            uint32_t incl = total;   // inclusive scan over the wavefront
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const uint32_t v = __shfl_up(incl, off);
@@ -643,12 +644,12 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
             }
             if (lane == 63) sal_wave[wave] = incl;
             __syncthreads();
-            uint32_t base = sal_before + incl - c3;
+            uint32_t base = sal_before + incl - total;
             for (uint32_t k = 0; k < wave; ++k) base += sal_wave[k];
-            if (scanner) {
-                uint16_t* rank = reinterpret_cast<uint16_t*>(lds + kLdsSalRank) + threadIdx.x * 4;
-                rank[0] = (uint16_t)base; rank[1] = (uint16_t)(base + c0);
-                rank[2] = (uint16_t)(base + c1); rank[3] = (uint16_t)(base + c2);
+#pragma unroll
+            for (uint32_t k = 0; k < kWpt; ++k) {
+                const uint32_t wi = threadIdx.x * kWpt + k;
+                if (wi < kWords) reinterpret_cast<uint16_t*>(lds + kLdsSalRank)[wi] = (uint16_t)(base + run[k]);
             }
         }
         // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
