@@ -239,6 +239,17 @@ def main():
             k = i % N_SETS
             F.fb4_repack_mxfp8(luts, codes[k], metas[k], elems=els[k], scales=scs[k])
         add("repack_mxfp8", repack_step, n_el // 2 + n_el // 16 + n_el + n_el // 32, n_el)
+        # the headline kernel on a four times larger tensor (65536 x 3072): the fixed cost of a launch (table
+        # set-up, pipeline fill and drain) weighs less
+        del els, scs, outs
+        big = [x0.repeat(4, 1) for _ in range(3)]
+        bc = [torch.empty((4 * ROWS, COLS // 2), dtype=torch.uint8, device="cuda") for _ in range(3)]
+        bm = [torch.empty((4 * ROWS, COLS // BLOCK), dtype=torch.int16, device="cuda") for _ in range(3)]
+
+        def big_step(i):
+            k = i % 3
+            F.fb4_quantize(luts, o_main, big[k], codes=bc[k], meta=bm[k])
+        add("quantize_lut_g8_65536x3072", big_step, 4 * abytes, 4 * n_el)
         result["extras"] = extras
 
     # ---- CPU oracle on the host cores of this machine (a baseline for context, not a target)
