@@ -695,6 +695,64 @@ def test_random_shapes_options_and_magnitudes(F, luts):
             assert np.array_equal(host_u8(el), elr) and np.array_equal(host_u8(sc), scr), what
 
 
+def test_entry_points_replay_correctly_from_a_hip_graph(F, luts):
+    """Every entry point only enqueues kernels (no allocation, no memset node), so a captured sequence must
+    give the eager results on every replay, also after the inputs changed in place."""
+    rows, cols = 512, 3072
+    x = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+    sal = torch.arange(3, rows, 17, dtype=torch.int32, device="cuda")
+    anchors = torch.where(torch.arange(rows, device="cuda") % 5 == 0, torch.arange(rows, device="cuda") % 4, -1).int()
+    o = F.opts()
+    c1 = torch.empty((rows, cols // 2), dtype=torch.uint8, device="cuda")
+    m1 = torch.empty((rows, cols // 32), dtype=torch.int16, device="cuda")
+    c2 = torch.empty((sal.numel(), cols // 2), dtype=torch.uint8, device="cuda")
+    m2 = torch.empty((sal.numel(), cols // 32), dtype=torch.int16, device="cuda")
+    y = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+    el = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+    sc = torch.empty((rows, cols // 32), dtype=torch.uint8, device="cuda")
+    counts = torch.empty((4, 32), dtype=torch.int32, device="cuda")
+    sub = torch.empty((4, 8), dtype=torch.uint8, device="cuda")
+    cs = torch.empty_like(c1)
+    ms = torch.empty_like(m1)
+    tg = (torch.arange(rows, device="cuda") % 4).int()
+
+    def sequence():
+        F.fb4_quantize_decompose(luts, o, x, sal, codes1=c1, meta1=m1, codes2=c2, meta2=m2)
+        F.fb4_dequantize(luts, c1, m1, codes2=c2, meta2=m2, salient_rows=sal, out=y)
+        F.fb4_repack_mxfp8(luts, c1, m1, elems=el, scales=sc)
+        F.fb4_seda_profile(luts, m1, anchors, 4, counts=counts, sub_formatbooks=sub)
+        F.fb4_quantize_seda(luts, o, x, tg, sub, codes=cs, meta=ms)
+
+    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms)
+    x.copy_(synth.vdit_activation(rows=rows, cols=cols, seed=70, device="cuda"))
+    sequence()                                                # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            sequence()
+    torch.cuda.synchronize()
+    for rep, seed in enumerate((71, 72, 73)):
+        x.copy_(synth.vdit_activation(rows=rows, cols=cols, seed=seed, device="cuda"))
+        for t in outs:
+            t.fill_(7 if t.dtype != torch.bfloat16 else 0.5)
+        sequence()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in outs]
+        for t in outs:
+            t.fill_(9 if t.dtype != torch.bfloat16 else 0.25)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k, (a, b) in enumerate(zip(outs, want)):
+            assert torch.equal(a, b), "replay %d: output %d differs from the eager run" % (rep, k)
+    # and the eager results themselves are the oracle's (last input)
+    xb = synth.bf16_bits(x)
+    c1r, m1r = O.quantize(DEFAULT_FORMATBOOK, xb)
+    assert np.array_equal(host_u8(c1), c1r) and np.array_equal(host_u16(m1), m1r)
+
+
 def test_luts_handle_is_reusable_across_streams(F, luts):
     x = synth.gaussian_outlier(rows=256, cols=1024, seed=45, device="cuda")
     o = F.opts()
