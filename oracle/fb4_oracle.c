@@ -32,7 +32,17 @@
  *     byte j; metadata is DID | (e+127) << 8;
  *   - the residual of the decomposition is computed exactly and rounded once
  *     to bf16 (round to nearest even); a non-finite input is its own residual;
- *   - a reconstructed salient value is bf16(fp32(y1) + fp32(y2)).
+ *   - a reconstructed salient value is bf16(fp32(y1) + fp32(y2));
+ *   - MXFP8 operands: block size 32 maps one to one; with block size 16 the
+ *     two blocks of an MX block share the larger exponent and the other
+ *     block's magnitudes are shifted down and rounded to nearest even in E4M3.
+ *
+ * Every routine here is pinned by tests/test_oracle_pins.py against hand-worked
+ * fixtures, closed forms, exact rational brute force or torch's own number
+ * formats.  Parity unpinned: the VALUES of the default 32-dialect formatbook
+ * (input data of every routine; the paper gives them only in a figure that is
+ * not available), and how often the online rule and the exhaustive rule pick
+ * the same dialect (the paper only says quality is comparable).
  */
 #include <math.h>
 #include <stdint.h>
