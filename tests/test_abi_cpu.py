@@ -222,3 +222,18 @@ def test_build_luts_rejects_bad_formatbooks_on_the_host():
     rc = B.lib().fb4_build_luts_host(fb.ctypes.data_as(ctypes.c_void_p), 32, small.ctypes.data_as(ctypes.c_void_p),
                                      16, ctypes.byref(size))
     assert rc == F.ERR_INVALID_ARG
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/fb4.h must compile as C (no C++ or HIP types in the boundary) and as C++."""
+    import subprocess
+    src = tmp_path / "use_fb4.c"
+    src.write_text('#include "fb4.h"\n'
+                   "int use(const fb4_luts* l, const fb4_opts* o, const void* x, unsigned char* c, unsigned short* m) {\n"
+                   "    return fb4_quantize(l, o, x, 1, 32, 32, c, m, (void*)0) + fb4_version();\n"
+                   "}\n")
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    cpp = tmp_path / "use_fb4.cpp"
+    cpp.write_text(src.read_text())
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)], check=True)
