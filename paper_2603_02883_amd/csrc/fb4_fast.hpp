@@ -611,6 +611,17 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
             }
         }
         __syncthreads();
+        // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
+        for (int i = threadIdx.x; i < 1024; i += kFastThreads) {
+            const int hi = i >> 5, lo = i & 31;
+            const uint4* rl = reinterpret_cast<const uint4*>(lds + kLdsNibT + lo * 32);
+            const uint4* rh = reinterpret_cast<const uint4*>(lds + kLdsNibT + hi * 32);
+            uint4* dst = reinterpret_cast<uint4*>(lds + kLdsPair + i * 32);
+            const uint4 l0 = rl[0], l1 = rl[1], h0 = rh[0], h1 = rh[1];
+            dst[0] = make_uint4(l0.x | (h0.x << 4), l0.y | (h0.y << 4), l0.z | (h0.z << 4), l0.w | (h0.w << 4));
+            dst[1] = make_uint4(l1.x | (h1.x << 4), l1.y | (h1.y << 4), l1.z | (h1.z << 4), l1.w | (h1.w << 4));
+        }
+        // (the salient-row tables come after the pair table: their list is still on its way from memory)
         if (kDecomp) {
             // Salient rows as a bitmap.  The list is ascending and unique, so the position of row r in it is
             // (entries below row 0) + (salient rows below r): kept as a running count per bitmap word.
@@ -651,16 +662,6 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
                 const uint32_t wi = threadIdx.x * kWpt + k;
                 if (wi < kWords) reinterpret_cast<uint16_t*>(lds + kLdsSalRank)[wi] = (uint16_t)(base + run[k]);
             }
-        }
-        // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
-        for (int i = threadIdx.x; i < 1024; i += kFastThreads) {
-            const int hi = i >> 5, lo = i & 31;
-            const uint4* rl = reinterpret_cast<const uint4*>(lds + kLdsNibT + lo * 32);
-            const uint4* rh = reinterpret_cast<const uint4*>(lds + kLdsNibT + hi * 32);
-            uint4* dst = reinterpret_cast<uint4*>(lds + kLdsPair + i * 32);
-            const uint4 l0 = rl[0], l1 = rl[1], h0 = rh[0], h1 = rh[1];
-            dst[0] = make_uint4(l0.x | (h0.x << 4), l0.y | (h0.y << 4), l0.z | (h0.z << 4), l0.w | (h0.w << 4));
-            dst[1] = make_uint4(l1.x | (h1.x << 4), l1.y | (h1.y << 4), l1.z | (h1.z << 4), l1.w | (h1.w << 4));
         }
         __syncthreads();
     }
