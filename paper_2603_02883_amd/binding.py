@@ -3,7 +3,8 @@
 Argument marshalling only -- every step of the quantizer runs in the library's
 HIP kernels.  PyTorch tensors are used for device memory and for the current
 stream; nothing here computes on them.  There is no CPU fallback: if the
-library has not been built, importing this module raises.
+library is not there it is compiled once (hipcc), and if that fails importing
+this module raises.
 """
 
 import ctypes
@@ -42,8 +43,12 @@ class fb4_opts(ctypes.Structure):
 
 def _load():
     if not os.path.exists(_build.LIB):
-        raise ImportError("libfb4.so is not built: run `python -m paper_2603_02883_amd.build` "
-                          "(or __graft_entry__.build()) first; there is no CPU fallback")
+        # nothing built yet (fresh checkout): compile once; an existing library is loaded as it is
+        try:
+            _build.build(force=True)
+        except Exception as e:   # no compiler, compile error: fail loudly, there is no CPU fallback
+            raise ImportError("libfb4.so is not built and could not be compiled (%s); run "
+                              "`python paper_2603_02883_amd/build.py`; there is no CPU fallback" % e)
     lib = ctypes.CDLL(_build.LIB)
     p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.fb4_version.restype = i32

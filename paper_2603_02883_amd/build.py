@@ -8,8 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfb4.so")
 SOURCES = [os.path.join(CSRC, "fb4_api.hip")]
-DEPS = SOURCES + [os.path.join(CSRC, "fb4_kernels.hpp"), os.path.join(CSRC, "fb4_tables.hpp"),
-                  os.path.join(os.path.dirname(HERE), "include", "fb4.h")]
+DEPS = SOURCES + [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".hpp")] + [
+    os.path.join(os.path.dirname(HERE), "include", "fb4.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
