@@ -157,13 +157,12 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
         f.meta2 = fused->meta2;
     }
     long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
-    // Persistent workgroups.  One per compute unit (8 wavefronts) is fastest for the plain variants: measured
-    // 24.4 us against 26.0 us with two on the 16384x3072 workload, and 4, 12 or 16 wavefronts are slower too.
-    // The variants with a per-row lookup (SeDA group, salient-row bitmap) gain from a second resident
-    // workgroup, unless both tables together need more than half of a compute unit's LDS.
-    const bool lookups = token_group != nullptr || fused != nullptr;
+    // Persistent workgroups.  One per compute unit (8 wavefronts) is fastest: measured 24.4 us against 26.0 us
+    // with two on the 16384x3072 workload (SeDA: 25.7 against 27.2), and 4, 12 or 16 wavefronts are slower
+    // too.  Only the variant that also forms the second plane, whose salient tiles cost twice the arithmetic,
+    // is not slower with a second resident workgroup, when its tables leave room for one.
     const bool fits_twice = lds_fast_bytes(token_group != nullptr, fused != nullptr) <= 80 * 1024;
-    const long long cap = (long long)luts->n_cu * ((lookups && fits_twice) ? 2 : 1);
+    const long long cap = (long long)luts->n_cu * ((fused != nullptr && fits_twice) ? 2 : 1);
     if (groups > cap) groups = cap;
     const unsigned ng = (unsigned)groups;
     const bool flat = p.row_stride == cols;

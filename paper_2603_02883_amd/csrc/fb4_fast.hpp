@@ -673,8 +673,25 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
     uint4 held_code = make_uint4(0, 0, 0, 0);
     uint32_t held_meta = 0, held_gb = 0;
     bool have_held = false;   // wave-uniform
+    // second plane of a salient tile: held the same way
+    uint4 held2_code = make_uint4(0, 0, 0, 0);
+    uint32_t held2_meta = 0;
+    size_t held2_ob = 0;
+    bool held2_lane = false;   // this lane has a second-plane block to write
+    bool held2_any = false;    // wave-uniform
     const bool meta_aligned = (reinterpret_cast<uintptr_t>(p.meta) & 15u) == 0;
 
+    auto store_plane2 = [&]() {
+        if (held2_lane) {
+            *reinterpret_cast<uint4*>(p.codes2 + held2_ob * 16) = held2_code;
+            if (kBlock == 16) {
+                p.meta2[held2_ob * 2] = (uint16_t)held2_meta;
+                p.meta2[held2_ob * 2 + 1] = (uint16_t)(held2_meta >> 16);
+            } else {
+                p.meta2[held2_ob] = (uint16_t)held2_meta;
+            }
+        }
+    };
     while (t < p.n_tiles) {
         const uint32_t gb = t * 64u + lane;
         uint32_t w[16];
@@ -682,12 +699,16 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
         w[4] = cur.q1.x; w[5] = cur.q1.y; w[6] = cur.q1.z; w[7] = cur.q1.w;
         w[8] = cur.q2.x; w[9] = cur.q2.y; w[10] = cur.q2.z; w[11] = cur.q2.w;
         w[12] = cur.q3.x; w[13] = cur.q3.y; w[14] = cur.q3.z; w[15] = cur.q3.w;
-        const uint32_t excl_a =
-            kLdsSeda + 32u * ((cur.grp >= 0 && (uint32_t)cur.grp < p.n_groups) ? (uint32_t)cur.grp : p.n_groups);
-        // the previous tile's stores must not be scheduled above the arrival of this tile's input
-        asm volatile("" : "+v"(held_meta) : "v"(w[0]), "v"(w[15]));
+        // The previous tile's stores must not be scheduled above the arrival of this tile's input, and the
+        // row's SeDA group (the last load of the tile) is consumed here too: left to the compiler, the wait
+        // for it lands behind the next tile's loads and waits for those as well.
+        int32_t grp = kSeda ? cur.grp : -1;
+        asm volatile("" : "+v"(held_meta), "+v"(grp) : "v"(w[0]), "v"(w[15]));
+        const uint32_t excl_a = kLdsSeda + 32u * ((grp >= 0 && (uint32_t)grp < p.n_groups) ? (uint32_t)grp : p.n_groups);
         if (have_held) store_tile<kBlock>(p, held_gb, lane, held_code, held_meta, meta_aligned);
         have_held = true;
+        if (kDecomp && held2_any) store_plane2();
+        held2_any = false;
         // the next tile's loads go out before this tile's arithmetic
         cur = load_block<kFlat, kSeda>(p, (t_next < p.n_tiles) ? t_next * 64u + lane : 0xFFFFFFFFu);
         uint32_t claim = 0;
@@ -718,16 +739,11 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
                 bool special2;
                 compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, sal, excl_a, code2, meta2, code, meta,
                                                                 special2);
-                if (sal) {
-                    const size_t ob = (size_t)lo * p.nb + (gb - row * p.nb);
-                    *reinterpret_cast<uint4*>(p.codes2 + ob * 16) = make_uint4(code2[0], code2[1], code2[2], code2[3]);
-                    if (kBlock == 16) {
-                        p.meta2[ob * 2] = (uint16_t)meta2;
-                        p.meta2[ob * 2 + 1] = (uint16_t)(meta2 >> 16);
-                    } else {
-                        p.meta2[ob] = (uint16_t)meta2;
-                    }
-                }
+                held2_any = true;
+                held2_lane = sal;
+                held2_ob = (size_t)lo * p.nb + (gb - row * p.nb);
+                held2_code = make_uint4(code2[0], code2[1], code2[2], code2[3]);
+                held2_meta = meta2;
             }
         }
         held_code = make_uint4(code[0], code[1], code[2], code[3]);
@@ -737,6 +753,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
         t_next = t_after;
     }
     if (have_held) store_tile<kBlock>(p, held_gb, lane, held_code, held_meta, meta_aligned);
+    if (kDecomp && held2_any) store_plane2();
 }
 
 }  // namespace fb4
