@@ -254,15 +254,21 @@ __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], c
 #pragma unroll
     for (int c = 0; c < R / 8; ++c) {
         uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        // all row reads are issued before the first sum: with two wavefronts per SIMD their latency shows
+        uint4 r0[8], r1[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t gb = gbin[8 * c + j];
             if (kTwoStage) binmax = max(binmax, gb);
             const uint8_t* row = lds + K.row_base + (gb << 8);
-            const uint4 r0 = *reinterpret_cast<const uint4*>(row);
-            const uint4 r1 = *reinterpret_cast<const uint4*>(row + 128);
-            acc[0] += r0.x; acc[1] += r0.y; acc[2] += r0.z; acc[3] += r0.w;
-            acc[4] += r1.x; acc[5] += r1.y; acc[6] += r1.z; acc[7] += r1.w;
+            r0[j] = *reinterpret_cast<const uint4*>(row);
+            r1[j] = *reinterpret_cast<const uint4*>(row + 128);
+        }
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            acc[0] += r0[j].x; acc[1] += r0[j].y; acc[2] += r0[j].z; acc[3] += r0[j].w;
+            acc[4] += r1[j].x; acc[5] += r1[j].y; acc[6] += r1[j].z; acc[7] += r1[j].w;
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
