@@ -157,12 +157,10 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
         f.meta2 = fused->meta2;
     }
     long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
-    // Persistent workgroups.  One per compute unit (8 wavefronts) is fastest: measured 24.4 us against 26.0 us
-    // with two on the 16384x3072 workload (SeDA: 25.7 against 27.2), and 4, 12 or 16 wavefronts are slower
-    // too.  Only the variant that also forms the second plane, whose salient tiles cost twice the arithmetic,
-    // is not slower with a second resident workgroup, when its tables leave room for one.
-    const bool fits_twice = lds_fast_bytes(token_group != nullptr, fused != nullptr) <= 80 * 1024;
-    const long long cap = (long long)luts->n_cu * ((fused != nullptr && fits_twice) ? 2 : 1);
+    // Persistent workgroups, one per compute unit (8 wavefronts): measured 24.4 us against 26.0 us with two on
+    // the 16384x3072 workload (SeDA: 25.7 against 27.2; 4, 12 or 16 wavefronts are slower too), and the kernels
+    // are free to use up to 256 vector registers per lane.
+    const long long cap = (long long)luts->n_cu;
     if (groups > cap) groups = cap;
     const unsigned ng = (unsigned)groups;
     const bool flat = p.row_stride == cols;
@@ -212,7 +210,8 @@ bool tiling(int64_t out_rows, int64_t cols, int block, int* nb, int* tpr, int* n
 {
     int64_t b = cols / block;
     int64_t t = (cols + kTileElems - 1) / kTileElems;
-    if (b > 0x7FFFFFFF || t * out_rows > 0x7FFFFFF0LL) return false;
+    // the kernels step a 32-bit tile index by the grid size: leave room for that last step
+    if (b > 0x7FFFFFFF || t * out_rows > 0x7FF00000LL) return false;
     *nb = (int)b;
     *tpr = (int)t;
     *n_tiles = (int)(t * out_rows);

@@ -107,11 +107,14 @@ __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(DeqFastPar
     const uint32_t n_words = p.n_blocks * 4u;
     const uint32_t stride = gridDim.x * kDeqThreads;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    for (uint32_t i0 = blockIdx.x * kDeqThreads + threadIdx.x; i0 < n_words; i0 += stride * U) {
+    // 64-bit loop counter: i0 + stride * U may pass 2^32 for the largest tensors
+    for (unsigned long long i64 = blockIdx.x * kDeqThreads + threadIdx.x; i64 < n_words;
+         i64 += (unsigned long long)stride * U) {
+        const uint32_t i0 = (uint32_t)i64;
         uint32_t cw[U], mw[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t i = i0 + u * stride;
+            const unsigned long long i = i64 + (unsigned long long)u * stride;
             cw[u] = 0;
             mw[u] = 0;
             if (i < n_words) {
@@ -121,8 +124,8 @@ __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(DeqFastPar
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            if (i64 + (unsigned long long)u * stride >= n_words) break;
             const uint32_t i = i0 + u * stride;
-            if (i >= n_words) break;
             const uint32_t m = mw[u];
             const uint32_t did = m & 0xFFu;
             // exponent offset for both halves; a DID outside the table decodes as zeros

@@ -250,7 +250,22 @@ __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], c
 {
     static_assert(R % 8 == 0, "rows are summed eight at a time");
     uint32_t ev[8], od[8];   // 16-bit sums of dialects (4i, 4i+2) and (4i+1, 4i+3); R == 8 keeps bytes in ev
-    uint32_t binmax = 0;
+    // ---- candidate restrictions (Sec. 3.4 SeDA, Sec. 3.2 two-stage) as rows of bytes, 0xFF = excluded.  Their
+    // reads go out together with the first batch of Qerror rows.
+    uint4 xa0 = make_uint4(0, 0, 0, 0), xa1 = xa0, xr0 = xa0, xr1 = xa0;
+    if (kSeda) {
+        xa0 = *reinterpret_cast<const uint4*>(lds + excl_a);
+        xa1 = *reinterpret_cast<const uint4*>(lds + excl_a + 16);
+    }
+    if (kTwoStage) {
+        // first stage: keep the dialects whose top magnitude is the integer part of the block maximum
+        uint32_t binmax = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) binmax = max(binmax, gbin[r]);
+        const uint32_t roff = kLdsRange + (min(max(binmax >> 1, 8u), 15u) - 8u) * 32u;
+        xr0 = *reinterpret_cast<const uint4*>(lds + roff);
+        xr1 = *reinterpret_cast<const uint4*>(lds + roff + 16);
+    }
 #pragma unroll
     for (int c = 0; c < R / 8; ++c) {
         uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -258,9 +273,7 @@ __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], c
         uint4 r0[8], r1[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const uint32_t gb = gbin[8 * c + j];
-            if (kTwoStage) binmax = max(binmax, gb);
-            const uint8_t* row = lds + K.row_base + (gb << 8);
+            const uint8_t* row = lds + K.row_base + (gbin[8 * c + j] << 8);
             r0[j] = *reinterpret_cast<const uint4*>(row);
             r1[j] = *reinterpret_cast<const uint4*>(row + 128);
         }
@@ -282,27 +295,14 @@ __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], c
             }
         }
     }
-    // ---- candidate restrictions (Sec. 3.4 SeDA, Sec. 3.2 two-stage): bytes, 0xFF = excluded
-    uint32_t ea[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (kSeda || kTwoStage) {
-        if (kSeda) {
-            const uint4 a0 = *reinterpret_cast<const uint4*>(lds + excl_a);
-            const uint4 a1 = *reinterpret_cast<const uint4*>(lds + excl_a + 16);
-            ea[0] = a0.x; ea[1] = a0.y; ea[2] = a0.z; ea[3] = a0.w;
-            ea[4] = a1.x; ea[5] = a1.y; ea[6] = a1.z; ea[7] = a1.w;
-        }
-        if (kTwoStage) {
-            // first stage: keep the dialects whose top magnitude is the integer part of the block maximum
-            const uint32_t roff = kLdsRange + (min(max(binmax >> 1, 8u), 15u) - 8u) * 32u;
-            const uint4 r0 = *reinterpret_cast<const uint4*>(lds + roff);
-            const uint4 r1 = *reinterpret_cast<const uint4*>(lds + roff + 16);
-            const uint32_t eb2[8] = {ea[0] | r0.x, ea[1] | r0.y, ea[2] | r0.z, ea[3] | r0.w,
-                                     ea[4] | r1.x, ea[5] | r1.y, ea[6] | r1.z, ea[7] | r1.w};
-            // ... unless that leaves nothing (possible only together with a SeDA list)
-            const bool none = kSeda && ((eb2[0] & eb2[1] & eb2[2] & eb2[3] & eb2[4] & eb2[5] & eb2[6] & eb2[7]) == 0xFFFFFFFFu);
+    uint32_t ea[8] = {xa0.x, xa0.y, xa0.z, xa0.w, xa1.x, xa1.y, xa1.z, xa1.w};
+    if (kTwoStage) {
+        const uint32_t eb2[8] = {ea[0] | xr0.x, ea[1] | xr0.y, ea[2] | xr0.z, ea[3] | xr0.w,
+                                 ea[4] | xr1.x, ea[5] | xr1.y, ea[6] | xr1.z, ea[7] | xr1.w};
+        // ... unless that leaves nothing (possible only together with a SeDA list)
+        const bool none = kSeda && ((eb2[0] & eb2[1] & eb2[2] & eb2[3] & eb2[4] & eb2[5] & eb2[6] & eb2[7]) == 0xFFFFFFFFu);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) ea[i] = none ? ea[i] : eb2[i];
-        }
+        for (int i = 0; i < 8; ++i) ea[i] = none ? ea[i] : eb2[i];
     }
     // ---- argmin with lowest DID on ties: 16-bit keys (sum << 5 | DID), 32 of them in 16 registers.  An
     // excluded dialect gets a key no real sum reaches.

@@ -78,7 +78,9 @@ __global__ __launch_bounds__(kRepackThreads) void repack_mxfp8_kernel(RepackPara
     const uint32_t n_words = p.n_chunks * 4u;
     const uint32_t stride = gridDim.x * kRepackThreads;
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    for (uint32_t i = blockIdx.x * kRepackThreads + threadIdx.x; i < n_words; i += stride) {
+    // 64-bit loop counter: i + stride may pass 2^32 for the largest tensors
+    for (unsigned long long i64 = blockIdx.x * kRepackThreads + threadIdx.x; i64 < n_words; i64 += stride) {
+        const uint32_t i = (uint32_t)i64;
         const uint32_t cw = reinterpret_cast<const uint32_t*>(p.codes)[i];
         const uint32_t chunk = i >> 2;
         uint32_t m, k = 0, sbyte;
