@@ -227,6 +227,11 @@ def main():
             abytes + n_sal * COLS // 2 + n_sal * (COLS // BLOCK) * 2 + n_sal * 4, n_el)
         outs = [torch.empty((ROWS, COLS), dtype=torch.bfloat16, device="cuda") for _ in range(N_SETS)]
 
+        def deq_plain_step(i):
+            k = i % N_SETS
+            F.fb4_dequantize(luts, codes[k], metas[k], out=outs[k])
+        add("dequantize_bf16", deq_plain_step, abytes, n_el)
+
         def deq_step(i):
             k = i % N_SETS
             F.fb4_dequantize(luts, codes[k], metas[k], codes2=c2, meta2=m2, salient_rows=sal_d, out=outs[k])
