@@ -531,11 +531,9 @@ static uint8_t e4m3_of(double v)
     if (e < -6) e = -6;  /* subnormals share the spacing of the smallest normal binade */
     double n = nearbyint(ldexp(v, 3 - e)); /* v in units of the spacing 2^(e-3); default rounding = ties to even */
     if (n < 8.0) return (uint8_t)n;        /* subnormal (only reachable with e == -6) */
-    if (n == 16.0) {
-        e += 1;
-        n = 8.0;
-    }
-    return (uint8_t)(((e + 7) << 3) | ((int)n - 8));
+    /* n in 8..16: exponent field and three mantissa bits; n == 16 (rounded up to the next power of two)
+     * carries into the exponent field by itself */
+    return (uint8_t)(((e + 7) << 3) + ((int)n - 8));
 }
 
 /* Sec. 4.5 / App. E.2: the integer magnitudes 0..15 are exact in FP8 E4M3 and
