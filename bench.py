@@ -267,9 +267,15 @@ def main():
         cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb, selector=O.SEL_LUT, num_groups=8, nthreads=nthr)
         dt = time.perf_counter() - t0
         same = bool(np.array_equal(cr, codes[0].cpu().numpy()) if args.no_extras else True)
+        # one thread, on the first 1024 rows, for scale
+        t0 = time.perf_counter()
+        O.quantize(DEFAULT_FORMATBOOK, xb[:1024], selector=O.SEL_LUT, num_groups=8, nthreads=1)
+        dt1 = time.perf_counter() - t0
         result["cpu_baseline"] = {
             "value": n_el / dt / 1e9, "unit": "G elements/s", "cores": nthr, "kind": "oracle",
             "sample": "the whole 16384x3072 cfg2 tensor, selector lut g=8, %.2f s wall on %d threads" % (dt, nthr),
+            "one_thread_value": 1024 * COLS / dt1 / 1e9,
+            "one_thread_sample": "its first 1024 rows, %.2f s" % dt1,
         }
         if args.no_extras:
             result["cpu_baseline"]["matches_gpu_codes"] = same
