@@ -29,6 +29,7 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = 129056541
 ROWS, COLS, BLOCK = 16384, 3072, 32
 N_SETS = 6
+SETTLE_S = 0.05   # untimed load before a timed graph replay
 
 
 def algorithmic_bytes(rows, cols, block=32):
@@ -37,11 +38,12 @@ def algorithmic_bytes(rows, cols, block=32):
 
 
 def time_graph(fn_steps, steps, warmup):
-    """Run `warmup` eager steps, capture `steps` steps into one HIP graph, replay it untimed (once, and
-    again until `warmup` steps have been replayed: clocks need tens of milliseconds of load to settle), then
-    once timed.  Returns (wall seconds, event seconds) for the timed replay."""
+    """Run a few eager steps (at most 100), capture `steps` steps into one HIP graph, replay it untimed (until `warmup`
+    steps have been replayed and the card has been under load for SETTLE_S seconds: the capture leaves it idle
+    for a moment, and from idle the clocks take 20 to 25 ms of load to come back up), then once timed.
+    Returns (wall seconds, event seconds) for the timed replay."""
     import torch
-    for i in range(warmup):
+    for i in range(min(warmup, 100)):
         fn_steps(i)
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
@@ -51,9 +53,12 @@ def time_graph(fn_steps, steps, warmup):
             for i in range(steps):
                 fn_steps(i)
     torch.cuda.synchronize()
-    for _ in range(max(1, -(-warmup // steps))):
+    replays, t_load = 0, time.perf_counter()
+    while replays * steps < warmup or time.perf_counter() - t_load < SETTLE_S:
         g.replay()
-    torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        replays += 2
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
