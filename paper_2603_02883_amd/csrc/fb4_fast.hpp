@@ -457,6 +457,20 @@ __device__ __forceinline__ Block64 load_block(const FastParams& p, uint32_t gb)
     return b;
 }
 
+// The same without a branch, for the prologue: a lane past the end reads the last block (its result is never
+// stored), so that the loads sit in straight-line code and the waits that follow can be counted exactly.
+template <bool kFlat, bool kSeda>
+__device__ __forceinline__ Block64 load_block_clamped(const FastParams& p, uint32_t gb)
+{
+    Block64 b;
+    const uint32_t gbc = min(gb, p.n_blocks - 1u);
+    const uint4* px = reinterpret_cast<const uint4*>(p.x + block_offset<kFlat>(p, gbc));
+    b.q0 = px[0]; b.q1 = px[1]; b.q2 = px[2]; b.q3 = px[3];
+    b.grp = -1;
+    if (kSeda) b.grp = p.token_group[(uint32_t)(((unsigned long long)gbc * p.div_mul) >> p.div_shift)];
+    return b;
+}
+
 // Writes one tile's results: 16 bytes of codes per lane and the metadata words.  When the whole tile is in
 // range and the metadata array is 16-byte aligned, eight neighbouring lanes gather their 16-bit metadata
 // into one 16-byte store (sub-dword stores are slow to coalesce); block size 16 has one dword per lane.
@@ -546,40 +560,67 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
     uint32_t t = blockIdx.x + wave * W;                      // first tile: static
     uint32_t t_next = blockIdx.x + (kFastWaves + wave) * W;   // second tile: static
     if (threadIdx.x == 0) wg_next = 2 * kFastWaves;
-    // the first tile is requested before anything else: it streams in while the tables are built
-    cur = load_block<kFlat, kSeda>(p, t * 64u + lane);
+    // Loads are answered in the order they were issued.  The (small, mostly cached) table and list loads
+    // therefore go out first and the first tile's right behind them: the tables are then built while the
+    // tile is still on its way, instead of after it.
+    constexpr int kRowIt = (512 + kFastThreads - 1) / kFastThreads;
+    constexpr int kNibIt = (256 + kFastThreads - 1) / kFastThreads;
+    constexpr int kSalEarly = 8;
+    uint4 rowv[kRowIt];
+    uint32_t nibv[kNibIt], rngv = 0, decv = 0;
+    uint4 magq = make_uint4(0, 0, 0, 0);
+    uint2 sub0 = make_uint2(0, 0);
+    int32_t sal_reg[kSalEarly];
+    const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kFastThreads;
     {
         // Qerror rows as eight bank-disjoint copies: piece i = (bin, half, copy) is 16 bytes of row `bin`
-        for (int i = threadIdx.x; i < 512; i += kFastThreads) {
-            const int bin = i >> 4, half = (i >> 3) & 1;
-            reinterpret_cast<uint4*>(lds + kLdsRows)[i] =
-                *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
-        }
-        for (int i = threadIdx.x; i < 256; i += kFastThreads)
-            reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[i];
-        if (kTwoStage && threadIdx.x < 64)
-            reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] =
-                reinterpret_cast<const uint32_t*>(p.blob + kOffRangeExcl)[threadIdx.x];
-        // fused decomposition: a short salient list is requested now, together with the tables, and used
-        // after the barrier; a long one is read in a loop later
-        constexpr int kSalEarly = 8;
-        int32_t sal_reg[kSalEarly];
-        const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kFastThreads;
-        if (kDecomp && sal_early) {
+        // (indices are clamped, not predicated: a thread past the end loads a piece it does not write)
 #pragma unroll
-            for (int k = 0; k < kSalEarly; ++k) {
-                const uint32_t i = threadIdx.x + k * kFastThreads;
-                sal_reg[k] = i < p.n_sal ? p.salient[i] : 0x7FFFFFFF;   // beyond any row: ignored
+        for (int k = 0; k < kRowIt; ++k) {
+            const int i = min((int)threadIdx.x + k * kFastThreads, 511);
+            const int bin = i >> 4, half = (i >> 3) & 1;
+            rowv[k] = *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
+        }
+#pragma unroll
+        for (int k = 0; k < kNibIt; ++k)
+            nibv[k] = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[min((int)threadIdx.x + k * kFastThreads, 255)];
+        if (kTwoStage) rngv = reinterpret_cast<const uint32_t*>(p.blob + kOffRangeExcl)[threadIdx.x & 63u];
+        if (kDecomp) {
+            decv = reinterpret_cast<const uint32_t*>(p.blob + kOffDecode)[threadIdx.x & 127u];
+            magq = *reinterpret_cast<const uint4*>(p.blob + kOffDecode + (threadIdx.x & 31u) * 16);
+            // a short salient list is requested now and used after the pair table; a long one is read in a
+            // loop later
+            if (sal_early) {
+#pragma unroll
+                for (int k = 0; k < kSalEarly; ++k) {
+                    const uint32_t i = threadIdx.x + k * kFastThreads;
+                    sal_reg[k] = i < p.n_sal ? p.salient[i] : 0x7FFFFFFF;   // beyond any row: ignored
+                }
             }
         }
+        if (kSeda && p.n_groups > 0)
+            sub0 = *reinterpret_cast<const uint2*>(p.sub + (size_t)min(threadIdx.x, p.n_groups - 1u) * 8);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    cur = load_block_clamped<kFlat, kSeda>(p, t * 64u + lane);
+    __builtin_amdgcn_sched_barrier(0);
+    {
+#pragma unroll
+        for (int k = 0; k < kRowIt; ++k) {
+            const int i = threadIdx.x + k * kFastThreads;
+            if (i < 512) reinterpret_cast<uint4*>(lds + kLdsRows)[i] = rowv[k];
+        }
+#pragma unroll
+        for (int k = 0; k < kNibIt; ++k) {
+            const int i = threadIdx.x + k * kFastThreads;
+            if (i < 256) reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = nibv[k];
+        }
+        if (kTwoStage && threadIdx.x < 64) reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] = rngv;
         if (kDecomp) {
-            if (threadIdx.x < 128)
-                reinterpret_cast<uint32_t*>(lds + kLdsDecode)[threadIdx.x] =
-                    reinterpret_cast<const uint32_t*>(p.blob + kOffDecode)[threadIdx.x];
+            if (threadIdx.x < 128) reinterpret_cast<uint32_t*>(lds + kLdsDecode)[threadIdx.x] = decv;
             if (threadIdx.x < 32) {
                 // the dialect's eight magnitudes (integers 0..15 stored as bf16 patterns) as nibbles
-                const uint4 dq = *reinterpret_cast<const uint4*>(p.blob + kOffDecode + threadIdx.x * 16);
-                const uint32_t dv[4] = {dq.x, dq.y, dq.z, dq.w};
+                const uint32_t dv[4] = {magq.x, magq.y, magq.z, magq.w};
                 uint32_t mw = 0;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -598,7 +639,8 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
             for (uint32_t g = threadIdx.x; g <= p.n_groups; g += kFastThreads) {
                 uint32_t keep = 0;
                 if (g < p.n_groups) {
-                    const uint2 s8 = *reinterpret_cast<const uint2*>(p.sub + (size_t)g * 8);
+                    // the first round's entries were requested with the tables
+                    const uint2 s8 = g < (uint32_t)kFastThreads ? sub0 : *reinterpret_cast<const uint2*>(p.sub + (size_t)g * 8);
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
                         const uint32_t d = ((k < 4 ? s8.x : s8.y) >> (8 * (k & 3))) & 0xFFu;
