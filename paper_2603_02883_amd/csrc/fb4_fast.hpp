@@ -443,24 +443,11 @@ struct Block64 {   // one block: 32 bf16 = four 16-byte loads, plus its row's Se
     int32_t grp;
 };
 
+// Requests block gb.  There is no branch: a lane past the end reads the last block (its result is never
+// stored, and data that a valid lane holds too cannot send the tile down another route), so that the loads
+// sit in straight-line code and the waits that follow can be counted exactly.
 template <bool kFlat, bool kSeda>
 __device__ __forceinline__ Block64 load_block(const FastParams& p, uint32_t gb)
-{
-    Block64 b;
-    b.q0 = b.q1 = b.q2 = b.q3 = make_uint4(0, 0, 0, 0);
-    b.grp = -1;
-    if (gb < p.n_blocks) {
-        const uint4* px = reinterpret_cast<const uint4*>(p.x + block_offset<kFlat>(p, gb));
-        b.q0 = px[0]; b.q1 = px[1]; b.q2 = px[2]; b.q3 = px[3];
-        if (kSeda) b.grp = p.token_group[(uint32_t)(((unsigned long long)gb * p.div_mul) >> p.div_shift)];
-    }
-    return b;
-}
-
-// The same without a branch, for the prologue: a lane past the end reads the last block (its result is never
-// stored), so that the loads sit in straight-line code and the waits that follow can be counted exactly.
-template <bool kFlat, bool kSeda>
-__device__ __forceinline__ Block64 load_block_clamped(const FastParams& p, uint32_t gb)
 {
     Block64 b;
     const uint32_t gbc = min(gb, p.n_blocks - 1u);
@@ -602,7 +589,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
             sub0 = *reinterpret_cast<const uint2*>(p.sub + (size_t)min(threadIdx.x, p.n_groups - 1u) * 8);
     }
     __builtin_amdgcn_sched_barrier(0);
-    cur = load_block_clamped<kFlat, kSeda>(p, t * 64u + lane);
+    cur = load_block<kFlat, kSeda>(p, t * 64u + lane);
     __builtin_amdgcn_sched_barrier(0);
     {
 #pragma unroll
@@ -758,7 +745,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
         if (kDecomp && held2_any) store_plane2();
         held2_any = false;
         // the next tile's loads go out before this tile's arithmetic
-        cur = load_block<kFlat, kSeda>(p, (t_next < p.n_tiles) ? t_next * 64u + lane : 0xFFFFFFFFu);
+        cur = load_block<kFlat, kSeda>(p, t_next * 64u + lane);
         uint32_t claim = 0;
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
         const uint32_t t_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
