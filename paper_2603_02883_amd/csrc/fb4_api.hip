@@ -99,13 +99,16 @@ int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& 
 template <int kBlock, int G, bool kFlat, bool kDecomp>
 void launch_fast_variant(bool ts, bool seda, unsigned groups, hipStream_t s, const FastParams& f)
 {
+    // (the leading arguments repeat fields of f: see the kernel)
+#define FB4_FAST_ARGS f.blob, f.x, f.n_blocks, f.n_tiles, f.div_mul, f.div_shift, f.nb, groups, f.row_stride, f.codes, f.meta, f
     if (seda) {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, f);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, f);
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, FB4_FAST_ARGS);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, FB4_FAST_ARGS);
     } else {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, f);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, f);
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, FB4_FAST_ARGS);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, FB4_FAST_ARGS);
     }
+#undef FB4_FAST_ARGS
 }
 
 // Second-plane outputs of the fused quantize + decompose call.

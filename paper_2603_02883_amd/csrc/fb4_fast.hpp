@@ -529,9 +529,17 @@ __device__ __forceinline__ void residual32(const uint32_t (&w)[16], const uint32
     }
 }
 
+// The leading scalar arguments repeat the fields of `p` that the first loads and the loop bound depend on:
+// the library is compiled so that up to 16 leading argument registers are filled by the dispatcher when the
+// wavefront starts (the rest of the arguments come by a load, half a microsecond later), and the table and
+// tile requests can then go out at once.
 template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda, bool kDecomp = false>
-__global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p)
+__global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
+    const uint8_t* blob, const uint16_t* x, uint32_t n_blocks, uint32_t n_tiles, uint32_t div_mul, uint32_t div_shift,
+    uint32_t nb, uint32_t n_workgroups, long long row_stride, uint8_t* codes, uint16_t* meta, FastParams p)
 {
+    p.blob = blob; p.x = x; p.n_blocks = n_blocks; p.n_tiles = n_tiles; p.div_mul = div_mul; p.div_shift = div_shift;
+    p.nb = nb; p.row_stride = row_stride; p.codes = codes; p.meta = meta;
     constexpr int kLdsSeda = lds_seda_offset(kDecomp);
     __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kDecomp)];
     __shared__ uint32_t sal_before;      // fused decomposition: list entries below row 0
@@ -542,7 +550,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(FastParams p
     // take them from a shared counter as they become free, so a wave that runs ahead of its neighbours
     // keeps working instead of idling at the end.
     __shared__ uint32_t wg_next;
-    const uint32_t W = gridDim.x;
+    const uint32_t W = n_workgroups;   // = gridDim.x, which would have to be loaded
     Block64 cur;
     uint32_t t = blockIdx.x + wave * W;                      // first tile: static
     uint32_t t_next = blockIdx.x + (kFastWaves + wave) * W;   // second tile: static
