@@ -469,6 +469,8 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
         if (groups > cap) groups = cap;
         const bool flat = out_row_stride == cols;
         const dim3 dg((unsigned)groups), db(kDeqThreads);
+        // (the leading arguments repeat fields of f: see the kernel)
+#define FB4_DEQ_ARGS f.blob, f.codes, f.meta, f.n_blocks, f.meta_shift, dg.x, f
         if (n_sal > 0 && rows <= (int64_t)kMaxFusedRows) {
             // salient rows get both planes in the same pass
             f.codes2 = codes2;
@@ -477,21 +479,22 @@ int fb4_dequantize(const fb4_luts* luts, const uint8_t* codes1, const uint16_t* 
             f.n_sal = (uint32_t)n_sal;
             f.rows = (uint32_t)rows;
             if (out_dtype == FB4_DTYPE_F32) {
-                if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, true, true>), dg, db, 0, s, f);
-                else hipLaunchKernelGGL((dequantize_fast_kernel<false, true, true>), dg, db, 0, s, f);
+                if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, true, true>), dg, db, 0, s, FB4_DEQ_ARGS);
+                else hipLaunchKernelGGL((dequantize_fast_kernel<false, true, true>), dg, db, 0, s, FB4_DEQ_ARGS);
             } else {
-                if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, false, true>), dg, db, 0, s, f);
-                else hipLaunchKernelGGL((dequantize_fast_kernel<false, false, true>), dg, db, 0, s, f);
+                if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, false, true>), dg, db, 0, s, FB4_DEQ_ARGS);
+                else hipLaunchKernelGGL((dequantize_fast_kernel<false, false, true>), dg, db, 0, s, FB4_DEQ_ARGS);
             }
             return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
         }
         if (out_dtype == FB4_DTYPE_F32) {
-            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, true>), dg, db, 0, s, f);
-            else hipLaunchKernelGGL((dequantize_fast_kernel<false, true>), dg, db, 0, s, f);
+            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, true>), dg, db, 0, s, FB4_DEQ_ARGS);
+            else hipLaunchKernelGGL((dequantize_fast_kernel<false, true>), dg, db, 0, s, FB4_DEQ_ARGS);
         } else {
-            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, false>), dg, db, 0, s, f);
-            else hipLaunchKernelGGL((dequantize_fast_kernel<false, false>), dg, db, 0, s, f);
+            if (flat) hipLaunchKernelGGL((dequantize_fast_kernel<true, false>), dg, db, 0, s, FB4_DEQ_ARGS);
+            else hipLaunchKernelGGL((dequantize_fast_kernel<false, false>), dg, db, 0, s, FB4_DEQ_ARGS);
         }
+#undef FB4_DEQ_ARGS
     } else if (out_dtype == FB4_DTYPE_F32) {
         hipLaunchKernelGGL((dequantize_kernel<false, true>), dim3(grid), dim3(kThreads), 0, s, p);
     } else {
@@ -549,11 +552,11 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool flat = elem_row_stride == cols;
     if (block == 16) {
-        if (flat) hipLaunchKernelGGL((repack_mxfp8_kernel<true, true>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
-        else hipLaunchKernelGGL((repack_mxfp8_kernel<false, true>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
+        if (flat) hipLaunchKernelGGL((repack_mxfp8_kernel<true, true>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f.blob, f.codes, f.meta, f.n_chunks, (uint32_t)groups, f);
+        else hipLaunchKernelGGL((repack_mxfp8_kernel<false, true>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f.blob, f.codes, f.meta, f.n_chunks, (uint32_t)groups, f);
     } else {
-        if (flat) hipLaunchKernelGGL((repack_mxfp8_kernel<true, false>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
-        else hipLaunchKernelGGL((repack_mxfp8_kernel<false, false>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f);
+        if (flat) hipLaunchKernelGGL((repack_mxfp8_kernel<true, false>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f.blob, f.codes, f.meta, f.n_chunks, (uint32_t)groups, f);
+        else hipLaunchKernelGGL((repack_mxfp8_kernel<false, false>), dim3((unsigned)groups), dim3(kRepackThreads), 0, s, f.blob, f.codes, f.meta, f.n_chunks, (uint32_t)groups, f);
     }
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }

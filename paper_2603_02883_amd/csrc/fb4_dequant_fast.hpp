@@ -49,9 +49,14 @@ __device__ __forceinline__ uint32_t decode_pair(const uint32_t* pair, uint32_t b
 
 // kSum: rows listed in p.salient are written as round(fp32(plane 1) + fp32(plane 2)); a bitmap of those rows
 // with a running count per bitmap word (LDS) gives a row's position in the compact second plane.
+// The leading scalar arguments repeat the fields of `p` that the first loads depend on; they arrive in
+// registers when the wavefront starts (kernel-argument preload), the rest by a load.
 template <bool kFlat, bool kF32, bool kSum = false>
-__global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(DeqFastParams p)
+__global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(
+    const uint8_t* blob, const uint8_t* codes, const uint16_t* meta, uint32_t n_blocks, uint32_t meta_shift,
+    uint32_t n_workgroups, DeqFastParams p)
 {
+    p.blob = blob; p.codes = codes; p.meta = meta; p.n_blocks = n_blocks; p.meta_shift = meta_shift;
     __shared__ __align__(16) uint32_t pair[32 * 256];   // [DID][code byte] -> two bf16 patterns
     __shared__ __align__(16) uint32_t sal_bits[kSum ? kMaxFusedRows / 32 : 4];
     __shared__ uint16_t sal_rank[kSum ? kMaxFusedRows / 32 : 4];
@@ -86,42 +91,48 @@ __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(DeqFastPar
         sal_rank[threadIdx.x * 4 + 2] = (uint16_t)(base + c1);
         sal_rank[threadIdx.x * 4 + 3] = (uint16_t)(base + c2);
     }
-    {
-        // thread (DID, high nibble) fills 16 entries
-        const uint32_t did = threadIdx.x >> 4, hn = threadIdx.x & 15;
-        const uint4 dq = *reinterpret_cast<const uint4*>(p.blob + kOffDecode + did * 16);   // 8 bf16 magnitudes
-        const uint32_t dv[8] = {dq.x & 0xFFFFu, dq.x >> 16, dq.y & 0xFFFFu, dq.y >> 16,
-                                dq.z & 0xFFFFu, dq.z >> 16, dq.w & 0xFFFFu, dq.w >> 16};
-        uint32_t hi = 0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) hi = ((hn & 7u) == (uint32_t)k) ? dv[k] : hi;
-        hi = (hi | ((hn & 8u) << 12)) << 16;
-        uint32_t* dst = pair + did * 256 + hn * 16;
-#pragma unroll
-        for (int ln = 0; ln < 16; ++ln) dst[ln] = hi | dv[ln & 7] | ((uint32_t)(ln & 8) << 12);
-        __syncthreads();
-    }
     // Work item = one code word (4 bytes = 8 elements) -> 16 bytes of bf16: consecutive lanes take consecutive
     // words, so every load and store instruction of a wavefront covers one contiguous span.
     constexpr int U = 4;
     const uint32_t n_words = p.n_blocks * 4u;
-    const uint32_t stride = gridDim.x * kDeqThreads;
+    const uint32_t stride = n_workgroups * kDeqThreads;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    // 64-bit loop counter: i0 + stride * U may pass 2^32 for the largest tensors
-    for (unsigned long long i64 = blockIdx.x * kDeqThreads + threadIdx.x; i64 < n_words;
-         i64 += (unsigned long long)stride * U) {
-        const uint32_t i0 = (uint32_t)i64;
-        uint32_t cw[U], mw[U];
+    uint32_t cw[U], mw[U];
+    // (indices are clamped, not predicated: a lane past the end reads the last word and stores nothing)
+    auto request = [&](unsigned long long i64) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const unsigned long long i = i64 + (unsigned long long)u * stride;
-            cw[u] = 0;
-            mw[u] = 0;
-            if (i < n_words) {
-                cw[u] = reinterpret_cast<const uint32_t*>(p.codes)[i];
-                mw[u] = p.meta[i >> p.meta_shift];
-            }
+            const uint32_t ic = (uint32_t)(i < n_words ? i : n_words - 1u);
+            cw[u] = reinterpret_cast<const uint32_t*>(p.codes)[ic];
+            mw[u] = p.meta[ic >> p.meta_shift];
         }
+    };
+    const unsigned long long first = blockIdx.x * kDeqThreads + threadIdx.x;
+    // the table's source and the first round of codes are requested together; the table is built while the
+    // codes are on their way
+    const uint32_t did_t = threadIdx.x >> 4, hn_t = threadIdx.x & 15;
+    const uint4 dq = *reinterpret_cast<const uint4*>(p.blob + kOffDecode + did_t * 16);   // 8 bf16 magnitudes
+    __builtin_amdgcn_sched_barrier(0);
+    request(first);
+    __builtin_amdgcn_sched_barrier(0);
+    {
+        // thread (DID, high nibble) fills 16 entries
+        const uint32_t dv[8] = {dq.x & 0xFFFFu, dq.x >> 16, dq.y & 0xFFFFu, dq.y >> 16,
+                                dq.z & 0xFFFFu, dq.z >> 16, dq.w & 0xFFFFu, dq.w >> 16};
+        uint32_t hi = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) hi = ((hn_t & 7u) == (uint32_t)k) ? dv[k] : hi;
+        hi = (hi | ((hn_t & 8u) << 12)) << 16;
+        uint32_t* dst = pair + did_t * 256 + hn_t * 16;
+#pragma unroll
+        for (int ln = 0; ln < 16; ++ln) dst[ln] = hi | dv[ln & 7] | ((uint32_t)(ln & 8) << 12);
+        __syncthreads();
+    }
+    // 64-bit loop counter: i0 + stride * U may pass 2^32 for the largest tensors
+    for (unsigned long long i64 = first; i64 < n_words; i64 += (unsigned long long)stride * U) {
+        const uint32_t i0 = (uint32_t)i64;
+        if (i64 != first) request(i64);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (i64 + (unsigned long long)u * stride >= n_words) break;

@@ -52,14 +52,40 @@ __device__ __forceinline__ uint32_t e4m3_of_shifted(uint32_t m, uint32_t k)
     return q;
 }
 
+// The leading scalar arguments repeat the fields of `p` that the first loads depend on; they arrive in
+// registers when the wavefront starts (kernel-argument preload), the rest by a load.
 template <bool kFlat, bool kB16>
-__global__ __launch_bounds__(kRepackThreads) void repack_mxfp8_kernel(RepackParams p)
+__global__ __launch_bounds__(kRepackThreads) void repack_mxfp8_kernel(
+    const uint8_t* blob, const uint8_t* codes, const uint16_t* meta, uint32_t n_chunks, uint32_t n_workgroups,
+    RepackParams p)
 {
+    p.blob = blob; p.codes = codes; p.meta = meta; p.n_chunks = n_chunks;
     __shared__ __align__(16) uint16_t pair[32 * 256];   // [DID][code byte] -> E4M3 of element 2j | element 2j+1 << 8
     __shared__ uint8_t magT[32 * 8];                     // [DID][index] -> integer magnitude
     __shared__ uint8_t shT[16 * 16];                     // [k][magnitude] -> E4M3 byte of magnitude * 2^-k
+    const uint32_t n_words = p.n_chunks * 4u;
+    const uint32_t stride = n_workgroups * kRepackThreads;
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    uint32_t cw, mcur, mother = 0;
+    // (the index is clamped, not predicated: a lane past the end reads the last word and stores nothing)
+    auto request = [&](unsigned long long i64) {
+        const uint32_t ic = (uint32_t)(i64 < n_words ? i64 : n_words - 1u);
+        cw = reinterpret_cast<const uint32_t*>(p.codes)[ic];
+        if (kB16) {
+            mcur = p.meta[ic >> 1];
+            mother = p.meta[(ic >> 1) ^ 1u];
+        } else {
+            mcur = p.meta[ic >> 2];
+        }
+    };
+    const unsigned long long first = blockIdx.x * kRepackThreads + threadIdx.x;
+    // the tables' source and the first code word are requested together; the tables are built while the
+    // codes are on their way
+    const uint32_t bits = reinterpret_cast<const uint16_t*>(p.blob + kOffDecode)[threadIdx.x & 255u];
+    __builtin_amdgcn_sched_barrier(0);
+    request(first);
+    __builtin_amdgcn_sched_barrier(0);
     if (threadIdx.x < 256) {
-        const uint32_t bits = reinterpret_cast<const uint16_t*>(p.blob + kOffDecode)[threadIdx.x];
         magT[threadIdx.x] = (uint8_t)(int)__uint_as_float(bits << 16);
         shT[threadIdx.x] = (uint8_t)e4m3_of_shifted(threadIdx.x & 15u, threadIdx.x >> 4);
     }
@@ -75,24 +101,20 @@ __global__ __launch_bounds__(kRepackThreads) void repack_mxfp8_kernel(RepackPara
     }
     __syncthreads();
 
-    const uint32_t n_words = p.n_chunks * 4u;
-    const uint32_t stride = gridDim.x * kRepackThreads;
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     // 64-bit loop counter: i + stride may pass 2^32 for the largest tensors
-    for (unsigned long long i64 = blockIdx.x * kRepackThreads + threadIdx.x; i64 < n_words; i64 += stride) {
+    for (unsigned long long i64 = first; i64 < n_words; i64 += stride) {
         const uint32_t i = (uint32_t)i64;
-        const uint32_t cw = reinterpret_cast<const uint32_t*>(p.codes)[i];
+        if (i64 != first) request(i64);
         const uint32_t chunk = i >> 2;
         uint32_t m, k = 0, sbyte;
         if (kB16) {
-            const uint32_t blk = i >> 1;
-            m = p.meta[blk];
-            const uint32_t other = p.meta[blk ^ 1u];
+            m = mcur;
+            const uint32_t other = mother;
             const uint32_t emax = max(m >> 8, other >> 8);
             k = min(emax - (m >> 8), 15u);          // 14 and more: every magnitude rounds to zero
             sbyte = emax - 3u;
         } else {
-            m = p.meta[chunk];
+            m = mcur;
             sbyte = (m >> 8) - 3u;
         }
         const uint32_t did = m & 0xFFu;
