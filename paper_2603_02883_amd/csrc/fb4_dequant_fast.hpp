@@ -61,36 +61,6 @@ __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(
     __shared__ __align__(16) uint32_t sal_bits[kSum ? kMaxFusedRows / 32 : 4];
     __shared__ uint16_t sal_rank[kSum ? kMaxFusedRows / 32 : 4];
     __shared__ uint32_t sal_before, sal_wave[kDeqWaves];
-    if (kSum) {
-        static_assert(kDeqThreads * 4 * 32 == (int)kMaxFusedRows, "four bitmap words per thread");
-        for (uint32_t i = threadIdx.x; i < kMaxFusedRows / 32; i += kDeqThreads) sal_bits[i] = 0;
-        if (threadIdx.x == 0) sal_before = 0;
-        __syncthreads();
-        for (uint32_t i = threadIdx.x; i < p.n_sal; i += kDeqThreads) {
-            const int32_t r = p.salient[i];
-            if (r < 0) atomicAdd(&sal_before, 1u);
-            else if ((uint32_t)r < p.rows) atomicOr(&sal_bits[(uint32_t)r >> 5], 1u << (r & 31));
-        }
-        __syncthreads();
-        const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        const uint4 wv = reinterpret_cast<const uint4*>(sal_bits)[threadIdx.x];
-        const uint32_t c0 = __builtin_popcount(wv.x), c1 = c0 + __builtin_popcount(wv.y);
-        const uint32_t c2 = c1 + __builtin_popcount(wv.z), c3 = c2 + __builtin_popcount(wv.w);
-        uint32_t incl = c3;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t v = __shfl_up(incl, off);
-            if ((int)lane >= off) incl += v;
-        }
-        if (lane == 63) sal_wave[wave] = incl;
-        __syncthreads();
-        uint32_t base = sal_before + incl - c3;
-        for (uint32_t k = 0; k < wave; ++k) base += sal_wave[k];
-        sal_rank[threadIdx.x * 4] = (uint16_t)base;
-        sal_rank[threadIdx.x * 4 + 1] = (uint16_t)(base + c0);
-        sal_rank[threadIdx.x * 4 + 2] = (uint16_t)(base + c1);
-        sal_rank[threadIdx.x * 4 + 3] = (uint16_t)(base + c2);
-    }
     // Work item = one code word (4 bytes = 8 elements) -> 16 bytes of bf16: consecutive lanes take consecutive
     // words, so every load and store instruction of a wavefront covers one contiguous span.
     constexpr int U = 4;
@@ -127,6 +97,38 @@ __global__ __launch_bounds__(kDeqThreads) void dequantize_fast_kernel(
         uint32_t* dst = pair + did_t * 256 + hn_t * 16;
 #pragma unroll
         for (int ln = 0; ln < 16; ++ln) dst[ln] = hi | dv[ln & 7] | ((uint32_t)(ln & 8) << 12);
+        __syncthreads();
+    }
+    // (the salient list is read after the codes were requested: both are then on their way together)
+    if (kSum) {
+        static_assert(kDeqThreads * 4 * 32 == (int)kMaxFusedRows, "four bitmap words per thread");
+        for (uint32_t i = threadIdx.x; i < kMaxFusedRows / 32; i += kDeqThreads) sal_bits[i] = 0;
+        if (threadIdx.x == 0) sal_before = 0;
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < p.n_sal; i += kDeqThreads) {
+            const int32_t r = p.salient[i];
+            if (r < 0) atomicAdd(&sal_before, 1u);
+            else if ((uint32_t)r < p.rows) atomicOr(&sal_bits[(uint32_t)r >> 5], 1u << (r & 31));
+        }
+        __syncthreads();
+        const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const uint4 wv = reinterpret_cast<const uint4*>(sal_bits)[threadIdx.x];
+        const uint32_t c0 = __builtin_popcount(wv.x), c1 = c0 + __builtin_popcount(wv.y);
+        const uint32_t c2 = c1 + __builtin_popcount(wv.z), c3 = c2 + __builtin_popcount(wv.w);
+        uint32_t incl = c3;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t v = __shfl_up(incl, off);
+            if ((int)lane >= off) incl += v;
+        }
+        if (lane == 63) sal_wave[wave] = incl;
+        __syncthreads();
+        uint32_t base = sal_before + incl - c3;
+        for (uint32_t k = 0; k < wave; ++k) base += sal_wave[k];
+        sal_rank[threadIdx.x * 4] = (uint16_t)base;
+        sal_rank[threadIdx.x * 4 + 1] = (uint16_t)(base + c0);
+        sal_rank[threadIdx.x * 4 + 2] = (uint16_t)(base + c1);
+        sal_rank[threadIdx.x * 4 + 3] = (uint16_t)(base + c2);
         __syncthreads();
     }
     // 64-bit loop counter: i0 + stride * U may pass 2^32 for the largest tensors
