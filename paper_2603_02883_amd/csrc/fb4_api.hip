@@ -64,10 +64,13 @@ int check_opts(const fb4_opts* o)
 template <int SEL, int G, int MODE, int LPB>
 void launch_ts(bool two_stage, int grid, hipStream_t s, const QuantParams& p)
 {
+    // (the leading arguments repeat fields of p: see the kernel)
     if (two_stage)
-        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, true, LPB>), dim3(grid), dim3(kThreads), 0, s, p);
+        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, true, LPB>), dim3(grid), dim3(kThreads), 0, s, p.blob, p.x,
+                           p.salient, p.n_tiles, p.tiles_per_row, grid, p.row_stride, p.cols, p);
     else
-        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, false, LPB>), dim3(grid), dim3(kThreads), 0, s, p);
+        hipLaunchKernelGGL((quantize_kernel<SEL, G, MODE, false, LPB>), dim3(grid), dim3(kThreads), 0, s, p.blob, p.x,
+                           p.salient, p.n_tiles, p.tiles_per_row, grid, p.row_stride, p.cols, p);
 }
 
 template <int MODE>

@@ -413,44 +413,83 @@ __device__ __forceinline__ uint32_t select_sse_seda(const Lane8& e, const Tables
 
 // ------------------------------------------------------------ quantize kernel
 // LPB = lanes per block: 4 for block size 32, 2 for block size 16.
-template <int SEL, int G, int MODE, bool kTwoStage, int LPB>
-__global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p)
-{
-    __shared__ __align__(16) uint8_t lds[kBlobBytes];
-    copy_tables_to_lds(lds, p.blob);
-    const Tables T = table_views(lds);
+// What a lane reads for one tile: its eight elements and, for the second plane (Sec. 3.3), the first
+// plane's code word and metadata of its block.
+struct TileInput {
+    uint4 w;
+    uint32_t c1, m1;
+    long long srow;   // source row of x
+    bool live;        // false: the salient list names a row outside the tensor (wave-uniform)
+};
 
+// The leading scalar arguments repeat the fields of `p` that the first loads depend on; they arrive in
+// registers when the wavefront starts (kernel-argument preload), the rest by a load.
+template <int SEL, int G, int MODE, bool kTwoStage, int LPB>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const uint8_t* blob, const uint16_t* x,
+                                                            const int32_t* salient, int n_tiles, int tiles_per_row,
+                                                            int n_workgroups, long long row_stride, long long cols,
+                                                            QuantParams p)
+{
+    p.blob = blob; p.x = x; p.salient = salient; p.n_tiles = n_tiles; p.tiles_per_row = tiles_per_row;
+    p.row_stride = row_stride; p.cols = cols;
+    __shared__ __align__(16) uint8_t lds[kBlobBytes];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int jb = lane & (LPB - 1);      // lane within its block
-    const int stride = gridDim.x * kWavesPerGroup;
+    const int stride = n_workgroups * kWavesPerGroup;
     const long long code_pitch = p.cols / 2;
 
-    for (int t = blockIdx.x * kWavesPerGroup + wave; t < p.n_tiles; t += stride) {
+    auto request = [&](int t) {
+        TileInput in;
+        in.w = make_uint4(0, 0, 0, 0);
+        in.c1 = in.m1 = 0;
+        in.live = true;
         const int orow = t / p.tiles_per_row;               // output row (wave-uniform)
         const int chunk = t - orow * p.tiles_per_row;
-        long long srow = orow;
+        in.srow = orow;
         if (MODE == kDecomp) {
-            srow = p.salient[orow];
-            if (srow < 0 || srow >= p.rows) continue;       // wave-uniform
+            in.srow = p.salient[orow];
+            if (in.srow < 0 || in.srow >= p.rows) {
+                in.live = false;
+                return in;
+            }
         }
         const long long col = (long long)chunk * kTileElems + lane * 8;   // first of this lane's 8 elements
+        if (col < p.cols) {
+            in.w = *reinterpret_cast<const uint4*>(p.x + in.srow * p.row_stride + col);
+            if (MODE == kDecomp) {
+                in.c1 = *reinterpret_cast<const uint32_t*>(p.codes1 + in.srow * code_pitch + col / 2);
+                in.m1 = p.meta1[in.srow * p.nb + col / (8 * LPB)];
+            }
+        }
+        return in;
+    };
+
+    // The wavefront's first tile is requested before the tables: it is on its way while they are copied.
+    const int t_first = blockIdx.x * kWavesPerGroup + wave;
+    TileInput in;
+    in.live = false;
+    if (t_first < p.n_tiles) in = request(t_first);
+    copy_tables_to_lds(lds, p.blob);
+    const Tables T = table_views(lds);
+
+    for (int t = t_first; t < p.n_tiles; t += stride) {
+        if (t != t_first) in = request(t);
+        if (!in.live) continue;                             // wave-uniform
+        const int orow = t / p.tiles_per_row;
+        const int chunk = t - orow * p.tiles_per_row;
+        const long long srow = in.srow;
+        const long long col = (long long)chunk * kTileElems + lane * 8;
         const bool valid = col < p.cols;                    // the same for all lanes of a block
         const long long blk = col / (8 * LPB);              // block within the row
 
-        // ---- load this lane's eight elements
-        uint4 w = make_uint4(0, 0, 0, 0);
-        if (valid) w = *reinterpret_cast<const uint4*>(p.x + srow * p.row_stride + col);
+        const uint4 w = in.w;
         uint32_t h[8] = {w.x & 0xFFFFu, w.x >> 16, w.y & 0xFFFFu, w.y >> 16,
                          w.z & 0xFFFFu, w.z >> 16, w.w & 0xFFFFu, w.w >> 16};
 
         if (MODE == kDecomp) {
             // Sec. 3.3: residual of the first plane, exact, rounded once to bf16
-            uint32_t c1 = 0, m1 = 0;
-            if (valid) {
-                c1 = *reinterpret_cast<const uint32_t*>(p.codes1 + srow * code_pitch + col / 2);
-                m1 = p.meta1[srow * p.nb + blk];
-            }
+            const uint32_t c1 = in.c1, m1 = in.m1;
             const uint32_t did1 = m1 & 0xFFu, e1 = m1 >> 8;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
