@@ -87,6 +87,50 @@ def time_eager(fn_steps, steps, warmup):
     return wall, e0.elapsed_time(e1) * 1e-3
 
 
+def selector_agreement(F, luts, synth):
+    """Per workload: fraction of blocks on which a selector picks the same dialect as the exhaustive one, and
+    its total squared error relative to the exhaustive selector's (>= 1).  Evaluation only: the comparison
+    runs in torch on the dequantized fp32 tensors."""
+    import torch
+    work = {
+        "cfg1": lambda: synth.gaussian_outlier(rows=1024, cols=3072, seed=1, device="cuda"),
+        "cfg2": lambda: synth.vdit_activation(rows=16384, cols=3072, seed=2, device="cuda"),
+        "cfg4": lambda: synth.mixture_activation(rows=16384, cols=3072, seed=4, device="cuda")[0],
+        "cfg5_activation": lambda: synth.vdit_activation(rows=65536, cols=12288, seed=5, device="cuda",
+                                                         outlier_frac=0.01),
+        "cfg5_weight": lambda: synth.weight_matrix(rows=12288, cols=3072, seed=5, device="cuda"),
+    }
+    variants = {"lut_g8": F.opts(selector=F.SEL_LUT, num_groups=8),
+                "lut_g8_two_stage": F.opts(selector=F.SEL_LUT, num_groups=8, flags=F.FLAG_TWO_STAGE),
+                "lut_g16": F.opts(selector=F.SEL_LUT, num_groups=16),
+                "lut_g32": F.opts(selector=F.SEL_LUT, num_groups=32)}
+
+    def sq_err(x, c, m):
+        total = 0.0
+        for r0 in range(0, x.shape[0], 8192):           # in row chunks: the fp32 copies stay small
+            y = F.fb4_dequantize(luts, c[r0:r0 + 8192], m[r0:r0 + 8192], out_dtype=F.DTYPE_F32)
+            d = (x[r0:r0 + 8192].float() - y).double()
+            d = torch.where(torch.isfinite(d), d, torch.zeros_like(d))
+            total += float((d * d).sum())
+        return total
+
+    out = {}
+    for name, make in work.items():
+        x = make()
+        c0, m0 = F.fb4_quantize(luts, F.opts(selector=F.SEL_SSE), x)
+        e0 = sq_err(x, c0, m0)
+        res = {"blocks": int(m0.numel())}
+        for vname, o in variants.items():
+            c, m = F.fb4_quantize(luts, o, x)
+            same = float(((m & 0xFF) == (m0 & 0xFF)).float().mean())
+            res[vname] = {"same_dialect": round(same, 4), "squared_error_ratio": round(sq_err(x, c, m) / e0, 4)}
+            del c, m
+        out[name] = res
+        del x, c0, m0
+        torch.cuda.empty_cache()
+    return {"selector_agreement": out, "reference": "exhaustive squared-error selector", "block": 32}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,6 +139,9 @@ def main():
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of one HIP graph")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--selector-agreement", action="store_true",
+                    help="instead of timing: how often the online selectors pick the exhaustive selector's "
+                         "dialect, and what the difference costs in squared error, on the five workloads")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc ...`: a few plain device copies of known size, then a few "
                          "launches of the headline kernel and of the exhaustive selector; prints a marker line")
@@ -114,6 +161,11 @@ def main():
     torch.cuda.set_device(0)
     timer = time_eager if args.eager else time_graph
     luts = F.fb4_build_luts(DEFAULT_FORMATBOOK)
+
+    if args.selector_agreement:
+        print(json.dumps(selector_agreement(F, luts, synth)))
+        luts.free()
+        return
 
     x0 = synth.vdit_activation(rows=ROWS, cols=COLS, seed=2, device="cuda")
     xs = [x0] + [x0.clone() for _ in range(N_SETS - 1)]
