@@ -766,3 +766,56 @@ def test_luts_handle_is_reusable_across_streams(F, luts):
     torch.cuda.synchronize()
     for c, m in outs:
         assert torch.equal(c, ref[0]) and torch.equal(m, ref[1])
+
+
+def test_offsets_beyond_4_gib(F, luts):
+    """A 1,500,001 x 3072 tensor (9.2 GB of input, 2.3 GB of codes): every byte offset past 2^32 and the ragged
+    last tile, on sampled rows, through both quantize kernels, the second plane, decode and repack."""
+    rows, cols = 1_500_001, 3072
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 * 2**30:
+        pytest.skip("needs 40 GiB of free device memory")
+    x = torch.empty((rows, cols), dtype=torch.bfloat16, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4242)
+    for r0 in range(0, rows, 65536):
+        r1 = min(rows, r0 + 65536)
+        v = torch.randn((r1 - r0, cols), device="cuda", generator=g)
+        v *= torch.exp2(torch.randint(-6, 7, (r1 - r0, cols // 32), device="cuda", generator=g)
+                        .float()).repeat_interleave(32, dim=1)
+        x[r0:r1] = v.to(torch.bfloat16)
+    del v
+    rng = np.random.default_rng(4242)
+    sample = np.unique(np.concatenate([rng.integers(0, rows, 40), [0, 1, 699_050, 699_051, rows - 2, rows - 1]]))
+    idx = torch.from_numpy(sample).cuda()
+    xs = synth.bf16_bits(x[idx])
+    sal = np.unique(np.concatenate([sample[::3], [rows - 1]])).astype(np.int32)
+    sal_d = torch.from_numpy(sal).cuda()
+    in_sal = np.isin(sample, sal)
+    p_of = torch.from_numpy(np.searchsorted(sal, sample[in_sal])).cuda()
+    for name, sel, gg in (SELECTORS[0], SELECTORS[2]):
+        o = F.opts(selector=sel, num_groups=gg)
+        c1, m1, c2, m2 = F.fb4_quantize_decompose(luts, o, x, sal_d)
+        y = F.fb4_dequantize(luts, c1, m1, codes2=c2, meta2=m2, salient_rows=sal_d)
+        torch.cuda.synchronize()
+        c1s, m1s = host_u8(c1[idx]), host_u16(m1[idx])
+        cr, mr = O.quantize(DEFAULT_FORMATBOOK, xs, selector=sel, num_groups=gg)
+        compare_quant(DEFAULT_FORMATBOOK, xs, c1s, m1s, cr, mr, sel, gg, what="large " + name)
+        c2r, m2r = O.decompose(DEFAULT_FORMATBOOK, xs[in_sal], c1s[in_sal], m1s[in_sal],
+                               np.arange(int(in_sal.sum()), dtype=np.int32), selector=sel, num_groups=gg)
+        c2s, m2s = host_u8(c2[p_of]), host_u16(m2[p_of])
+        compare_quant(DEFAULT_FORMATBOOK, xs[in_sal], c2s, m2s, c2r, m2r, sel, gg, what="large plane 2 " + name)
+        # decode of the sampled rows: both planes where the row is salient
+        yr = O.dequantize(DEFAULT_FORMATBOOK, c1s, m1s)
+        yr[in_sal] = O.dequantize(DEFAULT_FORMATBOOK, c1s[in_sal], m1s[in_sal], codes2=c2s, meta2=m2s,
+                                  salient_rows=np.arange(int(in_sal.sum()), dtype=np.int32))
+        assert np.array_equal(synth.bf16_bits(y[idx]), yr), "large decode " + name
+        del y, c2, m2
+        if sel == 1:
+            el, sc = F.fb4_repack_mxfp8(luts, c1, m1)
+            torch.cuda.synchronize()
+            elr, scr = O.repack_mxfp8(DEFAULT_FORMATBOOK, c1s, m1s)
+            assert np.array_equal(host_u8(el[idx]), elr) and np.array_equal(host_u8(sc[idx]), scr), "large repack"
+            del el, sc
+        del c1, m1
+        torch.cuda.empty_cache()
