@@ -130,13 +130,14 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
                  const int32_t* token_group, const uint8_t* sub, int n_groups, const FusedPlane* fused,
                  hipStream_t s, int* rc)
 {
-    if (opts->selector != FB4_SEL_LUT || (cols % 32) || !aligned(p.codes, 16)) return false;
+    if ((cols % 32) || !aligned(p.codes, 16)) return false;
+    const bool sse = opts->selector == FB4_SEL_SSE;
     if (opts->block == 16 && !aligned(p.meta, 4)) return false;
     const uint64_t nb = (uint64_t)cols / 32;
     const uint64_t n_blocks = (uint64_t)p.rows * nb;
     if (n_blocks >= 0x7FFFFF00ull) return false;
     if (token_group && (uint32_t)n_groups > kMaxFastGroups) return false;
-    if (fused && (opts->num_groups != 8 || p.rows > (long long)kMaxFusedRows || !aligned(fused->codes2, 16)))
+    if (fused && ((!sse && opts->num_groups != 8) || p.rows > (long long)kMaxFusedRows || !aligned(fused->codes2, 16)))
         return false;
     FastParams f = {};
     f.x = p.x;
@@ -172,7 +173,16 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
     const bool flat = p.row_stride == cols;
     const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
     const bool seda = token_group != nullptr;
-    if (fused) {
+    if (sse) {
+        // the exhaustive selector: group count 0 in the kernel's template
+        if (fused) {
+            if (opts->block == 32) launch_fast_variant<32, 0, false, true>(ts, seda, ng, s, f);
+            else launch_fast_variant<16, 0, false, true>(ts, seda, ng, s, f);
+        } else {
+            if (opts->block == 32) launch_fast_variant<32, 0, false, false>(ts, seda, ng, s, f);
+            else launch_fast_variant<16, 0, false, false>(ts, seda, ng, s, f);
+        }
+    } else if (fused) {
         if (opts->block == 32) {
             if (flat) launch_fast_variant<32, 8, true, true>(ts, seda, ng, s, f);
             else launch_fast_variant<32, 8, false, true>(ts, seda, ng, s, f);

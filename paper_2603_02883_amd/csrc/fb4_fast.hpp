@@ -77,6 +77,16 @@ __device__ __forceinline__ uint32_t pk_sub(uint32_t a, uint32_t b)
 {
     return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, a) - __builtin_bit_cast(u16x2, b));
 }
+// max(a - b, 0) in both halves
+__device__ __forceinline__ uint32_t pk_sub_sat(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(__builtin_bit_cast(u16x2, a),
+                                                                      __builtin_bit_cast(u16x2, b)));
+}
+__device__ __forceinline__ uint32_t pk_shl(uint32_t a, uint32_t n)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, a) << __builtin_bit_cast(u16x2, n));
+}
 __device__ __forceinline__ uint32_t pk_shr(uint32_t v, uint32_t s)   // per half: v >> s, s <= 15
 {
     return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, v) >> __builtin_bit_cast(u16x2, s));
@@ -117,9 +127,17 @@ constexpr int kLdsSalRank = kLdsSalBits + kMaxFusedRows / 8;   // uint16 per bit
 constexpr int kLdsDecompBytes = 512 + 128 + kMaxFusedRows / 8 + kMaxFusedRows / 32 * 2;
 // SeDA: [n_groups + 1][32 B] 0xFF = dialect excluded; last row: none.  Placed after everything else.
 constexpr int lds_seda_offset(bool decomp) { return kLdsRange + 256 + (decomp ? kLdsDecompBytes : 0); }
-constexpr int lds_fast_bytes(bool seda, bool decomp)
+// Exhaustive selector only: per bin the (gain, magnitude) byte pairs of the 32 dialects, 64 B in four 16-byte
+// pieces, each piece in 16 copies so that the 16 lanes of one LDS pass read 16 different bank groups whatever
+// their bins: [32 bins][4 pieces][16 copies][16 B] = 32 KiB.  Placed last.
+constexpr int kGmBytes = 32 * 4 * 16 * 16;
+constexpr int lds_gm_offset(bool seda, bool decomp)
 {
     return lds_seda_offset(decomp) + (seda ? (int)(kMaxFastGroups + 1) * 32 : 0);
+}
+constexpr int lds_fast_bytes(bool seda, bool decomp, bool sse = false)
+{
+    return lds_gm_offset(seda, decomp) + (sse ? kGmBytes : 0);
 }
 
 struct BlockCodes {
@@ -151,11 +169,14 @@ __device__ __forceinline__ uint32_t residual_elem(uint32_t xh, uint32_t nib, uin
 // excluded by excl_a never wins; excl_b (the two-stage range filter) applies only if it leaves a candidate.
 // kResidual: quantize the residual of the first plane (c1 = the block's first-plane code words, m1 = its
 // metadata word) instead of x itself.
+// G == 0: the exhaustive selector (gm_off: LDS offset of its table, copy 0 is read).
 template <int kBlock, int G, bool kResidual>
 __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, const uint8_t* lds, uint32_t excl_a,
-                                                        bool two_stage, uint4 c1, uint32_t m1)
+                                                        bool two_stage, uint4 c1, uint32_t m1, uint32_t gm_off)
 {
-    constexpr int PER = kBlock / G;
+    constexpr bool kSse = G == 0;
+    constexpr int GG = kSse ? kBlock : G;   // the exhaustive selector looks at every element
+    constexpr int PER = kBlock / GG;
     BlockCodes out;
     auto elem = [&](int i) -> uint32_t {
         const uint32_t h = xb[i];
@@ -171,18 +192,19 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
         amax = max(amax, (m > 0x7F80u) ? 0u : m);
     }
     const uint32_t eb = min(max(amax >> 7, 4u), 254u);
-    auto bin_of = [&](uint32_t h) -> uint32_t {
+    // X = 256 * xhat (exact whenever xhat >= 0.5)
+    auto x256_of = [&](uint32_t h) -> uint32_t {
         uint32_t m = h & 0x7FFFu;
         if (m > 0x7F80u) m = 0;
         uint32_t ef = m >> 7;
         uint32_t sig = (m & 0x7Fu) | (ef ? 0x80u : 0u);
         uint32_t sh = eb + 3u - max(ef, 1u);
-        uint32_t X = (sh <= 7u) ? (sig << (7u - sh)) : (sig >> min(sh - 7u, 31u));
-        return min(X >> 7, 31u);
+        return (sh <= 7u) ? (sig << (7u - sh)) : (sig >> min(sh - 7u, 31u));
     };
-    uint32_t gbin[G];
+    auto bin_of = [&](uint32_t h) -> uint32_t { return min(x256_of(h) >> 7, 31u); };
+    uint32_t gbin[GG];
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
+    for (int j = 0; j < GG; ++j) {
         uint32_t g = 0;
 #pragma unroll 1
         for (int i = 0; i < PER; ++i) g = max(g, bin_of(elem(PER * j + i)));
@@ -190,15 +212,28 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
     }
     uint32_t bmax = 0;
 #pragma unroll
-    for (int j = 0; j < G; ++j) bmax = max(bmax, gbin[j]);
+    for (int j = 0; j < GG; ++j) bmax = max(bmax, gbin[j]);
     const uint32_t excl_b = kLdsRange + (min(max(bmax >> 1, 8u), 15u) - 8u) * 32u;
     uint32_t best = 0xFFFFFFFFu, best_b = 0xFFFFFFFFu;
 #pragma unroll 1
     for (uint32_t d = 0; d < 32; ++d) {
         if (excl_a != 0xFFFFFFFFu && lds[excl_a + d]) continue;
         uint32_t s = 0;
+        if (kSse) {
+            // Z_d = sum of 128 * gain + frac * magnitude: the largest Z is the smallest squared error
+            uint32_t z = 0;
+#pragma unroll 1
+            for (int i = 0; i < kBlock; ++i) {
+                const uint32_t X = x256_of(elem(i));
+                const uint32_t b = min(X >> 7, 31u), f = X - (b << 7);
+                const uint8_t* e = lds + gm_off + (b << 10) + (d >> 3) * 256u + (d & 7u) * 2u;
+                z += ((uint32_t)e[0] << 7) + (uint32_t)e[1] * f;
+            }
+            s = 0xFFFFFu - z;
+        } else {
 #pragma unroll
-        for (int j = 0; j < G; ++j) s += lds[kLdsRows + gbin[j] * 256 + (d >> 4) * 128 + (d & 15)];
+            for (int j = 0; j < GG; ++j) s += lds[kLdsRows + gbin[j] * 256 + (d >> 4) * 128 + (d & 15)];
+        }
         best = min(best, (s << 5) | d);
         if (two_stage && !lds[excl_b + d]) best_b = min(best_b, (s << 5) | d);
     }
@@ -223,11 +258,13 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
 struct TileConsts {
     uint32_t k7f, k80, kpair, row_base;
     uint32_t kdid[16];   // DID pairs of the 16 key registers: (4i, 4i+2) and (4i+1, 4i+3)
+    uint32_t gm_off;     // exhaustive selector: LDS offset of its table
 };
 
-__device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane)
+__device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane, uint32_t gm_off)
 {
     TileConsts K;
+    K.gm_off = gm_off;
     K.row_base = kLdsRows + (lane & 7u) * 16u;
     K.k7f = sgpr_const(0x007F007Fu);
     K.k80 = vgpr_const(0x00800080u);
@@ -331,6 +368,71 @@ __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], c
     return halves_min(best) & 31u;
 }
 
+// Exhaustive selection (Sec. 3.2, first paragraph) for one block whose elements sit in registers
+// b2[first .. first + RB) (bins, two per register) and x2 (256 * xhat, two per register).  With X = 256 * xhat =
+// 128 * bin + frac and m the nearest magnitude of a dialect, (X - 256 m)^2 = X^2 - 512 Z with
+// Z = 128 * m * (bin - m) + frac * m: the smallest error is the largest Z_d = sum over the elements of
+// 128 * gain[bin][d] + frac * mag[bin][d] (< 2^20).  A table row holds the byte pairs (gain, mag) of two
+// dialects per dword, so one four-byte dot product with (128, frac, 0, 0) or (0, 0, 128, frac) adds an
+// element's term to a dialect's sum.  Candidate restrictions as in select_lut_rows.
+template <int RB, bool kTwoStage, bool kSeda>
+__device__ __forceinline__ uint32_t select_sse_rows(const uint32_t (&b2)[16], const uint32_t (&x2)[16], int first,
+                                                    const uint8_t* lds, const TileConsts& K, uint32_t lane,
+                                                    uint32_t excl_a)
+{
+    uint32_t z[32];
+#pragma unroll
+    for (int d = 0; d < 32; ++d) z[d] = 0;
+    const uint32_t base = K.gm_off + (lane & 15u) * 16u;
+#pragma unroll
+    for (int k = first; k < first + RB; ++k) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t bin = h ? (b2[k] >> 16) : (b2[k] & 0xFFFFu);
+            const uint32_t f = (h ? (x2[k] >> 16) : x2[k]) & 0x7Fu;
+            const uint8_t* row = lds + base + (bin << 10);
+            const uint4 r[4] = {*reinterpret_cast<const uint4*>(row), *reinterpret_cast<const uint4*>(row + 256),
+                                *reinterpret_cast<const uint4*>(row + 512), *reinterpret_cast<const uint4*>(row + 768)};
+            const uint32_t sel_lo = 128u | (f << 8), sel_hi = sel_lo << 16;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t v[4] = {r[q].x, r[q].y, r[q].z, r[q].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    z[8 * q + 2 * j] = __builtin_amdgcn_udot4(v[j], sel_lo, z[8 * q + 2 * j], false);
+                    z[8 * q + 2 * j + 1] = __builtin_amdgcn_udot4(v[j], sel_hi, z[8 * q + 2 * j + 1], false);
+                }
+            }
+        }
+    }
+    // ---- restrictions: rows of bytes, 0xFF = excluded
+    uint32_t xa[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (kSeda) {
+        const uint4 a0 = *reinterpret_cast<const uint4*>(lds + excl_a), a1 = *reinterpret_cast<const uint4*>(lds + excl_a + 16);
+        xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w; xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+    }
+    if (kTwoStage) {
+        uint32_t bm2 = 0;
+#pragma unroll
+        for (int k = first; k < first + RB; ++k) bm2 = pk_max(bm2, b2[k]);
+        const uint32_t roff = kLdsRange + (min(max(halves_max(bm2) >> 1, 8u), 15u) - 8u) * 32u;
+        const uint4 a0 = *reinterpret_cast<const uint4*>(lds + roff), a1 = *reinterpret_cast<const uint4*>(lds + roff + 16);
+        xr[0] = a0.x; xr[1] = a0.y; xr[2] = a0.z; xr[3] = a0.w; xr[4] = a1.x; xr[5] = a1.y; xr[6] = a1.z; xr[7] = a1.w;
+    }
+    // ---- largest Z, lowest DID on ties: keys (2^20 - 1 - Z) << 5 | DID, smallest wins
+    uint32_t best = 0xFFFFFFFFu, best_r = 0xFFFFFFFFu;
+#pragma unroll
+    for (int d = 0; d < 32; ++d) {
+        uint32_t key = ((0xFFFFFu - z[d]) << 5) | (uint32_t)d;
+        if (kSeda) key |= (uint32_t)__builtin_amdgcn_sbfe((int)xa[d >> 2], 8 * (d & 3), 8);   // 0xFF -> all ones
+        best = min(best, key);
+        if (kTwoStage) best_r = min(best_r, key | (uint32_t)__builtin_amdgcn_sbfe((int)xr[d >> 2], 8 * (d & 3), 8));
+    }
+    // the range filter applies unless it leaves no candidate
+    if (kTwoStage && best_r != 0xFFFFFFFFu) best = best_r;
+    return best & 31u;
+}
+
 // One lane owns 32 consecutive elements of a row: w = its 32 bf16 as 16 packed pairs, holding one block of
 // 32 or two blocks of 16.  Produces the four code words and the metadata (one 16-bit word, or two for block
 // size 16 with the first block in the low half).  xb / in_range are only used by the plain per-element
@@ -344,7 +446,9 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
 {
     constexpr int NB = 32 / kBlock;     // blocks per lane
     constexpr int RB = 16 / NB;         // packed registers per block
-    constexpr int PER = kBlock / G;     // elements per group
+    constexpr bool kSse = G == 0;       // exhaustive selector: every element, no groups
+    constexpr int GG = kSse ? kBlock : G;
+    constexpr int PER = kBlock / GG;    // elements per group
     static_assert((kBlock == 32 || kBlock == 16) && (PER == 4 || PER == 2 || PER == 1), "supported shapes");
     // ---- magnitudes and maxima (bf16 bit patterns order like the values)
     uint32_t a[16];
@@ -376,7 +480,8 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
                 const uint4 c1 = NB == 1 ? make_uint4(code1[0], code1[1], code1[2], code1[3])
                                          : make_uint4(code1[2 * b], code1[2 * b + 1], 0u, 0u);
                 const BlockCodes r = quantize_block_plain<kBlock, G, kResidual>(
-                    xb + b * kBlock, lds, kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage, c1, (meta1 >> (16 * b)) & 0xFFFFu);
+                    xb + b * kBlock, lds, kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage, c1, (meta1 >> (16 * b)) & 0xFFFFu,
+                    K.gm_off);
 #pragma unroll
                 for (int c = 0; c < 4 / NB; ++c) code[b * (4 / NB) + c] = r.code[c];
                 meta |= r.meta << (16 * b);
@@ -384,6 +489,7 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
         }
     } else {
         uint32_t b2[16];
+        uint32_t x2[16];   // exhaustive selector: 256 * xhat
         uint32_t did[NB];
         meta = 0;
 #pragma unroll
@@ -398,16 +504,22 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
                 const uint32_t sh = pk_min(pk_sub(ec, ef), 0x000F000Fu);       // >= 3; >= 8 means bin 0
                 const uint32_t sig = (a[k] & K.k7f) | K.k80;                   // 1.m as 8-bit integers
                 b2[k] = pk_shr(sig, sh);                                       // floor(2*xhat), 0..31
+                // 256 * xhat = sig << (7 - sh); an element with sh > 7 is in bin 0 and its value is not used
+                if (kSse) x2[k] = pk_shl(sig, pk_sub_sat(0x00070007u, sh));
             }
-            // ---- group-wise maxima: groups are runs of PER elements
-            uint32_t gbin[G];
+            if (kSse) {
+                did[b] = select_sse_rows<RB, kTwoStage, kSeda>(b2, x2, b * RB, lds, K, threadIdx.x, excl_a);
+            } else {
+                // ---- group-wise maxima: groups are runs of PER elements
+                uint32_t gbin[GG];
 #pragma unroll
-            for (int r = 0; r < G; ++r) {
-                if (PER == 4) gbin[r] = halves_max(pk_max(b2[b * RB + 2 * r], b2[b * RB + 2 * r + 1]));
-                else if (PER == 2) gbin[r] = halves_max(b2[b * RB + r]);
-                else gbin[r] = (r & 1) ? (b2[b * RB + r / 2] >> 16) : (b2[b * RB + r / 2] & 0xFFFFu);
+                for (int r = 0; r < GG; ++r) {
+                    if (PER == 4) gbin[r] = halves_max(pk_max(b2[b * RB + 2 * r], b2[b * RB + 2 * r + 1]));
+                    else if (PER == 2) gbin[r] = halves_max(b2[b * RB + r]);
+                    else gbin[r] = (r & 1) ? (b2[b * RB + r / 2] >> 16) : (b2[b * RB + r / 2] & 0xFFFFu);
+                }
+                did[b] = select_lut_rows<GG, kTwoStage, kSeda>(gbin, lds, K, excl_a);
             }
-            did[b] = select_lut_rows<G, kTwoStage, kSeda>(gbin, lds, K, excl_a);
             meta |= (did[b] | (eb << 8)) << (16 * b);
         }
         // ---- emit: every element through Qvalue of the chosen dialect, two elements per pair-table lookup
@@ -541,7 +653,9 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
     p.blob = blob; p.x = x; p.n_blocks = n_blocks; p.n_tiles = n_tiles; p.div_mul = div_mul; p.div_shift = div_shift;
     p.nb = nb; p.row_stride = row_stride; p.codes = codes; p.meta = meta;
     constexpr int kLdsSeda = lds_seda_offset(kDecomp);
-    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kDecomp)];
+    constexpr bool kSse = G == 0;   // the exhaustive selector
+    constexpr int kLdsGm = lds_gm_offset(kSeda, kDecomp);
+    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kDecomp, kSse)];
     __shared__ uint32_t sal_before;      // fused decomposition: list entries below row 0
     __shared__ uint32_t sal_wave[kFastWaves];
     const uint32_t lane = threadIdx.x & 63;
@@ -565,6 +679,8 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
     uint32_t nibv[kNibIt], rngv = 0, decv = 0;
     uint4 magq = make_uint4(0, 0, 0, 0);
     uint2 sub0 = make_uint2(0, 0);
+    constexpr int kGmIt = kSse ? (512 + kFastThreads - 1) / kFastThreads : 1;
+    uint4 gmm[kGmIt][4], gmg[kGmIt][4];
     int32_t sal_reg[kSalEarly];
     const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kFastThreads;
     {
@@ -595,6 +711,18 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
         }
         if (kSeda && p.n_groups > 0)
             sub0 = *reinterpret_cast<const uint2*>(p.sub + (size_t)min(threadIdx.x, p.n_groups - 1u) * 8);
+        if (kSse) {
+            // work item i = (bin, copy): the bin's 32 magnitudes and 32 gains (16 bits each in the table blob)
+#pragma unroll
+            for (int k = 0; k < kGmIt; ++k) {
+                const int bin = min((int)threadIdx.x + k * kFastThreads, 511) >> 4;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    gmm[k][q] = *reinterpret_cast<const uint4*>(p.blob + kOffMag16 + bin * 64 + q * 16);
+                    gmg[k][q] = *reinterpret_cast<const uint4*>(p.blob + kOffGain16 + bin * 64 + q * 16);
+                }
+            }
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     cur = load_block<kFlat, kSeda>(p, t * 64u + lane);
@@ -611,6 +739,27 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
             if (i < 256) reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = nibv[k];
         }
         if (kTwoStage && threadIdx.x < 64) reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] = rngv;
+        if (kSse) {
+#pragma unroll
+            for (int k = 0; k < kGmIt; ++k) {
+                const int i = threadIdx.x + k * kFastThreads;
+                if (i < 512) {
+                    const int bin = i >> 4, copy = i & 15;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        // piece q: dialects 8q .. 8q+7; a source dword holds two dialects' 16-bit values
+                        const uint32_t m[4] = {gmm[k][q].x, gmm[k][q].y, gmm[k][q].z, gmm[k][q].w};
+                        const uint32_t g[4] = {gmg[k][q].x, gmg[k][q].y, gmg[k][q].z, gmg[k][q].w};
+                        uint32_t o[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)   // bytes: gain, mag of dialect 8q+2j, then of 8q+2j+1
+                            o[j] = (g[j] & 0xFFu) | ((m[j] & 0xFFu) << 8) | ((g[j] >> 16) << 16) | ((m[j] >> 16) << 24);
+                        *reinterpret_cast<uint4*>(lds + kLdsGm + bin * 1024 + q * 256 + copy * 16) =
+                            make_uint4(o[0], o[1], o[2], o[3]);
+                    }
+                }
+            }
+        }
         if (kDecomp) {
             if (threadIdx.x < 128) reinterpret_cast<uint32_t*>(lds + kLdsDecode)[threadIdx.x] = decv;
             if (threadIdx.x < 32) {
@@ -708,7 +857,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
         }
         __syncthreads();
     }
-    const TileConsts K = make_tile_consts(lane);
+    const TileConsts K = make_tile_consts(lane, kLdsGm);
 
     // Results of a tile are held in registers and written at the top of the next iteration, right after
     // that iteration's input has arrived: memory operations retire in issue order, so a store issued just
