@@ -99,17 +99,25 @@ int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& 
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
-template <int kBlock, int G, bool kFlat, bool kDecomp>
-void launch_fast_variant(bool ts, bool seda, unsigned groups, hipStream_t s, const FastParams& f)
+// Persistent workgroups, one per compute unit: measured 24.4 us against 26.0 us with two on the 16384x3072
+// workload with 8 wavefronts each (SeDA: 25.7 against 27.2; 4, 12 or 16 wavefronts are slower too), and the
+// kernels are free to use up to 256 vector registers per lane.  The exhaustive selector, bound by the vector
+// ALU, runs 12 wavefronts (83 -> 74.5 us).
+template <int kBlock, int G, bool kFlat, bool kDecomp, int kThreads = kFastThreads>
+void launch_fast_variant(bool ts, bool seda, int n_cu, hipStream_t s, const FastParams& f)
 {
+    constexpr int kWaves = kThreads / 64;
+    long long g = ((long long)f.n_tiles + kWaves - 1) / kWaves;
+    if (g > n_cu) g = n_cu;
+    const unsigned groups = (unsigned)g;
     // (the leading arguments repeat fields of f: see the kernel)
 #define FB4_FAST_ARGS f.blob, f.x, f.n_blocks, f.n_tiles, f.div_mul, f.div_shift, f.nb, groups, f.row_stride, f.codes, f.meta, f
     if (seda) {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, FB4_FAST_ARGS);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, FB4_FAST_ARGS);
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kDecomp, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kDecomp, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
     } else {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, FB4_FAST_ARGS);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false, kDecomp>), dim3(groups), dim3(kFastThreads), 0, s, FB4_FAST_ARGS);
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false, kDecomp, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false, kDecomp, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
     }
 #undef FB4_FAST_ARGS
 }
@@ -163,13 +171,7 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
         f.codes2 = fused->codes2;
         f.meta2 = fused->meta2;
     }
-    long long groups = ((long long)f.n_tiles + kFastWaves - 1) / kFastWaves;
-    // Persistent workgroups, one per compute unit (8 wavefronts): measured 24.4 us against 26.0 us with two on
-    // the 16384x3072 workload (SeDA: 25.7 against 27.2; 4, 12 or 16 wavefronts are slower too), and the kernels
-    // are free to use up to 256 vector registers per lane.
-    const long long cap = (long long)luts->n_cu;
-    if (groups > cap) groups = cap;
-    const unsigned ng = (unsigned)groups;
+    const int ng = luts->n_cu;   // workgroups at most: one per compute unit
     const bool flat = p.row_stride == cols;
     const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
     const bool seda = token_group != nullptr;
@@ -179,8 +181,14 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
             if (opts->block == 32) launch_fast_variant<32, 0, false, true>(ts, seda, ng, s, f);
             else launch_fast_variant<16, 0, false, true>(ts, seda, ng, s, f);
         } else {
-            if (opts->block == 32) launch_fast_variant<32, 0, false, false>(ts, seda, ng, s, f);
-            else launch_fast_variant<16, 0, false, false>(ts, seda, ng, s, f);
+            // 12 wavefronts, unless the candidate lists would push the kernel past their 168 registers
+            if (seda) {
+                if (opts->block == 32) launch_fast_variant<32, 0, false, false>(ts, seda, ng, s, f);
+                else launch_fast_variant<16, 0, false, false>(ts, seda, ng, s, f);
+            } else {
+                if (opts->block == 32) launch_fast_variant<32, 0, false, false, 768>(ts, seda, ng, s, f);
+                else launch_fast_variant<16, 0, false, false, 768>(ts, seda, ng, s, f);
+            }
         }
     } else if (fused) {
         if (opts->block == 32) {

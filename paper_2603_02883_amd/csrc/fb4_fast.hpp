@@ -645,19 +645,20 @@ __device__ __forceinline__ void residual32(const uint32_t (&w)[16], const uint32
 // the library is compiled so that up to 16 leading argument registers are filled by the dispatcher when the
 // wavefront starts (the rest of the arguments come by a load, half a microsecond later), and the table and
 // tile requests can then go out at once.
-template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda, bool kDecomp = false>
-__global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
+template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda, bool kDecomp = false, int kThreads = kFastThreads>
+__global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     const uint8_t* blob, const uint16_t* x, uint32_t n_blocks, uint32_t n_tiles, uint32_t div_mul, uint32_t div_shift,
     uint32_t nb, uint32_t n_workgroups, long long row_stride, uint8_t* codes, uint16_t* meta, FastParams p)
 {
     p.blob = blob; p.x = x; p.n_blocks = n_blocks; p.n_tiles = n_tiles; p.div_mul = div_mul; p.div_shift = div_shift;
     p.nb = nb; p.row_stride = row_stride; p.codes = codes; p.meta = meta;
+    constexpr int kWaves = kThreads / 64;
     constexpr int kLdsSeda = lds_seda_offset(kDecomp);
     constexpr bool kSse = G == 0;   // the exhaustive selector
     constexpr int kLdsGm = lds_gm_offset(kSeda, kDecomp);
     __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kDecomp, kSse)];
     __shared__ uint32_t sal_before;      // fused decomposition: list entries below row 0
-    __shared__ uint32_t sal_wave[kFastWaves];
+    __shared__ uint32_t sal_wave[kWaves];
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // Tiles of workgroup b are b, b + W, b + 2W, ... (W = number of workgroups).  The waves of a workgroup
@@ -667,34 +668,34 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
     const uint32_t W = n_workgroups;   // = gridDim.x, which would have to be loaded
     Block64 cur;
     uint32_t t = blockIdx.x + wave * W;                      // first tile: static
-    uint32_t t_next = blockIdx.x + (kFastWaves + wave) * W;   // second tile: static
-    if (threadIdx.x == 0) wg_next = 2 * kFastWaves;
+    uint32_t t_next = blockIdx.x + (kWaves + wave) * W;   // second tile: static
+    if (threadIdx.x == 0) wg_next = 2 * kWaves;
     // Loads are answered in the order they were issued.  The (small, mostly cached) table and list loads
     // therefore go out first and the first tile's right behind them: the tables are then built while the
     // tile is still on its way, instead of after it.
-    constexpr int kRowIt = (512 + kFastThreads - 1) / kFastThreads;
-    constexpr int kNibIt = (256 + kFastThreads - 1) / kFastThreads;
+    constexpr int kRowIt = (512 + kThreads - 1) / kThreads;
+    constexpr int kNibIt = (256 + kThreads - 1) / kThreads;
     constexpr int kSalEarly = 8;
     uint4 rowv[kRowIt];
     uint32_t nibv[kNibIt], rngv = 0, decv = 0;
     uint4 magq = make_uint4(0, 0, 0, 0);
     uint2 sub0 = make_uint2(0, 0);
-    constexpr int kGmIt = kSse ? (512 + kFastThreads - 1) / kFastThreads : 1;
+    constexpr int kGmIt = kSse ? (512 + kThreads - 1) / kThreads : 1;
     uint4 gmm[kGmIt][4], gmg[kGmIt][4];
     int32_t sal_reg[kSalEarly];
-    const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kFastThreads;
+    const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kThreads;
     {
         // Qerror rows as eight bank-disjoint copies: piece i = (bin, half, copy) is 16 bytes of row `bin`
         // (indices are clamped, not predicated: a thread past the end loads a piece it does not write)
 #pragma unroll
         for (int k = 0; k < kRowIt; ++k) {
-            const int i = min((int)threadIdx.x + k * kFastThreads, 511);
+            const int i = min((int)threadIdx.x + k * kThreads, 511);
             const int bin = i >> 4, half = (i >> 3) & 1;
             rowv[k] = *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
         }
 #pragma unroll
         for (int k = 0; k < kNibIt; ++k)
-            nibv[k] = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[min((int)threadIdx.x + k * kFastThreads, 255)];
+            nibv[k] = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[min((int)threadIdx.x + k * kThreads, 255)];
         if (kTwoStage) rngv = reinterpret_cast<const uint32_t*>(p.blob + kOffRangeExcl)[threadIdx.x & 63u];
         if (kDecomp) {
             decv = reinterpret_cast<const uint32_t*>(p.blob + kOffDecode)[threadIdx.x & 127u];
@@ -704,7 +705,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
             if (sal_early) {
 #pragma unroll
                 for (int k = 0; k < kSalEarly; ++k) {
-                    const uint32_t i = threadIdx.x + k * kFastThreads;
+                    const uint32_t i = threadIdx.x + k * kThreads;
                     sal_reg[k] = i < p.n_sal ? p.salient[i] : 0x7FFFFFFF;   // beyond any row: ignored
                 }
             }
@@ -715,7 +716,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
             // work item i = (bin, copy): the bin's 32 magnitudes and 32 gains (16 bits each in the table blob)
 #pragma unroll
             for (int k = 0; k < kGmIt; ++k) {
-                const int bin = min((int)threadIdx.x + k * kFastThreads, 511) >> 4;
+                const int bin = min((int)threadIdx.x + k * kThreads, 511) >> 4;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     gmm[k][q] = *reinterpret_cast<const uint4*>(p.blob + kOffMag16 + bin * 64 + q * 16);
@@ -730,19 +731,19 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
     {
 #pragma unroll
         for (int k = 0; k < kRowIt; ++k) {
-            const int i = threadIdx.x + k * kFastThreads;
+            const int i = threadIdx.x + k * kThreads;
             if (i < 512) reinterpret_cast<uint4*>(lds + kLdsRows)[i] = rowv[k];
         }
 #pragma unroll
         for (int k = 0; k < kNibIt; ++k) {
-            const int i = threadIdx.x + k * kFastThreads;
+            const int i = threadIdx.x + k * kThreads;
             if (i < 256) reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = nibv[k];
         }
         if (kTwoStage && threadIdx.x < 64) reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] = rngv;
         if (kSse) {
 #pragma unroll
             for (int k = 0; k < kGmIt; ++k) {
-                const int i = threadIdx.x + k * kFastThreads;
+                const int i = threadIdx.x + k * kThreads;
                 if (i < 512) {
                     const int bin = i >> 4, copy = i & 15;
 #pragma unroll
@@ -773,18 +774,18 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
                 }
                 reinterpret_cast<uint32_t*>(lds + kLdsMagNib)[threadIdx.x] = mw;
             }
-            for (uint32_t i = threadIdx.x; i < kMaxFusedRows / 32; i += kFastThreads)
+            for (uint32_t i = threadIdx.x; i < kMaxFusedRows / 32; i += kThreads)
                 reinterpret_cast<uint32_t*>(lds + kLdsSalBits)[i] = 0;
             if (threadIdx.x == 0) sal_before = 0;
         }
         if (kSeda) {
             // one exclusion row per group: everything excluded except the group's valid DIDs; a group without
             // a valid DID, and the extra last row (rows outside any group), exclude nothing
-            for (uint32_t g = threadIdx.x; g <= p.n_groups; g += kFastThreads) {
+            for (uint32_t g = threadIdx.x; g <= p.n_groups; g += kThreads) {
                 uint32_t keep = 0;
                 if (g < p.n_groups) {
                     // the first round's entries were requested with the tables
-                    const uint2 s8 = g < (uint32_t)kFastThreads ? sub0 : *reinterpret_cast<const uint2*>(p.sub + (size_t)g * 8);
+                    const uint2 s8 = g < (uint32_t)kThreads ? sub0 : *reinterpret_cast<const uint2*>(p.sub + (size_t)g * 8);
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
                         const uint32_t d = ((k < 4 ? s8.x : s8.y) >> (8 * (k & 3))) & 0xFFu;
@@ -804,7 +805,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
         }
         __syncthreads();
         // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
-        for (int i = threadIdx.x; i < 1024; i += kFastThreads) {
+        for (int i = threadIdx.x; i < 1024; i += kThreads) {
             const int hi = i >> 5, lo = i & 31;
             const uint4* rl = reinterpret_cast<const uint4*>(lds + kLdsNibT + lo * 32);
             const uint4* rh = reinterpret_cast<const uint4*>(lds + kLdsNibT + hi * 32);
@@ -818,7 +819,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
             // Salient rows as a bitmap.  The list is ascending and unique, so the position of row r in it is
             // (entries below row 0) + (salient rows below r): kept as a running count per bitmap word.
             constexpr uint32_t kWords = kMaxFusedRows / 32;
-            constexpr uint32_t kWpt = (kWords + kFastThreads - 1) / kFastThreads;   // bitmap words per thread
+            constexpr uint32_t kWpt = (kWords + kThreads - 1) / kThreads;   // bitmap words per thread
             uint32_t* bits = reinterpret_cast<uint32_t*>(lds + kLdsSalBits);
             auto mark = [&](int32_t r) {
                 if (r < 0) atomicAdd(&sal_before, 1u);
@@ -828,7 +829,7 @@ __global__ __launch_bounds__(kFastThreads) void quantize_lut_kernel(
 #pragma unroll
                 for (int k = 0; k < kSalEarly; ++k) mark(sal_reg[k]);
             } else {
-                for (uint32_t i = threadIdx.x; i < p.n_sal; i += kFastThreads) mark(p.salient[i]);
+                for (uint32_t i = threadIdx.x; i < p.n_sal; i += kThreads) mark(p.salient[i]);
             }
             __syncthreads();
             uint32_t run[kWpt];   // salient rows in this thread's words before word k
