@@ -384,16 +384,21 @@ __device__ __forceinline__ uint32_t select_sse_rows(const uint32_t (&b2)[16], co
 #pragma unroll
     for (int d = 0; d < 32; ++d) z[d] = 0;
     const uint32_t base = K.gm_off + (lane & 15u) * 16u;
+    // byte selectors that build (128, frac, 0, 0) and (0, 0, 128, frac) from a register pair's fractions
+    const uint32_t k80 = vgpr_const(0x80u);
+    const uint32_t s_lo[2] = {sgpr_const(0x0C0C0004u), sgpr_const(0x0C0C0204u)};
+    const uint32_t s_hi[2] = {sgpr_const(0x00040C0Cu), sgpr_const(0x02040C0Cu)};
+    const uint32_t k_row[2] = {sgpr_const(1024u), sgpr_const(1024u << 16)};   // bin * 1024 from either half
 #pragma unroll
     for (int k = first; k < first + RB; ++k) {
+        const uint32_t f2 = x2[k] & 0x007F007Fu;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const uint32_t bin = h ? (b2[k] >> 16) : (b2[k] & 0xFFFFu);
-            const uint32_t f = (h ? (x2[k] >> 16) : x2[k]) & 0x7Fu;
-            const uint8_t* row = lds + base + (bin << 10);
+            const uint8_t* row = lds + dot2_u16(b2[k], k_row[h], base);
             const uint4 r[4] = {*reinterpret_cast<const uint4*>(row), *reinterpret_cast<const uint4*>(row + 256),
                                 *reinterpret_cast<const uint4*>(row + 512), *reinterpret_cast<const uint4*>(row + 768)};
-            const uint32_t sel_lo = 128u | (f << 8), sel_hi = sel_lo << 16;
+            const uint32_t sel_lo = __builtin_amdgcn_perm(k80, f2, s_lo[h]);
+            const uint32_t sel_hi = __builtin_amdgcn_perm(k80, f2, s_hi[h]);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const uint32_t v[4] = {r[q].x, r[q].y, r[q].z, r[q].w};
@@ -404,6 +409,14 @@ __device__ __forceinline__ uint32_t select_sse_rows(const uint32_t (&b2)[16], co
                 }
             }
         }
+    }
+    if (!kSeda && !kTwoStage) {
+        // largest Z, lowest DID on ties: keys Z << 5 | (31 - DID), largest wins
+        uint32_t best = 0;
+#pragma unroll
+        for (int d = 0; d < 32; d += 2)
+            best = max(best, max((z[d] << 5) | (uint32_t)(31 - d), (z[d + 1] << 5) | (uint32_t)(30 - d)));
+        return 31u - (best & 31u);
     }
     // ---- restrictions: rows of bytes, 0xFF = excluded
     uint32_t xa[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
