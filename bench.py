@@ -25,8 +25,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the headline kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the
 # same counter reads for a plain copy of known size (profiles/quantize_lut_kernel_cfg2_traffic.md): 98,380 KiB
-# read (counter x 1.99945) + 27,648 KiB written (counter x 1.0).
-MEASURED_TRAFFIC_BYTES = 129052608
+# read (counter x 1.99947) + 27,648 KiB written (counter x 1.0).
+MEASURED_TRAFFIC_BYTES = 129053436
 ROWS, COLS, BLOCK = 16384, 3072, 32
 N_SETS = 6
 SETTLE_S = 0.05   # untimed load before a timed graph replay
@@ -226,7 +226,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-            "kernel": "fb4::quantize_lut_kernel<32, 8, true, false, false, false>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
+            "kernel": "fb4::quantize_lut_kernel<32, 8, true, false, false, false, 512>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
         },
     }
 
