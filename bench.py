@@ -9,7 +9,8 @@ the 129 MB working set is streamed from HBM and not served by the 256 MB
 Infinity Cache.  Prints ONE JSON line.
 
 The other entry points (exhaustive selector, g = 32, SeDA, decomposition,
-dequantize) are timed the same way and reported under "extras".
+dequantize, MXFP8 repack) and the other workloads (cfg1, cfg5 activation and
+weight) are timed the same way and reported under "extras".
 """
 
 import argparse
@@ -313,6 +314,49 @@ def main():
             k = i % 3
             F.fb4_quantize(luts, o_main, big[k], codes=bc[k], meta=bm[k])
         add("quantize_lut_g8_65536x3072", big_step, 4 * abytes, 4 * n_el)
+        del big, bc, bm
+        # cfg1 (1024 x 3072: 8 MB per launch, bound by the launch, not by the memory) ...
+        x1 = synth.gaussian_outlier(rows=1024, cols=COLS, seed=1, device="cuda")
+        x1s = [x1] + [x1.clone() for _ in range(63)]          # 64 sets = 516 MB: not served from the cache
+        c1s = [torch.empty((1024, COLS // 2), dtype=torch.uint8, device="cuda") for _ in range(64)]
+        m1s = [torch.empty((1024, COLS // BLOCK), dtype=torch.int16, device="cuda") for _ in range(64)]
+
+        def cfg1_step(i):
+            k = i % 64
+            F.fb4_quantize(luts, o_main, x1s[k], codes=c1s[k], meta=m1s[k])
+        add("cfg1_quantize_lut_g8_1024x3072", cfg1_step, algorithmic_bytes(1024, COLS), 1024 * COLS, steps=128)
+        del x1s, c1s, m1s
+        # ... and cfg5: the 65536 x 12288 activation (online selector, both planes in one pass with 3276
+        # salient rows) and the 12288 x 3072 weight (exhaustive selector)
+        R5, C5 = synth.CONFIG_SHAPES["cfg5"]
+        x5 = synth.vdit_activation(rows=R5, cols=C5, seed=5, device="cuda", outlier_frac=0.01)
+        c5 = torch.empty((R5, C5 // 2), dtype=torch.uint8, device="cuda")
+        m5 = torch.empty((R5, C5 // BLOCK), dtype=torch.int16, device="cuda")
+
+        def cfg5_step(i):
+            F.fb4_quantize(luts, o_main, x5, codes=c5, meta=m5)
+        add("cfg5_quantize_lut_g8_65536x12288", cfg5_step, algorithmic_bytes(R5, C5), R5 * C5, steps=10)
+        sal5 = synth.salient_rows_from_attention(R5, frac=0.05, heads=24, seed=5, device="cuda", window=1024)
+        sal5_d = torch.from_numpy(sal5).cuda()
+        c52 = torch.empty((sal5.size, C5 // 2), dtype=torch.uint8, device="cuda")
+        m52 = torch.empty((sal5.size, C5 // BLOCK), dtype=torch.int16, device="cuda")
+
+        def cfg5_fused_step(i):
+            F.fb4_quantize_decompose(luts, o_main, x5, sal5_d, codes1=c5, meta1=m5, codes2=c52, meta2=m52)
+        add("cfg5_quantize_decompose_5pct_one_pass", cfg5_fused_step,
+            algorithmic_bytes(R5, C5) + sal5.size * (C5 // 2 + (C5 // BLOCK) * 2 + 4), R5 * C5, steps=10)
+        del x5, c5, m5, c52, m52
+        RW, CW = synth.CONFIG_SHAPES["cfg5_weight"]
+        w5 = synth.weight_matrix(rows=RW, cols=CW, seed=5, device="cuda")
+        w5s = [w5] + [w5.clone() for _ in range(7)]
+        cws = [torch.empty((RW, CW // 2), dtype=torch.uint8, device="cuda") for _ in range(8)]
+        mws = [torch.empty((RW, CW // BLOCK), dtype=torch.int16, device="cuda") for _ in range(8)]
+        o_sse = F.opts(selector=F.SEL_SSE)
+
+        def cfg5_weight_step(i):
+            k = i % 8
+            F.fb4_quantize(luts, o_sse, w5s[k], codes=cws[k], meta=mws[k])
+        add("cfg5_weight_quantize_sse_12288x3072", cfg5_weight_step, algorithmic_bytes(RW, CW), RW * CW, steps=16)
         result["extras"] = extras
 
     # ---- CPU oracle on the host cores of this machine (a baseline for context, not a target)
