@@ -695,7 +695,8 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     constexpr int kRowIt = (64 * kCopies + kThreads - 1) / kThreads;
     constexpr int kNibIt = (256 + kThreads - 1) / kThreads;
     constexpr int kSalEarly = 8;
-    uint4 rowv[kRowIt];
+    static_assert(kRowIt <= 2, "two row pieces per thread at most");
+    uint4 row_a, row_b = make_uint4(0, 0, 0, 0);   // (scalars, not an array: an array here ends up in scratch memory)
     uint32_t nibv[kNibIt], rngv = 0, decv = 0;
     uint4 magq = make_uint4(0, 0, 0, 0);
     uint2 sub0 = make_uint2(0, 0);
@@ -706,12 +707,13 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     {
         // Qerror rows in kCopies bank-disjoint copies: piece i = (bin, half, copy) is 16 bytes of row `bin`
         // (indices are clamped, not predicated: a thread past the end loads a piece it does not write)
-#pragma unroll
-        for (int k = 0; k < kRowIt; ++k) {
+        auto row_piece = [&](int k) {
             const int i = min((int)threadIdx.x + k * kThreads, 64 * kCopies - 1);
             const int bin = i / (2 * kCopies), half = (i / kCopies) & 1;
-            rowv[k] = *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
-        }
+            return *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
+        };
+        row_a = row_piece(0);
+        if (kRowIt > 1) row_b = row_piece(1);
 #pragma unroll
         for (int k = 0; k < kNibIt; ++k)
             nibv[k] = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[min((int)threadIdx.x + k * kThreads, 255)];
@@ -748,11 +750,9 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     cur = load_block<kFlat, kSeda>(p, t * 64u + lane);
     __builtin_amdgcn_sched_barrier(0);
     {
-#pragma unroll
-        for (int k = 0; k < kRowIt; ++k) {
-            const int i = threadIdx.x + k * kThreads;
-            if (i < 64 * kCopies) reinterpret_cast<uint4*>(lds + kLdsRows)[i] = rowv[k];
-        }
+        if ((int)threadIdx.x < 64 * kCopies) reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x] = row_a;
+        if (kRowIt > 1 && (int)threadIdx.x + kThreads < 64 * kCopies)
+            reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x + kThreads] = row_b;
 #pragma unroll
         for (int k = 0; k < kNibIt; ++k) {
             const int i = threadIdx.x + k * kThreads;
