@@ -114,12 +114,11 @@ __device__ __forceinline__ uint32_t vgpr_const(uint32_t v)
 }
 
 // LDS layout of the fast kernel (bytes)
-// Qerror rows in bank-disjoint copies, piece (bin, half, copy) = 16 bytes of row `bin`.  16 copies make every
-// row read conflict-free (an LDS pass serves 16 lanes) and pay where a lane reads 32 rows per tile (32 groups:
-// 36.1 -> 32.6 us on the 16384x3072 workload); with fewer rows 8 copies are as fast or faster (8 groups: 23.9
-// against 25.4 us with 16) and half the space stays unused.
-constexpr int kLdsRows = 0;              // [32 bins][2 halves][8 or 16 copies][16 B]  <= 16 KiB
-constexpr int row_copies(int block, int groups) { return groups * (32 / block) >= 32 ? 16 : 8; }
+// Qerror rows in 16 bank-disjoint copies, piece (bin, half, copy) = 16 bytes of row `bin`: an LDS pass serves
+// 16 lanes, and lane l reads copy l % 16, so a row read never conflicts whatever the lanes' bins (8 groups:
+// 23.85 -> 23.6 us on the 16384x3072 workload against 8 copies, 16 groups 25.4 -> 24.6, 32 groups 36.1 -> 31.5).
+constexpr int kRowCopies = 16;
+constexpr int kLdsRows = 0;              // [32 bins][2 halves][16 copies][16 B]  16 KiB
 constexpr int kLdsPair = 16384;          // [32 hi bins][32 lo bins][32 dialects] 32 KiB
 constexpr int kLdsNibT = 16384 + 32768;  // [32 bins][32 dialects]                1 KiB
 constexpr int kLdsRange = kLdsNibT + 1024;   // two-stage: [8 ranges][32 B] 0xFF = dialect excluded
@@ -237,7 +236,7 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
             s = 0xFFFFFu - z;
         } else {
 #pragma unroll
-            for (int j = 0; j < GG; ++j) s += lds[kLdsRows + gbin[j] * (32 * row_copies(kBlock, G)) + (d >> 4) * (16 * row_copies(kBlock, G)) + (d & 15)];
+            for (int j = 0; j < GG; ++j) s += lds[kLdsRows + gbin[j] * (32 * kRowCopies) + (d >> 4) * (16 * kRowCopies) + (d & 15)];
         }
         best = min(best, (s << 5) | d);
         if (two_stage && !lds[excl_b + d]) best_b = min(best_b, (s << 5) | d);
@@ -266,11 +265,11 @@ struct TileConsts {
     uint32_t gm_off;     // exhaustive selector: LDS offset of its table
 };
 
-__device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane, uint32_t gm_off, uint32_t copies)
+__device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane, uint32_t gm_off)
 {
     TileConsts K;
     K.gm_off = gm_off;
-    K.row_base = kLdsRows + (lane & (copies - 1u)) * 16u;
+    K.row_base = kLdsRows + (lane & (kRowCopies - 1u)) * 16u;
     K.k7f = sgpr_const(0x007F007Fu);
     K.k80 = vgpr_const(0x00800080u);
     K.kpair = sgpr_const(32u | (1024u << 16));   // lo bin * 32 + hi bin * 1024
@@ -286,7 +285,7 @@ __device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane, uint32_t g
 // excluded candidates, argmin with the lowest DID on ties.  Rows hold one byte per dialect; eight of them
 // (8 x 31 = 248) still fit the byte, so rows are summed eight at a time and widened to 16 bits in between.
 // excl_a: LDS offset of this block's SeDA exclusion row (kSeda only).
-template <int R, bool kTwoStage, bool kSeda, int kCopies>
+template <int R, bool kTwoStage, bool kSeda>
 __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], const uint8_t* lds,
                                                     const TileConsts& K, uint32_t excl_a)
 {
@@ -315,9 +314,9 @@ __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], c
         uint4 r0[8], r1[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const uint8_t* row = lds + K.row_base + gbin[8 * c + j] * (32u * kCopies);
+            const uint8_t* row = lds + K.row_base + gbin[8 * c + j] * (32u * kRowCopies);
             r0[j] = *reinterpret_cast<const uint4*>(row);
-            r1[j] = *reinterpret_cast<const uint4*>(row + 16 * kCopies);
+            r1[j] = *reinterpret_cast<const uint4*>(row + 16 * kRowCopies);
         }
         asm volatile("" ::: "memory");
 #pragma unroll
@@ -536,7 +535,7 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
                     else if (PER == 2) gbin[r] = halves_max(b2[b * RB + r]);
                     else gbin[r] = (r & 1) ? (b2[b * RB + r / 2] >> 16) : (b2[b * RB + r / 2] & 0xFFFFu);
                 }
-                did[b] = select_lut_rows<GG, kTwoStage, kSeda, row_copies(kBlock, GG)>(gbin, lds, K, excl_a);
+                did[b] = select_lut_rows<GG, kTwoStage, kSeda>(gbin, lds, K, excl_a);
             }
             meta |= (did[b] | (eb << 8)) << (16 * b);
         }
@@ -691,7 +690,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     // Loads are answered in the order they were issued.  The (small, mostly cached) table and list loads
     // therefore go out first and the first tile's right behind them: the tables are then built while the
     // tile is still on its way, instead of after it.
-    constexpr int kCopies = row_copies(kBlock, G == 0 ? 8 : G);
+    constexpr int kCopies = kRowCopies;
     constexpr int kRowIt = (64 * kCopies + kThreads - 1) / kThreads;
     constexpr int kNibIt = (256 + kThreads - 1) / kThreads;
     constexpr int kSalEarly = 8;
@@ -705,7 +704,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     int32_t sal_reg[kSalEarly];
     const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kThreads;
     {
-        // Qerror rows in kCopies bank-disjoint copies: piece i = (bin, half, copy) is 16 bytes of row `bin`
+        // Qerror rows in their bank-disjoint copies: piece i = (bin, half, copy) is 16 bytes of row `bin`
         // (indices are clamped, not predicated: a thread past the end loads a piece it does not write)
         auto row_piece = [&](int k) {
             const int i = min((int)threadIdx.x + k * kThreads, 64 * kCopies - 1);
@@ -877,7 +876,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         }
         __syncthreads();
     }
-    const TileConsts K = make_tile_consts(lane, kLdsGm, kCopies);
+    const TileConsts K = make_tile_consts(lane, kLdsGm);
 
     // Results of a tile are held in registers and written at the top of the next iteration, right after
     // that iteration's input has arrived: memory operations retire in issue order, so a store issued just
