@@ -345,6 +345,11 @@ def main():
             F.fb4_quantize_decompose(luts, o_main, x5, sal5_d, codes1=c5, meta1=m5, codes2=c52, meta2=m52)
         add("cfg5_quantize_decompose_5pct_one_pass", cfg5_fused_step,
             algorithmic_bytes(R5, C5) + sal5.size * (C5 // 2 + (C5 // BLOCK) * 2 + 4), R5 * C5, steps=10)
+
+        def cfg5_decomp_step(i):
+            F.fb4_decompose(luts, o_main, x5, c5, m5, sal5_d, codes2=c52, meta2=m52)
+        add("cfg5_decompose_5pct_lut_g8", cfg5_decomp_step,
+            sal5.size * (C5 * 2 + 2 * (C5 // 2 + (C5 // BLOCK) * 2) + 4), sal5.size * C5, steps=20)
         del x5, c5, m5, c52, m52
         RW, CW = synth.CONFIG_SHAPES["cfg5_weight"]
         w5 = synth.weight_matrix(rows=RW, cols=CW, seed=5, device="cuda")

@@ -103,7 +103,7 @@ int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& 
 // workload with 8 wavefronts each (SeDA: 25.7 against 27.2; 4, 12 or 16 wavefronts are slower too), and the
 // kernels are free to use up to 256 vector registers per lane.  The exhaustive selector, bound by the vector
 // ALU, runs 12 wavefronts (83 -> 74.5 us).
-template <int kBlock, int G, bool kFlat, bool kDecomp, int kThreads = kFastThreads>
+template <int kBlock, int G, bool kFlat, int kMode, int kThreads = kFastThreads>
 void launch_fast_variant(bool ts, bool seda, int n_cu, hipStream_t s, const FastParams& f)
 {
     constexpr int kWaves = kThreads / 64;
@@ -113,11 +113,11 @@ void launch_fast_variant(bool ts, bool seda, int n_cu, hipStream_t s, const Fast
     // (the leading arguments repeat fields of f: see the kernel)
 #define FB4_FAST_ARGS f.blob, f.x, f.n_blocks, f.n_tiles, f.div_mul, f.div_shift, f.nb, groups, f.row_stride, f.codes, f.meta, f
     if (seda) {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kDecomp, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kDecomp, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
     } else {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false, kDecomp, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false, kDecomp, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
     }
 #undef FB4_FAST_ARGS
 }
@@ -178,37 +178,85 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
     if (sse) {
         // the exhaustive selector: group count 0 in the kernel's template
         if (fused) {
-            if (opts->block == 32) launch_fast_variant<32, 0, false, true>(ts, seda, ng, s, f);
-            else launch_fast_variant<16, 0, false, true>(ts, seda, ng, s, f);
+            if (opts->block == 32) launch_fast_variant<32, 0, false, 1>(ts, seda, ng, s, f);
+            else launch_fast_variant<16, 0, false, 1>(ts, seda, ng, s, f);
         } else {
             // 12 wavefronts, unless the candidate lists would push the kernel past their 168 registers
             if (seda) {
-                if (opts->block == 32) launch_fast_variant<32, 0, false, false>(ts, seda, ng, s, f);
-                else launch_fast_variant<16, 0, false, false>(ts, seda, ng, s, f);
+                if (opts->block == 32) launch_fast_variant<32, 0, false, 0>(ts, seda, ng, s, f);
+                else launch_fast_variant<16, 0, false, 0>(ts, seda, ng, s, f);
             } else {
-                if (opts->block == 32) launch_fast_variant<32, 0, false, false, 768>(ts, seda, ng, s, f);
-                else launch_fast_variant<16, 0, false, false, 768>(ts, seda, ng, s, f);
+                if (opts->block == 32) launch_fast_variant<32, 0, false, 0, 768>(ts, seda, ng, s, f);
+                else launch_fast_variant<16, 0, false, 0, 768>(ts, seda, ng, s, f);
             }
         }
     } else if (fused) {
         if (opts->block == 32) {
-            if (flat) launch_fast_variant<32, 8, true, true>(ts, seda, ng, s, f);
-            else launch_fast_variant<32, 8, false, true>(ts, seda, ng, s, f);
+            if (flat) launch_fast_variant<32, 8, true, 1>(ts, seda, ng, s, f);
+            else launch_fast_variant<32, 8, false, 1>(ts, seda, ng, s, f);
         } else {
-            launch_fast_variant<16, 8, false, true>(ts, seda, ng, s, f);
+            launch_fast_variant<16, 8, false, 1>(ts, seda, ng, s, f);
         }
     } else if (opts->block == 32) {
         if (opts->num_groups == 8) {
-            if (flat) launch_fast_variant<32, 8, true, false>(ts, seda, ng, s, f);
-            else launch_fast_variant<32, 8, false, false>(ts, seda, ng, s, f);
+            if (flat) launch_fast_variant<32, 8, true, 0>(ts, seda, ng, s, f);
+            else launch_fast_variant<32, 8, false, 0>(ts, seda, ng, s, f);
         } else if (opts->num_groups == 16) {
-            launch_fast_variant<32, 16, false, false>(ts, seda, ng, s, f);
+            launch_fast_variant<32, 16, false, 0>(ts, seda, ng, s, f);
         } else {
-            launch_fast_variant<32, 32, false, false>(ts, seda, ng, s, f);
+            launch_fast_variant<32, 32, false, 0>(ts, seda, ng, s, f);
         }
     } else {
-        if (opts->num_groups == 8) launch_fast_variant<16, 8, false, false>(ts, seda, ng, s, f);
-        else launch_fast_variant<16, 16, false, false>(ts, seda, ng, s, f);
+        if (opts->num_groups == 8) launch_fast_variant<16, 8, false, 0>(ts, seda, ng, s, f);
+        else launch_fast_variant<16, 16, false, 0>(ts, seda, ng, s, f);
+    }
+    *rc = hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+    return true;
+}
+
+// The second plane of listed rows from x and a first plane in memory (fb4_decompose) in the streaming kernel:
+// the default online selector (8 groups) and the exhaustive one, when rows are whole 32-element chunks and
+// the planes are aligned for its wide loads and stores.  p.codes / p.meta are the second plane.
+bool launch_fast_second_plane(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& p, int64_t cols,
+                              int64_t n_sal, hipStream_t s, int* rc)
+{
+    const bool sse = opts->selector == FB4_SEL_SSE;
+    if ((cols % 32) || !aligned(p.codes, 16) || !aligned(p.codes1, 16) || (!sse && opts->num_groups != 8)) return false;
+    if (opts->block == 16 && (!aligned(p.meta, 4) || !aligned(p.meta1, 4))) return false;
+    const uint64_t nb = (uint64_t)cols / 32;
+    const uint64_t n_blocks = (uint64_t)n_sal * nb;
+    if (n_blocks >= 0x7FFFFF00ull || p.rows > 0x7FFFFFFFll) return false;
+    if (p.token_group && (uint32_t)p.n_groups > kMaxFastGroups) return false;
+    FastParams f = {};
+    f.x = p.x;
+    f.row_stride = p.row_stride;
+    f.nb = (uint32_t)nb;
+    f.n_blocks = (uint32_t)n_blocks;
+    f.n_tiles = (uint32_t)((n_blocks + 63) / 64);
+    uint32_t l = 0;
+    while ((1ull << l) < nb) ++l;
+    f.div_shift = 31 + l;
+    f.div_mul = (uint32_t)(((1ull << f.div_shift) + nb - 1) / nb);
+    f.codes = p.codes;
+    f.meta = p.meta;
+    f.blob = luts->dev_blob;
+    f.token_group = p.token_group;
+    f.sub = p.sub;
+    f.n_groups = (uint32_t)p.n_groups;
+    f.n_dialects = (uint32_t)luts->n_dialects;
+    f.salient = p.salient;
+    f.n_sal = (uint32_t)n_sal;
+    f.rows = (uint32_t)p.rows;
+    f.codes1 = p.codes1;
+    f.meta1 = p.meta1;
+    const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
+    const bool seda = p.token_group != nullptr;
+    if (sse) {
+        if (opts->block == 32) launch_fast_variant<32, 0, false, 2>(ts, seda, luts->n_cu, s, f);
+        else launch_fast_variant<16, 0, false, 2>(ts, seda, luts->n_cu, s, f);
+    } else {
+        if (opts->block == 32) launch_fast_variant<32, 8, false, 2>(ts, seda, luts->n_cu, s, f);
+        else launch_fast_variant<16, 8, false, 2>(ts, seda, luts->n_cu, s, f);
     }
     *rc = hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
     return true;
@@ -392,6 +440,7 @@ int fb4_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int
     p.salient = salient_rows;
     p.blob = luts->dev_blob;
     p.n_dialects = luts->n_dialects;
+    if (launch_fast_second_plane(luts, opts, p, cols, n_sal, static_cast<hipStream_t>(stream), &rc)) return rc;
     return launch_quant<kDecomp>(opts, grid_for(luts, p.n_tiles), static_cast<hipStream_t>(stream), p);
 }
 

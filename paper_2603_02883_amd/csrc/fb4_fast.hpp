@@ -57,6 +57,10 @@ struct FastParams {
     uint32_t rows;                // <= kMaxFusedRows
     uint8_t* codes2;              // [n_sal][nb * 16]
     uint16_t* meta2;              // [n_sal][nb * 32 / block]
+    // second plane only (mode 2): the first plane of the whole tensor; x is read at the rows `salient` lists and
+    // codes / meta are the compact second plane
+    const uint8_t* codes1;        // [rows][nb * 16]
+    const uint16_t* meta1;        // [rows][nb * 32 / block]
 };
 
 constexpr uint32_t kMaxFastGroups = 1023;   // SeDA groups whose exclusion rows fit the workgroup's LDS
@@ -570,32 +574,63 @@ __device__ __forceinline__ long long block_offset(const FastParams& p, uint32_t 
 struct Block64 {   // one block: 32 bf16 = four 16-byte loads, plus its row's SeDA group
     uint4 q0, q1, q2, q3;
     int32_t grp;
+    // second plane only: the block's first-plane code words and metadata, and its source row (-1: none)
+    uint4 c1;
+    uint32_t m1;
+    int32_t row;
 };
 
 // Requests block gb.  There is no branch: a lane past the end reads the last block (its result is never
 // stored, and data that a valid lane holds too cannot send the tile down another route), so that the loads
 // sit in straight-line code and the waits that follow can be counted exactly.
-template <bool kFlat, bool kSeda>
-__device__ __forceinline__ Block64 load_block(const FastParams& p, uint32_t gb)
+// kGather: gb counts the blocks of the compact second plane; `row` is the tensor row of gb's list entry (a
+// row outside the tensor reads row 0 and is marked).
+template <int kBlock, bool kFlat, bool kSeda, bool kGather>
+__device__ __forceinline__ Block64 load_block(const FastParams& p, uint32_t gb, int32_t row = 0)
 {
     Block64 b;
     const uint32_t gbc = min(gb, p.n_blocks - 1u);
+    b.grp = -1;
+    b.c1 = make_uint4(0, 0, 0, 0);
+    b.m1 = 0;
+    b.row = 0;
+    if (kGather) {
+        const uint32_t pos = (uint32_t)(((unsigned long long)gbc * p.div_mul) >> p.div_shift);
+        const uint32_t j = gbc - pos * p.nb;
+        const bool ok = (uint32_t)row < p.rows;
+        const size_t rowc = ok ? (size_t)row : 0;
+        b.row = ok ? row : -1;
+        const uint4* px = reinterpret_cast<const uint4*>(p.x + (long long)rowc * p.row_stride + (long long)j * 32);
+        b.q0 = px[0]; b.q1 = px[1]; b.q2 = px[2]; b.q3 = px[3];
+        const size_t blk = rowc * p.nb + j;
+        b.c1 = *reinterpret_cast<const uint4*>(p.codes1 + blk * 16);
+        b.m1 = kBlock == 16 ? reinterpret_cast<const uint32_t*>(p.meta1)[blk] : (uint32_t)p.meta1[blk];
+        if (kSeda) b.grp = p.token_group[rowc];
+        return b;
+    }
     const uint4* px = reinterpret_cast<const uint4*>(p.x + block_offset<kFlat>(p, gbc));
     b.q0 = px[0]; b.q1 = px[1]; b.q2 = px[2]; b.q3 = px[3];
-    b.grp = -1;
     if (kSeda) b.grp = p.token_group[(uint32_t)(((unsigned long long)gbc * p.div_mul) >> p.div_shift)];
     return b;
+}
+
+// Second plane only: the tensor row that block gb of the compact plane belongs to.
+__device__ __forceinline__ int32_t load_row(const FastParams& p, uint32_t gb)
+{
+    const uint32_t gbc = min(gb, p.n_blocks - 1u);
+    return p.salient[(uint32_t)(((unsigned long long)gbc * p.div_mul) >> p.div_shift)];
 }
 
 // Writes one tile's results: 16 bytes of codes per lane and the metadata words.  When the whole tile is in
 // range and the metadata array is 16-byte aligned, eight neighbouring lanes gather their 16-bit metadata
 // into one 16-byte store (sub-dword stores are slow to coalesce); block size 16 has one dword per lane.
+// lane_ok = false: this lane writes nothing (second plane only: its list entry names no row of the tensor).
 template <int kBlock>
 __device__ __forceinline__ void store_tile(const FastParams& p, uint32_t gb, uint32_t lane, const uint4& code,
-                                           uint32_t meta, bool meta_aligned)
+                                           uint32_t meta, bool meta_aligned, bool lane_ok = true)
 {
     const uint32_t tile_first = gb - lane;   // wave-uniform
-    if (meta_aligned && tile_first + 64u <= p.n_blocks) {
+    if (meta_aligned && tile_first + 64u <= p.n_blocks && __builtin_amdgcn_ballot_w64(!lane_ok) == 0) {
         // results are written once and not read again by this kernel: streaming (non-temporal) stores
         typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
         const u32x4s cv = {code.x, code.y, code.z, code.w};
@@ -612,7 +647,7 @@ __device__ __forceinline__ void store_tile(const FastParams& p, uint32_t gb, uin
             const u32x4s mv = {p2, q2, r0, r1};
             if ((lane & 7u) == 0u) __builtin_nontemporal_store(mv, reinterpret_cast<u32x4s*>(p.meta + gb));
         }
-    } else if (gb < p.n_blocks) {
+    } else if (gb < p.n_blocks && lane_ok) {
         *reinterpret_cast<uint4*>(p.codes + (size_t)gb * 16) = code;
         if (kBlock == 16) reinterpret_cast<uint32_t*>(p.meta)[gb] = meta;   // the launcher checks 4-byte alignment
         else p.meta[gb] = (uint16_t)meta;
@@ -662,7 +697,9 @@ __device__ __forceinline__ void residual32(const uint32_t (&w)[16], const uint32
 // the library is compiled so that up to 16 leading argument registers are filled by the dispatcher when the
 // wavefront starts (the rest of the arguments come by a load, half a microsecond later), and the table and
 // tile requests can then go out at once.
-template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda, bool kDecomp = false, int kThreads = kFastThreads>
+// kMode: 0 = the first plane, 1 = both planes in one pass (rows listed in p.salient get a second plane),
+// 2 = the second plane only, of the rows p.salient lists, from x and a first plane already in memory.
+template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda, int kMode = 0, int kThreads = kFastThreads>
 __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     const uint8_t* blob, const uint16_t* x, uint32_t n_blocks, uint32_t n_tiles, uint32_t div_mul, uint32_t div_shift,
     uint32_t nb, uint32_t n_workgroups, long long row_stride, uint8_t* codes, uint16_t* meta, FastParams p)
@@ -670,10 +707,13 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     p.blob = blob; p.x = x; p.n_blocks = n_blocks; p.n_tiles = n_tiles; p.div_mul = div_mul; p.div_shift = div_shift;
     p.nb = nb; p.row_stride = row_stride; p.codes = codes; p.meta = meta;
     constexpr int kWaves = kThreads / 64;
-    constexpr int kLdsSeda = lds_seda_offset(kDecomp);
+    constexpr bool kDecomp = kMode == 1, kGather = kMode == 2;
+    constexpr bool kRes = kMode != 0;   // residuals are formed: decode tables needed
+    static_assert(!(kGather && kFlat), "gathered rows are addressed through their row stride");
+    constexpr int kLdsSeda = lds_seda_offset(kRes);
     constexpr bool kSse = G == 0;   // the exhaustive selector
-    constexpr int kLdsGm = lds_gm_offset(kSeda, kDecomp);
-    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kDecomp, kSse)];
+    constexpr int kLdsGm = lds_gm_offset(kSeda, kRes);
+    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kRes, kSse)];
     __shared__ uint32_t sal_before;      // fused decomposition: list entries below row 0
     __shared__ uint32_t sal_wave[kWaves];
     const uint32_t lane = threadIdx.x & 63;
@@ -717,9 +757,11 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         for (int k = 0; k < kNibIt; ++k)
             nibv[k] = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[min((int)threadIdx.x + k * kThreads, 255)];
         if (kTwoStage) rngv = reinterpret_cast<const uint32_t*>(p.blob + kOffRangeExcl)[threadIdx.x & 63u];
-        if (kDecomp) {
+        if (kRes) {
             decv = reinterpret_cast<const uint32_t*>(p.blob + kOffDecode)[threadIdx.x & 127u];
             magq = *reinterpret_cast<const uint4*>(p.blob + kOffDecode + (threadIdx.x & 31u) * 16);
+        }
+        if (kDecomp) {
             // a short salient list is requested now and used after the pair table; a long one is read in a
             // loop later
             if (sal_early) {
@@ -746,7 +788,14 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         }
     }
     __builtin_amdgcn_sched_barrier(0);
-    cur = load_block<kFlat, kSeda>(p, t * 64u + lane);
+    int32_t row_next = 0;   // second plane only: source row of this lane's block in the tile after `cur`
+    if (kGather) {
+        const int32_t row0 = load_row(p, t * 64u + lane);
+        row_next = load_row(p, t_next * 64u + lane);
+        cur = load_block<kBlock, kFlat, kSeda, kGather>(p, t * 64u + lane, row0);
+    } else {
+        cur = load_block<kBlock, kFlat, kSeda, kGather>(p, t * 64u + lane);
+    }
     __builtin_amdgcn_sched_barrier(0);
     {
         if ((int)threadIdx.x < 64 * kCopies) reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x] = row_a;
@@ -779,7 +828,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
                 }
             }
         }
-        if (kDecomp) {
+        if (kRes) {
             if (threadIdx.x < 128) reinterpret_cast<uint32_t*>(lds + kLdsDecode)[threadIdx.x] = decv;
             if (threadIdx.x < 32) {
                 // the dialect's eight magnitudes (integers 0..15 stored as bf16 patterns) as nibbles
@@ -792,6 +841,8 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
                 }
                 reinterpret_cast<uint32_t*>(lds + kLdsMagNib)[threadIdx.x] = mw;
             }
+        }
+        if (kDecomp) {
             for (uint32_t i = threadIdx.x; i < kMaxFusedRows / 32; i += kThreads)
                 reinterpret_cast<uint32_t*>(lds + kLdsSalBits)[i] = 0;
             if (threadIdx.x == 0) sal_before = 0;
@@ -884,6 +935,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     uint4 held_code = make_uint4(0, 0, 0, 0);
     uint32_t held_meta = 0, held_gb = 0;
     bool have_held = false;   // wave-uniform
+    bool held_ok = true;      // second plane only: this lane's list entry names a row of the tensor
     // second plane of a salient tile: held the same way
     uint4 held2_code = make_uint4(0, 0, 0, 0);
     uint32_t held2_meta = 0;
@@ -914,21 +966,43 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         // row's SeDA group (the last load of the tile) is consumed here too: left to the compiler, the wait
         // for it lands behind the next tile's loads and waits for those as well.
         int32_t grp = kSeda ? cur.grp : -1;
+        // (second plane only: the first plane's words and the rows of the next tile arrive with the tile too)
+        uint32_t c1m1[5] = {cur.c1.x, cur.c1.y, cur.c1.z, cur.c1.w, cur.m1};
+        const int32_t row = cur.row;
+        if (kGather)
+            asm volatile("" : "+v"(row_next), "+v"(c1m1[0]), "+v"(c1m1[1]), "+v"(c1m1[2]), "+v"(c1m1[3]), "+v"(c1m1[4]));
         asm volatile("" : "+v"(held_meta), "+v"(grp) : "v"(w[0]), "v"(w[15]));
         const uint32_t excl_a = kLdsSeda + 32u * ((grp >= 0 && (uint32_t)grp < p.n_groups) ? (uint32_t)grp : p.n_groups);
-        if (have_held) store_tile<kBlock>(p, held_gb, lane, held_code, held_meta, meta_aligned);
+        if (have_held) store_tile<kBlock>(p, held_gb, lane, held_code, held_meta, meta_aligned, held_ok);
         have_held = true;
         if (kDecomp && held2_any) store_plane2();
         held2_any = false;
         // the next tile's loads go out before this tile's arithmetic
-        cur = load_block<kFlat, kSeda>(p, t_next * 64u + lane);
+        cur = load_block<kBlock, kFlat, kSeda, kGather>(p, t_next * 64u + lane, row_next);
         uint32_t claim = 0;
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
         const uint32_t t_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
+        if (kGather) row_next = load_row(p, t_after * 64u + lane);
         uint32_t code[4], meta;
+        bool tile_special;
+        if (kGather) {
+            // Sec. 3.3: residual of the first plane (exact, rounded once to bf16), then the same routine on it
+            const bool ok = gb < p.n_blocks && row >= 0;
+            const uint32_t gbc = min(gb, p.n_blocks - 1u);
+            const uint32_t pos = (uint32_t)(((unsigned long long)gbc * p.div_mul) >> p.div_shift);
+            const uint16_t* xb = p.x + (long long)(ok ? row : 0) * p.row_stride + (long long)(gbc - pos * p.nb) * 32;
+            const uint32_t code1[4] = {c1m1[0], c1m1[1], c1m1[2], c1m1[3]};
+            uint32_t w2[16];
+            residual32<kBlock>(w, code1, c1m1[4], lds, true, w2);
+            // a lane without a row runs the arithmetic on zeros and stores nothing
+#pragma unroll
+            for (int k = 0; k < 16; ++k) w2[k] = ok ? w2[k] : 0u;
+            compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, ok, excl_a, code, meta, code1, c1m1[4],
+                                                            tile_special);
+            held_ok = ok;
+        } else {
         const uint16_t* xb = p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u);
         const uint32_t no_code[4] = {0, 0, 0, 0};
-        bool tile_special;
         compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
                                                   tile_special);
         if (kDecomp) {
@@ -957,13 +1031,14 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
                 held2_meta = meta2;
             }
         }
+        }
         held_code = make_uint4(code[0], code[1], code[2], code[3]);
         held_meta = meta;
         held_gb = gb;
         t = t_next;
         t_next = t_after;
     }
-    if (have_held) store_tile<kBlock>(p, held_gb, lane, held_code, held_meta, meta_aligned);
+    if (have_held) store_tile<kBlock>(p, held_gb, lane, held_code, held_meta, meta_aligned, held_ok);
     if (kDecomp && held2_any) store_plane2();
 }
 
