@@ -1,5 +1,9 @@
-// Streaming kernel for the paper's online selector (Sec. 3.2: Qerror summed
-// over group-wise maxima; default 8 groups, all dialects, block 32).
+// Streaming kernel for both selectors of Sec. 3.2: the paper's online rule (Qerror
+// summed over group-wise maxima; default 8 groups, all dialects, block 32) and
+// the exhaustive squared-error search (group count 0 in the template), with
+// the two-stage filter, SeDA candidate lists (Sec. 3.4) and the second plane
+// of the activation decomposition (Sec. 3.3): in one pass with the first
+// plane, or alone from a first plane already in memory.
 //
 // One lane owns 32 consecutive elements of a row -- one block of 32 or two
 // blocks of 16: it loads the 64 bytes with four 16-byte loads, keeps the
@@ -11,11 +15,13 @@
 // count these 32-element pieces.
 //
 // LDS tables, built once per workgroup:
-//   * Qerror rows (32 bytes per bin, one byte per dialect), eight copies laid
-//     out so that lane l always reads banks 4*(l%8)..4*(l%8)+3: the 16-byte row
-//     reads of a wavefront never collide whatever bins the lanes ask for;
+//   * Qerror rows (32 bytes per bin, one byte per dialect) in 16 copies laid
+//     out so that lane l always reads banks 4*(l%16)..4*(l%16)+3: the 16-byte
+//     row reads of a wavefront never collide whatever bins the lanes ask for;
 //   * a pair table: (bin of element 2m, bin of element 2m+1, dialect) -> the
-//     finished code byte without sign bits, so one lookup emits two elements.
+//     finished code byte without sign bits, so one lookup emits two elements;
+//   * exhaustive selector: per bin the (gain, magnitude) byte pairs of the 32
+//     dialects, in 16 copies the same way.
 //
 // A block whose largest magnitude is NaN/Inf-sized or below 2^-122 (and not
 // zero) leaves the packed path: the wavefront then redoes its tile with a
@@ -1001,36 +1007,36 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
                                                             tile_special);
             held_ok = ok;
         } else {
-        const uint16_t* xb = p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u);
-        const uint32_t no_code[4] = {0, 0, 0, 0};
-        compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
-                                                  tile_special);
-        if (kDecomp) {
-            // second plane of the salient rows, from the registers that still hold the tile
-            const uint32_t gbc = gb < p.n_blocks ? gb : 0u;
-            const uint32_t row = (uint32_t)(((unsigned long long)gbc * p.div_mul) >> p.div_shift);
-            const bool sal = gb < p.n_blocks &&
-                             ((reinterpret_cast<const uint32_t*>(lds + kLdsSalBits)[row >> 5] >> (row & 31)) & 1u);
-            if (__builtin_amdgcn_ballot_w64(sal) != 0) {
-                // position of the row in the salient list
-                const uint32_t wbits = reinterpret_cast<const uint32_t*>(lds + kLdsSalBits)[row >> 5];
-                const uint32_t lo = reinterpret_cast<const uint16_t*>(lds + kLdsSalRank)[row >> 5] +
-                                    __builtin_popcount(wbits & ((1u << (row & 31)) - 1u));
-                uint32_t w2[16], code2[4], meta2;
-                residual32<kBlock>(w, code, meta, lds, tile_special, w2);
-                // a lane that is not salient runs the arithmetic on zeros and stores nothing
+            const uint16_t* xb = p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u);
+            const uint32_t no_code[4] = {0, 0, 0, 0};
+            compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
+                                                      tile_special);
+            if (kDecomp) {
+                // second plane of the salient rows, from the registers that still hold the tile
+                const uint32_t gbc = gb < p.n_blocks ? gb : 0u;
+                const uint32_t row = (uint32_t)(((unsigned long long)gbc * p.div_mul) >> p.div_shift);
+                const bool sal = gb < p.n_blocks &&
+                                 ((reinterpret_cast<const uint32_t*>(lds + kLdsSalBits)[row >> 5] >> (row & 31)) & 1u);
+                if (__builtin_amdgcn_ballot_w64(sal) != 0) {
+                    // position of the row in the salient list
+                    const uint32_t wbits = reinterpret_cast<const uint32_t*>(lds + kLdsSalBits)[row >> 5];
+                    const uint32_t lo = reinterpret_cast<const uint16_t*>(lds + kLdsSalRank)[row >> 5] +
+                                        __builtin_popcount(wbits & ((1u << (row & 31)) - 1u));
+                    uint32_t w2[16], code2[4], meta2;
+                    residual32<kBlock>(w, code, meta, lds, tile_special, w2);
+                    // a lane that is not salient runs the arithmetic on zeros and stores nothing
 #pragma unroll
-                for (int k = 0; k < 16; ++k) w2[k] = sal ? w2[k] : 0u;
-                bool special2;
-                compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, sal, excl_a, code2, meta2, code, meta,
-                                                                special2);
-                held2_any = true;
-                held2_lane = sal;
-                held2_ob = (size_t)lo * p.nb + (gb - row * p.nb);
-                held2_code = make_uint4(code2[0], code2[1], code2[2], code2[3]);
-                held2_meta = meta2;
+                    for (int k = 0; k < 16; ++k) w2[k] = sal ? w2[k] : 0u;
+                    bool special2;
+                    compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, sal, excl_a, code2, meta2, code, meta,
+                                                                    special2);
+                    held2_any = true;
+                    held2_lane = sal;
+                    held2_ob = (size_t)lo * p.nb + (gb - row * p.nb);
+                    held2_code = make_uint4(code2[0], code2[1], code2[2], code2[3]);
+                    held2_meta = meta2;
+                }
             }
-        }
         }
         held_code = make_uint4(code[0], code[1], code[2], code[3]);
         held_meta = meta;
