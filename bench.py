@@ -227,7 +227,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-            "kernel": "fb4::quantize_lut_kernel<32, 8, true, false, false, false, 512>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
+            "kernel": "fb4::quantize_lut_kernel<32, 8, true, false, false, 0, 512>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
         },
     }
 
