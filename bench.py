@@ -25,9 +25,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the headline kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the
-# same counter reads for a plain copy of known size (profiles/quantize_lut_kernel_cfg2_traffic.md): 98,380 KiB
-# read (counter x 1.99947) + 27,648 KiB written (counter x 1.0).
-MEASURED_TRAFFIC_BYTES = 129053436
+# same counter reads for a plain copy of known size (profiles/quantize_lut_kernel_cfg2_traffic.md): 98,371 KiB
+# read (counter x 1.99927) + 27,648 KiB written (counter x 1.0).
+MEASURED_TRAFFIC_BYTES = 129043141
 ROWS, COLS, BLOCK = 16384, 3072, 32
 N_SETS = 6
 SETTLE_S = 0.05   # untimed load before a timed graph replay
