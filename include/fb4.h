@@ -181,8 +181,8 @@ int fb4_decompose(const fb4_luts* luts, const fb4_opts* opts, const void* x, int
  * Sec. 3.1-3.4 in one pass: fb4_quantize (or fb4_quantize_seda when
  * token_group is given) followed by fb4_decompose of the salient rows with the
  * same options and SeDA lists, with identical results.  When the request fits
- * the streaming kernel (FB4_SEL_LUT with 8 groups, rows <= 65536, cols a
- * multiple of 32, 16-byte aligned code planes) x is read once and
+ * the streaming kernel (FB4_SEL_LUT with 8 groups or FB4_SEL_SSE, rows <=
+ * 65536, cols a multiple of 32, 16-byte aligned code planes) x is read once and
  * the residual is formed from registers; otherwise the two kernels run one after
  * the other on `stream`.
  *   token_group, sub_formatbooks, n_groups   NULL, NULL, 0 for the full formatbook

@@ -130,10 +130,11 @@ struct FusedPlane {
     uint16_t* meta2;
 };
 
-// The streaming kernel serves the paper's online selector (LUT, any supported block size and group count),
+// The streaming kernel serves both selectors (the online one with any supported block size and group count),
 // with or without the two-stage filter and SeDA lists, when rows are whole 32-element chunks and the outputs
-// are aligned for its wide stores; with `fused` it also writes the second plane of the salient rows (8 groups,
-// row and list counts that fit its LDS).  Returns false if the request is not one it serves.
+// are aligned for its wide stores; with `fused` it also writes the second plane of the salient rows (online
+// selector: 8 groups; row and list counts that fit its LDS).  Returns false if the request is not one it
+// serves.
 bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& p, int64_t cols,
                  const int32_t* token_group, const uint8_t* sub, int n_groups, const FusedPlane* fused,
                  hipStream_t s, int* rc)
