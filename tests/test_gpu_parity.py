@@ -544,7 +544,8 @@ def test_quantize_decompose_in_one_pass(F, luts, block):
         c2r, m2r = O.decompose(fbk, xe, c1r, m1r, sal, block=block, flags=flags)
         compare_quant(fbk, xe, host_u8(c1), host_u16(m1), c1r, m1r, 1, 8, flags=flags, block=block, what="fused edge 1")
         assert np.array_equal(host_u8(c2), c2r) and np.array_equal(host_u16(m2), m2r)
-    # requests the one-pass kernel does not serve run the two kernels: other selectors, too many rows
+    # the exhaustive selector in one pass, and requests the one-pass kernel does not serve (16 groups, too many
+    # rows), which run the two kernels
     x = synth.gaussian_outlier(rows=64, cols=512, seed=56, device="cuda")
     sal_d = torch.arange(0, 64, 5, dtype=torch.int32, device="cuda")
     for o in (F.opts(block=block, selector=F.SEL_SSE), F.opts(block=block, num_groups=16)):
