@@ -506,6 +506,18 @@ def test_quantize_decompose_in_one_pass(F, luts, block):
     assert np.array_equal(host_u8(c2), c2r) and np.array_equal(host_u16(m2), m2r)
     s1, t1, s2, t2 = _both_planes_separately(F, luts, o, x, sal_d)
     assert torch.equal(c1, s1) and torch.equal(m1, t1) and torch.equal(c2, s2) and torch.equal(m2, t2)
+    # the exhaustive selector in one pass, against the oracle (first 2048 rows of the same tensor)
+    xs, xsb = x[:2048], xb[:2048]
+    sal_s = sal[sal < 2048]
+    o = F.opts(block=block, selector=F.SEL_SSE)
+    c1, m1, c2, m2 = F.fb4_quantize_decompose(luts, o, xs, torch.from_numpy(sal_s).cuda())
+    torch.cuda.synchronize()
+    c1r, m1r = O.quantize(fbk, xsb, block=block, selector=O.SEL_SSE)
+    compare_quant(fbk, xsb, host_u8(c1), host_u16(m1), c1r, m1r, 0, 8, block=block, what="one pass, exhaustive")
+    c2r, m2r = O.decompose(fbk, xsb[sal_s], host_u8(c1)[sal_s], host_u16(m1)[sal_s],
+                           np.arange(sal_s.size, dtype=np.int32), block=block, selector=O.SEL_SSE)
+    compare_quant(fbk, xsb[sal_s], host_u8(c2), host_u16(m2), c2r, m2r, 0, 8, block=block,
+                  what="one pass, exhaustive, plane 2")
     # variants: two-stage, SeDA, row stride, list entries outside the tensor, no salient row at all
     xm, comp = synth.mixture_activation(rows=300, cols=32 * 21 + 8, seed=55, device="cuda", n_components=5)
     xs = xm[:, :32 * 21]
