@@ -266,6 +266,16 @@ def main():
             k = i % N_SETS
             F.fb4_quantize_seda(luts, o_main, xms[k], tg, sub, codes=codes[k], meta=metas[k])
         add("quantize_seda_lut_g8", seda_step, abytes + ROWS * 4, n_el)
+        # SeDA bookkeeping (Sec. 3.4): dialect counts of the anchor rows (every tenth row here) per group and
+        # the eight-dialect sub-formatbooks from them; reads the metadata of the anchor rows only
+        anchors = torch.from_numpy(np.where(np.arange(ROWS) % 10 == 0, comp, -1).astype(np.int32)).cuda()
+        counts = torch.zeros((64, 32), dtype=torch.int32, device="cuda")
+        subs = torch.zeros((64, 8), dtype=torch.uint8, device="cuda")
+
+        def profile_step(i):
+            F.fb4_seda_profile(luts, metas[i % N_SETS], anchors, 64, counts=counts, sub_formatbooks=subs)
+        add("seda_profile_10pct_anchor_rows", profile_step, ROWS * 4 + (ROWS // 10) * (COLS // BLOCK) * 2,
+            (ROWS // 10) * COLS)
         # decomposition (cfg3): 5 % salient rows
         sal = synth.salient_rows_from_attention(ROWS, frac=0.05, heads=24, seed=3, device="cuda")
         sal_d = torch.from_numpy(sal).cuda()
