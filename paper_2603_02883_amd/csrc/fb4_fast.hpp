@@ -700,8 +700,8 @@ __device__ __forceinline__ void residual32(const uint32_t (&w)[16], const uint32
 }
 
 // The leading scalar arguments repeat the fields of `p` that the first loads and the loop bound depend on:
-// the library is compiled so that up to 16 leading argument registers are filled by the dispatcher when the
-// wavefront starts (the rest of the arguments come by a load, half a microsecond later), and the table and
+// the library is compiled so that the leading argument registers (14 of them on this target, all but `meta`
+// here) are filled by the dispatcher when the wavefront starts (the rest of the arguments come by a load, half a microsecond later), and the table and
 // tile requests can then go out at once.
 // kMode: 0 = the first plane, 1 = both planes in one pass (rows listed in p.salient get a second plane),
 // 2 = the second plane only, of the rows p.salient lists, from x and a first plane already in memory.
