@@ -111,7 +111,7 @@ void launch_fast_variant(bool ts, bool seda, int n_cu, hipStream_t s, const Fast
     if (g > n_cu) g = n_cu;
     const unsigned groups = (unsigned)g;
     // (the leading arguments repeat fields of f: see the kernel)
-#define FB4_FAST_ARGS f.blob, f.x, f.n_blocks, f.n_tiles, f.div_mul, f.div_shift, f.nb, groups, f.row_stride, f.codes, f.meta, f
+#define FB4_FAST_ARGS f.blob, f.x, f.n_blocks, f.n_tiles, f.div_mul, f.div_shift, f.nb, groups, f.row_stride, f.salient, f
     if (seda) {
         if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
         else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);

@@ -700,18 +700,18 @@ __device__ __forceinline__ void residual32(const uint32_t (&w)[16], const uint32
 }
 
 // The leading scalar arguments repeat the fields of `p` that the first loads and the loop bound depend on:
-// the library is compiled so that the leading argument registers (14 of them on this target, all but `meta`
-// here) are filled by the dispatcher when the wavefront starts (the rest of the arguments come by a load, half a microsecond later), and the table and
+// the library is compiled so that the leading argument registers (14 of them on this target: all of these)
+// are filled by the dispatcher when the wavefront starts (the rest of the arguments come by a load, half a microsecond later), and the table and
 // tile requests can then go out at once.
 // kMode: 0 = the first plane, 1 = both planes in one pass (rows listed in p.salient get a second plane),
 // 2 = the second plane only, of the rows p.salient lists, from x and a first plane already in memory.
 template <int kBlock, int G, bool kFlat, bool kTwoStage, bool kSeda, int kMode = 0, int kThreads = kFastThreads>
 __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     const uint8_t* blob, const uint16_t* x, uint32_t n_blocks, uint32_t n_tiles, uint32_t div_mul, uint32_t div_shift,
-    uint32_t nb, uint32_t n_workgroups, long long row_stride, uint8_t* codes, uint16_t* meta, FastParams p)
+    uint32_t nb, uint32_t n_workgroups, long long row_stride, const int32_t* salient, FastParams p)
 {
     p.blob = blob; p.x = x; p.n_blocks = n_blocks; p.n_tiles = n_tiles; p.div_mul = div_mul; p.div_shift = div_shift;
-    p.nb = nb; p.row_stride = row_stride; p.codes = codes; p.meta = meta;
+    p.nb = nb; p.row_stride = row_stride; p.salient = salient;
     constexpr int kWaves = kThreads / 64;
     constexpr bool kDecomp = kMode == 1, kGather = kMode == 2;
     constexpr bool kRes = kMode != 0;   // residuals are formed: decode tables needed
