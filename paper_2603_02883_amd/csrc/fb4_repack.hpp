@@ -10,9 +10,9 @@
 // difference k and rounded to E4M3 (exact for k <= 9).
 //
 // One lane re-encodes one code word (8 elements) into 8 bytes, so a wavefront
-// reads 256 and writes 512 contiguous bytes.  LDS tables: (DID, code byte) ->
-// the two finished E4M3 bytes for k = 0, and (k, magnitude) -> E4M3 byte for
-// the shifted block of a block-16 pair.
+// reads 256 and writes 512 contiguous bytes.  LDS tables: block 32: (DID, code
+// byte) -> the two finished E4M3 bytes; block 16: (DID, code byte) -> the two
+// magnitudes, then (k, magnitude pair) -> their two E4M3 bytes after the shift.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -60,7 +60,11 @@ __global__ __launch_bounds__(kRepackThreads) void repack_mxfp8_kernel(
     RepackParams p)
 {
     p.blob = blob; p.codes = codes; p.meta = meta; p.n_chunks = n_chunks;
-    __shared__ __align__(16) uint16_t pair[32 * 256];   // [DID][code byte] -> E4M3 of element 2j | element 2j+1 << 8
+    // block 32: [DID][code byte] -> E4M3 of element 2j | element 2j+1 << 8 (no signs).  Block 16, two steps
+    // because the shift k varies: magP [DID][code byte] -> the two magnitudes as nibbles, then
+    // shP [k][magnitude pair] -> their two E4M3 bytes.
+    __shared__ __align__(16) uint16_t pair[kB16 ? 16 * 256 : 32 * 256];   // block 16: shP
+    __shared__ uint8_t magP[kB16 ? 32 * 256 : 4];
     __shared__ uint8_t magT[32 * 8];                     // [DID][index] -> integer magnitude
     __shared__ uint8_t shT[16 * 16];                     // [k][magnitude] -> E4M3 byte of magnitude * 2^-k
     const uint32_t n_words = p.n_chunks * 4u;
@@ -90,7 +94,16 @@ __global__ __launch_bounds__(kRepackThreads) void repack_mxfp8_kernel(
         shT[threadIdx.x] = (uint8_t)e4m3_of_shifted(threadIdx.x & 15u, threadIdx.x >> 4);
     }
     __syncthreads();
-    {
+    if (kB16) {
+        for (uint32_t i = threadIdx.x; i < 32u * 256u; i += kRepackThreads) {
+            const uint32_t did = i >> 8, cb = i & 255u;
+            magP[i] = (uint8_t)(magT[did * 8 + (cb & 7u)] | (magT[did * 8 + ((cb >> 4) & 7u)] << 4));
+        }
+        for (uint32_t i = threadIdx.x; i < 16u * 256u; i += kRepackThreads) {
+            const uint32_t k = i >> 8, mp = i & 255u;
+            pair[i] = (uint16_t)(shT[k * 16 + (mp & 15u)] | (shT[k * 16 + (mp >> 4)] << 8));
+        }
+    } else {
         const uint32_t did = threadIdx.x >> 4, hn = threadIdx.x & 15;
         const uint32_t hi = (uint32_t)shT[magT[did * 8 + (hn & 7u)]] | ((hn & 8u) << 4);
 #pragma unroll
@@ -121,20 +134,23 @@ __global__ __launch_bounds__(kRepackThreads) void repack_mxfp8_kernel(
         const bool live = did < 32u;                 // a DID outside the table decodes as zeros
         const uint32_t d = live ? did : 0u;
         uint32_t o0 = 0, o1 = 0;
-        if (!kB16 || k == 0) {
+        if (!kB16) {
             const uint32_t base = d * 256u;
             const uint32_t v0 = pair[base + (cw & 0xFFu)], v1 = pair[base + ((cw >> 8) & 0xFFu)];
             const uint32_t v2 = pair[base + ((cw >> 16) & 0xFFu)], v3 = pair[base + (cw >> 24)];
             o0 = v0 | (v1 << 16);
             o1 = v2 | (v3 << 16);
         } else {
+            // magnitudes of the byte's two elements, then their E4M3 bytes after the shift by k; sign bits
+            // (bit 3 and bit 7 of a code byte) go to bit 7 of either output byte
+            uint32_t v[4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t nib = (cw >> (4 * e)) & 0xFu;
-                const uint32_t b = (uint32_t)shT[k * 16u + magT[d * 8u + (nib & 7u)]] | ((nib & 8u) << 4);
-                if (e < 4) o0 |= b << (8 * e);
-                else o1 |= b << (8 * (e - 4));
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t cb = (cw >> (8 * j)) & 0xFFu;
+                v[j] = (uint32_t)pair[k * 256u + magP[d * 256u + cb]] | ((cb & 0x08u) << 4) | ((cb & 0x80u) << 8);
             }
+            o0 = v[0] | (v[1] << 16);
+            o1 = v[2] | (v[3] << 16);
         }
         if (!live) {
             // keep the sign bits, drop the magnitudes
