@@ -145,7 +145,8 @@ def main():
                          "dialect, and what the difference costs in squared error, on the five workloads")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for `rocprofv3 --pmc ...`: a few plain device copies of known size, then a few "
-                         "launches of the headline kernel and of the exhaustive selector; prints a marker line")
+                         "launches of the headline kernel, of the exhaustive selector and of the other streaming "
+                         "kernels; prints a marker line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -187,6 +188,21 @@ def main():
         o_sse = F.opts(block=BLOCK, selector=F.SEL_SSE)
         for i in range(4):
             F.fb4_quantize(luts, o_sse, xs[i % N_SETS], codes=codes[i % N_SETS], meta=metas[i % N_SETS])
+        # the other streaming kernels: both planes in one pass, the second plane alone, decode, repack
+        sal_d = torch.from_numpy(synth.salient_rows_from_attention(ROWS, frac=0.05, heads=24, seed=3,
+                                                                   device="cuda")).cuda()
+        c2 = torch.empty((sal_d.numel(), COLS // 2), dtype=torch.uint8, device="cuda")
+        m2 = torch.empty((sal_d.numel(), COLS // BLOCK), dtype=torch.int16, device="cuda")
+        outs = [torch.empty((ROWS, COLS), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+        els = [torch.empty((ROWS, COLS), dtype=torch.uint8, device="cuda") for _ in range(2)]
+        scs = [torch.empty((ROWS, COLS // 32), dtype=torch.uint8, device="cuda") for _ in range(2)]
+        for i in range(4):
+            k = i % N_SETS
+            F.fb4_quantize_decompose(luts, o, xs[k], sal_d, codes1=codes[k], meta1=metas[k], codes2=c2, meta2=m2)
+            F.fb4_decompose(luts, o, xs[k], codes[k], metas[k], sal_d, codes2=c2, meta2=m2)
+            F.fb4_dequantize(luts, codes[k], metas[k], out=outs[i % 2])
+            F.fb4_dequantize(luts, codes[k], metas[k], codes2=c2, meta2=m2, salient_rows=sal_d, out=outs[i % 2])
+            F.fb4_repack_mxfp8(luts, codes[k], metas[k], elems=els[i % 2], scales=scs[i % 2])
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": True, "copy_bytes_read": x0.numel() * 2, "copy_bytes_written": x0.numel() * 2,
                           "quantize_algorithmic_bytes": abytes}))
