@@ -735,8 +735,12 @@ def test_entry_points_replay_correctly_from_a_hip_graph(F, luts):
         F.fb4_repack_mxfp8(luts, c1, m1, elems=el, scales=sc)
         F.fb4_seda_profile(luts, m1, anchors, 4, counts=counts, sub_formatbooks=sub)
         F.fb4_quantize_seda(luts, o, x, tg, sub, codes=cs, meta=ms)
+        F.fb4_decompose(luts, o, x, c1, m1, sal, codes2=c2b, meta2=m2b)
+        F.fb4_quantize(luts, o_sse, x, codes=c3, meta=m3)
 
-    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms)
+    c2b, m2b, c3, m3 = torch.empty_like(c2), torch.empty_like(m2), torch.empty_like(c1), torch.empty_like(m1)
+    o_sse = F.opts(selector=F.SEL_SSE)
+    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms, c2b, m2b, c3, m3)
     x.copy_(synth.vdit_activation(rows=rows, cols=cols, seed=70, device="cuda"))
     sequence()                                                # warm-up outside the capture
     torch.cuda.synchronize()
