@@ -135,6 +135,16 @@ def seda_sub_formatbooks(formatbook, n_groups=64, seed=4):
     return sub
 
 
+def layernorm_affine(cols=3072, seed=6):
+    """Per-channel scale and shift of a LayerNorm in front of a quantized linear layer (in a DiT block the
+    conditioning supplies them: gamma = 1 + scale, beta = shift): gamma = 1 + 0.1 N(0,1), beta = 0.1 N(0,1),
+    float32 [cols] each."""
+    prng = np.random.default_rng([int(seed), 0xB0])
+    gamma = (1.0 + 0.1 * prng.standard_normal(cols)).astype(np.float32)
+    beta = (0.1 * prng.standard_normal(cols)).astype(np.float32)
+    return gamma, beta
+
+
 def weight_matrix(rows=12288, cols=3072, seed=5, device="cpu", std=0.02):
     """cfg5 weight: N(0, std^2), blocks along the contiguous (reduction) dim."""
     out = torch.empty((rows, cols), dtype=torch.bfloat16, device=device)

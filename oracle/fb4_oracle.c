@@ -35,7 +35,10 @@
  *   - a reconstructed salient value is bf16(fp32(y1) + fp32(y2));
  *   - MXFP8 operands: block size 32 maps one to one; with block size 16 the
  *     two blocks of an MX block share the larger exponent and the other
- *     block's magnitudes are shifted down and rounded to nearest even in E4M3.
+ *     block's magnitudes are shifted down and rounded to nearest even in E4M3;
+ *   - a producer in front of the quantizer (App. E.2 names LayerNorm) hands
+ *     the quantizer bf16 values; since that rounding decides codes, its
+ *     arithmetic is fixed (see fb4o_layernorm) rather than done in double.
  *
  * Every routine here is pinned by tests/test_oracle_pins.py against hand-worked
  * fixtures, closed forms, exact rational brute force or torch's own number
@@ -574,3 +577,54 @@ int fb4o_repack_mxfp8(const uint8_t* fbk, int n_dialects, int block, const uint8
     return 0;
 }
 
+
+/* ------------------------------------------------------------------ */
+/* App. E.2: the quantizer runs fused behind the operation that produces the
+ * activation; LayerNorm is one of the two the paper names.  The paper does not
+ * define that operation, so this is the textbook one over the channels of a
+ * token, y_c = (x_c - mean) / sqrt(var + eps) * gamma_c + beta_c with the biased
+ * variance, and the quantizer's input is y rounded to bf16.  That rounding
+ * decides 4-bit codes, so the precision of every step is part of the definition
+ * (and is what a GPU producer would use), not "double everywhere":
+ *   S1 = sum x_c, S2 = sum x_c^2            in double (each term is exact)
+ *   mean = S1 / C, var = max(S2 / C - mean^2, 0) with one fused multiply-add
+ *   r = 1 / sqrt(var + eps)                  in double
+ *   a = float(r), b = float(-mean * r)
+ *   y_c = fmaf(fmaf(x_c, a, b), gamma_c, beta_c)   in float, then bf16 (RNE);
+ *         a NaN becomes the canonical quiet NaN 0x7FC0
+ * x is read as plain IEEE bf16 here (an Inf makes its row NaN).  The order of
+ * the two sums is channel order; they are exact, hence independent of order,
+ * whenever the row's values span fewer than about 2^12 in magnitude (S2) --
+ * otherwise another order can move S2 by an ulp of a double, which changes a
+ * or b with probability about 2^-29 per row.
+ * gamma / beta: [cols] or NULL (1 / 0).  y: [rows][cols] bf16 bit patterns;
+ * a, b: [rows] or NULL. */
+int fb4o_layernorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t row_stride, const float* gamma,
+                   const float* beta, float eps, uint16_t* y, float* a_out, float* b_out)
+{
+    if (!x || !y || rows < 0 || cols <= 0 || row_stride < cols) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t* xr = x + r * row_stride;
+        double s1 = 0.0, s2 = 0.0;
+        for (int64_t c = 0; c < cols; ++c) {
+            double v = bf16_value(xr[c]);
+            s1 += v;
+            s2 += v * v;
+        }
+        double mean = s1 / (double)cols;
+        double var = fma(-mean, mean, s2 / (double)cols);
+        if (var < 0.0) var = 0.0;
+        double rstd = 1.0 / sqrt(var + (double)eps);
+        float a = (float)rstd;
+        float b = (float)(-mean * rstd);
+        if (a_out) a_out[r] = a;
+        if (b_out) b_out[r] = b;
+        for (int64_t c = 0; c < cols; ++c) {
+            float xf = (float)bf16_value(xr[c]);
+            float t = fmaf(xf, a, b);
+            float yf = fmaf(t, gamma ? gamma[c] : 1.0f, beta ? beta[c] : 0.0f);
+            y[r * cols + c] = isnan(yf) ? (uint16_t)0x7FC0 : f32_to_bf16_rne(yf);
+        }
+    }
+    return 0;
+}

@@ -50,6 +50,7 @@ def _load():
                                        p, p, i32, p, p, i32]
         lib.fb4o_dequantize.argtypes = [p, i32, i32, p, p, i64, i64, p, p, p, i64, p, i32, i64, i32]
         lib.fb4o_repack_mxfp8.argtypes = [p, i32, i32, p, p, i64, i64, p, p]
+        lib.fb4o_layernorm.argtypes = [p, i64, i64, i64, p, p, ctypes.c_float, p, p, p]
         _lib = lib
     return _lib
 
@@ -170,6 +171,25 @@ def repack_mxfp8(fbk, codes, meta, block=32):
     if rc != 0:
         raise ValueError("fb4o_repack_mxfp8: invalid argument")
     return elems, scales
+
+
+def layernorm(x_bits, gamma=None, beta=None, eps=1e-6):
+    """The LayerNorm producer in front of the quantizer (App. E.2), arithmetic as fixed in fb4_oracle.c.
+    x_bits: uint16 [rows][cols]; gamma / beta: float32 [cols] or None.  Returns (y bf16 bit patterns
+    [rows][cols], a float32 [rows] = 1/std, b float32 [rows] = -mean/std)."""
+    assert x_bits.dtype == np.uint16 and x_bits.ndim == 2 and x_bits.strides[1] == 2
+    rows, cols = x_bits.shape
+    stride = x_bits.strides[0] // 2 if rows > 1 else cols
+    g = _c(gamma, np.float32)
+    b = _c(beta, np.float32)
+    y = np.zeros((rows, cols), dtype=np.uint16)
+    a_out = np.zeros(rows, dtype=np.float32)
+    b_out = np.zeros(rows, dtype=np.float32)
+    rc = _load().fb4o_layernorm(_ptr(x_bits), rows, cols, stride, _ptr(g), _ptr(b), float(eps), _ptr(y),
+                                _ptr(a_out), _ptr(b_out))
+    if rc != 0:
+        raise ValueError("fb4o_layernorm: invalid argument")
+    return y, a_out, b_out
 
 
 def seda_profile(fbk, meta, anchor_group, n_groups):

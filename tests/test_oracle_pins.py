@@ -684,3 +684,107 @@ def test_seda_profile_on_a_quantized_tensor_restricts_to_dialects_that_were_in_u
     # the constructed tables are valid SeDA inputs: every DID of the restricted pass comes from its row's table
     c2, m2 = O.quantize(fbk, xb, token_group=comp, sub_formatbooks=sub)
     assert ((m2 & 0xFF)[:, :, None] == sub[comp][:, None, :]).any(axis=2).all()
+
+
+# ------------------------------------------------- LayerNorm producer in front of the quantizer (App. E.2)
+def _ln_textbook(x64, gamma, beta, eps):
+    """Two-pass LayerNorm in float64, straight from the definition (biased variance)."""
+    mean = x64.mean(axis=1, keepdims=True)
+    var = ((x64 - mean) ** 2).mean(axis=1, keepdims=True)
+    return (x64 - mean) / np.sqrt(var + eps) * gamma + beta
+
+
+def test_layernorm_hand_worked_rows():
+    one = np.float32(1.0)
+    # [2,-2,2,-2]: mean 0, biased variance 4, eps 0 -> t = +-1; y = t * gamma + beta
+    x = f2b([[2, -2, 2, -2]])
+    y, a, b = O.layernorm(x, gamma=[1, 2, 3, 4], beta=[10, 20, 30, 40], eps=0.0)
+    assert b2f(y).tolist() == [[11.0, 18.0, 33.0, 36.0]]
+    assert a[0] == np.float32(0.5) and b[0] == 0.0
+    # biased variance: [1,-1] has variance 1, not 2
+    y, _, _ = O.layernorm(f2b([[1, -1]]), eps=0.0)
+    assert b2f(y).tolist() == [[1.0, -1.0]]
+    # eps is added to the variance: variance 1, eps 3 -> divide by 2
+    y, _, _ = O.layernorm(f2b([[1, -1]]), eps=3.0)
+    assert b2f(y).tolist() == [[0.5, -0.5]]
+    # mean is removed: [5, 1] -> mean 3, variance 4 -> +-1
+    y, a, b = O.layernorm(f2b([[5, 1]]), eps=0.0)
+    assert b2f(y).tolist() == [[1.0, -1.0]] and a[0] == np.float32(0.5) and b[0] == np.float32(-1.5)
+    # [1,-1,3,-3]: variance 5; 1/sqrt(5) = 0.4472136 -> bf16 0x3EE5, 3/sqrt(5) = 1.3416408 -> bf16 0x3FAC
+    y, _, _ = O.layernorm(f2b([[1, -1, 3, -3]]), eps=0.0)
+    assert y.tolist() == [[0x3EE5, 0xBEE5, 0x3FAC, 0xBFAC]]
+    assert one == 1.0
+
+
+def test_layernorm_agrees_with_the_float64_definition_to_the_last_bf16_bit():
+    rng = np.random.default_rng(71)
+    for rows, cols, mu, sigma in [(64, 96, 0.0, 1.0), (32, 3072, 0.0, 1.0), (16, 1152, 100.0, 1.0), (16, 64, -3.0, 20.0)]:
+        xb = f2b(mu + sigma * rng.standard_normal((rows, cols)))
+        gamma, beta = synth.layernorm_affine(cols, seed=rows)
+        y, a, b = O.layernorm(xb, gamma, beta, eps=1e-6)
+        x64 = b2f(xb)
+        ref = _ln_textbook(x64, gamma.astype(np.float64), beta.astype(np.float64), 1e-6)
+        got = b2f(y)
+        # one bf16 step at |ref|, plus what rounding 1/std and -mean/std to float leaves on the normalized value
+        tol = np.abs(ref) * 2.0 ** -7 + 2.0 ** -21 * (1.0 + abs(mu) / sigma)
+        assert (np.abs(got - ref) <= tol).all()
+        # with a large mean the float steps lose a little more; on centred data nearly every value is the
+        # correctly rounded one
+        if mu == 0.0:
+            assert (y == f2b(ref.astype(np.float32))).mean() > 0.999
+        mean = x64.mean(axis=1)
+        std = np.sqrt(x64.var(axis=1) + 1e-6)
+        assert np.allclose(a, 1.0 / std, rtol=1e-6, atol=0) and np.allclose(b, -mean / std, rtol=1e-6, atol=1e-7)
+
+
+def test_layernorm_invariants():
+    rng = np.random.default_rng(72)
+    xb = f2b(rng.standard_normal((8, 256)))
+    gamma, beta = synth.layernorm_affine(256, seed=3)
+    y, a, b = O.layernorm(xb, gamma, beta, eps=0.0)
+    # scaling a row by a power of two changes nothing when eps = 0 (every step scales exactly)
+    y4, a4, b4 = O.layernorm(f2b(b2f(xb) * 4.0), gamma, beta, eps=0.0)
+    assert np.array_equal(y, y4) and np.array_equal(a4 * 4, a) and np.array_equal(b4, b)
+    # rows are independent, and a row stride changes nothing
+    wide = np.zeros((8, 300), dtype=np.uint16)
+    wide[:, :256] = xb
+    wide[:, 256:] = 0x7FC0
+    ys, _, _ = O.layernorm(wide[:, :256], gamma, beta, eps=0.0)
+    assert np.array_equal(ys, y)
+    y1, _, _ = O.layernorm(xb[3:4], gamma, beta, eps=0.0)
+    assert np.array_equal(y1[0], y[3])
+    # negating the input negates the normalized value: with beta = 0 the output changes sign only
+    yn, _, _ = O.layernorm(xb ^ 0x8000, gamma, None, eps=0.0)
+    yp, _, _ = O.layernorm(xb, gamma, None, eps=0.0)
+    assert np.array_equal(yn ^ 0x8000, yp)
+    # a constant row has variance 0: y = beta
+    const = f2b(np.full((1, 256), 1.5))
+    yc, _, _ = O.layernorm(const, gamma, beta, eps=1e-6)
+    assert np.array_equal(yc[0], f2b(beta))
+    # a zero row with gamma only: exactly zero
+    yz, az, bz = O.layernorm(np.zeros((1, 256), dtype=np.uint16), gamma, None, eps=1e-6)
+    assert not (yz & 0x7FFF).any() and az[0] == np.float32(1000.0) and bz[0] == 0.0
+
+
+def test_layernorm_rows_with_nan_or_inf_become_canonical_nan():
+    rng = np.random.default_rng(73)
+    xb = f2b(rng.standard_normal((4, 64)))
+    clean, _, _ = O.layernorm(xb)
+    xb[1, 5] = 0xFFC1          # a negative NaN with a payload
+    xb[2, 60] = 0x7F80         # +Inf
+    y, _, _ = O.layernorm(xb)
+    assert (y[1] == 0x7FC0).all() and (y[2] == 0x7FC0).all()
+    assert np.array_equal(y[0], clean[0]) and np.array_equal(y[3], clean[3])
+
+
+def test_layernorm_then_quantize_sees_unit_scale_blocks(fbk):
+    # after LayerNorm without affine a row has unit variance: the block maxima of a Gaussian row (32 draws) sit
+    # in [1, 4) for nearly every block, whatever the scale of the input was
+    rng = np.random.default_rng(74)
+    xb = f2b(1e4 * rng.standard_normal((4, 3072)))
+    y, _, _ = O.layernorm(xb)
+    _, m = O.quantize(fbk, y)
+    e = (m >> 8).astype(int) - 127
+    assert np.isin(e, (0, 1)).mean() > 0.98 and e.max() <= 2 and e.min() >= -1
+    _, m_raw = O.quantize(fbk, xb)
+    assert ((m_raw >> 8).astype(int) - 127).min() >= 12
