@@ -256,6 +256,30 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
                      int64_t cols, int block, uint8_t* elems, int64_t elem_row_stride,
                      uint8_t* scales, void* stream);
 
+/*
+ * App. E.2 (the quantizer is fused into the operation that produces the
+ * activation; LayerNorm is one of the two the paper names): LayerNorm over the
+ * cols channels of every row, then fb4_quantize of the result, in one pass --
+ * x is read once and the normalized tensor is never written.
+ *   y[r][c] = (x[r][c] - mean_r) / sqrt(var_r + eps) * gamma[c] + beta[c]
+ * with the biased variance, rounded to bf16, is what gets quantized.  Because
+ * that rounding decides codes, the precision of each step is part of the
+ * contract: the row sums of x and x^2 in double; mean, variance (clamped at 0)
+ * and r = 1/sqrt(var + eps) in double; a = float(r), b = float(-mean * r);
+ * y = fmaf(fmaf(x, a, b), gamma, beta) in float, rounded to nearest even; a
+ * NaN result is the quiet NaN 0x7FC0.  x is read as plain IEEE bf16 (a row
+ * with an Inf or NaN normalizes to NaN throughout).
+ *   opts        block 32, FB4_SEL_LUT with 8 groups (FB4_FLAG_TWO_STAGE allowed);
+ *               anything else FB4_ERR_UNSUPPORTED
+ *   cols        a multiple of 32, at most 12288 (FB4_ERR_UNSUPPORTED otherwise)
+ *   gamma,beta  device, float [cols]; NULL = all ones / all zeros
+ *   eps         >= 0 (FB4_ERR_INVALID_ARG otherwise)
+ *   codes       device, 16-byte aligned (FB4_ERR_UNSUPPORTED otherwise)
+ */
+int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
+                           int64_t cols, int64_t row_stride, const float* gamma, const float* beta,
+                           float eps, uint8_t* codes, uint16_t* meta, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,6 +10,7 @@
 #include "fb4_dequant_fast.hpp"
 #include "fb4_fast.hpp"
 #include "fb4_kernels.hpp"
+#include "fb4_layernorm.hpp"
 #include "fb4_profile.hpp"
 #include "fb4_repack.hpp"
 #include "fb4_tables.hpp"
@@ -656,6 +657,59 @@ int fb4_seda_profile(const fb4_luts* luts, const uint16_t* meta, int64_t rows, i
     }
     hipLaunchKernelGGL(profile_select_kernel, dim3(((unsigned)n_groups * 8u + kProfileThreads - 1) / kProfileThreads),
                        dim3(kProfileThreads), 0, s, counts, n_groups, luts->dev_blob, sub_formatbooks);
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
+                           int64_t row_stride, const float* gamma, const float* beta, float eps, uint8_t* codes,
+                           uint16_t* meta, void* stream)
+{
+    int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
+    if (rc != FB4_OK) return rc;
+    if (!(eps >= 0.0f) || eps > 3.0e38f) return FB4_ERR_INVALID_ARG;
+    if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8) return FB4_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return FB4_OK;
+    const int64_t nb = cols / 32;
+    if (nb > 64 * kLnMaxChunksPerLane || !aligned(codes, 16) || (gamma && !aligned(gamma, 4)) || (beta && !aligned(beta, 4)))
+        return FB4_ERR_UNSUPPORTED;
+    if ((uint64_t)rows * (uint64_t)nb >= 0x7F000000ull) return FB4_ERR_UNSUPPORTED;
+    if ((rc = check_device(luts)) != FB4_OK) return rc;
+    // chunks per lane B and rows per bundle: the fullest wavefront, the fewest registers among equals
+    int B = 0;
+    uint32_t rw = 0;
+    double best = 0.0;
+    for (int b = 1; b <= kLnMaxChunksPerLane; ++b) {
+        if (nb > 64 * b) continue;
+        const uint32_t r = (uint32_t)(64 * b / nb);
+        const double fill = (double)(r * nb) / (64.0 * b);
+        if (fill > best + 1e-9) { best = fill; B = b; rw = r; }
+    }
+    if (rw > (uint32_t)rows) rw = (uint32_t)rows;
+    const uint32_t n_bundles = (uint32_t)((rows + rw - 1) / rw);
+    long long g = ((long long)n_bundles + 7) / 8;
+    if (g > luts->n_cu) g = luts->n_cu;
+    const unsigned groups = (unsigned)g;
+    LayerNormParams p = {};
+    p.rows = (uint32_t)rows;
+    p.cols = (uint32_t)cols;
+    p.n_blocks = (uint32_t)(rows * nb);
+    p.eps = eps;
+    p.codes = codes;
+    p.meta = meta;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
+#define FB4_LN_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), n_bundles, rw, (uint32_t)nb, groups, (long long)row_stride, gamma, beta, p
+#define FB4_LN_CASE(b)                                                                                                              \
+    case b:                                                                                                                         \
+        if (ts) hipLaunchKernelGGL((layernorm_quantize_kernel<b, true>), dim3(groups), dim3(kLnThreads), 0, s, FB4_LN_ARGS);  \
+        else hipLaunchKernelGGL((layernorm_quantize_kernel<b, false>), dim3(groups), dim3(kLnThreads), 0, s, FB4_LN_ARGS);    \
+        break;
+    switch (B) {
+        FB4_LN_CASE(1) FB4_LN_CASE(2) FB4_LN_CASE(3) FB4_LN_CASE(4) FB4_LN_CASE(5) FB4_LN_CASE(6)
+        default: return FB4_ERR_UNSUPPORTED;
+    }
+#undef FB4_LN_CASE
+#undef FB4_LN_ARGS
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 

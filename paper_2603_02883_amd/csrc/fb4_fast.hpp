@@ -464,12 +464,14 @@ __device__ __forceinline__ uint32_t select_sse_rows(const uint32_t (&b2)[16], co
 // 32 or two blocks of 16.  Produces the four code words and the metadata (one 16-bit word, or two for block
 // size 16 with the first block in the low half).  xb / in_range are only used by the plain per-element
 // routine of a tile with special values (tile_special reports that this route was taken).  kResidual: w holds the Sec. 3.3 residual of the first plane
-// (code1, meta1), which the plain routine recomputes from x.
+// (code1, meta1), which the plain routine recomputes from x.  stage: 16 words of the lane's private memory when w
+// is not in global memory at all (xb is then ignored).
 template <int kBlock, int G, bool kTwoStage, bool kSeda, bool kResidual = false>
 __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint8_t* lds, const TileConsts& K,
                                              const uint16_t* xb, bool in_range, uint32_t excl_a,
                                              uint32_t (&code)[4], uint32_t& meta,
-                                             const uint32_t (&code1)[4], uint32_t meta1, bool& tile_special)
+                                             const uint32_t (&code1)[4], uint32_t meta1, bool& tile_special,
+                                             uint32_t* stage = nullptr)
 {
     constexpr int NB = 32 / kBlock;     // blocks per lane
     constexpr int RB = 16 / NB;         // packed registers per block
@@ -501,6 +503,18 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
         // rare: some block of this tile holds NaN / Inf or is tiny
         code[0] = code[1] = code[2] = code[3] = 0;
         meta = 0;
+        if (stage) {
+            // the elements exist in registers only (a fused producer made them): the plain routine gets them
+            // through this lane's private memory, NaNs as the canonical quiet NaN
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                uint32_t v = w[k];
+                if ((v & 0x7FFFu) > 0x7F80u) v = (v & 0xFFFF0000u) | 0x7FC0u;
+                if ((v & 0x7FFF0000u) > 0x7F800000u) v = (v & 0xFFFFu) | 0x7FC00000u;
+                stage[k] = v;
+            }
+            xb = reinterpret_cast<const uint16_t*>(stage);
+        }
         if (in_range) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) {

@@ -1,0 +1,225 @@
+// The online quantizer fused behind a LayerNorm (App. E.2: quantization runs
+// inside the operation that produces the activation; LayerNorm is one of the
+// two the paper names).  One pass: x is read once, the normalized activation
+// never reaches memory, codes and metadata are written as by the streaming
+// kernel.
+//
+// The producer is the textbook LayerNorm over the channels of a token with a
+// per-channel scale and shift; the quantizer's input is its result rounded to
+// bf16.  That rounding decides codes, so the precision of each step is fixed:
+//   S1 = sum x, S2 = sum x^2 in double (every term exact); mean = S1 / C;
+//   var = max(fma(-mean, mean, S2 / C), 0); r = 1 / sqrt(var + eps) in double;
+//   a = float(r), b = float(-mean * r);
+//   y = fmaf(fmaf(x, a, b), gamma, beta) in float, rounded to bf16 (nearest
+//   even); a NaN becomes the canonical quiet NaN 0x7FC0.
+// The sums are exact, hence independent of their order, whenever a row's values
+// span less than about 2^12 in magnitude; beyond that another order may move
+// S2 by one ulp of a double, which changes a or b once in about 2^29 rows.
+//
+// Work split: a wavefront owns whole rows, so the row sums never leave it.  A
+// "bundle" is RW consecutive rows, RW * nb <= 64 * B chunks of 32 elements;
+// lane l holds chunks l, l + 64, ..., l + 64 (B - 1) of the bundle in
+// registers (the same channels in every bundle, so its scale / shift addresses
+// are loop invariants), sums them, the wavefront reduces per row with
+// butterfly exchanges (a fixed order: results do not change from run to run),
+// and each lane then normalizes and quantizes its chunks with the streaming
+// kernel's per-chunk routine.  Bundles are dealt like that kernel's tiles: to
+// persistent workgroups round robin, to a workgroup's wavefronts on demand.
+#pragma once
+
+#include "fb4_fast.hpp"
+
+namespace fb4 {
+
+struct LayerNormParams {
+    uint32_t rows;
+    uint32_t cols;
+    uint32_t n_blocks;   // rows * nb
+    float eps;
+    uint8_t* codes;
+    uint16_t* meta;
+};
+
+constexpr int kLnThreads = 512;
+constexpr int kLnMaxChunksPerLane = 6;
+constexpr int kLdsLnTables = lds_fast_bytes(false, false, false);
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// B: chunks per lane (the host picks it from the row length); gamma / beta may be null (1 / 0).
+template <int B, bool kTwoStage>
+__global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
+    const uint8_t* blob, const uint16_t* x, uint32_t n_bundles, uint32_t rw, uint32_t nb, uint32_t n_workgroups,
+    long long row_stride, const float* gamma, const float* beta, LayerNormParams p)
+{
+    constexpr int kWaves = kLnThreads / 64;
+    constexpr int kGbFloats = 2048 * B;   // nb <= 64 * B chunks = 2048 * B channels
+    __shared__ __align__(16) uint8_t lds[kLdsLnTables + 2 * kGbFloats * 4];
+    __shared__ uint32_t wg_next;
+    float* lds_gamma = reinterpret_cast<float*>(lds + kLdsLnTables);
+    float* lds_beta = lds_gamma + kGbFloats;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t W = n_workgroups;
+    const uint32_t per_bundle = rw * nb;   // chunks of a bundle, <= 64 * B
+
+    // this lane's chunks: position in the bundle, row within the bundle, chunk within the row
+    uint32_t rloc[B], cb[B];
+    bool valid[B];
+#pragma unroll
+    for (int j = 0; j < B; ++j) {
+        const uint32_t i = lane + 64u * j;
+        valid[j] = i < per_bundle;
+        const uint32_t ic = valid[j] ? i : 0u;
+        rloc[j] = ic / nb;
+        cb[j] = ic - rloc[j] * nb;
+    }
+    // A chunk that does not exist (past the bundle or past the last row) is read from the last row
+    // instead: no branch around the loads, nothing of it is stored.
+    auto request = [&](uint32_t u, uint4 (&q)[B][4]) {
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const uint32_t row = min(min(u, n_bundles - 1u) * rw + rloc[j], p.rows - 1u);
+            const uint4* px = reinterpret_cast<const uint4*>(x + (long long)row * row_stride + (long long)cb[j] * 32);
+            q[j][0] = px[0]; q[j][1] = px[1]; q[j][2] = px[2]; q[j][3] = px[3];
+        }
+    };
+
+    uint32_t u = blockIdx.x + wave * W;
+    uint32_t u_next = blockIdx.x + (kWaves + wave) * W;
+    if (threadIdx.x == 0) wg_next = 2 * kWaves;
+    uint4 cur[B][4];
+    request(u, cur);
+
+    // ---- tables (layout of the streaming kernel) and the scale / shift vectors
+    for (int i = threadIdx.x; i < 64 * kRowCopies; i += kLnThreads) {
+        const int bin = i / (2 * kRowCopies), half = (i / kRowCopies) & 1;
+        reinterpret_cast<uint4*>(lds + kLdsRows)[i] = *reinterpret_cast<const uint4*>(blob + kOffQerror8 + bin * 32 + half * 16);
+    }
+    for (int i = threadIdx.x; i < 256; i += kLnThreads)
+        reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = reinterpret_cast<const uint32_t*>(blob + kOffQvalueT)[i];
+    if (kTwoStage && threadIdx.x < 64)
+        reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] = reinterpret_cast<const uint32_t*>(blob + kOffRangeExcl)[threadIdx.x];
+    for (uint32_t c = threadIdx.x; c < p.cols; c += kLnThreads) {
+        lds_gamma[c] = gamma ? gamma[c] : 1.0f;
+        lds_beta[c] = beta ? beta[c] : 0.0f;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 1024; i += kLnThreads) {   // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
+        const int hi = i >> 5, lo = i & 31;
+        const uint4* rl = reinterpret_cast<const uint4*>(lds + kLdsNibT + lo * 32);
+        const uint4* rh = reinterpret_cast<const uint4*>(lds + kLdsNibT + hi * 32);
+        uint4* dst = reinterpret_cast<uint4*>(lds + kLdsPair + i * 32);
+        const uint4 l0 = rl[0], l1 = rl[1], h0 = rh[0], h1 = rh[1];
+        dst[0] = make_uint4(l0.x | (h0.x << 4), l0.y | (h0.y << 4), l0.z | (h0.z << 4), l0.w | (h0.w << 4));
+        dst[1] = make_uint4(l1.x | (h1.x << 4), l1.y | (h1.y << 4), l1.z | (h1.z << 4), l1.w | (h1.w << 4));
+    }
+    __syncthreads();
+    const TileConsts K = make_tile_consts(lane, 0);
+    FastParams sp = {};   // what the store routine looks at
+    sp.codes = p.codes;
+    sp.meta = p.meta;
+    sp.n_blocks = p.n_blocks;
+    const bool meta_aligned = (reinterpret_cast<uintptr_t>(p.meta) & 15u) == 0;
+    const double n_channels = (double)p.cols;
+    const double eps = (double)p.eps;
+
+    while (u < n_bundles) {
+        uint32_t w[B][16];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                w[j][4 * q] = cur[j][q].x; w[j][4 * q + 1] = cur[j][q].y;
+                w[j][4 * q + 2] = cur[j][q].z; w[j][4 * q + 3] = cur[j][q].w;
+            }
+        }
+        // the next bundle's loads go out before this bundle's arithmetic (short rows only: the registers
+        // of a long row's chunks are needed for the arithmetic)
+        if (B <= 3) request(u_next, cur);
+        uint32_t claim = 0;
+        if (lane == 0) claim = atomicAdd(&wg_next, 1u);
+        const uint32_t u_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
+
+        // ---- per-chunk sums in double
+        double p1[B], p2[B];
+        bool ok[B];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            ok[j] = valid[j] && u * rw + rloc[j] < p.rows;
+            double s1a = 0.0, s1b = 0.0, s2a = 0.0, s2b = 0.0;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const double d0 = (double)__uint_as_float(w[j][k] << 16);
+                const double d1 = (double)__uint_as_float(w[j][k] & 0xFFFF0000u);
+                s1a += d0; s1b += d1;
+                s2a = fma(d0, d0, s2a); s2b = fma(d1, d1, s2b);
+            }
+            p1[j] = ok[j] ? s1a + s1b : 0.0;
+            p2[j] = ok[j] ? s2a + s2b : 0.0;
+        }
+        // ---- per row: reduce over the wavefront, then 1/std and -mean/std as floats
+        float a[B], b[B];
+#pragma unroll
+        for (int j = 0; j < B; ++j) a[j] = b[j] = 0.0f;
+        for (uint32_t r = 0; r < rw; ++r) {
+            double c1 = 0.0, c2 = 0.0;
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                c1 += (valid[j] && rloc[j] == r) ? p1[j] : 0.0;
+                c2 += (valid[j] && rloc[j] == r) ? p2[j] : 0.0;
+            }
+            c1 = wave_sum(c1);
+            c2 = wave_sum(c2);
+            const double mean = c1 / n_channels;
+            double var = fma(-mean, mean, c2 / n_channels);
+            var = var < 0.0 ? 0.0 : var;   // (a NaN stays a NaN)
+            const double rstd = 1.0 / sqrt(var + eps);
+            const float ar = (float)rstd, br = (float)(-mean * rstd);
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                if (ok[j] && rloc[j] == r) { a[j] = ar; b[j] = br; }   // (a chunk that does not exist keeps 0, 0)
+            }
+        }
+        // ---- normalize, scale and shift, round to bf16, quantize, store
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            const float4* g4 = reinterpret_cast<const float4*>(lds_gamma + cb[j] * 32u);
+            const float4* b4 = reinterpret_cast<const float4*>(lds_beta + cb[j] * 32u);
+            uint32_t y[16];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const float4 g = g4[q], be = b4[q];
+                const float x0 = __uint_as_float(w[j][2 * q] << 16), x1 = __uint_as_float(w[j][2 * q] & 0xFFFF0000u);
+                const float x2 = __uint_as_float(w[j][2 * q + 1] << 16), x3 = __uint_as_float(w[j][2 * q + 1] & 0xFFFF0000u);
+                const f32x2 y01 = {__builtin_fmaf(__builtin_fmaf(x0, a[j], b[j]), g.x, be.x),
+                                   __builtin_fmaf(__builtin_fmaf(x1, a[j], b[j]), g.y, be.y)};
+                const f32x2 y23 = {__builtin_fmaf(__builtin_fmaf(x2, a[j], b[j]), g.z, be.z),
+                                   __builtin_fmaf(__builtin_fmaf(x3, a[j], b[j]), g.w, be.w)};
+                y[2 * q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(y01, bf16x2));
+                y[2 * q + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(y23, bf16x2));
+            }
+            uint32_t stage[16];   // the plain routine reads its block from memory: used by special tiles only
+            uint32_t code[4], meta;
+            bool tile_special;
+            const uint32_t no_code[4] = {0, 0, 0, 0};
+            compute_tile<32, 8, kTwoStage, false>(y, lds, K, nullptr, ok[j], 0u, code, meta, no_code, 0u, tile_special,
+                                                  stage);
+            const uint32_t gb = u * per_bundle + lane + 64u * j;
+            const bool al = meta_aligned && (((gb - lane) & 7u) == 0u);
+            store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, al, ok[j]);
+        }
+        if (B > 3) request(u_next, cur);
+        u = u_next;
+        u_next = u_after;
+    }
+}
+
+}  // namespace fb4

@@ -836,3 +836,96 @@ def test_offsets_beyond_4_gib(F, luts):
             del el, sc
         del c1, m1
         torch.cuda.empty_cache()
+
+
+# ------------------------------------------------- LayerNorm fused in front of the quantizer (App. E.2)
+def _ln_case(F, luts, xb, gamma, beta, eps, flags=0, what="", x_dev=None):
+    x = dev_bits(xb) if x_dev is None else x_dev
+    g = None if gamma is None else torch.from_numpy(gamma).cuda()
+    b = None if beta is None else torch.from_numpy(beta).cuda()
+    o = F.opts(selector=1, num_groups=8, flags=flags)
+    c, m = F.fb4_layernorm_quantize(luts, o, x, g, b, eps)
+    torch.cuda.synchronize()
+    y, _, _ = O.layernorm(xb, gamma, beta, eps)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, y, selector=1, num_groups=8, flags=flags)
+    compare_quant(DEFAULT_FORMATBOOK, y, host_u8(c), host_u16(m), cr, mr, 1, 8, flags=flags, what="layernorm " + what)
+    return c, m
+
+
+# rows x cols -> chunks per lane / rows per bundle the launcher picks: 3/2, 4/7 (ragged last bundle, bundles that
+# do not fill the wavefront), 6/1, 1/64 cut to the row count, 2/1, 4/1, 5/1 with idle lanes, 1/2, 2/3
+LN_SHAPES = [(1024, 3072), (1000, 1152), (37, 12288), (5, 32), (129, 4096), (50, 8192), (33, 9600), (131, 1024),
+             (77, 1344), (1, 3072), (513, 64)]
+
+
+@pytest.mark.parametrize("rows,cols", LN_SHAPES)
+def test_layernorm_quantize_shapes(F, luts, rows, cols):
+    x = synth.vdit_activation(rows=rows, cols=cols, seed=rows + cols, device="cuda")
+    gamma, beta = synth.layernorm_affine(cols, seed=cols)
+    _ln_case(F, luts, synth.bf16_bits(x), gamma, beta, 1e-6, what="%dx%d" % (rows, cols), x_dev=x)
+
+
+def test_layernorm_quantize_full_size_two_stage_and_no_affine(F, luts):
+    x = synth.vdit_activation(device="cuda")                  # 16384 x 3072, the benchmark workload
+    xb = synth.bf16_bits(x)
+    gamma, beta = synth.layernorm_affine(3072)
+    _ln_case(F, luts, xb, gamma, beta, 1e-6, what="cfg2", x_dev=x)
+    _ln_case(F, luts, xb, gamma, beta, 1e-5, flags=F.FLAG_TWO_STAGE, what="cfg2 two-stage", x_dev=x)
+    _ln_case(F, luts, xb, None, None, 1e-6, what="cfg2 no affine", x_dev=x)
+    _ln_case(F, luts, xb, gamma, None, 0.0, what="cfg2 scale only, eps 0", x_dev=x)
+
+
+def test_layernorm_quantize_degenerate_rows_and_strides(F, luts):
+    xe = synth.edge_case_tensor(cols=256)                      # zero rows, subnormals, Inf, NaN, constants, 1e30
+    gamma, beta = synth.layernorm_affine(256, seed=9)
+    for eps in (1e-6, 0.0):                                    # eps 0: a constant row divides by zero -> NaN row
+        _ln_case(F, luts, xe, gamma, beta, eps, what="edge rows eps %g" % eps)
+        _ln_case(F, luts, xe, None, None, eps, what="edge rows, no affine, eps %g" % eps)
+    # scale / shift with zeros, huge values and an Inf: products overflow, Inf * 0 and Inf - Inf make single NaNs
+    g2 = gamma.copy(); b2 = beta.copy()
+    g2[3] = 0.0; g2[40] = 3e38; g2[41] = -3e38; b2[40] = 3e38; b2[41] = 3e38; g2[100] = np.inf; b2[100] = -np.inf
+    g2[130] = 1e-30; b2[130] = 0.0; g2[131] = 1e-38; b2[131] = 1e-40
+    x = synth.vdit_activation(rows=64, cols=256, seed=5, device="cuda")
+    _ln_case(F, luts, synth.bf16_bits(x), g2, b2, 1e-6, what="extreme scale and shift", x_dev=x)
+    # a row stride, and outputs that are only 16 / 2 byte aligned
+    wide = synth.vdit_activation(rows=70, cols=3072 + 64, seed=6, device="cuda")
+    xs = wide[:, 32:32 + 3072]
+    gamma, beta = synth.layernorm_affine(3072, seed=2)
+    o = F.opts(selector=1, num_groups=8)
+    cbuf = torch.zeros(70 * 1536 + 16, dtype=torch.uint8, device="cuda")
+    mbuf = torch.zeros(70 * 96 + 1, dtype=torch.int16, device="cuda")
+    c = cbuf[16:].view(70, 1536); m = mbuf[1:].view(70, 96)
+    F.fb4_layernorm_quantize(luts, o, xs, torch.from_numpy(gamma).cuda(), torch.from_numpy(beta).cuda(), 1e-6, codes=c, meta=m)
+    torch.cuda.synchronize()
+    xb = synth.bf16_bits(xs.contiguous())
+    y, _, _ = O.layernorm(xb, gamma, beta, 1e-6)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, y)
+    assert np.array_equal(host_u8(c), cr) and np.array_equal(host_u16(m), mr)
+    assert not cbuf[:16].any() and mbuf[0] == 0
+
+
+def test_layernorm_quantize_is_the_unfused_pair_and_rejects_what_it_does_not_serve(F, luts):
+    # the same codes as the plain entry point run on the oracle's normalized tensor
+    x = synth.gaussian_outlier(rows=256, cols=3072, seed=8, device="cuda")
+    gamma, beta = synth.layernorm_affine(3072, seed=8)
+    c, m = _ln_case(F, luts, synth.bf16_bits(x), gamma, beta, 1e-6, what="unfused", x_dev=x)
+    y, _, _ = O.layernorm(synth.bf16_bits(x), gamma, beta, 1e-6)
+    c2, m2 = F.fb4_quantize(luts, F.opts(), dev_bits(y))
+    torch.cuda.synchronize()
+    assert torch.equal(c, c2) and torch.equal(m, m2)
+    for o, code in ((F.opts(block=16), F.ERR_UNSUPPORTED), (F.opts(num_groups=16), F.ERR_UNSUPPORTED),
+                    (F.opts(selector=0), F.ERR_UNSUPPORTED)):
+        with pytest.raises(F.Fb4Error) as e:
+            F.fb4_layernorm_quantize(luts, o, x)
+        assert e.value.code == code
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_layernorm_quantize(luts, F.opts(), x, eps=-1.0)
+    assert e.value.code == F.ERR_INVALID_ARG
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_layernorm_quantize(luts, F.opts(), x, eps=float("nan"))
+    assert e.value.code == F.ERR_INVALID_ARG
+    big = torch.zeros((2, 12288 + 32), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_layernorm_quantize(luts, F.opts(), big)
+    assert e.value.code == F.ERR_UNSUPPORTED
+    F.fb4_layernorm_quantize(luts, F.opts(), x[:0])           # no rows: a successful no-op
