@@ -203,6 +203,12 @@ def main():
             F.fb4_dequantize(luts, codes[k], metas[k], out=outs[i % 2])
             F.fb4_dequantize(luts, codes[k], metas[k], codes2=c2, meta2=m2, salient_rows=sal_d, out=outs[i % 2])
             F.fb4_repack_mxfp8(luts, codes[k], metas[k], elems=els[i % 2], scales=scs[i % 2])
+        # LayerNorm + quantizer in one pass
+        gamma_h, beta_h = synth.layernorm_affine(COLS)
+        gamma_d, beta_d = torch.from_numpy(gamma_h).cuda(), torch.from_numpy(beta_h).cuda()
+        for i in range(4):
+            k = i % N_SETS
+            F.fb4_layernorm_quantize(luts, o, xs[k], gamma_d, beta_d, 1e-6, codes=codes[k], meta=metas[k])
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": True, "copy_bytes_read": x0.numel() * 2, "copy_bytes_written": x0.numel() * 2,
                           "quantize_algorithmic_bytes": abytes}))
@@ -272,6 +278,23 @@ def main():
         add("quantize_block16_lut_g8", b16_step, algorithmic_bytes(ROWS, COLS, 16), n_el)
         add("quantize_lut_g8_two_stage", quant_step(F.opts(selector=F.SEL_LUT, num_groups=8,
                                                            flags=F.FLAG_TWO_STAGE)), abytes, n_el)
+        # LayerNorm fused in front of the quantizer: x read once, the normalized tensor never written ...
+        gamma_h, beta_h = synth.layernorm_affine(COLS)
+        gamma_d, beta_d = torch.from_numpy(gamma_h).cuda(), torch.from_numpy(beta_h).cuda()
+
+        def ln_step(i):
+            k = i % N_SETS
+            F.fb4_layernorm_quantize(luts, o_main, xs[k], gamma_d, beta_d, 1e-6, codes=codes[k], meta=metas[k])
+        add("layernorm_quantize_one_pass", ln_step, abytes + 2 * COLS * 4, n_el)
+        # ... against the two-pass form: the framework's LayerNorm writing bf16 (into a buffer that is reused at
+        # once, so part of it is still in the Infinity Cache), then the quantizer reading that back
+        gamma_b, beta_b = gamma_d.bfloat16(), beta_d.bfloat16()
+
+        def ln_unfused_step(i):
+            k = i % N_SETS
+            y = torch.nn.functional.layer_norm(xs[k], (COLS,), gamma_b, beta_b, 1e-6)
+            F.fb4_quantize(luts, o_main, y, codes=codes[k], meta=metas[k])
+        add("layernorm_by_torch_then_quantize", ln_unfused_step, abytes + 2 * n_el * 2, n_el)
         # SeDA (cfg4)
         xm, comp = synth.mixture_activation(rows=ROWS, cols=COLS, seed=4, device="cuda")
         xms = [xm] + [xm.clone() for _ in range(N_SETS - 1)]

@@ -81,20 +81,20 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
     }
     // A chunk that does not exist (past the bundle or past the last row) is read from the last row
     // instead: no branch around the loads, nothing of it is stored.
-    auto request = [&](uint32_t u, uint4 (&q)[B][4]) {
-#pragma unroll
-        for (int j = 0; j < B; ++j) {
-            const uint32_t row = min(min(u, n_bundles - 1u) * rw + rloc[j], p.rows - 1u);
-            const uint4* px = reinterpret_cast<const uint4*>(x + (long long)row * row_stride + (long long)cb[j] * 32);
-            q[j][0] = px[0]; q[j][1] = px[1]; q[j][2] = px[2]; q[j][3] = px[3];
-        }
+    auto request = [&](uint32_t u, int j, uint32_t (&q)[16]) {
+        const uint32_t row = min(min(u, n_bundles - 1u) * rw + rloc[j], p.rows - 1u);
+        const uint4* px = reinterpret_cast<const uint4*>(x + (long long)row * row_stride + (long long)cb[j] * 32);
+        const uint4 q0 = px[0], q1 = px[1], q2 = px[2], q3 = px[3];
+        q[0] = q0.x; q[1] = q0.y; q[2] = q0.z; q[3] = q0.w; q[4] = q1.x; q[5] = q1.y; q[6] = q1.z; q[7] = q1.w;
+        q[8] = q2.x; q[9] = q2.y; q[10] = q2.z; q[11] = q2.w; q[12] = q3.x; q[13] = q3.y; q[14] = q3.z; q[15] = q3.w;
     };
 
     uint32_t u = blockIdx.x + wave * W;
     uint32_t u_next = blockIdx.x + (kWaves + wave) * W;
     if (threadIdx.x == 0) wg_next = 2 * kWaves;
-    uint4 cur[B][4];
-    request(u, cur);
+    uint32_t w[B][16];   // the bundle's chunks; chunk j is replaced by the next bundle's as soon as it is normalized
+#pragma unroll
+    for (int j = 0; j < B; ++j) request(u, j, w[j]);
 
     // ---- tables (layout of the streaming kernel) and the scale / shift vectors
     for (int i = threadIdx.x; i < 64 * kRowCopies; i += kLnThreads) {
@@ -105,9 +105,12 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
         reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = reinterpret_cast<const uint32_t*>(blob + kOffQvalueT)[i];
     if (kTwoStage && threadIdx.x < 64)
         reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] = reinterpret_cast<const uint32_t*>(blob + kOffRangeExcl)[threadIdx.x];
+    // scale / shift: the four channels (4q .. 4q+3) of chunk cb at [q][64 B][4], so that the 16-byte reads of
+    // neighbouring lanes (neighbouring chunks, same q) fall into different banks and q is a constant offset
     for (uint32_t c = threadIdx.x; c < p.cols; c += kLnThreads) {
-        lds_gamma[c] = gamma ? gamma[c] : 1.0f;
-        lds_beta[c] = beta ? beta[c] : 0.0f;
+        const uint32_t at = (((c & 31u) >> 2) * (64u * B) + (c >> 5)) * 4u + (c & 3u);
+        lds_gamma[at] = gamma ? gamma[c] : 1.0f;
+        lds_beta[at] = beta ? beta[c] : 0.0f;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < 1024; i += kLnThreads) {   // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
@@ -130,18 +133,6 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
     const double eps = (double)p.eps;
 
     while (u < n_bundles) {
-        uint32_t w[B][16];
-#pragma unroll
-        for (int j = 0; j < B; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                w[j][4 * q] = cur[j][q].x; w[j][4 * q + 1] = cur[j][q].y;
-                w[j][4 * q + 2] = cur[j][q].z; w[j][4 * q + 3] = cur[j][q].w;
-            }
-        }
-        // the next bundle's loads go out before this bundle's arithmetic (short rows only: the registers
-        // of a long row's chunks are needed for the arithmetic)
-        if (B <= 3) request(u_next, cur);
         uint32_t claim = 0;
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
         const uint32_t u_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
@@ -162,6 +153,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
             }
             p1[j] = ok[j] ? s1a + s1b : 0.0;
             p2[j] = ok[j] ? s2a + s2b : 0.0;
+            __builtin_amdgcn_sched_barrier(0);   // one chunk at a time: interleaving them costs registers
         }
         // ---- per row: reduce over the wavefront, then 1/std and -mean/std as floats
         float a[B], b[B];
@@ -191,12 +183,13 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
         for (int j = 0; j < B; ++j) {
             typedef float f32x2 __attribute__((ext_vector_type(2)));
             typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-            const float4* g4 = reinterpret_cast<const float4*>(lds_gamma + cb[j] * 32u);
-            const float4* b4 = reinterpret_cast<const float4*>(lds_beta + cb[j] * 32u);
+            const float4* g4 = reinterpret_cast<const float4*>(lds_gamma) + cb[j];
+            const float4* b4 = reinterpret_cast<const float4*>(lds_beta) + cb[j];
+            const uint32_t gb = u * per_bundle + lane + 64u * j;
             uint32_t y[16];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const float4 g = g4[q], be = b4[q];
+                const float4 g = g4[q * 64 * B], be = b4[q * 64 * B];
                 const float x0 = __uint_as_float(w[j][2 * q] << 16), x1 = __uint_as_float(w[j][2 * q] & 0xFFFF0000u);
                 const float x2 = __uint_as_float(w[j][2 * q + 1] << 16), x3 = __uint_as_float(w[j][2 * q + 1] & 0xFFFF0000u);
                 const f32x2 y01 = {__builtin_fmaf(__builtin_fmaf(x0, a[j], b[j]), g.x, be.x),
@@ -206,17 +199,20 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
                 y[2 * q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(y01, bf16x2));
                 y[2 * q + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(y23, bf16x2));
             }
+            // the registers of chunk j are free: the next bundle's chunk j is requested into them, ahead of
+            // this chunk's selection and of the sums of the next bundle's earlier chunks
+            request(u_next, j, w[j]);
+            __builtin_amdgcn_sched_barrier(0);
             uint32_t stage[16];   // the plain routine reads its block from memory: used by special tiles only
             uint32_t code[4], meta;
             bool tile_special;
             const uint32_t no_code[4] = {0, 0, 0, 0};
             compute_tile<32, 8, kTwoStage, false>(y, lds, K, nullptr, ok[j], 0u, code, meta, no_code, 0u, tile_special,
                                                   stage);
-            const uint32_t gb = u * per_bundle + lane + 64u * j;
             const bool al = meta_aligned && (((gb - lane) & 7u) == 0u);
             store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, al, ok[j]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (B > 3) request(u_next, cur);
         u = u_next;
         u_next = u_after;
     }
