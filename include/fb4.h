@@ -264,10 +264,11 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
  *   y[r][c] = (x[r][c] - mean_r) / sqrt(var_r + eps) * gamma[c] + beta[c]
  * with the biased variance, rounded to bf16, is what gets quantized.  Because
  * that rounding decides codes, the precision of each step is part of the
- * contract: the row sums of x and x^2 in double; mean, variance (clamped at 0)
- * and r = 1/sqrt(var + eps) in double; a = float(r), b = float(-mean * r);
- * y = fmaf(fmaf(x, a, b), gamma, beta) in float, rounded to nearest even; a
- * NaN result is the quiet NaN 0x7FC0.  x is read as plain IEEE bf16 (a row
+ * contract: the row sums of x and x^2 in double; mean = S1 * (1/C) and
+ * var = max(S2 * (1/C) - mean^2, 0) in double (one fused multiply-add);
+ * a = 1 / sqrt(float(var + eps)) and b = -float(mean) * a in float (IEEE
+ * square root and divide); y = fmaf(fmaf(x, a, b), gamma, beta) in float,
+ * rounded to nearest even; a NaN result is the quiet NaN 0x7FC0.  x is read as plain IEEE bf16 (a row
  * with an Inf or NaN normalizes to NaN throughout).
  *   opts        block 32, FB4_SEL_LUT with 8 groups (FB4_FLAG_TWO_STAGE allowed);
  *               anything else FB4_ERR_UNSUPPORTED

@@ -586,10 +586,12 @@ int fb4o_repack_mxfp8(const uint8_t* fbk, int n_dialects, int block, const uint8
  * variance, and the quantizer's input is y rounded to bf16.  That rounding
  * decides 4-bit codes, so the precision of every step is part of the definition
  * (and is what a GPU producer would use), not "double everywhere":
- *   S1 = sum x_c, S2 = sum x_c^2            in double (each term is exact)
- *   mean = S1 / C, var = max(S2 / C - mean^2, 0) with one fused multiply-add
- *   r = 1 / sqrt(var + eps)                  in double
- *   a = float(r), b = float(-mean * r)
+ *   S1 = sum x_c, S2 = sum x_c^2             in double (each term is exact)
+ *   mean = S1 * (1/C), m2 = S2 * (1/C)       in double, 1/C rounded to double
+ *   var = max(m2 - mean^2, 0)                in double, one fused multiply-add
+ *   a = 1 / sqrt(float(var + eps))           in float (IEEE square root, then
+ *                                            IEEE divide)
+ *   b = -float(mean) * a                     in float
  *   y_c = fmaf(fmaf(x_c, a, b), gamma_c, beta_c)   in float, then bf16 (RNE);
  *         a NaN becomes the canonical quiet NaN 0x7FC0
  * x is read as plain IEEE bf16 here (an Inf makes its row NaN).  The order of
@@ -611,12 +613,13 @@ int fb4o_layernorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t row_st
             s1 += v;
             s2 += v * v;
         }
-        double mean = s1 / (double)cols;
-        double var = fma(-mean, mean, s2 / (double)cols);
+        double inv_c = 1.0 / (double)cols;
+        double mean = s1 * inv_c;
+        double var = fma(-mean, mean, s2 * inv_c);
         if (var < 0.0) var = 0.0;
-        double rstd = 1.0 / sqrt(var + (double)eps);
-        float a = (float)rstd;
-        float b = (float)(-mean * rstd);
+        float v = (float)(var + (double)eps);
+        float a = 1.0f / sqrtf(v);
+        float b = -(float)mean * a;
         if (a_out) a_out[r] = a;
         if (b_out) b_out[r] = b;
         for (int64_t c = 0; c < cols; ++c) {

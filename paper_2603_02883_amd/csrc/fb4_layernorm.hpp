@@ -7,9 +7,10 @@
 // The producer is the textbook LayerNorm over the channels of a token with a
 // per-channel scale and shift; the quantizer's input is its result rounded to
 // bf16.  That rounding decides codes, so the precision of each step is fixed:
-//   S1 = sum x, S2 = sum x^2 in double (every term exact); mean = S1 / C;
-//   var = max(fma(-mean, mean, S2 / C), 0); r = 1 / sqrt(var + eps) in double;
-//   a = float(r), b = float(-mean * r);
+//   S1 = sum x, S2 = sum x^2 in double (every term exact); mean = S1 * (1/C),
+//   var = max(fma(-mean, mean, S2 * (1/C)), 0) in double;
+//   a = 1 / sqrt(float(var + eps)), b = -float(mean) * a in float (IEEE
+//   square root and divide);
 //   y = fmaf(fmaf(x, a, b), gamma, beta) in float, rounded to bf16 (nearest
 //   even); a NaN becomes the canonical quiet NaN 0x7FC0.
 // The sums are exact, hence independent of their order, whenever a row's values
@@ -43,13 +44,6 @@ struct LayerNormParams {
 constexpr int kLnThreads = 512;
 constexpr int kLnMaxChunksPerLane = 6;
 constexpr int kLdsLnTables = lds_fast_bytes(false, false, false);
-
-__device__ __forceinline__ double wave_sum(double v)
-{
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
-    return v;
-}
 
 // B: chunks per lane (the host picks it from the row length); gamma / beta may be null (1 / 0).
 template <int B, bool kTwoStage>
@@ -129,7 +123,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
     sp.meta = p.meta;
     sp.n_blocks = p.n_blocks;
     const bool meta_aligned = (reinterpret_cast<uintptr_t>(p.meta) & 15u) == 0;
-    const double n_channels = (double)p.cols;
+    const double inv_channels = 1.0 / (double)p.cols;
     const double eps = (double)p.eps;
 
     while (u < n_bundles) {
@@ -159,23 +153,35 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
         float a[B], b[B];
 #pragma unroll
         for (int j = 0; j < B; ++j) a[j] = b[j] = 0.0f;
-        for (uint32_t r = 0; r < rw; ++r) {
-            double c1 = 0.0, c2 = 0.0;
+        for (uint32_t r = 0; r < rw; r += 2) {   // two rows at a time: their exchange chains overlap
+            double c1[2] = {0.0, 0.0}, c2[2] = {0.0, 0.0};
 #pragma unroll
-            for (int j = 0; j < B; ++j) {
-                c1 += (valid[j] && rloc[j] == r) ? p1[j] : 0.0;
-                c2 += (valid[j] && rloc[j] == r) ? p2[j] : 0.0;
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int j = 0; j < B; ++j) {
+                    c1[h] += (valid[j] && rloc[j] == r + h) ? p1[j] : 0.0;
+                    c2[h] += (valid[j] && rloc[j] == r + h) ? p2[j] : 0.0;
+                }
             }
-            c1 = wave_sum(c1);
-            c2 = wave_sum(c2);
-            const double mean = c1 / n_channels;
-            double var = fma(-mean, mean, c2 / n_channels);
-            var = var < 0.0 ? 0.0 : var;   // (a NaN stays a NaN)
-            const double rstd = 1.0 / sqrt(var + eps);
-            const float ar = (float)rstd, br = (float)(-mean * rstd);
 #pragma unroll
-            for (int j = 0; j < B; ++j) {
-                if (ok[j] && rloc[j] == r) { a[j] = ar; b[j] = br; }   // (a chunk that does not exist keeps 0, 0)
+            for (int off = 1; off < 64; off <<= 1) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    c1[h] += __shfl_xor(c1[h], off);
+                    c2[h] += __shfl_xor(c2[h], off);
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const double mean = c1[h] * inv_channels;
+                double var = fma(-mean, mean, c2[h] * inv_channels);
+                var = var < 0.0 ? 0.0 : var;   // (a NaN stays a NaN)
+                const float ar = 1.0f / __builtin_sqrtf((float)(var + eps));
+                const float br = -(float)mean * ar;
+#pragma unroll
+                for (int j = 0; j < B; ++j) {
+                    if (ok[j] && rloc[j] == r + h) { a[j] = ar; b[j] = br; }   // (a chunk that does not exist keeps 0, 0)
+                }
             }
         }
         // ---- normalize, scale and shift, round to bf16, quantize, store

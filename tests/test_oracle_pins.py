@@ -757,13 +757,16 @@ def test_layernorm_invariants():
     yn, _, _ = O.layernorm(xb ^ 0x8000, gamma, None, eps=0.0)
     yp, _, _ = O.layernorm(xb, gamma, None, eps=0.0)
     assert np.array_equal(yn ^ 0x8000, yp)
-    # a constant row has variance 0: y = beta
+    # a constant row has variance 0: y = beta, up to what x * a + b leaves when mean / std is in the thousands
+    # (here 1.5 / 1e-3: the two terms cancel to about 1e-4 instead of to nothing)
     const = f2b(np.full((1, 256), 1.5))
-    yc, _, _ = O.layernorm(const, gamma, beta, eps=1e-6)
-    assert np.array_equal(yc[0], f2b(beta))
+    yc, ac, bc = O.layernorm(const, gamma, beta, eps=1e-6)
+    assert np.abs(b2f(yc[0]) - beta).max() <= 2.0 ** -7 * np.abs(beta).max() + 3e-4
+    assert abs(float(ac[0]) - 1000.0) < 1e-3 and abs(float(bc[0]) + 1500.0) < 1e-3
     # a zero row with gamma only: exactly zero
     yz, az, bz = O.layernorm(np.zeros((1, 256), dtype=np.uint16), gamma, None, eps=1e-6)
-    assert not (yz & 0x7FFF).any() and az[0] == np.float32(1000.0) and bz[0] == 0.0
+    assert not (yz & 0x7FFF).any() and bz[0] == 0.0
+    assert az[0] == np.float32(1.0) / np.sqrt(np.float32(1e-6)) and abs(float(az[0]) - 1000.0) < 1e-3
 
 
 def test_layernorm_rows_with_nan_or_inf_become_canonical_nan():
