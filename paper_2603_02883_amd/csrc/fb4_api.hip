@@ -674,16 +674,19 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
         return FB4_ERR_UNSUPPORTED;
     if ((uint64_t)rows * (uint64_t)nb >= 0x7F000000ull) return FB4_ERR_UNSUPPORTED;
     if ((rc = check_device(luts)) != FB4_OK) return rc;
-    // chunks per lane B and rows per bundle: the fullest wavefront, the fewest registers among equals
+    // Chunks per lane B and rows per bundle: the fullest wavefront among B <= 4 (the kernel keeps a bundle in
+    // registers: up to 3 chunks per lane fit, the 4th costs a few spilled registers, 5 and 6 -- rows longer
+    // than 8192 -- spill heavily and run at half the rate per element).
     int B = 0;
     uint32_t rw = 0;
     double best = 0.0;
-    for (int b = 1; b <= kLnMaxChunksPerLane; ++b) {
+    for (int b = 1; b <= 4; ++b) {
         if (nb > 64 * b) continue;
         const uint32_t r = (uint32_t)(64 * b / nb);
-        const double fill = (double)(r * nb) / (64.0 * b);
+        const double fill = (double)(r * nb) / (64.0 * b) - (b == 4 ? 0.05 : 0.0);
         if (fill > best + 1e-9) { best = fill; B = b; rw = r; }
     }
+    if (B == 0) { B = (int)((nb + 63) / 64); rw = 1; }
     if (rw > (uint32_t)rows) rw = (uint32_t)rows;
     const uint32_t n_bundles = (uint32_t)((rows + rw - 1) / rw);
     long long g = ((long long)n_bundles + 7) / 8;

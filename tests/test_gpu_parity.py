@@ -852,7 +852,7 @@ def _ln_case(F, luts, xb, gamma, beta, eps, flags=0, what="", x_dev=None):
     return c, m
 
 
-# rows x cols -> chunks per lane / rows per bundle the launcher picks: 3/2, 4/7 (ragged last bundle, bundles that
+# rows x cols -> chunks per lane / rows per bundle the launcher picks: 3/2, 3/5 (ragged last bundle, bundles that
 # do not fill the wavefront), 6/1, 1/64 cut to the row count, 2/1, 4/1, 5/1 with idle lanes, 1/2, 2/3
 LN_SHAPES = [(1024, 3072), (1000, 1152), (37, 12288), (5, 32), (129, 4096), (50, 8192), (33, 9600), (131, 1024),
              (77, 1344), (1, 3072), (513, 64)]
