@@ -36,9 +36,11 @@
  *   - MXFP8 operands: block size 32 maps one to one; with block size 16 the
  *     two blocks of an MX block share the larger exponent and the other
  *     block's magnitudes are shifted down and rounded to nearest even in E4M3;
- *   - a producer in front of the quantizer (App. E.2 names LayerNorm) hands
- *     the quantizer bf16 values; since that rounding decides codes, its
- *     arithmetic is fixed (see fb4o_layernorm) rather than done in double.
+ *   - a producer in front of the quantizer (App. E.2 names GeLU and
+ *     LayerNorm) hands the quantizer bf16 values; since that rounding decides
+ *     codes, LayerNorm's arithmetic is fixed (see fb4o_layernorm) rather than
+ *     done in double; GeLU is evaluated in double and rounded once, with
+ *     GeLU(-Inf) = -0 (the limit) and GeLU(NaN) = the quiet NaN 0x7FC0.
  *
  * Every routine here is pinned by tests/test_oracle_pins.py against hand-worked
  * fixtures, closed forms, exact rational brute force or torch's own number
@@ -47,6 +49,7 @@
  * not available), and how often the online rule and the exhaustive rule pick
  * the same dialect (the paper only says quality is comparable).
  */
+#define _GNU_SOURCE
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -628,6 +631,64 @@ int fb4o_layernorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t row_st
             float yf = fmaf(t, gamma ? gamma[c] : 1.0f, beta ? beta[c] : 0.0f);
             y[r * cols + c] = isnan(yf) ? (uint16_t)0x7FC0 : f32_to_bf16_rne(yf);
         }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* App. E.2: the other producer the paper names is GeLU.  Elementwise on bf16:
+ * the value in double, rounded once to bf16 (nearest even).
+ *   approximate == 0:  x * Phi(x) = 0.5 * x * erfc(-x / sqrt(2))
+ *   approximate == 1:  the tanh form 0.5 * x * (1 + tanh(u)),
+ *                      u = sqrt(2/pi) * (x + 0.044715 x^3), written as
+ *                      x / (1 + exp(-2u)) so that nothing cancels for x << 0
+ * GeLU(+Inf) = +Inf, GeLU(-Inf) = -0 (the limit), GeLU(NaN) = 0x7FC0. */
+static uint16_t f64_to_bf16_rne(double v)
+{
+    if (isnan(v)) return 0x7FC0;
+    uint16_t sign = signbit(v) ? 0x8000 : 0;
+    double a = fabs(v);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return (uint16_t)(sign | 0x7F80);
+    int ex;
+    (void)frexp(a, &ex); /* a = f * 2^ex, f in [0.5, 1) */
+    int e = ex - 1;      /* floor(log2 a) */
+    if (e < -126) {      /* subnormal range: steps of 2^-133 */
+        double q = rint(ldexp(a, 133));
+        return (uint16_t)(sign | (uint16_t)q); /* q == 128 is the smallest normal */
+    }
+    double q = rint(ldexp(a, 7 - e)); /* 128 .. 256 */
+    if (q >= 256.0) {
+        q = 128.0;
+        e += 1;
+    }
+    if (e + 127 >= 255) return (uint16_t)(sign | 0x7F80);
+    return (uint16_t)(sign | ((e + 127) << 7) | ((int)q - 128));
+}
+
+int fb4o_gelu(const uint16_t* x, int64_t n, int approximate, uint16_t* y)
+{
+    if ((!x || !y) && n > 0) return -1;
+    if (n < 0 || (approximate != 0 && approximate != 1)) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        double v = bf16_value(x[i]);
+        double r;
+        if (isnan(v)) {
+            y[i] = 0x7FC0;
+            continue;
+        }
+        if (isinf(v)) {
+            y[i] = v > 0 ? 0x7F80 : 0x8000;
+            continue;
+        }
+        if (approximate == 0) {
+            r = 0.5 * v * erfc(-v / sqrt(2.0));
+        } else {
+            double u = sqrt(2.0 / M_PI) * (v + 0.044715 * v * v * v);
+            r = v / (1.0 + exp(-2.0 * u));
+        }
+        y[i] = f64_to_bf16_rne(r);
+        if (v == 0.0) y[i] = x[i]; /* +-0 stays +-0 */
     }
     return 0;
 }

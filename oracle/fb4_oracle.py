@@ -51,6 +51,7 @@ def _load():
         lib.fb4o_dequantize.argtypes = [p, i32, i32, p, p, i64, i64, p, p, p, i64, p, i32, i64, i32]
         lib.fb4o_repack_mxfp8.argtypes = [p, i32, i32, p, p, i64, i64, p, p]
         lib.fb4o_layernorm.argtypes = [p, i64, i64, i64, p, p, ctypes.c_float, p, p, p]
+        lib.fb4o_gelu.argtypes = [p, i64, i32, p]
         _lib = lib
     return _lib
 
@@ -190,6 +191,17 @@ def layernorm(x_bits, gamma=None, beta=None, eps=1e-6):
     if rc != 0:
         raise ValueError("fb4o_layernorm: invalid argument")
     return y, a_out, b_out
+
+
+def gelu(x_bits, approximate=0):
+    """GeLU in front of the quantizer (App. E.2): elementwise on bf16 bit patterns, the value in double rounded
+    once.  approximate: 0 = x Phi(x), 1 = the tanh form.  Returns uint16 of the same shape."""
+    xb = np.ascontiguousarray(x_bits, dtype=np.uint16)
+    y = np.zeros(xb.shape, dtype=np.uint16)
+    rc = _load().fb4o_gelu(_ptr(xb), xb.size, int(approximate), _ptr(y))
+    if rc != 0:
+        raise ValueError("fb4o_gelu: invalid argument")
+    return y
 
 
 def seda_profile(fbk, meta, anchor_group, n_groups):

@@ -791,3 +791,75 @@ def test_layernorm_then_quantize_sees_unit_scale_blocks(fbk):
     assert np.isin(e, (0, 1)).mean() > 0.98 and e.max() <= 2 and e.min() >= -1
     _, m_raw = O.quantize(fbk, xb)
     assert ((m_raw >> 8).astype(int) - 127).min() >= 12
+
+
+# ------------------------------------------------- GeLU producer in front of the quantizer (App. E.2)
+ALL_BF16 = np.arange(65536, dtype=np.uint16)
+
+
+def _bf16_of_f64(v):
+    """float64 -> bf16 bits through torch (float64 -> float32 -> bf16; a double rounding that matters only
+    within 2^-29 of a tie, which no value below hits)."""
+    return torch.from_numpy(np.asarray(v, dtype=np.float64)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("approximate", [0, 1])
+def test_gelu_equals_the_library_routine_on_every_bf16_value_where_that_is_accurate(approximate):
+    y = O.gelu(ALL_BF16, approximate)
+    x = b2f(ALL_BF16)
+    ref = torch.nn.functional.gelu(torch.from_numpy(x), approximate="tanh" if approximate else "none").numpy()
+    # 0.5 x (1 + erf) / 0.5 x (1 + tanh) cancel for x << 0: the library's float64 result is good to the last
+    # bf16 bit down to about -5; the tail is pinned by the next test
+    ok = np.isfinite(x) & (x > -5.0)
+    assert np.array_equal(y[ok], _bf16_of_f64(ref[ok]))
+    # specials: NaN -> canonical quiet NaN, +Inf -> +Inf, -Inf -> -0 (the limit), signed zeros kept
+    nan = (ALL_BF16 & 0x7FFF) > 0x7F80
+    assert (y[nan] == 0x7FC0).all() and y[0x7F80] == 0x7F80 and y[0xFF80] == 0x8000
+    assert y[0x0000] == 0x0000 and y[0x8000] == 0x8000
+
+
+def test_gelu_negative_tail_against_bounds_and_the_other_closed_form():
+    x = b2f(ALL_BF16)
+    neg = np.isfinite(x) & (x <= -5.0)
+    t = -x[neg]
+    # exact form: x Phi(x); Mills-ratio bounds  phi(t) t / (t^2 + 1) < Phi(-t) < phi(t) / t
+    with np.errstate(under="ignore"):
+        phi = np.exp(-0.5 * t * t) / math.sqrt(2.0 * math.pi)
+        lo = t * phi * t / (t * t + 1.0)        # |y| lower bound
+        hi = phi                                 # |y| upper bound (t * phi / t)
+    y = -b2f(O.gelu(ALL_BF16[neg], 0))
+    step = 1.0 + 2.0 ** -7
+    tiny = 2.0 ** -133                           # the smallest bf16 step near zero
+    assert (y <= hi * step + tiny).all() and (y >= lo / step - tiny).all()
+    # tanh form: 0.5 x (1 + tanh u) = x e^{2u} / (1 + e^{2u}), accurate for u << 0
+    u = math.sqrt(2.0 / math.pi) * (x[neg] + 0.044715 * x[neg] ** 3)
+    with np.errstate(under="ignore"):
+        e2 = np.exp(2.0 * u)
+        ref = x[neg] * e2 / (1.0 + e2)
+    assert np.array_equal(O.gelu(ALL_BF16[neg], 1), _bf16_of_f64(ref) | np.uint16(0x8000))
+
+
+@pytest.mark.parametrize("approximate", [0, 1])
+def test_gelu_shape_of_the_function(approximate):
+    y = b2f(O.gelu(ALL_BF16, approximate))
+    x = b2f(ALL_BF16)
+    fin = np.isfinite(x)
+    pos = fin & (x >= 0)
+    # identity from x = 8 upwards (1 - Phi(8) is far below half a bf16 step), x / 2 near zero
+    big = pos & (x >= 8.0)
+    assert np.array_equal(O.gelu(ALL_BF16[big], approximate), ALL_BF16[big])
+    small = fin & (np.abs(x) < 2.0 ** -12) & (np.abs(x) >= 2.0 ** -120)
+    assert np.array_equal(y[small], x[small] / 2)
+    # GeLU(x) - GeLU(-x) = x, up to the two roundings
+    a = ALL_BF16[pos]
+    d = y[a] - y[a | 0x8000]
+    assert (np.abs(d - x[pos]) <= 2.0 ** -7 * x[pos] + 2.0 ** -133).all()
+    # increasing on x >= 0, bounded below by about -0.17 (attained near x = -0.75), never positive for x < 0
+    assert (np.diff(y[pos][np.argsort(x[pos], kind="stable")]) >= 0).all()
+    negv = y[fin & (x < 0)]
+    assert negv.max() <= 0 and abs(negv.min() + 0.17) < 0.005
+    assert abs(x[fin & (x < 0)][np.argmin(negv)] + 0.75) < 0.1      # (flat at bf16 resolution around the minimum)
+    # one worked value: GeLU(1) = 0.841345 (exact form), 0.841192 (tanh form) -> both bf16 0x3F57 = 0.83984375
+    assert O.gelu(f2b([1.0]), approximate)[0] == 0x3F57
+    # ... and one where the two forms differ: GeLU(3) = 2.995950 -> 0x4040 (3.0); tanh form 2.996363 -> 0x4040
+    assert O.gelu(f2b([-2.0]), 0)[0] == f2b([-0.04550026])[0] and O.gelu(f2b([-2.0]), 1)[0] == f2b([-0.04540231])[0]
