@@ -281,6 +281,36 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
                            int64_t cols, int64_t row_stride, const float* gamma, const float* beta,
                            float eps, uint8_t* codes, uint16_t* meta, void* stream);
 
+/*
+ * App. E.2, the other producer the paper names: GeLU of every element, then
+ * fb4_quantize of the result, in one pass -- x is read once and GeLU(x) is
+ * never written.  What gets quantized is GeLU(x) evaluated in double and
+ * rounded once to bf16 (nearest even); the library tabulates that for all
+ * 65536 bf16 patterns when the handle is built.  GeLU(+Inf) = +Inf,
+ * GeLU(-Inf) = -0 (the limit), GeLU(NaN) = the quiet NaN 0x7FC0, signed zeros
+ * are kept.
+ *   approximate  0: x * Phi(x) = 0.5 x erfc(-x / sqrt 2)
+ *                1: the tanh form 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))
+ *                anything else FB4_ERR_INVALID_ARG
+ *   opts         block 32, FB4_SEL_LUT with 8 groups (FB4_FLAG_TWO_STAGE allowed);
+ *                anything else FB4_ERR_UNSUPPORTED
+ *   codes        device, 16-byte aligned (FB4_ERR_UNSUPPORTED otherwise)
+ */
+int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
+                      int64_t cols, int64_t row_stride, int approximate, uint8_t* codes,
+                      uint16_t* meta, void* stream);
+
+/*
+ * The table fb4_gelu_quantize looks GeLU up in, for inspection without a GPU:
+ * entry k is GeLU of the bf16 value with bit pattern k, for k = 0 .. 0xC180
+ * (the positive patterns, then the negative ones down to -16.0; every value
+ * below -16 shares the entry of -16, which is -0).
+ *   table     host, uint16 [capacity]; capacity >= 49537 entries
+ *             (FB4_ERR_INVALID_ARG otherwise)
+ *   entries   host, optional: receives 49537
+ */
+int fb4_gelu_table_host(int approximate, uint16_t* table, size_t capacity, size_t* entries);
+
 #ifdef __cplusplus
 }
 #endif

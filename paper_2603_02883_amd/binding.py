@@ -67,6 +67,8 @@ def _load():
     lib.fb4_quantize_decompose.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, i32, p, i64, p, p, p, p, p]
     lib.fb4_seda_profile.argtypes = [p, p, i64, i64, p, i32, p, p, p]
     lib.fb4_repack_mxfp8.argtypes = [p, p, p, i64, i64, i32, p, i64, p, p]
+    lib.fb4_gelu_table_host.argtypes = [i32, p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+    lib.fb4_gelu_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, i32, p, p, p]
     lib.fb4_layernorm_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, ctypes.c_float, p, p, p]
     return lib
 
@@ -76,7 +78,8 @@ _lib = _load()
 EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts", "fb4_build_luts_host",
            "fb4_free_luts", "fb4_quantize", "fb4_quantize_seda", "fb4_decompose", "fb4_dequantize",
            "fb4_quantize_decompose", "fb4_seda_profile",
-           "fb4_repack_mxfp8", "fb4_layernorm_quantize"]
+           "fb4_repack_mxfp8", "fb4_layernorm_quantize", "fb4_gelu_quantize",
+           "fb4_gelu_table_host"]
 
 
 def lib():
@@ -184,6 +187,30 @@ def fb4_layernorm_quantize(luts, o, x, gamma=None, beta=None, eps=1e-6, codes=No
                                      x.stride(0) if rows > 1 else cols, _dp(gamma), _dp(beta), float(eps),
                                      _dp(codes), _dp(meta), _stream(stream))
     _check(rc, "fb4_layernorm_quantize")
+    return codes, meta
+
+
+def fb4_gelu_table_host(approximate=0):
+    """The library's GeLU table as a uint16 numpy array (no GPU needed): entry k = GeLU of bit pattern k."""
+    n = ctypes.c_size_t(0)
+    _lib.fb4_gelu_table_host(int(approximate), None, 0, ctypes.byref(n))
+    t = np.zeros(n.value, dtype=np.uint16)
+    _check(_lib.fb4_gelu_table_host(int(approximate), t.ctypes.data_as(ctypes.c_void_p), t.size, ctypes.byref(n)),
+           "fb4_gelu_table_host")
+    return t
+
+
+def fb4_gelu_quantize(luts, o, x, approximate=0, codes=None, meta=None, stream=None):
+    """GeLU of every element (approximate: 0 = x Phi(x), 1 = the tanh form), then quantize, in one pass.
+    Returns (codes, meta)."""
+    rows, cols = x.shape
+    if codes is None:
+        codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
+    if meta is None:
+        meta = torch.empty((rows, cols // o.block), dtype=torch.int16, device=x.device)
+    rc = _lib.fb4_gelu_quantize(luts.handle, ctypes.byref(o), _dp(x), rows, cols, x.stride(0) if rows > 1 else cols,
+                                int(approximate), _dp(codes), _dp(meta), _stream(stream))
+    _check(rc, "fb4_gelu_quantize")
     return codes, meta
 
 

@@ -9,6 +9,7 @@
 #include "../../include/fb4.h"
 #include "fb4_dequant_fast.hpp"
 #include "fb4_fast.hpp"
+#include "fb4_gelu.hpp"
 #include "fb4_kernels.hpp"
 #include "fb4_layernorm.hpp"
 #include "fb4_profile.hpp"
@@ -39,6 +40,19 @@ int check_device(const fb4_luts* l)
         return FB4_ERR_HIP;
     }
     return dev == l->device ? FB4_OK : FB4_ERR_INVALID_ARG;
+}
+
+// The two GeLU tables, evaluated once per process (about 100,000 calls of erfc / exp).
+const uint16_t* gelu_tables()
+{
+    static const uint16_t* tables = []() -> const uint16_t* {
+        uint16_t* t = static_cast<uint16_t*>(std::malloc(2 * kGeluTableBytes));
+        if (!t) return nullptr;
+        build_gelu_table(false, t);
+        build_gelu_table(true, t + kGeluTableBytes / 2);
+        return t;
+    }();
+    return tables;
 }
 
 int grid_for(const fb4_luts* l, long long n_tiles)
@@ -338,12 +352,21 @@ int fb4_build_luts(const uint8_t* formatbook, int n_dialects, fb4_luts** out)
         return FB4_ERR_HIP;
     }
     l->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    if (hipMalloc(reinterpret_cast<void**>(&l->dev_blob), kBlobBytes) != hipSuccess) {
+    // one allocation: the table blob, then the two GeLU tables (exact form, tanh form) of fb4_gelu_quantize
+    if (hipMalloc(reinterpret_cast<void**>(&l->dev_blob), kBlobBytes + 2 * kGeluTableBytes) != hipSuccess) {
         (void)hipGetLastError();
         delete l;
         return FB4_ERR_ALLOC;
     }
-    if (hipMemcpy(l->dev_blob, l->host_blob, kBlobBytes, hipMemcpyHostToDevice) != hipSuccess) {
+    const uint16_t* gelu = gelu_tables();
+    if (!gelu) {
+        (void)hipFree(l->dev_blob);
+        delete l;
+        return FB4_ERR_ALLOC;
+    }
+    if (hipMemcpy(l->dev_blob, l->host_blob, kBlobBytes, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(l->dev_blob + kBlobBytes, gelu, 2 * kGeluTableBytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
         (void)hipFree(l->dev_blob);
         delete l;
         return FB4_ERR_HIP;
@@ -714,6 +737,48 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
 #undef FB4_LN_CASE
 #undef FB4_LN_ARGS
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
+                      int64_t row_stride, int approximate, uint8_t* codes, uint16_t* meta, void* stream)
+{
+    int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
+    if (rc != FB4_OK) return rc;
+    if (approximate != 0 && approximate != 1) return FB4_ERR_INVALID_ARG;
+    if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8) return FB4_ERR_UNSUPPORTED;
+    if (rows == 0 || cols == 0) return FB4_OK;
+    if (!aligned(codes, 16)) return FB4_ERR_UNSUPPORTED;
+    const uint64_t nb = (uint64_t)cols / 32;
+    const uint64_t n_blocks = (uint64_t)rows * nb;
+    if (n_blocks >= 0x7F000000ull) return FB4_ERR_UNSUPPORTED;
+    if ((rc = check_device(luts)) != FB4_OK) return rc;
+    const uint32_t n_tiles = (uint32_t)((n_blocks + 63) / 64);
+    uint32_t l = 0;
+    while ((1ull << l) < nb) ++l;
+    const uint32_t div_shift = 31 + l;
+    const uint32_t div_mul = (uint32_t)(((1ull << div_shift) + nb - 1) / nb);
+    long long g = ((long long)n_tiles + 7) / 8;
+    if (g > luts->n_cu) g = luts->n_cu;
+    const unsigned groups = (unsigned)g;
+    GeluParams p = {codes, meta};
+    const uint16_t* table = reinterpret_cast<const uint16_t*>(luts->dev_blob + kBlobBytes + (approximate ? kGeluTableBytes : 0));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define FB4_GELU_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), table, (uint32_t)n_blocks, n_tiles, div_mul, div_shift, (uint32_t)nb, groups, (long long)row_stride, p
+    if (opts->flags & FB4_FLAG_TWO_STAGE) hipLaunchKernelGGL((gelu_quantize_kernel<true>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
+    else hipLaunchKernelGGL((gelu_quantize_kernel<false>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
+#undef FB4_GELU_ARGS
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+int fb4_gelu_table_host(int approximate, uint16_t* table, size_t capacity, size_t* entries)
+{
+    if (entries) *entries = kGeluEntries;
+    if (approximate != 0 && approximate != 1) return FB4_ERR_INVALID_ARG;
+    if (!table || capacity < kGeluEntries) return FB4_ERR_INVALID_ARG;
+    const uint16_t* t = gelu_tables();
+    if (!t) return FB4_ERR_ALLOC;
+    std::memcpy(table, t + (approximate ? kGeluTableBytes / 2 : 0), kGeluEntries * 2);
+    return FB4_OK;
 }
 
 }  // extern "C"

@@ -237,3 +237,20 @@ def test_header_is_plain_c(tmp_path):
     cpp = tmp_path / "use_fb4.cpp"
     cpp.write_text(src.read_text())
     subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)], check=True)
+
+
+def test_gelu_table_equals_the_oracle_on_every_pattern_it_covers():
+    """The host-built table of fb4_gelu_quantize against the oracle's GeLU: every positive bf16 pattern, every
+    negative one down to -16, and everything below -16 (which shares the entry of -16) is -0 in the oracle too."""
+    from oracle import fb4_oracle as O
+    allb = np.arange(65536, dtype=np.uint16)
+    for approximate in (0, 1):
+        t = F.fb4_gelu_table_host(approximate)
+        assert t.size == 0xC181
+        ref = O.gelu(allb, approximate)
+        assert np.array_equal(t, ref[:0xC181])
+        beyond = allb[(allb > 0xC180) & (allb <= 0xFF80)]            # -16 > x >= -Inf
+        assert (ref[beyond] == 0x8000).all() and t[0xC180] == 0x8000
+        assert (ref[allb > 0xFF80] == 0x7FC0).all()                   # negative NaNs: patched in the kernel
+    with pytest.raises(F.Fb4Error):
+        F.fb4_gelu_table_host(2)

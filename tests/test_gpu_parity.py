@@ -929,3 +929,76 @@ def test_layernorm_quantize_is_the_unfused_pair_and_rejects_what_it_does_not_ser
         F.fb4_layernorm_quantize(luts, F.opts(), big)
     assert e.value.code == F.ERR_UNSUPPORTED
     F.fb4_layernorm_quantize(luts, F.opts(), x[:0])           # no rows: a successful no-op
+
+
+# ------------------------------------------------- GeLU fused in front of the quantizer (App. E.2)
+def _gelu_case(F, luts, xb, approximate, flags=0, what="", x_dev=None, rows=None):
+    """rows: compare these rows only (the oracle runs on them alone)."""
+    x = dev_bits(xb) if x_dev is None else x_dev
+    o = F.opts(selector=1, num_groups=8, flags=flags)
+    c, m = F.fb4_gelu_quantize(luts, o, x, approximate)
+    torch.cuda.synchronize()
+    cg, mg = host_u8(c), host_u16(m)
+    if rows is not None:
+        xb, cg, mg = xb[rows], cg[rows], mg[rows]
+    y = O.gelu(xb, approximate)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, y, selector=1, num_groups=8, flags=flags)
+    compare_quant(DEFAULT_FORMATBOOK, y, cg, mg, cr, mr, 1, 8, flags=flags, what="gelu " + what)
+    return c, m
+
+
+@pytest.mark.parametrize("approximate", [0, 1])
+def test_gelu_quantize_shapes_and_full_size(F, luts, approximate):
+    for rows, cols in [(1024, 3072), (333, 1184), (1, 32), (7, 64), (65, 12288), (129, 4096)]:
+        x = synth.vdit_activation(rows=rows, cols=cols, seed=rows + cols, device="cuda")
+        _gelu_case(F, luts, synth.bf16_bits(x), approximate, what="%dx%d" % (rows, cols), x_dev=x)
+    x = synth.vdit_activation(device="cuda")                  # 16384 x 3072, the benchmark workload
+    xb = synth.bf16_bits(x)
+    _gelu_case(F, luts, xb, approximate, what="cfg2", x_dev=x)
+    _gelu_case(F, luts, xb, approximate, flags=F.FLAG_TWO_STAGE, what="cfg2 two-stage", x_dev=x)
+
+
+def test_gelu_quantize_cfg5_sampled_rows(F, luts):
+    R5, C5 = synth.CONFIG_SHAPES["cfg5"]                       # 65536 x 12288: the input of mlp.fc2
+    x = synth.vdit_activation(rows=R5, cols=C5, seed=5, device="cuda", outlier_frac=0.01)
+    rows = np.unique(np.concatenate([np.arange(0, 64), np.arange(R5 - 64, R5),
+                                     np.random.default_rng(5).integers(0, R5, 384)]))
+    xb = np.zeros((R5, C5), dtype=np.uint16)
+    xb[rows] = synth.bf16_bits(x[torch.from_numpy(rows).cuda()])
+    _gelu_case(F, luts, xb, 1, what="cfg5", x_dev=x, rows=rows)
+    del x
+
+
+def test_gelu_quantize_degenerate_values_strides_and_errors(F, luts):
+    xe = synth.edge_case_tensor(cols=256).copy()               # zeros, subnormals, +-Inf, NaNs of both signs, 1e30
+    xe[2, 9] = 0xFFFF; xe[2, 200] = 0xFF81; xe[12, 3] = 0xC180; xe[12, 4] = 0xC181; xe[12, 5] = 0x4180; xe[12, 6] = 0x7F7F
+    for approximate in (0, 1):
+        _gelu_case(F, luts, xe, approximate, what="edge rows")
+        _gelu_case(F, luts, xe, approximate, flags=F.FLAG_TWO_STAGE, what="edge rows two-stage")
+    # every bf16 pattern once
+    allb = np.arange(65536, dtype=np.uint16).reshape(32, 2048)
+    _gelu_case(F, luts, allb, 0, what="all patterns")
+    _gelu_case(F, luts, allb, 1, what="all patterns, tanh form")
+    # a row stride, outputs that are only 16 / 2 byte aligned
+    wide = synth.vdit_activation(rows=70, cols=3072 + 64, seed=6, device="cuda")
+    xs = wide[:, 32:32 + 3072]
+    cbuf = torch.zeros(70 * 1536 + 16, dtype=torch.uint8, device="cuda")
+    mbuf = torch.zeros(70 * 96 + 1, dtype=torch.int16, device="cuda")
+    c = cbuf[16:].view(70, 1536); m = mbuf[1:].view(70, 96)
+    F.fb4_gelu_quantize(luts, F.opts(), xs, 1, codes=c, meta=m)
+    torch.cuda.synchronize()
+    y = O.gelu(synth.bf16_bits(xs.contiguous()), 1)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, y)
+    assert np.array_equal(host_u8(c), cr) and np.array_equal(host_u16(m), mr)
+    assert not cbuf[:16].any() and mbuf[0] == 0
+    # what it does not serve
+    x = synth.gaussian_outlier(rows=64, cols=1024, seed=8, device="cuda")
+    for o, code in ((F.opts(block=16), F.ERR_UNSUPPORTED), (F.opts(num_groups=16), F.ERR_UNSUPPORTED),
+                    (F.opts(selector=0), F.ERR_UNSUPPORTED)):
+        with pytest.raises(F.Fb4Error) as e:
+            F.fb4_gelu_quantize(luts, o, x)
+        assert e.value.code == code
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_gelu_quantize(luts, F.opts(), x, approximate=2)
+    assert e.value.code == F.ERR_INVALID_ARG
+    F.fb4_gelu_quantize(luts, F.opts(), x[:0])                 # no rows: a successful no-op
