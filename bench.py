@@ -203,6 +203,10 @@ def main():
             F.fb4_dequantize(luts, codes[k], metas[k], out=outs[i % 2])
             F.fb4_dequantize(luts, codes[k], metas[k], codes2=c2, meta2=m2, salient_rows=sal_d, out=outs[i % 2])
             F.fb4_repack_mxfp8(luts, codes[k], metas[k], elems=els[i % 2], scales=scs[i % 2])
+        # GeLU + quantizer in one pass
+        for i in range(4):
+            k = i % N_SETS
+            F.fb4_gelu_quantize(luts, o, xs[k], 1, codes=codes[k], meta=metas[k])
         # LayerNorm + quantizer in one pass
         gamma_h, beta_h = synth.layernorm_affine(COLS)
         gamma_d, beta_d = torch.from_numpy(gamma_h).cuda(), torch.from_numpy(beta_h).cuda()
@@ -295,6 +299,17 @@ def main():
             y = torch.nn.functional.layer_norm(xs[k], (COLS,), gamma_b, beta_b, 1e-6)
             F.fb4_quantize(luts, o_main, y, codes=codes[k], meta=metas[k])
         add("layernorm_by_torch_then_quantize", ln_unfused_step, abytes + 2 * n_el * 2, n_el)
+        # GeLU fused in front of the quantizer, against the framework's GeLU followed by the quantizer
+        def gelu_step(i):
+            k = i % N_SETS
+            F.fb4_gelu_quantize(luts, o_main, xs[k], 1, codes=codes[k], meta=metas[k])
+        add("gelu_quantize_one_pass", gelu_step, abytes, n_el)
+
+        def gelu_unfused_step(i):
+            k = i % N_SETS
+            y = torch.nn.functional.gelu(xs[k], approximate="tanh")
+            F.fb4_quantize(luts, o_main, y, codes=codes[k], meta=metas[k])
+        add("gelu_by_torch_then_quantize", gelu_unfused_step, abytes + 2 * n_el * 2, n_el)
         # SeDA (cfg4)
         xm, comp = synth.mixture_activation(rows=ROWS, cols=COLS, seed=4, device="cuda")
         xms = [xm] + [xm.clone() for _ in range(N_SETS - 1)]
@@ -389,6 +404,10 @@ def main():
         def cfg5_step(i):
             F.fb4_quantize(luts, o_main, x5, codes=c5, meta=m5)
         add("cfg5_quantize_lut_g8_65536x12288", cfg5_step, algorithmic_bytes(R5, C5), R5 * C5, steps=10)
+
+        def cfg5_gelu_step(i):
+            F.fb4_gelu_quantize(luts, o_main, x5, 1, codes=c5, meta=m5)
+        add("cfg5_gelu_quantize_one_pass", cfg5_gelu_step, algorithmic_bytes(R5, C5), R5 * C5, steps=10)
         sal5 = synth.salient_rows_from_attention(R5, frac=0.05, heads=24, seed=5, device="cuda", window=1024)
         sal5_d = torch.from_numpy(sal5).cuda()
         c52 = torch.empty((sal5.size, C5 // 2), dtype=torch.uint8, device="cuda")

@@ -24,6 +24,10 @@ namespace fb4 {
 constexpr uint32_t kGeluClamp = 0xC180u;                          // -16.0
 constexpr uint32_t kGeluEntries = kGeluClamp + 1u;                // 49537
 constexpr uint32_t kGeluTableBytes = ((kGeluEntries * 2u + 15u) / 16u) * 16u;   // 99088
+// Runs of the table that follow from the bit pattern alone (both forms of GeLU; multiples of 8 entries):
+// magnitudes [kGeluSubnormalEnd, kGeluHalfEnd) of either sign map to pattern - 0x80 (x / 2), positive
+// patterns from kGeluIdentityBegin to +Inf map to themselves.
+constexpr int kGeluSubnormalEnd = 0x0100, kGeluHalfEnd = 0x3B00, kGeluIdentityBegin = 0x4038;
 
 // ---- host: the table
 // double -> bf16 bits, one rounding to nearest even, from the bits of the double.
@@ -121,18 +125,41 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
     if (kTwoStage && threadIdx.x < 64)
         reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] = reinterpret_cast<const uint32_t*>(blob + kOffRangeExcl)[threadIdx.x];
     {
-        constexpr int kPieces = kGeluTableBytes / 16;   // 6193
-        const uint4* src = reinterpret_cast<const uint4*>(table);
+        // Most of the table follows from the bit pattern: GeLU(x) rounds to x / 2 (pattern - 0x80) for
+        // 2^-125 <= |x| < 2^-9.25, to x from 2.875 upwards, a positive NaN gives the quiet NaN.  Only the
+        // 16-byte pieces outside these runs are read from memory, at most one per thread.
+        constexpr int kPieces = kGeluTableBytes / 16;   // 6193 pieces of 8 entries
+        constexpr int kSub = kGeluSubnormalEnd / 8, kHalf = kGeluHalfEnd / 8, kIdent = kGeluIdentityBegin / 8;
+        constexpr int kNeg = 0x8000 / 8;
+        constexpr int kRunA = kSub, kRunB = kIdent - kHalf, kRunC = kSub, kRunD = kPieces - (kNeg + kHalf);
+        static_assert(kRunA + kRunB + kRunC + kRunD <= kGeluThreads, "one loaded piece per thread");
+        int mine = -1;   // the piece this thread reads
+        const int tid = threadIdx.x;
+        if (tid < kRunA) mine = tid;
+        else if (tid < kRunA + kRunB) mine = kHalf + (tid - kRunA);
+        else if (tid < kRunA + kRunB + kRunC) mine = kNeg + (tid - kRunA - kRunB);
+        else if (tid < kRunA + kRunB + kRunC + kRunD) mine = kNeg + kHalf + (tid - kRunA - kRunB - kRunC);
+        const uint4 loaded = reinterpret_cast<const uint4*>(table)[mine < 0 ? 0 : mine];
         uint4* dst = reinterpret_cast<uint4*>(lds + kLdsGelu);
-        for (int i = threadIdx.x; i < kPieces; i += 4 * kGeluThreads) {
-            // four requests in flight per thread (clamped, not predicated), then the four writes
-            uint4 v[4];
+        for (int i = tid; i < kPieces; i += kGeluThreads) {
+            const int ip = i & (kNeg - 1);   // piece index within its sign
+            const bool from_memory = ip < kSub || (i < kNeg ? (ip >= kHalf && ip < kIdent) : ip >= kHalf);
+            if (from_memory) continue;
+            uint32_t e[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = src[min(i + k * kGeluThreads, kPieces - 1)];
+            for (int j = 0; j < 4; ++j) {
+                uint32_t pair = 0;
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (i + k * kGeluThreads < kPieces) dst[i + k * kGeluThreads] = v[k];
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t k = 8u * i + 2u * j + h;
+                    const uint32_t v = ip < kHalf ? k - 0x80u : (k <= 0x7F80u ? k : 0x7FC0u);
+                    pair |= v << (16 * h);
+                }
+                e[j] = pair;
+            }
+            dst[i] = make_uint4(e[0], e[1], e[2], e[3]);
         }
+        if (mine >= 0) dst[mine] = loaded;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < 1024; i += kGeluThreads) {   // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4

@@ -252,5 +252,12 @@ def test_gelu_table_equals_the_oracle_on_every_pattern_it_covers():
         beyond = allb[(allb > 0xC180) & (allb <= 0xFF80)]            # -16 > x >= -Inf
         assert (ref[beyond] == 0x8000).all() and t[0xC180] == 0x8000
         assert (ref[allb > 0xFF80] == 0x7FC0).all()                   # negative NaNs: patched in the kernel
+        # the runs the kernel fills in from the bit pattern instead of reading them: x / 2 for 2^-125 <= |x| <
+        # 2^-9.25, x from 2.875 upwards, the quiet NaN for positive NaNs
+        k = np.arange(0xC181)
+        half = ((k & 0x7FFF) >= 0x0100) & ((k & 0x7FFF) < 0x3B00)
+        assert np.array_equal(t[half], (k[half] - 0x80).astype(np.uint16))
+        ident = (k >= 0x4038) & (k <= 0x7F80)
+        assert np.array_equal(t[ident], k[ident].astype(np.uint16)) and (t[0x7F81:0x8000] == 0x7FC0).all()
     with pytest.raises(F.Fb4Error):
         F.fb4_gelu_table_host(2)
