@@ -737,10 +737,14 @@ def test_entry_points_replay_correctly_from_a_hip_graph(F, luts):
         F.fb4_quantize_seda(luts, o, x, tg, sub, codes=cs, meta=ms)
         F.fb4_decompose(luts, o, x, c1, m1, sal, codes2=c2b, meta2=m2b)
         F.fb4_quantize(luts, o_sse, x, codes=c3, meta=m3)
+        F.fb4_layernorm_quantize(luts, o, x, gamma, beta, 1e-6, codes=c4, meta=m4)
+        F.fb4_gelu_quantize(luts, o, x, 1, codes=c5, meta=m5)
 
     c2b, m2b, c3, m3 = torch.empty_like(c2), torch.empty_like(m2), torch.empty_like(c1), torch.empty_like(m1)
+    c4, m4, c5, m5 = torch.empty_like(c1), torch.empty_like(m1), torch.empty_like(c1), torch.empty_like(m1)
+    gamma, beta = (torch.from_numpy(a).cuda() for a in synth.layernorm_affine(cols, seed=70))
     o_sse = F.opts(selector=F.SEL_SSE)
-    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms, c2b, m2b, c3, m3)
+    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms, c2b, m2b, c3, m3, c4, m4, c5, m5)
     x.copy_(synth.vdit_activation(rows=rows, cols=cols, seed=70, device="cuda"))
     sequence()                                                # warm-up outside the capture
     torch.cuda.synchronize()
