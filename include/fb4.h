@@ -275,11 +275,16 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
  *   cols        a multiple of 32, at most 12288 (FB4_ERR_UNSUPPORTED otherwise)
  *   gamma,beta  device, float [cols]; NULL = all ones / all zeros
  *   eps         >= 0 (FB4_ERR_INVALID_ARG otherwise)
+ *   token_group, sub_formatbooks, n_groups
+ *               Sec. 3.4, as in fb4_quantize_seda (the paper applies SeDA to
+ *               mlp.fc1, whose input this is); all NULL / 0 = full formatbook;
+ *               at most 255 groups (FB4_ERR_UNSUPPORTED beyond)
  *   codes       device, 16-byte aligned (FB4_ERR_UNSUPPORTED otherwise)
  */
 int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
                            int64_t cols, int64_t row_stride, const float* gamma, const float* beta,
-                           float eps, uint8_t* codes, uint16_t* meta, void* stream);
+                           float eps, const int32_t* token_group, const uint8_t* sub_formatbooks,
+                           int n_groups, uint8_t* codes, uint16_t* meta, void* stream);
 
 /*
  * App. E.2, the other producer the paper names: GeLU of every element, then
@@ -294,11 +299,16 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
  *                anything else FB4_ERR_INVALID_ARG
  *   opts         block 32, FB4_SEL_LUT with 8 groups (FB4_FLAG_TWO_STAGE allowed);
  *                anything else FB4_ERR_UNSUPPORTED
+ *   token_group, sub_formatbooks, n_groups
+ *                Sec. 3.4, as in fb4_quantize_seda (the paper applies SeDA to
+ *                mlp.fc2, whose input this is); all NULL / 0 = full formatbook;
+ *                at most 255 groups (FB4_ERR_UNSUPPORTED beyond)
  *   codes        device, 16-byte aligned (FB4_ERR_UNSUPPORTED otherwise)
  */
 int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
-                      int64_t cols, int64_t row_stride, int approximate, uint8_t* codes,
-                      uint16_t* meta, void* stream);
+                      int64_t cols, int64_t row_stride, int approximate, const int32_t* token_group,
+                      const uint8_t* sub_formatbooks, int n_groups, uint8_t* codes, uint16_t* meta,
+                      void* stream);
 
 /*
  * The table fb4_gelu_quantize looks GeLU up in, for inspection without a GPU:

@@ -68,8 +68,9 @@ def _load():
     lib.fb4_seda_profile.argtypes = [p, p, i64, i64, p, i32, p, p, p]
     lib.fb4_repack_mxfp8.argtypes = [p, p, p, i64, i64, i32, p, i64, p, p]
     lib.fb4_gelu_table_host.argtypes = [i32, p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
-    lib.fb4_gelu_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, i32, p, p, p]
-    lib.fb4_layernorm_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, ctypes.c_float, p, p, p]
+    lib.fb4_gelu_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, i32, p, p, i32, p, p, p]
+    lib.fb4_layernorm_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, ctypes.c_float, p, p, i32,
+                                           p, p, p]
     return lib
 
 
@@ -175,9 +176,10 @@ def fb4_quantize(luts, o, x, codes=None, meta=None, stream=None):
     return codes, meta
 
 
-def fb4_layernorm_quantize(luts, o, x, gamma=None, beta=None, eps=1e-6, codes=None, meta=None, stream=None):
+def fb4_layernorm_quantize(luts, o, x, gamma=None, beta=None, eps=1e-6, codes=None, meta=None, stream=None,
+                           token_group=None, sub_formatbooks=None):
     """LayerNorm over the channels of each row (gamma, beta: float32 cuda [cols] or None), then quantize, in one
-    pass.  Returns (codes, meta)."""
+    pass; token_group / sub_formatbooks as in fb4_quantize_seda (optional).  Returns (codes, meta)."""
     rows, cols = x.shape
     if codes is None:
         codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
@@ -185,6 +187,8 @@ def fb4_layernorm_quantize(luts, o, x, gamma=None, beta=None, eps=1e-6, codes=No
         meta = torch.empty((rows, cols // o.block), dtype=torch.int16, device=x.device)
     rc = _lib.fb4_layernorm_quantize(luts.handle, ctypes.byref(o), _dp(x), rows, cols,
                                      x.stride(0) if rows > 1 else cols, _dp(gamma), _dp(beta), float(eps),
+                                     _dp(token_group), _dp(sub_formatbooks),
+                                     0 if sub_formatbooks is None else sub_formatbooks.shape[0],
                                      _dp(codes), _dp(meta), _stream(stream))
     _check(rc, "fb4_layernorm_quantize")
     return codes, meta
@@ -200,16 +204,19 @@ def fb4_gelu_table_host(approximate=0):
     return t
 
 
-def fb4_gelu_quantize(luts, o, x, approximate=0, codes=None, meta=None, stream=None):
-    """GeLU of every element (approximate: 0 = x Phi(x), 1 = the tanh form), then quantize, in one pass.
-    Returns (codes, meta)."""
+def fb4_gelu_quantize(luts, o, x, approximate=0, codes=None, meta=None, stream=None, token_group=None,
+                      sub_formatbooks=None):
+    """GeLU of every element (approximate: 0 = x Phi(x), 1 = the tanh form), then quantize, in one pass;
+    token_group / sub_formatbooks as in fb4_quantize_seda (optional).  Returns (codes, meta)."""
     rows, cols = x.shape
     if codes is None:
         codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
     if meta is None:
         meta = torch.empty((rows, cols // o.block), dtype=torch.int16, device=x.device)
     rc = _lib.fb4_gelu_quantize(luts.handle, ctypes.byref(o), _dp(x), rows, cols, x.stride(0) if rows > 1 else cols,
-                                int(approximate), _dp(codes), _dp(meta), _stream(stream))
+                                int(approximate), _dp(token_group), _dp(sub_formatbooks),
+                                0 if sub_formatbooks is None else sub_formatbooks.shape[0],
+                                _dp(codes), _dp(meta), _stream(stream))
     _check(rc, "fb4_gelu_quantize")
     return codes, meta
 

@@ -278,6 +278,16 @@ bool launch_fast_second_plane(const fb4_luts* luts, const fb4_opts* opts, const 
     return true;
 }
 
+// The optional SeDA arguments of the producer-fused calls: all absent, or all there and small enough.
+int check_fused_seda(const int32_t* token_group, const uint8_t* sub, int n_groups, int64_t rows)
+{
+    if (!token_group && !sub) return n_groups == 0 ? FB4_OK : FB4_ERR_INVALID_ARG;
+    if (n_groups < 1) return FB4_ERR_INVALID_ARG;
+    if (rows > 0 && (!token_group || !sub)) return FB4_ERR_INVALID_ARG;
+    if (!aligned(token_group, 4) || (uint32_t)n_groups > kMaxFusedProducerGroups) return FB4_ERR_UNSUPPORTED;
+    return FB4_OK;
+}
+
 // Shared validation of the tensor arguments of the three quantizing calls.
 int check_tensor(const fb4_luts* l, const fb4_opts* o, const void* x, int64_t rows, int64_t cols,
                  int64_t row_stride, const void* codes, const void* meta)
@@ -684,12 +694,14 @@ int fb4_seda_profile(const fb4_luts* luts, const uint16_t* meta, int64_t rows, i
 }
 
 int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
-                           int64_t row_stride, const float* gamma, const float* beta, float eps, uint8_t* codes,
+                           int64_t row_stride, const float* gamma, const float* beta, float eps,
+                           const int32_t* token_group, const uint8_t* sub_formatbooks, int n_groups, uint8_t* codes,
                            uint16_t* meta, void* stream)
 {
     int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
     if (rc != FB4_OK) return rc;
     if (!(eps >= 0.0f) || eps > 3.0e38f) return FB4_ERR_INVALID_ARG;
+    if ((rc = check_fused_seda(token_group, sub_formatbooks, n_groups, rows)) != FB4_OK) return rc;
     if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8) return FB4_ERR_UNSUPPORTED;
     if (rows == 0 || cols == 0) return FB4_OK;
     const int64_t nb = cols / 32;
@@ -722,29 +734,43 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     p.eps = eps;
     p.codes = codes;
     p.meta = meta;
+    p.token_group = token_group;
+    p.sub = sub_formatbooks;
+    p.n_groups = (uint32_t)n_groups;
+    p.n_dialects = (uint32_t)luts->n_dialects;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
+    const bool seda = token_group != nullptr;
 #define FB4_LN_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), n_bundles, rw, (uint32_t)nb, groups, (long long)row_stride, gamma, beta, p
-#define FB4_LN_CASE(b)                                                                                                              \
-    case b:                                                                                                                         \
-        if (ts) hipLaunchKernelGGL((layernorm_quantize_kernel<b, true>), dim3(groups), dim3(kLnThreads), 0, s, FB4_LN_ARGS);  \
-        else hipLaunchKernelGGL((layernorm_quantize_kernel<b, false>), dim3(groups), dim3(kLnThreads), 0, s, FB4_LN_ARGS);    \
+#define FB4_LN_LAUNCH(b, t, sd) hipLaunchKernelGGL((layernorm_quantize_kernel<b, t, sd>), dim3(groups), dim3(kLnThreads), 0, s, FB4_LN_ARGS)
+#define FB4_LN_CASE(b)                                  \
+    case b:                                             \
+        if (seda) {                                     \
+            if (ts) FB4_LN_LAUNCH(b, true, true);       \
+            else FB4_LN_LAUNCH(b, false, true);         \
+        } else {                                        \
+            if (ts) FB4_LN_LAUNCH(b, true, false);      \
+            else FB4_LN_LAUNCH(b, false, false);        \
+        }                                               \
         break;
     switch (B) {
         FB4_LN_CASE(1) FB4_LN_CASE(2) FB4_LN_CASE(3) FB4_LN_CASE(4) FB4_LN_CASE(5) FB4_LN_CASE(6)
         default: return FB4_ERR_UNSUPPORTED;
     }
 #undef FB4_LN_CASE
+#undef FB4_LN_LAUNCH
 #undef FB4_LN_ARGS
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
 int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
-                      int64_t row_stride, int approximate, uint8_t* codes, uint16_t* meta, void* stream)
+                      int64_t row_stride, int approximate, const int32_t* token_group, const uint8_t* sub_formatbooks,
+                      int n_groups, uint8_t* codes, uint16_t* meta, void* stream)
 {
     int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
     if (rc != FB4_OK) return rc;
     if (approximate != 0 && approximate != 1) return FB4_ERR_INVALID_ARG;
+    if ((rc = check_fused_seda(token_group, sub_formatbooks, n_groups, rows)) != FB4_OK) return rc;
     if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8) return FB4_ERR_UNSUPPORTED;
     if (rows == 0 || cols == 0) return FB4_OK;
     if (!aligned(codes, 16)) return FB4_ERR_UNSUPPORTED;
@@ -760,12 +786,18 @@ int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x,
     long long g = ((long long)n_tiles + 7) / 8;
     if (g > luts->n_cu) g = luts->n_cu;
     const unsigned groups = (unsigned)g;
-    GeluParams p = {codes, meta};
+    GeluParams p = {codes, meta, token_group, sub_formatbooks, (uint32_t)n_groups, (uint32_t)luts->n_dialects};
+    const bool seda = token_group != nullptr, ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
     const uint16_t* table = reinterpret_cast<const uint16_t*>(luts->dev_blob + kBlobBytes + (approximate ? kGeluTableBytes : 0));
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define FB4_GELU_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), table, (uint32_t)n_blocks, n_tiles, div_mul, div_shift, (uint32_t)nb, groups, (long long)row_stride, p
-    if (opts->flags & FB4_FLAG_TWO_STAGE) hipLaunchKernelGGL((gelu_quantize_kernel<true>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
-    else hipLaunchKernelGGL((gelu_quantize_kernel<false>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
+    if (seda) {
+        if (ts) hipLaunchKernelGGL((gelu_quantize_kernel<true, true>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
+        else hipLaunchKernelGGL((gelu_quantize_kernel<false, true>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
+    } else {
+        if (ts) hipLaunchKernelGGL((gelu_quantize_kernel<true, false>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
+        else hipLaunchKernelGGL((gelu_quantize_kernel<false, false>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
+    }
 #undef FB4_GELU_ARGS
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }

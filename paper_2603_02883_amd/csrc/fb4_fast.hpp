@@ -713,6 +713,34 @@ __device__ __forceinline__ void residual32(const uint32_t (&w)[16], const uint32
     }
 }
 
+// Sec. 3.4 exclusion rows for kernels that fuse a producer in front of the quantizer: row g of
+// lds[offset ..] holds 0xFF for every dialect that group g may not use, the extra row n_groups (rows outside
+// any group) and a group without a valid DID exclude nothing.  Call from all threads, then synchronize.
+__device__ __forceinline__ void build_seda_rows(uint8_t* lds, int offset, const uint8_t* sub, uint32_t n_groups,
+                                                uint32_t n_dialects, uint32_t n_threads)
+{
+    for (uint32_t g = threadIdx.x; g <= n_groups; g += n_threads) {
+        uint32_t keep = 0;
+        if (g < n_groups) {
+            const uint2 s8 = *reinterpret_cast<const uint2*>(sub + (size_t)g * 8);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const uint32_t d = ((k < 4 ? s8.x : s8.y) >> (8 * (k & 3))) & 0xFFu;
+                if (d < n_dialects) keep |= 1u << d;
+            }
+        }
+        uint32_t* row = reinterpret_cast<uint32_t*>(lds + offset + g * 32);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t k4 = (keep >> (4 * i)) & 0xFu;
+            const uint32_t ex = ((k4 & 1u) ? 0u : 0x000000FFu) | ((k4 & 2u) ? 0u : 0x0000FF00u) |
+                                ((k4 & 4u) ? 0u : 0x00FF0000u) | ((k4 & 8u) ? 0u : 0xFF000000u);
+            row[i] = keep ? ex : 0u;
+        }
+    }
+}
+constexpr uint32_t kMaxFusedProducerGroups = 255;   // SeDA groups the producer-fused kernels hold in LDS
+
 // The leading scalar arguments repeat the fields of `p` that the first loads and the loop bound depend on:
 // the library is compiled so that the leading argument registers (14 of them on this target: all of these)
 // are filled by the dispatcher when the wavefront starts (the rest of the arguments come by a load, half a microsecond later), and the table and

@@ -80,18 +80,24 @@ inline void build_gelu_table(bool approximate, uint16_t* table)
 struct GeluParams {
     uint8_t* codes;
     uint16_t* meta;
+    // Sec. 3.4 (optional): candidate lists per token group
+    const int32_t* token_group;   // [rows] or null
+    const uint8_t* sub;           // [n_groups][8] DIDs
+    uint32_t n_groups;            // <= kMaxFusedProducerGroups
+    uint32_t n_dialects;
 };
 
 constexpr int kGeluThreads = 512;
 constexpr int kLdsGelu = lds_fast_bytes(false, false, false);
 
-template <bool kTwoStage>
+template <bool kTwoStage, bool kSeda>
 __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
     const uint8_t* blob, const uint16_t* x, const uint16_t* table, uint32_t n_blocks, uint32_t n_tiles, uint32_t div_mul,
     uint32_t div_shift, uint32_t nb, uint32_t n_workgroups, long long row_stride, GeluParams p)
 {
     constexpr int kWaves = kGeluThreads / 64;
-    __shared__ __align__(16) uint8_t lds[kLdsGelu + kGeluTableBytes];
+    constexpr int kLdsSeda = kLdsGelu + kGeluTableBytes;
+    __shared__ __align__(16) uint8_t lds[kLdsSeda + (kSeda ? (kMaxFusedProducerGroups + 1) * 32 : 0)];
     __shared__ uint32_t wg_next;
     const uint16_t* lds_tab = reinterpret_cast<const uint16_t*>(lds + kLdsGelu);
     const uint32_t lane = threadIdx.x & 63;
@@ -102,8 +108,9 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
     sp.div_mul = div_mul; sp.div_shift = div_shift; sp.codes = p.codes; sp.meta = p.meta;
 
     // A chunk past the end is read from the last one instead: no branch around the loads, nothing of it stored.
-    auto request = [&](uint32_t t, uint32_t (&q)[16]) {
+    auto request = [&](uint32_t t, uint32_t (&q)[16], int32_t& grp) {
         const uint32_t gbc = min(t * 64u + lane, n_blocks - 1u);
+        if (kSeda) grp = p.token_group[(uint32_t)(((unsigned long long)gbc * div_mul) >> div_shift)];
         const uint4* px = reinterpret_cast<const uint4*>(x + block_offset<false>(sp, gbc));
         const uint4 q0 = px[0], q1 = px[1], q2 = px[2], q3 = px[3];
         q[0] = q0.x; q[1] = q0.y; q[2] = q0.z; q[3] = q0.w; q[4] = q1.x; q[5] = q1.y; q[6] = q1.z; q[7] = q1.w;
@@ -113,7 +120,8 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
     uint32_t t_next = blockIdx.x + (kWaves + wave) * W;
     if (threadIdx.x == 0) wg_next = 2 * kWaves;
     uint32_t w[16];
-    request(min(t, n_tiles - 1u), w);
+    int32_t grp = -1;   // SeDA: the token group of the chunk's row
+    request(min(t, n_tiles - 1u), w, grp);
 
     // ---- tables (layout of the streaming kernel) and the GeLU table
     for (int i = threadIdx.x; i < 64 * kRowCopies; i += kGeluThreads) {
@@ -161,6 +169,7 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
         }
         if (mine >= 0) dst[mine] = loaded;
     }
+    if (kSeda) build_seda_rows(lds, kLdsSeda, p.sub, p.n_groups, p.n_dialects, kGeluThreads);
     __syncthreads();
     for (int i = threadIdx.x; i < 1024; i += kGeluThreads) {   // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
         const int hi = i >> 5, lo = i & 31;
@@ -181,6 +190,7 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
         const uint32_t t_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
         const uint32_t gb = t * 64u + lane;
+        const uint32_t excl = kSeda ? kLdsSeda + 32u * ((grp >= 0 && (uint32_t)grp < p.n_groups) ? (uint32_t)grp : p.n_groups) : 0u;
         // ---- GeLU of the 32 elements: two table lookups per register
         uint32_t y[16];
         uint32_t top = 0;   // largest bit pattern of the chunk, per half
@@ -199,13 +209,13 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
             }
         }
         // the registers of the tile are free: the next tile is requested into them, ahead of the selection
-        request(min(t_next, n_tiles - 1u), w);
+        request(min(t_next, n_tiles - 1u), w, grp);
         __builtin_amdgcn_sched_barrier(0);
         uint32_t stage[16];   // the plain routine reads its block from memory: used by special tiles only
         uint32_t code[4], meta;
         bool tile_special;
         const uint32_t no_code[4] = {0, 0, 0, 0};
-        compute_tile<32, 8, kTwoStage, false>(y, lds, K, nullptr, gb < n_blocks, 0u, code, meta, no_code, 0u, tile_special, stage);
+        compute_tile<32, 8, kTwoStage, kSeda>(y, lds, K, nullptr, gb < n_blocks, excl, code, meta, no_code, 0u, tile_special, stage);
         store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, meta_aligned);
         t = t_next;
         t_next = t_after;

@@ -39,6 +39,11 @@ struct LayerNormParams {
     float eps;
     uint8_t* codes;
     uint16_t* meta;
+    // Sec. 3.4 (optional): candidate lists per token group
+    const int32_t* token_group;   // [rows] or null
+    const uint8_t* sub;           // [n_groups][8] DIDs
+    uint32_t n_groups;            // <= kMaxFusedProducerGroups
+    uint32_t n_dialects;
 };
 
 constexpr int kLnThreads = 512;
@@ -46,14 +51,15 @@ constexpr int kLnMaxChunksPerLane = 6;
 constexpr int kLdsLnTables = lds_fast_bytes(false, false, false);
 
 // B: chunks per lane (the host picks it from the row length); gamma / beta may be null (1 / 0).
-template <int B, bool kTwoStage>
+template <int B, bool kTwoStage, bool kSeda>
 __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
     const uint8_t* blob, const uint16_t* x, uint32_t n_bundles, uint32_t rw, uint32_t nb, uint32_t n_workgroups,
     long long row_stride, const float* gamma, const float* beta, LayerNormParams p)
 {
     constexpr int kWaves = kLnThreads / 64;
     constexpr int kGbFloats = 2048 * B;   // nb <= 64 * B chunks = 2048 * B channels
-    __shared__ __align__(16) uint8_t lds[kLdsLnTables + 2 * kGbFloats * 4];
+    constexpr int kLdsSeda = kLdsLnTables + 2 * kGbFloats * 4;
+    __shared__ __align__(16) uint8_t lds[kLdsSeda + (kSeda ? (kMaxFusedProducerGroups + 1) * 32 : 0)];
     __shared__ uint32_t wg_next;
     float* lds_gamma = reinterpret_cast<float*>(lds + kLdsLnTables);
     float* lds_beta = lds_gamma + kGbFloats;
@@ -75,8 +81,9 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
     }
     // A chunk that does not exist (past the bundle or past the last row) is read from the last row
     // instead: no branch around the loads, nothing of it is stored.
-    auto request = [&](uint32_t u, int j, uint32_t (&q)[16]) {
+    auto request = [&](uint32_t u, int j, uint32_t (&q)[16], int32_t& grp) {
         const uint32_t row = min(min(u, n_bundles - 1u) * rw + rloc[j], p.rows - 1u);
+        if (kSeda) grp = p.token_group[row];
         const uint4* px = reinterpret_cast<const uint4*>(x + (long long)row * row_stride + (long long)cb[j] * 32);
         const uint4 q0 = px[0], q1 = px[1], q2 = px[2], q3 = px[3];
         q[0] = q0.x; q[1] = q0.y; q[2] = q0.z; q[3] = q0.w; q[4] = q1.x; q[5] = q1.y; q[6] = q1.z; q[7] = q1.w;
@@ -87,8 +94,12 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
     uint32_t u_next = blockIdx.x + (kWaves + wave) * W;
     if (threadIdx.x == 0) wg_next = 2 * kWaves;
     uint32_t w[B][16];   // the bundle's chunks; chunk j is replaced by the next bundle's as soon as it is normalized
+    int32_t grp[B];      // SeDA: the token group of each chunk's row
 #pragma unroll
-    for (int j = 0; j < B; ++j) request(u, j, w[j]);
+    for (int j = 0; j < B; ++j) {
+        grp[j] = -1;
+        request(u, j, w[j], grp[j]);
+    }
 
     // ---- tables (layout of the streaming kernel) and the scale / shift vectors
     for (int i = threadIdx.x; i < 64 * kRowCopies; i += kLnThreads) {
@@ -106,6 +117,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
         lds_gamma[at] = gamma ? gamma[c] : 1.0f;
         lds_beta[at] = beta ? beta[c] : 0.0f;
     }
+    if (kSeda) build_seda_rows(lds, kLdsSeda, p.sub, p.n_groups, p.n_dialects, kLnThreads);
     __syncthreads();
     for (int i = threadIdx.x; i < 1024; i += kLnThreads) {   // pair table: byte(hi, lo, d) = index(d, lo) | index(d, hi) << 4
         const int hi = i >> 5, lo = i & 31;
@@ -134,9 +146,11 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
         // ---- per-chunk sums in double
         double p1[B], p2[B];
         bool ok[B];
+        uint32_t excl[B];   // SeDA: LDS offset of the chunk's exclusion row
 #pragma unroll
         for (int j = 0; j < B; ++j) {
             ok[j] = valid[j] && u * rw + rloc[j] < p.rows;
+            excl[j] = kSeda ? kLdsSeda + 32u * ((grp[j] >= 0 && (uint32_t)grp[j] < p.n_groups) ? (uint32_t)grp[j] : p.n_groups) : 0u;
             double s1a = 0.0, s1b = 0.0, s2a = 0.0, s2b = 0.0;
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
@@ -207,13 +221,13 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
             }
             // the registers of chunk j are free: the next bundle's chunk j is requested into them, ahead of
             // this chunk's selection and of the sums of the next bundle's earlier chunks
-            request(u_next, j, w[j]);
+            request(u_next, j, w[j], grp[j]);
             __builtin_amdgcn_sched_barrier(0);
             uint32_t stage[16];   // the plain routine reads its block from memory: used by special tiles only
             uint32_t code[4], meta;
             bool tile_special;
             const uint32_t no_code[4] = {0, 0, 0, 0};
-            compute_tile<32, 8, kTwoStage, false>(y, lds, K, nullptr, ok[j], 0u, code, meta, no_code, 0u, tile_special,
+            compute_tile<32, 8, kTwoStage, kSeda>(y, lds, K, nullptr, ok[j], excl[j], code, meta, no_code, 0u, tile_special,
                                                   stage);
             const bool al = meta_aligned && (((gb - lane) & 7u) == 0u);
             store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, al, ok[j]);

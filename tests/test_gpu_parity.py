@@ -1006,3 +1006,76 @@ def test_gelu_quantize_degenerate_values_strides_and_errors(F, luts):
         F.fb4_gelu_quantize(luts, F.opts(), x, approximate=2)
     assert e.value.code == F.ERR_INVALID_ARG
     F.fb4_gelu_quantize(luts, F.opts(), x[:0])                 # no rows: a successful no-op
+
+
+# ------------------------------------------------- SeDA candidate lists behind the fused producers (Sec. 3.4 + App. E.2)
+def _odd_seda_tables(n_groups, seed):
+    """Sub-formatbooks with some invalid DIDs and one group without any valid DID (inputs the oracle refuses:
+    such a case is compared with fb4_quantize_seda on the oracle's producer output)."""
+    sub = synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, n_groups, seed).copy()
+    sub[1, 2] = 200; sub[1, 5] = 32
+    sub[n_groups - 1, :] = 255
+    return sub
+
+
+@pytest.mark.parametrize("producer", ["layernorm", "gelu"])
+def test_fused_producers_with_seda_candidate_lists(F, luts, producer):
+    for rows, cols, n_groups, flags in [(2048, 3072, 64, 0), (515, 1152, 255, 0), (300, 4096, 7, 1), (64, 12288, 3, 0)]:
+        x, comp = synth.mixture_activation(rows=rows, cols=cols, seed=rows, n_components=n_groups, device="cuda")
+        xb = synth.bf16_bits(x)
+        tg = comp.copy()
+        tg[::13] = -1                                              # no group: full formatbook
+        sub = synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, n_groups, rows)
+        o = F.opts(selector=1, num_groups=8, flags=flags)
+        tg_d, sub_d = torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda()
+        if producer == "layernorm":
+            gamma, beta = synth.layernorm_affine(cols, seed=cols)
+            c, m = F.fb4_layernorm_quantize(luts, o, x, torch.from_numpy(gamma).cuda(), torch.from_numpy(beta).cuda(), 1e-6,
+                                            token_group=tg_d, sub_formatbooks=sub_d)
+            y, _, _ = O.layernorm(xb, gamma, beta, 1e-6)
+        else:
+            c, m = F.fb4_gelu_quantize(luts, o, x, 1, token_group=tg_d, sub_formatbooks=sub_d)
+            y = O.gelu(xb, 1)
+        torch.cuda.synchronize()
+        cr, mr = O.quantize(DEFAULT_FORMATBOOK, y, selector=1, num_groups=8, flags=flags, token_group=tg, sub_formatbooks=sub)
+        compare_quant(DEFAULT_FORMATBOOK, y, host_u8(c), host_u16(m), cr, mr, 1, 8, flags=flags, token_group=tg, sub=sub,
+                      what="%s seda %dx%d" % (producer, rows, cols))
+        # the lists do constrain: rows in a valid group only use its DIDs
+        dids = host_u16(m) & 0xFF
+        for r in (0, 1, 2, 7):
+            g = tg[r]
+            if g >= 0:
+                assert np.isin(dids[r], sub[g]).all()
+    # degenerate values under the lists, and the argument checks
+    xe = synth.edge_case_tensor(cols=256)
+    tg = (np.arange(xe.shape[0]) % 5).astype(np.int32) - 1
+    sub = synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, 4, 3)
+    tg_d, sub_d = torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda()
+    if producer == "layernorm":
+        c, m = F.fb4_layernorm_quantize(luts, F.opts(), dev_bits(xe), None, None, 1e-6, token_group=tg_d, sub_formatbooks=sub_d)
+        y, _, _ = O.layernorm(xe, None, None, 1e-6)
+    else:
+        c, m = F.fb4_gelu_quantize(luts, F.opts(), dev_bits(xe), 0, token_group=tg_d, sub_formatbooks=sub_d)
+        y = O.gelu(xe, 0)
+    torch.cuda.synchronize()
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, y, token_group=tg, sub_formatbooks=sub)
+    assert np.array_equal(host_u8(c), cr) and np.array_equal(host_u16(m), mr)
+    call = F.fb4_layernorm_quantize if producer == "layernorm" else F.fb4_gelu_quantize
+    # lists with invalid DIDs, a group without a valid DID and rows outside every group behave as in
+    # fb4_quantize_seda (the oracle refuses such tables): same codes as that call on the oracle's producer output
+    x, comp = synth.mixture_activation(rows=200, cols=1024, seed=77, n_components=6, device="cuda")
+    tg = comp.copy(); tg[::7] = -5; tg[3::11] = 9
+    sub = _odd_seda_tables(6, 77)
+    tg2_d, sub2_d = torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda()
+    c, m = call(luts, F.opts(), x, token_group=tg2_d, sub_formatbooks=sub2_d)
+    y = O.layernorm(synth.bf16_bits(x), None, None, 1e-6)[0] if producer == "layernorm" else O.gelu(synth.bf16_bits(x), 0)
+    c2, m2 = F.fb4_quantize_seda(luts, F.opts(), dev_bits(y), tg2_d, sub2_d)
+    torch.cuda.synchronize()
+    assert torch.equal(c, c2) and torch.equal(m, m2)
+    big = torch.zeros((256, 8), dtype=torch.uint8, device="cuda")
+    with pytest.raises(F.Fb4Error) as e:
+        call(luts, F.opts(), dev_bits(xe), token_group=tg_d, sub_formatbooks=big)
+    assert e.value.code == F.ERR_UNSUPPORTED                       # more groups than the fused kernels hold
+    with pytest.raises(F.Fb4Error) as e:
+        call(luts, F.opts(), dev_bits(xe), token_group=tg_d, sub_formatbooks=None)
+    assert e.value.code == F.ERR_INVALID_ARG
