@@ -783,7 +783,7 @@ int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x,
     while ((1ull << l) < nb) ++l;
     const uint32_t div_shift = 31 + l;
     const uint32_t div_mul = (uint32_t)(((1ull << div_shift) + nb - 1) / nb);
-    long long g = ((long long)n_tiles + 7) / 8;
+    long long g = ((long long)n_tiles + kGeluThreads / 64 - 1) / (kGeluThreads / 64);
     if (g > luts->n_cu) g = luts->n_cu;
     const unsigned groups = (unsigned)g;
     GeluParams p = {codes, meta, token_group, sub_formatbooks, (uint32_t)n_groups, (uint32_t)luts->n_dialects};
