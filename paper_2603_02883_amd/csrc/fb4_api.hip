@@ -724,7 +724,7 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     if (B == 0) { B = (int)((nb + 63) / 64); rw = 1; }
     if (rw > (uint32_t)rows) rw = (uint32_t)rows;
     const uint32_t n_bundles = (uint32_t)((rows + rw - 1) / rw);
-    long long g = ((long long)n_bundles + 7) / 8;
+    long long g = ((long long)n_bundles + kLnThreads / 64 - 1) / (kLnThreads / 64);
     if (g > luts->n_cu) g = luts->n_cu;
     const unsigned groups = (unsigned)g;
     LayerNormParams p = {};
