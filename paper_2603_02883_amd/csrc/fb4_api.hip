@@ -709,9 +709,8 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
         return FB4_ERR_UNSUPPORTED;
     if ((uint64_t)rows * (uint64_t)nb >= 0x7F000000ull) return FB4_ERR_UNSUPPORTED;
     if ((rc = check_device(luts)) != FB4_OK) return rc;
-    // Chunks per lane B and rows per bundle: the fullest wavefront among B <= 4 (the kernel keeps a bundle in
-    // registers: up to 3 chunks per lane fit, the 4th costs a few spilled registers, 5 and 6 -- rows longer
-    // than 8192 -- spill heavily and run at half the rate per element).
+    // Chunks per lane B and rows per bundle: the fullest wavefront among B <= 4 (with 5 or 6 -- rows longer than
+    // 8192 -- the kernel runs 8 instead of 12 wavefronts per CU), the fewest chunks among equals.
     int B = 0;
     uint32_t rw = 0;
     double best = 0.0;
@@ -724,7 +723,8 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     if (B == 0) { B = (int)((nb + 63) / 64); rw = 1; }
     if (rw > (uint32_t)rows) rw = (uint32_t)rows;
     const uint32_t n_bundles = (uint32_t)((rows + rw - 1) / rw);
-    long long g = ((long long)n_bundles + kLnThreads / 64 - 1) / (kLnThreads / 64);
+    const int kLnWaves = ln_threads(B) / 64;
+    long long g = ((long long)n_bundles + kLnWaves - 1) / kLnWaves;
     if (g > luts->n_cu) g = luts->n_cu;
     const unsigned groups = (unsigned)g;
     LayerNormParams p = {};
@@ -742,7 +742,7 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
     const bool seda = token_group != nullptr;
 #define FB4_LN_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), n_bundles, rw, (uint32_t)nb, groups, (long long)row_stride, gamma, beta, p
-#define FB4_LN_LAUNCH(b, t, sd) hipLaunchKernelGGL((layernorm_quantize_kernel<b, t, sd>), dim3(groups), dim3(kLnThreads), 0, s, FB4_LN_ARGS)
+#define FB4_LN_LAUNCH(b, t, sd) hipLaunchKernelGGL((layernorm_quantize_kernel<b, t, sd, ln_threads(b)>), dim3(groups), dim3(ln_threads(b)), 0, s, FB4_LN_ARGS)
 #define FB4_LN_CASE(b)                                  \
     case b:                                             \
         if (seda) {                                     \
