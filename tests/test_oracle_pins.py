@@ -32,7 +32,8 @@ def f2b(a):
 def b2f(bits):
     """bf16 bit patterns -> float64 (IEEE value)."""
     u = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16
-    return u.view(np.float32).astype(np.float64)
+    with np.errstate(invalid="ignore"):          # (signalling NaN patterns)
+        return u.view(np.float32).astype(np.float64)
 
 
 def exact(bits):
