@@ -204,6 +204,62 @@ def gelu(x_bits, approximate=0):
     return y
 
 
+def _bf16_to_f64(bits):
+    u = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16
+    with np.errstate(invalid="ignore"):
+        return u.view(np.float32).astype(np.float64)
+
+
+def attention_scores(q_bits, k_bits, mode="abs"):
+    """Sec. 3.3, salient-token scoring: the mean pre-softmax attention score of every query token over the keys of
+    its attention group, score[g][q] = (1/T) sum_k f(Q[g][q] . K[g][k]) with f = |.| ("abs": spatial / 3D attention)
+    or max(., 0) ("relu": temporal attention).  q_bits, k_bits: uint16 [G][T][d] bf16 patterns (a group is one
+    head of one frame, or of one spatial position for temporal attention).  float64 [G][T].  The product is
+    numpy's float64 matmul."""
+    assert mode in ("abs", "relu")
+    q = _bf16_to_f64(q_bits)
+    k = _bf16_to_f64(k_bits)
+    assert q.ndim == 3 and q.shape == k.shape
+    out = np.zeros(q.shape[:2], dtype=np.float64)
+    for g in range(q.shape[0]):
+        s = q[g] @ k[g].T
+        s = np.abs(s) if mode == "abs" else np.maximum(s, 0.0)
+        out[g] = s.sum(axis=1) / q.shape[1]
+    return out
+
+
+def select_salient_tokens(scores, grid_h, grid_w, tile_h=4, tile_w=4):
+    """Sec. 3.3 / App. F: one salient token per tile.  scores: [frames][heads][grid_h * grid_w] (float32 or
+    float64), tokens row-major on the frame's grid.  Per frame the head scores are averaged (summed head by head in
+    float64), then the best token of every tile_h x tile_w tile is taken (ties: the lowest token index; a NaN
+    never wins; ragged tiles at the right / bottom edge are allowed).  Returns the chosen tokens as rows of
+    the [frames * tokens] tensor, frame by frame and ascending within a frame: int32 [frames][tiles]."""
+    scores = np.asarray(scores)
+    frames, heads, tokens = scores.shape
+    assert tokens == grid_h * grid_w
+    th, tw = (grid_h + tile_h - 1) // tile_h, (grid_w + tile_w - 1) // tile_w
+    out = np.zeros((frames, th * tw), dtype=np.int32)
+    for f in range(frames):
+        mean = np.zeros(tokens, dtype=np.float64)
+        for h in range(heads):
+            mean += scores[f, h].astype(np.float64)
+        mean /= heads
+        picks = []
+        for ty in range(th):
+            for tx in range(tw):
+                best, best_v = -1, -np.inf
+                for y in range(ty * tile_h, min(grid_h, (ty + 1) * tile_h)):
+                    for x in range(tx * tile_w, min(grid_w, (tx + 1) * tile_w)):
+                        v = mean[y * grid_w + x]
+                        if np.isnan(v):
+                            v = -np.inf
+                        if best < 0 or v > best_v:
+                            best, best_v = y * grid_w + x, v
+                picks.append(best)
+        out[f] = np.sort(np.asarray(picks, dtype=np.int64)) + f * tokens
+    return out
+
+
 def seda_profile(fbk, meta, anchor_group, n_groups):
     """Sec. 3.4, "Constructing an 8-Dialect Sub-Formatbook": bin-count profile of the dialects selected on the
     anchor tokens of each group, then per dynamic-range bucket (largest magnitude 8..15) the most frequently

@@ -864,3 +864,68 @@ def test_gelu_shape_of_the_function(approximate):
     assert O.gelu(f2b([1.0]), approximate)[0] == 0x3F57
     # ... and one where the two forms differ: GeLU(3) = 2.995950 -> 0x4040 (3.0); tanh form 2.996363 -> 0x4040
     assert O.gelu(f2b([-2.0]), 0)[0] == f2b([-0.04550026])[0] and O.gelu(f2b([-2.0]), 1)[0] == f2b([-0.04540231])[0]
+
+
+# ------------------------------------------------- attention-guided salient tokens (Sec. 3.3, App. F)
+def test_attention_scores_hand_worked_and_brute_force():
+    # two tokens, two channels: Q = [[1, 0], [0, 2]], K = [[1, 1], [-1, 0.5]]; QK^T = [[1, -1], [2, 1]]
+    q = f2b([[[1, 0], [0, 2]]])
+    k = f2b([[[1, 1], [-1, 0.5]]])
+    assert O.attention_scores(q, k, "abs").tolist() == [[1.0, 1.5]]          # (|1| + |-1|) / 2, (2 + 1) / 2
+    assert O.attention_scores(q, k, "relu").tolist() == [[0.5, 1.5]]         # (1 + 0) / 2, (2 + 1) / 2
+    # plain loops in exact rational arithmetic on a small random case
+    rng = np.random.default_rng(81)
+    qb, kb = f2b(rng.standard_normal((3, 5, 8))), f2b(rng.standard_normal((3, 5, 8)))
+    for mode in ("abs", "relu"):
+        got = O.attention_scores(qb, kb, mode)
+        for g in range(3):
+            for i in range(5):
+                acc = Fraction(0)
+                for j in range(5):
+                    dot = sum(exact(int(a)) * exact(int(b)) for a, b in zip(qb[g, i], kb[g, j]))
+                    acc += abs(dot) if mode == "abs" else max(dot, Fraction(0))
+                assert abs(got[g, i] - float(acc / 5)) <= 1e-12 * max(1.0, float(acc))
+
+
+def test_attention_scores_against_the_library_contraction_and_invariants():
+    rng = np.random.default_rng(82)
+    qb, kb = f2b(rng.standard_normal((4, 96, 64))), f2b(rng.standard_normal((4, 96, 64)))
+    q, k = torch.from_numpy(b2f(qb)), torch.from_numpy(b2f(kb))
+    s = torch.einsum("gqc,gkc->gqk", q, k)
+    assert np.allclose(O.attention_scores(qb, kb, "abs"), s.abs().mean(dim=2).numpy(), rtol=1e-12, atol=0)
+    assert np.allclose(O.attention_scores(qb, kb, "relu"), s.clamp(min=0).mean(dim=2).numpy(), rtol=1e-12, atol=0)
+    # |.| does not see the sign of K; relu(s) - relu(-s) = s and relu(s) + relu(-s) = |s|
+    a = O.attention_scores(qb, kb, "abs")
+    assert np.array_equal(a, O.attention_scores(qb, kb ^ 0x8000, "abs"))
+    rp, rn = O.attention_scores(qb, kb, "relu"), O.attention_scores(qb, kb ^ 0x8000, "relu")
+    assert np.allclose(rp + rn, a, rtol=1e-12) and np.allclose(rp - rn, s.mean(dim=2).numpy(), rtol=1e-9, atol=1e-12)
+    # groups are independent, keys may come in any order, scaling Q by 2 doubles the score
+    assert np.array_equal(O.attention_scores(qb[1:2], kb[1:2], "abs")[0], a[1])
+    assert np.allclose(O.attention_scores(qb, kb[:, ::-1], "abs"), a, rtol=1e-12)
+    assert np.array_equal(O.attention_scores(f2b(b2f(qb) * 2), kb, "abs"), 2 * a)
+
+
+def test_salient_token_selection_per_tile():
+    # 4 x 4 grid, 2 x 2 tiles, two heads: hand-made scores
+    s = np.zeros((1, 2, 16))
+    s[0, 0, 5] = 1; s[0, 1, 5] = 1            # tile (0,0): token 5, mean 1
+    s[0, 0, 2] = 3                            # tile (0,1): token 2, mean 1.5 (one head only)
+    s[0, 1, 10] = 2.5; s[0, :, 15] = np.nan   # tile (1,1): token 10; a NaN never wins.  tile (1,0): all equal -> 8
+    assert O.select_salient_tokens(s, 4, 4, 2, 2).tolist() == [[2, 5, 8, 10]]
+    # ragged tiles, several frames: one token per tile, inside its tile, with the tile's largest mean
+    rng = np.random.default_rng(83)
+    sc = rng.random((3, 5, 7 * 10)).astype(np.float32)
+    out = O.select_salient_tokens(sc, 7, 10, 4, 4)
+    assert out.shape == (3, 2 * 3) and (np.diff(out, axis=1) > 0).all()
+    mean = sc.astype(np.float64).mean(axis=1)
+    for f in range(3):
+        seen = set()
+        for row in out[f]:
+            t = int(row) - f * 70
+            y, x = divmod(t, 10)
+            tile = (y // 4, x // 4)
+            assert tile not in seen
+            seen.add(tile)
+            ys, xs = range(tile[0] * 4, min(7, tile[0] * 4 + 4)), range(tile[1] * 4, min(10, tile[1] * 4 + 4))
+            assert mean[f, t] == max(mean[f, yy * 10 + xx] for yy in ys for xx in xs)
+        assert len(seen) == 6
