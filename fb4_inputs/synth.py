@@ -184,6 +184,22 @@ def salient_rows_from_attention(tokens, frac=0.05, heads=24, seed=3, device="cpu
     return np.sort(order[:n_sal]).astype(np.int32)
 
 
+def attention_qk(groups, tokens, dim, seed=7, device="cpu", salient_frac=0.03):
+    """Synthetic query / key projections of one attention layer: bf16 [groups][tokens][dim] each, N(0, 1) with a
+    common per-group direction mixed in (tokens of a frame resemble each other) and a few tokens per group with
+    three times the norm (the ones an attention-guided choice should find)."""
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) * 7919 + 17)
+    out = []
+    for _ in range(2):
+        x = torch.randn((groups, tokens, dim), device=device, generator=g)
+        x += 0.5 * torch.randn((groups, 1, dim), device=device, generator=g)
+        big = torch.rand((groups, tokens, 1), device=device, generator=g) < salient_frac
+        x = torch.where(big, 3.0 * x, x)
+        out.append(x.to(torch.bfloat16))
+    return out[0], out[1]
+
+
 def edge_case_tensor(cols=256, seed=11):
     """A small uint16 (bf16 bit pattern) tensor exercising the degenerate
     inputs: all-zero and all-negative-zero blocks, subnormals, values at and

@@ -321,6 +321,38 @@ int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x,
  */
 int fb4_gelu_table_host(int approximate, uint16_t* table, size_t capacity, size_t* entries);
 
+/*
+ * Sec. 3.3 and App. F (attention-guided salient tokens): how strongly every
+ * query token attends on average, pre-softmax:
+ *   scores[g][i] = (1/tokens) * sum_j f(Q[g][i] . K[g][j]),
+ *   f = |.| (mode 0: spatial / 3D attention) or max(., 0) (mode 1: temporal).
+ * A group g is one attention problem: one head of one frame (spatial), of one
+ * spatial position (temporal), or of the whole clip (3D).  Runs on the matrix
+ * cores: bf16 products, fp32 accumulation and sums (results agree with a
+ * float64 evaluation to about 1e-5 relative, not bit for bit).
+ *   q, k     device, bf16 [groups][tokens][dim], contiguous, 16-byte aligned
+ *   dim      a multiple of 8, at most 256 (FB4_ERR_UNSUPPORTED otherwise)
+ *   scores   device, float [groups][tokens]
+ */
+int fb4_attention_scores(const void* q, const void* k, int64_t groups, int64_t tokens, int64_t dim,
+                         int mode, float* scores, void* stream);
+
+/*
+ * Sec. 3.3 and App. F: one salient token per tile.  Per frame, the scores of
+ * the heads are averaged (in double, head by head) and every tile_h x tile_w
+ * tile of the grid_h x grid_w token grid (row-major tokens; ragged tiles at the
+ * right / bottom edge allowed) contributes its best token: the lowest token
+ * index on ties, a NaN never wins.
+ *   scores    device, float [frames][heads][grid_h * grid_w]
+ *   rows_out  device, int32 [frames][tiles], tiles = ceil(grid_h / tile_h) *
+ *             ceil(grid_w / tile_w): the chosen tokens as rows frame * tokens +
+ *             token of the [frames * tokens] activation, ascending -- the
+ *             salient_rows argument of fb4_decompose / fb4_quantize_decompose
+ *   grid_h * grid_w at most 8192 (FB4_ERR_UNSUPPORTED beyond)
+ */
+int fb4_select_salient_tokens(const float* scores, int64_t frames, int heads, int grid_h, int grid_w,
+                              int tile_h, int tile_w, int32_t* rows_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -67,6 +67,8 @@ def _load():
     lib.fb4_quantize_decompose.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, i32, p, i64, p, p, p, p, p]
     lib.fb4_seda_profile.argtypes = [p, p, i64, i64, p, i32, p, p, p]
     lib.fb4_repack_mxfp8.argtypes = [p, p, p, i64, i64, i32, p, i64, p, p]
+    lib.fb4_attention_scores.argtypes = [p, p, i64, i64, i64, i32, p, p]
+    lib.fb4_select_salient_tokens.argtypes = [p, i64, i32, i32, i32, i32, i32, p, p]
     lib.fb4_gelu_table_host.argtypes = [i32, p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
     lib.fb4_gelu_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, i32, p, p, i32, p, p, p]
     lib.fb4_layernorm_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, ctypes.c_float, p, p, i32,
@@ -80,7 +82,7 @@ EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts
            "fb4_free_luts", "fb4_quantize", "fb4_quantize_seda", "fb4_decompose", "fb4_dequantize",
            "fb4_quantize_decompose", "fb4_seda_profile",
            "fb4_repack_mxfp8", "fb4_layernorm_quantize", "fb4_gelu_quantize",
-           "fb4_gelu_table_host"]
+           "fb4_gelu_table_host", "fb4_attention_scores", "fb4_select_salient_tokens"]
 
 
 def lib():
@@ -192,6 +194,30 @@ def fb4_layernorm_quantize(luts, o, x, gamma=None, beta=None, eps=1e-6, codes=No
                                      _dp(codes), _dp(meta), _stream(stream))
     _check(rc, "fb4_layernorm_quantize")
     return codes, meta
+
+
+def fb4_attention_scores(q, k, mode=0, scores=None, stream=None):
+    """q, k: bf16 cuda [groups][tokens][dim].  mode 0: mean |Q.K^T| over the keys, 1: mean max(Q.K^T, 0).
+    Returns float32 [groups][tokens]."""
+    groups, tokens, dim = q.shape
+    if scores is None:
+        scores = torch.empty((groups, tokens), dtype=torch.float32, device=q.device)
+    _check(_lib.fb4_attention_scores(_dp(q), _dp(k), groups, tokens, dim, int(mode), _dp(scores), _stream(stream)),
+           "fb4_attention_scores")
+    return scores
+
+
+def fb4_select_salient_tokens(scores, grid_h, grid_w, tile_h=4, tile_w=4, rows_out=None, stream=None):
+    """scores: float32 cuda [frames][heads][grid_h * grid_w].  Returns int32 [frames][tiles]: one row per tile,
+    ascending within a frame, as rows of the [frames * tokens] tensor."""
+    frames, heads, tokens = scores.shape
+    assert tokens == grid_h * grid_w
+    tiles = ((grid_h + tile_h - 1) // tile_h) * ((grid_w + tile_w - 1) // tile_w)
+    if rows_out is None:
+        rows_out = torch.empty((frames, tiles), dtype=torch.int32, device=scores.device)
+    _check(_lib.fb4_select_salient_tokens(_dp(scores), frames, heads, grid_h, grid_w, tile_h, tile_w, _dp(rows_out),
+                                          _stream(stream)), "fb4_select_salient_tokens")
+    return rows_out
 
 
 def fb4_gelu_table_host(approximate=0):

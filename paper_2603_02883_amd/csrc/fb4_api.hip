@@ -14,6 +14,7 @@
 #include "fb4_layernorm.hpp"
 #include "fb4_profile.hpp"
 #include "fb4_repack.hpp"
+#include "fb4_salient.hpp"
 #include "fb4_tables.hpp"
 
 struct fb4_luts {
@@ -811,6 +812,47 @@ int fb4_gelu_table_host(int approximate, uint16_t* table, size_t capacity, size_
     if (!t) return FB4_ERR_ALLOC;
     std::memcpy(table, t + (approximate ? kGeluTableBytes / 2 : 0), kGeluEntries * 2);
     return FB4_OK;
+}
+
+int fb4_attention_scores(const void* q, const void* k, int64_t groups, int64_t tokens, int64_t dim, int mode,
+                         float* scores, void* stream)
+{
+    if (groups < 0 || tokens < 0 || dim < 0 || (mode != 0 && mode != 1)) return FB4_ERR_INVALID_ARG;
+    if (groups == 0 || tokens == 0) return FB4_OK;
+    if (!q || !k || !scores || dim == 0) return FB4_ERR_INVALID_ARG;
+    if ((dim % 8) || dim > 256 || !aligned(q, 16) || !aligned(k, 16) || !aligned(scores, 4)) return FB4_ERR_UNSUPPORTED;
+    const int64_t bpg = (tokens + kScoreQueries - 1) / kScoreQueries;
+    if (tokens > 0x7FFFFFFFll || groups * bpg > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)(groups * bpg));
+#define FB4_SCORE_ARGS static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), (uint32_t)tokens, (uint32_t)dim, (uint32_t)bpg, scores
+#define FB4_SCORE_CASE(d)                                                                                                      \
+    case d:                                                                                                                    \
+        if (mode) hipLaunchKernelGGL((attention_scores_kernel<d, true>), grid, dim3(kScoreThreads), 0, s, FB4_SCORE_ARGS);  \
+        else hipLaunchKernelGGL((attention_scores_kernel<d, false>), grid, dim3(kScoreThreads), 0, s, FB4_SCORE_ARGS);      \
+        break;
+    switch ((int)((dim + 31) / 32)) {
+        FB4_SCORE_CASE(1) FB4_SCORE_CASE(2) FB4_SCORE_CASE(3) FB4_SCORE_CASE(4)
+        FB4_SCORE_CASE(5) FB4_SCORE_CASE(6) FB4_SCORE_CASE(7) FB4_SCORE_CASE(8)
+        default: return FB4_ERR_UNSUPPORTED;
+    }
+#undef FB4_SCORE_CASE
+#undef FB4_SCORE_ARGS
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+int fb4_select_salient_tokens(const float* scores, int64_t frames, int heads, int grid_h, int grid_w, int tile_h,
+                              int tile_w, int32_t* rows_out, void* stream)
+{
+    if (frames < 0 || heads < 1 || grid_h < 1 || grid_w < 1 || tile_h < 1 || tile_w < 1) return FB4_ERR_INVALID_ARG;
+    if (frames == 0) return FB4_OK;
+    if (!scores || !rows_out) return FB4_ERR_INVALID_ARG;
+    const int64_t tokens = (int64_t)grid_h * grid_w;
+    if (tokens > (int64_t)kSelectMaxTokens || frames * tokens > 0x7FFFFFFFll || !aligned(scores, 4) || !aligned(rows_out, 4))
+        return FB4_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(select_salient_kernel, dim3((unsigned)frames), dim3(kSelectThreads), 0, static_cast<hipStream_t>(stream),
+                       scores, (uint32_t)heads, (uint32_t)grid_h, (uint32_t)grid_w, (uint32_t)tile_h, (uint32_t)tile_w, rows_out);
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
 }  // extern "C"

@@ -1,0 +1,172 @@
+// Attention-guided salient tokens (Sec. 3.3, App. F): the rows that the
+// activation decomposition gives a second plane are, per tile of tokens, the one
+// whose query attends most strongly on average -- the mean over the keys of
+// its attention group of |Q.K^T| (spatial / 3D attention) or max(Q.K^T, 0)
+// (temporal attention), pre-softmax.
+//
+// attention_scores_kernel: the one dense contraction of this library, on the
+// matrix cores.  A workgroup of four wavefronts takes 128 queries of one group;
+// every wavefront keeps its 32 queries as B operands in registers for the whole
+// pass and walks over the group's keys 32 at a time: the key block goes through
+// LDS once for the four wavefronts (rows padded by 8 bytes so that the 8-byte
+// operand reads of 16 lanes fall into 16 different bank pairs), each step is a
+// 32x32x8 bf16 MFMA with fp32 accumulation computing S^T = K Q^T -- transposed
+// so that a lane's 16 accumulators are 16 keys of ONE query: |.| or max(., 0)
+// and the sum over keys then stay inside the lane, and the two half-wavefronts
+// are only added up once at the very end.
+//
+// select_salient_kernel: per frame the head mean (in double, head by head), the
+// best token of every tile (lowest index on ties, a NaN never wins), and the
+// chosen tokens as ascending row numbers of the [frames * tokens] tensor.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fb4 {
+
+typedef short mfma_bf16x4 __attribute__((ext_vector_type(4)));
+typedef float mfma_f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kScoreThreads = 256;
+constexpr int kScoreQueries = 128;   // per workgroup
+constexpr int kScoreKeys = 32;       // per step of the key loop
+
+// D32: channels / 32, rounded up (channels beyond `dim` are zero on both sides).  kRelu: max(., 0), else |.|.
+template <int D32, bool kRelu>
+__global__ __launch_bounds__(kScoreThreads) void attention_scores_kernel(const uint16_t* q, const uint16_t* k,
+                                                                         uint32_t tokens, uint32_t dim,
+                                                                         uint32_t blocks_per_group, float* scores)
+{
+    constexpr int kSteps = D32 * 4;                  // MFMA steps of 8 channels
+    constexpr int kRowBytes = D32 * 64 + 8;          // one key row in LDS: channels, then 8 bytes of padding
+    __shared__ __align__(16) uint8_t lds[2][kScoreKeys * kRowBytes];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t g = blockIdx.x / blocks_per_group;
+    const uint32_t q0 = (blockIdx.x - g * blocks_per_group) * kScoreQueries + wave * 32u;
+    const uint16_t* qg = q + (size_t)g * tokens * dim;
+    const uint16_t* kg = k + (size_t)g * tokens * dim;
+    const uint32_t half = lane >> 5, col = lane & 31u;
+
+    // ---- this wavefront's queries as B operands: lane holds query q0 + lane % 32, channels 8 s + 4 (lane / 32) ..
+    // (a query past the end reads the last one; a channel past `dim` is zero)
+    mfma_bf16x4 qf[kSteps];
+    {
+        const uint16_t* row = qg + (size_t)min(q0 + col, tokens - 1u) * dim;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const uint32_t c = 8u * s + 4u * half;
+            uint2 v = make_uint2(0, 0);
+            if (c + 4u <= dim) v = *reinterpret_cast<const uint2*>(row + c);   // dim is a multiple of 8
+            qf[s] = __builtin_bit_cast(mfma_bf16x4, v);
+        }
+    }
+    // ---- key blocks: 32 keys x dim channels; thread t stages 16-byte pieces t, t + 256, ...
+    constexpr int kPiecesPerRow = D32 * 4;           // 16-byte pieces of a padded row's channel part
+    constexpr int kPieces = kScoreKeys * kPiecesPerRow;
+    constexpr int kPerThread = (kPieces + kScoreThreads - 1) / kScoreThreads;
+    uint4 stage[kPerThread];
+    auto fetch = [&](uint32_t kb) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const uint32_t piece = threadIdx.x + i * kScoreThreads;
+            const uint32_t r = piece / kPiecesPerRow, c8 = (piece - r * kPiecesPerRow) * 8u;   // key row, first channel
+            const uint32_t key = kb * kScoreKeys + r;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (piece < (uint32_t)kPieces && key < tokens && c8 + 8u <= dim)
+                v = *reinterpret_cast<const uint4*>(kg + (size_t)key * dim + c8);
+            stage[i] = v;
+        }
+    };
+    auto deposit = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const uint32_t piece = threadIdx.x + i * kScoreThreads;
+            const uint32_t r = piece / kPiecesPerRow, cb = (piece - r * kPiecesPerRow) * 16u;
+            if (piece < (uint32_t)kPieces) {
+                // (rows are 8-byte aligned only: two 8-byte writes)
+                uint2* dst = reinterpret_cast<uint2*>(&lds[buf][r * kRowBytes + cb]);
+                dst[0] = make_uint2(stage[i].x, stage[i].y);
+                dst[1] = make_uint2(stage[i].z, stage[i].w);
+            }
+        }
+    };
+    const uint32_t n_kb = (tokens + kScoreKeys - 1) / kScoreKeys;
+    fetch(0);
+    deposit(0);
+    __syncthreads();
+    float sum = 0.0f;   // over this lane's keys of f(S[query][key])
+    for (uint32_t kb = 0; kb < n_kb; ++kb) {
+        const int buf = kb & 1;
+        if (kb + 1 < n_kb) fetch(kb + 1);
+        mfma_f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            // A operand: key row lane % 32 of the block, channels 8 s + 4 (lane / 32) ..
+            const uint2 a = *reinterpret_cast<const uint2*>(&lds[buf][col * kRowBytes + s * 16 + half * 8]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(mfma_bf16x4, a), qf[s], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += kRelu ? fmaxf(acc[r], 0.0f) : fabsf(acc[r]);
+        if (kb + 1 < n_kb) deposit(buf ^ 1);
+        __syncthreads();
+    }
+    sum += __shfl_xor(sum, 32);   // the two half-wavefronts hold different keys of the same query
+    if (half == 0 && q0 + col < tokens) scores[(size_t)g * tokens + q0 + col] = sum / (float)tokens;
+}
+
+constexpr int kSelectThreads = 256;
+constexpr uint32_t kSelectMaxTokens = 8192;   // per frame (the head means sit in LDS)
+
+__global__ __launch_bounds__(kSelectThreads) void select_salient_kernel(const float* scores, uint32_t heads,
+                                                                        uint32_t grid_h, uint32_t grid_w, uint32_t tile_h,
+                                                                        uint32_t tile_w, int32_t* rows_out)
+{
+    __shared__ double mean[kSelectMaxTokens];
+    __shared__ uint8_t chosen[kSelectMaxTokens];
+    __shared__ uint32_t wave_total[kSelectThreads / 64];
+    const uint32_t tokens = grid_h * grid_w, frame = blockIdx.x;
+    const float* sf = scores + (size_t)frame * heads * tokens;
+    for (uint32_t t = threadIdx.x; t < tokens; t += kSelectThreads) {
+        double m = 0.0;
+        for (uint32_t h = 0; h < heads; ++h) m += (double)sf[(size_t)h * tokens + t];
+        mean[t] = m / (double)heads;
+        chosen[t] = 0;
+    }
+    __syncthreads();
+    const uint32_t th = (grid_h + tile_h - 1) / tile_h, tw = (grid_w + tile_w - 1) / tile_w;
+    for (uint32_t tile = threadIdx.x; tile < th * tw; tile += kSelectThreads) {
+        const uint32_t ty = tile / tw, tx = tile - ty * tw;
+        uint32_t best = 0xFFFFFFFFu;
+        double best_v = 0.0;
+        for (uint32_t y = ty * tile_h; y < min(grid_h, (ty + 1) * tile_h); ++y) {
+            for (uint32_t x = tx * tile_w; x < min(grid_w, (tx + 1) * tile_w); ++x) {
+                double v = mean[y * grid_w + x];
+                if (v != v) v = -__builtin_inf();
+                if (best == 0xFFFFFFFFu || v > best_v) { best = y * grid_w + x; best_v = v; }
+            }
+        }
+        chosen[best] = 1;   // (tiles are disjoint: no two threads write the same byte)
+    }
+    __syncthreads();
+    // ascending compaction: thread t owns a contiguous run of tokens
+    const uint32_t per = (tokens + kSelectThreads - 1) / kSelectThreads;
+    const uint32_t first = threadIdx.x * per, last = min(tokens, first + per);
+    uint32_t count = 0;
+    for (uint32_t t = first; t < last; ++t) count += chosen[t];
+    uint32_t incl = count;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t v = __shfl_up(incl, off);
+        if ((int)(threadIdx.x & 63) >= off) incl += v;
+    }
+    if ((threadIdx.x & 63) == 63) wave_total[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    uint32_t at = incl - count;
+    for (uint32_t w = 0; w < (threadIdx.x >> 6); ++w) at += wave_total[w];
+    int32_t* out = rows_out + (size_t)frame * th * tw;
+    for (uint32_t t = first; t < last; ++t)
+        if (chosen[t]) out[at++] = (int32_t)(frame * tokens + t);
+}
+
+}  // namespace fb4

@@ -1079,3 +1079,79 @@ def test_fused_producers_with_seda_candidate_lists(F, luts, producer):
     with pytest.raises(F.Fb4Error) as e:
         call(luts, F.opts(), dev_bits(xe), token_group=tg_d, sub_formatbooks=None)
     assert e.value.code == F.ERR_INVALID_ARG
+
+
+# ------------------------------------------------- attention-guided salient tokens (Sec. 3.3, App. F)
+@pytest.mark.parametrize("mode", [0, 1])
+def test_attention_scores_against_the_oracle(F, mode):
+    """The one floating-point contraction of the library (bf16 products, fp32 accumulation on the matrix cores):
+    compared with the float64 oracle to 2e-5 relative (the terms of a score are all non-negative: no cancellation
+    in the sum over keys; a single dot product loses at most sqrt(dim) * 2^-24 of its operands' magnitude)."""
+    for groups, tokens, dim in [(3, 100, 64), (2, 1024, 128), (5, 33, 72), (1, 1, 8), (2, 257, 256), (4, 128, 40),
+                                (2, 300, 96), (1, 2049, 16)]:
+        q, k = synth.attention_qk(groups, tokens, dim, seed=tokens + dim, device="cuda")
+        got = F.fb4_attention_scores(q, k, mode).cpu().numpy().astype(np.float64)
+        torch.cuda.synchronize()
+        ref = O.attention_scores(synth.bf16_bits(q), synth.bf16_bits(k), "relu" if mode else "abs")
+        # scale of the terms: mean |s| (for relu the sum can be much smaller than the terms it leaves out)
+        scale = O.attention_scores(synth.bf16_bits(q), synth.bf16_bits(k), "abs")
+        assert np.abs(got - ref).max() <= 2e-5 * scale.max(), (groups, tokens, dim)
+        assert (np.abs(got - ref) <= 2e-5 * scale + 1e-30).all(), (groups, tokens, dim)
+    # exactly representable case: 0 / 1 inputs give integer dot products, exact in fp32
+    rng = np.random.default_rng(91)
+    qb = (rng.random((2, 200, 64)) < 0.3).astype(np.float32) * np.where(rng.random((2, 200, 64)) < 0.5, -1, 1)
+    kb = (rng.random((2, 200, 64)) < 0.3).astype(np.float32)
+    q, k = torch.from_numpy(qb).cuda().bfloat16(), torch.from_numpy(kb).cuda().bfloat16()
+    got = F.fb4_attention_scores(q, k, mode).cpu().numpy()
+    ref = O.attention_scores(synth.bf16_bits(q), synth.bf16_bits(k), "relu" if mode else "abs")
+    assert np.array_equal(got, ref.astype(np.float32))          # sums of small integers / 200: one rounding each
+
+
+def test_salient_token_selection_and_the_whole_chain(F, luts):
+    # selection alone, on the oracle's scores: bit-exact (ties, NaNs, ragged tiles)
+    rng = np.random.default_rng(92)
+    for frames, heads, gh, gw, th, tw in [(3, 5, 7, 10, 4, 4), (16, 24, 32, 32, 4, 4), (1, 1, 1, 1, 4, 4), (2, 3, 64, 64, 8, 8),
+                                          (2, 2, 9, 33, 2, 5)]:
+        sc = rng.random((frames, heads, gh * gw)).astype(np.float32)
+        sc[:, :, ::7] = 0.5                                        # ties
+        if gh * gw > 20:
+            sc[0, 0, 3] = np.nan; sc[-1, :, 11] = np.nan
+        got = F.fb4_select_salient_tokens(torch.from_numpy(sc).cuda(), gh, gw, th, tw).cpu().numpy()
+        assert np.array_equal(got, O.select_salient_tokens(sc, gh, gw, th, tw))
+    # the chain: scores on the GPU, selection on the GPU, the rows into the one-pass decomposition.  The chosen token
+    # of a tile must be (one of) the oracle's best: its float64 mean score within 1e-4 of the tile's largest.
+    frames, heads, gh, gw, dim = 4, 6, 16, 16, 64
+    tokens = gh * gw
+    q, k = synth.attention_qk(frames * heads, tokens, dim, seed=5, device="cuda")
+    scores = F.fb4_attention_scores(q, k, 0)
+    rows = F.fb4_select_salient_tokens(scores.view(frames, heads, tokens), gh, gw)
+    torch.cuda.synchronize()
+    ref = O.attention_scores(synth.bf16_bits(q), synth.bf16_bits(k), "abs").reshape(frames, heads, tokens).mean(axis=1)
+    r = rows.cpu().numpy()
+    assert r.shape == (frames, 16) and (np.diff(r.reshape(-1)) > 0).all()
+    for f in range(frames):
+        tiles = set()
+        for row in r[f]:
+            t = int(row) - f * tokens
+            y, x = divmod(t, gw)
+            tiles.add((y // 4, x // 4))
+            best = max(ref[f, yy * gw + xx] for yy in range(y // 4 * 4, y // 4 * 4 + 4) for xx in range(x // 4 * 4, x // 4 * 4 + 4))
+            assert ref[f, t] >= best * (1 - 1e-4)
+        assert len(tiles) == 16
+    x = synth.vdit_activation(rows=frames * tokens, cols=1024, seed=9, device="cuda")
+    c1, m1, c2, m2 = F.fb4_quantize_decompose(luts, F.opts(), x, rows.view(-1))
+    torch.cuda.synchronize()
+    xb = synth.bf16_bits(x)
+    c1r, m1r = O.quantize(DEFAULT_FORMATBOOK, xb)
+    c2r, m2r = O.decompose(DEFAULT_FORMATBOOK, xb, c1r, m1r, r.reshape(-1))
+    assert np.array_equal(host_u8(c2), c2r) and np.array_equal(host_u16(m2), m2r)
+    # argument checks
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_attention_scores(q[:, :, :60].contiguous(), k[:, :, :60].contiguous(), 0)      # dim not a multiple of 8
+    assert e.value.code == F.ERR_UNSUPPORTED
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_attention_scores(q, k, 2)
+    assert e.value.code == F.ERR_INVALID_ARG
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_select_salient_tokens(torch.zeros((1, 1, 128 * 128), device="cuda"), 128, 128)   # more than 8192 tokens
+    assert e.value.code == F.ERR_UNSUPPORTED
