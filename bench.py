@@ -203,6 +203,12 @@ def main():
             F.fb4_dequantize(luts, codes[k], metas[k], out=outs[i % 2])
             F.fb4_dequantize(luts, codes[k], metas[k], codes2=c2, meta2=m2, salient_rows=sal_d, out=outs[i % 2])
             F.fb4_repack_mxfp8(luts, codes[k], metas[k], elems=els[i % 2], scales=scs[i % 2])
+        # attention scores of 384 groups x 1024 tokens x 128 channels, and the per-tile choice
+        qa, ka = synth.attention_qk(16 * 24, 1024, 128, seed=7, device="cuda")
+        att = torch.empty((16 * 24, 1024), dtype=torch.float32, device="cuda")
+        for i in range(4):
+            F.fb4_attention_scores(qa, ka, 0, scores=att)
+            F.fb4_select_salient_tokens(att.view(16, 24, 1024), 32, 32)
         # GeLU + quantizer in one pass
         for i in range(4):
             k = i % N_SETS
@@ -330,6 +336,23 @@ def main():
             F.fb4_seda_profile(luts, metas[i % N_SETS], anchors, 64, counts=counts, sub_formatbooks=subs)
         add("seda_profile_10pct_anchor_rows", profile_step, ROWS * 4 + (ROWS // 10) * (COLS // BLOCK) * 2,
             (ROWS // 10) * COLS)
+        # attention-guided salient tokens (Sec. 3.3) for this tensor: 16 frames x 24 heads, 32 x 32 tokens per frame,
+        # 128 channels per head; one token per 4 x 4 tile = 1024 rows
+        qa, ka = synth.attention_qk(16 * 24, 1024, 128, seed=7, device="cuda")
+        att = torch.empty((16 * 24, 1024), dtype=torch.float32, device="cuda")
+        sal_rows = torch.empty((16, 64), dtype=torch.int32, device="cuda")
+
+        def scores_step(i):
+            F.fb4_attention_scores(qa, ka, 0, scores=att)
+        w_s, e_s = timer(scores_step, steps2, 2 * steps2)
+        flops = 2.0 * 16 * 24 * 1024 * 1024 * 128
+        extras["attention_scores_384x1024x128"] = {"us": e_s / steps2 * 1e6, "TFLOP_per_s": flops / (e_s / steps2) / 1e12,
+                                                   "mfma_frac": flops / (e_s / steps2) / 1e12 / 2500.0}
+
+        def select_step(i):
+            F.fb4_select_salient_tokens(att.view(16, 24, 1024), 32, 32, rows_out=sal_rows)
+        add("select_salient_tokens_16x24x1024", select_step, 16 * 24 * 1024 * 4 + 16 * 64 * 4, 16 * 1024)
+        del qa, ka
         # decomposition (cfg3): 5 % salient rows
         sal = synth.salient_rows_from_attention(ROWS, frac=0.05, heads=24, seed=3, device="cuda")
         sal_d = torch.from_numpy(sal).cuda()

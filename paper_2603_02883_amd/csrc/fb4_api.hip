@@ -821,15 +821,23 @@ int fb4_attention_scores(const void* q, const void* k, int64_t groups, int64_t t
     if (groups == 0 || tokens == 0) return FB4_OK;
     if (!q || !k || !scores || dim == 0) return FB4_ERR_INVALID_ARG;
     if ((dim % 8) || dim > 256 || !aligned(q, 16) || !aligned(k, 16) || !aligned(scores, 4)) return FB4_ERR_UNSUPPORTED;
-    const int64_t bpg = (tokens + kScoreQueries - 1) / kScoreQueries;
-    if (tokens > 0x7FFFFFFFll || groups * bpg > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
+    const bool small = tokens <= (int64_t)kScoreShortGroup;
+    const int64_t per_wg = small ? 128 : 256;   // queries per workgroup of the two kernel shapes
+    const int64_t bpg = (tokens + per_wg - 1) / per_wg;
+    if (tokens * dim > 0x7FFFFFFFll || groups * bpg > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)(groups * bpg));
 #define FB4_SCORE_ARGS static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), (uint32_t)tokens, (uint32_t)dim, (uint32_t)bpg, scores
-#define FB4_SCORE_CASE(d)                                                                                                      \
-    case d:                                                                                                                    \
-        if (mode) hipLaunchKernelGGL((attention_scores_kernel<d, true>), grid, dim3(kScoreThreads), 0, s, FB4_SCORE_ARGS);  \
-        else hipLaunchKernelGGL((attention_scores_kernel<d, false>), grid, dim3(kScoreThreads), 0, s, FB4_SCORE_ARGS);      \
+#define FB4_SCORE_LAUNCH(d, relu, qb, keys) hipLaunchKernelGGL((attention_scores_kernel<d, relu, qb, keys>), grid, dim3(kScoreThreads), 0, s, FB4_SCORE_ARGS)
+#define FB4_SCORE_CASE(d)                                   \
+    case d:                                                 \
+        if (small) {                                        \
+            if (mode) FB4_SCORE_LAUNCH(d, true, 1, 32);     \
+            else FB4_SCORE_LAUNCH(d, false, 1, 32);         \
+        } else {                                            \
+            if (mode) FB4_SCORE_LAUNCH(d, true, 2, 64);     \
+            else FB4_SCORE_LAUNCH(d, false, 2, 64);         \
+        }                                                   \
         break;
     switch ((int)((dim + 31) / 32)) {
         FB4_SCORE_CASE(1) FB4_SCORE_CASE(2) FB4_SCORE_CASE(3) FB4_SCORE_CASE(4)
@@ -837,6 +845,7 @@ int fb4_attention_scores(const void* q, const void* k, int64_t groups, int64_t t
         default: return FB4_ERR_UNSUPPORTED;
     }
 #undef FB4_SCORE_CASE
+#undef FB4_SCORE_LAUNCH
 #undef FB4_SCORE_ARGS
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }

@@ -5,12 +5,12 @@
 // (temporal attention), pre-softmax.
 //
 // attention_scores_kernel: the one dense contraction of this library, on the
-// matrix cores.  A workgroup of four wavefronts takes 128 queries of one group;
-// every wavefront keeps its 32 queries as B operands in registers for the whole
-// pass and walks over the group's keys 32 at a time: the key block goes through
-// LDS once for the four wavefronts (rows padded by 8 bytes so that the 8-byte
-// operand reads of 16 lanes fall into 16 different bank pairs), each step is a
-// 32x32x8 bf16 MFMA with fp32 accumulation computing S^T = K Q^T -- transposed
+// matrix cores.  A workgroup of four wavefronts takes 256 queries of one group;
+// every wavefront keeps its 64 queries as B operands in registers for the whole
+// pass and walks over the group's keys 64 at a time: the key block goes through
+// LDS once for the four wavefronts (rows padded by 16 bytes so that the 16-byte
+// operand reads of the 16 lanes of a pass fall into 16 different bank groups),
+// each step is a 32x32x16 bf16 MFMA with fp32 accumulation computing S^T = K Q^T -- transposed
 // so that a lane's 16 accumulators are 16 keys of ONE query: |.| or max(., 0)
 // and the sum over keys then stay inside the lane, and the two half-wavefronts
 // are only added up once at the very end.
@@ -25,40 +25,44 @@
 
 namespace fb4 {
 
-typedef short mfma_bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 mfma_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float mfma_f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kScoreThreads = 256;
-constexpr int kScoreQueries = 128;   // per workgroup
-constexpr int kScoreKeys = 32;       // per step of the key loop
+// Two shapes of the kernel: 64 queries per wavefront and 64 keys per barrier for long groups (spatial / 3D
+// attention), 32 and 32 for short ones (temporal attention: a group is a handful of frames).
+constexpr uint32_t kScoreShortGroup = 64;   // tokens up to which the small shape is used
 
 // D32: channels / 32, rounded up (channels beyond `dim` are zero on both sides).  kRelu: max(., 0), else |.|.
-template <int D32, bool kRelu>
+// kScoreQB: blocks of 32 queries per wavefront; kScoreKeys: keys per barrier (a multiple of 32).
+template <int D32, bool kRelu, int kScoreQB, int kScoreKeys>
 __global__ __launch_bounds__(kScoreThreads) void attention_scores_kernel(const uint16_t* q, const uint16_t* k,
                                                                          uint32_t tokens, uint32_t dim,
                                                                          uint32_t blocks_per_group, float* scores)
 {
-    constexpr int kSteps = D32 * 4;                  // MFMA steps of 8 channels
-    constexpr int kRowBytes = D32 * 64 + 8;          // one key row in LDS: channels, then 8 bytes of padding
+    constexpr int kScoreQueries = 128 * kScoreQB;    // per workgroup
+    constexpr int kSteps = D32 * 2;                  // MFMA steps of 16 channels
+    constexpr int kRowBytes = D32 * 64 + 16;         // one key row in LDS: channels, then 16 bytes of padding
     __shared__ __align__(16) uint8_t lds[2][kScoreKeys * kRowBytes];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t g = blockIdx.x / blocks_per_group;
-    const uint32_t q0 = (blockIdx.x - g * blocks_per_group) * kScoreQueries + wave * 32u;
+    const uint32_t q0 = (blockIdx.x - g * blocks_per_group) * kScoreQueries + wave * (32u * kScoreQB);
     const uint16_t* qg = q + (size_t)g * tokens * dim;
     const uint16_t* kg = k + (size_t)g * tokens * dim;
     const uint32_t half = lane >> 5, col = lane & 31u;
 
-    // ---- this wavefront's queries as B operands: lane holds query q0 + lane % 32, channels 8 s + 4 (lane / 32) ..
+    // ---- this wavefront's queries as B operands: lane holds query q0 + lane % 32, channels 16 s + 8 (lane / 32) ..
     // (a query past the end reads the last one; a channel past `dim` is zero)
-    mfma_bf16x4 qf[kSteps];
-    {
-        const uint16_t* row = qg + (size_t)min(q0 + col, tokens - 1u) * dim;
+    mfma_bf16x8 qf[kScoreQB][kSteps];
+#pragma unroll
+    for (int b = 0; b < kScoreQB; ++b) {
+        const uint16_t* row = qg + (size_t)min(q0 + 32u * b + col, tokens - 1u) * dim;
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) {
-            const uint32_t c = 8u * s + 4u * half;
-            uint2 v = make_uint2(0, 0);
-            if (c + 4u <= dim) v = *reinterpret_cast<const uint2*>(row + c);   // dim is a multiple of 8
-            qf[s] = __builtin_bit_cast(mfma_bf16x4, v);
+            const uint32_t c = 16u * s + 8u * half;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (c + 8u <= dim) v = *reinterpret_cast<const uint4*>(row + c);   // dim is a multiple of 8
+            qf[b][s] = __builtin_bit_cast(mfma_bf16x8, v);
         }
     }
     // ---- key blocks: 32 keys x dim channels; thread t stages 16-byte pieces t, t + 256, ...
@@ -84,10 +88,7 @@ __global__ __launch_bounds__(kScoreThreads) void attention_scores_kernel(const u
             const uint32_t piece = threadIdx.x + i * kScoreThreads;
             const uint32_t r = piece / kPiecesPerRow, cb = (piece - r * kPiecesPerRow) * 16u;
             if (piece < (uint32_t)kPieces) {
-                // (rows are 8-byte aligned only: two 8-byte writes)
-                uint2* dst = reinterpret_cast<uint2*>(&lds[buf][r * kRowBytes + cb]);
-                dst[0] = make_uint2(stage[i].x, stage[i].y);
-                dst[1] = make_uint2(stage[i].z, stage[i].w);
+                *reinterpret_cast<uint4*>(&lds[buf][r * kRowBytes + cb]) = stage[i];
             }
         }
     };
@@ -95,24 +96,41 @@ __global__ __launch_bounds__(kScoreThreads) void attention_scores_kernel(const u
     fetch(0);
     deposit(0);
     __syncthreads();
-    float sum = 0.0f;   // over this lane's keys of f(S[query][key])
+    float sum[kScoreQB];   // over this lane's keys of f(S[query][key])
+#pragma unroll
+    for (int b = 0; b < kScoreQB; ++b) sum[b] = 0.0f;
     for (uint32_t kb = 0; kb < n_kb; ++kb) {
         const int buf = kb & 1;
         if (kb + 1 < n_kb) fetch(kb + 1);
-        mfma_f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) {
-            // A operand: key row lane % 32 of the block, channels 8 s + 4 (lane / 32) ..
-            const uint2 a = *reinterpret_cast<const uint2*>(&lds[buf][col * kRowBytes + s * 16 + half * 8]);
-            acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(mfma_bf16x4, a), qf[s], acc, 0, 0, 0);
+        for (int kk = 0; kk < kScoreKeys / 32; ++kk) {   // 32 keys at a time
+            mfma_f32x16 acc[kScoreQB];
+#pragma unroll
+            for (int b = 0; b < kScoreQB; ++b) acc[b] = mfma_f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s) {
+                // A operand: key row lane % 32 of the 32 keys, channels 16 s + 8 (lane / 32) ..; one read feeds the
+                // MFMAs of all the wavefront's query blocks (with one block per read the kernel is bound by LDS bandwidth)
+                const uint4 a = *reinterpret_cast<const uint4*>(&lds[buf][(kk * 32 + col) * kRowBytes + s * 32 + half * 16]);
+#pragma unroll
+                for (int b = 0; b < kScoreQB; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mfma_bf16x8, a), qf[b][s], acc[b], 0, 0, 0);
+            }
+#pragma unroll
+            for (int b = 0; b < kScoreQB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum[b] += kRelu ? fmaxf(acc[b][r], 0.0f) : fabsf(acc[b][r]);
+            }
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += kRelu ? fmaxf(acc[r], 0.0f) : fabsf(acc[r]);
         if (kb + 1 < n_kb) deposit(buf ^ 1);
         __syncthreads();
     }
-    sum += __shfl_xor(sum, 32);   // the two half-wavefronts hold different keys of the same query
-    if (half == 0 && q0 + col < tokens) scores[(size_t)g * tokens + q0 + col] = sum / (float)tokens;
+#pragma unroll
+    for (int b = 0; b < kScoreQB; ++b) {
+        const float total = sum[b] + __shfl_xor(sum[b], 32);   // the two half-wavefronts hold different keys of the same query
+        const uint32_t qi = q0 + 32u * b + col;
+        if (half == 0 && qi < tokens) scores[(size_t)g * tokens + qi] = total / (float)tokens;
+    }
 }
 
 constexpr int kSelectThreads = 256;

@@ -1087,8 +1087,9 @@ def test_attention_scores_against_the_oracle(F, mode):
     """The one floating-point contraction of the library (bf16 products, fp32 accumulation on the matrix cores):
     compared with the float64 oracle to 2e-5 relative (the terms of a score are all non-negative: no cancellation
     in the sum over keys; a single dot product loses at most sqrt(dim) * 2^-24 of its operands' magnitude)."""
+    # (groups of up to 64 tokens -- temporal attention -- run the small shape of the kernel, longer ones the large)
     for groups, tokens, dim in [(3, 100, 64), (2, 1024, 128), (5, 33, 72), (1, 1, 8), (2, 257, 256), (4, 128, 40),
-                                (2, 300, 96), (1, 2049, 16)]:
+                                (2, 300, 96), (1, 2049, 16), (300, 16, 72), (50, 64, 128), (7, 65, 64), (3, 513, 200)]:
         q, k = synth.attention_qk(groups, tokens, dim, seed=tokens + dim, device="cuda")
         got = F.fb4_attention_scores(q, k, mode).cpu().numpy().astype(np.float64)
         torch.cuda.synchronize()
