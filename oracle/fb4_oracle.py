@@ -260,6 +260,50 @@ def select_salient_tokens(scores, grid_h, grid_w, tile_h=4, tile_w=4):
     return out
 
 
+def seda_assign(q_bits, k_bits, anchors, grid_h, grid_w, window=5, threshold=5.0):
+    """Sec. 3.4, "Attention-Guided Semantic Relatedness Extraction", the per-frame part: every tile's anchor token
+    (one per frame and tile: `anchors`, int32 [frames][tiles], rows of the [frames * tokens] tensor, ascending per
+    frame as select_salient_tokens returns them -- tile g of a frame is the g-th tile in row-major tile order, found
+    again from the anchor's position) marks as correlated the tokens of a window x window square around it (clipped
+    to the frame) whose raw pre-softmax attention score FROM the anchor, Q[anchor] . K[token] averaged over the heads,
+    exceeds `threshold`.  A token marked by several anchors belongs to the one with the highest group number (the
+    "subsequent" anchor); an anchor always belongs to its own group.  Group number = position of the anchor in its
+    frame's list.  q_bits, k_bits: uint16 [frames][heads][tokens][dim].  Returns (token_group int32 [frames * tokens],
+    -1 = none; anchor_group int32 [frames * tokens], the group on anchor rows and -1 elsewhere; score float64
+    [frames][tiles][window * window], NaN outside the frame).  Plain loops; the dot products are numpy float64."""
+    q = _bf16_to_f64(q_bits)
+    k = _bf16_to_f64(k_bits)
+    frames, heads, tokens, dim = q.shape
+    assert tokens == grid_h * grid_w
+    anchors = np.asarray(anchors, dtype=np.int64)
+    tiles = anchors.shape[1]
+    token_group = np.full(frames * tokens, -1, dtype=np.int32)
+    anchor_group = np.full(frames * tokens, -1, dtype=np.int32)
+    score = np.full((frames, tiles, window * window), np.nan)
+    half = window // 2
+    for f in range(frames):
+        for g in range(tiles):
+            a = int(anchors[f, g]) - f * tokens
+            ay, ax = divmod(a, grid_w)
+            for wy in range(window):
+                for wx in range(window):
+                    y, x = ay + wy - half, ax + wx - half
+                    if not (0 <= y < grid_h and 0 <= x < grid_w):
+                        continue
+                    t = y * grid_w + x
+                    sc = 0.0
+                    for h in range(heads):
+                        sc += float(q[f, h, a] @ k[f, h, t])
+                    sc /= heads
+                    score[f, g, wy * window + wx] = sc
+                    if sc > threshold:
+                        token_group[f * tokens + t] = max(token_group[f * tokens + t], g)
+        for g in range(tiles):                      # an anchor belongs to its own group
+            token_group[int(anchors[f, g])] = g
+            anchor_group[int(anchors[f, g])] = g
+    return token_group, anchor_group, score
+
+
 def seda_profile(fbk, meta, anchor_group, n_groups):
     """Sec. 3.4, "Constructing an 8-Dialect Sub-Formatbook": bin-count profile of the dialects selected on the
     anchor tokens of each group, then per dynamic-range bucket (largest magnitude 8..15) the most frequently

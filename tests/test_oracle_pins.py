@@ -929,3 +929,30 @@ def test_salient_token_selection_per_tile():
             ys, xs = range(tile[0] * 4, min(7, tile[0] * 4 + 4)), range(tile[1] * 4, min(10, tile[1] * 4 + 4))
             assert mean[f, t] == max(mean[f, yy * 10 + xx] for yy in ys for xx in xs)
         assert len(seen) == 6
+
+
+def test_seda_assignment_marks_the_window_tokens_an_anchor_attends_to():
+    # one frame, one head, 4 x 4 grid, 2 channels; anchors at tokens 5 and 10; window 3
+    q = np.zeros((1, 1, 16, 2), dtype=np.float32)
+    k = np.zeros((1, 1, 16, 2), dtype=np.float32)
+    q[0, 0, 5] = [1, 0]; q[0, 0, 10] = [0, 1]
+    k[0, 0, :, 0] = [0, 9, 0, 0,  2, 0, 7, 0,  0, 6, 0, 0,  0, 0, 0, 0]      # what anchor 5 sees
+    k[0, 0, :, 1] = [0, 0, 0, 0,  0, 8, 6.5, 0,  0, 0, 0, 9,  0, 0, 9, 5]    # what anchor 10 sees
+    tg, ag, sc = O.seda_assign(f2b(q), f2b(k), [[5, 10]], 4, 4, window=3, threshold=5.0)
+    # anchor 5 (row 1, col 1) sees tokens 0-2, 4-6, 8-10: above 5 are 1 (9), 6 (7), 9 (6)
+    # anchor 10 (row 2, col 2) sees 5-7, 9-11, 13-15: above 5 are 5 (8), 6 (6.5), 11 (9), 14 (9); 15 (5) is not above
+    want = np.full(16, -1)
+    want[[1, 9]] = 0
+    want[[6, 11, 14]] = 1          # token 6: both anchors -> the later one
+    want[5] = 0; want[10] = 1      # anchors keep their own group (anchor 10 marked token 5, but 5 is an anchor)
+    assert tg.tolist() == want.tolist()
+    assert ag.tolist() == [-1] * 5 + [0] + [-1] * 4 + [1] + [-1] * 5
+    assert sc[0, 0].tolist() == [0, 9, 0, 2, 0, 7, 0, 6, 0] and sc[0, 1, 8] == 5.0
+    # a window clipped by the frame edge, two heads averaged, negative scores never mark
+    q2 = np.zeros((1, 2, 16, 2), dtype=np.float32); k2 = np.zeros((1, 2, 16, 2), dtype=np.float32)
+    q2[0, :, 0] = [1, 0]
+    k2[0, 0, :, 0] = [0, 12, 0, 0, -20, 4, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0]
+    k2[0, 1, :, 0] = [0, 0, 0, 0, -20, 8, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0]
+    tg, _, sc = O.seda_assign(f2b(q2), f2b(k2), [[0]], 4, 4, window=3, threshold=5.0)
+    assert tg.tolist() == [0, 0, -1, -1, -1, 0] + [-1] * 10           # token 1: (12 + 0) / 2 = 6, token 5: 6, token 4: -20
+    assert np.isnan(sc[0, 0, :3]).all() and np.isnan(sc[0, 0, 3]) and sc[0, 0, 5] == 6.0
