@@ -353,6 +353,34 @@ int fb4_attention_scores(const void* q, const void* k, int64_t groups, int64_t t
 int fb4_select_salient_tokens(const float* scores, int64_t frames, int heads, int grid_h, int grid_w,
                               int tile_h, int tile_w, int32_t* rows_out, void* stream);
 
+/*
+ * Sec. 3.4 ("Attention-Guided Semantic Relatedness Extraction"), the per-frame
+ * part: every anchor token -- one per frame and tile, as
+ * fb4_select_salient_tokens returns them -- marks as correlated the tokens of
+ * a window x window square around it (clipped to the frame) whose raw
+ * pre-softmax attention score from the anchor, Q[anchor] . K[token] averaged
+ * over the heads (fp32), exceeds `threshold`.  A token marked by several
+ * anchors belongs to the one with the highest group number; an anchor belongs
+ * to its own group.  Group number = position of the anchor in its frame's
+ * list, so the tiles of all frames share groups.  The cross-frame main anchor
+ * and the pruning of weakly correlated frames are left to the caller (an
+ * anchor entry outside its frame marks nothing).
+ *   q, k           device, bf16 [frames][heads][tokens][dim], tokens = grid_h *
+ *                  grid_w, dim a multiple of 8 (FB4_ERR_UNSUPPORTED otherwise)
+ *   anchors        device, int32 [frames][tiles], rows of [frames * tokens]
+ *   window         1..8 (FB4_ERR_UNSUPPORTED beyond); the square is centred
+ *                  at the anchor, window / 2 tokens to the left and above
+ *   token_group    device, int32 [frames * tokens]: group or -1 -- the
+ *                  token_group argument of fb4_quantize_seda
+ *   anchor_group   device, int32 [frames * tokens]: the group on anchor rows,
+ *                  -1 elsewhere -- the anchor_group argument of fb4_seda_profile
+ *   window_scores  device, float [frames][tiles][window * window] or NULL: the
+ *                  scores that were compared (NaN outside the frame)
+ */
+int fb4_seda_assign(const void* q, const void* k, int64_t frames, int heads, int grid_h, int grid_w,
+                    int64_t dim, const int32_t* anchors, int tiles, int window, float threshold,
+                    int32_t* token_group, int32_t* anchor_group, float* window_scores, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -69,6 +69,7 @@ def _load():
     lib.fb4_repack_mxfp8.argtypes = [p, p, p, i64, i64, i32, p, i64, p, p]
     lib.fb4_attention_scores.argtypes = [p, p, i64, i64, i64, i32, p, p]
     lib.fb4_select_salient_tokens.argtypes = [p, i64, i32, i32, i32, i32, i32, p, p]
+    lib.fb4_seda_assign.argtypes = [p, p, i64, i32, i32, i32, i64, p, i32, i32, ctypes.c_float, p, p, p, p]
     lib.fb4_gelu_table_host.argtypes = [i32, p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
     lib.fb4_gelu_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, i32, p, p, i32, p, p, p]
     lib.fb4_layernorm_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, ctypes.c_float, p, p, i32,
@@ -82,7 +83,8 @@ EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts
            "fb4_free_luts", "fb4_quantize", "fb4_quantize_seda", "fb4_decompose", "fb4_dequantize",
            "fb4_quantize_decompose", "fb4_seda_profile",
            "fb4_repack_mxfp8", "fb4_layernorm_quantize", "fb4_gelu_quantize",
-           "fb4_gelu_table_host", "fb4_attention_scores", "fb4_select_salient_tokens"]
+           "fb4_gelu_table_host", "fb4_attention_scores", "fb4_select_salient_tokens",
+           "fb4_seda_assign"]
 
 
 def lib():
@@ -218,6 +220,20 @@ def fb4_select_salient_tokens(scores, grid_h, grid_w, tile_h=4, tile_w=4, rows_o
     _check(_lib.fb4_select_salient_tokens(_dp(scores), frames, heads, grid_h, grid_w, tile_h, tile_w, _dp(rows_out),
                                           _stream(stream)), "fb4_select_salient_tokens")
     return rows_out
+
+
+def fb4_seda_assign(q, k, anchors, grid_h, grid_w, window=5, threshold=5.0, want_scores=False, stream=None):
+    """q, k: bf16 cuda [frames][heads][tokens][dim]; anchors: int32 cuda [frames][tiles].  Returns (token_group,
+    anchor_group) int32 [frames * tokens] (and the compared scores, float32 [frames][tiles][window^2], if asked)."""
+    frames, heads, tokens, dim = q.shape
+    assert tokens == grid_h * grid_w
+    tiles = anchors.shape[1]
+    tg = torch.empty(frames * tokens, dtype=torch.int32, device=q.device)
+    ag = torch.empty(frames * tokens, dtype=torch.int32, device=q.device)
+    sc = torch.empty((frames, tiles, window * window), dtype=torch.float32, device=q.device) if want_scores else None
+    _check(_lib.fb4_seda_assign(_dp(q), _dp(k), frames, heads, grid_h, grid_w, dim, _dp(anchors), tiles, window,
+                                float(threshold), _dp(tg), _dp(ag), _dp(sc), _stream(stream)), "fb4_seda_assign")
+    return (tg, ag, sc) if want_scores else (tg, ag)
 
 
 def fb4_gelu_table_host(approximate=0):

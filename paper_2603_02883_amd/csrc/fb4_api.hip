@@ -864,4 +864,29 @@ int fb4_select_salient_tokens(const float* scores, int64_t frames, int heads, in
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
+int fb4_seda_assign(const void* q, const void* k, int64_t frames, int heads, int grid_h, int grid_w, int64_t dim,
+                    const int32_t* anchors, int tiles, int window, float threshold, int32_t* token_group,
+                    int32_t* anchor_group, float* window_scores, void* stream)
+{
+    if (frames < 0 || heads < 1 || grid_h < 1 || grid_w < 1 || dim < 1 || tiles < 1 || window < 1) return FB4_ERR_INVALID_ARG;
+    if (!(threshold == threshold)) return FB4_ERR_INVALID_ARG;
+    if (frames == 0) return FB4_OK;
+    if (!q || !k || !anchors || !token_group || !anchor_group) return FB4_ERR_INVALID_ARG;
+    const int64_t tokens = (int64_t)grid_h * grid_w;
+    if ((dim % 8) || window > 8 || !aligned(q, 16) || !aligned(k, 16) || !aligned(anchors, 4) || !aligned(token_group, 4) ||
+        !aligned(anchor_group, 4) || (window_scores && !aligned(window_scores, 4)))
+        return FB4_ERR_UNSUPPORTED;
+    if (frames * tokens > 0x7FFFFFFFll || frames * tiles > 0x7FFFFFFFll || tokens * dim > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t n = (uint32_t)(frames * tokens);
+    hipLaunchKernelGGL(seda_fill_kernel, dim3((n + 255) / 256), dim3(256), 0, s, token_group, anchor_group, n);
+    hipLaunchKernelGGL(seda_mark_kernel, dim3((unsigned)(frames * tiles)), dim3(kAssignThreads), 0, s,
+                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), (uint32_t)heads, (uint32_t)grid_h,
+                       (uint32_t)grid_w, (uint32_t)dim, anchors, (uint32_t)tiles, (uint32_t)window, threshold, token_group,
+                       window_scores);
+    hipLaunchKernelGGL(seda_anchor_kernel, dim3((unsigned)((frames * tiles + 255) / 256)), dim3(256), 0, s, anchors,
+                       (uint32_t)frames, (uint32_t)tiles, (uint32_t)tokens, token_group, anchor_group);
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
 }  // extern "C"

@@ -187,4 +187,66 @@ __global__ __launch_bounds__(kSelectThreads) void select_salient_kernel(const fl
         if (chosen[t]) out[at++] = (int32_t)(frame * tokens + t);
 }
 
+// Sec. 3.4, per-frame part of the anchor / correlated-token extraction: every anchor (one per frame and tile)
+// marks the tokens of a window x window square around it whose raw attention score from the anchor -- Q[anchor] .
+// K[token], averaged over the heads -- exceeds a threshold; a token marked by several anchors belongs to the one
+// with the highest group number, an anchor to its own group.  Three small launches: fill with -1, mark (one
+// wavefront per anchor, one lane per window token, a maximum on the group number), anchors.
+constexpr int kAssignThreads = 64;
+
+__global__ __launch_bounds__(256) void seda_fill_kernel(int32_t* a, int32_t* b, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i < n) { a[i] = -1; b[i] = -1; }
+}
+
+__global__ __launch_bounds__(kAssignThreads) void seda_mark_kernel(const uint16_t* q, const uint16_t* k, uint32_t heads,
+                                                                   uint32_t grid_h, uint32_t grid_w, uint32_t dim,
+                                                                   const int32_t* anchors, uint32_t tiles, uint32_t window,
+                                                                   float threshold, int32_t* token_group, float* scores)
+{
+    const uint32_t tokens = grid_h * grid_w;
+    const uint32_t f = blockIdx.x / tiles, g = blockIdx.x - f * tiles;
+    const int64_t a = (int64_t)anchors[(size_t)f * tiles + g] - (int64_t)f * tokens;
+    const uint32_t w = threadIdx.x;
+    if (w >= window * window) return;
+    float* out = scores ? scores + ((size_t)f * tiles + g) * window * window + w : nullptr;
+    if (out) *out = __builtin_nanf("");
+    if (a < 0 || a >= (int64_t)tokens) return;   // not a token of this frame: marks nothing
+    const int32_t ay = (int32_t)((uint32_t)a / grid_w), ax = (int32_t)((uint32_t)a % grid_w);
+    const int32_t y = ay + (int32_t)(w / window) - (int32_t)(window / 2), x = ax + (int32_t)(w % window) - (int32_t)(window / 2);
+    if (y < 0 || y >= (int32_t)grid_h || x < 0 || x >= (int32_t)grid_w) return;
+    const uint32_t t = (uint32_t)y * grid_w + (uint32_t)x;
+    float acc = 0.0f;
+    for (uint32_t h = 0; h < heads; ++h) {
+        const size_t base = ((size_t)f * heads + h) * tokens;
+        const uint4* qr = reinterpret_cast<const uint4*>(q + (base + (uint32_t)a) * dim);
+        const uint4* kr = reinterpret_cast<const uint4*>(k + (base + t) * dim);
+        for (uint32_t c = 0; c < dim / 8; ++c) {
+            const uint4 qa = qr[c], kb = kr[c];
+            const uint32_t qs[4] = {qa.x, qa.y, qa.z, qa.w}, ks[4] = {kb.x, kb.y, kb.z, kb.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc = __builtin_fmaf(__uint_as_float(qs[i] << 16), __uint_as_float(ks[i] << 16), acc);
+                acc = __builtin_fmaf(__uint_as_float(qs[i] & 0xFFFF0000u), __uint_as_float(ks[i] & 0xFFFF0000u), acc);
+            }
+        }
+    }
+    const float sc = acc / (float)heads;
+    if (out) *out = sc;
+    if (sc > threshold) atomicMax(token_group + (size_t)f * tokens + t, (int32_t)g);
+}
+
+__global__ __launch_bounds__(256) void seda_anchor_kernel(const int32_t* anchors, uint32_t frames, uint32_t tiles,
+                                                          uint32_t tokens, int32_t* token_group, int32_t* anchor_group)
+{
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= frames * tiles) return;
+    const uint32_t f = i / tiles, g = i - f * tiles;
+    const int64_t row = anchors[i];
+    if (row < (int64_t)f * tokens || row >= (int64_t)(f + 1) * tokens) return;
+    token_group[row] = (int32_t)g;
+    anchor_group[row] = (int32_t)g;
+}
+
 }  // namespace fb4

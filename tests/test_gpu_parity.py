@@ -1156,3 +1156,56 @@ def test_salient_token_selection_and_the_whole_chain(F, luts):
     with pytest.raises(F.Fb4Error) as e:
         F.fb4_select_salient_tokens(torch.zeros((1, 1, 128 * 128), device="cuda"), 128, 128)   # more than 8192 tokens
     assert e.value.code == F.ERR_UNSUPPORTED
+
+
+def test_seda_assignment_and_the_chain_to_restricted_quantization(F, luts):
+    """Sec. 3.4 on the GPU from Q and K: anchors (one per frame and tile) -> correlated tokens -> dialect profile of the
+    anchors -> sub-formatbooks -> quantization restricted to them.  The threshold comparison is made on fp32 scores:
+    a token whose float64 score lies within 1e-4 of the threshold may fall on either side and is left out of the
+    comparison (none is expected on this input); everything else is bit-exact."""
+    for frames, heads, gh, gw, dim, window, thr in [(3, 4, 12, 16, 64, 5, 6.0), (2, 2, 7, 9, 40, 3, 2.0), (1, 1, 4, 4, 8, 8, 0.5)]:
+        tokens = gh * gw
+        q, k = synth.attention_qk(frames * heads, tokens, dim, seed=gh + dim, device="cuda")
+        q4, k4 = q.view(frames, heads, tokens, dim), k.view(frames, heads, tokens, dim)
+        qb, kb = synth.bf16_bits(q).reshape(frames, heads, tokens, dim), synth.bf16_bits(k).reshape(frames, heads, tokens, dim)
+        ref_scores = O.attention_scores(qb.reshape(-1, tokens, dim), kb.reshape(-1, tokens, dim), "abs")
+        sc32 = ref_scores.astype(np.float32).reshape(frames, heads, tokens)
+        anchors = O.select_salient_tokens(sc32, gh, gw)
+        tg, ag, sc = F.fb4_seda_assign(q4, k4, torch.from_numpy(anchors).cuda(), gh, gw, window, thr, want_scores=True)
+        torch.cuda.synchronize()
+        tgr, agr, scr = O.seda_assign(qb, kb, anchors, gh, gw, window, thr)
+        got = sc.cpu().numpy().astype(np.float64)
+        assert np.array_equal(np.isnan(got), np.isnan(scr))
+        inside = ~np.isnan(scr)
+        assert np.abs(got[inside] - scr[inside]).max() <= 2e-5 * np.abs(scr[inside]).max() + 1e-6
+        assert np.array_equal(ag.cpu().numpy(), agr)
+        borderline = inside & (np.abs(scr - thr) <= 1e-4 * max(1.0, abs(thr)))
+        assert not borderline.any()                                 # (seeded input: stays so)
+        assert np.array_equal(tg.cpu().numpy(), tgr)
+        assert (tgr >= 0).sum() > anchors.size                      # some correlated tokens beyond the anchors
+    # the chain on the last-but-two shape: 3 frames x 192 tokens, 12 tiles = 12 groups
+    frames, heads, gh, gw, dim = 3, 4, 12, 16, 64
+    tokens = gh * gw
+    q, k = synth.attention_qk(frames * heads, tokens, dim, seed=gh + dim, device="cuda")
+    scores = F.fb4_attention_scores(q, k, 0)
+    anchors_d = F.fb4_select_salient_tokens(scores.view(frames, heads, tokens), gh, gw)
+    tg, ag = F.fb4_seda_assign(q.view(frames, heads, tokens, dim), k.view(frames, heads, tokens, dim), anchors_d, gh, gw, 5, 6.0)
+    x = synth.vdit_activation(rows=frames * tokens, cols=1024, seed=4, device="cuda")
+    c, m = F.fb4_quantize(luts, F.opts(), x)
+    n_groups = anchors_d.shape[1]
+    counts, sub = F.fb4_seda_profile(luts, m, ag, n_groups)
+    cs, ms = F.fb4_quantize_seda(luts, F.opts(), x, tg, sub)
+    torch.cuda.synchronize()
+    tg_h, ag_h = tg.cpu().numpy(), ag.cpu().numpy()
+    xb = synth.bf16_bits(x)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, xb)
+    counts_r, sub_r = O.seda_profile(DEFAULT_FORMATBOOK, mr, ag_h, n_groups)
+    assert np.array_equal(counts.cpu().numpy().astype(np.uint32), counts_r) and np.array_equal(sub.cpu().numpy(), sub_r)
+    valid = (sub_r < 32).all(axis=1)                                # (every range bucket has a dialect in the default table)
+    assert valid.all()
+    csr, msr = O.quantize(DEFAULT_FORMATBOOK, xb, token_group=tg_h, sub_formatbooks=sub_r)
+    assert np.array_equal(host_u8(cs), csr) and np.array_equal(host_u16(ms), msr)
+    # argument checks
+    with pytest.raises(F.Fb4Error) as e:
+        F.fb4_seda_assign(q.view(frames, heads, tokens, dim), k.view(frames, heads, tokens, dim), anchors_d, gh, gw, 9, 6.0)
+    assert e.value.code == F.ERR_UNSUPPORTED
