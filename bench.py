@@ -352,7 +352,13 @@ def main():
         def select_step(i):
             F.fb4_select_salient_tokens(att.view(16, 24, 1024), 32, 32, rows_out=sal_rows)
         add("select_salient_tokens_16x24x1024", select_step, 16 * 24 * 1024 * 4 + 16 * 64 * 4, 16 * 1024)
-        del qa, ka
+        # ... and the tokens each of those 1024 anchors is correlated with (5 x 5 window, Sec. 3.4)
+        q4, k4 = qa.view(16, 24, 1024, 128), ka.view(16, 24, 1024, 128)
+
+        def assign_step(i):
+            F.fb4_seda_assign(q4, k4, sal_rows, 32, 32, 5, 5.0)
+        add("seda_assign_16x24x1024_window5", assign_step, 1024 * 26 * 24 * 128 * 2 + 2 * 16384 * 4, 16 * 1024)
+        del qa, ka, q4, k4
         # decomposition (cfg3): 5 % salient rows
         sal = synth.salient_rows_from_attention(ROWS, frac=0.05, heads=24, seed=3, device="cuda")
         sal_d = torch.from_numpy(sal).cuda()

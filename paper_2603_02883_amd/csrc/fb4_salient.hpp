@@ -191,8 +191,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_salient_kernel(const fl
 // marks the tokens of a window x window square around it whose raw attention score from the anchor -- Q[anchor] .
 // K[token], averaged over the heads -- exceeds a threshold; a token marked by several anchors belongs to the one
 // with the highest group number, an anchor to its own group.  Three small launches: fill with -1, mark (one
-// wavefront per anchor, one lane per window token, a maximum on the group number), anchors.
-constexpr int kAssignThreads = 64;
+// workgroup per anchor: 64 window slots x 4 shares of the heads, a maximum on the group number), anchors.
+constexpr int kAssignThreads = 256;   // 64 window slots x 4 groups of heads
 
 __global__ __launch_bounds__(256) void seda_fill_kernel(int32_t* a, int32_t* b, uint32_t n)
 {
@@ -205,36 +205,57 @@ __global__ __launch_bounds__(kAssignThreads) void seda_mark_kernel(const uint16_
                                                                    const int32_t* anchors, uint32_t tiles, uint32_t window,
                                                                    float threshold, int32_t* token_group, float* scores)
 {
+    __shared__ float partial[4][64];
     const uint32_t tokens = grid_h * grid_w;
     const uint32_t f = blockIdx.x / tiles, g = blockIdx.x - f * tiles;
     const int64_t a = (int64_t)anchors[(size_t)f * tiles + g] - (int64_t)f * tokens;
-    const uint32_t w = threadIdx.x;
-    if (w >= window * window) return;
-    float* out = scores ? scores + ((size_t)f * tiles + g) * window * window + w : nullptr;
-    if (out) *out = __builtin_nanf("");
-    if (a < 0 || a >= (int64_t)tokens) return;   // not a token of this frame: marks nothing
-    const int32_t ay = (int32_t)((uint32_t)a / grid_w), ax = (int32_t)((uint32_t)a % grid_w);
+    const uint32_t w = threadIdx.x & 63u, hq = threadIdx.x >> 6;
+    // (no early exit: every thread reaches the barrier)
+    const bool slot = w < window * window;
+    const bool anchor_ok = a >= 0 && a < (int64_t)tokens;   // otherwise: not a token of this frame, marks nothing
+    const uint32_t ac = anchor_ok ? (uint32_t)a : 0u;
+    const int32_t ay = (int32_t)(ac / grid_w), ax = (int32_t)(ac % grid_w);
     const int32_t y = ay + (int32_t)(w / window) - (int32_t)(window / 2), x = ax + (int32_t)(w % window) - (int32_t)(window / 2);
-    if (y < 0 || y >= (int32_t)grid_h || x < 0 || x >= (int32_t)grid_w) return;
-    const uint32_t t = (uint32_t)y * grid_w + (uint32_t)x;
+    const bool inside = slot && anchor_ok && y >= 0 && y < (int32_t)grid_h && x >= 0 && x < (int32_t)grid_w;
+    const uint32_t t = inside ? (uint32_t)y * grid_w + (uint32_t)x : 0u;
     float acc = 0.0f;
-    for (uint32_t h = 0; h < heads; ++h) {
-        const size_t base = ((size_t)f * heads + h) * tokens;
-        const uint4* qr = reinterpret_cast<const uint4*>(q + (base + (uint32_t)a) * dim);
-        const uint4* kr = reinterpret_cast<const uint4*>(k + (base + t) * dim);
-        for (uint32_t c = 0; c < dim / 8; ++c) {
-            const uint4 qa = qr[c], kb = kr[c];
-            const uint32_t qs[4] = {qa.x, qa.y, qa.z, qa.w}, ks[4] = {kb.x, kb.y, kb.z, kb.w};
+    if (inside) {
+        float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // four chains: 16-byte pieces c, c + 1, c + 2, c + 3 (mod 4)
+        for (uint32_t h = hq; h < heads; h += 4) {   // this thread's share of the heads
+            const size_t base = ((size_t)f * heads + h) * tokens;
+            const uint4* qr = reinterpret_cast<const uint4*>(q + (base + ac) * dim);
+            const uint4* kr = reinterpret_cast<const uint4*>(k + (base + t) * dim);
+            const uint32_t n16 = dim / 8;
+            for (uint32_t c = 0; c < n16; c += 4) {
+                uint4 qa[4], kb[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc = __builtin_fmaf(__uint_as_float(qs[i] << 16), __uint_as_float(ks[i] << 16), acc);
-                acc = __builtin_fmaf(__uint_as_float(qs[i] & 0xFFFF0000u), __uint_as_float(ks[i] & 0xFFFF0000u), acc);
+                for (int j = 0; j < 4; ++j) {   // (a piece past the row's end re-reads the last one and is skipped)
+                    qa[j] = qr[min(c + j, n16 - 1u)];
+                    kb[j] = kr[min(c + j, n16 - 1u)];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (c + j < n16) {
+                        const uint32_t qs[4] = {qa[j].x, qa[j].y, qa[j].z, qa[j].w}, ks[4] = {kb[j].x, kb[j].y, kb[j].z, kb[j].w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            part[j] = __builtin_fmaf(__uint_as_float(qs[i] << 16), __uint_as_float(ks[i] << 16), part[j]);
+                            part[j] = __builtin_fmaf(__uint_as_float(qs[i] & 0xFFFF0000u), __uint_as_float(ks[i] & 0xFFFF0000u), part[j]);
+                        }
+                    }
+                }
             }
         }
+        acc = (part[0] + part[1]) + (part[2] + part[3]);
     }
-    const float sc = acc / (float)heads;
-    if (out) *out = sc;
-    if (sc > threshold) atomicMax(token_group + (size_t)f * tokens + t, (int32_t)g);
+    partial[hq][w] = acc;
+    __syncthreads();
+    if (hq == 0 && slot) {
+        float* out = scores ? scores + ((size_t)f * tiles + g) * window * window + w : nullptr;
+        const float sc = (partial[0][w] + partial[1][w] + partial[2][w] + partial[3][w]) / (float)heads;   // fixed order
+        if (out) *out = inside ? sc : __builtin_nanf("");
+        if (inside && sc > threshold) atomicMax(token_group + (size_t)f * tokens + t, (int32_t)g);
+    }
 }
 
 __global__ __launch_bounds__(256) void seda_anchor_kernel(const int32_t* anchors, uint32_t frames, uint32_t tiles,
