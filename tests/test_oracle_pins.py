@@ -912,6 +912,12 @@ def test_salient_token_selection_per_tile():
     s[0, 0, 2] = 3                            # tile (0,1): token 2, mean 1.5 (one head only)
     s[0, 1, 10] = 2.5; s[0, :, 15] = np.nan   # tile (1,1): token 10; a NaN never wins.  tile (1,0): all equal -> 8
     assert O.select_salient_tokens(s, 4, 4, 2, 2).tolist() == [[2, 5, 8, 10]]
+    # tiles that are not square: 4 x 6 grid, tiles 2 high and 3 wide; the best of tile (0,1) = columns 3-5 of rows 0-1
+    s2 = np.zeros((1, 1, 24))
+    s2[0, 0, 2 * 6 + 1] = 5          # row 2, col 1 -> tile (1,0)
+    s2[0, 0, 1 * 6 + 4] = 7          # row 1, col 4 -> tile (0,1)
+    s2[0, 0, 3 * 6 + 5] = 1          # row 3, col 5 -> tile (1,1)
+    assert O.select_salient_tokens(s2, 4, 6, 2, 3).tolist() == [[0, 10, 13, 23]]
     # ragged tiles, several frames: one token per tile, inside its tile, with the tile's largest mean
     rng = np.random.default_rng(83)
     sc = rng.random((3, 5, 7 * 10)).astype(np.float32)
