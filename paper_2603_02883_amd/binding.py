@@ -222,14 +222,15 @@ def fb4_select_salient_tokens(scores, grid_h, grid_w, tile_h=4, tile_w=4, rows_o
     return rows_out
 
 
-def fb4_seda_assign(q, k, anchors, grid_h, grid_w, window=5, threshold=5.0, want_scores=False, stream=None):
+def fb4_seda_assign(q, k, anchors, grid_h, grid_w, window=5, threshold=5.0, want_scores=False, stream=None,
+                    token_group=None, anchor_group=None):
     """q, k: bf16 cuda [frames][heads][tokens][dim]; anchors: int32 cuda [frames][tiles].  Returns (token_group,
     anchor_group) int32 [frames * tokens] (and the compared scores, float32 [frames][tiles][window^2], if asked)."""
     frames, heads, tokens, dim = q.shape
     assert tokens == grid_h * grid_w
     tiles = anchors.shape[1]
-    tg = torch.empty(frames * tokens, dtype=torch.int32, device=q.device)
-    ag = torch.empty(frames * tokens, dtype=torch.int32, device=q.device)
+    tg = torch.empty(frames * tokens, dtype=torch.int32, device=q.device) if token_group is None else token_group
+    ag = torch.empty(frames * tokens, dtype=torch.int32, device=q.device) if anchor_group is None else anchor_group
     sc = torch.empty((frames, tiles, window * window), dtype=torch.float32, device=q.device) if want_scores else None
     _check(_lib.fb4_seda_assign(_dp(q), _dp(k), frames, heads, grid_h, grid_w, dim, _dp(anchors), tiles, window,
                                 float(threshold), _dp(tg), _dp(ag), _dp(sc), _stream(stream)), "fb4_seda_assign")

@@ -739,13 +739,26 @@ def test_entry_points_replay_correctly_from_a_hip_graph(F, luts):
         F.fb4_quantize(luts, o_sse, x, codes=c3, meta=m3)
         F.fb4_layernorm_quantize(luts, o, x, gamma, beta, 1e-6, codes=c4, meta=m4)
         F.fb4_gelu_quantize(luts, o, x, 1, codes=c5, meta=m5)
+        # attention-guided selection on the first 384 channels of x as Q and the next 384 as K: 2 frames x 3 heads x
+        # 256 tokens x 128 channels
+        F.fb4_attention_scores(qv, kv, 0, scores=att)
+        F.fb4_select_salient_tokens(att.view(2, 3, 256), 16, 16, rows_out=anch)
+        F.fb4_seda_assign(qv.view(2, 3, 256, 128), kv.view(2, 3, 256, 128), anch, 16, 16, 5, 4.0, token_group=tgo,
+                          anchor_group=ago)
 
+    qk = torch.empty((2, 2 * 3 * 256 * 128), dtype=torch.bfloat16, device="cuda")
+    qv, kv = qk[0].view(6, 256, 128), qk[1].view(6, 256, 128)
+    att = torch.empty((6, 256), dtype=torch.float32, device="cuda")
+    anch = torch.empty((2, 16), dtype=torch.int32, device="cuda")
+    tgo = torch.empty(512, dtype=torch.int32, device="cuda")
+    ago = torch.empty(512, dtype=torch.int32, device="cuda")
     c2b, m2b, c3, m3 = torch.empty_like(c2), torch.empty_like(m2), torch.empty_like(c1), torch.empty_like(m1)
     c4, m4, c5, m5 = torch.empty_like(c1), torch.empty_like(m1), torch.empty_like(c1), torch.empty_like(m1)
     gamma, beta = (torch.from_numpy(a).cuda() for a in synth.layernorm_affine(cols, seed=70))
     o_sse = F.opts(selector=F.SEL_SSE)
-    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms, c2b, m2b, c3, m3, c4, m4, c5, m5)
+    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms, c2b, m2b, c3, m3, c4, m4, c5, m5, att, anch, tgo, ago)
     x.copy_(synth.vdit_activation(rows=rows, cols=cols, seed=70, device="cuda"))
+    qk.copy_(synth.vdit_activation(rows=2, cols=qk.shape[1], seed=170, device="cuda"))
     sequence()                                                # warm-up outside the capture
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
@@ -756,13 +769,14 @@ def test_entry_points_replay_correctly_from_a_hip_graph(F, luts):
     torch.cuda.synchronize()
     for rep, seed in enumerate((71, 72, 73)):
         x.copy_(synth.vdit_activation(rows=rows, cols=cols, seed=seed, device="cuda"))
+        qk.copy_(synth.vdit_activation(rows=2, cols=qk.shape[1], seed=seed + 100, device="cuda"))
         for t in outs:
-            t.fill_(7 if t.dtype != torch.bfloat16 else 0.5)
+            t.fill_(7 if t.dtype not in (torch.bfloat16, torch.float32) else 0.5)
         sequence()
         torch.cuda.synchronize()
         want = [t.clone() for t in outs]
         for t in outs:
-            t.fill_(9 if t.dtype != torch.bfloat16 else 0.25)
+            t.fill_(9 if t.dtype not in (torch.bfloat16, torch.float32) else 0.25)
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
