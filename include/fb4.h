@@ -33,7 +33,12 @@
  *     of the input is copied to the code even when the magnitude rounds to 0.
  *   - rows == 0 or cols == 0 is a successful no-op.
  *   - A call made while another device than the handle's is current returns
- *     FB4_ERR_INVALID_ARG.
+ *     FB4_ERR_INVALID_ARG.  The entry points without a handle
+ *     (fb4_attention_scores, fb4_select_salient_tokens, fb4_seda_assign) run
+ *     on the current device.
+ *   - The producer-fused entry points (fb4_layernorm_quantize,
+ *     fb4_gelu_quantize) read x as plain IEEE bf16 and hand the quantizer the
+ *     producer's bf16 result, to which the rules above then apply.
  */
 #ifndef FB4_H
 #define FB4_H
