@@ -147,7 +147,15 @@ __global__ __launch_bounds__(kSelectThreads) void select_salient_kernel(const fl
     const float* sf = scores + (size_t)frame * heads * tokens;
     for (uint32_t t = threadIdx.x; t < tokens; t += kSelectThreads) {
         double m = 0.0;
-        for (uint32_t h = 0; h < heads; ++h) m += (double)sf[(size_t)h * tokens + t];
+        uint32_t h = 0;
+        for (; h + 8 <= heads; h += 8) {   // eight loads in flight, added in head order
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = sf[(size_t)(h + j) * tokens + t];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) m += (double)v[j];
+        }
+        for (; h < heads; ++h) m += (double)sf[(size_t)h * tokens + t];
         mean[t] = m / (double)heads;
         chosen[t] = 0;
     }
