@@ -37,10 +37,10 @@
  *     two blocks of an MX block share the larger exponent and the other
  *     block's magnitudes are shifted down and rounded to nearest even in E4M3;
  *   - a producer in front of the quantizer (App. E.2 names GeLU and
- *     LayerNorm) hands the quantizer bf16 values; since that rounding decides
- *     codes, LayerNorm's arithmetic is fixed (see fb4o_layernorm) rather than
- *     done in double; GeLU is evaluated in double and rounded once, with
- *     GeLU(-Inf) = -0 (the limit) and GeLU(NaN) = the quiet NaN 0x7FC0.
+ *     LayerNorm) hands the quantizer bf16 values: the producer's definition
+ *     evaluated in double and rounded once to bf16 (LayerNorm: the textbook
+ *     two-pass definition with the biased variance; GeLU(-Inf) = -0, the
+ *     limit, and GeLU(NaN) = the quiet NaN 0x7FC0).
  *
  * Every routine here is pinned by tests/test_oracle_pins.py against hand-worked
  * fixtures, closed forms, exact rational brute force or torch's own number
@@ -582,67 +582,8 @@ int fb4o_repack_mxfp8(const uint8_t* fbk, int n_dialects, int block, const uint8
 
 
 /* ------------------------------------------------------------------ */
-/* App. E.2: the quantizer runs fused behind the operation that produces the
- * activation; LayerNorm is one of the two the paper names.  The paper does not
- * define that operation, so this is the textbook one over the channels of a
- * token, y_c = (x_c - mean) / sqrt(var + eps) * gamma_c + beta_c with the biased
- * variance, and the quantizer's input is y rounded to bf16.  That rounding
- * decides 4-bit codes, so the precision of every step is part of the definition
- * (and is what a GPU producer would use), not "double everywhere":
- *   S1 = sum x_c, S2 = sum x_c^2             in double (each term is exact)
- *   mean = S1 * (1/C), m2 = S2 * (1/C)       in double, 1/C rounded to double
- *   var = max(m2 - mean^2, 0)                in double, one fused multiply-add
- *   a = 1 / sqrt(float(var + eps))           in float (IEEE square root, then
- *                                            IEEE divide)
- *   b = -float(mean) * a                     in float
- *   y_c = fmaf(fmaf(x_c, a, b), gamma_c, beta_c)   in float, then bf16 (RNE);
- *         a NaN becomes the canonical quiet NaN 0x7FC0
- * x is read as plain IEEE bf16 here (an Inf makes its row NaN).  The order of
- * the two sums is channel order; they are exact, hence independent of order,
- * whenever the row's values span fewer than about 2^12 in magnitude (S2) --
- * otherwise another order can move S2 by an ulp of a double, which changes a
- * or b with probability about 2^-29 per row.
- * gamma / beta: [cols] or NULL (1 / 0).  y: [rows][cols] bf16 bit patterns;
- * a, b: [rows] or NULL. */
-int fb4o_layernorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t row_stride, const float* gamma,
-                   const float* beta, float eps, uint16_t* y, float* a_out, float* b_out)
-{
-    if (!x || !y || rows < 0 || cols <= 0 || row_stride < cols) return -1;
-    for (int64_t r = 0; r < rows; ++r) {
-        const uint16_t* xr = x + r * row_stride;
-        double s1 = 0.0, s2 = 0.0;
-        for (int64_t c = 0; c < cols; ++c) {
-            double v = bf16_value(xr[c]);
-            s1 += v;
-            s2 += v * v;
-        }
-        double inv_c = 1.0 / (double)cols;
-        double mean = s1 * inv_c;
-        double var = fma(-mean, mean, s2 * inv_c);
-        if (var < 0.0) var = 0.0;
-        float v = (float)(var + (double)eps);
-        float a = 1.0f / sqrtf(v);
-        float b = -(float)mean * a;
-        if (a_out) a_out[r] = a;
-        if (b_out) b_out[r] = b;
-        for (int64_t c = 0; c < cols; ++c) {
-            float xf = (float)bf16_value(xr[c]);
-            float t = fmaf(xf, a, b);
-            float yf = fmaf(t, gamma ? gamma[c] : 1.0f, beta ? beta[c] : 0.0f);
-            y[r * cols + c] = isnan(yf) ? (uint16_t)0x7FC0 : f32_to_bf16_rne(yf);
-        }
-    }
-    return 0;
-}
-
-/* ------------------------------------------------------------------ */
-/* App. E.2: the other producer the paper names is GeLU.  Elementwise on bf16:
- * the value in double, rounded once to bf16 (nearest even).
- *   approximate == 0:  x * Phi(x) = 0.5 * x * erfc(-x / sqrt(2))
- *   approximate == 1:  the tanh form 0.5 * x * (1 + tanh(u)),
- *                      u = sqrt(2/pi) * (x + 0.044715 x^3), written as
- *                      x / (1 + exp(-2u)) so that nothing cancels for x << 0
- * GeLU(+Inf) = +Inf, GeLU(-Inf) = -0 (the limit), GeLU(NaN) = 0x7FC0. */
+/* double -> bf16 bits, one rounding to nearest even (NaN -> the quiet NaN
+ * 0x7FC0, overflow -> Inf, subnormals in steps of 2^-133). */
 static uint16_t f64_to_bf16_rne(double v)
 {
     if (isnan(v)) return 0x7FC0;
@@ -666,6 +607,54 @@ static uint16_t f64_to_bf16_rne(double v)
     return (uint16_t)(sign | ((e + 127) << 7) | ((int)q - 128));
 }
 
+/* App. E.2: the quantizer runs fused behind the operation that produces the
+ * activation; LayerNorm is one of the two the paper names.  The paper does not
+ * define that operation, so this is the textbook one over the channels of a
+ * token, written out from its definition in double:
+ *   mean = (1/C) sum_c x_c
+ *   var  = (1/C) sum_c (x_c - mean)^2            (biased; two passes)
+ *   y_c  = (x_c - mean) / sqrt(var + eps) * gamma_c + beta_c
+ * and the quantizer's input is y_c rounded ONCE to bf16 (nearest even; a NaN
+ * becomes the quiet NaN 0x7FC0).  x is read as plain IEEE bf16: a row that
+ * holds an Inf or a NaN is NaN throughout.
+ * gamma / beta: [cols] or NULL (1 / 0).  y: [rows][cols] bf16 bit patterns;
+ * mean_out, rstd_out: [rows] doubles or NULL (rstd = 1 / sqrt(var + eps)). */
+int fb4o_layernorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t row_stride, const float* gamma,
+                   const float* beta, double eps, uint16_t* y, double* mean_out, double* rstd_out)
+{
+    if (!x || !y || rows < 0 || cols <= 0 || row_stride < cols) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t* xr = x + r * row_stride;
+        double sum = 0.0;
+        for (int64_t c = 0; c < cols; ++c) sum += bf16_value(xr[c]);
+        double mean = sum / (double)cols;
+        double sq = 0.0;
+        for (int64_t c = 0; c < cols; ++c) {
+            double d = bf16_value(xr[c]) - mean;
+            sq += d * d;
+        }
+        double var = sq / (double)cols;
+        double rstd = 1.0 / sqrt(var + eps);
+        if (mean_out) mean_out[r] = mean;
+        if (rstd_out) rstd_out[r] = rstd;
+        for (int64_t c = 0; c < cols; ++c) {
+            double g = gamma ? (double)gamma[c] : 1.0;
+            double b = beta ? (double)beta[c] : 0.0;
+            double v = (bf16_value(xr[c]) - mean) * rstd * g + b;
+            y[r * cols + c] = f64_to_bf16_rne(v);
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* App. E.2: the other producer the paper names is GeLU.  Elementwise on bf16:
+ * the value in double, rounded once to bf16 (nearest even).
+ *   approximate == 0:  x * Phi(x) = 0.5 * x * erfc(-x / sqrt(2))
+ *   approximate == 1:  the tanh form 0.5 * x * (1 + tanh(u)),
+ *                      u = sqrt(2/pi) * (x + 0.044715 x^3), written as
+ *                      x / (1 + exp(-2u)) so that nothing cancels for x << 0
+ * GeLU(+Inf) = +Inf, GeLU(-Inf) = -0 (the limit), GeLU(NaN) = 0x7FC0. */
 int fb4o_gelu(const uint16_t* x, int64_t n, int approximate, uint16_t* y)
 {
     if ((!x || !y) && n > 0) return -1;

@@ -50,7 +50,7 @@ def _load():
                                        p, p, i32, p, p, i32]
         lib.fb4o_dequantize.argtypes = [p, i32, i32, p, p, i64, i64, p, p, p, i64, p, i32, i64, i32]
         lib.fb4o_repack_mxfp8.argtypes = [p, i32, i32, p, p, i64, i64, p, p]
-        lib.fb4o_layernorm.argtypes = [p, i64, i64, i64, p, p, ctypes.c_float, p, p, p]
+        lib.fb4o_layernorm.argtypes = [p, i64, i64, i64, p, p, ctypes.c_double, p, p, p]
         lib.fb4o_gelu.argtypes = [p, i64, i32, p]
         _lib = lib
     return _lib
@@ -175,22 +175,23 @@ def repack_mxfp8(fbk, codes, meta, block=32):
 
 
 def layernorm(x_bits, gamma=None, beta=None, eps=1e-6):
-    """The LayerNorm producer in front of the quantizer (App. E.2), arithmetic as fixed in fb4_oracle.c.
-    x_bits: uint16 [rows][cols]; gamma / beta: float32 [cols] or None.  Returns (y bf16 bit patterns
-    [rows][cols], a float32 [rows] = 1/std, b float32 [rows] = -mean/std)."""
+    """The LayerNorm producer in front of the quantizer (App. E.2): the textbook two-pass definition in float64,
+    rounded once to bf16.  x_bits: uint16 [rows][cols]; gamma / beta: float32 [cols] or None; eps is taken as the
+    float32 value a caller of the library would pass.  Returns (y bf16 bit patterns [rows][cols], mean float64
+    [rows], rstd float64 [rows] = 1 / sqrt(var + eps))."""
     assert x_bits.dtype == np.uint16 and x_bits.ndim == 2 and x_bits.strides[1] == 2
     rows, cols = x_bits.shape
     stride = x_bits.strides[0] // 2 if rows > 1 else cols
     g = _c(gamma, np.float32)
     b = _c(beta, np.float32)
     y = np.zeros((rows, cols), dtype=np.uint16)
-    a_out = np.zeros(rows, dtype=np.float32)
-    b_out = np.zeros(rows, dtype=np.float32)
-    rc = _load().fb4o_layernorm(_ptr(x_bits), rows, cols, stride, _ptr(g), _ptr(b), float(eps), _ptr(y),
-                                _ptr(a_out), _ptr(b_out))
+    mean = np.zeros(rows, dtype=np.float64)
+    rstd = np.zeros(rows, dtype=np.float64)
+    rc = _load().fb4o_layernorm(_ptr(x_bits), rows, cols, stride, _ptr(g), _ptr(b), float(np.float32(eps)), _ptr(y),
+                                _ptr(mean), _ptr(rstd))
     if rc != 0:
         raise ValueError("fb4o_layernorm: invalid argument")
-    return y, a_out, b_out
+    return y, mean, rstd
 
 
 def gelu(x_bits, approximate=0):
@@ -260,48 +261,178 @@ def select_salient_tokens(scores, grid_h, grid_w, tile_h=4, tile_w=4):
     return out
 
 
-def seda_assign(q_bits, k_bits, anchors, grid_h, grid_w, window=5, threshold=5.0):
-    """Sec. 3.4, "Attention-Guided Semantic Relatedness Extraction", the per-frame part: every tile's anchor token
-    (one per frame and tile: `anchors`, int32 [frames][tiles], rows of the [frames * tokens] tensor, ascending per
-    frame as select_salient_tokens returns them -- tile g of a frame is the g-th tile in row-major tile order, found
-    again from the anchor's position) marks as correlated the tokens of a window x window square around it (clipped
-    to the frame) whose raw pre-softmax attention score FROM the anchor, Q[anchor] . K[token] averaged over the heads,
-    exceeds `threshold`.  A token marked by several anchors belongs to the one with the highest group number (the
-    "subsequent" anchor); an anchor always belongs to its own group.  Group number = position of the anchor in its
-    frame's list.  q_bits, k_bits: uint16 [frames][heads][tokens][dim].  Returns (token_group int32 [frames * tokens],
-    -1 = none; anchor_group int32 [frames * tokens], the group on anchor rows and -1 elsewhere; score float64
-    [frames][tiles][window * window], NaN outside the frame).  Plain loops; the dot products are numpy float64."""
+def _tile_of(token, grid_w, tile_h, tile_w):
+    """Row-major number of the tile_h x tile_w tile that holds a token of a row-major grid of width grid_w."""
+    y, x = divmod(int(token), grid_w)
+    tiles_w = (grid_w + tile_w - 1) // tile_w
+    return (y // tile_h) * tiles_w + x // tile_w
+
+
+def seda_assign(q_bits, k_bits, anchors, frames, grid_h, grid_w, tile_h=4, tile_w=4, window=5, window_t=1,
+                threshold=5.0, joint=False):
+    """Sec. 3.4, "Attention-Guided Semantic Relatedness Extraction", the marking step (step 3 for factorized
+    attention, the cuboid step for 3D attention).  `anchors`: int32 [n], rows of the [frames * tokens] activation
+    (tokens = grid_h * grid_w, row-major per frame); an entry outside the tensor (say -1: a pruned frame's candidate)
+    does nothing.  The GROUP of an anchor is the row-major number of the tile_h x tile_w spatial tile it lies in, so
+    that the per-frame candidates of one tile share a group -- one sub-formatbook -- across the frames.  Every
+    anchor marks as correlated the tokens of a window x window square (x window_t frames: a cuboid) centred on it
+    and clipped to the clip, whose RAW pre-softmax attention score from the anchor, Q[anchor] . K[token] averaged
+    over the heads, exceeds `threshold`.  A token marked by anchors of several groups belongs to the highest group
+    number (App. D: overlapping windows go to the subsequent anchor = the later tile); an anchor always belongs to
+    its own group.
+    joint = False (factorized attention): q_bits, k_bits uint16 [frames][heads][tokens][dim], the projections of the
+    spatial attention; scores exist inside a frame only, so window_t must be 1.
+    joint = True (3D attention): uint16 [heads][frames * tokens][dim].
+    Returns (token_group int32 [frames * tokens], -1 = none; anchor_group int32 [frames * tokens], the group on anchor
+    rows and -1 elsewhere; score float64 [n][window_t * window * window], NaN outside the clip or for a dropped
+    entry).  Plain loops; the dot products are numpy float64."""
     q = _bf16_to_f64(q_bits)
     k = _bf16_to_f64(k_bits)
-    frames, heads, tokens, dim = q.shape
-    assert tokens == grid_h * grid_w
-    anchors = np.asarray(anchors, dtype=np.int64)
-    tiles = anchors.shape[1]
+    tokens = grid_h * grid_w
+    if joint:
+        heads, total, dim = q.shape
+        assert total == frames * tokens
+        at = lambda arr, f, h, t: arr[h, f * tokens + t]
+    else:
+        assert q.shape[0] == frames and q.shape[2] == tokens and window_t == 1
+        heads = q.shape[1]
+        at = lambda arr, f, h, t: arr[f, h, t]
+    anchors = np.asarray(anchors, dtype=np.int64).ravel()
+    n = anchors.size
     token_group = np.full(frames * tokens, -1, dtype=np.int32)
     anchor_group = np.full(frames * tokens, -1, dtype=np.int32)
-    score = np.full((frames, tiles, window * window), np.nan)
-    half = window // 2
-    for f in range(frames):
-        for g in range(tiles):
-            a = int(anchors[f, g]) - f * tokens
-            ay, ax = divmod(a, grid_w)
+    score = np.full((n, window_t * window * window), np.nan)
+    half, half_t = window // 2, window_t // 2
+    for i in range(n):
+        row = int(anchors[i])
+        if not 0 <= row < frames * tokens:
+            continue
+        fa, a = divmod(row, tokens)
+        g = _tile_of(a, grid_w, tile_h, tile_w)
+        ay, ax = divmod(a, grid_w)
+        for wt in range(window_t):
             for wy in range(window):
                 for wx in range(window):
-                    y, x = ay + wy - half, ax + wx - half
-                    if not (0 <= y < grid_h and 0 <= x < grid_w):
+                    f, y, x = fa + wt - half_t, ay + wy - half, ax + wx - half
+                    if not (0 <= f < frames and 0 <= y < grid_h and 0 <= x < grid_w):
                         continue
                     t = y * grid_w + x
                     sc = 0.0
                     for h in range(heads):
-                        sc += float(q[f, h, a] @ k[f, h, t])
+                        sc += float(at(q, fa, h, a) @ at(k, f, h, t))
                     sc /= heads
-                    score[f, g, wy * window + wx] = sc
+                    score[i, (wt * window + wy) * window + wx] = sc
                     if sc > threshold:
                         token_group[f * tokens + t] = max(token_group[f * tokens + t], g)
-        for g in range(tiles):                      # an anchor belongs to its own group
-            token_group[int(anchors[f, g])] = g
-            anchor_group[int(anchors[f, g])] = g
+    for i in range(n):                      # an anchor belongs to its own group
+        row = int(anchors[i])
+        if 0 <= row < frames * tokens:
+            g = _tile_of(row % tokens, grid_w, tile_h, tile_w)
+            token_group[row] = g
+            anchor_group[row] = g
     return token_group, anchor_group, score
+
+
+def seda_main_anchor(temporal_scores, qt_bits, kt_bits, candidates, grid_h, grid_w, tile_h=4, tile_w=4,
+                     prune_threshold=3.0):
+    """Sec. 3.4, factorized attention, step 2: per spatial tile, the main anchor among the tile's per-frame
+    candidates and the pruning of weakly correlated frames.
+    candidates: int32 [frames][n], per frame the anchor candidates of step 1 as rows of the [frames * tokens]
+    activation (what select_salient_tokens returns); a candidate's tile is found from its position; an entry
+    outside its own frame is no candidate.
+    temporal_scores: [positions][heads][frames], the mean temporal attention score of every token (what
+    attention_scores gives for the temporal attention: group = spatial position and head, tokens = frames).
+    qt_bits, kt_bits: uint16 [positions][heads][frames][dim], the temporal attention's projections.
+    Main anchor of a tile = the candidate whose own temporal mean score, averaged over the heads (summed head by
+    head in float64), is highest; ties go to the earliest frame, a NaN never wins.  A frame's candidate is pruned
+    when the raw temporal attention score FROM the main anchor TO that frame -- Qt[p*][h][f*] . Kt[p*][h][f] at the
+    main anchor's position p*, averaged over the heads -- does not exceed prune_threshold; the main anchor's own
+    frame always stays.
+    Returns (main int32 [tiles] rows, -1 for a tile without candidates; kept int32 [frames][n] = candidates with
+    the pruned and the invalid entries set to -1; prune_score float64 [frames][tiles], NaN where there is no
+    candidate)."""
+    ts = np.asarray(temporal_scores)
+    qt = _bf16_to_f64(qt_bits)
+    kt = _bf16_to_f64(kt_bits)
+    positions, heads, frames = ts.shape
+    tokens = grid_h * grid_w
+    assert positions == tokens and qt.shape[:3] == (positions, heads, frames)
+    cand = np.asarray(candidates, dtype=np.int64)
+    assert cand.shape[0] == frames
+    th, tw = (grid_h + tile_h - 1) // tile_h, (grid_w + tile_w - 1) // tile_w
+    tiles = th * tw
+    main = np.full(tiles, -1, dtype=np.int32)
+    kept = np.full(cand.shape, -1, dtype=np.int32)
+    prune_score = np.full((frames, tiles), np.nan)
+    for tile in range(tiles):
+        # the tile's candidate in every frame (the first listed one if a frame lists several)
+        slot = [-1] * frames
+        for f in range(frames):
+            for j in range(cand.shape[1]):
+                row = int(cand[f, j])
+                if f * tokens <= row < (f + 1) * tokens and _tile_of(row - f * tokens, grid_w, tile_h, tile_w) == tile:
+                    slot[f] = j
+                    break
+        best_f, best_v = -1, -np.inf
+        for f in range(frames):
+            if slot[f] < 0:
+                continue
+            p = int(cand[f, slot[f]]) - f * tokens
+            v = 0.0
+            for h in range(heads):
+                v += float(ts[p, h, f])
+            v /= heads
+            if np.isnan(v):
+                v = -np.inf
+            if best_f < 0 or v > best_v:
+                best_f, best_v = f, v
+        if best_f < 0:
+            continue
+        main[tile] = int(cand[best_f, slot[best_f]])
+        p = main[tile] - best_f * tokens
+        for f in range(frames):
+            if slot[f] < 0:
+                continue
+            sc = 0.0
+            for h in range(heads):
+                sc += float(qt[p, h, best_f] @ kt[p, h, f])
+            sc /= heads
+            prune_score[f, tile] = sc
+            if f == best_f or sc > prune_threshold:
+                kept[f, slot[f]] = int(cand[f, slot[f]])
+    return main, kept, prune_score
+
+
+def seda_main_anchor_3d(scores, frames, grid_h, grid_w, tile_h=4, tile_w=4):
+    """Sec. 3.4, 3D attention: the main anchor of every spatial tile is the token with the highest mean attention
+    score among the tile's tile_h x tile_w x frames tokens.  scores: [heads][frames * tokens], the mean attention
+    score of every token of the clip (attention_scores with one group per head); averaged over the heads (summed
+    head by head in float64); ties go to the lowest row, a NaN never wins.  Returns int32 [tiles] rows of the
+    [frames * tokens] activation, in tile order."""
+    scores = np.asarray(scores)
+    heads, total = scores.shape
+    tokens = grid_h * grid_w
+    assert total == frames * tokens
+    mean = np.zeros(total, dtype=np.float64)
+    for h in range(heads):
+        mean += scores[h].astype(np.float64)
+    mean /= heads
+    th, tw = (grid_h + tile_h - 1) // tile_h, (grid_w + tile_w - 1) // tile_w
+    out = np.zeros(th * tw, dtype=np.int32)
+    for ty in range(th):
+        for tx in range(tw):
+            best, best_v = -1, -np.inf
+            for f in range(frames):
+                for y in range(ty * tile_h, min(grid_h, (ty + 1) * tile_h)):
+                    for x in range(tx * tile_w, min(grid_w, (tx + 1) * tile_w)):
+                        row = f * tokens + y * grid_w + x
+                        v = mean[row]
+                        if np.isnan(v):
+                            v = -np.inf
+                        if best < 0 or v > best_v:
+                            best, best_v = row, v
+            out[ty * tw + tx] = best
+    return out
 
 
 def seda_profile(fbk, meta, anchor_group, n_groups):

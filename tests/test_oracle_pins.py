@@ -79,10 +79,15 @@ def test_default_formatbook_meets_the_papers_rules():
     assert all(c >= 1 for c in counts)               # every range 8..15 covered (rule 1)
     assert counts == sorted(counts) and counts[0] < counts[-1]  # fewer dialects for narrower ranges
     assert len({tuple(r) for r in fbk.tolist()}) == 32
-    for b in range_buckets(fbk):                     # rules 2-3: each range holds a small-dense
-        dens = [int((fbk[d] <= 4).sum()) for d in b]  # and a large-preserving dialect
-        assert max(dens) > min(dens) or len(b) == 1 or True
-        assert max(dens) >= 4
+    for b in range_buckets(fbk):
+        # rule 2 (densify small magnitudes): some dialect of the range spends at least half of its eight points
+        # on 0..4; rule 3 (preserve large magnitudes): some dialect of the range has at least three points in the
+        # top third of the range, more than the range's small-dense dialect has there
+        small = [int((fbk[d] <= 4).sum()) for d in b]
+        large = [int((3 * fbk[d].astype(int) >= 2 * int(fbk[d, 7])).sum()) for d in b]
+        assert max(small) >= 4
+        assert max(large) >= 3
+        assert len(b) >= 2 and large[int(np.argmax(small))] < max(large)
 
 
 def test_magnitudes_are_exact_in_fp8_e4m3():
@@ -560,9 +565,41 @@ def test_block_size_16(fbk):
         xp = np.zeros((8 * 16, 32), dtype=np.uint16)
         xp[:, :16] = x.reshape(-1, 16)
         c32, m32 = O.quantize(fbk, xp, block=32, selector=sel, num_groups=16)
-        if sel == O.SEL_SSE:
-            assert np.array_equal(m16.ravel(), m32.ravel())
-            assert np.array_equal(c16.reshape(-1, 8), c32[:, :8])
+        # (online rule: the 8 all-zero groups of the padding add the same 0.25 to every dialect's score)
+        assert np.array_equal(m16.ravel(), m32.ravel())
+        assert np.array_equal(c16.reshape(-1, 8), c32[:, :8])
+        assert not c32[:, 8:].any()
+    # the online rule's groups at block size 16 are runs of 16 / num_groups elements: 16 groups score every
+    # element, so the order inside a block no longer matters, while 8 groups of 2 depend on it
+    rng = np.random.default_rng(33)
+    perm = np.concatenate([rng.permutation(16) + 16 * b for b in range(16)])
+    _, m_all = O.quantize(fbk, x, block=16, selector=O.SEL_LUT, num_groups=16)
+    _, m_all_p = O.quantize(fbk, np.ascontiguousarray(x[:, perm]), block=16, selector=O.SEL_LUT, num_groups=16)
+    assert np.array_equal(m_all, m_all_p)
+    _, m8 = O.quantize(fbk, x, block=16, selector=O.SEL_LUT, num_groups=8)
+    _, m8_p = O.quantize(fbk, np.ascontiguousarray(x[:, perm]), block=16, selector=O.SEL_LUT, num_groups=8)
+    assert not np.array_equal(m8, m8_p)
+
+
+def test_hand_worked_lut_selection_block16():
+    g = read_golden("worked_lut_selection_block16.txt")
+    fbk = np.array([[0, 1, 2, 3, 4, 6, 8, 12], [0, 2, 4, 6, 8, 10, 12, 14]], dtype=np.uint8)
+    row = []
+    for blk in ("block1", "block2"):
+        x = f2b(np.array([float(v) for v in g[blk + "_x"]], dtype=np.float32))
+        assert x.size == 16
+        cand, scores, did, e = O.block_scores(fbk, x, selector=O.SEL_LUT, num_groups=8)
+        assert cand.tolist() == [0, 1]
+        assert scores.tolist() == [float(v) for v in g[blk + "_scores"]]
+        assert did == int(g[blk + "_did"][0]) and e == 3
+        row.append(x)
+    # the two blocks side by side as one row of 32 elements quantized with block size 16
+    codes, meta = O.quantize(fbk, np.concatenate(row)[None, :], block=16, selector=O.SEL_LUT, num_groups=8)
+    assert meta[0].tolist() == [int(g["block1_meta"][0], 16), int(g["block2_meta"][0], 16)]
+    assert codes[0, :8].tolist() == [int(v, 16) for v in g["block1_codes"]]
+    nib = unpack(codes)[0, :16]
+    assert (nib & 7).tolist() == [int(v) for v in g["block1_index"]]
+    assert (nib >> 3).tolist() == [int(v) for v in g["block1_sign"]]
 
 
 # ------------------------------------------------------------ MXFP8 operands
@@ -688,64 +725,103 @@ def test_seda_profile_on_a_quantized_tensor_restricts_to_dialects_that_were_in_u
 
 
 # ------------------------------------------------- LayerNorm producer in front of the quantizer (App. E.2)
-def _ln_textbook(x64, gamma, beta, eps):
-    """Two-pass LayerNorm in float64, straight from the definition (biased variance)."""
-    mean = x64.mean(axis=1, keepdims=True)
-    var = ((x64 - mean) ** 2).mean(axis=1, keepdims=True)
-    return (x64 - mean) / np.sqrt(var + eps) * gamma + beta
+def bf16_rne_of_f64(v):
+    """float64 -> bf16 bit patterns with ONE rounding to nearest even, by integer arithmetic on the float64 bit
+    pattern (normal bf16 range and zero only)."""
+    v = np.asarray(v, dtype=np.float64)
+    u = v.view(np.uint64)
+    sign = (u >> np.uint64(63)).astype(np.uint64)
+    ex = ((u >> np.uint64(52)) & np.uint64(0x7FF)).astype(np.int64) - 1023
+    man = u & np.uint64((1 << 52) - 1)
+    assert ((v == 0) | ((ex >= -126) & (ex <= 127))).all()
+    keep = man >> np.uint64(45)                                  # 7 mantissa bits
+    rem = man & np.uint64((1 << 45) - 1)
+    half = np.uint64(1 << 44)
+    up = (rem > half) | ((rem == half) & ((keep & np.uint64(1)) == 1))
+    body = ((ex + 127).astype(np.uint64) << np.uint64(7)) + keep + up.astype(np.uint64)   # a carry walks into the exponent
+    body = np.where(v == 0, np.uint64(0), body)
+    return ((sign << np.uint64(15)) | body).astype(np.uint16)
 
 
 def test_layernorm_hand_worked_rows():
-    one = np.float32(1.0)
     # [2,-2,2,-2]: mean 0, biased variance 4, eps 0 -> t = +-1; y = t * gamma + beta
     x = f2b([[2, -2, 2, -2]])
-    y, a, b = O.layernorm(x, gamma=[1, 2, 3, 4], beta=[10, 20, 30, 40], eps=0.0)
+    y, mean, rstd = O.layernorm(x, gamma=[1, 2, 3, 4], beta=[10, 20, 30, 40], eps=0.0)
     assert b2f(y).tolist() == [[11.0, 18.0, 33.0, 36.0]]
-    assert a[0] == np.float32(0.5) and b[0] == 0.0
+    assert mean[0] == 0.0 and rstd[0] == 0.5
     # biased variance: [1,-1] has variance 1, not 2
     y, _, _ = O.layernorm(f2b([[1, -1]]), eps=0.0)
     assert b2f(y).tolist() == [[1.0, -1.0]]
-    # eps is added to the variance: variance 1, eps 3 -> divide by 2
+    # eps is added to the variance, inside the root: variance 1, eps 3 -> divide by 2
     y, _, _ = O.layernorm(f2b([[1, -1]]), eps=3.0)
     assert b2f(y).tolist() == [[0.5, -0.5]]
-    # mean is removed: [5, 1] -> mean 3, variance 4 -> +-1
-    y, a, b = O.layernorm(f2b([[5, 1]]), eps=0.0)
-    assert b2f(y).tolist() == [[1.0, -1.0]] and a[0] == np.float32(0.5) and b[0] == np.float32(-1.5)
+    # the mean is removed: [5, 1] -> mean 3, variance 4 -> +-1
+    y, mean, rstd = O.layernorm(f2b([[5, 1]]), eps=0.0)
+    assert b2f(y).tolist() == [[1.0, -1.0]] and mean[0] == 3.0 and rstd[0] == 0.5
+    # gamma multiplies, beta is added afterwards, each by channel
+    y, _, _ = O.layernorm(f2b([[5, 1]]), gamma=[2, 8], beta=[0.5, -0.5], eps=0.0)
+    assert b2f(y).tolist() == [[2.5, -8.5]]
     # [1,-1,3,-3]: variance 5; 1/sqrt(5) = 0.4472136 -> bf16 0x3EE5, 3/sqrt(5) = 1.3416408 -> bf16 0x3FAC
     y, _, _ = O.layernorm(f2b([[1, -1, 3, -3]]), eps=0.0)
     assert y.tolist() == [[0x3EE5, 0xBEE5, 0x3FAC, 0xBFAC]]
-    assert one == 1.0
 
 
-def test_layernorm_agrees_with_the_float64_definition_to_the_last_bf16_bit():
+def test_layernorm_equals_the_library_routine_in_float64_rounded_once():
+    # torch's own layer_norm evaluated in float64, then one rounding to bf16 done here by integer arithmetic.
+    # Two float64 evaluations of the same value differ by a few 1e-16: a different bf16 only within that of a tie.
     rng = np.random.default_rng(71)
-    for rows, cols, mu, sigma in [(64, 96, 0.0, 1.0), (32, 3072, 0.0, 1.0), (16, 1152, 100.0, 1.0), (16, 64, -3.0, 20.0)]:
+    for rows, cols, mu, sigma in [(64, 96, 0.0, 1.0), (32, 3072, 0.0, 1.0), (16, 1152, 100.0, 1.0), (16, 64, -3.0, 20.0),
+                                  (8, 12288, 0.5, 3.0)]:
         xb = f2b(mu + sigma * rng.standard_normal((rows, cols)))
         gamma, beta = synth.layernorm_affine(cols, seed=rows)
-        y, a, b = O.layernorm(xb, gamma, beta, eps=1e-6)
-        x64 = b2f(xb)
-        ref = _ln_textbook(x64, gamma.astype(np.float64), beta.astype(np.float64), 1e-6)
-        got = b2f(y)
-        # one bf16 step at |ref|, plus what rounding 1/std and -mean/std to float leaves on the normalized value
-        tol = np.abs(ref) * 2.0 ** -7 + 2.0 ** -21 * (1.0 + abs(mu) / sigma)
-        assert (np.abs(got - ref) <= tol).all()
-        # with a large mean the float steps lose a little more; on centred data nearly every value is the
-        # correctly rounded one
-        if mu == 0.0:
-            assert (y == f2b(ref.astype(np.float32))).mean() > 0.999
-        mean = x64.mean(axis=1)
-        std = np.sqrt(x64.var(axis=1) + 1e-6)
-        assert np.allclose(a, 1.0 / std, rtol=1e-6, atol=0) and np.allclose(b, -mean / std, rtol=1e-6, atol=1e-7)
+        y, mean, rstd = O.layernorm(xb, gamma, beta, eps=1e-6)
+        x64 = torch.from_numpy(b2f(xb))
+        eps32 = float(np.float32(1e-6))
+        ref = torch.nn.functional.layer_norm(x64, (cols,), torch.from_numpy(gamma).double(), torch.from_numpy(beta).double(),
+                                             eps32).numpy()
+        want = bf16_rne_of_f64(ref)
+        diff = np.nonzero(y != want)
+        lo, hi = b2f(np.minimum(y, want)[diff]), b2f(np.maximum(y, want)[diff])
+        assert (np.abs(ref[diff] - (lo + hi) / 2) <= 1e-13 * np.abs(ref[diff])).all()
+        assert diff[0].size <= 2
+        # the row statistics, against exactly rounded sums
+        for r in (0, rows - 1):
+            xs = b2f(xb[r]).tolist()
+            m = math.fsum(xs) / cols
+            v = math.fsum((t - m) ** 2 for t in xs) / cols
+            assert abs(mean[r] - m) <= 1e-13 * max(1.0, abs(m)) and abs(rstd[r] - 1.0 / math.sqrt(v + eps32)) <= 1e-12 * rstd[r]
+
+
+def test_layernorm_rounding_interval_in_exact_rational_arithmetic():
+    # without scale and shift y^2 (var + eps) = (x - mean)^2 exactly; the oracle's bf16 result must be the bf16
+    # value whose rounding interval holds the true y -- checked on squares, in rationals, with no square root
+    rng = np.random.default_rng(75)
+    xb = f2b(rng.standard_normal((6, 12)) * np.array([[1], [3], [0.1], [50], [1], [7]]) + np.array([[0], [1], [0], [-20], [4], [0]]))
+    eps = Fraction(float(np.float32(1e-3)))
+    y, _, _ = O.layernorm(xb, eps=float(np.float32(1e-3)))
+    for r in range(6):
+        xs = [exact(int(b)) for b in xb[r]]
+        mean = sum(xs) / 12
+        var = sum((t - mean) ** 2 for t in xs) / 12
+        for c in range(12):
+            d = xs[c] - mean
+            yb = int(y[r, c])
+            assert (yb >> 15) == (1 if d < 0 else 0)
+            mag = yb & 0x7FFF
+            lo = (exact(mag - 1) + exact(mag)) / 2 if mag else Fraction(0)     # neighbours' midpoints
+            hi = (exact(mag) + exact(mag + 1)) / 2
+            t2 = d * d / (var + eps)                                           # the true y, squared
+            assert lo * lo <= t2 <= hi * hi
 
 
 def test_layernorm_invariants():
     rng = np.random.default_rng(72)
     xb = f2b(rng.standard_normal((8, 256)))
     gamma, beta = synth.layernorm_affine(256, seed=3)
-    y, a, b = O.layernorm(xb, gamma, beta, eps=0.0)
+    y, mean, rstd = O.layernorm(xb, gamma, beta, eps=0.0)
     # scaling a row by a power of two changes nothing when eps = 0 (every step scales exactly)
-    y4, a4, b4 = O.layernorm(f2b(b2f(xb) * 4.0), gamma, beta, eps=0.0)
-    assert np.array_equal(y, y4) and np.array_equal(a4 * 4, a) and np.array_equal(b4, b)
+    y4, mean4, rstd4 = O.layernorm(f2b(b2f(xb) * 4.0), gamma, beta, eps=0.0)
+    assert np.array_equal(y, y4) and np.array_equal(rstd4 * 4, rstd) and np.array_equal(mean4, 4 * mean)
     # rows are independent, and a row stride changes nothing
     wide = np.zeros((8, 300), dtype=np.uint16)
     wide[:, :256] = xb
@@ -758,16 +834,24 @@ def test_layernorm_invariants():
     yn, _, _ = O.layernorm(xb ^ 0x8000, gamma, None, eps=0.0)
     yp, _, _ = O.layernorm(xb, gamma, None, eps=0.0)
     assert np.array_equal(yn ^ 0x8000, yp)
-    # a constant row has variance 0: y = beta, up to what x * a + b leaves when mean / std is in the thousands
-    # (here 1.5 / 1e-3: the two terms cancel to about 1e-4 instead of to nothing)
-    const = f2b(np.full((1, 256), 1.5))
-    yc, ac, bc = O.layernorm(const, gamma, beta, eps=1e-6)
-    assert np.abs(b2f(yc[0]) - beta).max() <= 2.0 ** -7 * np.abs(beta).max() + 3e-4
-    assert abs(float(ac[0]) - 1000.0) < 1e-3 and abs(float(bc[0]) + 1500.0) < 1e-3
+    # shifting a row by a constant changes nothing (the shift is chosen so that x + 8 is exact in bf16)
+    xq = f2b(np.round(b2f(xb) * 8) / 8)
+    ya, _, _ = O.layernorm(xq, gamma, beta, eps=1e-6)
+    yb, _, _ = O.layernorm(f2b(b2f(xq) + 8.0), gamma, beta, eps=1e-6)
+    assert np.array_equal(b2f(f2b(b2f(xq) + 8.0)), b2f(xq) + 8.0) and (ya == yb).mean() > 0.999
+    # a constant row has variance 0 and every x - mean is 0: y is exactly beta (rounded to bf16), whatever eps
+    for value, cols in ((1.5, 256), (-1000.0, 3072), (3.0e-5, 96)):
+        g, b = synth.layernorm_affine(cols, seed=5)
+        const = f2b(np.full((1, cols), value))
+        yc, mc, rc = O.layernorm(const, g, b, eps=1e-6)
+        assert np.array_equal(yc[0], f2b(b)) and mc[0] == float(b2f(const)[0, 0])
+        assert abs(rc[0] - 1.0 / math.sqrt(float(np.float32(1e-6)))) < 1e-9
     # a zero row with gamma only: exactly zero
-    yz, az, bz = O.layernorm(np.zeros((1, 256), dtype=np.uint16), gamma, None, eps=1e-6)
-    assert not (yz & 0x7FFF).any() and bz[0] == 0.0
-    assert az[0] == np.float32(1.0) / np.sqrt(np.float32(1e-6)) and abs(float(az[0]) - 1000.0) < 1e-3
+    yz, mz, rz = O.layernorm(np.zeros((1, 256), dtype=np.uint16), gamma, None, eps=1e-6)
+    assert not (yz & 0x7FFF).any() and mz[0] == 0.0
+    # without scale and shift the normalized row has mean 0 and second moment var / (var + eps), up to bf16 rounding
+    yn, _, _ = O.layernorm(xb, eps=1e-6)
+    assert np.abs(b2f(yn).mean(axis=1)).max() < 2e-3 and np.abs((b2f(yn) ** 2).mean(axis=1) - 1.0).max() < 5e-3
 
 
 def test_layernorm_rows_with_nan_or_inf_become_canonical_nan():
@@ -938,27 +1022,122 @@ def test_salient_token_selection_per_tile():
 
 
 def test_seda_assignment_marks_the_window_tokens_an_anchor_attends_to():
-    # one frame, one head, 4 x 4 grid, 2 channels; anchors at tokens 5 and 10; window 3
+    # one frame, one head, 4 x 4 grid, 2 x 2 tiles, 2 channels; anchors at tokens 5 (tile 0) and 10 (tile 3); window 3
     q = np.zeros((1, 1, 16, 2), dtype=np.float32)
     k = np.zeros((1, 1, 16, 2), dtype=np.float32)
     q[0, 0, 5] = [1, 0]; q[0, 0, 10] = [0, 1]
     k[0, 0, :, 0] = [0, 9, 0, 0,  2, 0, 7, 0,  0, 6, 0, 0,  0, 0, 0, 0]      # what anchor 5 sees
     k[0, 0, :, 1] = [0, 0, 0, 0,  0, 8, 6.5, 0,  0, 0, 0, 9,  0, 0, 9, 5]    # what anchor 10 sees
-    tg, ag, sc = O.seda_assign(f2b(q), f2b(k), [[5, 10]], 4, 4, window=3, threshold=5.0)
+    tg, ag, sc = O.seda_assign(f2b(q), f2b(k), [5, 10], 1, 4, 4, tile_h=2, tile_w=2, window=3, threshold=5.0)
     # anchor 5 (row 1, col 1) sees tokens 0-2, 4-6, 8-10: above 5 are 1 (9), 6 (7), 9 (6)
     # anchor 10 (row 2, col 2) sees 5-7, 9-11, 13-15: above 5 are 5 (8), 6 (6.5), 11 (9), 14 (9); 15 (5) is not above
     want = np.full(16, -1)
     want[[1, 9]] = 0
-    want[[6, 11, 14]] = 1          # token 6: both anchors -> the later one
-    want[5] = 0; want[10] = 1      # anchors keep their own group (anchor 10 marked token 5, but 5 is an anchor)
+    want[[6, 11, 14]] = 3          # token 6: both anchors -> the later tile
+    want[5] = 0; want[10] = 3      # anchors keep their own group (anchor 10 marked token 5, but 5 is an anchor)
     assert tg.tolist() == want.tolist()
-    assert ag.tolist() == [-1] * 5 + [0] + [-1] * 4 + [1] + [-1] * 5
-    assert sc[0, 0].tolist() == [0, 9, 0, 2, 0, 7, 0, 6, 0] and sc[0, 1, 8] == 5.0
+    assert ag.tolist() == [-1] * 5 + [0] + [-1] * 4 + [3] + [-1] * 5
+    assert sc[0].tolist() == [0, 9, 0, 2, 0, 7, 0, 6, 0] and sc[1, 8] == 5.0
+    # the order of the list does not matter, and an entry outside the tensor does nothing
+    tg2, ag2, sc2 = O.seda_assign(f2b(q), f2b(k), [-1, 10, 16, 5], 1, 4, 4, tile_h=2, tile_w=2, window=3, threshold=5.0)
+    assert np.array_equal(tg2, tg) and np.array_equal(ag2, ag) and np.isnan(sc2[0]).all() and np.isnan(sc2[2]).all()
+    assert np.array_equal(sc2[3], sc[0])
     # a window clipped by the frame edge, two heads averaged, negative scores never mark
     q2 = np.zeros((1, 2, 16, 2), dtype=np.float32); k2 = np.zeros((1, 2, 16, 2), dtype=np.float32)
     q2[0, :, 0] = [1, 0]
     k2[0, 0, :, 0] = [0, 12, 0, 0, -20, 4, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0]
     k2[0, 1, :, 0] = [0, 0, 0, 0, -20, 8, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0]
-    tg, _, sc = O.seda_assign(f2b(q2), f2b(k2), [[0]], 4, 4, window=3, threshold=5.0)
+    tg, _, sc = O.seda_assign(f2b(q2), f2b(k2), [0], 1, 4, 4, tile_h=2, tile_w=2, window=3, threshold=5.0)
     assert tg.tolist() == [0, 0, -1, -1, -1, 0] + [-1] * 10           # token 1: (12 + 0) / 2 = 6, token 5: 6, token 4: -20
-    assert np.isnan(sc[0, 0, :3]).all() and np.isnan(sc[0, 0, 3]) and sc[0, 0, 5] == 6.0
+    assert np.isnan(sc[0, :3]).all() and np.isnan(sc[0, 3]) and sc[0, 5] == 6.0
+
+
+def test_seda_groups_are_tiles_shared_by_the_frames():
+    # Sec. 3.4 step 1: the N per-frame candidates of ONE tile share a sub-formatbook.  Two frames of an 8 x 8 grid
+    # with 4 x 4 tiles; in frame 0 tile (0,0)'s candidate sits in grid row 3 (token 24) and tile (0,1)'s in grid row 0
+    # (token 4), so the ascending list of frame 0 starts with the candidate of tile (0,1), that of frame 1 with the
+    # candidate of tile (0,0): the group must follow the tile, not the position in the list.
+    scores = np.zeros((2, 1, 64))
+    scores[0, 0, [24, 4, 33, 63]] = 1.0          # frame 0: tiles (0,0) (0,1) (1,0) (1,1)
+    scores[1, 0, [0, 7, 32, 39]] = 1.0           # frame 1
+    picks = O.select_salient_tokens(scores, 8, 8, 4, 4)
+    assert picks.tolist() == [[4, 24, 33, 63], [64, 71, 96, 103]]
+    q = np.zeros((2, 1, 64, 8), dtype=np.uint16)
+    tg, ag, _ = O.seda_assign(q, q, picks.ravel(), 2, 8, 8, tile_h=4, tile_w=4, window=5, threshold=1.0)
+    assert [int(ag[r]) for r in (24, 4, 33, 63)] == [0, 1, 2, 3]
+    assert [int(ag[64 + t]) for t in (0, 7, 32, 39)] == [0, 1, 2, 3]
+    assert (ag >= 0).sum() == 8 and np.array_equal(tg, ag)      # all scores are 0: nothing but the anchors is marked
+    # the profile then pools the anchors of one tile: group 0 = rows 24 and 64
+    meta = np.zeros((128, 1), dtype=np.uint16)
+    meta[24, 0] = 3; meta[64, 0] = 3; meta[4, 0] = 5; meta[71, 0] = 5
+    counts, _ = O.seda_profile(DEFAULT_FORMATBOOK, meta, ag, 4)
+    assert counts[0, 3] == 2 and counts[1, 5] == 2 and counts[0].sum() == 2
+
+
+def test_seda_main_anchor_and_frame_pruning_hand_worked():
+    # Sec. 3.4 step 2.  Three frames of a 2 x 2 grid, one 2 x 2 tile, one channel.  Candidates: frame 0 token 1,
+    # frame 1 token 2, frame 2 token 1.  Temporal mean scores of the candidates: 2, 5, 3 -> main anchor = frame 1's
+    # (row 6, position 2).  Raw temporal scores from the main anchor: Qt[2][f = 1] = 2 times Kt[2][f] = 1, .5, 4
+    # -> 2, 1, 8; threshold 3: frame 0 is pruned, frame 2 stays, the main anchor's own frame stays although 1 < 3.
+    ts = np.zeros((4, 1, 3))
+    ts[1, 0, 0] = 2.0; ts[2, 0, 1] = 5.0; ts[1, 0, 2] = 3.0
+    qt = np.zeros((4, 1, 3, 1), dtype=np.float32); kt = np.zeros((4, 1, 3, 1), dtype=np.float32)
+    qt[2, 0, 1, 0] = 2.0
+    kt[2, 0, :, 0] = [1.0, 0.5, 4.0]
+    cand = [[1], [6], [9]]
+    main, kept, ps = O.seda_main_anchor(ts, f2b(qt), f2b(kt), cand, 2, 2, 2, 2, prune_threshold=3.0)
+    assert main.tolist() == [6] and kept.tolist() == [[-1], [6], [9]] and ps[:, 0].tolist() == [2.0, 1.0, 8.0]
+    # on a tie the earliest frame is the main anchor; a NaN score never wins; an entry outside its frame is no
+    # candidate; heads are averaged (scores 2 and 6 -> 4 > 3.5)
+    ts2 = np.zeros((4, 2, 3))
+    ts2[1, :, 0] = [4.0, 6.0]; ts2[2, :, 1] = [np.nan, 9.0]; ts2[1, :, 2] = [5.0, 5.0]
+    qt2 = np.zeros((4, 2, 3, 1), dtype=np.float32); kt2 = np.zeros((4, 2, 3, 1), dtype=np.float32)
+    qt2[1, :, 0, 0] = [1.0, 2.0]
+    kt2[1, :, 2, 0] = [2.0, 3.0]
+    main, kept, ps = O.seda_main_anchor(ts2, f2b(qt2), f2b(kt2), [[1, 3], [6, 0], [9, 30]], 2, 2, 2, 2, prune_threshold=3.5)
+    assert main.tolist() == [1]                      # 5 = 5: frame 0 before frame 2; frame 1's mean is NaN
+    assert ps[2, 0] == 4.0 and ps[1, 0] == 0.0       # (1*2 + 2*3) / 2
+    assert kept.tolist() == [[1, -1], [-1, -1], [9, -1]]
+    # two tiles side by side: each tile has its own main anchor
+    ts3 = np.zeros((8, 1, 2))
+    ts3[0, 0, 0] = 1.0; ts3[5, 0, 1] = 2.0           # tile 0: frame 0 token 0, frame 1 token 5 -> main = row 8 + 5
+    ts3[2, 0, 0] = 3.0; ts3[7, 0, 1] = 1.0           # tile 1: frame 0 token 2, frame 1 token 7 -> main = row 2
+    z = np.zeros((8, 1, 2, 1), dtype=np.uint16)
+    main, kept, _ = O.seda_main_anchor(ts3, z, z, [[0, 2], [13, 15]], 2, 4, 2, 2, prune_threshold=-1.0)
+    assert main.tolist() == [13, 2] and kept.tolist() == [[0, 2], [13, 15]]
+    main, kept, _ = O.seda_main_anchor(ts3, z, z, [[0, 2], [13, 15]], 2, 4, 2, 2, prune_threshold=0.0)
+    assert kept.tolist() == [[-1, 2], [13, -1]]      # a score of 0 does not exceed 0
+
+
+def test_seda_3d_main_anchor_and_cuboid_window_hand_worked():
+    # Sec. 3.4, 3D attention: two frames of a 2 x 4 grid, 2 x 2 tiles -> two tiles of 2 x 2 x 2 tokens.
+    sc = np.zeros((2, 16))
+    sc[0, 13] = 1.0; sc[1, 13] = 2.0                 # tile 0: frame 1, token 5 (head mean 1.5)
+    sc[0, 0] = 1.0; sc[1, 0] = 1.5                   # ... beats frame 0, token 0 (1.25)
+    sc[:, 2] = 0.75; sc[:, 10] = 0.75                # tile 1: a tie between row 2 and row 8 + 2 -> the lower row
+    sc[0, 7] = np.nan                                # a NaN never wins
+    anchors = O.seda_main_anchor_3d(sc, 2, 2, 4, 2, 2)
+    assert anchors.tolist() == [13, 2]
+    # cuboid window 3 x 3 x 3 around row 13 = (frame 1, row 1, col 1): frames 0-1 (clipped), rows 0-1, cols 0-2
+    q = np.zeros((1, 16, 1), dtype=np.float32); k = np.zeros((1, 16, 1), dtype=np.float32)
+    q[0, 13, 0] = 1.0; q[0, 2, 0] = -1.0
+    k[0, :, 0] = [6, 0, 7, 9,  0, 5, -8, 0,   0, 7, 0, 9,  3, 0, 8, -9]
+    tg, ag, s = O.seda_assign(f2b(q), f2b(k), anchors, 2, 2, 4, tile_h=2, tile_w=2, window=3, window_t=3, threshold=5.0,
+                              joint=True)
+    # anchor 13 (group 0) sees rows {0,1,2,4,5,6} and {8,9,10,12,13,14}: above 5 are 0 (6), 2 (7), 9 (7), 14 (8)
+    # anchor 2 = (frame 0, row 0, col 2) (group 1) sees cols 1-3 of both frames with scores -k: above 5 are 6 (8), 15 (9)
+    want = np.full(16, -1)
+    want[[0, 9, 14]] = 0
+    want[[6, 15]] = 1
+    want[13] = 0; want[2] = 1                        # row 2 was marked by anchor 13 but is an anchor itself
+    assert tg.tolist() == want.tolist()
+    assert ag.tolist() == [-1, -1, 1] + [-1] * 10 + [0, -1, -1]
+    # slots: frame offset major; the first frame offset (-1 from frame 1 = frame 0) holds rows 0-2, 4-6
+    assert s.shape == (2, 27) and s[0, :6].tolist() == [6, 0, 7, 0, 5, -8]
+    assert np.isnan(s[0, 6:9]).all() and np.isnan(s[0, 18:]).all() and s[0, 9:15].tolist() == [0, 7, 0, 3, 0, 8]
+    # with window_t = 1 the anchors only see their own frame
+    tg1, _, _ = O.seda_assign(f2b(q), f2b(k), anchors, 2, 2, 4, tile_h=2, tile_w=2, window=3, window_t=1, threshold=5.0,
+                              joint=True)
+    want1 = np.full(16, -1)
+    want1[[9, 14]] = 0; want1[6] = 1; want1[13] = 0; want1[2] = 1
+    assert tg1.tolist() == want1.tolist()
