@@ -356,7 +356,7 @@ def main():
         q4, k4 = qa.view(16, 24, 1024, 128), ka.view(16, 24, 1024, 128)
 
         def assign_step(i):
-            F.fb4_seda_assign(q4, k4, sal_rows, 32, 32, 5, 5.0)
+            F.fb4_seda_assign(q4, k4, sal_rows, 16, 32, 32, window=5, threshold=5.0)
         add("seda_assign_16x24x1024_window5", assign_step, 1024 * 26 * 24 * 128 * 2 + 2 * 16384 * 4, 16 * 1024)
         del qa, ka, q4, k4
         # decomposition (cfg3): 5 % salient rows

@@ -34,8 +34,8 @@
  *   - rows == 0 or cols == 0 is a successful no-op.
  *   - A call made while another device than the handle's is current returns
  *     FB4_ERR_INVALID_ARG.  The entry points without a handle
- *     (fb4_attention_scores, fb4_select_salient_tokens, fb4_seda_assign) run
- *     on the current device.
+ *     (fb4_attention_scores, fb4_select_salient_tokens, fb4_seda_assign,
+ *     fb4_seda_main_anchor, fb4_seda_main_anchor_3d) run on the current device.
  *   - The producer-fused entry points (fb4_layernorm_quantize,
  *     fb4_gelu_quantize) read x as plain IEEE bf16 and hand the quantizer the
  *     producer's bf16 result, to which the rules above then apply.
@@ -267,14 +267,17 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
  * cols channels of every row, then fb4_quantize of the result, in one pass --
  * x is read once and the normalized tensor is never written.
  *   y[r][c] = (x[r][c] - mean_r) / sqrt(var_r + eps) * gamma[c] + beta[c]
- * with the biased variance, rounded to bf16, is what gets quantized.  Because
- * that rounding decides codes, the precision of each step is part of the
- * contract: the row sums of x and x^2 in double; mean = S1 * (1/C) and
- * var = max(S2 * (1/C) - mean^2, 0) in double (one fused multiply-add);
- * a = 1 / sqrt(float(var + eps)) and b = -float(mean) * a in float (IEEE
- * square root and divide); y = fmaf(fmaf(x, a, b), gamma, beta) in float,
- * rounded to nearest even; a NaN result is the quiet NaN 0x7FC0.  x is read as plain IEEE bf16 (a row
- * with an Inf or NaN normalizes to NaN throughout).
+ * with the biased variance, rounded once to bf16, is what gets quantized.  The
+ * producer runs in fp32, the textbook way: mean_r from the sum of the row,
+ * var_r from the sum of the squared deviations from mean_r, then
+ * fma((x - mean_r) * rstd_r, gamma, beta); a NaN result is the quiet NaN
+ * 0x7FC0.  Its bf16 result agrees with the definition evaluated in double to
+ * within one bf16 step (almost always exactly; where gamma * t and beta cancel,
+ * to within 2^-20 of |gamma * t| + |beta|), a constant row gives exactly beta,
+ * and the codes are exactly fb4_quantize of that bf16 tensor.  Rows outside the
+ * range of fp32 sums (an Inf or NaN, squares beyond 2^100, var + eps below
+ * 2^-100) are evaluated in double instead.  x is read as plain IEEE bf16 (a
+ * row with an Inf or NaN normalizes to NaN throughout).
  *   opts        block 32, FB4_SEL_LUT with 8 groups (FB4_FLAG_TWO_STAGE allowed);
  *               anything else FB4_ERR_UNSUPPORTED
  *   cols        a multiple of 32, at most 12288 (FB4_ERR_UNSUPPORTED otherwise)
@@ -285,11 +288,14 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
  *               mlp.fc1, whose input this is); all NULL / 0 = full formatbook;
  *               at most 255 groups (FB4_ERR_UNSUPPORTED beyond)
  *   codes       device, 16-byte aligned (FB4_ERR_UNSUPPORTED otherwise)
+ *   y_out       NULL in production.  For checking the producer: device, bf16
+ *               [rows][cols], contiguous, 16-byte aligned; a second launch of
+ *               the producer alone writes the normalized tensor there
  */
 int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
                            int64_t cols, int64_t row_stride, const float* gamma, const float* beta,
                            float eps, const int32_t* token_group, const uint8_t* sub_formatbooks,
-                           int n_groups, uint8_t* codes, uint16_t* meta, void* stream);
+                           int n_groups, uint8_t* codes, uint16_t* meta, void* y_out, void* stream);
 
 /*
  * App. E.2, the other producer the paper names: GeLU of every element, then
@@ -359,32 +365,95 @@ int fb4_select_salient_tokens(const float* scores, int64_t frames, int heads, in
                               int tile_h, int tile_w, int32_t* rows_out, void* stream);
 
 /*
- * Sec. 3.4 ("Attention-Guided Semantic Relatedness Extraction"), the per-frame
- * part: every anchor token -- one per frame and tile, as
- * fb4_select_salient_tokens returns them -- marks as correlated the tokens of
- * a window x window square around it (clipped to the frame) whose raw
- * pre-softmax attention score from the anchor, Q[anchor] . K[token] averaged
- * over the heads (fp32), exceeds `threshold`.  A token marked by several
- * anchors belongs to the one with the highest group number; an anchor belongs
- * to its own group.  Group number = position of the anchor in its frame's
- * list, so the tiles of all frames share groups.  The cross-frame main anchor
- * and the pruning of weakly correlated frames are left to the caller (an
- * anchor entry outside its frame marks nothing).
- *   q, k           device, bf16 [frames][heads][tokens][dim], tokens = grid_h *
- *                  grid_w, dim a multiple of 8 (FB4_ERR_UNSUPPORTED otherwise)
- *   anchors        device, int32 [frames][tiles], rows of [frames * tokens]
- *   window         1..8 (FB4_ERR_UNSUPPORTED beyond); the square is centred
- *                  at the anchor, window / 2 tokens to the left and above
+ * Sec. 3.4 ("Attention-Guided Semantic Relatedness Extraction"), the marking
+ * step (step 3 for factorized attention; the cuboid step for 3D attention):
+ * every anchor token marks as correlated the tokens of a window x window
+ * square -- times window_t frames: a cuboid -- centred on it and clipped to the
+ * clip, whose raw pre-softmax attention score from the anchor, Q[anchor] .
+ * K[token] averaged over the heads (fp32), exceeds `threshold`.
+ * The GROUP of an anchor is the row-major number of the tile_h x tile_w spatial
+ * tile it lies in, (y / tile_h) * ceil(grid_w / tile_w) + x / tile_w, so the
+ * per-frame candidates of one tile share a group -- one sub-formatbook --
+ * across the frames (step 1: "N candidates per tile").  A token marked by
+ * anchors of several groups belongs to the highest group number (App. D:
+ * overlapping windows go to the subsequent anchor = the later tile); an anchor
+ * belongs to its own group.
+ *   q, k           device, bf16, 16-byte aligned, dim a multiple of 8
+ *                  (FB4_ERR_UNSUPPORTED otherwise); tokens = grid_h * grid_w
+ *                  joint = 0 (factorized attention): [frames][heads][tokens][dim],
+ *                  the spatial attention's projections; window_t must be 1
+ *                  joint = 1 (3D attention): [heads][frames * tokens][dim]
+ *   anchors        device, int32 [n_anchors], rows of the [frames * tokens]
+ *                  activation in any order (fb4_select_salient_tokens,
+ *                  fb4_seda_main_anchor's `kept`, fb4_seda_main_anchor_3d); an
+ *                  entry outside 0 .. frames * tokens - 1 (a pruned frame's -1)
+ *                  does nothing
+ *   window         1..8, window_t 1..64 (FB4_ERR_UNSUPPORTED beyond); the box
+ *                  starts window / 2 tokens to the left and above and
+ *                  window_t / 2 frames before the anchor
  *   token_group    device, int32 [frames * tokens]: group or -1 -- the
  *                  token_group argument of fb4_quantize_seda
  *   anchor_group   device, int32 [frames * tokens]: the group on anchor rows,
- *                  -1 elsewhere -- the anchor_group argument of fb4_seda_profile
- *   window_scores  device, float [frames][tiles][window * window] or NULL: the
- *                  scores that were compared (NaN outside the frame)
+ *                  -1 elsewhere -- the anchor_group argument of
+ *                  fb4_seda_profile (whose n_groups is the number of tiles)
+ *   window_scores  device, float [n_anchors][window_t * window * window] or
+ *                  NULL: the scores that were compared, frame offset major (NaN
+ *                  outside the clip)
  */
-int fb4_seda_assign(const void* q, const void* k, int64_t frames, int heads, int grid_h, int grid_w,
-                    int64_t dim, const int32_t* anchors, int tiles, int window, float threshold,
-                    int32_t* token_group, int32_t* anchor_group, float* window_scores, void* stream);
+int fb4_seda_assign(const void* q, const void* k, int joint, int64_t frames, int heads, int grid_h, int grid_w,
+                    int64_t dim, const int32_t* anchors, int64_t n_anchors, int tile_h, int tile_w, int window,
+                    int window_t, float threshold, int32_t* token_group, int32_t* anchor_group, float* window_scores,
+                    void* stream);
+
+/*
+ * Sec. 3.4, factorized attention, step 2 (and App. H, "Temporal Axis
+ * Integration"): per spatial tile, the main anchor among the tile's per-frame
+ * candidates, and the pruning of the frames that are weakly correlated with it.
+ * A candidate's tile is found from its position.  Main anchor = the candidate
+ * whose own temporal mean attention score, averaged over the heads (in double,
+ * head by head), is highest; the earliest frame on ties, a NaN never wins.
+ * Frame f keeps its candidate if it is the main anchor's frame f*, or if the raw
+ * temporal attention score from the main anchor to frame f at the main
+ * anchor's position p*, Qt[p*][h][f*] . Kt[p*][h][f] averaged over the heads
+ * (fp32), exceeds prune_threshold.
+ *   temporal_scores  device, float [tokens][heads][frames]: what
+ *                    fb4_attention_scores returns for the temporal attention
+ *                    (group = spatial position and head, tokens = frames)
+ *   qt, kt           device, bf16 [tokens][heads][frames][dim], the temporal
+ *                    attention's projections; dim a multiple of 8
+ *   candidates       device, int32 [frames][n_per_frame]: per frame the anchor
+ *                    candidates of step 1 as rows of the [frames * tokens]
+ *                    activation (fb4_select_salient_tokens); an entry outside
+ *                    its own frame is no candidate; of several candidates of
+ *                    one tile in one frame the first listed counts
+ *   main_anchor      device, int32 [tiles]: the main anchor's row, -1 for a tile
+ *                    without candidates
+ *   kept             device, int32 [frames][n_per_frame]: `candidates` with the
+ *                    pruned and the invalid entries set to -1 -- the `anchors`
+ *                    argument of fb4_seda_assign
+ *   prune_scores     device, float [frames][tiles] or NULL: the scores that
+ *                    were compared (NaN where a frame has no candidate)
+ *   frames at most 1024 (FB4_ERR_UNSUPPORTED beyond)
+ */
+int fb4_seda_main_anchor(const float* temporal_scores, const void* qt, const void* kt, int64_t frames, int heads,
+                         int grid_h, int grid_w, int64_t dim, const int32_t* candidates, int n_per_frame, int tile_h,
+                         int tile_w, float prune_threshold, int32_t* main_anchor, int32_t* kept, float* prune_scores,
+                         void* stream);
+
+/*
+ * Sec. 3.4, 3D attention: the main anchor of every spatial tile is the token
+ * with the highest mean attention score among the tile's tile_h x tile_w x
+ * frames tokens; the scores of the heads are averaged in double, head by head;
+ * the lowest row on ties, a NaN never wins.
+ *   scores    device, float [heads][frames * tokens]: fb4_attention_scores with
+ *             one group per head over the whole clip
+ *   anchors   device, int32 [tiles], tiles = ceil(grid_h / tile_h) *
+ *             ceil(grid_w / tile_w): rows of the [frames * tokens] activation,
+ *             in tile order -- the `anchors` argument of fb4_seda_assign with
+ *             joint = 1
+ */
+int fb4_seda_main_anchor_3d(const float* scores, int64_t frames, int heads, int grid_h, int grid_w, int tile_h,
+                            int tile_w, int32_t* anchors, void* stream);
 
 #ifdef __cplusplus
 }

@@ -69,11 +69,14 @@ def _load():
     lib.fb4_repack_mxfp8.argtypes = [p, p, p, i64, i64, i32, p, i64, p, p]
     lib.fb4_attention_scores.argtypes = [p, p, i64, i64, i64, i32, p, p]
     lib.fb4_select_salient_tokens.argtypes = [p, i64, i32, i32, i32, i32, i32, p, p]
-    lib.fb4_seda_assign.argtypes = [p, p, i64, i32, i32, i32, i64, p, i32, i32, ctypes.c_float, p, p, p, p]
+    lib.fb4_seda_assign.argtypes = [p, p, i32, i64, i32, i32, i32, i64, p, i64, i32, i32, i32, i32, ctypes.c_float, p, p,
+                                    p, p]
+    lib.fb4_seda_main_anchor.argtypes = [p, p, p, i64, i32, i32, i32, i64, p, i32, i32, i32, ctypes.c_float, p, p, p, p]
+    lib.fb4_seda_main_anchor_3d.argtypes = [p, i64, i32, i32, i32, i32, i32, p, p]
     lib.fb4_gelu_table_host.argtypes = [i32, p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
     lib.fb4_gelu_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, i32, p, p, i32, p, p, p]
     lib.fb4_layernorm_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, ctypes.c_float, p, p, i32,
-                                           p, p, p]
+                                           p, p, p, p]
     return lib
 
 
@@ -84,7 +87,7 @@ EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts
            "fb4_quantize_decompose", "fb4_seda_profile",
            "fb4_repack_mxfp8", "fb4_layernorm_quantize", "fb4_gelu_quantize",
            "fb4_gelu_table_host", "fb4_attention_scores", "fb4_select_salient_tokens",
-           "fb4_seda_assign"]
+           "fb4_seda_assign", "fb4_seda_main_anchor", "fb4_seda_main_anchor_3d"]
 
 
 def lib():
@@ -181,9 +184,10 @@ def fb4_quantize(luts, o, x, codes=None, meta=None, stream=None):
 
 
 def fb4_layernorm_quantize(luts, o, x, gamma=None, beta=None, eps=1e-6, codes=None, meta=None, stream=None,
-                           token_group=None, sub_formatbooks=None):
+                           token_group=None, sub_formatbooks=None, y_out=None):
     """LayerNorm over the channels of each row (gamma, beta: float32 cuda [cols] or None), then quantize, in one
-    pass; token_group / sub_formatbooks as in fb4_quantize_seda (optional).  Returns (codes, meta)."""
+    pass; token_group / sub_formatbooks as in fb4_quantize_seda (optional); y_out: bf16 cuda [rows][cols] that
+    receives the producer's result (checks only).  Returns (codes, meta)."""
     rows, cols = x.shape
     if codes is None:
         codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
@@ -193,7 +197,7 @@ def fb4_layernorm_quantize(luts, o, x, gamma=None, beta=None, eps=1e-6, codes=No
                                      x.stride(0) if rows > 1 else cols, _dp(gamma), _dp(beta), float(eps),
                                      _dp(token_group), _dp(sub_formatbooks),
                                      0 if sub_formatbooks is None else sub_formatbooks.shape[0],
-                                     _dp(codes), _dp(meta), _stream(stream))
+                                     _dp(codes), _dp(meta), _dp(y_out), _stream(stream))
     _check(rc, "fb4_layernorm_quantize")
     return codes, meta
 
@@ -222,19 +226,48 @@ def fb4_select_salient_tokens(scores, grid_h, grid_w, tile_h=4, tile_w=4, rows_o
     return rows_out
 
 
-def fb4_seda_assign(q, k, anchors, grid_h, grid_w, window=5, threshold=5.0, want_scores=False, stream=None,
-                    token_group=None, anchor_group=None):
-    """q, k: bf16 cuda [frames][heads][tokens][dim]; anchors: int32 cuda [frames][tiles].  Returns (token_group,
-    anchor_group) int32 [frames * tokens] (and the compared scores, float32 [frames][tiles][window^2], if asked)."""
-    frames, heads, tokens, dim = q.shape
-    assert tokens == grid_h * grid_w
-    tiles = anchors.shape[1]
+def fb4_seda_assign(q, k, anchors, frames, grid_h, grid_w, tile_h=4, tile_w=4, window=5, window_t=1, threshold=5.0,
+                    joint=False, want_scores=False, stream=None, token_group=None, anchor_group=None):
+    """q, k: bf16 cuda [frames][heads][tokens][dim] (joint=False) or [heads][frames * tokens][dim] (joint=True);
+    anchors: int32 cuda, any shape, rows of the [frames * tokens] activation.  Returns (token_group, anchor_group)
+    int32 [frames * tokens] (and the compared scores, float32 [n_anchors][window_t * window^2], if asked)."""
+    heads, dim = (q.shape[0], q.shape[2]) if joint else (q.shape[1], q.shape[3])
+    tokens = grid_h * grid_w
+    n = anchors.numel()
     tg = torch.empty(frames * tokens, dtype=torch.int32, device=q.device) if token_group is None else token_group
     ag = torch.empty(frames * tokens, dtype=torch.int32, device=q.device) if anchor_group is None else anchor_group
-    sc = torch.empty((frames, tiles, window * window), dtype=torch.float32, device=q.device) if want_scores else None
-    _check(_lib.fb4_seda_assign(_dp(q), _dp(k), frames, heads, grid_h, grid_w, dim, _dp(anchors), tiles, window,
-                                float(threshold), _dp(tg), _dp(ag), _dp(sc), _stream(stream)), "fb4_seda_assign")
+    sc = torch.empty((n, window_t * window * window), dtype=torch.float32, device=q.device) if want_scores else None
+    _check(_lib.fb4_seda_assign(_dp(q), _dp(k), 1 if joint else 0, frames, heads, grid_h, grid_w, dim, _dp(anchors), n,
+                                tile_h, tile_w, window, window_t, float(threshold), _dp(tg), _dp(ag), _dp(sc),
+                                _stream(stream)), "fb4_seda_assign")
     return (tg, ag, sc) if want_scores else (tg, ag)
+
+
+def fb4_seda_main_anchor(temporal_scores, qt, kt, candidates, grid_h, grid_w, tile_h=4, tile_w=4, prune_threshold=3.0,
+                         want_scores=False, stream=None):
+    """temporal_scores: float32 cuda [tokens][heads][frames]; qt, kt: bf16 cuda [tokens][heads][frames][dim];
+    candidates: int32 cuda [frames][n].  Returns (main_anchor int32 [tiles], kept int32 [frames][n]) and the compared
+    scores float32 [frames][tiles] if asked."""
+    tokens, heads, frames, dim = qt.shape
+    assert tokens == grid_h * grid_w and candidates.shape[0] == frames
+    tiles = ((grid_h + tile_h - 1) // tile_h) * ((grid_w + tile_w - 1) // tile_w)
+    main = torch.empty(tiles, dtype=torch.int32, device=qt.device)
+    kept = torch.empty_like(candidates)
+    ps = torch.empty((frames, tiles), dtype=torch.float32, device=qt.device) if want_scores else None
+    _check(_lib.fb4_seda_main_anchor(_dp(temporal_scores), _dp(qt), _dp(kt), frames, heads, grid_h, grid_w, dim,
+                                     _dp(candidates), candidates.shape[1], tile_h, tile_w, float(prune_threshold),
+                                     _dp(main), _dp(kept), _dp(ps), _stream(stream)), "fb4_seda_main_anchor")
+    return (main, kept, ps) if want_scores else (main, kept)
+
+
+def fb4_seda_main_anchor_3d(scores, frames, grid_h, grid_w, tile_h=4, tile_w=4, stream=None):
+    """scores: float32 cuda [heads][frames * tokens].  Returns int32 [tiles]: the main anchor of every spatial tile."""
+    heads = scores.shape[0]
+    tiles = ((grid_h + tile_h - 1) // tile_h) * ((grid_w + tile_w - 1) // tile_w)
+    anchors = torch.empty(tiles, dtype=torch.int32, device=scores.device)
+    _check(_lib.fb4_seda_main_anchor_3d(_dp(scores), frames, heads, grid_h, grid_w, tile_h, tile_w, _dp(anchors),
+                                        _stream(stream)), "fb4_seda_main_anchor_3d")
+    return anchors
 
 
 def fb4_gelu_table_host(approximate=0):

@@ -697,7 +697,7 @@ int fb4_seda_profile(const fb4_luts* luts, const uint16_t* meta, int64_t rows, i
 int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
                            int64_t row_stride, const float* gamma, const float* beta, float eps,
                            const int32_t* token_group, const uint8_t* sub_formatbooks, int n_groups, uint8_t* codes,
-                           uint16_t* meta, void* stream)
+                           uint16_t* meta, void* y_out, void* stream)
 {
     int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
     if (rc != FB4_OK) return rc;
@@ -706,12 +706,13 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8) return FB4_ERR_UNSUPPORTED;
     if (rows == 0 || cols == 0) return FB4_OK;
     const int64_t nb = cols / 32;
-    if (nb > 64 * kLnMaxChunksPerLane || !aligned(codes, 16) || (gamma && !aligned(gamma, 4)) || (beta && !aligned(beta, 4)))
+    if (nb > 64 * kLnMaxChunksPerLane || !aligned(codes, 16) || (gamma && !aligned(gamma, 4)) || (beta && !aligned(beta, 4)) ||
+        (y_out && !aligned(y_out, 16)))
         return FB4_ERR_UNSUPPORTED;
     if ((uint64_t)rows * (uint64_t)nb >= 0x7F000000ull) return FB4_ERR_UNSUPPORTED;
     if ((rc = check_device(luts)) != FB4_OK) return rc;
-    // Chunks per lane B and rows per bundle: the fullest wavefront among B <= 4 (with 5 or 6 -- rows longer than
-    // 8192 -- the kernel runs 8 instead of 12 wavefronts per CU), the fewest chunks among equals.
+    // Chunks per lane B and rows per bundle: the fullest wavefront among B <= 4, the fewest chunks among equals;
+    // rows longer than 8192 need 5 or 6.
     int B = 0;
     uint32_t rw = 0;
     double best = 0.0;
@@ -724,7 +725,7 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     if (B == 0) { B = (int)((nb + 63) / 64); rw = 1; }
     if (rw > (uint32_t)rows) rw = (uint32_t)rows;
     const uint32_t n_bundles = (uint32_t)((rows + rw - 1) / rw);
-    const int kLnWaves = ln_threads(B) / 64;
+    const int kLnWaves = kLnThreads / 64;
     long long g = ((long long)n_bundles + kLnWaves - 1) / kLnWaves;
     if (g > luts->n_cu) g = luts->n_cu;
     const unsigned groups = (unsigned)g;
@@ -739,20 +740,22 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     p.sub = sub_formatbooks;
     p.n_groups = (uint32_t)n_groups;
     p.n_dialects = (uint32_t)luts->n_dialects;
+    p.y_out = static_cast<uint16_t*>(y_out);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
     const bool seda = token_group != nullptr;
 #define FB4_LN_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), n_bundles, rw, (uint32_t)nb, groups, (long long)row_stride, gamma, beta, p
-#define FB4_LN_LAUNCH(b, t, sd) hipLaunchKernelGGL((layernorm_quantize_kernel<b, t, sd, ln_threads(b)>), dim3(groups), dim3(ln_threads(b)), 0, s, FB4_LN_ARGS)
-#define FB4_LN_CASE(b)                                  \
-    case b:                                             \
-        if (seda) {                                     \
-            if (ts) FB4_LN_LAUNCH(b, true, true);       \
-            else FB4_LN_LAUNCH(b, false, true);         \
-        } else {                                        \
-            if (ts) FB4_LN_LAUNCH(b, true, false);      \
-            else FB4_LN_LAUNCH(b, false, false);        \
-        }                                               \
+#define FB4_LN_LAUNCH(b, t, sd, wy) hipLaunchKernelGGL((layernorm_quantize_kernel<b, t, sd, wy>), dim3(groups), dim3(kLnThreads), 0, s, FB4_LN_ARGS)
+#define FB4_LN_CASE(b)                                         \
+    case b:                                                    \
+        if (y_out) FB4_LN_LAUNCH(b, false, false, true);       \
+        if (seda) {                                            \
+            if (ts) FB4_LN_LAUNCH(b, true, true, false);       \
+            else FB4_LN_LAUNCH(b, false, true, false);         \
+        } else {                                               \
+            if (ts) FB4_LN_LAUNCH(b, true, false, false);      \
+            else FB4_LN_LAUNCH(b, false, false, false);        \
+        }                                                      \
         break;
     switch (B) {
         FB4_LN_CASE(1) FB4_LN_CASE(2) FB4_LN_CASE(3) FB4_LN_CASE(4) FB4_LN_CASE(5) FB4_LN_CASE(6)
@@ -864,28 +867,83 @@ int fb4_select_salient_tokens(const float* scores, int64_t frames, int heads, in
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
-int fb4_seda_assign(const void* q, const void* k, int64_t frames, int heads, int grid_h, int grid_w, int64_t dim,
-                    const int32_t* anchors, int tiles, int window, float threshold, int32_t* token_group,
-                    int32_t* anchor_group, float* window_scores, void* stream)
+int fb4_seda_assign(const void* q, const void* k, int joint, int64_t frames, int heads, int grid_h, int grid_w,
+                    int64_t dim, const int32_t* anchors, int64_t n_anchors, int tile_h, int tile_w, int window,
+                    int window_t, float threshold, int32_t* token_group, int32_t* anchor_group, float* window_scores,
+                    void* stream)
 {
-    if (frames < 0 || heads < 1 || grid_h < 1 || grid_w < 1 || dim < 1 || tiles < 1 || window < 1) return FB4_ERR_INVALID_ARG;
+    if (frames < 0 || heads < 1 || grid_h < 1 || grid_w < 1 || dim < 1 || n_anchors < 0 || window < 1 || window_t < 1 ||
+        tile_h < 1 || tile_w < 1 || (joint != 0 && joint != 1))
+        return FB4_ERR_INVALID_ARG;
     if (!(threshold == threshold)) return FB4_ERR_INVALID_ARG;
+    if (!joint && window_t != 1) return FB4_ERR_INVALID_ARG;   // factorized attention has no scores across frames
     if (frames == 0) return FB4_OK;
-    if (!q || !k || !anchors || !token_group || !anchor_group) return FB4_ERR_INVALID_ARG;
+    if (!token_group || !anchor_group || (n_anchors > 0 && (!q || !k || !anchors))) return FB4_ERR_INVALID_ARG;
     const int64_t tokens = (int64_t)grid_h * grid_w;
-    if ((dim % 8) || window > 8 || !aligned(q, 16) || !aligned(k, 16) || !aligned(anchors, 4) || !aligned(token_group, 4) ||
-        !aligned(anchor_group, 4) || (window_scores && !aligned(window_scores, 4)))
+    if ((dim % 8) || window > 8 || window_t > 64 || !aligned(q, 16) || !aligned(k, 16) || !aligned(anchors, 4) ||
+        !aligned(token_group, 4) || !aligned(anchor_group, 4) || (window_scores && !aligned(window_scores, 4)))
         return FB4_ERR_UNSUPPORTED;
-    if (frames * tokens > 0x7FFFFFFFll || frames * tiles > 0x7FFFFFFFll || tokens * dim > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
+    if (frames * tokens > 0x7FFFFFFFll || n_anchors > 0x7FFFFFFFll || tokens * dim > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint32_t n = (uint32_t)(frames * tokens);
     hipLaunchKernelGGL(seda_fill_kernel, dim3((n + 255) / 256), dim3(256), 0, s, token_group, anchor_group, n);
-    hipLaunchKernelGGL(seda_mark_kernel, dim3((unsigned)(frames * tiles)), dim3(kAssignThreads), 0, s,
-                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), (uint32_t)heads, (uint32_t)grid_h,
-                       (uint32_t)grid_w, (uint32_t)dim, anchors, (uint32_t)tiles, (uint32_t)window, threshold, token_group,
-                       window_scores);
-    hipLaunchKernelGGL(seda_anchor_kernel, dim3((unsigned)((frames * tiles + 255) / 256)), dim3(256), 0, s, anchors,
-                       (uint32_t)frames, (uint32_t)tiles, (uint32_t)tokens, token_group, anchor_group);
+    if (n_anchors > 0) {
+        AssignParams p = {};
+        p.frames = (uint32_t)frames; p.heads = (uint32_t)heads; p.grid_h = (uint32_t)grid_h; p.grid_w = (uint32_t)grid_w;
+        p.dim = (uint32_t)dim; p.tile_h = (uint32_t)tile_h; p.tile_w = (uint32_t)tile_w;
+        p.window = (uint32_t)window; p.window_t = (uint32_t)window_t;
+        p.stride_f = joint ? (uint64_t)tokens : (uint64_t)heads * tokens;
+        p.stride_h = joint ? (uint64_t)frames * tokens : (uint64_t)tokens;
+        p.threshold = threshold;
+        hipLaunchKernelGGL(seda_mark_kernel, dim3((unsigned)n_anchors, (unsigned)window_t), dim3(kAssignThreads), 0, s,
+                           static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), anchors, p, token_group,
+                           window_scores);
+        hipLaunchKernelGGL(seda_anchor_kernel, dim3((unsigned)((n_anchors + 255) / 256)), dim3(256), 0, s, anchors,
+                           (uint32_t)n_anchors, (uint32_t)frames, (uint32_t)grid_h, (uint32_t)grid_w, (uint32_t)tile_h,
+                           (uint32_t)tile_w, token_group, anchor_group);
+    }
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+int fb4_seda_main_anchor(const float* temporal_scores, const void* qt, const void* kt, int64_t frames, int heads,
+                         int grid_h, int grid_w, int64_t dim, const int32_t* candidates, int n_per_frame, int tile_h,
+                         int tile_w, float prune_threshold, int32_t* main_anchor, int32_t* kept, float* prune_scores,
+                         void* stream)
+{
+    if (frames < 0 || heads < 1 || grid_h < 1 || grid_w < 1 || dim < 1 || n_per_frame < 0 || tile_h < 1 || tile_w < 1)
+        return FB4_ERR_INVALID_ARG;
+    if (!(prune_threshold == prune_threshold)) return FB4_ERR_INVALID_ARG;
+    if (!main_anchor) return FB4_ERR_INVALID_ARG;
+    const int64_t tokens = (int64_t)grid_h * grid_w;
+    const int64_t tiles = (int64_t)((grid_h + tile_h - 1) / tile_h) * ((grid_w + tile_w - 1) / tile_w);
+    const int64_t n_cand = frames * n_per_frame;
+    if (n_cand > 0 && (!temporal_scores || !qt || !kt || !candidates || !kept)) return FB4_ERR_INVALID_ARG;
+    if ((dim % 8) || frames > (int64_t)kMainMaxFrames || !aligned(qt, 16) || !aligned(kt, 16) || !aligned(temporal_scores, 4) ||
+        !aligned(candidates, 4) || !aligned(main_anchor, 4) || !aligned(kept, 4) || (prune_scores && !aligned(prune_scores, 4)))
+        return FB4_ERR_UNSUPPORTED;
+    if (frames * tokens > 0x7FFFFFFFll || n_cand > 0x7FFFFFFFll || frames * dim > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n_cand > 0)
+        hipLaunchKernelGGL(seda_fill_kernel, dim3((unsigned)((n_cand + 255) / 256)), dim3(256), 0, s, kept,
+                           static_cast<int32_t*>(nullptr), (uint32_t)n_cand);
+    hipLaunchKernelGGL(seda_main_anchor_kernel, dim3((unsigned)tiles), dim3(kMainThreads), 0, s, temporal_scores,
+                       static_cast<const uint16_t*>(qt), static_cast<const uint16_t*>(kt), (uint32_t)frames, (uint32_t)heads,
+                       (uint32_t)grid_h, (uint32_t)grid_w, (uint32_t)dim, candidates, (uint32_t)n_per_frame, (uint32_t)tile_h,
+                       (uint32_t)tile_w, prune_threshold, main_anchor, kept, prune_scores);
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
+int fb4_seda_main_anchor_3d(const float* scores, int64_t frames, int heads, int grid_h, int grid_w, int tile_h,
+                            int tile_w, int32_t* anchors, void* stream)
+{
+    if (frames < 1 || heads < 1 || grid_h < 1 || grid_w < 1 || tile_h < 1 || tile_w < 1) return FB4_ERR_INVALID_ARG;
+    if (!scores || !anchors) return FB4_ERR_INVALID_ARG;
+    const int64_t tokens = (int64_t)grid_h * grid_w;
+    const int64_t tiles = (int64_t)((grid_h + tile_h - 1) / tile_h) * ((grid_w + tile_w - 1) / tile_w);
+    if (frames * tokens > 0x7FFFFFFFll || !aligned(scores, 4) || !aligned(anchors, 4)) return FB4_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(seda_main_anchor_3d_kernel, dim3((unsigned)tiles), dim3(kMainThreads), 0,
+                       static_cast<hipStream_t>(stream), scores, (uint32_t)frames, (uint32_t)heads, (uint32_t)grid_h,
+                       (uint32_t)grid_w, (uint32_t)tile_h, (uint32_t)tile_w, anchors);
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 

@@ -4,27 +4,27 @@
 // never reaches memory, codes and metadata are written as by the streaming
 // kernel.
 //
-// The producer is the textbook LayerNorm over the channels of a token with a
-// per-channel scale and shift; the quantizer's input is its result rounded to
-// bf16.  That rounding decides codes, so the precision of each step is fixed:
-//   S1 = sum x, S2 = sum x^2 in double (every term exact); mean = S1 * (1/C),
-//   var = max(fma(-mean, mean, S2 * (1/C)), 0) in double;
-//   a = 1 / sqrt(float(var + eps)), b = -float(mean) * a in float (IEEE
-//   square root and divide);
-//   y = fmaf(fmaf(x, a, b), gamma, beta) in float, rounded to bf16 (nearest
-//   even); a NaN becomes the canonical quiet NaN 0x7FC0.
-// The sums are exact, hence independent of their order, whenever a row's values
-// span less than about 2^12 in magnitude; beyond that another order may move
-// S2 by one ulp of a double, which changes a or b once in about 2^29 rows.
+// The producer is the textbook LayerNorm over the channels of a token,
+//   y = (x - mean) / sqrt(var + eps) * gamma + beta,   var biased,
+// evaluated the textbook way in fp32: the mean from the sum of the row, the
+// variance from the sum of the squared deviations from that mean (two passes
+// over the registers that hold the row), then (x - mean) * rstd, one fused
+// multiply-add with gamma and beta, and one rounding to bf16 (a NaN becomes the
+// quiet NaN 0x7FC0).  The result agrees with the definition evaluated in double
+// to within one bf16 step and is the correctly rounded value for nearly every
+// element; a constant row gives exactly beta.
+// Rows whose fp32 sums leave the range (an Inf or NaN among the inputs, values
+// beyond about 1e18 whose squares overflow, deviations so small that var + eps
+// underflows) are redone for the whole bundle by a plain routine in double.
 //
 // Work split: a wavefront owns whole rows, so the row sums never leave it.  A
 // "bundle" is RW consecutive rows, RW * nb <= 64 * B chunks of 32 elements;
-// lane l works on chunks l, l + 64, ..., l + 64 (B - 1) of the bundle (the
-// same channels in every bundle, so its scale / shift addresses are loop
-// invariants), the wavefront reduces the sums per row with butterfly exchanges
-// (a fixed order: results do not change from run to run), and each lane then
-// normalizes and quantizes its chunks with the streaming kernel's per-chunk
-// routine.  Bundles are dealt like that kernel's tiles: to persistent
+// lane l holds chunks l, l + 64, ..., l + 64 (B - 1) of the bundle in
+// registers (the same channels in every bundle, so its scale / shift addresses
+// are loop invariants), the wavefront reduces the sums per row with butterfly
+// exchanges (a fixed order: results do not change from run to run), and each
+// lane then normalizes and quantizes its chunks with the streaming kernel's
+// per-chunk routine.  Bundles are dealt like that kernel's tiles: to persistent
 // workgroups round robin, to a workgroup's wavefronts on demand.
 #pragma once
 
@@ -44,9 +44,12 @@ struct LayerNormParams {
     const uint8_t* sub;           // [n_groups][8] DIDs
     uint32_t n_groups;            // <= kMaxFusedProducerGroups
     uint32_t n_dialects;
+    uint16_t* y_out;              // kWriteY only: [rows][cols] bf16, the producer's result
 };
 
-constexpr int ln_threads(int chunks_per_lane) { return chunks_per_lane <= 4 ? 768 : 512; }
+constexpr int kLnThreads = 512;
+// chunks per lane up to which the next bundle is requested while this one is worked on (two bundles in registers)
+constexpr int kLnPrefetchChunks = 3;
 constexpr int kLnMaxChunksPerLane = 6;
 constexpr int kLdsLnTables = lds_fast_bytes(false, false, false);
 
@@ -90,21 +93,69 @@ __device__ __forceinline__ void layernorm_tables_to_lds(uint8_t* lds, const uint
     __syncthreads();
 }
 
+// What the normalization of a row needs: t = fma(x, s, nms) * r is (x - mean) * rstd, with a power of two s
+// that is 1 unless the plain routine had to rescale the row to stay inside fp32's range.
+struct RowNorm {
+    float s, nms, r;
+};
+
+// Plain routine for one row of any content, by the whole wavefront, in double: the row is read again from
+// memory (lane l takes the 32-bit words l, l + 64, ...), mean and squared deviations are summed in double, and
+// the three factors come back scaled by a power of two so that neither x * s nor the product with r leaves
+// fp32's range.  Kept out of line: it runs for rows outside the fast path's range only.
+__device__ __noinline__ RowNorm layernorm_row_plain(const uint16_t* xrow, uint32_t cols, float eps)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(xrow);
+    double s1 = 0.0;
+    uint32_t amax = 0;
+#pragma unroll 1
+    for (uint32_t i = lane; i < cols / 2; i += 64) {
+        const uint32_t v = w[i];
+        s1 += (double)__uint_as_float(v << 16) + (double)__uint_as_float(v & 0xFFFF0000u);
+        amax = max(amax, max(v & 0x7FFFu, (v >> 16) & 0x7FFFu));
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        s1 += __shfl_xor(s1, off);
+        amax = max(amax, (uint32_t)__shfl_xor((int)amax, off));
+    }
+    const double mean = s1 / (double)cols;
+    double s2 = 0.0;
+#pragma unroll 1
+    for (uint32_t i = lane; i < cols / 2; i += 64) {
+        const uint32_t v = w[i];
+        const double d0 = (double)__uint_as_float(v << 16) - mean, d1 = (double)__uint_as_float(v & 0xFFFF0000u) - mean;
+        s2 = fma(d0, d0, s2);
+        s2 = fma(d1, d1, s2);
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) s2 += __shfl_xor(s2, off);
+    const double rstd = 1.0 / sqrt(s2 / (double)cols + (double)eps);
+    // s = 2^-(exponent of the row's largest magnitude), an exact factor
+    const int e = (int)min(max(amax >> 7, 1u), 254u) - 127;
+    const double sc = __builtin_ldexp(1.0, -e);
+    RowNorm out;
+    out.s = (float)sc;
+    out.nms = (float)(-mean * sc);
+    const double r = rstd / sc;
+    out.r = (r > 3.0e38 && r < __builtin_inf()) ? 3.0e38f : (float)r;   // (Inf and NaN stay)
+    return out;
+}
+
 // B: chunks per lane (the host picks it from the row length); gamma / beta may be null (1 / 0).
-// One chunk per lane is in registers at a time: a first pass over the bundle's chunks forms the sums, a second
-// pass reads the chunks again (from the L2 cache: the wavefront has just read them) and normalizes and
-// quantizes them.  Keeping the whole bundle in registers instead saves the second read but needs 220 registers
-// for three chunks, i.e. 8 wavefronts per CU: 43.9 us on a 16384x3072 tensor against 40.7 us this way with 12,
-// and rows longer than 8192 spilled (100 us per 50 M elements against 62-76 us).
-// kThreads: 768 up to four chunks per lane, 512 beyond (the per-chunk bookkeeping then needs the registers).
-template <int B, bool kTwoStage, bool kSeda, int kThreads>
-__global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
+// kWriteY: the producer alone -- writes the normalized bf16 tensor to p.y_out and nothing else (for checking the
+// producer against its definition; production launches never use it).
+template <int B, bool kTwoStage, bool kSeda, bool kWriteY>
+__global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
     const uint8_t* blob, const uint16_t* x, uint32_t n_bundles, uint32_t rw, uint32_t nb, uint32_t n_workgroups,
     long long row_stride, const float* gamma, const float* beta, LayerNormParams p)
 {
+    constexpr int kThreads = kLnThreads;
     constexpr int kWaves = kThreads / 64;
     constexpr int kGbFloats = 2048 * B;
     constexpr int kLdsSeda = kLdsLnTables + 2 * kGbFloats * 4;
+    constexpr bool kPrefetch = B <= kLnPrefetchChunks;
     __shared__ __align__(16) uint8_t lds[kLdsSeda + (kSeda ? (kMaxFusedProducerGroups + 1) * 32 : 0)];
     __shared__ uint32_t wg_next;
     float* lds_gamma = reinterpret_cast<float*>(lds + kLdsLnTables);
@@ -124,106 +175,145 @@ __global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
         rloc[j] = ic / nb;
         cb[j] = ic - rloc[j] * nb;
     }
-    auto request = [&](uint32_t u, int j, uint32_t (&q)[16], int32_t& grp) {
-        const uint32_t row = min(min(u, n_bundles - 1u) * rw + rloc[j], p.rows - 1u);
-        if (kSeda) grp = p.token_group[row];
-        const uint4* px = reinterpret_cast<const uint4*>(x + (long long)row * row_stride + (long long)cb[j] * 32);
-        const uint4 q0 = px[0], q1 = px[1], q2 = px[2], q3 = px[3];
-        q[0] = q0.x; q[1] = q0.y; q[2] = q0.z; q[3] = q0.w; q[4] = q1.x; q[5] = q1.y; q[6] = q1.z; q[7] = q1.w;
-        q[8] = q2.x; q[9] = q2.y; q[10] = q2.z; q[11] = q2.w; q[12] = q3.x; q[13] = q3.y; q[14] = q3.z; q[15] = q3.w;
+    // Requests all of this lane's chunks of bundle u (a bundle or row past the end reads the last one; its
+    // results are never stored).
+    auto request = [&](uint32_t u, uint32_t (&q)[B][16], int32_t (&grp)[B]) {
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const uint32_t row = min(min(u, n_bundles - 1u) * rw + rloc[j], p.rows - 1u);
+            grp[j] = kSeda ? p.token_group[row] : -1;
+            const uint4* px = reinterpret_cast<const uint4*>(x + (long long)row * row_stride + (long long)cb[j] * 32);
+            const uint4 q0 = px[0], q1 = px[1], q2 = px[2], q3 = px[3];
+            q[j][0] = q0.x; q[j][1] = q0.y; q[j][2] = q0.z; q[j][3] = q0.w; q[j][4] = q1.x; q[j][5] = q1.y; q[j][6] = q1.z; q[j][7] = q1.w;
+            q[j][8] = q2.x; q[j][9] = q2.y; q[j][10] = q2.z; q[j][11] = q2.w; q[j][12] = q3.x; q[j][13] = q3.y; q[j][14] = q3.z; q[j][15] = q3.w;
+        }
     };
 
     uint32_t u = blockIdx.x + wave * W;
     uint32_t u_next = blockIdx.x + (kWaves + wave) * W;
     if (threadIdx.x == 0) wg_next = 2 * kWaves;
-    // Two chunk buffers used in turn: a bundle takes 2 B steps (B chunks summed, B chunks quantized), step s
-    // works on buf[s & 1] while the chunk of step s + 1 is on its way into the other one.
-    uint32_t buf[2][16];
-    int32_t gbuf[2] = {-1, -1};
-    request(u, 0, buf[0], gbuf[0]);
-    layernorm_tables_to_lds<B, kTwoStage, kSeda, kThreads>(lds, blob, gamma, beta, p);
+    uint32_t cur[B][16];
+    int32_t gcur[B];
+    request(u, cur, gcur);
+    layernorm_tables_to_lds<B, kTwoStage && !kWriteY, kSeda && !kWriteY, kThreads>(lds, blob, gamma, beta, p);
     const TileConsts K = make_tile_consts(lane, 0);
     FastParams sp = {};
     sp.codes = p.codes;
     sp.meta = p.meta;
     sp.n_blocks = p.n_blocks;
     const bool meta_aligned = (reinterpret_cast<uintptr_t>(p.meta) & 15u) == 0;
-    const double inv_channels = 1.0 / (double)p.cols;
-    const double eps = (double)p.eps;
+    const float n_channels = (float)p.cols;
 
     while (u < n_bundles) {
         uint32_t claim = 0;
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
         const uint32_t u_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
-        // ---- first pass: sums in double
-        double p1[B], p2[B];
+        uint32_t nxt[kPrefetch ? B : 1][16];
+        int32_t gnxt[kPrefetch ? B : 1];
+        if constexpr (kPrefetch) request(u_next, nxt, gnxt);   // the next bundle travels while this one is worked on
         bool ok[B];
 #pragma unroll
+        for (int j = 0; j < B; ++j) ok[j] = valid[j] && u * rw + rloc[j] < p.rows;
+        // ---- first pass: the sum of every chunk
+        float part[B];
+#pragma unroll
         for (int j = 0; j < B; ++j) {
-            constexpr int kSteps = 2 * B;
-            const int s = j;
-            (void)kSteps;
-            if (j + 1 < B) request(u, j + 1, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);
-            else request(u, 0, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);   // first chunk of the second pass
-            const uint32_t (&w)[16] = buf[s & 1];
-            ok[j] = valid[j] && u * rw + rloc[j] < p.rows;
-            double s1a = 0.0, s1b = 0.0, s2a = 0.0, s2b = 0.0;
+            float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const double d0 = (double)__uint_as_float(w[k] << 16);
-                const double d1 = (double)__uint_as_float(w[k] & 0xFFFF0000u);
-                s1a += d0; s1b += d1;
-                s2a = fma(d0, d0, s2a); s2b = fma(d1, d1, s2b);
+            for (int k = 0; k < 16; k += 2) {
+                a0 += __uint_as_float(cur[j][k] << 16);
+                a1 += __uint_as_float(cur[j][k] & 0xFFFF0000u);
+                a2 += __uint_as_float(cur[j][k + 1] << 16);
+                a3 += __uint_as_float(cur[j][k + 1] & 0xFFFF0000u);
             }
-            p1[j] = ok[j] ? s1a + s1b : 0.0;
-            p2[j] = ok[j] ? s2a + s2b : 0.0;
-            __builtin_amdgcn_sched_barrier(0);
+            part[j] = ok[j] ? (a0 + a1) + (a2 + a3) : 0.0f;
         }
-        // ---- per row: reduce over the wavefront, then 1/std and -mean/std as floats
-        float a[B], b[B];
+        // ---- per row: the sum over the wavefront's chunks of that row, then the mean
+        float mean[B];
 #pragma unroll
-        for (int j = 0; j < B; ++j) a[j] = b[j] = 0.0f;
+        for (int j = 0; j < B; ++j) mean[j] = 0.0f;
         for (uint32_t r = 0; r < rw; r += 2) {
-            double c1[2] = {0.0, 0.0}, c2[2] = {0.0, 0.0};
+            float c[2] = {0.0f, 0.0f};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
 #pragma unroll
-                for (int j = 0; j < B; ++j) {
-                    c1[h] += (valid[j] && rloc[j] == r + h) ? p1[j] : 0.0;
-                    c2[h] += (valid[j] && rloc[j] == r + h) ? p2[j] : 0.0;
-                }
+                for (int j = 0; j < B; ++j) c[h] += (valid[j] && rloc[j] == r + h) ? part[j] : 0.0f;
             }
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    c1[h] += __shfl_xor(c1[h], off);
-                    c2[h] += __shfl_xor(c2[h], off);
-                }
+                for (int h = 0; h < 2; ++h) c[h] += __shfl_xor(c[h], off);
             }
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const double mean = c1[h] * inv_channels;
-                double var = fma(-mean, mean, c2[h] * inv_channels);
-                var = var < 0.0 ? 0.0 : var;
-                const float ar = 1.0f / __builtin_sqrtf((float)(var + eps));
-                const float br = -(float)mean * ar;
+                const float m = c[h] / n_channels;
 #pragma unroll
                 for (int j = 0; j < B; ++j) {
-                    if (ok[j] && rloc[j] == r + h) { a[j] = ar; b[j] = br; }
+                    if (rloc[j] == r + h) mean[j] = m;
                 }
             }
         }
-        // ---- second pass: normalize, scale and shift, round to bf16, quantize, store
+        // ---- second pass: squared deviations from the mean
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 16; k += 2) {
+                const float d0 = __uint_as_float(cur[j][k] << 16) - mean[j], d1 = __uint_as_float(cur[j][k] & 0xFFFF0000u) - mean[j];
+                const float d2 = __uint_as_float(cur[j][k + 1] << 16) - mean[j], d3 = __uint_as_float(cur[j][k + 1] & 0xFFFF0000u) - mean[j];
+                a0 = __builtin_fmaf(d0, d0, a0);
+                a1 = __builtin_fmaf(d1, d1, a1);
+                a2 = __builtin_fmaf(d2, d2, a2);
+                a3 = __builtin_fmaf(d3, d3, a3);
+            }
+            part[j] = ok[j] ? (a0 + a1) + (a2 + a3) : 0.0f;
+        }
+        RowNorm rn[B];
+#pragma unroll
+        for (int j = 0; j < B; ++j) { rn[j].s = 1.0f; rn[j].nms = -mean[j]; rn[j].r = 0.0f; }
+        bool in_range = true;
+        for (uint32_t r = 0; r < rw; r += 2) {
+            float c[2] = {0.0f, 0.0f};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int j = 0; j < B; ++j) c[h] += (valid[j] && rloc[j] == r + h) ? part[j] : 0.0f;
+            }
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) c[h] += __shfl_xor(c[h], off);
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float v = c[h] / n_channels + p.eps;
+                // (the comparison is false for a NaN too; rows past the end of the bundle or the tensor have v = eps only)
+                in_range = in_range && ((v >= 0x1p-100f && v <= 0x1p+100f) || r + h >= rw || u * rw + r + h >= p.rows);
+                const float rstd = 1.0f / __builtin_sqrtf(v);
+#pragma unroll
+                for (int j = 0; j < B; ++j) {
+                    if (rloc[j] == r + h) rn[j].r = rstd;
+                }
+            }
+        }
+        if (__builtin_amdgcn_ballot_w64(!in_range) != 0) {
+            // some row of this bundle left the range of the fp32 sums: every row again, the plain way
+            for (uint32_t r = 0; r < rw; ++r) {
+                const uint32_t row = u * rw + r;
+                if (row >= p.rows) break;
+                const RowNorm v = layernorm_row_plain(x + (long long)row * row_stride, p.cols, p.eps);
+#pragma unroll
+                for (int j = 0; j < B; ++j) {
+                    if (rloc[j] == r) rn[j] = v;
+                }
+            }
+        }
+        // ---- third pass: normalize, scale and shift, round to bf16, quantize, store
 #pragma unroll
         for (int j = 0; j < B; ++j) {
             typedef float f32x2 __attribute__((ext_vector_type(2)));
             typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-            const int s = B + j;
-            const uint32_t excl = kSeda ? kLdsSeda + 32u * ((gbuf[s & 1] >= 0 && (uint32_t)gbuf[s & 1] < p.n_groups) ? (uint32_t)gbuf[s & 1] : p.n_groups) : 0u;
-            if (j + 1 < B) request(u, j + 1, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);
-            else request(u_next, 0, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);   // first chunk of the next bundle
-            const uint32_t (&w)[16] = buf[s & 1];
+            const uint32_t (&w)[16] = cur[j];
             const float4* g4 = reinterpret_cast<const float4*>(lds_gamma) + cb[j];
             const float4* b4 = reinterpret_cast<const float4*>(lds_beta) + cb[j];
             const uint32_t gb = u * per_bundle + lane + 64u * j;
@@ -233,22 +323,50 @@ __global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
                 const float4 g = g4[q * 64 * B], be = b4[q * 64 * B];
                 const float x0 = __uint_as_float(w[2 * q] << 16), x1 = __uint_as_float(w[2 * q] & 0xFFFF0000u);
                 const float x2 = __uint_as_float(w[2 * q + 1] << 16), x3 = __uint_as_float(w[2 * q + 1] & 0xFFFF0000u);
-                const f32x2 y01 = {__builtin_fmaf(__builtin_fmaf(x0, a[j], b[j]), g.x, be.x),
-                                   __builtin_fmaf(__builtin_fmaf(x1, a[j], b[j]), g.y, be.y)};
-                const f32x2 y23 = {__builtin_fmaf(__builtin_fmaf(x2, a[j], b[j]), g.z, be.z),
-                                   __builtin_fmaf(__builtin_fmaf(x3, a[j], b[j]), g.w, be.w)};
+                const float t0 = __builtin_fmaf(x0, rn[j].s, rn[j].nms) * rn[j].r, t1 = __builtin_fmaf(x1, rn[j].s, rn[j].nms) * rn[j].r;
+                const float t2 = __builtin_fmaf(x2, rn[j].s, rn[j].nms) * rn[j].r, t3 = __builtin_fmaf(x3, rn[j].s, rn[j].nms) * rn[j].r;
+                const f32x2 y01 = {__builtin_fmaf(t0, g.x, be.x), __builtin_fmaf(t1, g.y, be.y)};
+                const f32x2 y23 = {__builtin_fmaf(t2, g.z, be.z), __builtin_fmaf(t3, g.w, be.w)};
                 y[2 * q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(y01, bf16x2));
                 y[2 * q + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(y23, bf16x2));
             }
             __builtin_amdgcn_sched_barrier(0);
-            uint32_t stage[16];
-            uint32_t code[4], meta;
-            bool tile_special;
-            const uint32_t no_code[4] = {0, 0, 0, 0};
-            compute_tile<32, 8, kTwoStage, kSeda>(y, lds, K, nullptr, ok[j], excl, code, meta, no_code, 0u, tile_special, stage);
-            const bool al = meta_aligned && (((gb - lane) & 7u) == 0u);
-            store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, al, ok[j]);
+            if constexpr (kWriteY) {
+                if (ok[j]) {
+                    uint32_t v[16];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {   // NaNs as the quiet NaN 0x7FC0
+                        v[k] = y[k];
+                        if ((v[k] & 0x7FFFu) > 0x7F80u) v[k] = (v[k] & 0xFFFF0000u) | 0x7FC0u;
+                        if ((v[k] & 0x7FFF0000u) > 0x7F800000u) v[k] = (v[k] & 0xFFFFu) | 0x7FC00000u;
+                    }
+                    uint4* dst = reinterpret_cast<uint4*>(p.y_out + (size_t)gb * 32);
+                    dst[0] = make_uint4(v[0], v[1], v[2], v[3]);
+                    dst[1] = make_uint4(v[4], v[5], v[6], v[7]);
+                    dst[2] = make_uint4(v[8], v[9], v[10], v[11]);
+                    dst[3] = make_uint4(v[12], v[13], v[14], v[15]);
+                }
+            } else {
+                const uint32_t excl = kSeda ? kLdsSeda + 32u * ((gcur[j] >= 0 && (uint32_t)gcur[j] < p.n_groups) ? (uint32_t)gcur[j] : p.n_groups) : 0u;
+                uint32_t stage[16];
+                uint32_t code[4], meta;
+                bool tile_special;
+                const uint32_t no_code[4] = {0, 0, 0, 0};
+                compute_tile<32, 8, kTwoStage, kSeda>(y, lds, K, nullptr, ok[j], excl, code, meta, no_code, 0u, tile_special, stage);
+                const bool al = meta_aligned && (((gb - lane) & 7u) == 0u);
+                store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, al, ok[j]);
+            }
             __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (kPrefetch) {
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                gcur[j] = gnxt[j];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) cur[j][k] = nxt[j][k];
+            }
+        } else {
+            request(u_next, cur, gcur);
         }
         u = u_next;
         u_next = u_after;

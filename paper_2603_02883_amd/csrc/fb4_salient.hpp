@@ -195,87 +195,229 @@ __global__ __launch_bounds__(kSelectThreads) void select_salient_kernel(const fl
         if (chosen[t]) out[at++] = (int32_t)(frame * tokens + t);
 }
 
-// Sec. 3.4, per-frame part of the anchor / correlated-token extraction: every anchor (one per frame and tile)
-// marks the tokens of a window x window square around it whose raw attention score from the anchor -- Q[anchor] .
-// K[token], averaged over the heads -- exceeds a threshold; a token marked by several anchors belongs to the one
-// with the highest group number, an anchor to its own group.  Three small launches: fill with -1, mark (one
-// workgroup per anchor: 64 window slots x 4 shares of the heads, a maximum on the group number), anchors.
+// Sec. 3.4 ("Attention-Guided Semantic Relatedness Extraction"), the marking step: every anchor marks the tokens
+// of a window x window (x window_t frames) box around it whose raw attention score from the anchor -- Q[anchor] .
+// K[token], averaged over the heads -- exceeds a threshold.  The group of an anchor is the row-major number of the
+// spatial tile it lies in (the per-frame candidates of a tile share one sub-formatbook); a token marked by anchors
+// of several groups belongs to the highest group number (App. D: the subsequent anchor), an anchor to its own
+// group.  Three small launches: fill with -1, mark (one workgroup per anchor and frame of the window: 64 window
+// slots x 4 shares of the heads, a maximum on the group number), anchors.
+// Token (frame f, head h, token t) of Q / K sits at ((f * stride_f + h * stride_h) + t) * dim: factorized
+// attention [frames][heads][tokens][dim], 3D attention [heads][frames * tokens][dim].
 constexpr int kAssignThreads = 256;   // 64 window slots x 4 groups of heads
 
 __global__ __launch_bounds__(256) void seda_fill_kernel(int32_t* a, int32_t* b, uint32_t n)
 {
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    if (i < n) { a[i] = -1; b[i] = -1; }
+    if (i < n) {
+        a[i] = -1;
+        if (b) b[i] = -1;
+    }
 }
 
-__global__ __launch_bounds__(kAssignThreads) void seda_mark_kernel(const uint16_t* q, const uint16_t* k, uint32_t heads,
-                                                                   uint32_t grid_h, uint32_t grid_w, uint32_t dim,
-                                                                   const int32_t* anchors, uint32_t tiles, uint32_t window,
-                                                                   float threshold, int32_t* token_group, float* scores)
+__device__ __forceinline__ uint32_t tile_of(uint32_t token, uint32_t grid_w, uint32_t tile_h, uint32_t tile_w)
 {
-    __shared__ float partial[4][64];
-    const uint32_t tokens = grid_h * grid_w;
-    const uint32_t f = blockIdx.x / tiles, g = blockIdx.x - f * tiles;
-    const int64_t a = (int64_t)anchors[(size_t)f * tiles + g] - (int64_t)f * tokens;
-    const uint32_t w = threadIdx.x & 63u, hq = threadIdx.x >> 6;
-    // (no early exit: every thread reaches the barrier)
-    const bool slot = w < window * window;
-    const bool anchor_ok = a >= 0 && a < (int64_t)tokens;   // otherwise: not a token of this frame, marks nothing
-    const uint32_t ac = anchor_ok ? (uint32_t)a : 0u;
-    const int32_t ay = (int32_t)(ac / grid_w), ax = (int32_t)(ac % grid_w);
-    const int32_t y = ay + (int32_t)(w / window) - (int32_t)(window / 2), x = ax + (int32_t)(w % window) - (int32_t)(window / 2);
-    const bool inside = slot && anchor_ok && y >= 0 && y < (int32_t)grid_h && x >= 0 && x < (int32_t)grid_w;
-    const uint32_t t = inside ? (uint32_t)y * grid_w + (uint32_t)x : 0u;
-    float acc = 0.0f;
-    if (inside) {
-        float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // four chains: 16-byte pieces c, c + 1, c + 2, c + 3 (mod 4)
-        for (uint32_t h = hq; h < heads; h += 4) {   // this thread's share of the heads
-            const size_t base = ((size_t)f * heads + h) * tokens;
-            const uint4* qr = reinterpret_cast<const uint4*>(q + (base + ac) * dim);
-            const uint4* kr = reinterpret_cast<const uint4*>(k + (base + t) * dim);
-            const uint32_t n16 = dim / 8;
-            for (uint32_t c = 0; c < n16; c += 4) {
-                uint4 qa[4], kb[4];
+    const uint32_t y = token / grid_w, x = token - y * grid_w;
+    return (y / tile_h) * ((grid_w + tile_w - 1) / tile_w) + x / tile_w;
+}
+
+// Dot product of two bf16 rows of `dim` channels (a multiple of 8) in fp32: four chains over the 16-byte pieces
+// c, c + 1, c + 2, c + 3 (mod 4), added as (0 + 1) + (2 + 3).
+__device__ __forceinline__ float dot_bf16_rows(const uint16_t* qrow, const uint16_t* krow, uint32_t dim)
+{
+    const uint4* qr = reinterpret_cast<const uint4*>(qrow);
+    const uint4* kr = reinterpret_cast<const uint4*>(krow);
+    const uint32_t n16 = dim / 8;
+    float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (uint32_t c = 0; c < n16; c += 4) {
+        uint4 qa[4], kb[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {   // (a piece past the row's end re-reads the last one and is skipped)
-                    qa[j] = qr[min(c + j, n16 - 1u)];
-                    kb[j] = kr[min(c + j, n16 - 1u)];
-                }
+        for (int j = 0; j < 4; ++j) {   // (a piece past the row's end re-reads the last one and is skipped)
+            qa[j] = qr[min(c + j, n16 - 1u)];
+            kb[j] = kr[min(c + j, n16 - 1u)];
+        }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (c + j < n16) {
-                        const uint32_t qs[4] = {qa[j].x, qa[j].y, qa[j].z, qa[j].w}, ks[4] = {kb[j].x, kb[j].y, kb[j].z, kb[j].w};
+        for (int j = 0; j < 4; ++j) {
+            if (c + j < n16) {
+                const uint32_t qs[4] = {qa[j].x, qa[j].y, qa[j].z, qa[j].w}, ks[4] = {kb[j].x, kb[j].y, kb[j].z, kb[j].w};
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            part[j] = __builtin_fmaf(__uint_as_float(qs[i] << 16), __uint_as_float(ks[i] << 16), part[j]);
-                            part[j] = __builtin_fmaf(__uint_as_float(qs[i] & 0xFFFF0000u), __uint_as_float(ks[i] & 0xFFFF0000u), part[j]);
-                        }
-                    }
+                for (int i = 0; i < 4; ++i) {
+                    part[j] = __builtin_fmaf(__uint_as_float(qs[i] << 16), __uint_as_float(ks[i] << 16), part[j]);
+                    part[j] = __builtin_fmaf(__uint_as_float(qs[i] & 0xFFFF0000u), __uint_as_float(ks[i] & 0xFFFF0000u), part[j]);
                 }
             }
         }
-        acc = (part[0] + part[1]) + (part[2] + part[3]);
+    }
+    return (part[0] + part[1]) + (part[2] + part[3]);
+}
+
+struct AssignParams {
+    uint32_t frames, heads, grid_h, grid_w, dim, tile_h, tile_w, window, window_t;
+    uint64_t stride_f, stride_h;   // in tokens
+    float threshold;
+};
+
+__global__ __launch_bounds__(kAssignThreads) void seda_mark_kernel(const uint16_t* q, const uint16_t* k,
+                                                                   const int32_t* anchors, AssignParams p,
+                                                                   int32_t* token_group, float* scores)
+{
+    __shared__ float partial[4][64];
+    const uint32_t tokens = p.grid_h * p.grid_w;
+    const uint32_t i = blockIdx.x, wt = blockIdx.y;
+    const int64_t row = anchors[i];
+    const uint32_t w = threadIdx.x & 63u, hq = threadIdx.x >> 6;
+    // (no early exit: every thread reaches the barrier)
+    const bool slot = w < p.window * p.window;
+    const bool anchor_ok = row >= 0 && row < (int64_t)p.frames * tokens;   // otherwise: no token of the clip, marks nothing
+    const uint32_t rc = anchor_ok ? (uint32_t)row : 0u;
+    const uint32_t fa = rc / tokens, ac = rc - fa * tokens;
+    const uint32_t g = tile_of(ac, p.grid_w, p.tile_h, p.tile_w);
+    const int32_t ay = (int32_t)(ac / p.grid_w), ax = (int32_t)(ac % p.grid_w);
+    const int32_t f = (int32_t)fa + (int32_t)wt - (int32_t)(p.window_t / 2);
+    const int32_t y = ay + (int32_t)(w / p.window) - (int32_t)(p.window / 2), x = ax + (int32_t)(w % p.window) - (int32_t)(p.window / 2);
+    const bool inside = slot && anchor_ok && f >= 0 && f < (int32_t)p.frames && y >= 0 && y < (int32_t)p.grid_h && x >= 0 &&
+                        x < (int32_t)p.grid_w;
+    const uint32_t t = inside ? (uint32_t)y * p.grid_w + (uint32_t)x : 0u;
+    const uint32_t fc = inside ? (uint32_t)f : 0u;
+    float acc = 0.0f;
+    if (inside) {
+        for (uint32_t h = hq; h < p.heads; h += 4)   // this thread's share of the heads
+            acc += dot_bf16_rows(q + (fa * p.stride_f + h * p.stride_h + ac) * p.dim,
+                                 k + (fc * p.stride_f + h * p.stride_h + t) * p.dim, p.dim);
     }
     partial[hq][w] = acc;
     __syncthreads();
     if (hq == 0 && slot) {
-        float* out = scores ? scores + ((size_t)f * tiles + g) * window * window + w : nullptr;
-        const float sc = (partial[0][w] + partial[1][w] + partial[2][w] + partial[3][w]) / (float)heads;   // fixed order
+        const size_t per = (size_t)p.window_t * p.window * p.window;
+        float* out = scores ? scores + (size_t)i * per + (size_t)wt * p.window * p.window + w : nullptr;
+        const float sc = (partial[0][w] + partial[1][w] + partial[2][w] + partial[3][w]) / (float)p.heads;   // fixed order
         if (out) *out = inside ? sc : __builtin_nanf("");
-        if (inside && sc > threshold) atomicMax(token_group + (size_t)f * tokens + t, (int32_t)g);
+        if (inside && sc > p.threshold) atomicMax(token_group + (size_t)fc * tokens + t, (int32_t)g);
     }
 }
 
-__global__ __launch_bounds__(256) void seda_anchor_kernel(const int32_t* anchors, uint32_t frames, uint32_t tiles,
-                                                          uint32_t tokens, int32_t* token_group, int32_t* anchor_group)
+__global__ __launch_bounds__(256) void seda_anchor_kernel(const int32_t* anchors, uint32_t n, uint32_t frames,
+                                                          uint32_t grid_h, uint32_t grid_w, uint32_t tile_h, uint32_t tile_w,
+                                                          int32_t* token_group, int32_t* anchor_group)
 {
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    if (i >= frames * tiles) return;
-    const uint32_t f = i / tiles, g = i - f * tiles;
+    if (i >= n) return;
+    const uint32_t tokens = grid_h * grid_w;
     const int64_t row = anchors[i];
-    if (row < (int64_t)f * tokens || row >= (int64_t)(f + 1) * tokens) return;
-    token_group[row] = (int32_t)g;
-    anchor_group[row] = (int32_t)g;
+    if (row < 0 || row >= (int64_t)frames * tokens) return;
+    const int32_t g = (int32_t)tile_of((uint32_t)row % tokens, grid_w, tile_h, tile_w);
+    token_group[row] = g;    // (two entries naming one row write the same value)
+    anchor_group[row] = g;
+}
+
+// Sec. 3.4, factorized attention, step 2: one workgroup per spatial tile.  Per frame the tile's candidate (the
+// first entry of the frame's list that lies in this tile of this frame) and its temporal mean score averaged over
+// the heads (in double, head by head); the main anchor is the best of them (earliest frame on ties, a NaN never
+// wins); a frame stays if it is the main anchor's or if the raw temporal score from the main anchor to it --
+// Qt[p*][h][f*] . Kt[p*][h][f], head mean in fp32 -- exceeds the threshold.  `kept` was filled with -1 before.
+constexpr int kMainThreads = 256;
+constexpr uint32_t kMainMaxFrames = 1024;
+
+__global__ __launch_bounds__(kMainThreads) void seda_main_anchor_kernel(
+    const float* temporal_scores, const uint16_t* qt, const uint16_t* kt, uint32_t frames, uint32_t heads, uint32_t grid_h,
+    uint32_t grid_w, uint32_t dim, const int32_t* cand, uint32_t n_per_frame, uint32_t tile_h, uint32_t tile_w,
+    float prune_threshold, int32_t* main_anchor, int32_t* kept, float* prune_scores)
+{
+    __shared__ double score[kMainMaxFrames];
+    __shared__ int32_t slot[kMainMaxFrames];
+    __shared__ int32_t best_frame;
+    const uint32_t tokens = grid_h * grid_w, tile = blockIdx.x, tiles = gridDim.x;
+    for (uint32_t f = threadIdx.x; f < frames; f += kMainThreads) {
+        int32_t found = -1;
+        for (uint32_t j = 0; j < n_per_frame; ++j) {
+            const int64_t row = cand[(size_t)f * n_per_frame + j];
+            if (row >= (int64_t)f * tokens && row < (int64_t)(f + 1) * tokens &&
+                tile_of((uint32_t)(row - (int64_t)f * tokens), grid_w, tile_h, tile_w) == tile) {
+                found = (int32_t)j;
+                break;
+            }
+        }
+        slot[f] = found;
+        double v = 0.0;
+        if (found >= 0) {
+            const uint32_t pos = (uint32_t)(cand[(size_t)f * n_per_frame + found] - (int32_t)(f * tokens));
+            for (uint32_t h = 0; h < heads; ++h) v += (double)temporal_scores[((size_t)pos * heads + h) * frames + f];
+            v /= (double)heads;
+            if (v != v) v = -__builtin_inf();
+        }
+        score[f] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int32_t bf = -1;
+        double bv = 0.0;
+        for (uint32_t f = 0; f < frames; ++f) {
+            if (slot[f] < 0) continue;
+            if (bf < 0 || score[f] > bv) { bf = (int32_t)f; bv = score[f]; }
+        }
+        best_frame = bf;
+        main_anchor[tile] = bf < 0 ? -1 : cand[(size_t)bf * n_per_frame + slot[bf]];
+    }
+    __syncthreads();
+    const int32_t bf = best_frame;
+    for (uint32_t f = threadIdx.x; f < frames; f += kMainThreads) {
+        float sc = __builtin_nanf("");
+        if (bf >= 0 && slot[f] >= 0) {
+            const uint32_t pos = (uint32_t)(cand[(size_t)bf * n_per_frame + slot[bf]] - (int32_t)((uint32_t)bf * tokens));
+            float acc = 0.0f;
+            for (uint32_t h = 0; h < heads; ++h) {
+                const size_t base = ((size_t)pos * heads + h) * frames;
+                acc += dot_bf16_rows(qt + (base + (uint32_t)bf) * dim, kt + (base + f) * dim, dim);
+            }
+            sc = acc / (float)heads;
+            if ((int32_t)f == bf || sc > prune_threshold)
+                kept[(size_t)f * n_per_frame + slot[f]] = cand[(size_t)f * n_per_frame + slot[f]];
+        }
+        if (prune_scores) prune_scores[(size_t)f * tiles + tile] = sc;
+    }
+}
+
+// Sec. 3.4, 3D attention: the main anchor of a spatial tile is the best token among its tile_h x tile_w x frames
+// tokens by the head mean (double, head by head) of the clip-wide scores [heads][frames * tokens]; the lowest row
+// on ties, a NaN never wins.  One workgroup per tile.
+__global__ __launch_bounds__(kMainThreads) void seda_main_anchor_3d_kernel(const float* scores, uint32_t frames, uint32_t heads,
+                                                                            uint32_t grid_h, uint32_t grid_w, uint32_t tile_h,
+                                                                            uint32_t tile_w, int32_t* anchors)
+{
+    __shared__ double best_v[kMainThreads];
+    __shared__ uint32_t best_row[kMainThreads];
+    const uint32_t tokens = grid_h * grid_w, tile = blockIdx.x;
+    const uint32_t tw = (grid_w + tile_w - 1) / tile_w;
+    const uint32_t y0 = (tile / tw) * tile_h, x0 = (tile % tw) * tile_w;
+    const uint32_t hh = min(tile_h, grid_h - y0), ww = min(tile_w, grid_w - x0);
+    const uint32_t n = frames * hh * ww;
+    const size_t total = (size_t)frames * tokens;
+    double bv = 0.0;
+    uint32_t br = 0xFFFFFFFFu;
+    for (uint32_t i = threadIdx.x; i < n; i += kMainThreads) {   // ascending rows per thread
+        const uint32_t f = i / (hh * ww), r = i - f * (hh * ww);
+        const uint32_t row = f * tokens + (y0 + r / ww) * grid_w + x0 + r % ww;
+        double v = 0.0;
+        for (uint32_t h = 0; h < heads; ++h) v += (double)scores[(size_t)h * total + row];
+        v /= (double)heads;
+        if (v != v) v = -__builtin_inf();
+        if (br == 0xFFFFFFFFu || v > bv) { br = row; bv = v; }
+    }
+    best_v[threadIdx.x] = bv;
+    best_row[threadIdx.x] = br;
+    __syncthreads();
+    for (uint32_t s = kMainThreads / 2; s > 0; s >>= 1) {
+        if (threadIdx.x < s) {
+            const double ov = best_v[threadIdx.x + s];
+            const uint32_t orow = best_row[threadIdx.x + s];
+            const double mv = best_v[threadIdx.x];
+            const uint32_t mrow = best_row[threadIdx.x];
+            const bool take = orow != 0xFFFFFFFFu && (mrow == 0xFFFFFFFFu || ov > mv || (ov == mv && orow < mrow));
+            if (take) { best_v[threadIdx.x] = ov; best_row[threadIdx.x] = orow; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) anchors[tile] = (int32_t)best_row[0];
 }
 
 }  // namespace fb4
