@@ -505,10 +505,14 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
         meta = 0;
         if (stage) {
             // the elements exist in registers only (a fused producer made them): the plain routine gets them
-            // through this lane's private memory, NaNs as the canonical quiet NaN
+            // through this lane's private memory, NaNs as the canonical quiet NaN.  (The zero below is opaque to
+            // the optimizer: without it the 160 instructions of this loop are hoisted out of the rare branch
+            // and run for every tile.)
+            uint32_t zero;
+            asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                uint32_t v = w[k];
+                uint32_t v = w[k] | zero;
                 if ((v & 0x7FFFu) > 0x7F80u) v = (v & 0xFFFF0000u) | 0x7FC0u;
                 if ((v & 0x7FFF0000u) > 0x7F800000u) v = (v & 0xFFFFu) | 0x7FC00000u;
                 stage[k] = v;

@@ -47,9 +47,8 @@ struct LayerNormParams {
     uint16_t* y_out;              // kWriteY only: [rows][cols] bf16, the producer's result
 };
 
-constexpr int kLnThreads = 512;
-// chunks per lane up to which the next bundle is requested while this one is worked on (two bundles in registers)
-constexpr int kLnPrefetchChunks = 3;
+// threads per workgroup (one workgroup per CU)
+constexpr int ln_threads(int chunks_per_lane) { return chunks_per_lane <= 4 ? 768 : 512; }
 constexpr int kLnMaxChunksPerLane = 6;
 constexpr int kLdsLnTables = lds_fast_bytes(false, false, false);
 
@@ -91,6 +90,26 @@ __device__ __forceinline__ void layernorm_tables_to_lds(uint8_t* lds, const uint
         dst[1] = make_uint4(l1.x | (h1.x << 4), l1.y | (h1.y << 4), l1.z | (h1.z << 4), l1.w | (h1.w << 4));
     }
     __syncthreads();
+}
+
+// Sum over the 64 lanes of a wavefront, the same value in every lane of the result (it comes back through a
+// scalar register).  Data-parallel-primitive moves only: inside rows of 16 lanes by quad permutes and mirrors,
+// then row 0 -> 1 and 2 -> 3, then rows 0-1 -> 2-3; lane 63 holds the total.  A fixed order: the same input
+// always gives the same sum.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ float dpp_mov(float x)   // a lane outside the row mask receives 0
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kCtrl, kRowMask, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_mov<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141, 0xF>(v);   // row_half_mirror
+    v += dpp_mov<0x140, 0xF>(v);   // row_mirror: every lane now holds its row's sum
+    v += dpp_mov<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_mov<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // What the normalization of a row needs: t = fma(x, s, nms) * r is (x - mean) * rstd, with a power of two s
@@ -146,16 +165,19 @@ __device__ __noinline__ RowNorm layernorm_row_plain(const uint16_t* xrow, uint32
 // B: chunks per lane (the host picks it from the row length); gamma / beta may be null (1 / 0).
 // kWriteY: the producer alone -- writes the normalized bf16 tensor to p.y_out and nothing else (for checking the
 // producer against its definition; production launches never use it).
-template <int B, bool kTwoStage, bool kSeda, bool kWriteY>
-__global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
+// One chunk per lane is in registers at a time: a first walk over the bundle's chunks forms the sums, a last walk
+// reads the chunks again (from the L2 cache: the wavefront has just read them) and normalizes and quantizes
+// them; two chunk buffers alternate, the chunk of the next step is always in flight.  (Holding the bundle in
+// registers instead reads x once but leaves room for 8 wavefronts per CU only, or spills: 42-62 us on a
+// 16384x3072 tensor.)
+template <int B, bool kTwoStage, bool kSeda, bool kWriteY, int kThreads = ln_threads(B)>
+__global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
     const uint8_t* blob, const uint16_t* x, uint32_t n_bundles, uint32_t rw, uint32_t nb, uint32_t n_workgroups,
     long long row_stride, const float* gamma, const float* beta, LayerNormParams p)
 {
-    constexpr int kThreads = kLnThreads;
     constexpr int kWaves = kThreads / 64;
     constexpr int kGbFloats = 2048 * B;
     constexpr int kLdsSeda = kLdsLnTables + 2 * kGbFloats * 4;
-    constexpr bool kPrefetch = B <= kLnPrefetchChunks;
     __shared__ __align__(16) uint8_t lds[kLdsSeda + (kSeda ? (kMaxFusedProducerGroups + 1) * 32 : 0)];
     __shared__ uint32_t wg_next;
     float* lds_gamma = reinterpret_cast<float*>(lds + kLdsLnTables);
@@ -175,26 +197,25 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
         rloc[j] = ic / nb;
         cb[j] = ic - rloc[j] * nb;
     }
-    // Requests all of this lane's chunks of bundle u (a bundle or row past the end reads the last one; its
-    // results are never stored).
-    auto request = [&](uint32_t u, uint32_t (&q)[B][16], int32_t (&grp)[B]) {
-#pragma unroll
-        for (int j = 0; j < B; ++j) {
-            const uint32_t row = min(min(u, n_bundles - 1u) * rw + rloc[j], p.rows - 1u);
-            grp[j] = kSeda ? p.token_group[row] : -1;
-            const uint4* px = reinterpret_cast<const uint4*>(x + (long long)row * row_stride + (long long)cb[j] * 32);
-            const uint4 q0 = px[0], q1 = px[1], q2 = px[2], q3 = px[3];
-            q[j][0] = q0.x; q[j][1] = q0.y; q[j][2] = q0.z; q[j][3] = q0.w; q[j][4] = q1.x; q[j][5] = q1.y; q[j][6] = q1.z; q[j][7] = q1.w;
-            q[j][8] = q2.x; q[j][9] = q2.y; q[j][10] = q2.z; q[j][11] = q2.w; q[j][12] = q3.x; q[j][13] = q3.y; q[j][14] = q3.z; q[j][15] = q3.w;
-        }
+    // Requests this lane's chunk j of bundle u (a bundle or row past the end reads the last one; its results
+    // are never stored).
+    auto request = [&](uint32_t u, int j, uint32_t (&q)[16], int32_t& grp) {
+        const uint32_t row = min(min(u, n_bundles - 1u) * rw + rloc[j], p.rows - 1u);
+        if (kSeda) grp = p.token_group[row];
+        const uint4* px = reinterpret_cast<const uint4*>(x + (long long)row * row_stride + (long long)cb[j] * 32);
+        const uint4 q0 = px[0], q1 = px[1], q2 = px[2], q3 = px[3];
+        q[0] = q0.x; q[1] = q0.y; q[2] = q0.z; q[3] = q0.w; q[4] = q1.x; q[5] = q1.y; q[6] = q1.z; q[7] = q1.w;
+        q[8] = q2.x; q[9] = q2.y; q[10] = q2.z; q[11] = q2.w; q[12] = q3.x; q[13] = q3.y; q[14] = q3.z; q[15] = q3.w;
     };
 
     uint32_t u = blockIdx.x + wave * W;
     uint32_t u_next = blockIdx.x + (kWaves + wave) * W;
     if (threadIdx.x == 0) wg_next = 2 * kWaves;
-    uint32_t cur[B][16];
-    int32_t gcur[B];
-    request(u, cur, gcur);
+    // Two chunk buffers used in turn: step s of a bundle works on buf[s & 1] while the chunk of step s + 1 is on
+    // its way into the other one.  A bundle takes 2 B steps (B chunks summed, B chunks normalized and quantized).
+    uint32_t buf[2][16];
+    int32_t gbuf[2] = {-1, -1};
+    request(u, 0, buf[0], gbuf[0]);
     layernorm_tables_to_lds<B, kTwoStage && !kWriteY, kSeda && !kWriteY, kThreads>(lds, blob, gamma, beta, p);
     const TileConsts K = make_tile_consts(lane, 0);
     FastParams sp = {};
@@ -203,100 +224,109 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
     sp.n_blocks = p.n_blocks;
     const bool meta_aligned = (reinterpret_cast<uintptr_t>(p.meta) & 15u) == 0;
     const float n_channels = (float)p.cols;
+    const float inv_channels = 1.0f / n_channels;
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
     while (u < n_bundles) {
         uint32_t claim = 0;
         if (lane == 0) claim = atomicAdd(&wg_next, 1u);
         const uint32_t u_after = blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(claim) * W;
-        uint32_t nxt[kPrefetch ? B : 1][16];
-        int32_t gnxt[kPrefetch ? B : 1];
-        if constexpr (kPrefetch) request(u_next, nxt, gnxt);   // the next bundle travels while this one is worked on
         bool ok[B];
 #pragma unroll
         for (int j = 0; j < B; ++j) ok[j] = valid[j] && u * rw + rloc[j] < p.rows;
-        // ---- first pass: the sum of every chunk
-        float part[B];
+        // ---- first walk: per chunk the sum (plain fp32 additions) and the sum of squares (one two-element bf16
+        // dot product with fp32 accumulation per register, the register with itself)
+        float part[B], part2[B];
 #pragma unroll
         for (int j = 0; j < B; ++j) {
-            float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+            const int s = j;
+            request(u, (j + 1) % B, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);   // (after the last chunk: the first again)
+            const uint32_t (&w)[16] = buf[s & 1];
+            float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f, q0 = 0.0f, q1 = 0.0f;
 #pragma unroll
             for (int k = 0; k < 16; k += 2) {
-                a0 += __uint_as_float(cur[j][k] << 16);
-                a1 += __uint_as_float(cur[j][k] & 0xFFFF0000u);
-                a2 += __uint_as_float(cur[j][k + 1] << 16);
-                a3 += __uint_as_float(cur[j][k + 1] & 0xFFFF0000u);
+                a0 += __uint_as_float(w[k] << 16);
+                a1 += __uint_as_float(w[k] & 0xFFFF0000u);
+                a2 += __uint_as_float(w[k + 1] << 16);
+                a3 += __uint_as_float(w[k + 1] & 0xFFFF0000u);
+                q0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[k]), __builtin_bit_cast(bf16x2, w[k]), q0, false);
+                q1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[k + 1]), __builtin_bit_cast(bf16x2, w[k + 1]), q1, false);
             }
             part[j] = ok[j] ? (a0 + a1) + (a2 + a3) : 0.0f;
+            part2[j] = ok[j] ? q0 + q1 : 0.0f;
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // ---- per row: the sum over the wavefront's chunks of that row, then the mean
+        // ---- per row: both sums over the wavefront's chunks of that row; mean, and the variance as the mean
+        // square minus the squared mean -- kept only where that difference is well conditioned
         float mean[B];
-#pragma unroll
-        for (int j = 0; j < B; ++j) mean[j] = 0.0f;
-        for (uint32_t r = 0; r < rw; r += 2) {
-            float c[2] = {0.0f, 0.0f};
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-#pragma unroll
-                for (int j = 0; j < B; ++j) c[h] += (valid[j] && rloc[j] == r + h) ? part[j] : 0.0f;
-            }
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h) c[h] += __shfl_xor(c[h], off);
-            }
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const float m = c[h] / n_channels;
-#pragma unroll
-                for (int j = 0; j < B; ++j) {
-                    if (rloc[j] == r + h) mean[j] = m;
-                }
-            }
-        }
-        // ---- second pass: squared deviations from the mean
-#pragma unroll
-        for (int j = 0; j < B; ++j) {
-            float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
-#pragma unroll
-            for (int k = 0; k < 16; k += 2) {
-                const float d0 = __uint_as_float(cur[j][k] << 16) - mean[j], d1 = __uint_as_float(cur[j][k] & 0xFFFF0000u) - mean[j];
-                const float d2 = __uint_as_float(cur[j][k + 1] << 16) - mean[j], d3 = __uint_as_float(cur[j][k + 1] & 0xFFFF0000u) - mean[j];
-                a0 = __builtin_fmaf(d0, d0, a0);
-                a1 = __builtin_fmaf(d1, d1, a1);
-                a2 = __builtin_fmaf(d2, d2, a2);
-                a3 = __builtin_fmaf(d3, d3, a3);
-            }
-            part[j] = ok[j] ? (a0 + a1) + (a2 + a3) : 0.0f;
-        }
         RowNorm rn[B];
 #pragma unroll
-        for (int j = 0; j < B; ++j) { rn[j].s = 1.0f; rn[j].nms = -mean[j]; rn[j].r = 0.0f; }
-        bool in_range = true;
-        for (uint32_t r = 0; r < rw; r += 2) {
-            float c[2] = {0.0f, 0.0f};
+        for (int j = 0; j < B; ++j) { mean[j] = 0.0f; rn[j].s = 1.0f; rn[j].nms = 0.0f; rn[j].r = 0.0f; }
+        bool centered = false, in_range = true;   // wave-uniform
+        for (uint32_t r = 0; r < rw; ++r) {
+            float c1 = 0.0f, c2 = 0.0f;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-#pragma unroll
-                for (int j = 0; j < B; ++j) c[h] += (valid[j] && rloc[j] == r + h) ? part[j] : 0.0f;
+            for (int j = 0; j < B; ++j) {
+                c1 += (valid[j] && rloc[j] == r) ? part[j] : 0.0f;
+                c2 += (valid[j] && rloc[j] == r) ? part2[j] : 0.0f;
             }
+            c1 = wave_sum(c1);
+            c2 = wave_sum(c2);
+            const float m = c1 / n_channels;   // a true division: the mean of a constant row is that constant
+            const float msq = c2 * inv_channels;
+            const float var = msq - m * m;
+            // the subtraction loses log2(msq / var) bits: fine while the squared mean is at most the variance
+            centered = centered || !(var >= 0.5f * msq);
+            const float v = var + p.eps;
+            in_range = in_range && ((v >= 0x1p-100f && v <= 0x1p+100f) || u * rw + r >= p.rows);
+            const float rstd = __builtin_amdgcn_rsqf(v);
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h) c[h] += __shfl_xor(c[h], off);
+            for (int j = 0; j < B; ++j) {
+                if (rloc[j] == r) { mean[j] = m; rn[j].nms = -m; rn[j].r = rstd; }
             }
+        }
+        // (after B steps the bundle's first chunk is on its way into buf[B & 1])
+        if (centered) {
+            // ---- another walk (rows whose mean is not small against their spread): squared deviations from the mean
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const float v = c[h] / n_channels + p.eps;
-                // (the comparison is false for a NaN too; rows past the end of the bundle or the tensor have v = eps only)
-                in_range = in_range && ((v >= 0x1p-100f && v <= 0x1p+100f) || r + h >= rw || u * rw + r + h >= p.rows);
-                const float rstd = 1.0f / __builtin_sqrtf(v);
+            for (int j = 0; j < B; ++j) {
+                const int s = B + j;
+                // keeps the buffer parity of the path that skips this walk: with an odd number of chunks the first
+                // chunk comes back into the buffer this step works on, requested after its arithmetic
+                const bool late = (B & 1) && j == B - 1;
+                if (!late) request(u, (j + 1) % B, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);
+                const uint32_t (&w)[16] = buf[s & 1];
+                float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+#pragma unroll
+                for (int k = 0; k < 16; k += 2) {
+                    const float d0 = __uint_as_float(w[k] << 16) - mean[j], d1 = __uint_as_float(w[k] & 0xFFFF0000u) - mean[j];
+                    const float d2 = __uint_as_float(w[k + 1] << 16) - mean[j], d3 = __uint_as_float(w[k + 1] & 0xFFFF0000u) - mean[j];
+                    a0 = __builtin_fmaf(d0, d0, a0);
+                    a1 = __builtin_fmaf(d1, d1, a1);
+                    a2 = __builtin_fmaf(d2, d2, a2);
+                    a3 = __builtin_fmaf(d3, d3, a3);
+                }
+                part2[j] = ok[j] ? (a0 + a1) + (a2 + a3) : 0.0f;
+                __builtin_amdgcn_sched_barrier(0);
+                if (late) request(u, 0, buf[s & 1], gbuf[s & 1]);
+            }
+            in_range = true;
+            for (uint32_t r = 0; r < rw; ++r) {
+                float c2 = 0.0f;
+#pragma unroll
+                for (int j = 0; j < B; ++j) c2 += (valid[j] && rloc[j] == r) ? part2[j] : 0.0f;
+                c2 = wave_sum(c2);
+                const float v = c2 * inv_channels + p.eps;
+                // (the comparison is false for a NaN too; a row past the end of the tensor has v = eps only)
+                in_range = in_range && ((v >= 0x1p-100f && v <= 0x1p+100f) || u * rw + r >= p.rows);
+                const float rstd = __builtin_amdgcn_rsqf(v);
 #pragma unroll
                 for (int j = 0; j < B; ++j) {
-                    if (rloc[j] == r + h) rn[j].r = rstd;
+                    if (rloc[j] == r) rn[j].r = rstd;
                 }
             }
         }
-        if (__builtin_amdgcn_ballot_w64(!in_range) != 0) {
+        if (!in_range) {
             // some row of this bundle left the range of the fp32 sums: every row again, the plain way
             for (uint32_t r = 0; r < rw; ++r) {
                 const uint32_t row = u * rw + r;
@@ -308,12 +338,15 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
                 }
             }
         }
-        // ---- third pass: normalize, scale and shift, round to bf16, quantize, store
+        // ---- last walk: normalize, scale and shift, round to bf16, quantize, store
 #pragma unroll
         for (int j = 0; j < B; ++j) {
             typedef float f32x2 __attribute__((ext_vector_type(2)));
-            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-            const uint32_t (&w)[16] = cur[j];
+            const int s = B + j;
+            const int32_t grp = gbuf[s & 1];
+            if (j + 1 < B) request(u, j + 1, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);
+            else request(u_next, 0, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);   // first chunk of the next bundle
+            const uint32_t (&w)[16] = buf[s & 1];
             const float4* g4 = reinterpret_cast<const float4*>(lds_gamma) + cb[j];
             const float4* b4 = reinterpret_cast<const float4*>(lds_beta) + cb[j];
             const uint32_t gb = u * per_bundle + lane + 64u * j;
@@ -347,7 +380,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
                     dst[3] = make_uint4(v[12], v[13], v[14], v[15]);
                 }
             } else {
-                const uint32_t excl = kSeda ? kLdsSeda + 32u * ((gcur[j] >= 0 && (uint32_t)gcur[j] < p.n_groups) ? (uint32_t)gcur[j] : p.n_groups) : 0u;
+                const uint32_t excl = kSeda ? kLdsSeda + 32u * ((grp >= 0 && (uint32_t)grp < p.n_groups) ? (uint32_t)grp : p.n_groups) : 0u;
                 uint32_t stage[16];
                 uint32_t code[4], meta;
                 bool tile_special;
@@ -357,16 +390,6 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(
                 store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, al, ok[j]);
             }
             __builtin_amdgcn_sched_barrier(0);
-        }
-        if constexpr (kPrefetch) {
-#pragma unroll
-            for (int j = 0; j < B; ++j) {
-                gcur[j] = gnxt[j];
-#pragma unroll
-                for (int k = 0; k < 16; ++k) cur[j][k] = nxt[j][k];
-            }
-        } else {
-            request(u_next, cur, gcur);
         }
         u = u_next;
         u_next = u_after;
