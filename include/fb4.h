@@ -278,8 +278,9 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
  * range of fp32 sums (an Inf or NaN, squares beyond 2^100, var + eps below
  * 2^-100) are evaluated in double instead.  x is read as plain IEEE bf16 (a
  * row with an Inf or NaN normalizes to NaN throughout).
- *   opts        block 32, FB4_SEL_LUT with 8 groups (FB4_FLAG_TWO_STAGE allowed);
- *               anything else FB4_ERR_UNSUPPORTED
+ *   opts        FB4_SEL_LUT with 8 or 16 groups, block 32 or 16 (Sec. 4.1),
+ *               FB4_FLAG_TWO_STAGE allowed; the exhaustive selector and 32 groups
+ *               FB4_ERR_UNSUPPORTED
  *   cols        a multiple of 32, at most 12288 (FB4_ERR_UNSUPPORTED otherwise)
  *   gamma,beta  device, float [cols]; NULL = all ones / all zeros
  *   eps         >= 0 (FB4_ERR_INVALID_ARG otherwise)
@@ -287,7 +288,8 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
  *               Sec. 3.4, as in fb4_quantize_seda (the paper applies SeDA to
  *               mlp.fc1, whose input this is); all NULL / 0 = full formatbook;
  *               at most 255 groups (FB4_ERR_UNSUPPORTED beyond)
- *   codes       device, 16-byte aligned (FB4_ERR_UNSUPPORTED otherwise)
+ *   codes       device, 16-byte aligned; meta 4-byte aligned with block 16
+ *               (FB4_ERR_UNSUPPORTED otherwise)
  *   y_out       NULL in production.  For checking the producer: device, bf16
  *               [rows][cols], contiguous, 16-byte aligned; a second launch of
  *               the producer alone writes the normalized tensor there
@@ -308,13 +310,15 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
  *   approximate  0: x * Phi(x) = 0.5 x erfc(-x / sqrt 2)
  *                1: the tanh form 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))
  *                anything else FB4_ERR_INVALID_ARG
- *   opts         block 32, FB4_SEL_LUT with 8 groups (FB4_FLAG_TWO_STAGE allowed);
- *                anything else FB4_ERR_UNSUPPORTED
+ *   opts         FB4_SEL_LUT with 8 or 16 groups, block 32 or 16 (Sec. 4.1),
+ *                FB4_FLAG_TWO_STAGE allowed; the exhaustive selector and 32 groups
+ *                FB4_ERR_UNSUPPORTED; cols a multiple of 32
  *   token_group, sub_formatbooks, n_groups
  *                Sec. 3.4, as in fb4_quantize_seda (the paper applies SeDA to
  *                mlp.fc2, whose input this is); all NULL / 0 = full formatbook;
  *                at most 255 groups (FB4_ERR_UNSUPPORTED beyond)
- *   codes        device, 16-byte aligned (FB4_ERR_UNSUPPORTED otherwise)
+ *   codes        device, 16-byte aligned; meta 4-byte aligned with block 16
+ *                (FB4_ERR_UNSUPPORTED otherwise)
  */
 int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows,
                       int64_t cols, int64_t row_stride, int approximate, const int32_t* token_group,

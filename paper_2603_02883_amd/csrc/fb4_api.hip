@@ -1,60 +1,27 @@
-// C ABI of the FB4 quantizer library: argument checking, lookup-table
-// handle management and kernel launches.  Declarations and the contract of
+// C ABI of the FB4 quantizer library, first part: lookup-table handle management, the quantizing, decoding,
+// repacking and profiling entry points (the producer-fused ones are in fb4_producers.hip, the attention-guided
+// ones in fb4_attention.hip).  Declarations and the contract of
 // every entry point are in include/fb4.h.
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
 #include <new>
 
-#include "../../include/fb4.h"
+#include "fb4_common.hpp"
 #include "fb4_dequant_fast.hpp"
 #include "fb4_fast.hpp"
-#include "fb4_gelu.hpp"
 #include "fb4_kernels.hpp"
-#include "fb4_layernorm.hpp"
 #include "fb4_profile.hpp"
 #include "fb4_repack.hpp"
-#include "fb4_salient.hpp"
-#include "fb4_tables.hpp"
 
-struct fb4_luts {
-    uint8_t host_blob[fb4::kBlobBytes];
-    uint8_t* dev_blob;
-    int n_dialects;
-    int device;
-    int n_cu;
-};
+namespace fb4 {
+const uint16_t* gelu_tables();   // fb4_producers.hip
+size_t gelu_tables_bytes();
+}
 
 namespace {
 
 using namespace fb4;
-
-bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
-
-// The tables live on the device the handle was built on: launching from another current device would hand
-// the kernels a foreign pointer.
-int check_device(const fb4_luts* l)
-{
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) {
-        (void)hipGetLastError();
-        return FB4_ERR_HIP;
-    }
-    return dev == l->device ? FB4_OK : FB4_ERR_INVALID_ARG;
-}
-
-// The two GeLU tables, evaluated once per process (about 100,000 calls of erfc / exp).
-const uint16_t* gelu_tables()
-{
-    static const uint16_t* tables = []() -> const uint16_t* {
-        uint16_t* t = static_cast<uint16_t*>(std::malloc(2 * kGeluTableBytes));
-        if (!t) return nullptr;
-        build_gelu_table(false, t);
-        build_gelu_table(true, t + kGeluTableBytes / 2);
-        return t;
-    }();
-    return tables;
-}
 
 int grid_for(const fb4_luts* l, long long n_tiles)
 {
@@ -63,18 +30,6 @@ int grid_for(const fb4_luts* l, long long n_tiles)
     if (groups > cap) groups = cap;
     if (groups < 1) groups = 1;
     return (int)groups;
-}
-
-int check_opts(const fb4_opts* o)
-{
-    if (!o) return FB4_ERR_INVALID_ARG;
-    if (o->selector != FB4_SEL_SSE && o->selector != FB4_SEL_LUT) return FB4_ERR_INVALID_ARG;
-    if (o->flags & ~FB4_FLAG_TWO_STAGE) return FB4_ERR_INVALID_ARG;
-    if (o->block != 32 && o->block != 16) return FB4_ERR_INVALID_ARG;
-    if (o->selector == FB4_SEL_LUT &&
-        ((o->num_groups != 8 && o->num_groups != 16 && o->num_groups != 32) || o->num_groups > o->block))
-        return FB4_ERR_INVALID_ARG;
-    return FB4_OK;
 }
 
 template <int SEL, int G, int MODE, int LPB>
@@ -279,31 +234,6 @@ bool launch_fast_second_plane(const fb4_luts* luts, const fb4_opts* opts, const 
     return true;
 }
 
-// The optional SeDA arguments of the producer-fused calls: all absent, or all there and small enough.
-int check_fused_seda(const int32_t* token_group, const uint8_t* sub, int n_groups, int64_t rows)
-{
-    if (!token_group && !sub) return n_groups == 0 ? FB4_OK : FB4_ERR_INVALID_ARG;
-    if (n_groups < 1) return FB4_ERR_INVALID_ARG;
-    if (rows > 0 && (!token_group || !sub)) return FB4_ERR_INVALID_ARG;
-    if (!aligned(token_group, 4) || (uint32_t)n_groups > kMaxFusedProducerGroups) return FB4_ERR_UNSUPPORTED;
-    return FB4_OK;
-}
-
-// Shared validation of the tensor arguments of the three quantizing calls.
-int check_tensor(const fb4_luts* l, const fb4_opts* o, const void* x, int64_t rows, int64_t cols,
-                 int64_t row_stride, const void* codes, const void* meta)
-{
-    if (!l) return FB4_ERR_INVALID_ARG;
-    int rc = check_opts(o);
-    if (rc != FB4_OK) return rc;
-    if (rows < 0 || cols < 0 || row_stride < cols) return FB4_ERR_INVALID_ARG;
-    if (cols % o->block) return FB4_ERR_UNSUPPORTED;
-    if (rows == 0 || cols == 0) return FB4_OK;
-    if (!x || !codes || !meta) return FB4_ERR_INVALID_ARG;
-    if (!aligned(x, 16) || (row_stride % 8) || !aligned(codes, 4) || !aligned(meta, 2)) return FB4_ERR_UNSUPPORTED;
-    return FB4_OK;
-}
-
 // Tiling of `out_rows` rows of `cols` columns; false if it does not fit 32-bit tile indices.
 bool tiling(int64_t out_rows, int64_t cols, int block, int* nb, int* tpr, int* n_tiles)
 {
@@ -364,7 +294,7 @@ int fb4_build_luts(const uint8_t* formatbook, int n_dialects, fb4_luts** out)
     }
     l->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     // one allocation: the table blob, then the two GeLU tables (exact form, tanh form) of fb4_gelu_quantize
-    if (hipMalloc(reinterpret_cast<void**>(&l->dev_blob), kBlobBytes + 2 * kGeluTableBytes) != hipSuccess) {
+    if (hipMalloc(reinterpret_cast<void**>(&l->dev_blob), kBlobBytes + gelu_tables_bytes()) != hipSuccess) {
         (void)hipGetLastError();
         delete l;
         return FB4_ERR_ALLOC;
@@ -376,7 +306,7 @@ int fb4_build_luts(const uint8_t* formatbook, int n_dialects, fb4_luts** out)
         return FB4_ERR_ALLOC;
     }
     if (hipMemcpy(l->dev_blob, l->host_blob, kBlobBytes, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(l->dev_blob + kBlobBytes, gelu, 2 * kGeluTableBytes, hipMemcpyHostToDevice) != hipSuccess) {
+        hipMemcpy(l->dev_blob + kBlobBytes, gelu, gelu_tables_bytes(), hipMemcpyHostToDevice) != hipSuccess) {
         (void)hipGetLastError();
         (void)hipFree(l->dev_blob);
         delete l;
@@ -691,259 +621,6 @@ int fb4_seda_profile(const fb4_luts* luts, const uint16_t* meta, int64_t rows, i
     }
     hipLaunchKernelGGL(profile_select_kernel, dim3(((unsigned)n_groups * 8u + kProfileThreads - 1) / kProfileThreads),
                        dim3(kProfileThreads), 0, s, counts, n_groups, luts->dev_blob, sub_formatbooks);
-    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
-}
-
-int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
-                           int64_t row_stride, const float* gamma, const float* beta, float eps,
-                           const int32_t* token_group, const uint8_t* sub_formatbooks, int n_groups, uint8_t* codes,
-                           uint16_t* meta, void* y_out, void* stream)
-{
-    int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
-    if (rc != FB4_OK) return rc;
-    if (!(eps >= 0.0f) || eps > 3.0e38f) return FB4_ERR_INVALID_ARG;
-    if ((rc = check_fused_seda(token_group, sub_formatbooks, n_groups, rows)) != FB4_OK) return rc;
-    if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8) return FB4_ERR_UNSUPPORTED;
-    if (rows == 0 || cols == 0) return FB4_OK;
-    const int64_t nb = cols / 32;
-    if (nb > 64 * kLnMaxChunksPerLane || !aligned(codes, 16) || (gamma && !aligned(gamma, 4)) || (beta && !aligned(beta, 4)) ||
-        (y_out && !aligned(y_out, 16)))
-        return FB4_ERR_UNSUPPORTED;
-    if ((uint64_t)rows * (uint64_t)nb >= 0x7F000000ull) return FB4_ERR_UNSUPPORTED;
-    if ((rc = check_device(luts)) != FB4_OK) return rc;
-    // Chunks per lane B and rows per bundle: the fullest wavefront among B <= 4, the fewest chunks among equals;
-    // rows longer than 8192 need 5 or 6.
-    int B = 0;
-    uint32_t rw = 0;
-    double best = 0.0;
-    for (int b = 1; b <= 4; ++b) {
-        if (nb > 64 * b) continue;
-        const uint32_t r = (uint32_t)(64 * b / nb);
-        const double fill = (double)(r * nb) / (64.0 * b) - (b == 4 ? 0.05 : 0.0);
-        if (fill > best + 1e-9) { best = fill; B = b; rw = r; }
-    }
-    if (B == 0) { B = (int)((nb + 63) / 64); rw = 1; }
-    if (rw > (uint32_t)rows) rw = (uint32_t)rows;
-    const uint32_t n_bundles = (uint32_t)((rows + rw - 1) / rw);
-    const int kLnWaves = ln_threads(B) / 64;
-    long long g = ((long long)n_bundles + kLnWaves - 1) / kLnWaves;
-    if (g > luts->n_cu) g = luts->n_cu;
-    const unsigned groups = (unsigned)g;
-    LayerNormParams p = {};
-    p.rows = (uint32_t)rows;
-    p.cols = (uint32_t)cols;
-    p.n_blocks = (uint32_t)(rows * nb);
-    p.eps = eps;
-    p.codes = codes;
-    p.meta = meta;
-    p.token_group = token_group;
-    p.sub = sub_formatbooks;
-    p.n_groups = (uint32_t)n_groups;
-    p.n_dialects = (uint32_t)luts->n_dialects;
-    p.y_out = static_cast<uint16_t*>(y_out);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
-    const bool seda = token_group != nullptr;
-#define FB4_LN_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), n_bundles, rw, (uint32_t)nb, groups, (long long)row_stride, gamma, beta, p
-#define FB4_LN_LAUNCH(b, t, sd, wy) hipLaunchKernelGGL((layernorm_quantize_kernel<b, t, sd, wy>), dim3(groups), dim3(ln_threads(b)), 0, s, FB4_LN_ARGS)
-#define FB4_LN_CASE(b)                                         \
-    case b:                                                    \
-        if (y_out) FB4_LN_LAUNCH(b, false, false, true);       \
-        if (seda) {                                            \
-            if (ts) FB4_LN_LAUNCH(b, true, true, false);       \
-            else FB4_LN_LAUNCH(b, false, true, false);         \
-        } else {                                               \
-            if (ts) FB4_LN_LAUNCH(b, true, false, false);      \
-            else FB4_LN_LAUNCH(b, false, false, false);        \
-        }                                                      \
-        break;
-    switch (B) {
-        FB4_LN_CASE(1) FB4_LN_CASE(2) FB4_LN_CASE(3) FB4_LN_CASE(4) FB4_LN_CASE(5) FB4_LN_CASE(6)
-        default: return FB4_ERR_UNSUPPORTED;
-    }
-#undef FB4_LN_CASE
-#undef FB4_LN_LAUNCH
-#undef FB4_LN_ARGS
-    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
-}
-
-int fb4_gelu_quantize(const fb4_luts* luts, const fb4_opts* opts, const void* x, int64_t rows, int64_t cols,
-                      int64_t row_stride, int approximate, const int32_t* token_group, const uint8_t* sub_formatbooks,
-                      int n_groups, uint8_t* codes, uint16_t* meta, void* stream)
-{
-    int rc = check_tensor(luts, opts, x, rows, cols, row_stride, codes, meta);
-    if (rc != FB4_OK) return rc;
-    if (approximate != 0 && approximate != 1) return FB4_ERR_INVALID_ARG;
-    if ((rc = check_fused_seda(token_group, sub_formatbooks, n_groups, rows)) != FB4_OK) return rc;
-    if (opts->block != 32 || opts->selector != FB4_SEL_LUT || opts->num_groups != 8) return FB4_ERR_UNSUPPORTED;
-    if (rows == 0 || cols == 0) return FB4_OK;
-    if (!aligned(codes, 16)) return FB4_ERR_UNSUPPORTED;
-    const uint64_t nb = (uint64_t)cols / 32;
-    const uint64_t n_blocks = (uint64_t)rows * nb;
-    if (n_blocks >= 0x7F000000ull) return FB4_ERR_UNSUPPORTED;
-    if ((rc = check_device(luts)) != FB4_OK) return rc;
-    const uint32_t n_tiles = (uint32_t)((n_blocks + 63) / 64);
-    uint32_t l = 0;
-    while ((1ull << l) < nb) ++l;
-    const uint32_t div_shift = 31 + l;
-    const uint32_t div_mul = (uint32_t)(((1ull << div_shift) + nb - 1) / nb);
-    long long g = ((long long)n_tiles + kGeluThreads / 64 - 1) / (kGeluThreads / 64);
-    if (g > luts->n_cu) g = luts->n_cu;
-    const unsigned groups = (unsigned)g;
-    GeluParams p = {codes, meta, token_group, sub_formatbooks, (uint32_t)n_groups, (uint32_t)luts->n_dialects};
-    const bool seda = token_group != nullptr, ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
-    const uint16_t* table = reinterpret_cast<const uint16_t*>(luts->dev_blob + kBlobBytes + (approximate ? kGeluTableBytes : 0));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-#define FB4_GELU_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), table, (uint32_t)n_blocks, n_tiles, div_mul, div_shift, (uint32_t)nb, groups, (long long)row_stride, p
-    if (seda) {
-        if (ts) hipLaunchKernelGGL((gelu_quantize_kernel<true, true>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
-        else hipLaunchKernelGGL((gelu_quantize_kernel<false, true>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
-    } else {
-        if (ts) hipLaunchKernelGGL((gelu_quantize_kernel<true, false>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
-        else hipLaunchKernelGGL((gelu_quantize_kernel<false, false>), dim3(groups), dim3(kGeluThreads), 0, s, FB4_GELU_ARGS);
-    }
-#undef FB4_GELU_ARGS
-    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
-}
-
-int fb4_gelu_table_host(int approximate, uint16_t* table, size_t capacity, size_t* entries)
-{
-    if (entries) *entries = kGeluEntries;
-    if (approximate != 0 && approximate != 1) return FB4_ERR_INVALID_ARG;
-    if (!table || capacity < kGeluEntries) return FB4_ERR_INVALID_ARG;
-    const uint16_t* t = gelu_tables();
-    if (!t) return FB4_ERR_ALLOC;
-    std::memcpy(table, t + (approximate ? kGeluTableBytes / 2 : 0), kGeluEntries * 2);
-    return FB4_OK;
-}
-
-int fb4_attention_scores(const void* q, const void* k, int64_t groups, int64_t tokens, int64_t dim, int mode,
-                         float* scores, void* stream)
-{
-    if (groups < 0 || tokens < 0 || dim < 0 || (mode != 0 && mode != 1)) return FB4_ERR_INVALID_ARG;
-    if (groups == 0 || tokens == 0) return FB4_OK;
-    if (!q || !k || !scores || dim == 0) return FB4_ERR_INVALID_ARG;
-    if ((dim % 8) || dim > 256 || !aligned(q, 16) || !aligned(k, 16) || !aligned(scores, 4)) return FB4_ERR_UNSUPPORTED;
-    const bool small = tokens <= (int64_t)kScoreShortGroup;
-    const int64_t per_wg = small ? 128 : 256;   // queries per workgroup of the two kernel shapes
-    const int64_t bpg = (tokens + per_wg - 1) / per_wg;
-    if (tokens * dim > 0x7FFFFFFFll || groups * bpg > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid((unsigned)(groups * bpg));
-#define FB4_SCORE_ARGS static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), (uint32_t)tokens, (uint32_t)dim, (uint32_t)bpg, scores
-#define FB4_SCORE_LAUNCH(d, relu, qb, keys) hipLaunchKernelGGL((attention_scores_kernel<d, relu, qb, keys>), grid, dim3(kScoreThreads), 0, s, FB4_SCORE_ARGS)
-#define FB4_SCORE_CASE(d)                                   \
-    case d:                                                 \
-        if (small) {                                        \
-            if (mode) FB4_SCORE_LAUNCH(d, true, 1, 32);     \
-            else FB4_SCORE_LAUNCH(d, false, 1, 32);         \
-        } else {                                            \
-            if (mode) FB4_SCORE_LAUNCH(d, true, 2, 64);     \
-            else FB4_SCORE_LAUNCH(d, false, 2, 64);         \
-        }                                                   \
-        break;
-    switch ((int)((dim + 31) / 32)) {
-        FB4_SCORE_CASE(1) FB4_SCORE_CASE(2) FB4_SCORE_CASE(3) FB4_SCORE_CASE(4)
-        FB4_SCORE_CASE(5) FB4_SCORE_CASE(6) FB4_SCORE_CASE(7) FB4_SCORE_CASE(8)
-        default: return FB4_ERR_UNSUPPORTED;
-    }
-#undef FB4_SCORE_CASE
-#undef FB4_SCORE_LAUNCH
-#undef FB4_SCORE_ARGS
-    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
-}
-
-int fb4_select_salient_tokens(const float* scores, int64_t frames, int heads, int grid_h, int grid_w, int tile_h,
-                              int tile_w, int32_t* rows_out, void* stream)
-{
-    if (frames < 0 || heads < 1 || grid_h < 1 || grid_w < 1 || tile_h < 1 || tile_w < 1) return FB4_ERR_INVALID_ARG;
-    if (frames == 0) return FB4_OK;
-    if (!scores || !rows_out) return FB4_ERR_INVALID_ARG;
-    const int64_t tokens = (int64_t)grid_h * grid_w;
-    if (tokens > (int64_t)kSelectMaxTokens || frames * tokens > 0x7FFFFFFFll || !aligned(scores, 4) || !aligned(rows_out, 4))
-        return FB4_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(select_salient_kernel, dim3((unsigned)frames), dim3(kSelectThreads), 0, static_cast<hipStream_t>(stream),
-                       scores, (uint32_t)heads, (uint32_t)grid_h, (uint32_t)grid_w, (uint32_t)tile_h, (uint32_t)tile_w, rows_out);
-    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
-}
-
-int fb4_seda_assign(const void* q, const void* k, int joint, int64_t frames, int heads, int grid_h, int grid_w,
-                    int64_t dim, const int32_t* anchors, int64_t n_anchors, int tile_h, int tile_w, int window,
-                    int window_t, float threshold, int32_t* token_group, int32_t* anchor_group, float* window_scores,
-                    void* stream)
-{
-    if (frames < 0 || heads < 1 || grid_h < 1 || grid_w < 1 || dim < 1 || n_anchors < 0 || window < 1 || window_t < 1 ||
-        tile_h < 1 || tile_w < 1 || (joint != 0 && joint != 1))
-        return FB4_ERR_INVALID_ARG;
-    if (!(threshold == threshold)) return FB4_ERR_INVALID_ARG;
-    if (!joint && window_t != 1) return FB4_ERR_INVALID_ARG;   // factorized attention has no scores across frames
-    if (frames == 0) return FB4_OK;
-    if (!token_group || !anchor_group || (n_anchors > 0 && (!q || !k || !anchors))) return FB4_ERR_INVALID_ARG;
-    const int64_t tokens = (int64_t)grid_h * grid_w;
-    if ((dim % 8) || window > 8 || window_t > 64 || !aligned(q, 16) || !aligned(k, 16) || !aligned(anchors, 4) ||
-        !aligned(token_group, 4) || !aligned(anchor_group, 4) || (window_scores && !aligned(window_scores, 4)))
-        return FB4_ERR_UNSUPPORTED;
-    if (frames * tokens > 0x7FFFFFFFll || n_anchors > 0x7FFFFFFFll || tokens * dim > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint32_t n = (uint32_t)(frames * tokens);
-    hipLaunchKernelGGL(seda_fill_kernel, dim3((n + 255) / 256), dim3(256), 0, s, token_group, anchor_group, n);
-    if (n_anchors > 0) {
-        AssignParams p = {};
-        p.frames = (uint32_t)frames; p.heads = (uint32_t)heads; p.grid_h = (uint32_t)grid_h; p.grid_w = (uint32_t)grid_w;
-        p.dim = (uint32_t)dim; p.tile_h = (uint32_t)tile_h; p.tile_w = (uint32_t)tile_w;
-        p.window = (uint32_t)window; p.window_t = (uint32_t)window_t;
-        p.stride_f = joint ? (uint64_t)tokens : (uint64_t)heads * tokens;
-        p.stride_h = joint ? (uint64_t)frames * tokens : (uint64_t)tokens;
-        p.threshold = threshold;
-        hipLaunchKernelGGL(seda_mark_kernel, dim3((unsigned)n_anchors, (unsigned)window_t), dim3(kAssignThreads), 0, s,
-                           static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), anchors, p, token_group,
-                           window_scores);
-        hipLaunchKernelGGL(seda_anchor_kernel, dim3((unsigned)((n_anchors + 255) / 256)), dim3(256), 0, s, anchors,
-                           (uint32_t)n_anchors, (uint32_t)frames, (uint32_t)grid_h, (uint32_t)grid_w, (uint32_t)tile_h,
-                           (uint32_t)tile_w, token_group, anchor_group);
-    }
-    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
-}
-
-int fb4_seda_main_anchor(const float* temporal_scores, const void* qt, const void* kt, int64_t frames, int heads,
-                         int grid_h, int grid_w, int64_t dim, const int32_t* candidates, int n_per_frame, int tile_h,
-                         int tile_w, float prune_threshold, int32_t* main_anchor, int32_t* kept, float* prune_scores,
-                         void* stream)
-{
-    if (frames < 0 || heads < 1 || grid_h < 1 || grid_w < 1 || dim < 1 || n_per_frame < 0 || tile_h < 1 || tile_w < 1)
-        return FB4_ERR_INVALID_ARG;
-    if (!(prune_threshold == prune_threshold)) return FB4_ERR_INVALID_ARG;
-    if (!main_anchor) return FB4_ERR_INVALID_ARG;
-    const int64_t tokens = (int64_t)grid_h * grid_w;
-    const int64_t tiles = (int64_t)((grid_h + tile_h - 1) / tile_h) * ((grid_w + tile_w - 1) / tile_w);
-    const int64_t n_cand = frames * n_per_frame;
-    if (n_cand > 0 && (!temporal_scores || !qt || !kt || !candidates || !kept)) return FB4_ERR_INVALID_ARG;
-    if ((dim % 8) || frames > (int64_t)kMainMaxFrames || !aligned(qt, 16) || !aligned(kt, 16) || !aligned(temporal_scores, 4) ||
-        !aligned(candidates, 4) || !aligned(main_anchor, 4) || !aligned(kept, 4) || (prune_scores && !aligned(prune_scores, 4)))
-        return FB4_ERR_UNSUPPORTED;
-    if (frames * tokens > 0x7FFFFFFFll || n_cand > 0x7FFFFFFFll || frames * dim > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (n_cand > 0)
-        hipLaunchKernelGGL(seda_fill_kernel, dim3((unsigned)((n_cand + 255) / 256)), dim3(256), 0, s, kept,
-                           static_cast<int32_t*>(nullptr), (uint32_t)n_cand);
-    hipLaunchKernelGGL(seda_main_anchor_kernel, dim3((unsigned)tiles), dim3(kMainThreads), 0, s, temporal_scores,
-                       static_cast<const uint16_t*>(qt), static_cast<const uint16_t*>(kt), (uint32_t)frames, (uint32_t)heads,
-                       (uint32_t)grid_h, (uint32_t)grid_w, (uint32_t)dim, candidates, (uint32_t)n_per_frame, (uint32_t)tile_h,
-                       (uint32_t)tile_w, prune_threshold, main_anchor, kept, prune_scores);
-    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
-}
-
-int fb4_seda_main_anchor_3d(const float* scores, int64_t frames, int heads, int grid_h, int grid_w, int tile_h,
-                            int tile_w, int32_t* anchors, void* stream)
-{
-    if (frames < 1 || heads < 1 || grid_h < 1 || grid_w < 1 || tile_h < 1 || tile_w < 1) return FB4_ERR_INVALID_ARG;
-    if (!scores || !anchors) return FB4_ERR_INVALID_ARG;
-    const int64_t tokens = (int64_t)grid_h * grid_w;
-    const int64_t tiles = (int64_t)((grid_h + tile_h - 1) / tile_h) * ((grid_w + tile_w - 1) / tile_w);
-    if (frames * tokens > 0x7FFFFFFFll || !aligned(scores, 4) || !aligned(anchors, 4)) return FB4_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(seda_main_anchor_3d_kernel, dim3((unsigned)tiles), dim3(kMainThreads), 0,
-                       static_cast<hipStream_t>(stream), scores, (uint32_t)frames, (uint32_t)heads, (uint32_t)grid_h,
-                       (uint32_t)grid_w, (uint32_t)tile_h, (uint32_t)tile_w, anchors);
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 

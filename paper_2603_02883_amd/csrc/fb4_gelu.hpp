@@ -95,7 +95,8 @@ struct GeluParams {
 constexpr int kGeluThreads = FB4_GELU_THREADS;
 constexpr int kLdsGelu = lds_fast_bytes(false, false, false);
 
-template <bool kTwoStage, bool kSeda>
+// kBlock, G: block size (32 or 16) and number of groups of the online selector (Sec. 3.2, Sec. 4.1).
+template <int kBlock, int G, bool kTwoStage, bool kSeda>
 __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
     const uint8_t* blob, const uint16_t* x, const uint16_t* table, uint32_t n_blocks, uint32_t n_tiles, uint32_t div_mul,
     uint32_t div_shift, uint32_t nb, uint32_t n_workgroups, long long row_stride, GeluParams p)
@@ -220,8 +221,8 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
         uint32_t code[4], meta;
         bool tile_special;
         const uint32_t no_code[4] = {0, 0, 0, 0};
-        compute_tile<32, 8, kTwoStage, kSeda>(y, lds, K, nullptr, gb < n_blocks, excl, code, meta, no_code, 0u, tile_special, stage);
-        store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, meta_aligned);
+        compute_tile<kBlock, G, kTwoStage, kSeda>(y, lds, K, nullptr, gb < n_blocks, excl, code, meta, no_code, 0u, tile_special, stage);
+        store_tile<kBlock>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, meta_aligned);
         t = t_next;
         t_next = t_after;
     }

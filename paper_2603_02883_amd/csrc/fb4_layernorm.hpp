@@ -170,7 +170,8 @@ __device__ __noinline__ RowNorm layernorm_row_plain(const uint16_t* xrow, uint32
 // them; two chunk buffers alternate, the chunk of the next step is always in flight.  (Holding the bundle in
 // registers instead reads x once but leaves room for 8 wavefronts per CU only, or spills: 42-62 us on a
 // 16384x3072 tensor.)
-template <int B, bool kTwoStage, bool kSeda, bool kWriteY, int kThreads = ln_threads(B)>
+// kBlock, G: block size (32 or 16) and number of groups of the online selector (Sec. 3.2, Sec. 4.1).
+template <int B, int kBlock, int G, bool kTwoStage, bool kSeda, bool kWriteY, int kThreads = ln_threads(B)>
 __global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
     const uint8_t* blob, const uint16_t* x, uint32_t n_bundles, uint32_t rw, uint32_t nb, uint32_t n_workgroups,
     long long row_stride, const float* gamma, const float* beta, LayerNormParams p)
@@ -385,9 +386,9 @@ __global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
                 uint32_t code[4], meta;
                 bool tile_special;
                 const uint32_t no_code[4] = {0, 0, 0, 0};
-                compute_tile<32, 8, kTwoStage, kSeda>(y, lds, K, nullptr, ok[j], excl, code, meta, no_code, 0u, tile_special, stage);
+                compute_tile<kBlock, G, kTwoStage, kSeda>(y, lds, K, nullptr, ok[j], excl, code, meta, no_code, 0u, tile_special, stage);
                 const bool al = meta_aligned && (((gb - lane) & 7u) == 0u);
-                store_tile<32>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, al, ok[j]);
+                store_tile<kBlock>(sp, gb, lane, make_uint4(code[0], code[1], code[2], code[3]), meta, al, ok[j]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }

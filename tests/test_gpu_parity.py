@@ -922,13 +922,13 @@ def synth_b2f(bits):
         return u.view(np.float32).astype(np.float64)
 
 
-def _ln_case(F, luts, xb, gamma, beta, eps, flags=0, what="", x_dev=None, tg=None, sub=None, min_exact=None):
+def _ln_case(F, luts, xb, gamma, beta, eps, flags=0, what="", x_dev=None, tg=None, sub=None, min_exact=None, block=32, ng=8):
     """One call with the checking output: (i) the producer's bf16 tensor against the float64 definition,
     (ii) codes and metadata bit for bit against the oracle's quantizer run on the GPU's own bf16 tensor."""
     x = dev_bits(xb) if x_dev is None else x_dev
     g = None if gamma is None else torch.from_numpy(gamma).cuda()
     b = None if beta is None else torch.from_numpy(beta).cuda()
-    o = F.opts(selector=1, num_groups=8, flags=flags)
+    o = F.opts(block=block, selector=1, num_groups=ng, flags=flags)
     y_d = torch.full(x.shape, 7.0, dtype=torch.bfloat16, device="cuda")
     tg_d = None if tg is None else torch.from_numpy(tg).cuda()
     sub_d = None if sub is None else torch.from_numpy(sub).cuda()
@@ -937,9 +937,10 @@ def _ln_case(F, luts, xb, gamma, beta, eps, flags=0, what="", x_dev=None, tg=Non
     torch.cuda.synchronize()
     assert torch.equal(c, c0) and torch.equal(m, m0)
     y_gpu = synth.bf16_bits(y_d)
-    cr, mr = O.quantize(DEFAULT_FORMATBOOK, y_gpu, selector=1, num_groups=8, flags=flags, token_group=tg, sub_formatbooks=sub)
-    compare_quant(DEFAULT_FORMATBOOK, y_gpu, host_u8(c), host_u16(m), cr, mr, 1, 8, flags=flags, token_group=tg, sub=sub,
-                  what="layernorm " + what)
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, y_gpu, block=block, selector=1, num_groups=ng, flags=flags, token_group=tg,
+                        sub_formatbooks=sub)
+    compare_quant(DEFAULT_FORMATBOOK, y_gpu, host_u8(c), host_u16(m), cr, mr, 1, ng, flags=flags, token_group=tg, sub=sub,
+                  what="layernorm " + what, block=block)
     exact = check_layernorm_producer(y_gpu, xb, gamma, beta, eps, what="layernorm " + what, min_exact=min_exact)
     return c, m, y_gpu, exact
 
@@ -966,6 +967,49 @@ def test_layernorm_quantize_full_size_two_stage_and_no_affine(F, luts):
     _ln_case(F, luts, xb, gamma, beta, 1e-5, flags=F.FLAG_TWO_STAGE, what="cfg2 two-stage", x_dev=x, min_exact=0.999)
     _ln_case(F, luts, xb, None, None, 1e-6, what="cfg2 no affine", x_dev=x, min_exact=0.999)
     _ln_case(F, luts, xb, gamma, None, 0.0, what="cfg2 scale only, eps 0", x_dev=x, min_exact=0.999)
+
+
+@pytest.mark.parametrize("block,g", [(32, 16), (16, 8), (16, 16)])
+def test_fused_producers_other_block_sizes_and_group_counts(F, luts, block, g):
+    """Sec. 4.1 evaluates block sizes 16 and 32; the online rule with 8 or 16 groups: both producers, with and without
+    SeDA lists and the two-stage flag."""
+    for rows, cols, flags, n_groups in [(700, 3072, 0, 0), (333, 1152, 1, 0), (64, 12288, 0, 5), (2048, 4096, 1, 64), (129, 64, 0, 0)]:
+        x, comp = synth.mixture_activation(rows=rows, cols=cols, seed=rows + block + g, n_components=max(n_groups, 2), device="cuda")
+        xb = synth.bf16_bits(x)
+        tg = sub = tg_d = sub_d = None
+        if n_groups:
+            tg = comp.copy()
+            tg[::9] = -1
+            sub = synth.seda_sub_formatbooks(DEFAULT_FORMATBOOK, n_groups, rows)
+            tg_d, sub_d = torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda()
+        gamma, beta = synth.layernorm_affine(cols, seed=cols)
+        _ln_case(F, luts, xb, gamma, beta, 1e-6, flags=flags, what="block %d g %d %dx%d" % (block, g, rows, cols), x_dev=x, tg=tg,
+                 sub=sub, min_exact=0.999, block=block, ng=g)
+        o = F.opts(block=block, selector=1, num_groups=g, flags=flags)
+        for approximate in (0, 1):
+            c, m = F.fb4_gelu_quantize(luts, o, x, approximate, token_group=tg_d, sub_formatbooks=sub_d)
+            torch.cuda.synchronize()
+            y = O.gelu(xb, approximate)
+            cr, mr = O.quantize(DEFAULT_FORMATBOOK, y, block=block, selector=1, num_groups=g, flags=flags, token_group=tg,
+                                sub_formatbooks=sub)
+            compare_quant(DEFAULT_FORMATBOOK, y, host_u8(c), host_u16(m), cr, mr, 1, g, flags=flags, token_group=tg, sub=sub,
+                          what="gelu block %d g %d %dx%d" % (block, g, rows, cols), block=block)
+    # degenerate values through both producers
+    xe = synth.edge_case_tensor(cols=256)
+    _ln_case(F, luts, xe, None, None, 1e-6, what="edge rows block %d g %d" % (block, g), block=block, ng=g)
+    c, m = F.fb4_gelu_quantize(luts, F.opts(block=block, selector=1, num_groups=g), dev_bits(xe), 0)
+    torch.cuda.synchronize()
+    cr, mr = O.quantize(DEFAULT_FORMATBOOK, O.gelu(xe, 0), block=block, selector=1, num_groups=g)
+    assert np.array_equal(host_u8(c), cr) and np.array_equal(host_u16(m), mr)
+    # metadata of block-16 output must be 4-byte aligned
+    if block == 16:
+        x = synth.vdit_activation(rows=8, cols=256, seed=1, device="cuda")
+        mbuf = torch.zeros(8 * 16 + 1, dtype=torch.int16, device="cuda")
+        for call in (lambda **kw: F.fb4_layernorm_quantize(luts, F.opts(block=16, num_groups=g), x, **kw),
+                     lambda **kw: F.fb4_gelu_quantize(luts, F.opts(block=16, num_groups=g), x, 0, **kw)):
+            with pytest.raises(F.Fb4Error) as e:
+                call(meta=mbuf[1:].view(8, 16))
+            assert e.value.code == F.ERR_UNSUPPORTED
 
 
 def test_layernorm_producer_constant_rows_and_large_means(F, luts):
@@ -1027,8 +1071,7 @@ def test_layernorm_quantize_is_the_unfused_pair_and_rejects_what_it_does_not_ser
     c2, m2 = F.fb4_quantize(luts, F.opts(), dev_bits(y_gpu))
     torch.cuda.synchronize()
     assert torch.equal(c, c2) and torch.equal(m, m2)
-    for o, code in ((F.opts(block=16), F.ERR_UNSUPPORTED), (F.opts(num_groups=16), F.ERR_UNSUPPORTED),
-                    (F.opts(selector=0), F.ERR_UNSUPPORTED)):
+    for o, code in ((F.opts(num_groups=32), F.ERR_UNSUPPORTED), (F.opts(selector=0), F.ERR_UNSUPPORTED)):
         with pytest.raises(F.Fb4Error) as e:
             F.fb4_layernorm_quantize(luts, o, x)
         assert e.value.code == code
@@ -1107,8 +1150,7 @@ def test_gelu_quantize_degenerate_values_strides_and_errors(F, luts):
     assert not cbuf[:16].any() and mbuf[0] == 0
     # what it does not serve
     x = synth.gaussian_outlier(rows=64, cols=1024, seed=8, device="cuda")
-    for o, code in ((F.opts(block=16), F.ERR_UNSUPPORTED), (F.opts(num_groups=16), F.ERR_UNSUPPORTED),
-                    (F.opts(selector=0), F.ERR_UNSUPPORTED)):
+    for o, code in ((F.opts(num_groups=32), F.ERR_UNSUPPORTED), (F.opts(selector=0), F.ERR_UNSUPPORTED)):
         with pytest.raises(F.Fb4Error) as e:
             F.fb4_gelu_quantize(luts, o, x)
         assert e.value.code == code
