@@ -24,10 +24,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the headline kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the
-# same counter reads for a plain copy of known size (profiles/quantize_lut_kernel_cfg2_traffic.md): 98,371 KiB
-# read (counter x 1.99927) + 27,648 KiB written (counter x 1.0).
-MEASURED_TRAFFIC_BYTES = 129043141
+# HBM bytes per launch of the headline kernel (rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+# counter reads for a plain copy of known size) and the kernel's name come from this summary, which
+# paper_2603_02883_amd/profile_summary.py writes from raw rocprofv3 output; without the file both are null.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "headline_kernel_traffic.txt")
 ROWS, COLS, BLOCK = 16384, 3072, 32
 N_SETS = 6
 SETTLE_S = 0.05   # untimed load before a timed graph replay
@@ -233,6 +233,8 @@ def main():
 
     # ---- headline: the paper's online selector
     o_main = F.opts(block=BLOCK, selector=F.SEL_LUT, num_groups=8)
+    from paper_2603_02883_amd.profile_summary import read_summary
+    summary = read_summary(TRAFFIC_SUMMARY)
     wall, ev = timer(quant_step(o_main), args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
     kern_s = ev / args.steps
@@ -258,8 +260,10 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-            "kernel": "fb4::quantize_lut_kernel<32, 8, true, false, false, 0, 512>", "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
+            "frac": abytes / kern_s / 1e9 / HBM_PEAK_GBS,
+            "traffic": int(summary["traffic_bytes_per_launch"]) if "traffic_bytes_per_launch" in summary else None,
+            "kernel": summary.get("kernel"), "kernel_us": kern_s * 1e6, "algorithmic_bytes": abytes,
+            "traffic_source": os.path.relpath(TRAFFIC_SUMMARY, ROOT) if summary else None,
         },
     }
 
