@@ -1141,3 +1141,29 @@ def test_seda_3d_main_anchor_and_cuboid_window_hand_worked():
     want1 = np.full(16, -1)
     want1[[9, 14]] = 0; want1[6] = 1; want1[13] = 0; want1[2] = 1
     assert tg1.tolist() == want1.tolist()
+
+
+def test_seda_tiles_that_are_not_square_hand_worked():
+    # A 4 x 6 grid cut into tiles of 2 rows x 3 columns: 2 x 2 tiles, numbered row-major
+    #   tokens  0  1  2 |  3  4  5      tile 0 | tile 1
+    #           6  7  8 |  9 10 11
+    #          ---------+---------
+    #          12 13 14 | 15 16 17      tile 2 | tile 3
+    #          18 19 20 | 21 22 23
+    # (tile_h and tile_w exchanged, or the tile grid transposed, would give other numbers for tokens 8, 9, 12.)
+    q = np.zeros((1, 1, 24, 1), dtype=np.uint16)
+    anchors = [8, 9, 12, 23]
+    _, ag, _ = O.seda_assign(q, q, anchors, 1, 4, 6, tile_h=2, tile_w=3, window=3, threshold=1.0)
+    assert [int(ag[t]) for t in anchors] == [0, 1, 2, 3]
+    # the per-tile choice and the 3D main anchor use the same tiles: one frame, one head, the best token of
+    # each tile planted at 8, 9, 12, 23; a 4 x 9 grid with the same tiles has 2 x 3 tiles, the last row of
+    # tiles being numbers 3, 4, 5
+    sc = np.zeros((1, 24)); sc[0, anchors] = 1.0
+    assert O.seda_main_anchor_3d(sc, 1, 4, 6, 2, 3).tolist() == anchors
+    assert O.select_salient_tokens(sc.reshape(1, 1, 24), 4, 6, 2, 3).tolist() == [anchors]
+    sc = np.zeros((1, 36)); sc[0, [2, 12, 8, 18, 31, 26]] = 1.0
+    assert O.seda_main_anchor_3d(sc, 1, 4, 9, 2, 3).tolist() == [2, 12, 8, 18, 31, 26]
+    # step 2 finds a candidate's tile the same way: one frame, candidates 8 and 12 -> tiles 0 and 2
+    ts = np.ones((24, 1, 1)); z = np.zeros((24, 1, 1, 1), dtype=np.uint16)
+    main, kept, _ = O.seda_main_anchor(ts, z, z, [[8, 12]], 4, 6, 2, 3, prune_threshold=0.0)
+    assert main.tolist() == [8, -1, 12, -1] and kept.tolist() == [[8, 12]]
