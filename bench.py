@@ -320,6 +320,28 @@ def main():
             y = torch.nn.functional.gelu(xs[k], approximate="tanh")
             F.fb4_quantize(luts, o_main, y, codes=codes[k], meta=metas[k])
         add("gelu_by_torch_then_quantize", gelu_unfused_step, abytes + 2 * n_el * 2, n_el)
+        # the fused producers with a scale per 16 elements and with 16 groups per block
+        o_g16 = F.opts(block=BLOCK, selector=F.SEL_LUT, num_groups=16)
+
+        def ln16_step(i):
+            k = i % N_SETS
+            F.fb4_layernorm_quantize(luts, o16, xs[k], gamma_d, beta_d, 1e-6, codes=codes[k], meta=metas16[k])
+        add("layernorm_quantize_block16", ln16_step, algorithmic_bytes(ROWS, COLS, 16) + 2 * COLS * 4, n_el)
+
+        def ln_g16_step(i):
+            k = i % N_SETS
+            F.fb4_layernorm_quantize(luts, o_g16, xs[k], gamma_d, beta_d, 1e-6, codes=codes[k], meta=metas[k])
+        add("layernorm_quantize_g16", ln_g16_step, abytes + 2 * COLS * 4, n_el)
+
+        def gelu16_step(i):
+            k = i % N_SETS
+            F.fb4_gelu_quantize(luts, o16, xs[k], 1, codes=codes[k], meta=metas16[k])
+        add("gelu_quantize_block16", gelu16_step, algorithmic_bytes(ROWS, COLS, 16), n_el)
+
+        def gelu_g16_step(i):
+            k = i % N_SETS
+            F.fb4_gelu_quantize(luts, o_g16, xs[k], 1, codes=codes[k], meta=metas[k])
+        add("gelu_quantize_g16", gelu_g16_step, abytes, n_el)
         # SeDA (cfg4)
         xm, comp = synth.mixture_activation(rows=ROWS, cols=COLS, seed=4, device="cuda")
         xms = [xm] + [xm.clone() for _ in range(N_SETS - 1)]
@@ -362,7 +384,23 @@ def main():
         def assign_step(i):
             F.fb4_seda_assign(q4, k4, sal_rows, 16, 32, 32, window=5, threshold=5.0)
         add("seda_assign_16x24x1024_window5", assign_step, 1024 * 26 * 24 * 128 * 2 + 2 * 16384 * 4, 16 * 1024)
-        del qa, ka, q4, k4
+        # step 2 of Sec. 3.4 for the same clip: temporal attention (1024 positions x 24 heads, 16 frames), the main
+        # anchor of each of the 64 tiles among its 16 candidates and the pruning of weakly correlated frames
+        qt, kt = synth.attention_qk(1024 * 24, 16, 128, seed=8, device="cuda")
+        att_t = torch.empty((1024 * 24, 16), dtype=torch.float32, device="cuda")
+        F.fb4_attention_scores(qt, kt, 1, scores=att_t)
+        qt4, kt4 = qt.view(1024, 24, 16, 128), kt.view(1024, 24, 16, 128)
+
+        def main_anchor_step(i):
+            F.fb4_seda_main_anchor(att_t.view(1024, 24, 16), qt4, kt4, sal_rows, 32, 32, prune_threshold=3.0)
+        add("seda_main_anchor_64_tiles_16_frames", main_anchor_step, 64 * 17 * 24 * 128 * 2 + 1024 * 24 * 4, 1024)
+        # ... and the 3D variant's main anchors from per-head scores of all 16384 tokens
+        att3 = att.view(16, 24, 1024).transpose(0, 1).contiguous().view(24, 16384)
+
+        def main_anchor_3d_step(i):
+            F.fb4_seda_main_anchor_3d(att3, 16, 32, 32)
+        add("seda_main_anchor_3d_24x16384", main_anchor_3d_step, 24 * 16384 * 4, 16384)
+        del qa, ka, q4, k4, qt, kt, qt4, kt4
         # decomposition (cfg3): 5 % salient rows
         sal = synth.salient_rows_from_attention(ROWS, frac=0.05, heads=24, seed=3, device="cuda")
         sal_d = torch.from_numpy(sal).cuda()

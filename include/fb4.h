@@ -378,7 +378,7 @@ int fb4_select_salient_tokens(const float* scores, int64_t frames, int heads, in
  * The GROUP of an anchor is the row-major number of the tile_h x tile_w spatial
  * tile it lies in, (y / tile_h) * ceil(grid_w / tile_w) + x / tile_w, so the
  * per-frame candidates of one tile share a group -- one sub-formatbook --
- * across the frames (step 1: "N candidates per tile").  A token marked by
+ * across the frames (step 1 yields one candidate per frame for a tile).  A token marked by
  * anchors of several groups belongs to the highest group number (App. D:
  * overlapping windows go to the subsequent anchor = the later tile); an anchor
  * belongs to its own group.

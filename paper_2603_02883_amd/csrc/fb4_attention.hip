@@ -114,9 +114,6 @@ int fb4_seda_main_anchor(const float* temporal_scores, const void* qt, const voi
         return FB4_ERR_UNSUPPORTED;
     if (frames * tokens > 0x7FFFFFFFll || n_cand > 0x7FFFFFFFll || frames * dim > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (n_cand > 0)
-        hipLaunchKernelGGL(seda_fill_kernel, dim3((unsigned)((n_cand + 255) / 256)), dim3(256), 0, s, kept,
-                           static_cast<int32_t*>(nullptr), (uint32_t)n_cand);
     hipLaunchKernelGGL(seda_main_anchor_kernel, dim3((unsigned)tiles), dim3(kMainThreads), 0, s, temporal_scores,
                        static_cast<const uint16_t*>(qt), static_cast<const uint16_t*>(kt), (uint32_t)frames, (uint32_t)heads,
                        (uint32_t)grid_h, (uint32_t)grid_w, (uint32_t)dim, candidates, (uint32_t)n_per_frame, (uint32_t)tile_h,

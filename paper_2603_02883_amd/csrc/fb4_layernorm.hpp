@@ -47,8 +47,12 @@ struct LayerNormParams {
     uint16_t* y_out;              // kWriteY only: [rows][cols] bf16, the producer's result
 };
 
-// threads per workgroup (one workgroup per CU)
-constexpr int ln_threads(int chunks_per_lane) { return chunks_per_lane <= 4 ? 768 : 512; }
+// threads per workgroup (one workgroup per CU): three wavefronts per SIMD where 168 registers hold the kernel,
+// two (up to 256 registers) for five or six chunks per lane and for 16 groups from two chunks per lane on
+constexpr int ln_threads(int chunks_per_lane, int groups = 8)
+{
+    return (chunks_per_lane <= 4 && !(groups > 8 && chunks_per_lane >= 2)) ? 768 : 512;
+}
 constexpr int kLnMaxChunksPerLane = 6;
 constexpr int kLdsLnTables = lds_fast_bytes(false, false, false);
 
@@ -171,7 +175,7 @@ __device__ __noinline__ RowNorm layernorm_row_plain(const uint16_t* xrow, uint32
 // registers instead reads x once but leaves room for 8 wavefronts per CU only, or spills: 42-62 us on a
 // 16384x3072 tensor.)
 // kBlock, G: block size (32 or 16) and number of groups of the online selector (Sec. 3.2, Sec. 4.1).
-template <int B, int kBlock, int G, bool kTwoStage, bool kSeda, bool kWriteY, int kThreads = ln_threads(B)>
+template <int B, int kBlock, int G, bool kTwoStage, bool kSeda, bool kWriteY, int kThreads = ln_threads(B, G)>
 __global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
     const uint8_t* blob, const uint16_t* x, uint32_t n_bundles, uint32_t rw, uint32_t nb, uint32_t n_workgroups,
     long long row_stride, const float* gamma, const float* beta, LayerNormParams p)

@@ -75,7 +75,7 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     if (B == 0) { B = (int)((nb + 63) / 64); rw = 1; }
     if (rw > (uint32_t)rows) rw = (uint32_t)rows;
     const uint32_t n_bundles = (uint32_t)((rows + rw - 1) / rw);
-    const int kLnWaves = ln_threads(B) / 64;
+    const int kLnWaves = ln_threads(B, opts->num_groups) / 64;
     long long g = ((long long)n_bundles + kLnWaves - 1) / kLnWaves;
     if (g > luts->n_cu) g = luts->n_cu;
     const unsigned groups = (unsigned)g;
@@ -95,7 +95,7 @@ int fb4_layernorm_quantize(const fb4_luts* luts, const fb4_opts* opts, const voi
     const bool ts = (opts->flags & FB4_FLAG_TWO_STAGE) != 0;
     const bool seda = token_group != nullptr;
 #define FB4_LN_ARGS luts->dev_blob, static_cast<const uint16_t*>(x), n_bundles, rw, (uint32_t)nb, groups, (long long)row_stride, gamma, beta, p
-#define FB4_LN_LAUNCH(b, blk, g, t, sd, wy) hipLaunchKernelGGL((layernorm_quantize_kernel<b, blk, g, t, sd, wy>), dim3(groups), dim3(ln_threads(b)), 0, s, FB4_LN_ARGS)
+#define FB4_LN_LAUNCH(b, blk, g, t, sd, wy) hipLaunchKernelGGL((layernorm_quantize_kernel<b, blk, g, t, sd, wy>), dim3(groups), dim3(ln_threads(b, g)), 0, s, FB4_LN_ARGS)
 #define FB4_LN_SHAPE(b, blk, g)                                \
     if (seda) {                                                \
         if (ts) FB4_LN_LAUNCH(b, blk, g, true, true, false);   \

@@ -310,11 +310,13 @@ __global__ __launch_bounds__(256) void seda_anchor_kernel(const int32_t* anchors
     anchor_group[row] = g;
 }
 
-// Sec. 3.4, factorized attention, step 2: one workgroup per spatial tile.  Per frame the tile's candidate (the
-// first entry of the frame's list that lies in this tile of this frame) and its temporal mean score averaged over
-// the heads (in double, head by head); the main anchor is the best of them (earliest frame on ties, a NaN never
-// wins); a frame stays if it is the main anchor's or if the raw temporal score from the main anchor to it --
-// Qt[p*][h][f*] . Kt[p*][h][f], head mean in fp32 -- exceeds the threshold.  `kept` was filled with -1 before.
+// Sec. 3.4, factorized attention, step 2: one workgroup per spatial tile, one wavefront per frame at a time.  Per
+// frame the tile's candidate (the first entry of the frame's list that lies in this tile of this frame) and its
+// temporal mean score averaged over the heads (in double, head by head); the main anchor is the best of them
+// (earliest frame on ties, a NaN never wins); a frame stays if it is the main anchor's or if the raw temporal
+// score from the main anchor to it -- Qt[p*][h][f*] . Kt[p*][h][f], head mean in fp32 -- exceeds the threshold.
+// Every entry of `kept` is written exactly once: by the workgroup of the tile the entry lies in (an entry that is
+// no candidate of its frame by the workgroup of tile 0), so no launch has to clear it first.
 constexpr int kMainThreads = 256;
 constexpr uint32_t kMainMaxFrames = 1024;
 
@@ -326,26 +328,42 @@ __global__ __launch_bounds__(kMainThreads) void seda_main_anchor_kernel(
     __shared__ double score[kMainMaxFrames];
     __shared__ int32_t slot[kMainMaxFrames];
     __shared__ int32_t best_frame;
+    constexpr uint32_t kWaves = kMainThreads / 64, kNone = 0xFFFFFFFFu;
     const uint32_t tokens = grid_h * grid_w, tile = blockIdx.x, tiles = gridDim.x;
-    for (uint32_t f = threadIdx.x; f < frames; f += kMainThreads) {
-        int32_t found = -1;
-        for (uint32_t j = 0; j < n_per_frame; ++j) {
-            const int64_t row = cand[(size_t)f * n_per_frame + j];
-            if (row >= (int64_t)f * tokens && row < (int64_t)(f + 1) * tokens &&
-                tile_of((uint32_t)(row - (int64_t)f * tokens), grid_w, tile_h, tile_w) == tile) {
-                found = (int32_t)j;
-                break;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    for (uint32_t f = wave; f < frames; f += kWaves) {
+        const int32_t* list = cand + (size_t)f * n_per_frame;
+        int32_t* out = kept + (size_t)f * n_per_frame;
+        uint32_t found = kNone;
+        for (uint32_t j0 = 0; j0 < n_per_frame; j0 += 64) {
+            const uint32_t j = j0 + lane;
+            bool mine = false;
+            if (j < n_per_frame) {
+                const int64_t row = list[j];
+                const bool valid = row >= (int64_t)f * tokens && row < (int64_t)(f + 1) * tokens;
+                mine = valid && tile_of((uint32_t)(row - (int64_t)f * tokens), grid_w, tile_h, tile_w) == tile;
+                if (!valid && tile == 0) out[j] = -1;
             }
+            const unsigned long long m = __ballot(mine);
+            const uint32_t first = m ? j0 + (uint32_t)__builtin_ctzll(m) : kNone;
+            if (mine && (found != kNone || j != first)) out[j] = -1;   // a later entry of the same tile
+            if (found == kNone) found = first;
         }
-        slot[f] = found;
         double v = 0.0;
-        if (found >= 0) {
-            const uint32_t pos = (uint32_t)(cand[(size_t)f * n_per_frame + found] - (int32_t)(f * tokens));
-            for (uint32_t h = 0; h < heads; ++h) v += (double)temporal_scores[((size_t)pos * heads + h) * frames + f];
+        if (found != kNone) {
+            const uint32_t pos = (uint32_t)(list[found] - (int32_t)(f * tokens));
+            for (uint32_t h0 = 0; h0 < heads; h0 += 64) {
+                const uint32_t cnt = min(64u, heads - h0);
+                const float own = lane < cnt ? temporal_scores[((size_t)pos * heads + h0 + lane) * frames + f] : 0.0f;
+                for (uint32_t i = 0; i < cnt; ++i) v += (double)__shfl(own, (int)i);
+            }
             v /= (double)heads;
             if (v != v) v = -__builtin_inf();
         }
-        score[f] = v;
+        if (lane == 0) {
+            slot[f] = found == kNone ? -1 : (int32_t)found;
+            score[f] = v;
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -360,20 +378,36 @@ __global__ __launch_bounds__(kMainThreads) void seda_main_anchor_kernel(
     }
     __syncthreads();
     const int32_t bf = best_frame;
-    for (uint32_t f = threadIdx.x; f < frames; f += kMainThreads) {
+    const uint32_t n16 = dim / 8;
+    for (uint32_t f = wave; f < frames; f += kWaves) {
         float sc = __builtin_nanf("");
-        if (bf >= 0 && slot[f] >= 0) {
+        if (slot[f] >= 0) {   // (then the tile has a main anchor)
             const uint32_t pos = (uint32_t)(cand[(size_t)bf * n_per_frame + slot[bf]] - (int32_t)((uint32_t)bf * tokens));
+            // 16 lanes share a row's 16-byte pieces, four heads at a time; the wavefront's sum in a fixed order
             float acc = 0.0f;
-            for (uint32_t h = 0; h < heads; ++h) {
+            for (uint32_t h = lane >> 4; h < heads; h += 4) {
                 const size_t base = ((size_t)pos * heads + h) * frames;
-                acc += dot_bf16_rows(qt + (base + (uint32_t)bf) * dim, kt + (base + f) * dim, dim);
+                const uint4* qr = reinterpret_cast<const uint4*>(qt + (base + (uint32_t)bf) * dim);
+                const uint4* kr = reinterpret_cast<const uint4*>(kt + (base + f) * dim);
+                for (uint32_t c = lane & 15u; c < n16; c += 16) {
+                    const uint4 a = qr[c], b = kr[c];
+                    const uint32_t qs[4] = {a.x, a.y, a.z, a.w}, ks[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        acc = __builtin_fmaf(__uint_as_float(qs[i] << 16), __uint_as_float(ks[i] << 16), acc);
+                        acc = __builtin_fmaf(__uint_as_float(qs[i] & 0xFFFF0000u), __uint_as_float(ks[i] & 0xFFFF0000u), acc);
+                    }
+                }
             }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
             sc = acc / (float)heads;
-            if ((int32_t)f == bf || sc > prune_threshold)
-                kept[(size_t)f * n_per_frame + slot[f]] = cand[(size_t)f * n_per_frame + slot[f]];
+            if (lane == 0) {
+                const int32_t row = cand[(size_t)f * n_per_frame + slot[f]];
+                kept[(size_t)f * n_per_frame + slot[f]] = ((int32_t)f == bf || sc > prune_threshold) ? row : -1;
+            }
         }
-        if (prune_scores) prune_scores[(size_t)f * tiles + tile] = sc;
+        if (lane == 0 && prune_scores) prune_scores[(size_t)f * tiles + tile] = sc;
     }
 }
 
