@@ -21,6 +21,14 @@ int fb4_attention_scores(const void* q, const void* k, int64_t groups, int64_t t
     if (tokens * dim > 0x7FFFFFFFll || groups * bpg > 0x7FFFFFFFll) return FB4_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)(groups * bpg));
+    if (dim == kDmaDim && !small && tokens % 128 == 0) {
+        // rows of exactly 128 channels, key halves made of whole 64-key blocks: the kernel that loads straight to LDS
+        if (mode) hipLaunchKernelGGL(attention_scores_dma_kernel<true>, grid, dim3(kScoreThreads), 0, s, static_cast<const uint16_t*>(q),
+                                     static_cast<const uint16_t*>(k), (uint32_t)tokens, (uint32_t)bpg, scores);
+        else hipLaunchKernelGGL(attention_scores_dma_kernel<false>, grid, dim3(kScoreThreads), 0, s, static_cast<const uint16_t*>(q),
+                                static_cast<const uint16_t*>(k), (uint32_t)tokens, (uint32_t)bpg, scores);
+        return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+    }
 #define FB4_SCORE_ARGS static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), (uint32_t)tokens, (uint32_t)dim, (uint32_t)bpg, scores
 #define FB4_SCORE_LAUNCH(d, relu, qb, keys) hipLaunchKernelGGL((attention_scores_kernel<d, relu, qb, keys>), grid, dim3(kScoreThreads), 0, s, FB4_SCORE_ARGS)
 #define FB4_SCORE_CASE(d)                                   \

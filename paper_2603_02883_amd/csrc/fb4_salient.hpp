@@ -133,6 +133,128 @@ __global__ __launch_bounds__(kScoreThreads) void attention_scores_kernel(const u
     }
 }
 
+// The same scores for groups whose rows are exactly 128 channels and whose tokens are a multiple of 128: four blocks
+// of 32 queries per wavefront, so that one 16-byte operand read from LDS feeds four MFMAs (the kernel above feeds
+// two and is bound by that LDS traffic).  128 queries x 128 channels of B operands and four accumulator blocks
+// need about 220 registers; to keep two wavefronts per SIMD beside them, key blocks are not staged through
+// registers: `global_load_lds_dwordx4` writes a wavefront's 64 x 16 bytes straight into LDS.  Those 1 KiB land
+// contiguously, so rows cannot be padded; instead piece p (16 bytes) of key row r sits at position p ^ (r % 16) of
+// the row (the load fetches the matching piece of global memory), which spreads the 16 rows that the lanes of one
+// LDS pass read over all 64 banks.
+// A workgroup of four wavefronts takes 256 queries: wavefront w holds queries 128 (w % 2) .. and walks the keys of
+// half w / 2 of the group, 64 per barrier, from that half's own double-buffered LDS region; the two halves' sums
+// meet in LDS at the end (always half 0 + half 1).
+constexpr int kDmaQB = 4;                  // blocks of 32 queries per wavefront
+constexpr int kDmaQueries = 2 * 32 * kDmaQB;   // per workgroup
+constexpr int kDmaKeys = 64;               // per barrier and half
+constexpr int kDmaDim = 128;
+constexpr uint32_t kDmaBlockBytes = kDmaKeys * kDmaDim * 2;   // 16 KiB
+
+template <bool kRelu>
+__global__ __launch_bounds__(kScoreThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attention_scores_dma_kernel(const uint16_t* q, const uint16_t* k, uint32_t tokens, uint32_t blocks_per_group,
+                                 float* scores)
+{
+    constexpr int kSteps = kDmaDim / 16;
+    // Two buffers per key half, as two arrays: the compiler then sees that the loads into one do not touch the
+    // operand reads from the other and does not wait for them.
+    __shared__ __align__(1024) uint8_t lds_a[2 * kDmaBlockBytes];   // [half], even key blocks
+    __shared__ __align__(1024) uint8_t lds_b[2 * kDmaBlockBytes];   // [half], odd key blocks
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t qset = wave & 1u, kh = wave >> 1;
+    const uint32_t g = blockIdx.x / blocks_per_group;
+    const uint32_t q0 = (blockIdx.x - g * blocks_per_group) * kDmaQueries + qset * (32u * kDmaQB);
+    const uint16_t* qg = q + (size_t)g * tokens * kDmaDim;
+    const uint32_t half_keys = tokens / 2;                       // a multiple of 64
+    const uint8_t* kbase = reinterpret_cast<const uint8_t*>(k + ((size_t)g * tokens + (size_t)kh * half_keys) * kDmaDim);
+    const uint32_t half = lane >> 5, col = lane & 31u;
+
+    // ---- key blocks: this wavefront loads rows 32 (w % 2) .. + 31 of its half's block, eight loads of four rows
+    const uint32_t lrow = lane >> 4, lpos = lane & 15u;          // row within a load, position within the row
+    auto fetch = [&](uint32_t kb, uint8_t* buffer) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t row = qset * 32u + 4u * i + lrow;      // key row of the block
+            const uint8_t* src = kbase + ((size_t)kb * kDmaKeys + row) * (kDmaDim * 2) + ((lpos ^ (row & 15u)) << 4);
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(kh * kDmaBlockBytes + (qset * 32u + 4u * i) * 256u);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(buffer + dst), 16, 0, 0);
+        }
+    };
+    const uint32_t n_kb = half_keys / kDmaKeys;
+    fetch(0, lds_a);
+
+    // ---- this wavefront's queries as B operands (a query past the end reads the last one)
+    mfma_bf16x8 qf[kDmaQB][kSteps];
+#pragma unroll
+    for (int b = 0; b < kDmaQB; ++b) {
+        const uint16_t* row = qg + (size_t)min(q0 + 32u * b + col, tokens - 1u) * kDmaDim;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s)
+            qf[b][s] = __builtin_bit_cast(mfma_bf16x8, *reinterpret_cast<const uint4*>(row + 16u * s + 8u * half));
+    }
+    float sum[kDmaQB];
+#pragma unroll
+    for (int b = 0; b < kDmaQB; ++b) sum[b] = 0.0f;
+    // A operand of step s: key row 32 kk + lane % 32, piece 2 s + lane / 32, swizzled
+    const uint32_t a0 = kh * kDmaBlockBytes + col * 256u + (((col & 15u) ^ half) << 4);
+    auto compute = [&](const uint8_t* buffer) {
+        // the operand of the next step is read while this step's MFMAs run
+        uint4 a_next = *reinterpret_cast<const uint4*>(buffer + a0);
+#pragma unroll
+        for (int kk = 0; kk < kDmaKeys / 32; ++kk) {
+            mfma_f32x16 acc[kDmaQB];
+#pragma unroll
+            for (int b = 0; b < kDmaQB; ++b) acc[b] = mfma_f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s) {
+                const uint4 a = a_next;
+                const int ns = (s + 1) % kSteps, nk = kk + (s + 1) / kSteps;
+                if (nk < kDmaKeys / 32)
+                    a_next = *reinterpret_cast<const uint4*>(buffer + ((a0 ^ ((uint32_t)ns << 5)) + nk * 32 * 256));
+#pragma unroll
+                for (int b = 0; b < kDmaQB; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(mfma_bf16x8, a), qf[b][s], acc[b], 0, 0, 0);
+            }
+#pragma unroll
+            for (int b = 0; b < kDmaQB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum[b] += kRelu ? fmaxf(acc[b][r], 0.0f) : fabsf(acc[b][r]);
+            }
+        }
+    };
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the first block is in LDS
+    __syncthreads();
+    for (uint32_t kb = 0; kb < n_kb; kb += 2) {
+        if (kb + 1 < n_kb) fetch(kb + 1, lds_b);
+        compute(lds_a);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // the next block has landed before anyone reads it
+        __syncthreads();
+        if (kb + 1 < n_kb) {
+            if (kb + 2 < n_kb) fetch(kb + 2, lds_a);
+            compute(lds_b);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+        }
+    }
+    // ---- the two key halves meet: half 1 through LDS, then half 0 + half 1
+    float* meet = reinterpret_cast<float*>(lds_a);               // [query set][128]
+#pragma unroll
+    for (int b = 0; b < kDmaQB; ++b) sum[b] += __shfl_xor(sum[b], 32);   // the two half-wavefronts hold different keys
+    if (kh == 1 && half == 0) {
+#pragma unroll
+        for (int b = 0; b < kDmaQB; ++b) meet[qset * 128u + 32u * b + col] = sum[b];
+    }
+    __syncthreads();
+    if (kh == 0 && half == 0) {
+#pragma unroll
+        for (int b = 0; b < kDmaQB; ++b) {
+            const uint32_t qi = q0 + 32u * b + col;
+            if (qi < tokens) scores[(size_t)g * tokens + qi] = (sum[b] + meet[qset * 128u + 32u * b + col]) / (float)tokens;
+        }
+    }
+}
+
 constexpr int kSelectThreads = 256;
 constexpr uint32_t kSelectMaxTokens = 8192;   // per frame (the head means sit in LDS)
 
