@@ -410,6 +410,19 @@ def main():
         extras["attention_scores_384x1024x128"] = {"us": e_s / steps2 * 1e6, "TFLOP_per_s": flops / (e_s / steps2) / 1e12,
                                                    "mfma_frac": flops / (e_s / steps2) / 1e12 / 2500.0}
 
+        # what the matrix cores sustain on operands held in registers (no memory traffic): with one bit pattern in
+        # every element, and with random signs and mantissas -- the power management lowers the clock for the latter
+        probe_out = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+        for rnd in (0, 1):
+            def probe_step(i, rnd=rnd):
+                F.fb4_probe_mfma_rate(512, 400, rnd, out=probe_out)
+            w_p, e_p = timer(probe_step, steps2, 4 * steps2)
+            pflop = F.fb4_probe_mfma_rate(512, 400, rnd, out=probe_out)[1]
+            extras["mfma_bf16_register_loop_%s_operands" % ("random" if rnd else "constant")] = {
+                "us": e_p / steps2 * 1e6, "TFLOP_per_s": pflop / (e_p / steps2) / 1e12, "mfma_frac": pflop / (e_p / steps2) / 1e12 / 2500.0}
+        extras["attention_scores_384x1024x128"]["frac_of_register_loop_random_operands"] = (
+            extras["attention_scores_384x1024x128"]["TFLOP_per_s"] / extras["mfma_bf16_register_loop_random_operands"]["TFLOP_per_s"])
+
         def select_step(i):
             F.fb4_select_salient_tokens(att.view(16, 24, 1024), 32, 32, rows_out=sal_rows)
         add("select_salient_tokens_16x24x1024", select_step, 16 * 24 * 1024 * 4 + 16 * 64 * 4, 16 * 1024)

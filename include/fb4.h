@@ -35,7 +35,8 @@
  *   - A call made while another device than the handle's is current returns
  *     FB4_ERR_INVALID_ARG.  The entry points without a handle
  *     (fb4_attention_scores, fb4_select_salient_tokens, fb4_seda_assign,
- *     fb4_seda_main_anchor, fb4_seda_main_anchor_3d) run on the current device.
+ *     fb4_seda_main_anchor, fb4_seda_main_anchor_3d, fb4_probe_mfma_rate) run on
+ *     the current device.
  *   - The producer-fused entry points (fb4_layernorm_quantize,
  *     fb4_gelu_quantize) read x as plain IEEE bf16 and hand the quantizer the
  *     producer's bf16 result, to which the rules above then apply.
@@ -458,6 +459,25 @@ int fb4_seda_main_anchor(const float* temporal_scores, const void* qt, const voi
  */
 int fb4_seda_main_anchor_3d(const float* scores, int64_t frames, int heads, int grid_h, int grid_w, int tile_h,
                             int tile_w, int32_t* anchors, void* stream);
+
+/*
+ * Diagnostic, not part of the paper's method: launches a kernel that does
+ * nothing but v_mfma_f32_32x32x16_bf16 on operands held in registers (four
+ * independent accumulator chains per wavefront, four wavefronts per workgroup,
+ * 32 MFMAs per iteration and wavefront), so that a caller who times it learns
+ * the dense bf16 matrix rate this device sustains -- which depends on the
+ * operand data, because the power management lowers the clock under load.
+ * bench.py reports it beside the rate of fb4_attention_scores.
+ *   workgroups        1..65536 (256 threads each; two per compute unit fill
+ *                     the matrix cores)
+ *   iterations        loop count per wavefront
+ *   random_operands   0: one bit pattern in every operand element; otherwise
+ *                     random signs and mantissas, magnitudes in [0.5, 2)
+ *   out               device, float [workgroups * 256]: written so that the
+ *                     loop is not optimized away; the values mean nothing
+ *   flop              host, or NULL: receives the operations the launch performs
+ */
+int fb4_probe_mfma_rate(int64_t workgroups, int64_t iterations, int random_operands, float* out, double* flop, void* stream);
 
 #ifdef __cplusplus
 }

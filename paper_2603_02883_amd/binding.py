@@ -73,6 +73,7 @@ def _load():
                                     p, p]
     lib.fb4_seda_main_anchor.argtypes = [p, p, p, i64, i32, i32, i32, i64, p, i32, i32, i32, ctypes.c_float, p, p, p, p]
     lib.fb4_seda_main_anchor_3d.argtypes = [p, i64, i32, i32, i32, i32, i32, p, p]
+    lib.fb4_probe_mfma_rate.argtypes = [i64, i64, i32, p, ctypes.POINTER(ctypes.c_double), p]
     lib.fb4_gelu_table_host.argtypes = [i32, p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
     lib.fb4_gelu_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, i32, p, p, i32, p, p, p]
     lib.fb4_layernorm_quantize.argtypes = [p, ctypes.POINTER(fb4_opts), p, i64, i64, i64, p, p, ctypes.c_float, p, p, i32,
@@ -87,7 +88,7 @@ EXPORTS = ["fb4_version", "fb4_strerror", "fb4_workspace_bytes", "fb4_build_luts
            "fb4_quantize_decompose", "fb4_seda_profile",
            "fb4_repack_mxfp8", "fb4_layernorm_quantize", "fb4_gelu_quantize",
            "fb4_gelu_table_host", "fb4_attention_scores", "fb4_select_salient_tokens",
-           "fb4_seda_assign", "fb4_seda_main_anchor", "fb4_seda_main_anchor_3d"]
+           "fb4_seda_assign", "fb4_seda_main_anchor", "fb4_seda_main_anchor_3d", "fb4_probe_mfma_rate"]
 
 
 def lib():
@@ -268,6 +269,16 @@ def fb4_seda_main_anchor_3d(scores, frames, grid_h, grid_w, tile_h=4, tile_w=4, 
     _check(_lib.fb4_seda_main_anchor_3d(_dp(scores), frames, heads, grid_h, grid_w, tile_h, tile_w, _dp(anchors),
                                         _stream(stream)), "fb4_seda_main_anchor_3d")
     return anchors
+
+
+def fb4_probe_mfma_rate(workgroups, iterations, random_operands=True, out=None, stream=None):
+    """Diagnostic launch of a register-only bf16 MFMA loop; returns (out, operations performed)."""
+    if out is None:
+        out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    flop = ctypes.c_double(0.0)
+    _check(_lib.fb4_probe_mfma_rate(int(workgroups), int(iterations), int(bool(random_operands)), _dp(out), ctypes.byref(flop),
+                                    _stream(stream)), "fb4_probe_mfma_rate")
+    return out, flop.value
 
 
 def fb4_gelu_table_host(approximate=0):

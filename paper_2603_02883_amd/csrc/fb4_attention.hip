@@ -143,4 +143,15 @@ int fb4_seda_main_anchor_3d(const float* scores, int64_t frames, int heads, int 
     return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
 }
 
+int fb4_probe_mfma_rate(int64_t workgroups, int64_t iterations, int random_operands, float* out, double* flop, void* stream)
+{
+    if (workgroups < 1 || workgroups > 65536 || iterations < 0 || iterations > 0x7FFFFFFFll || !out) return FB4_ERR_INVALID_ARG;
+    if (!aligned(out, 4)) return FB4_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(probe_mfma_rate_kernel, dim3((unsigned)workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), out,
+                       (uint32_t)iterations, (uint32_t)(random_operands != 0));
+    // four wavefronts x 8 x 4 MFMAs of 32 x 32 x 16 per iteration, two operations per multiply-add
+    if (flop) *flop = (double)workgroups * 4.0 * (double)iterations * 32.0 * (2.0 * 32 * 32 * 16);
+    return hipGetLastError() == hipSuccess ? FB4_OK : FB4_ERR_HIP;
+}
+
 }  // extern "C"

@@ -27,6 +27,7 @@ namespace fb4 {
 
 typedef __bf16 mfma_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float mfma_f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t lds_u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kScoreThreads = 256;
 // Two shapes of the kernel: 64 queries per wavefront and 64 keys per barrier for long groups (spatial / 3D
@@ -253,6 +254,41 @@ void attention_scores_dma_kernel(const uint16_t* q, const uint16_t* k, uint32_t 
             if (qi < tokens) scores[(size_t)g * tokens + qi] = (sum[b] + meet[qset * 128u + 32u * b + col]) / (float)tokens;
         }
     }
+}
+
+// Diagnostic: the rate at which this device sustains v_mfma_f32_32x32x16_bf16 on operands held in registers -- four
+// independent accumulator chains per wavefront, no memory traffic inside the loop -- so that the attention
+// kernel's rate can be read against what the matrix cores deliver at the clock the power management allows.
+// random != 0: operands with random signs and mantissas (magnitudes in [0.5, 2)), as real activations toggle
+// the datapath; random == 0: the same bit pattern in every element.
+__global__ __launch_bounds__(256) void probe_mfma_rate_kernel(float* out, uint32_t iters, uint32_t random)
+{
+    auto word = [&](uint32_t i) {
+        uint32_t h = (threadIdx.x * 2654435761u + i * 40503u + blockIdx.x) * 2246822519u;
+        h ^= h >> 13;
+        h *= 3266489917u;
+        h ^= h >> 16;
+        return random ? ((h & 0x80FF80FFu) | 0x3F003F00u) : 0x3F803F80u;   // two bf16 per word
+    };
+    const lds_u32x4 av = {word(1), word(2), word(3), word(4)}, bv = {word(5), word(6), word(7), word(8)};
+    const mfma_bf16x8 a = __builtin_bit_cast(mfma_bf16x8, av), b = __builtin_bit_cast(mfma_bf16x8, bv);
+    mfma_f32x16 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = mfma_f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (uint32_t i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[c][r];
+    }
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
 constexpr int kSelectThreads = 256;

@@ -1246,7 +1246,11 @@ def test_attention_scores_against_the_oracle(F, mode):
     in the sum over keys; a single dot product loses at most sqrt(dim) * 2^-24 of its operands' magnitude)."""
     # (groups of up to 64 tokens -- temporal attention -- run the small shape of the kernel, longer ones the large)
     for groups, tokens, dim in [(3, 100, 64), (2, 1024, 128), (5, 33, 72), (1, 1, 8), (2, 257, 256), (4, 128, 40),
-                                (2, 300, 96), (1, 2049, 16), (300, 16, 72), (50, 64, 128), (7, 65, 64), (3, 513, 200)]:
+                                (2, 300, 96), (1, 2049, 16), (300, 16, 72), (50, 64, 128), (7, 65, 64), (3, 513, 200),
+                                # rows of 128 channels and a multiple of 128 tokens take the kernel that loads key blocks
+                                # straight into LDS: one block per key half, an odd number of blocks, a last workgroup
+                                # with 128 of its 256 queries, several workgroups per group; (2, 200, 128) does not
+                                (3, 128, 128), (2, 384, 128), (1, 640, 128), (2, 2048, 128), (2, 200, 128)]:
         q, k = synth.attention_qk(groups, tokens, dim, seed=tokens + dim, device="cuda")
         got = F.fb4_attention_scores(q, k, mode).cpu().numpy().astype(np.float64)
         torch.cuda.synchronize()
@@ -1263,6 +1267,24 @@ def test_attention_scores_against_the_oracle(F, mode):
     got = F.fb4_attention_scores(q, k, mode).cpu().numpy()
     ref = O.attention_scores(synth.bf16_bits(q), synth.bf16_bits(k), "relu" if mode else "abs")
     assert np.array_equal(got, ref.astype(np.float32))          # sums of small integers / 200: one rounding each
+    qb = (rng.random((2, 384, 128)) < 0.3).astype(np.float32) * np.where(rng.random((2, 384, 128)) < 0.5, -1, 1)
+    kb = (rng.random((2, 384, 128)) < 0.3).astype(np.float32)
+    q, k = torch.from_numpy(qb).cuda().bfloat16(), torch.from_numpy(kb).cuda().bfloat16()
+    got = F.fb4_attention_scores(q, k, mode).cpu().numpy()
+    ref = O.attention_scores(synth.bf16_bits(q), synth.bf16_bits(k), "relu" if mode else "abs")
+    assert np.array_equal(got, ref.astype(np.float32))          # the same through the other kernel
+
+
+def test_mfma_rate_probe_runs_and_counts_its_operations(F):
+    out, flop = F.fb4_probe_mfma_rate(8, 3, True)
+    torch.cuda.synchronize()
+    assert flop == 8 * 4 * 3 * 32 * 2 * 32 * 32 * 16 and out.shape == (8 * 256,) and bool(torch.isfinite(out).all())
+    out0, _ = F.fb4_probe_mfma_rate(8, 3, False)
+    # one bit pattern (1.0) everywhere: every accumulator is 3 * 8 * 16 products of 1, sixteen per lane and chain
+    assert bool((out0 == 3 * 8 * 16 * 64).all())
+    lib = F.binding.lib()
+    assert lib.fb4_probe_mfma_rate(0, 1, 1, out.data_ptr(), None, None) == F.ERR_INVALID_ARG
+    assert lib.fb4_probe_mfma_rate(8, 1, 1, None, None, None) == F.ERR_INVALID_ARG
 
 
 def test_salient_token_selection_and_the_whole_chain(F, luts):
