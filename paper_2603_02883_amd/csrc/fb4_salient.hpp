@@ -30,6 +30,15 @@ typedef float mfma_f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t lds_u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kScoreThreads = 256;
+
+// Workgroups are dealt to the eight XCDs in turn, and each XCD has its own L2.  The workgroups of one attention
+// group read the same keys, so they should share an L2: workgroup b works on position (b % 8) * (n / 8) + b / 8
+// of the launch, which puts consecutive positions on one XCD (the last n % 8 workgroups keep their own number).
+__device__ __forceinline__ uint32_t xcd_local_position(uint32_t b, uint32_t n)
+{
+    const uint32_t chunk = n / 8u;
+    return b < chunk * 8u ? (b % 8u) * chunk + b / 8u : b;
+}
 // Two shapes of the kernel: 64 queries per wavefront and 64 keys per barrier for long groups (spatial / 3D
 // attention), 32 and 32 for short ones (temporal attention: a group is a handful of frames).
 constexpr uint32_t kScoreShortGroup = 64;   // tokens up to which the small shape is used
@@ -46,8 +55,9 @@ __global__ __launch_bounds__(kScoreThreads) void attention_scores_kernel(const u
     constexpr int kRowBytes = D32 * 64 + 16;         // one key row in LDS: channels, then 16 bytes of padding
     __shared__ __align__(16) uint8_t lds[2][kScoreKeys * kRowBytes];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t g = blockIdx.x / blocks_per_group;
-    const uint32_t q0 = (blockIdx.x - g * blocks_per_group) * kScoreQueries + wave * (32u * kScoreQB);
+    const uint32_t pos = xcd_local_position(blockIdx.x, gridDim.x);
+    const uint32_t g = pos / blocks_per_group;
+    const uint32_t q0 = (pos - g * blocks_per_group) * kScoreQueries + wave * (32u * kScoreQB);
     const uint16_t* qg = q + (size_t)g * tokens * dim;
     const uint16_t* kg = k + (size_t)g * tokens * dim;
     const uint32_t half = lane >> 5, col = lane & 31u;
@@ -163,8 +173,9 @@ void attention_scores_dma_kernel(const uint16_t* q, const uint16_t* k, uint32_t 
     __shared__ __align__(1024) uint8_t lds_b[2 * kDmaBlockBytes];   // [half], odd key blocks
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t qset = wave & 1u, kh = wave >> 1;
-    const uint32_t g = blockIdx.x / blocks_per_group;
-    const uint32_t q0 = (blockIdx.x - g * blocks_per_group) * kDmaQueries + qset * (32u * kDmaQB);
+    const uint32_t pos = xcd_local_position(blockIdx.x, gridDim.x);
+    const uint32_t g = pos / blocks_per_group;
+    const uint32_t q0 = (pos - g * blocks_per_group) * kDmaQueries + qset * (32u * kDmaQB);
     const uint16_t* qg = q + (size_t)g * tokens * kDmaDim;
     const uint32_t half_keys = tokens / 2;                       // a multiple of 64
     const uint8_t* kbase = reinterpret_cast<const uint8_t*>(k + ((size_t)g * tokens + (size_t)kh * half_keys) * kDmaDim);
