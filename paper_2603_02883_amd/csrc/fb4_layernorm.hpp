@@ -231,6 +231,7 @@ __global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
     const float n_channels = (float)p.cols;
     const float inv_channels = 1.0f / n_channels;
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3F803F80u);
 
     while (u < n_bundles) {
         uint32_t claim = 0;
@@ -239,25 +240,23 @@ __global__ __launch_bounds__(kThreads) void layernorm_quantize_kernel(
         bool ok[B];
 #pragma unroll
         for (int j = 0; j < B; ++j) ok[j] = valid[j] && u * rw + rloc[j] < p.rows;
-        // ---- first walk: per chunk the sum (plain fp32 additions) and the sum of squares (one two-element bf16
-        // dot product with fp32 accumulation per register, the register with itself)
+        // ---- first walk: per chunk the sum and the sum of squares, each by one two-element bf16 dot product with
+        // fp32 accumulation per register (the register with a pair of ones, and with itself)
         float part[B], part2[B];
 #pragma unroll
         for (int j = 0; j < B; ++j) {
             const int s = j;
             request(u, (j + 1) % B, buf[(s + 1) & 1], gbuf[(s + 1) & 1]);   // (after the last chunk: the first again)
             const uint32_t (&w)[16] = buf[s & 1];
-            float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f, q0 = 0.0f, q1 = 0.0f;
+            float a0 = 0.0f, a1 = 0.0f, q0 = 0.0f, q1 = 0.0f;
 #pragma unroll
             for (int k = 0; k < 16; k += 2) {
-                a0 += __uint_as_float(w[k] << 16);
-                a1 += __uint_as_float(w[k] & 0xFFFF0000u);
-                a2 += __uint_as_float(w[k + 1] << 16);
-                a3 += __uint_as_float(w[k + 1] & 0xFFFF0000u);
+                a0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[k]), ones, a0, false);
+                a1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[k + 1]), ones, a1, false);
                 q0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[k]), __builtin_bit_cast(bf16x2, w[k]), q0, false);
                 q1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[k + 1]), __builtin_bit_cast(bf16x2, w[k + 1]), q1, false);
             }
-            part[j] = ok[j] ? (a0 + a1) + (a2 + a3) : 0.0f;
+            part[j] = ok[j] ? a0 + a1 : 0.0f;
             part2[j] = ok[j] ? q0 + q1 : 0.0f;
             __builtin_amdgcn_sched_barrier(0);
         }
