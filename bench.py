@@ -132,30 +132,38 @@ def selector_agreement(F, luts, synth):
     return {"selector_agreement": out, "reference": "exhaustive squared-error selector", "block": 32}
 
 
-def pruning_study():
+def pruning_study(n_wavefronts=512):
     """CPU only (numpy, no library, no oracle): how much work exact early-exit pruning of the exhaustive selector
-    could save on the first 32,768 blocks of cfg2.  A dialect is dropped for a block once its partial squared
-    error exceeds the total of the best dialect (the most favourable incumbent there is); a wavefront, which
-    holds 64 blocks in its lanes, executes the union of their surviving dialects."""
+    could save on the first n_wavefronts * 64 blocks of cfg2.  A dialect is dropped for a block once its partial
+    squared error exceeds the total of the best dialect (the most favourable incumbent there is); a wavefront,
+    which holds 64 blocks in its lanes, executes the union of their surviving dialects."""
     import numpy as np
 
     from fb4_inputs import DEFAULT_FORMATBOOK, synth
     fbk = np.asarray(DEFAULT_FORMATBOOK, dtype=np.float64)
-    x = synth.vdit_activation(rows=1024, cols=3072, seed=2, device="cpu").float().numpy().astype(np.float64)
-    blocks = np.abs(x.reshape(-1, 32))[:64 * 512]
-    e = np.floor(np.log2(np.maximum(blocks.max(1), 1e-30)))
-    xn = blocks * 2.0 ** (3 - e)[:, None]
-    err = np.abs(xn[:, :, None, None] - fbk[None, None, :, :]).min(-1) ** 2      # [block][element][dialect]
-    sse = err.sum(1)
-    srt = np.sort(sse, 1)
-    z_best = (xn ** 2).sum(1) - srt[:, 0]
-    alive = np.cumsum(err, 1) <= srt[:, :1, None] + 1e-12                        # [block][elements seen][dialect]
-    per_block = alive.sum(2).mean(0)
-    union = alive.reshape(-1, 64, 32, 32).any(1).sum(2).mean(0)
+    n_blocks = 64 * n_wavefronts
+    rows = (n_blocks * 32 + 3071) // 3072
+    x = synth.vdit_activation(rows=rows, cols=3072, seed=2, device="cpu").float().numpy().astype(np.float64)
+    blocks = np.abs(x.reshape(-1, 32))[:n_blocks]
+    per_block = np.zeros(32)
+    union = np.zeros(32)
+    gaps = []
+    for lo in range(0, n_blocks, 64 * 32):                                            # 32 wavefronts at a time
+        blk = blocks[lo:lo + 64 * 32]
+        e = np.floor(np.log2(np.maximum(blk.max(1), 1e-30)))
+        xn = blk * 2.0 ** (3 - e)[:, None]
+        err = np.abs(xn[:, :, None, None] - fbk[None, None, :, :]).min(-1) ** 2      # [block][element][dialect]
+        srt = np.sort(err.sum(1), 1)
+        gaps.append((srt[:, 1] - srt[:, 0]) / np.maximum((xn ** 2).sum(1) - srt[:, 0], 1e-300))
+        alive = np.cumsum(err, 1) <= srt[:, :1, None] + 1e-12                        # [block][elements seen][dialect]
+        per_block += alive.sum(2).sum(0)
+        union += alive.reshape(-1, 64, 32, 32).any(1).sum(2).sum(0)
+    per_block /= n_blocks
+    union /= n_wavefronts
     work = lambda a: float(np.concatenate([[32.0], a[:-1]]).sum() / 1024)
     return {"pruning_study": {
-        "blocks": int(blocks.shape[0]),
-        "median_gap_best_to_runner_up_rel_to_Z": float(np.median((srt[:, 1] - srt[:, 0]) / z_best)),
+        "blocks": int(n_blocks),
+        "median_gap_best_to_runner_up_rel_to_Z": float(np.median(np.concatenate(gaps))),
         "alive_dialects_per_block_after_8_16_24_32_elements": [float(per_block[k]) for k in (7, 15, 23, 31)],
         "alive_in_wavefront_union_after_8_16_24_32_elements": [float(union[k]) for k in (7, 15, 23, 31)],
         "work_fraction_per_block_pruning": work(per_block), "work_fraction_wavefront_union": work(union)}}

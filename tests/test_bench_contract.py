@@ -54,3 +54,14 @@ def test_profile_summary_turns_counter_csvs_into_the_traffic_figure(tmp_path):
     assert int(got["traffic_bytes_per_launch"]) == int(round((49202.0 * 2.0 + 27648.0) * 1024))
     assert got["kernel_trace_average_ns"] == "23500.0"
     assert ps.read_summary(str(tmp_path / "missing.txt")) == {}
+
+
+def test_pruning_study_is_consistent():
+    # bench.py --pruning-study on a small sample: the union over a wavefront's blocks can only keep more dialects
+    # alive than a block alone, all 32 are alive at the start, and at least the best one at the end
+    import bench
+    r = bench.pruning_study(n_wavefronts=4)["pruning_study"]
+    a, u = r["alive_dialects_per_block_after_8_16_24_32_elements"], r["alive_in_wavefront_union_after_8_16_24_32_elements"]
+    assert r["blocks"] == 256 and all(1.0 <= x <= y <= 32.0 for x, y in zip(a, u))
+    assert a == sorted(a, reverse=True) and u == sorted(u, reverse=True)
+    assert 0.0 < r["work_fraction_per_block_pruning"] <= r["work_fraction_wavefront_union"] <= 1.0
