@@ -245,15 +245,16 @@ def fb4_seda_assign(q, k, anchors, frames, grid_h, grid_w, tile_h=4, tile_w=4, w
 
 
 def fb4_seda_main_anchor(temporal_scores, qt, kt, candidates, grid_h, grid_w, tile_h=4, tile_w=4, prune_threshold=3.0,
-                         want_scores=False, stream=None):
+                         want_scores=False, stream=None, main_anchor=None, kept=None):
     """temporal_scores: float32 cuda [tokens][heads][frames]; qt, kt: bf16 cuda [tokens][heads][frames][dim];
     candidates: int32 cuda [frames][n].  Returns (main_anchor int32 [tiles], kept int32 [frames][n]) and the compared
     scores float32 [frames][tiles] if asked."""
     tokens, heads, frames, dim = qt.shape
     assert tokens == grid_h * grid_w and candidates.shape[0] == frames
     tiles = ((grid_h + tile_h - 1) // tile_h) * ((grid_w + tile_w - 1) // tile_w)
-    main = torch.empty(tiles, dtype=torch.int32, device=qt.device)
-    kept = torch.empty_like(candidates)
+    main = torch.empty(tiles, dtype=torch.int32, device=qt.device) if main_anchor is None else main_anchor
+    if kept is None:
+        kept = torch.empty_like(candidates)
     ps = torch.empty((frames, tiles), dtype=torch.float32, device=qt.device) if want_scores else None
     _check(_lib.fb4_seda_main_anchor(_dp(temporal_scores), _dp(qt), _dp(kt), frames, heads, grid_h, grid_w, dim,
                                      _dp(candidates), candidates.shape[1], tile_h, tile_w, float(prune_threshold),
@@ -261,11 +262,12 @@ def fb4_seda_main_anchor(temporal_scores, qt, kt, candidates, grid_h, grid_w, ti
     return (main, kept, ps) if want_scores else (main, kept)
 
 
-def fb4_seda_main_anchor_3d(scores, frames, grid_h, grid_w, tile_h=4, tile_w=4, stream=None):
+def fb4_seda_main_anchor_3d(scores, frames, grid_h, grid_w, tile_h=4, tile_w=4, stream=None, anchors=None):
     """scores: float32 cuda [heads][frames * tokens].  Returns int32 [tiles]: the main anchor of every spatial tile."""
     heads = scores.shape[0]
     tiles = ((grid_h + tile_h - 1) // tile_h) * ((grid_w + tile_w - 1) // tile_w)
-    anchors = torch.empty(tiles, dtype=torch.int32, device=scores.device)
+    if anchors is None:
+        anchors = torch.empty(tiles, dtype=torch.int32, device=scores.device)
     _check(_lib.fb4_seda_main_anchor_3d(_dp(scores), frames, heads, grid_h, grid_w, tile_h, tile_w, _dp(anchors),
                                         _stream(stream)), "fb4_seda_main_anchor_3d")
     return anchors

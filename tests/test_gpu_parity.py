@@ -771,18 +771,29 @@ def test_entry_points_replay_correctly_from_a_hip_graph(F, luts):
         F.fb4_select_salient_tokens(att.view(2, 3, 256), 16, 16, rows_out=anch)
         F.fb4_seda_assign(qv.view(2, 3, 256, 128), kv.view(2, 3, 256, 128), anch, 2, 16, 16, window=5, threshold=4.0,
                           token_group=tgo, anchor_group=ago)
+        # step 2 on the same bits read as temporal projections [256 positions][3 heads][2 frames][128], and the 3D
+        # variant's main anchors from the scores read as [3 heads][2 * 256 tokens]
+        F.fb4_attention_scores(qv.view(768, 2, 128), kv.view(768, 2, 128), 1, scores=att_t)
+        F.fb4_seda_main_anchor(att_t.view(256, 3, 2), qv.view(256, 3, 2, 128), kv.view(256, 3, 2, 128), anch, 16, 16,
+                               prune_threshold=0.0, main_anchor=main_a, kept=kept_a)
+        F.fb4_seda_main_anchor_3d(att.view(3, 512), 2, 16, 16, anchors=anch3)
 
     qk = torch.empty((2, 2 * 3 * 256 * 128), dtype=torch.bfloat16, device="cuda")
     qv, kv = qk[0].view(6, 256, 128), qk[1].view(6, 256, 128)
     att = torch.empty((6, 256), dtype=torch.float32, device="cuda")
     anch = torch.empty((2, 16), dtype=torch.int32, device="cuda")
     tgo = torch.empty(512, dtype=torch.int32, device="cuda")
+    att_t = torch.empty((768, 2), dtype=torch.float32, device="cuda")
+    main_a = torch.empty(16, dtype=torch.int32, device="cuda")
+    kept_a = torch.empty((2, 16), dtype=torch.int32, device="cuda")
+    anch3 = torch.empty(16, dtype=torch.int32, device="cuda")
     ago = torch.empty(512, dtype=torch.int32, device="cuda")
     c2b, m2b, c3, m3 = torch.empty_like(c2), torch.empty_like(m2), torch.empty_like(c1), torch.empty_like(m1)
     c4, m4, c5, m5 = torch.empty_like(c1), torch.empty_like(m1), torch.empty_like(c1), torch.empty_like(m1)
     gamma, beta = (torch.from_numpy(a).cuda() for a in synth.layernorm_affine(cols, seed=70))
     o_sse = F.opts(selector=F.SEL_SSE)
-    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms, c2b, m2b, c3, m3, c4, m4, c5, m5, att, anch, tgo, ago)
+    outs = (c1, m1, c2, m2, y, el, sc, counts, sub, cs, ms, c2b, m2b, c3, m3, c4, m4, c5, m5, att, anch, tgo, ago, att_t, main_a,
+            kept_a, anch3)
     x.copy_(synth.vdit_activation(rows=rows, cols=cols, seed=70, device="cuda"))
     qk.copy_(synth.vdit_activation(rows=2, cols=qk.shape[1], seed=170, device="cuda"))
     sequence()                                                # warm-up outside the capture
