@@ -261,3 +261,110 @@ def test_gelu_table_equals_the_oracle_on_every_pattern_it_covers():
         assert np.array_equal(t[ident], k[ident].astype(np.uint16)) and (t[0x7F81:0x8000] == 0x7FC0).all()
     with pytest.raises(F.Fb4Error):
         F.fb4_gelu_table_host(2)
+
+
+def test_argument_validation_of_the_attention_guided_entry_points():
+    """Every check below returns before any GPU work: no device is needed (pointers are host buffers that are
+    never dereferenced)."""
+    lib = B.lib()
+    buf = ctypes.create_string_buffer(4096 + 64)
+    al = (ctypes.addressof(buf) + 63) // 64 * 64
+    P = ctypes.c_void_p
+    a = lib.fb4_attention_scores
+    assert a(P(al), P(al), 0, 16, 64, 0, P(al), None) == F.OK                       # no groups: no-op
+    assert a(P(al), P(al), 2, 0, 64, 0, P(al), None) == F.OK                        # no tokens: no-op
+    assert a(P(al), P(al), -1, 16, 64, 0, P(al), None) == F.ERR_INVALID_ARG
+    assert a(P(al), P(al), 2, 16, 64, 2, P(al), None) == F.ERR_INVALID_ARG          # mode
+    assert a(None, P(al), 2, 16, 64, 0, P(al), None) == F.ERR_INVALID_ARG
+    assert a(P(al), P(al), 2, 16, 64, 0, None, None) == F.ERR_INVALID_ARG
+    assert a(P(al), P(al), 2, 16, 0, 0, P(al), None) == F.ERR_INVALID_ARG           # no channels
+    assert a(P(al), P(al), 2, 16, 60, 0, P(al), None) == F.ERR_UNSUPPORTED          # channels % 8
+    assert a(P(al), P(al), 2, 16, 264, 0, P(al), None) == F.ERR_UNSUPPORTED         # channels > 256
+    assert a(P(al + 8), P(al), 2, 16, 64, 0, P(al), None) == F.ERR_UNSUPPORTED      # alignment
+    s = lib.fb4_select_salient_tokens
+    assert s(P(al), 0, 2, 8, 8, 4, 4, P(al), None) == F.OK                          # no frames
+    assert s(P(al), 2, 0, 8, 8, 4, 4, P(al), None) == F.ERR_INVALID_ARG             # no heads
+    assert s(P(al), 2, 2, 8, 8, 0, 4, P(al), None) == F.ERR_INVALID_ARG             # tile height 0
+    assert s(None, 2, 2, 8, 8, 4, 4, P(al), None) == F.ERR_INVALID_ARG
+    assert s(P(al), 2, 2, 128, 128, 4, 4, P(al), None) == F.ERR_UNSUPPORTED         # more than 8192 tokens
+    g = lib.fb4_seda_assign
+    ok_args = dict(q=P(al), k=P(al), joint=0, frames=2, heads=2, gh=8, gw=8, dim=64, anchors=P(al), n=4, th=4, tw=4, window=5,
+                   wt=1, thr=5.0, tg=P(al), ag=P(al), sc=None)
+
+    def assign(**kw):
+        v = dict(ok_args, **kw)
+        return g(v["q"], v["k"], v["joint"], v["frames"], v["heads"], v["gh"], v["gw"], v["dim"], v["anchors"], v["n"], v["th"],
+                 v["tw"], v["window"], v["wt"], v["thr"], v["tg"], v["ag"], v["sc"], None)
+    assert assign(frames=0) == F.OK
+    assert assign(joint=2) == F.ERR_INVALID_ARG
+    assert assign(wt=3) == F.ERR_INVALID_ARG                                        # no scores across frames without joint
+    assert assign(thr=float("nan")) == F.ERR_INVALID_ARG
+    assert assign(window=0) == F.ERR_INVALID_ARG
+    assert assign(tg=None) == F.ERR_INVALID_ARG
+    assert assign(anchors=None) == F.ERR_INVALID_ARG
+    assert assign(window=9) == F.ERR_UNSUPPORTED
+    assert assign(joint=1, wt=65) == F.ERR_UNSUPPORTED
+    assert assign(dim=60) == F.ERR_UNSUPPORTED
+    assert assign(q=P(al + 2)) == F.ERR_UNSUPPORTED
+    m = lib.fb4_seda_main_anchor
+
+    def main(ts=P(al), qt=P(al), kt=P(al), frames=3, heads=2, gh=8, gw=8, dim=64, cand=P(al), n=4, th=4, tw=4, thr=3.0,
+             out=P(al), kept=P(al), sc=None):
+        return m(ts, qt, kt, frames, heads, gh, gw, dim, cand, n, th, tw, thr, out, kept, sc, None)
+    assert main(heads=0) == F.ERR_INVALID_ARG
+    assert main(thr=float("nan")) == F.ERR_INVALID_ARG
+    assert main(out=None) == F.ERR_INVALID_ARG
+    assert main(kept=None) == F.ERR_INVALID_ARG
+    assert main(cand=None) == F.ERR_INVALID_ARG
+    assert main(frames=1025) == F.ERR_UNSUPPORTED
+    assert main(dim=12) == F.ERR_UNSUPPORTED
+    assert main(qt=P(al + 4)) == F.ERR_UNSUPPORTED
+    d3 = lib.fb4_seda_main_anchor_3d
+    assert d3(P(al), 0, 2, 8, 8, 4, 4, P(al), None) == F.ERR_INVALID_ARG            # no frames
+    assert d3(None, 2, 2, 8, 8, 4, 4, P(al), None) == F.ERR_INVALID_ARG
+    assert d3(P(al), 2, 2, 8, 8, 4, 4, None, None) == F.ERR_INVALID_ARG
+    assert d3(P(al + 2), 2, 2, 8, 8, 4, 4, P(al), None) == F.ERR_UNSUPPORTED
+    pr = lib.fb4_probe_mfma_rate
+    assert pr(0, 1, 1, P(al), None, None) == F.ERR_INVALID_ARG
+    assert pr(70000, 1, 1, P(al), None, None) == F.ERR_INVALID_ARG
+    assert pr(8, -1, 1, P(al), None, None) == F.ERR_INVALID_ARG
+    assert pr(8, 1, 1, None, None, None) == F.ERR_INVALID_ARG
+
+
+def test_argument_validation_of_the_fused_producers():
+    lib = B.lib()
+    fake = ctypes.create_string_buffer(16384)               # stands in for a handle; never dereferenced
+    h = ctypes.cast(fake, ctypes.c_void_p)
+    buf = ctypes.create_string_buffer(4096 + 64)
+    al = (ctypes.addressof(buf) + 63) // 64 * 64
+    P = ctypes.c_void_p
+    good = F.opts()
+    ln = lib.fb4_layernorm_quantize
+
+    def layernorm(handle=h, o=good, x=P(al), rows=2, cols=64, stride=64, gamma=P(al), beta=P(al), eps=1e-6, tg=None, sub=None,
+                  ng=0, codes=P(al), meta=P(al), y=None):
+        return ln(handle, ctypes.byref(o) if o is not None else None, x, rows, cols, stride, gamma, beta, eps, tg, sub, ng,
+                  codes, meta, y, None)
+    assert layernorm(handle=None) == F.ERR_INVALID_ARG
+    assert layernorm(o=None) == F.ERR_INVALID_ARG
+    assert layernorm(rows=0, codes=None, meta=None) == F.OK
+    assert layernorm(eps=-1.0) == F.ERR_INVALID_ARG
+    assert layernorm(eps=float("nan")) == F.ERR_INVALID_ARG
+    assert layernorm(x=None) == F.ERR_INVALID_ARG
+    assert layernorm(tg=P(al)) == F.ERR_INVALID_ARG                                 # half a SeDA spec
+    assert layernorm(o=F.opts(selector=0)) == F.ERR_UNSUPPORTED                     # the online selector only
+    assert layernorm(o=F.opts(num_groups=32)) == F.ERR_UNSUPPORTED
+    assert layernorm(cols=40, stride=40) == F.ERR_UNSUPPORTED                       # whole 32-element chunks
+    assert layernorm(cols=12320, stride=12320) == F.ERR_UNSUPPORTED                 # rows longer than 12288
+    assert layernorm(gamma=P(al + 2)) == F.ERR_UNSUPPORTED
+    ge = lib.fb4_gelu_quantize
+
+    def gelu(handle=h, o=good, x=P(al), rows=2, cols=64, stride=64, approx=1, tg=None, sub=None, ng=0, codes=P(al), meta=P(al)):
+        return ge(handle, ctypes.byref(o) if o is not None else None, x, rows, cols, stride, approx, tg, sub, ng, codes, meta, None)
+    assert gelu(handle=None) == F.ERR_INVALID_ARG
+    assert gelu(approx=2) == F.ERR_INVALID_ARG
+    assert gelu(rows=0, codes=None, meta=None) == F.OK
+    assert gelu(o=F.opts(selector=0)) == F.ERR_UNSUPPORTED
+    assert gelu(o=F.opts(num_groups=32)) == F.ERR_UNSUPPORTED
+    assert gelu(cols=48, stride=48) == F.ERR_UNSUPPORTED
+    assert gelu(sub=P(al), ng=3) == F.ERR_INVALID_ARG                               # half a SeDA spec
