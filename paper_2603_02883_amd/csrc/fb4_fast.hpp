@@ -846,6 +846,13 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         row_next = load_row(p, t_next * 64u + lane);
         cur = load_block<kBlock, kFlat, kSeda, kGather>(p, t * 64u + lane, row0);
     } else {
+        // The first tiles of all wavefronts of the chip at once are a burst of 8 MB that queues up in the memory
+        // system, and everybody's first tile arrives late.  Only the first two wavefronts of a workgroup ask at
+        // once; the others ask 768 cycles (about a third of a microsecond) later, which is still before the
+        // tables are built: the early tiles arrive earlier and the memory pipeline is as busy as before
+        // (16384x3072: 23.4-23.7 -> 23.0-23.2 us; 8 to 16 sleep units give the same, 30 and more lose again,
+        // and a delay that grows with the wavefront number, or only one early wavefront, gains less).
+        if (kMode == 0 && !kSse && wave >= 2) __builtin_amdgcn_s_sleep(12);
         cur = load_block<kBlock, kFlat, kSeda, kGather>(p, t * 64u + lane);
     }
     __builtin_amdgcn_sched_barrier(0);
