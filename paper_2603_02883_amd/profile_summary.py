@@ -1,11 +1,11 @@
 """Turns the raw rocprofv3 output of `bench.py --traffic-probe` into the short summary that `bench.py` reads.
 
-Usage (the three rocprofv3 runs first, from /tmp with TMPDIR=/tmp, R = the repository root):
+Usage (the three rocprofv3 runs first, from /tmp with TMPDIR=/tmp, R = the repository root, OUT = a scratch folder for the raw output):
 
-    rocprofv3 --pmc FETCH_SIZE -d $R/gpurun_out/prof/fetch --output-format csv -- python3 $R/bench.py --traffic-probe
-    rocprofv3 --pmc WRITE_SIZE -d $R/gpurun_out/prof/write --output-format csv -- python3 $R/bench.py --traffic-probe
-    rocprofv3 --kernel-trace --stats -d $R/gpurun_out/prof/kt --output-format csv -- python3 $R/bench.py --steps 200 --no-extras --no-cpu-baseline
-    python3 -m paper_2603_02883_amd.profile_summary $R/gpurun_out/prof $R/profiles/headline_kernel_traffic.txt
+    rocprofv3 --pmc FETCH_SIZE -d $OUT/fetch --output-format csv -- python3 $R/bench.py --traffic-probe
+    rocprofv3 --pmc WRITE_SIZE -d $OUT/write --output-format csv -- python3 $R/bench.py --traffic-probe
+    rocprofv3 --kernel-trace --stats -d $OUT/kt --output-format csv -- python3 $R/bench.py --steps 200 --no-extras --no-cpu-baseline
+    python3 -m paper_2603_02883_amd.profile_summary $OUT $R/profiles/headline_kernel_traffic.txt
 
 The summary is `key: value` lines: the headline kernel's name, FETCH_SIZE / WRITE_SIZE per dispatch (KiB), the
 same counters for the plain device copy of known size that calibrates them, the HBM bytes per launch that
