@@ -269,13 +269,16 @@ int fb4_repack_mxfp8(const fb4_luts* luts, const uint8_t* codes, const uint16_t*
  * x is read once and the normalized tensor is never written.
  *   y[r][c] = (x[r][c] - mean_r) / sqrt(var_r + eps) * gamma[c] + beta[c]
  * with the biased variance, rounded once to bf16, is what gets quantized.  The
- * producer runs in fp32, the textbook way: mean_r from the sum of the row,
- * var_r from the sum of the squared deviations from mean_r, then
- * fma((x - mean_r) * rstd_r, gamma, beta); a NaN result is the quiet NaN
- * 0x7FC0.  Its bf16 result agrees with the definition evaluated in double to
- * within one bf16 step (almost always exactly; where gamma * t and beta cancel,
- * to within 2^-20 of |gamma * t| + |beta|), a constant row gives exactly beta,
- * and the codes are exactly fb4_quantize of that bf16 tensor.  Rows outside the
+ * producer runs in fp32: mean_r from the sum of the row; var_r as the mean
+ * square minus the squared mean where that difference keeps its bits (|mean_r|
+ * below the standard deviation), else from the sum of the squared deviations
+ * from mean_r in a walk of its own; then fma((x - mean_r) * rstd_r, gamma,
+ * beta); a NaN result is the quiet NaN 0x7FC0.  Its bf16 result agrees with
+ * the definition evaluated in double to within one bf16 step (almost always
+ * exactly), or -- where gamma * t and beta cancel, or the mean dwarfs the
+ * deviations -- to within 2^-19 (|gamma| (|t| + |mean_r| rstd_r + 1) + |beta|),
+ * t = (x - mean_r) rstd_r; a constant row gives exactly beta, and the codes
+ * are exactly fb4_quantize of that bf16 tensor.  Rows outside the
  * range of fp32 sums (an Inf or NaN, squares beyond 2^100, var + eps below
  * 2^-100) are evaluated in double instead.  x is read as plain IEEE bf16 (a
  * row with an Inf or NaN normalizes to NaN throughout).
