@@ -127,33 +127,36 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
     if (threadIdx.x == 0) wg_next = 2 * kWaves;
     uint32_t w[16];
     int32_t grp = -1;   // SeDA: the token group of the chunk's row
-    request(min(t, n_tiles - 1u), w, grp);
 
-    // ---- tables (layout of the streaming kernel) and the GeLU table
-    for (int i = threadIdx.x; i < 64 * kRowCopies; i += kGeluThreads) {
-        const int bin = i / (2 * kRowCopies), half = (i / kRowCopies) & 1;
-        reinterpret_cast<uint4*>(lds + kLdsRows)[i] = *reinterpret_cast<const uint4*>(blob + kOffQerror8 + bin * 32 + half * 16);
-    }
-    for (int i = threadIdx.x; i < 256; i += kGeluThreads)
-        reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = reinterpret_cast<const uint32_t*>(blob + kOffQvalueT)[i];
-    if (kTwoStage && threadIdx.x < 64)
-        reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] = reinterpret_cast<const uint32_t*>(blob + kOffRangeExcl)[threadIdx.x];
+    // ---- tables (layout of the streaming kernel) and the GeLU table.  Loads are answered in the order they were
+    // issued: the table pieces are requested first (into registers, one of each kind per thread) and the first
+    // tile right behind them, so that the tables can be written -- and most of the GeLU table generated -- while
+    // the tile is still on its way, instead of after it.
+    static_assert(64 * kRowCopies <= kGeluThreads && 256 <= kGeluThreads, "one piece of each table per thread");
+    // Most of the GeLU table follows from the bit pattern: GeLU(x) rounds to x / 2 (pattern - 0x80) for
+    // 2^-125 <= |x| < 2^-9.25, to x from 2.875 upwards, a positive NaN gives the quiet NaN.  Only the
+    // 16-byte pieces outside these runs are read from memory, at most one per thread.
+    constexpr int kPieces = kGeluTableBytes / 16;   // 6193 pieces of 8 entries
+    constexpr int kSub = kGeluSubnormalEnd / 8, kHalf = kGeluHalfEnd / 8, kIdent = kGeluIdentityBegin / 8;
+    constexpr int kNeg = 0x8000 / 8;
+    constexpr int kRunA = kSub, kRunB = kIdent - kHalf, kRunC = kSub, kRunD = kPieces - (kNeg + kHalf);
+    static_assert(kRunA + kRunB + kRunC + kRunD <= kGeluThreads, "one loaded piece per thread");
+    const int tid = threadIdx.x;
+    int mine = -1;   // the piece of the GeLU table this thread reads
+    if (tid < kRunA) mine = tid;
+    else if (tid < kRunA + kRunB) mine = kHalf + (tid - kRunA);
+    else if (tid < kRunA + kRunB + kRunC) mine = kNeg + (tid - kRunA - kRunB);
+    else if (tid < kRunA + kRunB + kRunC + kRunD) mine = kNeg + kHalf + (tid - kRunA - kRunB - kRunC);
+    // (indices are clamped, not predicated: a thread without a piece loads one it does not write)
+    const int ri = min(tid, 64 * kRowCopies - 1);
+    const uint4 rowv = *reinterpret_cast<const uint4*>(blob + kOffQerror8 + (ri / (2 * kRowCopies)) * 32 + ((ri / kRowCopies) & 1) * 16);
+    const uint32_t nibv = reinterpret_cast<const uint32_t*>(blob + kOffQvalueT)[tid & 255];
+    const uint32_t rngv = kTwoStage ? reinterpret_cast<const uint32_t*>(blob + kOffRangeExcl)[tid & 63] : 0u;
+    const uint4 loaded = reinterpret_cast<const uint4*>(table)[mine < 0 ? 0 : mine];
+    __builtin_amdgcn_sched_barrier(0);
+    request(min(t, n_tiles - 1u), w, grp);
+    __builtin_amdgcn_sched_barrier(0);
     {
-        // Most of the table follows from the bit pattern: GeLU(x) rounds to x / 2 (pattern - 0x80) for
-        // 2^-125 <= |x| < 2^-9.25, to x from 2.875 upwards, a positive NaN gives the quiet NaN.  Only the
-        // 16-byte pieces outside these runs are read from memory, at most one per thread.
-        constexpr int kPieces = kGeluTableBytes / 16;   // 6193 pieces of 8 entries
-        constexpr int kSub = kGeluSubnormalEnd / 8, kHalf = kGeluHalfEnd / 8, kIdent = kGeluIdentityBegin / 8;
-        constexpr int kNeg = 0x8000 / 8;
-        constexpr int kRunA = kSub, kRunB = kIdent - kHalf, kRunC = kSub, kRunD = kPieces - (kNeg + kHalf);
-        static_assert(kRunA + kRunB + kRunC + kRunD <= kGeluThreads, "one loaded piece per thread");
-        int mine = -1;   // the piece this thread reads
-        const int tid = threadIdx.x;
-        if (tid < kRunA) mine = tid;
-        else if (tid < kRunA + kRunB) mine = kHalf + (tid - kRunA);
-        else if (tid < kRunA + kRunB + kRunC) mine = kNeg + (tid - kRunA - kRunB);
-        else if (tid < kRunA + kRunB + kRunC + kRunD) mine = kNeg + kHalf + (tid - kRunA - kRunB - kRunC);
-        const uint4 loaded = reinterpret_cast<const uint4*>(table)[mine < 0 ? 0 : mine];
         uint4* dst = reinterpret_cast<uint4*>(lds + kLdsGelu);
         for (int i = tid; i < kPieces; i += kGeluThreads) {
             const int ip = i & (kNeg - 1);   // piece index within its sign
@@ -173,6 +176,10 @@ __global__ __launch_bounds__(kGeluThreads) void gelu_quantize_kernel(
             }
             dst[i] = make_uint4(e[0], e[1], e[2], e[3]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (tid < 64 * kRowCopies) reinterpret_cast<uint4*>(lds + kLdsRows)[tid] = rowv;
+        if (tid < 256) reinterpret_cast<uint32_t*>(lds + kLdsNibT)[tid] = nibv;
+        if (kTwoStage && tid < 64) reinterpret_cast<uint32_t*>(lds + kLdsRange)[tid] = rngv;
         if (mine >= 0) dst[mine] = loaded;
     }
     if (kSeda) build_seda_rows(lds, kLdsSeda, p.sub, p.n_groups, p.n_dialects, kGeluThreads);
