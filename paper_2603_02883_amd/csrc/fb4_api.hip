@@ -74,7 +74,8 @@ int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& 
 // workload with 8 wavefronts each (SeDA: 25.7 against 27.2; 4, 12 or 16 wavefronts are slower too), and the
 // kernels are free to use up to 256 vector registers per lane.  The exhaustive selector, bound by the vector
 // ALU, runs 12 wavefronts (83 -> 74.5 us).
-template <int kBlock, int G, bool kFlat, int kMode, int kThreads = kFastThreads>
+// kSedaToo = false: the variants with SeDA lists are not instantiated (`seda` must be false).
+template <int kBlock, int G, bool kFlat, int kMode, int kThreads = kFastThreads, bool kSedaToo = true>
 void launch_fast_variant(bool ts, bool seda, int n_cu, hipStream_t s, const FastParams& f)
 {
     constexpr int kWaves = kThreads / 64;
@@ -84,8 +85,10 @@ void launch_fast_variant(bool ts, bool seda, int n_cu, hipStream_t s, const Fast
     // (the leading arguments repeat fields of f: see the kernel)
 #define FB4_FAST_ARGS f.blob, f.x, f.n_blocks, f.n_tiles, f.div_mul, f.div_shift, f.nb, groups, f.row_stride, f.salient, f
     if (seda) {
-        if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
-        else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+        if constexpr (kSedaToo) {
+            if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, true, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+            else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, true, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
+        }
     } else {
         if (ts) hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, true, false, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
         else hipLaunchKernelGGL((quantize_lut_kernel<kBlock, G, kFlat, false, false, kMode, kThreads>), dim3(groups), dim3(kThreads), 0, s, FB4_FAST_ARGS);
@@ -153,13 +156,14 @@ bool launch_fast(const fb4_luts* luts, const fb4_opts* opts, const QuantParams& 
             if (opts->block == 32) launch_fast_variant<32, 0, false, 1>(ts, seda, ng, s, f);
             else launch_fast_variant<16, 0, false, 1>(ts, seda, ng, s, f);
         } else {
-            // 12 wavefronts, unless the candidate lists would push the kernel past their 168 registers
-            if (seda) {
+            // (matrix-core form) 12 wavefronts per workgroup; 8 with the SeDA rows, which leave LDS for no more
+            // histograms, and with the two-stage filter, which would spill at the 168 registers of 12
+            if (seda || ts) {
                 if (opts->block == 32) launch_fast_variant<32, 0, false, 0>(ts, seda, ng, s, f);
                 else launch_fast_variant<16, 0, false, 0>(ts, seda, ng, s, f);
             } else {
-                if (opts->block == 32) launch_fast_variant<32, 0, false, 0, 768>(ts, seda, ng, s, f);
-                else launch_fast_variant<16, 0, false, 0, 768>(ts, seda, ng, s, f);
+                if (opts->block == 32) launch_fast_variant<32, 0, false, 0, 768, false>(false, false, ng, s, f);
+                else launch_fast_variant<16, 0, false, 0, 768, false>(false, false, ng, s, f);
             }
         }
     } else if (fused) {

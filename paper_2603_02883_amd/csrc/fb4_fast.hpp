@@ -149,9 +149,20 @@ constexpr int lds_gm_offset(bool seda, bool decomp)
 {
     return lds_seda_offset(decomp) + (seda ? (int)(kMaxFastGroups + 1) * 32 : 0);
 }
-constexpr int lds_fast_bytes(bool seda, bool decomp, bool sse = false)
+// Exhaustive selector on the matrix cores (no candidate restrictions): the table above in ONE copy (2 KiB; only
+// the prologue and the plain routine read it), then per wavefront the histograms of its 64 blocks, one per lane:
+// dword (bin b, lane l) at (64 b + l) * 4 = (elements of the lane's block in bin b) << 24 | 128 + (sum of their
+// 7-bit fractions).  Bin-major, so that the 64 lanes of an instruction always touch 64 different banks, whatever
+// their bins (block-major rows: 39 us on 16384x3072, a third of it bank conflicts of the additions).
+constexpr int kGmCompactBytes = 32 * 4 * 16;
+constexpr int kMatrixTableBytes = 8 * 64 * 16;   // the lanes' pieces of the dialect matrices, in front of the histograms
+constexpr int kHistWaveBytes = 32 * 64 * 4;
+constexpr int lds_hist_offset(bool seda, bool decomp) { return lds_gm_offset(seda, decomp) + kGmCompactBytes; }
+// matrix_waves: wavefronts of a workgroup that runs the exhaustive selector on the matrix cores, else 0
+constexpr int lds_fast_bytes(bool seda, bool decomp, bool sse = false, int matrix_waves = 0)
 {
-    return lds_gm_offset(seda, decomp) + (sse ? kGmBytes : 0);
+    return lds_gm_offset(seda, decomp) +
+           (matrix_waves ? kGmCompactBytes + kMatrixTableBytes + matrix_waves * kHistWaveBytes : sse ? kGmBytes : 0);
 }
 
 struct BlockCodes {
@@ -183,8 +194,8 @@ __device__ __forceinline__ uint32_t residual_elem(uint32_t xh, uint32_t nib, uin
 // excluded by excl_a never wins; excl_b (the two-stage range filter) applies only if it leaves a candidate.
 // kResidual: quantize the residual of the first plane (c1 = the block's first-plane code words, m1 = its
 // metadata word) instead of x itself.
-// G == 0: the exhaustive selector (gm_off: LDS offset of its table, copy 0 is read).
-template <int kBlock, int G, bool kResidual>
+// G == 0: the exhaustive selector (gm_off: LDS offset of its table, copy 0 of its kGmCopies copies is read).
+template <int kBlock, int G, bool kResidual, int kGmCopies = 16>
 __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, const uint8_t* lds, uint32_t excl_a,
                                                         bool two_stage, uint4 c1, uint32_t m1, uint32_t gm_off)
 {
@@ -240,7 +251,7 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
             for (int i = 0; i < kBlock; ++i) {
                 const uint32_t X = x256_of(elem(i));
                 const uint32_t b = min(X >> 7, 31u), f = X - (b << 7);
-                const uint8_t* e = lds + gm_off + (b << 10) + (d >> 3) * 256u + (d & 7u) * 2u;
+                const uint8_t* e = lds + gm_off + b * (64u * kGmCopies) + (d >> 3) * (16u * kGmCopies) + (d & 7u) * 2u;
                 z += ((uint32_t)e[0] << 7) + (uint32_t)e[1] * f;
             }
             s = 0xFFFFFu - z;
@@ -269,10 +280,29 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
     return out;
 }
 
+// Which instantiations run the exhaustive selector on the matrix cores: all but those whose LDS tables (SeDA
+// exclusion rows AND the decomposition's row bitmap) leave no room for the histograms.
+constexpr bool sse_on_matrix_cores(int G, bool seda, bool decomp_tables) { return G == 0 && !(seda && decomp_tables); }
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+
+// Exhaustive selector on the matrix cores: what a lane keeps for the whole launch (make_matrix_consts).
+struct MatrixConsts {
+    uint32_t wtab;        // LDS offset of this lane's pieces of the two dialect matrices: piece (c, which) at
+                          // wtab + (2 c + which) * 1024, 16 bytes (kept in LDS, not in 32 registers: the kernel
+                          // then fits three wavefronts per SIMD)
+    uint32_t row;         // LDS offset of the histogram row of this lane's own block
+    uint32_t rd[2];       // LDS offsets of the 64 bytes it reads of block 32 t + lane % 32, t = 0, 1
+    uint32_t half4;       // 4 * (lane / 32)
+    i32x4 w3;             // candidate restrictions: byte j = 64 where 16 (lane / 32) + j == lane % 32, else 0
+};
+
 struct TileConsts {
     uint32_t k7f, k80, kpair, row_base;
     uint32_t kdid[16];   // DID pairs of the 16 key registers: (4i, 4i+2) and (4i+1, 4i+3)
     uint32_t gm_off;     // exhaustive selector: LDS offset of its table
+    MatrixConsts mx;     // only set by a kernel that runs the exhaustive selector on the matrix cores
 };
 
 __device__ __forceinline__ TileConsts make_tile_consts(uint32_t lane, uint32_t gm_off)
@@ -460,13 +490,161 @@ __device__ __forceinline__ uint32_t select_sse_rows(const uint32_t (&b2)[16], co
     return best & 31u;
 }
 
+// The exhaustive selection as a matrix product.  Z_d above depends on a block only through, per bin b, the number
+// of its elements in the bin, n_b, and the sum of their fractions, F_b: Z_d = sum_b 128 n_b gain[b][d] +
+// F_b mag[b][d] -- a [blocks x 64] by [64 x 32 dialects] product of small integers, which the matrix cores do
+// exactly (8-bit operands, 32-bit sums) in 16 instructions per 64 blocks where the vector ALU needs 1024.
+//   * Histogram: every lane adds its block's elements into its own LDS column, one ds_add_u32 per element:
+//     dword (bin, lane) += 1 << 24 | frac.  Dwords start at 0x80.
+//   * Operands: a matrix instruction takes 32 blocks; lane l reads the dwords of bins 16 h .. 16 h + 15
+//     (h = l / 32) of block l % 32, puts 0x80 back and flips bit 7 of what it read.  The four bytes of a dword
+//     are then: the low byte of F_b as a SIGNED number s_b; (F_b + 128) >> 8 = h_b, so that F_b = 256 h_b + s_b;
+//     zero; n_b -- all within the signed 8-bit range (n_b <= 32, h_b <= 16), and they go into the instruction as
+//     they lie: the reduction index of a piece of 16 bytes is (bin, byte), the same in both operands.
+//   * Dialect matrices (make_matrix_consts), for the same (bin, byte) positions: w1 = (mag, 0, 0, 0) gives
+//     P3 = sum s_b mag; w2 = (0, 2 mag, 0, gain - 120) gives P12 = sum 2 h_b mag + n_b (gain - 120), and
+//     Z_d = 128 P12 + P3 + 128 * 120 * (elements of the block); the last term is the same for all dialects and
+//     is left out (gain <= 240 would not fit a signed byte), so keys are signed.
+//   * The product is taken as dialects x blocks, so a lane ends up with 16 dialects of ONE block (dialect
+//     8 (i / 4) + 4 h + i % 4 in accumulator i): keys Z * 32 + 31 - DID, the largest wins, the two half-wavefronts
+//     meet through a lane swap, and lane l < 32 holds the choice for block l of the first 32 blocks,
+//     lane l >= 32 that for block l of the second 32: every lane ends up with its own block's dialect.
+// The LDS unit works a wavefront's instructions off in order, so the reads see the additions without any wait in
+// between.  Call from all 64 lanes (full EXEC).
+//   * Candidate restrictions (two-stage range filter, SeDA lists): the exclusion rows in LDS hold a byte per
+//     dialect, 0xFF = -1 where excluded.  The lane that owns a block knows where its rows are (range_row, seda_row:
+//     LDS offsets); a lane swap hands them to the two lanes that hold the block's dialects, which read their 16
+//     bytes and send them through one more matrix instruction each, against a matrix with 64 (SeDA) or 16 (range)
+//     on the diagonal: the result, -64 or -16 or their sum for an excluded dialect, is added to the key shifted
+//     up by 23 bits -- a SeDA-excluded dialect loses to every other one, a range-excluded one to every one that is
+//     not, and if the range excludes all candidates the best of them still wins, which is the rule
+//     ("unless it leaves no candidate").  |key| < 2^25 before that.
+template <int RB, bool kTwoStage, bool kSeda>
+__device__ __forceinline__ uint32_t select_sse_matrix(const uint32_t (&b2)[16], const uint32_t (&x2)[16], int first,
+                                                      uint8_t* lds, const MatrixConsts& M, uint32_t lane,
+                                                      uint32_t range_row, uint32_t seda_row)
+{
+    const uint32_t k_lo = sgpr_const(256u), k_hi = sgpr_const(256u << 16);   // 256 * bin from either half
+    const uint32_t one_lo = sgpr_const(1u), one_hi = sgpr_const(1u << 16);   // the fraction of either half
+    const uint32_t k_cnt = vgpr_const(0x01000000u);
+#pragma unroll
+    for (int k = first; k < first + RB; ++k) {
+        const uint32_t f2 = x2[k] & 0x007F007Fu;
+        uint32_t* a0 = reinterpret_cast<uint32_t*>(lds + dot2_u16(b2[k], k_lo, M.row));
+        uint32_t* a1 = reinterpret_cast<uint32_t*>(lds + dot2_u16(b2[k], k_hi, M.row));
+        __hip_atomic_fetch_add(a0, dot2_u16(f2, one_lo, k_cnt), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        __hip_atomic_fetch_add(a1, dot2_u16(f2, one_hi, k_cnt), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    uint32_t r[2][16];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        uint32_t* col = reinterpret_cast<uint32_t*>(lds + M.rd[t]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) r[t][j] = col[64 * j];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) col[64 * j] = 0x80u;
+    }
+    // exclusion rows of the blocks this lane works for: element t of a swapped pair is the owner's value for
+    // group t (lane % 32 of the first 32 lanes, of the second 32)
+    i32x4 xr[2], xa[2];
+    if (kTwoStage) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(range_row, range_row, false, false);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) xr[t] = *reinterpret_cast<const i32x4*>(lds + sw[t] + 4u * M.half4);
+    }
+    if (kSeda) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(seda_row, seda_row, false, false);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) xa[t] = *reinterpret_cast<const i32x4*>(lds + sw[t] + 4u * M.half4);
+    }
+    int res[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        i32x16 p12 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        i32x16 p3 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        i32x16 pen = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if (kSeda) pen = __builtin_amdgcn_mfma_i32_32x32x32_i8(M.w3, xa[t], pen, 0, 0, 0);
+        if (kTwoStage) {
+            const i32x4 w3r = {M.w3.x >> 2, M.w3.y >> 2, M.w3.z >> 2, M.w3.w >> 2};   // 16 on the diagonal
+            pen = __builtin_amdgcn_mfma_i32_32x32x32_i8(w3r, xr[t], pen, 0, 0, 0);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const i32x4 b = {(int)(r[t][4 * c] ^ 0x80u), (int)(r[t][4 * c + 1] ^ 0x80u), (int)(r[t][4 * c + 2] ^ 0x80u),
+                             (int)(r[t][4 * c + 3] ^ 0x80u)};
+            const i32x4 w1 = *reinterpret_cast<const i32x4*>(lds + M.wtab + (2 * c) * 1024);
+            const i32x4 w2 = *reinterpret_cast<const i32x4*>(lds + M.wtab + (2 * c + 1) * 1024);
+            p3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, b, p3, 0, 0, 0);
+            p12 = __builtin_amdgcn_mfma_i32_32x32x32_i8(w2, b, p12, 0, 0, 0);
+        }
+        int best = (int)0x80000000;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            // (the tie-break constant sits in a scalar register the optimizer cannot see through: shift-and-or,
+            // then shift-and-add, two instructions per key instead of three)
+            const uint32_t low = ((uint32_t)p3[i] << 5) | sgpr_const((uint32_t)(31 - 8 * (i >> 2) - (i & 3)));
+            uint32_t key = ((uint32_t)p12[i] << 12) + low;
+            if (kSeda || kTwoStage) key += (uint32_t)pen[i] << 23;
+            best = max(best, (int)key);
+        }
+        best -= (int)M.half4;   // this half's dialects are 4 * (lane / 32) further up
+        // (the other half-wavefront's best through a lane swap in the vector ALU: no LDS round trip)
+        const auto sw = __builtin_amdgcn_permlane32_swap((uint32_t)best, (uint32_t)best, false, false);
+        res[t] = max((int)sw[0], (int)sw[1]);
+    }
+    return 31u - ((uint32_t)(lane < 32u ? res[0] : res[1]) & 31u);
+}
+
+// The lane's pieces of the dialect matrices, from the one-copy (gain, magnitude) table at lds + gm_off (which
+// must be complete), and its places in the wavefront's histograms at lds + hist_off, which it initializes.
+__device__ __forceinline__ MatrixConsts make_matrix_consts(uint8_t* lds, uint32_t gm_off, uint32_t hist_off,
+                                                           uint32_t lane, uint32_t wave)
+{
+    MatrixConsts M;
+    const uint32_t d = lane & 31u, h = lane >> 5;
+    M.wtab = hist_off + lane * 16u;
+    const uint32_t base = hist_off + (uint32_t)kMatrixTableBytes + wave * (uint32_t)kHistWaveBytes;
+    M.row = base + lane * 4u;
+    M.rd[0] = base + d * 4u + h * (16u * 256u);
+    M.rd[1] = M.rd[0] + 32u * 4u;
+    M.half4 = 4u * h;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        uint32_t a[4], b[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t bin = 16u * h + 4u * c + j;
+            const uint32_t gm = *reinterpret_cast<const uint16_t*>(lds + gm_off + bin * 64u + d * 2u);   // gain | mag << 8
+            const uint32_t mag = gm >> 8, gain = gm & 0xFFu;
+            a[j] = mag;
+            b[j] = (mag << 9) | (((gain - 120u) & 0xFFu) << 24);
+        }
+        // (every wavefront writes the same values: no barrier needed before its own reads)
+        *reinterpret_cast<uint4*>(lds + M.wtab + (2 * c) * 1024) = make_uint4(a[0], a[1], a[2], a[3]);
+        *reinterpret_cast<uint4*>(lds + M.wtab + (2 * c + 1) * 1024) = make_uint4(b[0], b[1], b[2], b[3]);
+    }
+    {
+        const uint32_t j = d - 16u * h;   // the byte of this lane's own dialect, if it lies in this half
+        const uint32_t v = 64u << (8u * (j & 3u));
+        M.w3 = i32x4{(int)((j >> 2) == 0u ? v : 0u), (int)((j >> 2) == 1u ? v : 0u), (int)((j >> 2) == 2u ? v : 0u),
+                     (int)((j >> 2) == 3u ? v : 0u)};
+    }
+#pragma unroll
+    for (int b = 0; b < 32; ++b) reinterpret_cast<uint32_t*>(lds + M.row)[64 * b] = 0x80u;
+    return M;
+}
+
 // One lane owns 32 consecutive elements of a row: w = its 32 bf16 as 16 packed pairs, holding one block of
 // 32 or two blocks of 16.  Produces the four code words and the metadata (one 16-bit word, or two for block
 // size 16 with the first block in the low half).  xb / in_range are only used by the plain per-element
 // routine of a tile with special values (tile_special reports that this route was taken).  kResidual: w holds the Sec. 3.3 residual of the first plane
 // (code1, meta1), which the plain routine recomputes from x.  stage: 16 words of the lane's private memory when w
 // is not in global memory at all (xb is then ignored).
-template <int kBlock, int G, bool kTwoStage, bool kSeda, bool kResidual = false>
+// kMatrixOk: the calling kernel has the LDS histograms that the exhaustive selector on the matrix cores needs.
+template <int kBlock, int G, bool kTwoStage, bool kSeda, bool kResidual = false, bool kMatrixOk = false>
 __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint8_t* lds, const TileConsts& K,
                                              const uint16_t* xb, bool in_range, uint32_t excl_a,
                                              uint32_t (&code)[4], uint32_t& meta,
@@ -476,6 +654,7 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
     constexpr int NB = 32 / kBlock;     // blocks per lane
     constexpr int RB = 16 / NB;         // packed registers per block
     constexpr bool kSse = G == 0;       // exhaustive selector: every element, no groups
+    constexpr bool kMatrix = kSse && kMatrixOk;
     constexpr int GG = kSse ? kBlock : G;
     constexpr int PER = kBlock / GG;    // elements per group
     static_assert((kBlock == 32 || kBlock == 16) && (PER == 4 || PER == 2 || PER == 1), "supported shapes");
@@ -524,7 +703,7 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
             for (int b = 0; b < NB; ++b) {
                 const uint4 c1 = NB == 1 ? make_uint4(code1[0], code1[1], code1[2], code1[3])
                                          : make_uint4(code1[2 * b], code1[2 * b + 1], 0u, 0u);
-                const BlockCodes r = quantize_block_plain<kBlock, G, kResidual>(
+                const BlockCodes r = quantize_block_plain<kBlock, G, kResidual, kMatrix ? 1 : 16>(
                     xb + b * kBlock, lds, kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage, c1, (meta1 >> (16 * b)) & 0xFFFFu,
                     K.gm_off);
 #pragma unroll
@@ -552,7 +731,13 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
                 // 256 * xhat = sig << (7 - sh); an element with sh > 7 is in bin 0 and its value is not used
                 if (kSse) x2[k] = pk_shl(sig, pk_sub_sat(0x00070007u, sh));
             }
-            if (kSse) {
+            if (kMatrix) {
+                // the block's range row: its largest element has bin 16 + (top three mantissa bits), range = bin / 2
+                // (an all-zero block: range row 0, as from its bins)
+                const uint32_t range_row = kLdsRange + ((bm[b] >> 4) & 7u) * 32u;
+                did[b] = select_sse_matrix<RB, kTwoStage, kSeda>(b2, x2, b * RB, const_cast<uint8_t*>(lds), K.mx,
+                                                                 threadIdx.x & 63u, range_row, excl_a);
+            } else if (kSse) {
                 did[b] = select_sse_rows<RB, kTwoStage, kSeda>(b2, x2, b * RB, lds, K, threadIdx.x, excl_a);
             } else {
                 // ---- group-wise maxima: groups are runs of PER elements
@@ -764,8 +949,10 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     static_assert(!(kGather && kFlat), "gathered rows are addressed through their row stride");
     constexpr int kLdsSeda = lds_seda_offset(kRes);
     constexpr bool kSse = G == 0;   // the exhaustive selector
+    constexpr bool kMatrix = sse_on_matrix_cores(G, kSeda, kRes);
+    constexpr int kGmCopies = kMatrix ? 1 : 16;   // copies of the (gain, magnitude) table
     constexpr int kLdsGm = lds_gm_offset(kSeda, kRes);
-    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kRes, kSse)];
+    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kRes, kSse, kMatrix ? kThreads / 64 : 0)];
     __shared__ uint32_t sal_before;      // fused decomposition: list entries below row 0
     __shared__ uint32_t sal_wave[kWaves];
     const uint32_t lane = threadIdx.x & 63;
@@ -791,7 +978,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     uint32_t nibv[kNibIt], rngv = 0, decv = 0;
     uint4 magq = make_uint4(0, 0, 0, 0);
     uint2 sub0 = make_uint2(0, 0);
-    constexpr int kGmIt = kSse ? (512 + kThreads - 1) / kThreads : 1;
+    constexpr int kGmIt = kSse ? (32 * kGmCopies + kThreads - 1) / kThreads : 1;
     uint4 gmm[kGmIt][4], gmg[kGmIt][4];
     int32_t sal_reg[kSalEarly];
     const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kThreads;
@@ -830,7 +1017,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
             // work item i = (bin, copy): the bin's 32 magnitudes and 32 gains (16 bits each in the table blob)
 #pragma unroll
             for (int k = 0; k < kGmIt; ++k) {
-                const int bin = min((int)threadIdx.x + k * kThreads, 511) >> 4;
+                const int bin = min((int)threadIdx.x + k * kThreads, 32 * kGmCopies - 1) / kGmCopies;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     gmm[k][q] = *reinterpret_cast<const uint4*>(p.blob + kOffMag16 + bin * 64 + q * 16);
@@ -870,8 +1057,8 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
 #pragma unroll
             for (int k = 0; k < kGmIt; ++k) {
                 const int i = threadIdx.x + k * kThreads;
-                if (i < 512) {
-                    const int bin = i >> 4, copy = i & 15;
+                if (i < 32 * kGmCopies) {
+                    const int bin = i / kGmCopies, copy = i % kGmCopies;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         // piece q: dialects 8q .. 8q+7; a source dword holds two dialects' 16-bit values
@@ -881,7 +1068,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
 #pragma unroll
                         for (int j = 0; j < 4; ++j)   // bytes: gain, mag of dialect 8q+2j, then of 8q+2j+1
                             o[j] = (g[j] & 0xFFu) | ((m[j] & 0xFFu) << 8) | ((g[j] >> 16) << 16) | ((m[j] >> 16) << 24);
-                        *reinterpret_cast<uint4*>(lds + kLdsGm + bin * 1024 + q * 256 + copy * 16) =
+                        *reinterpret_cast<uint4*>(lds + kLdsGm + bin * (64 * kGmCopies) + q * (16 * kGmCopies) + copy * 16) =
                             make_uint4(o[0], o[1], o[2], o[3]);
                     }
                 }
@@ -986,7 +1173,8 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         }
         __syncthreads();
     }
-    const TileConsts K = make_tile_consts(lane, kLdsGm);
+    TileConsts K = make_tile_consts(lane, kLdsGm);
+    if (kMatrix) K.mx = make_matrix_consts(lds, kLdsGm, lds_hist_offset(kSeda, kRes), lane, wave);
 
     // Results of a tile are held in registers and written at the top of the next iteration, right after
     // that iteration's input has arrived: memory operations retire in issue order, so a store issued just
@@ -1056,13 +1244,13 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
             // a lane without a row runs the arithmetic on zeros and stores nothing
 #pragma unroll
             for (int k = 0; k < 16; ++k) w2[k] = ok ? w2[k] : 0u;
-            compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, ok, excl_a, code, meta, code1, c1m1[4],
+            compute_tile<kBlock, G, kTwoStage, kSeda, true, kMatrix>(w2, lds, K, xb, ok, excl_a, code, meta, code1, c1m1[4],
                                                             tile_special);
             held_ok = ok;
         } else {
             const uint16_t* xb = p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u);
             const uint32_t no_code[4] = {0, 0, 0, 0};
-            compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
+            compute_tile<kBlock, G, kTwoStage, kSeda, false, kMatrix>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
                                                       tile_special);
             if (kDecomp) {
                 // second plane of the salient rows, from the registers that still hold the tile
@@ -1081,7 +1269,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
 #pragma unroll
                     for (int k = 0; k < 16; ++k) w2[k] = sal ? w2[k] : 0u;
                     bool special2;
-                    compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, sal, excl_a, code2, meta2, code, meta,
+                    compute_tile<kBlock, G, kTwoStage, kSeda, true, kMatrix>(w2, lds, K, xb, sal, excl_a, code2, meta2, code, meta,
                                                                     special2);
                     held2_any = true;
                     held2_lane = sal;
