@@ -9,7 +9,7 @@
 // blocks of 16: it loads the 64 bytes with four 16-byte loads, keeps the
 // elements as 16 packed bf16 pairs and runs every per-element step on both
 // halves of a register at once (packed 16-bit integer instructions).  Nothing
-// crosses lanes.  A wavefront therefore covers 64 consecutive 32-element
+// crosses lanes (but the exhaustive selector's scores).  A wavefront therefore covers 64 consecutive 32-element
 // chunks (4 KiB of input) and writes 1 KiB of codes and 128 (block 16: 256)
 // bytes of metadata, all contiguous.  In the code below "chunk" indices (gb)
 // count these 32-element pieces.
@@ -20,8 +20,9 @@
 //     row reads of a wavefront never collide whatever bins the lanes ask for;
 //   * a pair table: (bin of element 2m, bin of element 2m+1, dialect) -> the
 //     finished code byte without sign bits, so one lookup emits two elements;
-//   * exhaustive selector: per bin the (gain, magnitude) byte pairs of the 32
-//     dialects, in 16 copies the same way.
+//   * exhaustive selector (instead of the Qerror rows): the dialect matrices and
+//     one histogram per block -- its scores are a matrix product, taken on the
+//     matrix cores (select_sse_matrix).
 //
 // A block whose largest magnitude is NaN/Inf-sized or below 2^-122 (and not
 // zero) leaves the packed path: the wavefront then redoes its tile with a
@@ -141,28 +142,33 @@ constexpr int kLdsSalRank = kLdsSalBits + kMaxFusedRows / 8;   // uint16 per bit
 constexpr int kLdsDecompBytes = 512 + 128 + kMaxFusedRows / 8 + kMaxFusedRows / 32 * 2;
 // SeDA: [n_groups + 1][32 B] 0xFF = dialect excluded; last row: none.  Placed after everything else.
 constexpr int lds_seda_offset(bool decomp) { return kLdsRange + 256 + (decomp ? kLdsDecompBytes : 0); }
-// Exhaustive selector only: per bin the (gain, magnitude) byte pairs of the 32 dialects, 64 B in four 16-byte
-// pieces, each piece in 16 copies so that the 16 lanes of one LDS pass read 16 different bank groups whatever
-// their bins: [32 bins][4 pieces][16 copies][16 B] = 32 KiB.  Placed last.
-constexpr int kGmBytes = 32 * 4 * 16 * 16;
+// Exhaustive selector only (it runs on the matrix cores: select_sse_matrix), placed last:
+//   * per bin the (gain, magnitude) byte pairs of the 32 dialects, 64 B: [32 bins][32 dialects][2] = 2 KiB (read by
+//     the prologue and the plain routine);
+//   * the lanes' pieces of the dialect matrices, [8 pieces][64 lanes][16 B] = 8 KiB;
+//   * per wavefront the histograms of its 64 blocks, one per lane: dword (bin b, lane l) at (64 b + l) * 4 =
+//     (elements of the lane's block in bin b) << 24 | 128 + (sum of their 7-bit fractions).  Bin-major, so that
+//     the 64 lanes of an instruction always touch 64 different banks, whatever their bins (block-major rows: a
+//     third of the LDS time went to bank conflicts of the additions).  The first two wavefronts' histograms lie
+//     in the 16 KiB of the Qerror rows, which this selector does not use.
+constexpr int kGmBytes = 32 * 4 * 16;
+constexpr int kMatrixTableBytes = 8 * 64 * 16;
+constexpr int kHistWaveBytes = 32 * 64 * 4;
 constexpr int lds_gm_offset(bool seda, bool decomp)
 {
     return lds_seda_offset(decomp) + (seda ? (int)(kMaxFastGroups + 1) * 32 : 0);
 }
-// Exhaustive selector on the matrix cores (no candidate restrictions): the table above in ONE copy (2 KiB; only
-// the prologue and the plain routine read it), then per wavefront the histograms of its 64 blocks, one per lane:
-// dword (bin b, lane l) at (64 b + l) * 4 = (elements of the lane's block in bin b) << 24 | 128 + (sum of their
-// 7-bit fractions).  Bin-major, so that the 64 lanes of an instruction always touch 64 different banks, whatever
-// their bins (block-major rows: 39 us on 16384x3072, a third of it bank conflicts of the additions).
-constexpr int kGmCompactBytes = 32 * 4 * 16;
-constexpr int kMatrixTableBytes = 8 * 64 * 16;   // the lanes' pieces of the dialect matrices, in front of the histograms
-constexpr int kHistWaveBytes = 32 * 64 * 4;
-constexpr int lds_hist_offset(bool seda, bool decomp) { return lds_gm_offset(seda, decomp) + kGmCompactBytes; }
-// matrix_waves: wavefronts of a workgroup that runs the exhaustive selector on the matrix cores, else 0
-constexpr int lds_fast_bytes(bool seda, bool decomp, bool sse = false, int matrix_waves = 0)
+constexpr int lds_matrix_offset(bool seda, bool decomp) { return lds_gm_offset(seda, decomp) + kGmBytes; }
+// LDS offset of wavefront w's histograms
+__host__ __device__ constexpr int lds_hist_offset(bool seda, bool decomp, int w)
 {
-    return lds_gm_offset(seda, decomp) +
-           (matrix_waves ? kGmCompactBytes + kMatrixTableBytes + matrix_waves * kHistWaveBytes : sse ? kGmBytes : 0);
+    return w < 2 ? kLdsRows + w * kHistWaveBytes
+                 : lds_matrix_offset(seda, decomp) + kMatrixTableBytes + (w - 2) * kHistWaveBytes;
+}
+// sse_waves: wavefronts of a workgroup that runs the exhaustive selector, else 0
+constexpr int lds_fast_bytes(bool seda, bool decomp, int sse_waves = 0)
+{
+    return sse_waves ? lds_hist_offset(seda, decomp, sse_waves > 2 ? sse_waves : 2) : lds_gm_offset(seda, decomp);
 }
 
 struct BlockCodes {
@@ -194,8 +200,8 @@ __device__ __forceinline__ uint32_t residual_elem(uint32_t xh, uint32_t nib, uin
 // excluded by excl_a never wins; excl_b (the two-stage range filter) applies only if it leaves a candidate.
 // kResidual: quantize the residual of the first plane (c1 = the block's first-plane code words, m1 = its
 // metadata word) instead of x itself.
-// G == 0: the exhaustive selector (gm_off: LDS offset of its table, copy 0 of its kGmCopies copies is read).
-template <int kBlock, int G, bool kResidual, int kGmCopies = 16>
+// G == 0: the exhaustive selector (gm_off: LDS offset of its (gain, magnitude) table).
+template <int kBlock, int G, bool kResidual>
 __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, const uint8_t* lds, uint32_t excl_a,
                                                         bool two_stage, uint4 c1, uint32_t m1, uint32_t gm_off)
 {
@@ -251,7 +257,7 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
             for (int i = 0; i < kBlock; ++i) {
                 const uint32_t X = x256_of(elem(i));
                 const uint32_t b = min(X >> 7, 31u), f = X - (b << 7);
-                const uint8_t* e = lds + gm_off + b * (64u * kGmCopies) + (d >> 3) * (16u * kGmCopies) + (d & 7u) * 2u;
+                const uint8_t* e = lds + gm_off + b * 64u + d * 2u;
                 z += ((uint32_t)e[0] << 7) + (uint32_t)e[1] * f;
             }
             s = 0xFFFFFu - z;
@@ -279,10 +285,6 @@ __device__ __noinline__ BlockCodes quantize_block_plain(const uint16_t* xb, cons
     out.meta = did | (eb << 8);
     return out;
 }
-
-// Which instantiations run the exhaustive selector on the matrix cores: all but those whose LDS tables (SeDA
-// exclusion rows AND the decomposition's row bitmap) leave no room for the histograms.
-constexpr bool sse_on_matrix_cores(int G, bool seda, bool decomp_tables) { return G == 0 && !(seda && decomp_tables); }
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
@@ -412,85 +414,12 @@ __device__ __forceinline__ uint32_t select_lut_rows(const uint32_t (&gbin)[R], c
     return halves_min(best) & 31u;
 }
 
-// Exhaustive selection (Sec. 3.2, first paragraph) for one block whose elements sit in registers
+// Exhaustive selection (Sec. 3.2, first paragraph) for the blocks of a wavefront, whose elements sit in registers
 // b2[first .. first + RB) (bins, two per register) and x2 (256 * xhat, two per register).  With X = 256 * xhat =
 // 128 * bin + frac and m the nearest magnitude of a dialect, (X - 256 m)^2 = X^2 - 512 Z with
 // Z = 128 * m * (bin - m) + frac * m: the smallest error is the largest Z_d = sum over the elements of
-// 128 * gain[bin][d] + frac * mag[bin][d] (< 2^20).  A table row holds the byte pairs (gain, mag) of two
-// dialects per dword, so one four-byte dot product with (128, frac, 0, 0) or (0, 0, 128, frac) adds an
-// element's term to a dialect's sum.  Candidate restrictions as in select_lut_rows.
-template <int RB, bool kTwoStage, bool kSeda>
-__device__ __forceinline__ uint32_t select_sse_rows(const uint32_t (&b2)[16], const uint32_t (&x2)[16], int first,
-                                                    const uint8_t* lds, const TileConsts& K, uint32_t lane,
-                                                    uint32_t excl_a)
-{
-    uint32_t z[32];
-#pragma unroll
-    for (int d = 0; d < 32; ++d) z[d] = 0;
-    const uint32_t base = K.gm_off + (lane & 15u) * 16u;
-    // byte selectors that build (128, frac, 0, 0) and (0, 0, 128, frac) from a register pair's fractions
-    const uint32_t k80 = vgpr_const(0x80u);
-    const uint32_t s_lo[2] = {sgpr_const(0x0C0C0004u), sgpr_const(0x0C0C0204u)};
-    const uint32_t s_hi[2] = {sgpr_const(0x00040C0Cu), sgpr_const(0x02040C0Cu)};
-    const uint32_t k_row[2] = {sgpr_const(1024u), sgpr_const(1024u << 16)};   // bin * 1024 from either half
-#pragma unroll
-    for (int k = first; k < first + RB; ++k) {
-        const uint32_t f2 = x2[k] & 0x007F007Fu;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint8_t* row = lds + dot2_u16(b2[k], k_row[h], base);
-            const uint4 r[4] = {*reinterpret_cast<const uint4*>(row), *reinterpret_cast<const uint4*>(row + 256),
-                                *reinterpret_cast<const uint4*>(row + 512), *reinterpret_cast<const uint4*>(row + 768)};
-            const uint32_t sel_lo = __builtin_amdgcn_perm(k80, f2, s_lo[h]);
-            const uint32_t sel_hi = __builtin_amdgcn_perm(k80, f2, s_hi[h]);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t v[4] = {r[q].x, r[q].y, r[q].z, r[q].w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    z[8 * q + 2 * j] = __builtin_amdgcn_udot4(v[j], sel_lo, z[8 * q + 2 * j], false);
-                    z[8 * q + 2 * j + 1] = __builtin_amdgcn_udot4(v[j], sel_hi, z[8 * q + 2 * j + 1], false);
-                }
-            }
-        }
-    }
-    if (!kSeda && !kTwoStage) {
-        // largest Z, lowest DID on ties: keys Z << 5 | (31 - DID), largest wins
-        uint32_t best = 0;
-#pragma unroll
-        for (int d = 0; d < 32; d += 2)
-            best = max(best, max((z[d] << 5) | (uint32_t)(31 - d), (z[d + 1] << 5) | (uint32_t)(30 - d)));
-        return 31u - (best & 31u);
-    }
-    // ---- restrictions: rows of bytes, 0xFF = excluded
-    uint32_t xa[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (kSeda) {
-        const uint4 a0 = *reinterpret_cast<const uint4*>(lds + excl_a), a1 = *reinterpret_cast<const uint4*>(lds + excl_a + 16);
-        xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w; xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
-    }
-    if (kTwoStage) {
-        uint32_t bm2 = 0;
-#pragma unroll
-        for (int k = first; k < first + RB; ++k) bm2 = pk_max(bm2, b2[k]);
-        const uint32_t roff = kLdsRange + (min(max(halves_max(bm2) >> 1, 8u), 15u) - 8u) * 32u;
-        const uint4 a0 = *reinterpret_cast<const uint4*>(lds + roff), a1 = *reinterpret_cast<const uint4*>(lds + roff + 16);
-        xr[0] = a0.x; xr[1] = a0.y; xr[2] = a0.z; xr[3] = a0.w; xr[4] = a1.x; xr[5] = a1.y; xr[6] = a1.z; xr[7] = a1.w;
-    }
-    // ---- largest Z, lowest DID on ties: keys (2^20 - 1 - Z) << 5 | DID, smallest wins
-    uint32_t best = 0xFFFFFFFFu, best_r = 0xFFFFFFFFu;
-#pragma unroll
-    for (int d = 0; d < 32; ++d) {
-        uint32_t key = ((0xFFFFFu - z[d]) << 5) | (uint32_t)d;
-        if (kSeda) key |= (uint32_t)__builtin_amdgcn_sbfe((int)xa[d >> 2], 8 * (d & 3), 8);   // 0xFF -> all ones
-        best = min(best, key);
-        if (kTwoStage) best_r = min(best_r, key | (uint32_t)__builtin_amdgcn_sbfe((int)xr[d >> 2], 8 * (d & 3), 8));
-    }
-    // the range filter applies unless it leaves no candidate
-    if (kTwoStage && best_r != 0xFFFFFFFFu) best = best_r;
-    return best & 31u;
-}
-
-// The exhaustive selection as a matrix product.  Z_d above depends on a block only through, per bin b, the number
+// 128 * gain[bin][d] + frac * mag[bin][d] (< 2^20, every quantity an exact integer).
+// As a matrix product: Z_d depends on a block only through, per bin b, the number
 // of its elements in the bin, n_b, and the sum of their fractions, F_b: Z_d = sum_b 128 n_b gain[b][d] +
 // F_b mag[b][d] -- a [blocks x 64] by [64 x 32 dialects] product of small integers, which the matrix cores do
 // exactly (8-bit operands, 32-bit sums) in 16 instructions per 64 blocks where the vector ALU needs 1024.
@@ -598,15 +527,16 @@ __device__ __forceinline__ uint32_t select_sse_matrix(const uint32_t (&b2)[16], 
     return 31u - ((uint32_t)(lane < 32u ? res[0] : res[1]) & 31u);
 }
 
-// The lane's pieces of the dialect matrices, from the one-copy (gain, magnitude) table at lds + gm_off (which
-// must be complete), and its places in the wavefront's histograms at lds + hist_off, which it initializes.
-__device__ __forceinline__ MatrixConsts make_matrix_consts(uint8_t* lds, uint32_t gm_off, uint32_t hist_off,
-                                                           uint32_t lane, uint32_t wave)
+// The lane's pieces of the dialect matrices (written to lds + matrix_off), from the (gain, magnitude) table at
+// lds + gm_off (which must be complete), and its places in the wavefront's histograms at lds + hist_off, which it
+// initializes.
+__device__ __forceinline__ MatrixConsts make_matrix_consts(uint8_t* lds, uint32_t gm_off, uint32_t matrix_off,
+                                                           uint32_t hist_off, uint32_t lane)
 {
     MatrixConsts M;
     const uint32_t d = lane & 31u, h = lane >> 5;
-    M.wtab = hist_off + lane * 16u;
-    const uint32_t base = hist_off + (uint32_t)kMatrixTableBytes + wave * (uint32_t)kHistWaveBytes;
+    M.wtab = matrix_off + lane * 16u;
+    const uint32_t base = hist_off;
     M.row = base + lane * 4u;
     M.rd[0] = base + d * 4u + h * (16u * 256u);
     M.rd[1] = M.rd[0] + 32u * 4u;
@@ -643,8 +573,7 @@ __device__ __forceinline__ MatrixConsts make_matrix_consts(uint8_t* lds, uint32_
 // routine of a tile with special values (tile_special reports that this route was taken).  kResidual: w holds the Sec. 3.3 residual of the first plane
 // (code1, meta1), which the plain routine recomputes from x.  stage: 16 words of the lane's private memory when w
 // is not in global memory at all (xb is then ignored).
-// kMatrixOk: the calling kernel has the LDS histograms that the exhaustive selector on the matrix cores needs.
-template <int kBlock, int G, bool kTwoStage, bool kSeda, bool kResidual = false, bool kMatrixOk = false>
+template <int kBlock, int G, bool kTwoStage, bool kSeda, bool kResidual = false>
 __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint8_t* lds, const TileConsts& K,
                                              const uint16_t* xb, bool in_range, uint32_t excl_a,
                                              uint32_t (&code)[4], uint32_t& meta,
@@ -654,7 +583,6 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
     constexpr int NB = 32 / kBlock;     // blocks per lane
     constexpr int RB = 16 / NB;         // packed registers per block
     constexpr bool kSse = G == 0;       // exhaustive selector: every element, no groups
-    constexpr bool kMatrix = kSse && kMatrixOk;
     constexpr int GG = kSse ? kBlock : G;
     constexpr int PER = kBlock / GG;    // elements per group
     static_assert((kBlock == 32 || kBlock == 16) && (PER == 4 || PER == 2 || PER == 1), "supported shapes");
@@ -703,7 +631,7 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
             for (int b = 0; b < NB; ++b) {
                 const uint4 c1 = NB == 1 ? make_uint4(code1[0], code1[1], code1[2], code1[3])
                                          : make_uint4(code1[2 * b], code1[2 * b + 1], 0u, 0u);
-                const BlockCodes r = quantize_block_plain<kBlock, G, kResidual, kMatrix ? 1 : 16>(
+                const BlockCodes r = quantize_block_plain<kBlock, G, kResidual>(
                     xb + b * kBlock, lds, kSeda ? excl_a : 0xFFFFFFFFu, kTwoStage, c1, (meta1 >> (16 * b)) & 0xFFFFu,
                     K.gm_off);
 #pragma unroll
@@ -731,14 +659,12 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
                 // 256 * xhat = sig << (7 - sh); an element with sh > 7 is in bin 0 and its value is not used
                 if (kSse) x2[k] = pk_shl(sig, pk_sub_sat(0x00070007u, sh));
             }
-            if (kMatrix) {
+            if (kSse) {
                 // the block's range row: its largest element has bin 16 + (top three mantissa bits), range = bin / 2
                 // (an all-zero block: range row 0, as from its bins)
                 const uint32_t range_row = kLdsRange + ((bm[b] >> 4) & 7u) * 32u;
                 did[b] = select_sse_matrix<RB, kTwoStage, kSeda>(b2, x2, b * RB, const_cast<uint8_t*>(lds), K.mx,
                                                                  threadIdx.x & 63u, range_row, excl_a);
-            } else if (kSse) {
-                did[b] = select_sse_rows<RB, kTwoStage, kSeda>(b2, x2, b * RB, lds, K, threadIdx.x, excl_a);
             } else {
                 // ---- group-wise maxima: groups are runs of PER elements
                 uint32_t gbin[GG];
@@ -949,10 +875,8 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     static_assert(!(kGather && kFlat), "gathered rows are addressed through their row stride");
     constexpr int kLdsSeda = lds_seda_offset(kRes);
     constexpr bool kSse = G == 0;   // the exhaustive selector
-    constexpr bool kMatrix = sse_on_matrix_cores(G, kSeda, kRes);
-    constexpr int kGmCopies = kMatrix ? 1 : 16;   // copies of the (gain, magnitude) table
     constexpr int kLdsGm = lds_gm_offset(kSeda, kRes);
-    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kRes, kSse, kMatrix ? kThreads / 64 : 0)];
+    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kRes, kSse ? kThreads / 64 : 0)];
     __shared__ uint32_t sal_before;      // fused decomposition: list entries below row 0
     __shared__ uint32_t sal_wave[kWaves];
     const uint32_t lane = threadIdx.x & 63;
@@ -974,12 +898,11 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     constexpr int kNibIt = (256 + kThreads - 1) / kThreads;
     constexpr int kSalEarly = 8;
     static_assert(kRowIt <= 2, "two row pieces per thread at most");
-    uint4 row_a, row_b = make_uint4(0, 0, 0, 0);   // (scalars, not an array: an array here ends up in scratch memory)
+    uint4 row_a = make_uint4(0, 0, 0, 0), row_b = make_uint4(0, 0, 0, 0);   // (scalars, not an array: an array here ends up in scratch memory)
     uint32_t nibv[kNibIt], rngv = 0, decv = 0;
     uint4 magq = make_uint4(0, 0, 0, 0);
     uint2 sub0 = make_uint2(0, 0);
-    constexpr int kGmIt = kSse ? (32 * kGmCopies + kThreads - 1) / kThreads : 1;
-    uint4 gmm[kGmIt][4], gmg[kGmIt][4];
+    uint4 gmm[4], gmg[4];
     int32_t sal_reg[kSalEarly];
     const bool sal_early = kDecomp && p.n_sal <= (uint32_t)kSalEarly * kThreads;
     {
@@ -990,8 +913,10 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
             const int bin = i / (2 * kCopies), half = (i / kCopies) & 1;
             return *reinterpret_cast<const uint4*>(p.blob + kOffQerror8 + bin * 32 + half * 16);
         };
-        row_a = row_piece(0);
-        if (kRowIt > 1) row_b = row_piece(1);
+        if (!kSse) {   // (the exhaustive selector does not use them: their LDS holds two wavefronts' histograms)
+            row_a = row_piece(0);
+            if (kRowIt > 1) row_b = row_piece(1);
+        }
 #pragma unroll
         for (int k = 0; k < kNibIt; ++k)
             nibv[k] = reinterpret_cast<const uint32_t*>(p.blob + kOffQvalueT)[min((int)threadIdx.x + k * kThreads, 255)];
@@ -1014,15 +939,12 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         if (kSeda && p.n_groups > 0)
             sub0 = *reinterpret_cast<const uint2*>(p.sub + (size_t)min(threadIdx.x, p.n_groups - 1u) * 8);
         if (kSse) {
-            // work item i = (bin, copy): the bin's 32 magnitudes and 32 gains (16 bits each in the table blob)
+            // thread `bin` of the first 32: the bin's 32 magnitudes and 32 gains (16 bits each in the table blob)
+            const int bin = threadIdx.x & 31u;
 #pragma unroll
-            for (int k = 0; k < kGmIt; ++k) {
-                const int bin = min((int)threadIdx.x + k * kThreads, 32 * kGmCopies - 1) / kGmCopies;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    gmm[k][q] = *reinterpret_cast<const uint4*>(p.blob + kOffMag16 + bin * 64 + q * 16);
-                    gmg[k][q] = *reinterpret_cast<const uint4*>(p.blob + kOffGain16 + bin * 64 + q * 16);
-                }
+            for (int q = 0; q < 4; ++q) {
+                gmm[q] = *reinterpret_cast<const uint4*>(p.blob + kOffMag16 + bin * 64 + q * 16);
+                gmg[q] = *reinterpret_cast<const uint4*>(p.blob + kOffGain16 + bin * 64 + q * 16);
             }
         }
     }
@@ -1044,34 +966,29 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     }
     __builtin_amdgcn_sched_barrier(0);
     {
-        if ((int)threadIdx.x < 64 * kCopies) reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x] = row_a;
-        if (kRowIt > 1 && (int)threadIdx.x + kThreads < 64 * kCopies)
-            reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x + kThreads] = row_b;
+        if (!kSse) {
+            if ((int)threadIdx.x < 64 * kCopies) reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x] = row_a;
+            if (kRowIt > 1 && (int)threadIdx.x + kThreads < 64 * kCopies)
+                reinterpret_cast<uint4*>(lds + kLdsRows)[threadIdx.x + kThreads] = row_b;
+        }
 #pragma unroll
         for (int k = 0; k < kNibIt; ++k) {
             const int i = threadIdx.x + k * kThreads;
             if (i < 256) reinterpret_cast<uint32_t*>(lds + kLdsNibT)[i] = nibv[k];
         }
         if (kTwoStage && threadIdx.x < 64) reinterpret_cast<uint32_t*>(lds + kLdsRange)[threadIdx.x] = rngv;
-        if (kSse) {
+        if (kSse && threadIdx.x < 32) {
+            const int bin = threadIdx.x;
 #pragma unroll
-            for (int k = 0; k < kGmIt; ++k) {
-                const int i = threadIdx.x + k * kThreads;
-                if (i < 32 * kGmCopies) {
-                    const int bin = i / kGmCopies, copy = i % kGmCopies;
+            for (int q = 0; q < 4; ++q) {
+                // piece q: dialects 8q .. 8q+7; a source dword holds two dialects' 16-bit values
+                const uint32_t m[4] = {gmm[q].x, gmm[q].y, gmm[q].z, gmm[q].w};
+                const uint32_t g[4] = {gmg[q].x, gmg[q].y, gmg[q].z, gmg[q].w};
+                uint32_t o[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        // piece q: dialects 8q .. 8q+7; a source dword holds two dialects' 16-bit values
-                        const uint32_t m[4] = {gmm[k][q].x, gmm[k][q].y, gmm[k][q].z, gmm[k][q].w};
-                        const uint32_t g[4] = {gmg[k][q].x, gmg[k][q].y, gmg[k][q].z, gmg[k][q].w};
-                        uint32_t o[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)   // bytes: gain, mag of dialect 8q+2j, then of 8q+2j+1
-                            o[j] = (g[j] & 0xFFu) | ((m[j] & 0xFFu) << 8) | ((g[j] >> 16) << 16) | ((m[j] >> 16) << 24);
-                        *reinterpret_cast<uint4*>(lds + kLdsGm + bin * (64 * kGmCopies) + q * (16 * kGmCopies) + copy * 16) =
-                            make_uint4(o[0], o[1], o[2], o[3]);
-                    }
-                }
+                for (int j = 0; j < 4; ++j)   // bytes: gain, mag of dialect 8q+2j, then of 8q+2j+1
+                    o[j] = (g[j] & 0xFFu) | ((m[j] & 0xFFu) << 8) | ((g[j] >> 16) << 16) | ((m[j] >> 16) << 24);
+                *reinterpret_cast<uint4*>(lds + kLdsGm + bin * 64 + q * 16) = make_uint4(o[0], o[1], o[2], o[3]);
             }
         }
         if (kRes) {
@@ -1174,7 +1091,10 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         __syncthreads();
     }
     TileConsts K = make_tile_consts(lane, kLdsGm);
-    if (kMatrix) K.mx = make_matrix_consts(lds, kLdsGm, lds_hist_offset(kSeda, kRes), lane, wave);
+    if (kSse)
+        K.mx = make_matrix_consts(lds, kLdsGm, lds_matrix_offset(kSeda, kRes),
+                                  wave < 2 ? kLdsRows + wave * kHistWaveBytes
+                                           : lds_hist_offset(kSeda, kRes, 2) + (wave - 2) * kHistWaveBytes, lane);
 
     // Results of a tile are held in registers and written at the top of the next iteration, right after
     // that iteration's input has arrived: memory operations retire in issue order, so a store issued just
@@ -1244,13 +1164,13 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
             // a lane without a row runs the arithmetic on zeros and stores nothing
 #pragma unroll
             for (int k = 0; k < 16; ++k) w2[k] = ok ? w2[k] : 0u;
-            compute_tile<kBlock, G, kTwoStage, kSeda, true, kMatrix>(w2, lds, K, xb, ok, excl_a, code, meta, code1, c1m1[4],
+            compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, ok, excl_a, code, meta, code1, c1m1[4],
                                                             tile_special);
             held_ok = ok;
         } else {
             const uint16_t* xb = p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u);
             const uint32_t no_code[4] = {0, 0, 0, 0};
-            compute_tile<kBlock, G, kTwoStage, kSeda, false, kMatrix>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
+            compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
                                                       tile_special);
             if (kDecomp) {
                 // second plane of the salient rows, from the registers that still hold the tile
@@ -1269,7 +1189,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
 #pragma unroll
                     for (int k = 0; k < 16; ++k) w2[k] = sal ? w2[k] : 0u;
                     bool special2;
-                    compute_tile<kBlock, G, kTwoStage, kSeda, true, kMatrix>(w2, lds, K, xb, sal, excl_a, code2, meta2, code, meta,
+                    compute_tile<kBlock, G, kTwoStage, kSeda, true>(w2, lds, K, xb, sal, excl_a, code2, meta2, code, meta,
                                                                     special2);
                     held2_any = true;
                     held2_lane = sal;
