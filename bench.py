@@ -498,6 +498,8 @@ def main():
         add("repack_mxfp8", repack_step, n_el // 2 + n_el // 16 + n_el + n_el // 32, n_el)
         # (the exhaustive selector runs last of the cfg2 extras: it heats the chip for whatever follows it)
         add("quantize_sse", quant_step(F.opts(selector=F.SEL_SSE)), abytes, n_el, steps=max(5, args.steps // 10))
+        add("quantize_sse_two_stage", quant_step(F.opts(selector=F.SEL_SSE, flags=F.FLAG_TWO_STAGE)), abytes, n_el,
+            steps=max(5, args.steps // 10))
         # the headline kernel on a four times larger tensor (65536 x 3072): the fixed cost of a launch (table
         # set-up, pipeline fill and drain) weighs less
         del els, scs, outs
