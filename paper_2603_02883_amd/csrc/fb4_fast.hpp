@@ -165,10 +165,18 @@ __host__ __device__ constexpr int lds_hist_offset(bool seda, bool decomp, int w)
     return w < 2 ? kLdsRows + w * kHistWaveBytes
                  : lds_matrix_offset(seda, decomp) + kMatrixTableBytes + (w - 2) * kHistWaveBytes;
 }
-// sse_waves: wavefronts of a workgroup that runs the exhaustive selector, else 0
-constexpr int lds_fast_bytes(bool seda, bool decomp, int sse_waves = 0)
+// Online selector with 32 groups (every element its own group): its score sum_elements Qerror[bin][d] is the block's
+// bin counts times the Qerror matrix, taken on the matrix cores as well (select_lut32_matrix).  Placed last: per
+// wavefront the counts of its 64 blocks, dword (bin b, lane l) at (64 b + l) * 4 (the Qerror rows stay: the plain
+// routine reads them).
+constexpr int lds_count_offset(bool seda, bool decomp, int w) { return lds_gm_offset(seda, decomp) + w * kHistWaveBytes; }
+// sse_waves: wavefronts of a workgroup that runs the exhaustive selector, else 0; count_waves: the same for the
+// online selector with 32 groups
+constexpr int lds_fast_bytes(bool seda, bool decomp, int sse_waves = 0, int count_waves = 0)
 {
-    return sse_waves ? lds_hist_offset(seda, decomp, sse_waves > 2 ? sse_waves : 2) : lds_gm_offset(seda, decomp);
+    return sse_waves     ? lds_hist_offset(seda, decomp, sse_waves > 2 ? sse_waves : 2)
+           : count_waves ? lds_count_offset(seda, decomp, count_waves)
+                         : lds_gm_offset(seda, decomp);
 }
 
 struct BlockCodes {
@@ -298,6 +306,7 @@ struct MatrixConsts {
     uint32_t rd[2];       // LDS offsets of the 64 bytes it reads of block 32 t + lane % 32, t = 0, 1
     uint32_t half4;       // 4 * (lane / 32)
     i32x4 w3;             // candidate restrictions: byte j = 64 where 16 (lane / 32) + j == lane % 32, else 0
+    i32x4 wq[4];          // online selector with 32 groups: this lane's pieces of the (negated) Qerror matrix
 };
 
 struct TileConsts {
@@ -567,13 +576,120 @@ __device__ __forceinline__ MatrixConsts make_matrix_consts(uint8_t* lds, uint32_
     return M;
 }
 
+// Sec. 3.2 online selection with 32 groups: every element is its own group, so the score of dialect d is
+// sum_elements Qerror[bin][d] = sum_b n_b Qerror[b][d] with n_b the block's elements in bin b -- the same matrix
+// product as the exhaustive selector's, with counts alone (32 row reads of 32 bytes per block otherwise, the LDS
+// pipe's bound: 30.7 us on 16384x3072).  A lane adds 1 to dword (bin, lane) per element; the lanes that hold a
+// block's dialects read its 32 dwords (byte 0 = n_b <= 32, the other bytes zero), put zero back, and four matrix
+// instructions against (-Qerror, 0, 0, 0) give minus the score: keys -S * 32 + 31 - DID, the largest wins (smallest
+// score, lowest DID on ties); candidate restrictions as in select_sse_matrix.  Block size 32, full EXEC.
+template <bool kTwoStage, bool kSeda>
+__device__ __forceinline__ uint32_t select_lut32_matrix(const uint32_t (&b2)[16], uint8_t* lds, const MatrixConsts& M,
+                                                        uint32_t lane, uint32_t range_row, uint32_t seda_row)
+{
+    const uint32_t k_lo = sgpr_const(256u), k_hi = sgpr_const(256u << 16);   // 256 * bin from either half
+    const uint32_t one = vgpr_const(1u);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        uint32_t* a0 = reinterpret_cast<uint32_t*>(lds + dot2_u16(b2[k], k_lo, M.row));
+        uint32_t* a1 = reinterpret_cast<uint32_t*>(lds + dot2_u16(b2[k], k_hi, M.row));
+        __hip_atomic_fetch_add(a0, one, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        __hip_atomic_fetch_add(a1, one, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    uint32_t r[2][16];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        uint32_t* col = reinterpret_cast<uint32_t*>(lds + M.rd[t]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) r[t][j] = col[64 * j];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) col[64 * j] = 0u;
+    }
+    i32x4 xr[2], xa[2];
+    if (kTwoStage) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(range_row, range_row, false, false);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) xr[t] = *reinterpret_cast<const i32x4*>(lds + sw[t] + 4u * M.half4);
+    }
+    if (kSeda) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(seda_row, seda_row, false, false);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) xa[t] = *reinterpret_cast<const i32x4*>(lds + sw[t] + 4u * M.half4);
+    }
+    int res[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        i32x16 ps = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        i32x16 pen = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if (kSeda) pen = __builtin_amdgcn_mfma_i32_32x32x32_i8(M.w3, xa[t], pen, 0, 0, 0);
+        if (kTwoStage) {
+            const i32x4 w3r = {M.w3.x >> 2, M.w3.y >> 2, M.w3.z >> 2, M.w3.w >> 2};   // 16 on the diagonal
+            pen = __builtin_amdgcn_mfma_i32_32x32x32_i8(w3r, xr[t], pen, 0, 0, 0);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const i32x4 b = {(int)r[t][4 * c], (int)r[t][4 * c + 1], (int)r[t][4 * c + 2], (int)r[t][4 * c + 3]};
+            ps = __builtin_amdgcn_mfma_i32_32x32x32_i8(M.wq[c], b, ps, 0, 0, 0);
+        }
+        int best = (int)0x80000000;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            uint32_t key = ((uint32_t)ps[i] << 5) | sgpr_const((uint32_t)(31 - 8 * (i >> 2) - (i & 3)));
+            if (kSeda || kTwoStage) key += (uint32_t)pen[i] << 23;
+            best = max(best, (int)key);
+        }
+        best -= (int)M.half4;
+        const auto sw = __builtin_amdgcn_permlane32_swap((uint32_t)best, (uint32_t)best, false, false);
+        res[t] = max((int)sw[0], (int)sw[1]);
+    }
+    return 31u - ((uint32_t)(lane < 32u ? res[0] : res[1]) & 31u);
+}
+
+// What select_lut32_matrix keeps per lane: the pieces of the negated Qerror matrix, from the Qerror rows at
+// lds + kLdsRows (copy 0; they must be complete), and its places in the wavefront's counts at lds + count_off,
+// which it clears.
+__device__ __forceinline__ MatrixConsts make_count_consts(uint8_t* lds, uint32_t count_off, uint32_t lane)
+{
+    MatrixConsts M;
+    const uint32_t d = lane & 31u, h = lane >> 5;
+    M.wtab = 0;
+    M.row = count_off + lane * 4u;
+    M.rd[0] = count_off + d * 4u + h * (16u * 256u);
+    M.rd[1] = M.rd[0] + 32u * 4u;
+    M.half4 = 4u * h;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        uint32_t a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t bin = 16u * h + 4u * c + j;
+            const uint32_t q = lds[kLdsRows + bin * (32 * kRowCopies) + (d >> 4) * (16 * kRowCopies) + (d & 15u)];
+            a[j] = (0u - q) & 0xFFu;
+        }
+        M.wq[c] = i32x4{(int)a[0], (int)a[1], (int)a[2], (int)a[3]};
+    }
+    {
+        const uint32_t j = d - 16u * h;
+        const uint32_t v = 64u << (8u * (j & 3u));
+        M.w3 = i32x4{(int)((j >> 2) == 0u ? v : 0u), (int)((j >> 2) == 1u ? v : 0u), (int)((j >> 2) == 2u ? v : 0u),
+                     (int)((j >> 2) == 3u ? v : 0u)};
+    }
+#pragma unroll
+    for (int b = 0; b < 32; ++b) reinterpret_cast<uint32_t*>(lds + M.row)[64 * b] = 0u;
+    return M;
+}
+
 // One lane owns 32 consecutive elements of a row: w = its 32 bf16 as 16 packed pairs, holding one block of
 // 32 or two blocks of 16.  Produces the four code words and the metadata (one 16-bit word, or two for block
 // size 16 with the first block in the low half).  xb / in_range are only used by the plain per-element
 // routine of a tile with special values (tile_special reports that this route was taken).  kResidual: w holds the Sec. 3.3 residual of the first plane
 // (code1, meta1), which the plain routine recomputes from x.  stage: 16 words of the lane's private memory when w
 // is not in global memory at all (xb is then ignored).
-template <int kBlock, int G, bool kTwoStage, bool kSeda, bool kResidual = false>
+// kCounts: the calling kernel has the LDS counts that select_lut32_matrix needs (32 groups only).
+template <int kBlock, int G, bool kTwoStage, bool kSeda, bool kResidual = false, bool kCounts = false>
 __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint8_t* lds, const TileConsts& K,
                                              const uint16_t* xb, bool in_range, uint32_t excl_a,
                                              uint32_t (&code)[4], uint32_t& meta,
@@ -665,6 +781,10 @@ __device__ __forceinline__ void compute_tile(const uint32_t (&w)[16], const uint
                 const uint32_t range_row = kLdsRange + ((bm[b] >> 4) & 7u) * 32u;
                 did[b] = select_sse_matrix<RB, kTwoStage, kSeda>(b2, x2, b * RB, const_cast<uint8_t*>(lds), K.mx,
                                                                  threadIdx.x & 63u, range_row, excl_a);
+            } else if (kCounts && G == 32) {
+                const uint32_t range_row = kLdsRange + ((bm[b] >> 4) & 7u) * 32u;
+                did[b] = select_lut32_matrix<kTwoStage, kSeda>(b2, const_cast<uint8_t*>(lds), K.mx, threadIdx.x & 63u,
+                                                               range_row, excl_a);
             } else {
                 // ---- group-wise maxima: groups are runs of PER elements
                 uint32_t gbin[GG];
@@ -876,7 +996,8 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
     constexpr int kLdsSeda = lds_seda_offset(kRes);
     constexpr bool kSse = G == 0;   // the exhaustive selector
     constexpr int kLdsGm = lds_gm_offset(kSeda, kRes);
-    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kRes, kSse ? kThreads / 64 : 0)];
+    constexpr bool kCounts = G == 32 && kBlock == 32 && !kRes;   // 32 groups: scores on the matrix cores
+    __shared__ __align__(16) uint8_t lds[lds_fast_bytes(kSeda, kRes, kSse ? kThreads / 64 : 0, kCounts ? kThreads / 64 : 0)];
     __shared__ uint32_t sal_before;      // fused decomposition: list entries below row 0
     __shared__ uint32_t sal_wave[kWaves];
     const uint32_t lane = threadIdx.x & 63;
@@ -1091,6 +1212,7 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         __syncthreads();
     }
     TileConsts K = make_tile_consts(lane, kLdsGm);
+    if (kCounts) K.mx = make_count_consts(lds, lds_count_offset(kSeda, kRes, 0) + wave * kHistWaveBytes, lane);
     if (kSse)
         K.mx = make_matrix_consts(lds, kLdsGm, lds_matrix_offset(kSeda, kRes),
                                   wave < 2 ? kLdsRows + wave * kHistWaveBytes
@@ -1170,8 +1292,8 @@ __global__ __launch_bounds__(kThreads) void quantize_lut_kernel(
         } else {
             const uint16_t* xb = p.x + block_offset<kFlat>(p, gb < p.n_blocks ? gb : 0u);
             const uint32_t no_code[4] = {0, 0, 0, 0};
-            compute_tile<kBlock, G, kTwoStage, kSeda>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta, no_code, 0u,
-                                                      tile_special);
+            compute_tile<kBlock, G, kTwoStage, kSeda, false, kCounts>(w, lds, K, xb, gb < p.n_blocks, excl_a, code, meta,
+                                                                      no_code, 0u, tile_special);
             if (kDecomp) {
                 // second plane of the salient rows, from the registers that still hold the tile
                 const uint32_t gbc = gb < p.n_blocks ? gb : 0u;
