@@ -413,6 +413,74 @@ def test_empty_inputs_and_error_codes_with_a_real_handle(F, luts):
 
 
 # ------------------------------------------------------------ block size 16
+def _histogram_extreme_blocks(block, seed):
+    """bf16 bit patterns [n][block] of blocks that drive the per-bin statistics of the matrix-core selectors to
+    their limits: every element in one bin with the largest fractions (count = block, fraction sum at its
+    maximum), every bin holding one element, alternating signs, a lone maximum over zeros, values just below
+    and on bin and rounding boundaries, and exact ties between dialects."""
+    rng = np.random.default_rng(seed)
+    f32 = lambda v: (np.asarray(v, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)   # exact for these values
+    blocks = []
+    for top in (8.0, 9.5, 12.0, 15.9375):
+        for scale in (1.0, 2.0 ** -9, 2.0 ** 20):
+            # all other elements in ONE bin, with the largest fraction that bin can hold
+            for b in (1, 2, 3, 7, 15, 16, 30, 31):
+                hi = (b + 1) / 2.0
+                v = np.full(block, hi, dtype=np.float64)
+                # the largest bf16 below the bin's upper edge that is at most `top`
+                cand = np.float32(min(hi, top))
+                bits = cand.view(np.uint32) >> 16
+                below = np.array([(int(bits) - 1) << 16], dtype=np.uint32).view(np.float32)[0]
+                v[:] = below if hi <= top else top
+                v[0] = top
+                blocks.append(f32(v * scale))
+                w = v.copy(); w[1::2] *= -1.0
+                blocks.append(f32(w * scale))
+            # one element per bin (block 32) / per second bin (block 16), smallest and largest fractions
+            for frac in (0.0, 0.49609375):
+                v = (np.arange(block) * (32 // block)) / 2.0 + frac
+                v = np.minimum(v, top); v[-1] = top
+                blocks.append(f32(rng.permutation(v) * scale))
+            # a lone maximum over zeros; everything equal to the maximum; everything at a rounding boundary
+            v = np.zeros(block); v[rng.integers(block)] = top; blocks.append(f32(v * scale))
+            blocks.append(f32(np.full(block, top) * scale))
+            for mid in (0.5, 1.5, 2.5, 4.5, 6.0, 7.5):
+                v = np.full(block, mid); v[0] = top; blocks.append(f32(v * scale))
+    return np.stack(blocks)
+
+
+@pytest.mark.parametrize("block", [32, 16])
+def test_matrix_core_selectors_at_the_limits_of_their_histograms(F, luts, block):
+    """The exhaustive selector and the 32-group online selector score on the matrix cores from per-bin counts
+    and fraction sums kept in byte fields: blocks that push every field to its limit, with and without the
+    two-stage filter and SeDA lists, against the oracle."""
+    fbk = DEFAULT_FORMATBOOK
+    blk = _histogram_extreme_blocks(block, 91)
+    per_row = 96 * 32 // block                       # blocks per row: rows of 3072 elements
+    n = (len(blk) + per_row - 1) // per_row * per_row
+    rng = np.random.default_rng(92)
+    blk = np.concatenate([blk, blk[rng.integers(len(blk), size=n - len(blk))]])
+    xb = blk[rng.permutation(n)].reshape(n // per_row, 3072)
+    x = dev_bits(xb)
+    sub = synth.seda_sub_formatbooks(fbk, n_groups=3, seed=93)
+    tg = (np.arange(xb.shape[0]) % 4 - 1).astype(np.int32)      # -1, 0, 1, 2
+    tg_d, sub_d = torch.from_numpy(tg).cuda(), torch.from_numpy(sub).cuda()
+    for sel, g in ((F.SEL_SSE, 8),) + (((F.SEL_LUT, 32),) if block == 32 else ()):
+        for flags in (0, F.FLAG_TWO_STAGE):
+            o = F.opts(block=block, selector=sel, num_groups=g, flags=flags)
+            c, m = F.fb4_quantize(luts, o, x)
+            torch.cuda.synchronize()
+            cr, mr = O.quantize(fbk, xb, block=block, selector=sel, num_groups=g, flags=flags)
+            assert compare_quant(fbk, xb, host_u8(c), host_u16(m), cr, mr, sel, g, flags=flags, block=block,
+                                 what="histogram limits sel %d flags %d" % (sel, flags)) == 0
+            c, m = F.fb4_quantize_seda(luts, o, x, tg_d, sub_d)
+            torch.cuda.synchronize()
+            cr, mr = O.quantize(fbk, xb, block=block, selector=sel, num_groups=g, flags=flags, token_group=tg,
+                                sub_formatbooks=sub)
+            assert compare_quant(fbk, xb, host_u8(c), host_u16(m), cr, mr, sel, g, flags=flags, token_group=tg,
+                                 sub=sub, block=block, what="histogram limits, SeDA, sel %d flags %d" % (sel, flags)) == 0
+
+
 SELECTORS_B16 = [("lut8", 1, 8), ("lut16", 1, 16), ("sse", 0, 8)]
 
 
