@@ -72,8 +72,8 @@ int launch_quant(const fb4_opts* o, int grid, hipStream_t s, const QuantParams& 
 
 // Persistent workgroups, one per compute unit: measured 24.4 us against 26.0 us with two on the 16384x3072
 // workload with 8 wavefronts each (SeDA: 25.7 against 27.2; 4, 12 or 16 wavefronts are slower too), and the
-// kernels are free to use up to 256 vector registers per lane.  The exhaustive selector, bound by the vector
-// ALU, runs 12 wavefronts (83 -> 74.5 us).
+// kernels are free to use up to 256 vector registers per lane.  The exhaustive selector without candidate
+// restrictions runs 12 wavefronts (37.7 against 39.1 us).
 // kSedaToo = false: the variants with SeDA lists are not instantiated (`seda` must be false).
 template <int kBlock, int G, bool kFlat, int kMode, int kThreads = kFastThreads, bool kSedaToo = true>
 void launch_fast_variant(bool ts, bool seda, int n_cu, hipStream_t s, const FastParams& f)
